@@ -1,0 +1,186 @@
+/*
+ * ess.h -- C ABI of libess: the decode-step hot path of ESS (Extended Sparse
+ * Server, arXiv 2512.10576) for DeepSeek-V3.2-Exp-style sparse attention,
+ * written for AMD MI355X (gfx950).
+ *
+ * Per layer and decode step the paper's design runs (Sec. 3, Sec. 3.3):
+ *   indexer over the GPU-resident Indexer-Cache -> Top-2K selection ->
+ *   look-up of the selected entries in the GPU-side Sparse Memory Pool under
+ *   an LRU policy (Sec. 3.2) -> fetch of the missed entries from the CPU-side
+ *   Total Memory Pool by direct GPU access to pinned host memory (Sec. 3.1,
+ *   FlashTrans) -> SparseMLA over the selected entries, split in Attn0
+ *   (resident entries, overlapping the fetch) and Attn1 (fetched entries),
+ *   merged (Sec. 3.3, DA overlap).
+ * Each of these stages is one call below; ess_decode_step chains them.
+ *
+ * Conventions
+ *   - Plain C, no exceptions cross the boundary.  Every call returns an int:
+ *     ESS_OK (0) or a negative ess_status.  ess_last_error() gives a text for
+ *     the last failure on the calling thread.
+ *   - Argument checks are synchronous.  GPU work is ENQUEUED on `stream`
+ *     (a hipStream_t passed as void*; NULL = the default stream) and the call
+ *     returns without waiting, except where stated.
+ *   - Pointers are DEVICE pointers unless the name starts with host_.  The
+ *     caller owns every data buffer, the cache state arrays and the pinned
+ *     host pool; the library owns only the opaque ess_ctx (workspace, one
+ *     side stream, events).  No call frees or reallocates caller memory.
+ *   - Row bases must be 16-byte aligned; row_stride must be a multiple of 16.
+ *   - Shapes use: B sequences, T query tokens per sequence (1 or 2), Lmax
+ *     cached positions per sequence (row pitch of key/score/slot_of), Hi x Di
+ *     indexer heads x dim, k = topk, H attention heads, S slots per sequence.
+ *     Visible positions of query t: vis(b,t) = ctx_len[b] - (T-1-t), i.e. the
+ *     cache already holds the T new tokens and query t sees itself and all
+ *     earlier positions (multi-token decode, the paper's MTP setting, Table 1).
+ *   - A context is not thread-safe; calls on one context must not overlap.
+ */
+#ifndef ESS_H
+#define ESS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  ESS_OK = 0,
+  ESS_ERR_INVALID_ARG = -1, /* null / misaligned pointer, size out of the configured range */
+  ESS_ERR_UNSUPPORTED = -2, /* a shape no kernel was compiled for */
+  ESS_ERR_CAPACITY = -3,    /* slot pool smaller than one step's selection (S < T*k), or over a stated maximum */
+  ESS_ERR_NOMEM = -4,       /* workspace allocation failed */
+  ESS_ERR_HIP = -5          /* a HIP runtime call failed; text in ess_last_error() */
+} ess_status;
+
+#define ESS_LATENT_DIM 512 /* value part of a Latent-Cache entry */
+#define ESS_ROPE_DIM 64    /* rotary part */
+#define ESS_FMT_BF16 0     /* entry = 576 bf16 (1152 bytes) */
+#define ESS_FMT_FP8 1      /* entry = 512 e4m3 + 4 bf16 scales (one per 128) + 64 bf16 rope (648 bytes) */
+
+#define ESS_FLAG_SERIAL 1u /* run the miss fill on the caller's stream (no side stream, no overlap) */
+
+typedef struct ess_ctx ess_ctx;
+
+/* Fixed for the life of a context. */
+typedef struct {
+  uint32_t struct_size;   /* sizeof(ess_config), checked */
+  int32_t max_batch;      /* largest B any call will pass */
+  int32_t max_q_tokens;   /* largest T (1 or 2) */
+  int32_t max_ctx;        /* Lmax: row pitch of key, score and slot_of; <= 1048576 */
+  int32_t idx_heads;      /* Hi, 1..64 */
+  int32_t idx_dim;        /* Di, 32 | 64 | 128 */
+  int32_t topk;           /* k, 1..4096 */
+  int32_t attn_heads;     /* H, 1..128 */
+  int32_t latent_fmt;     /* ESS_FMT_BF16 | ESS_FMT_FP8 */
+  int32_t row_stride;     /* bytes between entries in slot pool and host pool (>= entry size, multiple of 16) */
+  int32_t slots_per_seq;  /* S; = max_ctx when nothing is offloaded */
+  float sm_scale;         /* softmax scale of the attention logits */
+  uint32_t flags;         /* ESS_FLAG_* */
+} ess_config;
+
+/* Caller-owned Sparse Memory Pool state of ONE layer (Sec. 3.2).  Entry
+ * granularity (Sec. 3.1: one Latent-Cache entry is the swap unit). */
+typedef struct {
+  uint8_t* slot_pool;           /* [B,S,row_stride] device: the GPU-side pool */
+  const uint8_t* host_pool_dev; /* [B,Lmax,row_stride] pinned host memory, DEVICE-side address of it
+                                   (hipHostMalloc'ed / torch pinned memory is directly addressable);
+                                   NULL = nothing is offloaded: then S == Lmax and slot s holds token s */
+  int32_t* slot_of;             /* [B,Lmax] slot of a token, -1 = not resident */
+  int32_t* token_of;            /* [B,S]    token held by a slot, -1 = empty */
+  uint32_t* stamp;              /* [B,S]    step of last use, 0 = never used */
+} ess_cache;
+
+/* Per-call inputs and outputs of ess_decode_step. */
+typedef struct {
+  const uint8_t* q_idx_fp8;     /* [B,T,Hi,Di] e4m3 indexer queries */
+  const float* w;               /* [B,T,Hi] indexer head weights */
+  const uint8_t* key_fp8;       /* [B,Lmax,Di] e4m3 Indexer-Cache, one key per token */
+  const int32_t* ctx_len;       /* [B] cached positions per sequence (<= Lmax) */
+  const void* q_bf16;           /* [B,T,H,576] absorbed attention queries */
+  const int32_t* topk_override; /* [B,T,k] or NULL.  When given, stages 1-2 still run and fill
+                                   idx_out, but the cache and the attention use these indices
+                                   (trace replay); entries must be distinct per (b,t), < vis, or -1 */
+  int32_t B, T;
+  uint32_t step;                /* LRU clock: >= 1 and strictly increasing per cache */
+  int32_t* idx_out;             /* [B,T,k] selected positions, ascending, -1 padded */
+  void* out_bf16;               /* [B,T,H,512] attention output */
+  float* lse;                   /* [B,T,H] log-sum-exp of the logits, or NULL */
+  int32_t* miss_count;          /* [B] entries fetched from the host pool this step, or NULL */
+} ess_step_args;
+
+/* Create a context: validates the configuration, allocates the workspace
+ * (see ess_workspace_bytes), a side stream and events on the current device.
+ * ESS_ERR_INVALID_ARG / ESS_ERR_UNSUPPORTED / ESS_ERR_CAPACITY (S < T*k) / ESS_ERR_NOMEM. */
+int ess_create(const ess_config* cfg, ess_ctx** out);
+/* Waits for the context's side stream, frees what ess_create allocated. */
+int ess_destroy(ess_ctx* ctx);
+/* Text of the last failure on this thread ("" if none).  Never NULL. */
+const char* ess_last_error(void);
+/* Device bytes ess_create will allocate for this configuration. */
+int ess_workspace_bytes(const ess_config* cfg, size_t* out);
+
+/* Sparse Memory Pool set-up.  With host_pool_dev == NULL: identity residency
+ * (slot_of[b,s] = s, token_of[b,s] = s, stamp 0).  Otherwise all slots empty. */
+int ess_cache_reset(ess_ctx* ctx, const ess_cache* cache, int32_t B, void* stream);
+/* LRU-Warmup (Sec. 3.2): insert the given entries as one LRU step, fetching
+ * missing ones from the host pool.  tok [B,n] (-1 = none), n <= T*k. */
+int ess_cache_admit(ess_ctx* ctx, const ess_cache* cache, const int32_t* tok, int32_t B, int32_t n,
+                    uint32_t step, void* stream);
+
+/* Stage 1, indexer (Sec. 3: the Indexer-Cache scores every Latent-Cache entry):
+ *   score[b,t,s] = sum_j w[b,t,j] * max(0, sum_d q[b,t,j,d] * key[b,s,d]),  s < vis(b,t);
+ * fp8 x fp8 products accumulated in fp32.  score [B,T,Lmax] fp32; positions
+ * s >= vis(b,t) hold unspecified values. */
+int ess_index_score(ess_ctx* ctx, const uint8_t* q_idx_fp8, const float* w, const uint8_t* key_fp8,
+                    const int32_t* ctx_len, int32_t B, int32_t T, float* score, void* stream);
+
+/* Stage 2, Top-K (Sec. 3: the top 2,048 entries): idx[b,t,:] = the min(k,vis)
+ * positions largest under (score descending, position ascending), written in
+ * ascending position order, then -1.  NaN ranks as -inf; +0 and -0 are equal. */
+int ess_topk(ess_ctx* ctx, const float* score, const int32_t* ctx_len, int32_t B, int32_t T,
+             int32_t* idx, void* stream);
+
+/* Stages 3 + 5, Sparse Memory Pool look-up, LRU update and miss fetch
+ * (Sec. 3.1, 3.2).  Per sequence: R = distinct valid entries of idx[b]; resident
+ * ones are hits (stamp := step); the others, in ascending position, take the
+ * slots smallest in (stamp, slot) among slots with stamp < step, whose former
+ * tokens become non-resident; their rows are copied host pool -> slot.
+ *   slot_idx [B,T,k]  slot of every selected entry after the step (-1 where idx is -1)
+ *   rows_out [B,T,k,row_stride] or NULL: the selected rows, gathered (zero where idx is -1)
+ *   miss_count [B] or NULL
+ * The fetch runs on the context's side stream unless ESS_FLAG_SERIAL; either
+ * way it is ordered before anything enqueued on `stream` after this call. */
+int ess_gather_latent(ess_ctx* ctx, const ess_cache* cache, const int32_t* idx, const int32_t* ctx_len,
+                      int32_t B, int32_t T, uint32_t step, int32_t* slot_idx, uint8_t* rows_out,
+                      int32_t* miss_count, void* stream);
+
+/* Stage 4, SparseMLA decode (Sec. 3.3) in absorbed form: an entry's 576 values
+ * are the key, its first 512 the value.
+ *   z_s = sm_scale * q . c_s ; lse = log sum_s exp z_s ; out = sum_s exp(z_s - lse) c_s[:512]
+ * over the entries slot_idx[b,t,:] >= 0 of slot_pool [B,S,row_stride].  bf16
+ * operands (fp8 entries are dequantised to bf16), fp32 accumulation and softmax.
+ * Empty selection: out = 0, lse = -inf. */
+int ess_sparse_mla_decode(ess_ctx* ctx, const void* q_bf16, const uint8_t* slot_pool,
+                          const int32_t* slot_idx, int32_t B, int32_t T, void* out_bf16, float* lse,
+                          void* stream);
+
+/* One layer-step: stages 1-5 chained on `stream`, the miss fetch on the side
+ * stream overlapping Attn0 (Sec. 3.3, DA overlap), Attn1 after it, merged. */
+int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* args, void* stream);
+
+/* Counters accumulated by ess_gather_latent / ess_cache_admit / ess_decode_step
+ * since the last ess_reset_stats.  ess_get_stats WAITS for `stream` and the
+ * side stream. */
+typedef struct {
+  uint64_t steps;        /* bookkeeping steps */
+  uint64_t selected;     /* distinct entries requested */
+  uint64_t misses;       /* entries fetched from the host pool */
+  uint64_t bytes_filled; /* misses * row_stride */
+} ess_stats;
+int ess_get_stats(ess_ctx* ctx, ess_stats* host_out, void* stream);
+int ess_reset_stats(ess_ctx* ctx, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ESS_H */

@@ -1,0 +1,218 @@
+"""Thin ctypes binding over libess.so (see include/ess.h).
+
+Argument marshalling only: every function takes torch tensors that already
+live where the C ABI expects them (device memory, or pinned host memory for
+the host pool), checks dtype / contiguity, and passes raw pointers plus the
+current HIP stream.  No computation happens here and there is no fallback:
+if the library has not been built, `load()` raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libess.so")
+
+ESS_OK = 0
+ESS_ERR_INVALID_ARG, ESS_ERR_UNSUPPORTED, ESS_ERR_CAPACITY, ESS_ERR_NOMEM, ESS_ERR_HIP = -1, -2, -3, -4, -5
+ESS_FMT_BF16, ESS_FMT_FP8 = 0, 1
+ESS_FLAG_SERIAL = 1
+
+
+class EssConfig(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("max_batch", C.c_int32), ("max_q_tokens", C.c_int32),
+                ("max_ctx", C.c_int32), ("idx_heads", C.c_int32), ("idx_dim", C.c_int32), ("topk", C.c_int32),
+                ("attn_heads", C.c_int32), ("latent_fmt", C.c_int32), ("row_stride", C.c_int32),
+                ("slots_per_seq", C.c_int32), ("sm_scale", C.c_float), ("flags", C.c_uint32)]
+
+
+class EssCache(C.Structure):
+    _fields_ = [("slot_pool", C.c_void_p), ("host_pool_dev", C.c_void_p), ("slot_of", C.c_void_p),
+                ("token_of", C.c_void_p), ("stamp", C.c_void_p)]
+
+
+class EssStepArgs(C.Structure):
+    _fields_ = [("q_idx_fp8", C.c_void_p), ("w", C.c_void_p), ("key_fp8", C.c_void_p), ("ctx_len", C.c_void_p),
+                ("q_bf16", C.c_void_p), ("topk_override", C.c_void_p), ("B", C.c_int32), ("T", C.c_int32),
+                ("step", C.c_uint32), ("idx_out", C.c_void_p), ("out_bf16", C.c_void_p), ("lse", C.c_void_p),
+                ("miss_count", C.c_void_p)]
+
+
+class EssStats(C.Structure):
+    _fields_ = [("steps", C.c_uint64), ("selected", C.c_uint64), ("misses", C.c_uint64),
+                ("bytes_filled", C.c_uint64)]
+
+
+class EssError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__("libess error %d: %s" % (code, text))
+        self.code = code
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Load libess.so (after torch, so that both share one HIP runtime)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("libess.so is not built: run `python -m paper_2512_10576_amd.build`")
+    lib = C.CDLL(LIB_PATH, mode=C.RTLD_GLOBAL)
+    vp, i32, u32 = C.c_void_p, C.c_int32, C.c_uint32
+    sigs = {
+        "ess_create": [C.POINTER(EssConfig), C.POINTER(vp)],
+        "ess_destroy": [vp],
+        "ess_workspace_bytes": [C.POINTER(EssConfig), C.POINTER(C.c_size_t)],
+        "ess_cache_reset": [vp, C.POINTER(EssCache), i32, vp],
+        "ess_cache_admit": [vp, C.POINTER(EssCache), vp, i32, i32, u32, vp],
+        "ess_index_score": [vp, vp, vp, vp, vp, i32, i32, vp, vp],
+        "ess_topk": [vp, vp, vp, i32, i32, vp, vp],
+        "ess_gather_latent": [vp, C.POINTER(EssCache), vp, vp, i32, i32, u32, vp, vp, vp, vp],
+        "ess_sparse_mla_decode": [vp, vp, vp, vp, i32, i32, vp, vp, vp],
+        "ess_decode_step": [vp, C.POINTER(EssCache), C.POINTER(EssStepArgs), vp],
+        "ess_get_stats": [vp, C.POINTER(EssStats), vp],
+        "ess_reset_stats": [vp, vp],
+    }
+    for name, args in sigs.items():
+        fn = getattr(lib, name)
+        fn.argtypes = args
+        fn.restype = C.c_int
+    lib.ess_last_error.argtypes = []
+    lib.ess_last_error.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+def _check(rc):
+    if rc != ESS_OK:
+        raise EssError(rc, load().ess_last_error().decode())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t, dtype=None, device="cuda", optional=False):
+    if t is None:
+        if optional:
+            return None
+        raise ValueError("tensor required")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError("expected %s, got %s" % (dtype, t.dtype))
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    if device == "cuda" and not t.is_cuda:
+        raise ValueError("tensor must be in device memory")
+    if device == "pinned" and not (t.is_pinned() or t.is_cuda):
+        raise ValueError("host pool must be pinned host memory")
+    return C.c_void_p(t.data_ptr())
+
+
+def make_config(max_batch, max_q_tokens, max_ctx, idx_heads, idx_dim, topk, attn_heads, latent_fmt=ESS_FMT_BF16,
+                row_stride=None, slots_per_seq=None, sm_scale=576 ** -0.5, flags=0) -> EssConfig:
+    if row_stride is None:
+        row_stride = 1152 if latent_fmt == ESS_FMT_BF16 else 656
+    if slots_per_seq is None:
+        slots_per_seq = max_ctx
+    return EssConfig(C.sizeof(EssConfig), max_batch, max_q_tokens, max_ctx, idx_heads, idx_dim, topk, attn_heads,
+                     latent_fmt, row_stride, slots_per_seq, sm_scale, flags)
+
+
+def workspace_bytes(cfg: EssConfig) -> int:
+    out = C.c_size_t(0)
+    _check(load().ess_workspace_bytes(C.byref(cfg), C.byref(out)))
+    return out.value
+
+
+class Cache:
+    """Caller-owned Sparse Memory Pool state of one layer (tensors stay alive here)."""
+
+    def __init__(self, slot_pool, slot_of, token_of, stamp, host_pool=None):
+        self.slot_pool, self.slot_of, self.token_of, self.stamp, self.host_pool = slot_pool, slot_of, token_of, stamp, host_pool
+        self.c = EssCache(_ptr(slot_pool, torch.uint8), _ptr(host_pool, torch.uint8, "pinned", optional=True),
+                          _ptr(slot_of, torch.int32), _ptr(token_of, torch.int32), _ptr(stamp, torch.int32))
+
+    @staticmethod
+    def allocate(cfg: EssConfig, B, host_pool=None, slot_pool=None, device="cuda"):
+        S, L = cfg.slots_per_seq, cfg.max_ctx
+        if slot_pool is None:
+            slot_pool = torch.zeros((B, S, cfg.row_stride), dtype=torch.uint8, device=device)
+        return Cache(slot_pool, torch.empty((B, L), dtype=torch.int32, device=device),
+                     torch.empty((B, S), dtype=torch.int32, device=device),
+                     torch.empty((B, S), dtype=torch.int32, device=device), host_pool)
+
+
+class Context:
+    """Owns one ess_ctx.  Methods carry the names of the C entry points."""
+
+    def __init__(self, cfg: EssConfig):
+        self.lib = load()
+        self.cfg = cfg
+        h = C.c_void_p()
+        _check(self.lib.ess_create(C.byref(cfg), C.byref(h)))
+        self.h = h
+
+    def close(self):
+        if self.h:
+            self.lib.ess_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def cache_reset(self, cache: Cache, B):
+        _check(self.lib.ess_cache_reset(self.h, C.byref(cache.c), B, _stream()))
+
+    def cache_admit(self, cache: Cache, tok, step):
+        B, n = tok.shape
+        _check(self.lib.ess_cache_admit(self.h, C.byref(cache.c), _ptr(tok, torch.int32), B, n, step, _stream()))
+
+    def index_score(self, q_idx_fp8, w, key_fp8, ctx_len, score):
+        B, T = q_idx_fp8.shape[:2]
+        _check(self.lib.ess_index_score(self.h, _ptr(q_idx_fp8, torch.uint8), _ptr(w, torch.float32),
+                                        _ptr(key_fp8, torch.uint8), _ptr(ctx_len, torch.int32), B, T,
+                                        _ptr(score, torch.float32), _stream()))
+
+    def topk(self, score, ctx_len, idx):
+        B, T = score.shape[:2]
+        _check(self.lib.ess_topk(self.h, _ptr(score, torch.float32), _ptr(ctx_len, torch.int32), B, T,
+                                 _ptr(idx, torch.int32), _stream()))
+
+    def gather_latent(self, cache: Cache, idx, ctx_len, step, slot_idx, rows_out=None, miss_count=None):
+        B, T = idx.shape[:2]
+        _check(self.lib.ess_gather_latent(self.h, C.byref(cache.c), _ptr(idx, torch.int32),
+                                          _ptr(ctx_len, torch.int32), B, T, step, _ptr(slot_idx, torch.int32),
+                                          _ptr(rows_out, torch.uint8, optional=True),
+                                          _ptr(miss_count, torch.int32, optional=True), _stream()))
+
+    def sparse_mla_decode(self, q_bf16, slot_pool, slot_idx, out_bf16, lse=None):
+        B, T = q_bf16.shape[:2]
+        _check(self.lib.ess_sparse_mla_decode(self.h, _ptr(q_bf16, torch.bfloat16), _ptr(slot_pool, torch.uint8),
+                                              _ptr(slot_idx, torch.int32), B, T, _ptr(out_bf16, torch.bfloat16),
+                                              _ptr(lse, torch.float32, optional=True), _stream()))
+
+    def decode_step(self, cache: Cache, q_idx_fp8, w, key_fp8, ctx_len, q_bf16, step, idx_out, out_bf16, lse=None,
+                    miss_count=None, topk_override=None):
+        B, T = q_idx_fp8.shape[:2]
+        a = EssStepArgs(_ptr(q_idx_fp8, torch.uint8), _ptr(w, torch.float32), _ptr(key_fp8, torch.uint8),
+                        _ptr(ctx_len, torch.int32), _ptr(q_bf16, torch.bfloat16),
+                        _ptr(topk_override, torch.int32, optional=True), B, T, step, _ptr(idx_out, torch.int32),
+                        _ptr(out_bf16, torch.bfloat16), _ptr(lse, torch.float32, optional=True),
+                        _ptr(miss_count, torch.int32, optional=True))
+        _check(self.lib.ess_decode_step(self.h, C.byref(cache.c), C.byref(a), _stream()))
+
+    def get_stats(self) -> dict:
+        s = EssStats()
+        _check(self.lib.ess_get_stats(self.h, C.byref(s), _stream()))
+        return dict(steps=s.steps, selected=s.selected, misses=s.misses, bytes_filled=s.bytes_filled)
+
+    def reset_stats(self):
+        _check(self.lib.ess_reset_stats(self.h, _stream()))

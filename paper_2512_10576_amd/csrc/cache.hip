@@ -1,0 +1,356 @@
+// Stages 3 + 5: Sparse Memory Pool look-up, LRU update, miss fetch and row
+// gather (ESS paper Sec. 3.1 FlashTrans, Sec. 3.2 LRU-based eviction and
+// admission).  The swap unit is one Latent-Cache entry (Sec. 3.1).
+//
+// Reading of "LRU-based" implemented here (step-granular, order-free):
+//   R = distinct valid selected positions of a sequence; resident members are
+//   hits and get stamp := step; the others, in ascending position, take the
+//   slots smallest in (stamp, slot) among slots with stamp < step; the former
+//   token of a taken slot becomes non-resident.
+//
+// One workgroup per sequence does the whole update without any serial list:
+//   - the selection is turned into a bitmap in LDS (dedups the T query
+//     tokens and yields misses in ascending position by a prefix sum);
+//   - victims come from a 4-pass radix select on the 32-bit stamps
+//     (conflict-free histogram: 32 interleaved copies, copy = lane & 31),
+//     ties on the threshold stamp broken by slot order with one block scan,
+//     then a bitonic sort of the (stamp, slot) pairs in LDS;
+//   - the i-th miss is paired with the i-th victim and a fetch list is
+//     written for the fill kernel;
+//   - per (b,t), slots of hits and of fetched entries are compacted into two
+//     lists, which drive Attn0 and Attn1 (Sec. 3.3).
+// The fetch itself is a separate kernel so that it can run on a side stream:
+// GPU threads read the pinned host pool by address (the paper's UVA idea),
+// one wave per 1152- or 656-byte entry, many entries in flight.
+#include "ess_internal.h"
+
+namespace {
+
+constexpr int BT = 1024;
+
+struct BookShared {
+  union {
+    uint32_t hist[256 * 32];                   // 32 KiB
+    unsigned long long vict[ESS_MAX_SEL];      // 32 KiB
+  };
+  int32_t miss_tok[ESS_MAX_SEL];               // 16 KiB
+  uint32_t wave_tot[BT / 64];
+  uint32_t sel_digit, sel_below, vict_n;
+};
+
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v, int lane) {
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint32_t o = __shfl_up(v, d, 64);
+    if (lane >= d) v += o;
+  }
+  return v;
+}
+
+__device__ __forceinline__ uint32_t block_incl_scan(uint32_t v, uint32_t* wave_tot, uint32_t* total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint32_t inc = wave_incl_scan(v, lane);
+  __syncthreads();
+  if (lane == 63) wave_tot[wave] = inc;
+  __syncthreads();
+  uint32_t off = 0, tot = 0;
+#pragma unroll
+  for (int i = 0; i < BT / 64; ++i) {
+    const uint32_t x = wave_tot[i];
+    if (i < wave) off += x;
+    tot += x;
+  }
+  *total = tot;
+  return inc + off;
+}
+
+__device__ void bitonic_sort_u64(unsigned long long* a, int n) {
+  for (int size = 2; size <= n; size <<= 1) {
+    for (int stride = size >> 1; stride > 0; stride >>= 1) {
+      __syncthreads();
+      for (int t = threadIdx.x; t < (n >> 1); t += BT) {
+        const int lo = 2 * t - (t & (stride - 1));
+        const int hi = lo + stride;
+        const bool up = (lo & size) == 0;
+        const unsigned long long x = a[lo], y = a[hi];
+        if ((x > y) == up) { a[lo] = y; a[hi] = x; }
+      }
+    }
+  }
+  __syncthreads();
+}
+
+// idx: [B, T, kk] selected positions (-1 = none).  Dynamic LDS: bitmap of Lmax bits.
+__global__ __launch_bounds__(BT) void k_bookkeeping(
+    const int32_t* __restrict__ idx, int T, int kk, int Lmax, int S, int32_t* __restrict__ slot_of,
+    int32_t* __restrict__ token_of, uint32_t* __restrict__ stamp, uint32_t step, int32_t* __restrict__ slot_idx_out,
+    int32_t* __restrict__ hit_list, int32_t* __restrict__ miss_list, int32_t* __restrict__ n_hit,
+    int32_t* __restrict__ n_miss, int32_t* __restrict__ fill_tok, int32_t* __restrict__ fill_slot, int fill_cap,
+    int32_t* __restrict__ miss_cnt, int32_t* __restrict__ miss_count_out, unsigned long long* __restrict__ stats,
+    int row_stride) {
+  extern __shared__ uint32_t bm[];             // [W] selection bitmap, later the miss bitmap
+  __shared__ BookShared sm;
+  const int b = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int W = (Lmax + 31) >> 5;
+  const int nsel = T * kk;
+  const int32_t* sel = idx + (size_t)b * nsel;
+  int32_t* so = slot_of + (size_t)b * Lmax;
+  int32_t* to = token_of + (size_t)b * S;
+  uint32_t* stp = stamp + (size_t)b * S;
+
+  for (int j = tid; j < W; j += BT) bm[j] = 0;
+  __syncthreads();
+  for (int e = tid; e < nsel; e += BT) {
+    const int s = sel[e];
+    if (s >= 0 && s < Lmax) atomicOr(&bm[s >> 5], 1u << (s & 31));
+  }
+  __syncthreads();
+
+  // hits get their stamp; the bitmap keeps the misses only
+  const int wpt = (W + BT - 1) / BT;
+  const int w0 = min(tid * wpt, W), w1 = min(w0 + wpt, W);
+  uint32_t my_miss = 0, my_sel = 0;
+  for (int wd = w0; wd < w1; ++wd) {
+    uint32_t bits = bm[wd], keep = bits;
+    my_sel += __popc(bits);
+    while (bits) {
+      const int bit = __ffs(bits) - 1;
+      bits &= bits - 1;
+      const int sl = so[wd * 32 + bit];
+      if (sl >= 0) { stp[sl] = step; keep &= ~(1u << bit); }
+    }
+    bm[wd] = keep;
+    my_miss += __popc(keep);
+  }
+  uint32_t m, nuniq;
+  const uint32_t sel_inc = block_incl_scan(my_sel, sm.wave_tot, &nuniq);
+  (void)sel_inc;
+  const uint32_t miss_inc = block_incl_scan(my_miss, sm.wave_tot, &m);
+  {
+    uint32_t pos = miss_inc - my_miss;
+    for (int wd = w0; wd < w1; ++wd) {
+      uint32_t bits = bm[wd];
+      while (bits) {
+        const int bit = __ffs(bits) - 1;
+        bits &= bits - 1;
+        if (pos < ESS_MAX_SEL) sm.miss_tok[pos] = wd * 32 + bit;
+        ++pos;
+      }
+    }
+  }
+  __syncthreads();
+
+  if (m > 0) {
+    // ---- m-th smallest stamp among evictable slots (stamp < step): 4 x 8-bit MSD radix passes
+    uint32_t prefix = 0, need = m;
+    for (int pass = 0; pass < 4; ++pass) {
+      const int shift = 24 - 8 * pass;
+      for (int j = tid; j < 256 * 32; j += BT) sm.hist[j] = 0;
+      __syncthreads();
+      for (int v = tid; v < S; v += BT) {
+        const uint32_t st = stp[v];
+        if (st < step && (pass == 0 || (st >> (shift + 8)) == prefix))
+          atomicAdd(&sm.hist[((st >> shift) & 255u) * 32 + (lane & 31)], 1u);
+      }
+      __syncthreads();
+      uint32_t c = 0;
+      if (tid < 256) {
+#pragma unroll
+        for (int r = 0; r < 32; ++r) c += sm.hist[tid * 32 + r];
+      }
+      uint32_t total;
+      const uint32_t inc = block_incl_scan(c, sm.wave_tot, &total);
+      const uint32_t below = inc - c;
+      if (tid < 256 && below < need && below + c >= need) { sm.sel_digit = tid; sm.sel_below = below; }
+      __syncthreads();
+      need -= sm.sel_below;
+      prefix = (prefix << 8) | sm.sel_digit;
+      __syncthreads();
+    }
+    const uint32_t tau = prefix;               // threshold stamp; `need` slots with stamp == tau are taken, lowest slots first
+    // ---- collect victims: stamp < tau, plus the first `need` slots (in slot order) with stamp == tau
+    if (tid == 0) sm.vict_n = 0;
+    const int spt = (S + BT - 1) / BT;
+    const int v0 = min(tid * spt, S), v1 = min(v0 + spt, S);
+    uint32_t my_eq = 0;
+    for (int v = v0; v < v1; ++v) my_eq += (stp[v] == tau) ? 1u : 0u;
+    uint32_t eq_total;
+    const uint32_t eq_inc = block_incl_scan(my_eq, sm.wave_tot, &eq_total);   // also orders the vict_n reset
+    uint32_t rank = eq_inc - my_eq;
+    for (int v = v0; v < v1; ++v) {
+      const uint32_t st = stp[v];
+      bool take = st < tau;
+      if (st == tau) { take = rank < need; ++rank; }
+      if (take) {
+        const uint32_t p = atomicAdd(&sm.vict_n, 1u);
+        if (p < ESS_MAX_SEL) sm.vict[p] = ((unsigned long long)st << 32) | (uint32_t)v;
+      }
+    }
+    __syncthreads();
+    int np = 1;
+    while (np < (int)m) np <<= 1;
+    for (int j = (int)m + tid; j < np; j += BT) sm.vict[j] = ~0ull;
+    bitonic_sort_u64(sm.vict, np);
+    // ---- pair the i-th miss with the i-th victim
+    for (uint32_t i = tid; i < m; i += BT) {
+      const int s = sm.miss_tok[i];
+      const int v = (int)(uint32_t)sm.vict[i];
+      const int old = to[v];
+      if (old >= 0) so[old] = -1;
+      to[v] = s;
+      so[s] = v;
+      stp[v] = step;
+      fill_tok[(size_t)b * fill_cap + i] = s;
+      fill_slot[(size_t)b * fill_cap + i] = v;
+    }
+  }
+  if (tid == 0) {
+    miss_cnt[b] = (int32_t)m;
+    if (miss_count_out) miss_count_out[b] = (int32_t)m;
+    if (b == 0) atomicAdd(&stats[0], 1ull);
+    atomicAdd(&stats[1], (unsigned long long)nuniq);
+    atomicAdd(&stats[2], (unsigned long long)m);
+    atomicAdd(&stats[3], (unsigned long long)m * (unsigned long long)row_stride);
+  }
+  __syncthreads();                               // table updates visible to the whole workgroup
+
+  // ---- per (b,t): slot of every selected entry, and the compacted hit / fetched lists
+  if (slot_idx_out == nullptr && hit_list == nullptr) return;
+  for (int t = 0; t < T; ++t) {
+    const size_t rowoff = ((size_t)b * T + t) * kk;
+    uint32_t base_hit = 0, base_miss = 0;
+    for (int j0 = 0; j0 < kk; j0 += BT) {
+      const int j = j0 + tid;
+      int slot = -1;
+      bool fresh = false;
+      if (j < kk) {
+        const int s = idx[rowoff + j];
+        if (s >= 0 && s < Lmax) {
+          slot = so[s];
+          fresh = (bm[s >> 5] >> (s & 31)) & 1u;
+        }
+        if (slot_idx_out) slot_idx_out[rowoff + j] = slot;
+      }
+      if (hit_list) {
+        const uint32_t is_hit = (slot >= 0 && !fresh) ? 1u : 0u;
+        const uint32_t is_miss = (slot >= 0 && fresh) ? 1u : 0u;
+        uint32_t tot;
+        const uint32_t inc = block_incl_scan(is_hit | (is_miss << 16), sm.wave_tot, &tot);
+        const uint32_t ex = inc - (is_hit | (is_miss << 16));
+        if (is_hit) hit_list[rowoff + base_hit + (ex & 0xffffu)] = slot;
+        if (is_miss) miss_list[rowoff + base_miss + (ex >> 16)] = slot;
+        base_hit += tot & 0xffffu;
+        base_miss += tot >> 16;
+      }
+    }
+    if (hit_list && tid == 0) {
+      n_hit[b * T + t] = (int32_t)base_hit;
+      n_miss[b * T + t] = (int32_t)base_miss;
+    }
+  }
+}
+
+// Fetch: one wave per missed entry, rows copied host pool -> slot pool in 16-byte pieces.
+__global__ __launch_bounds__(256) void k_fill(const uint8_t* __restrict__ host_pool, uint8_t* __restrict__ slot_pool,
+                                              const int32_t* __restrict__ fill_tok,
+                                              const int32_t* __restrict__ fill_slot, int fill_cap,
+                                              const int32_t* __restrict__ miss_cnt, int Lmax, int S, int row_stride) {
+  const int b = blockIdx.y;
+  const int m = min(miss_cnt[b], fill_cap);
+  const int lane = threadIdx.x & 63;
+  const int nw = gridDim.x * 4;
+  const int chunks = row_stride >> 4;
+  for (int i = blockIdx.x * 4 + (threadIdx.x >> 6); i < m; i += nw) {
+    const int s = fill_tok[(size_t)b * fill_cap + i];
+    const int v = fill_slot[(size_t)b * fill_cap + i];
+    const uint4* src = reinterpret_cast<const uint4*>(host_pool + ((size_t)b * Lmax + s) * row_stride);
+    uint4* dst = reinterpret_cast<uint4*>(slot_pool + ((size_t)b * S + v) * row_stride);
+    for (int c = lane; c < chunks; c += 64) dst[c] = src[c];
+  }
+}
+
+// rows_out[b,t,j,:] = slot_pool[b, slot_idx[b,t,j], :] (zeros where the slot is -1); one wave per row
+__global__ __launch_bounds__(256) void k_gather_rows(const uint8_t* __restrict__ slot_pool,
+                                                     const int32_t* __restrict__ slot_idx, int per_seq, int S,
+                                                     int row_stride, uint8_t* __restrict__ rows_out) {
+  const int b = blockIdx.y;
+  const int lane = threadIdx.x & 63;
+  const int nw = gridDim.x * 4;
+  const int chunks = row_stride >> 4;
+  for (int i = blockIdx.x * 4 + (threadIdx.x >> 6); i < per_seq; i += nw) {
+    const int v = slot_idx[(size_t)b * per_seq + i];
+    uint4* dst = reinterpret_cast<uint4*>(rows_out + ((size_t)b * per_seq + i) * row_stride);
+    if (v >= 0 && v < S) {
+      const uint4* src = reinterpret_cast<const uint4*>(slot_pool + ((size_t)b * S + v) * row_stride);
+      for (int c = lane; c < chunks; c += 64) dst[c] = src[c];
+    } else {
+      for (int c = lane; c < chunks; c += 64) dst[c] = make_uint4(0, 0, 0, 0);
+    }
+  }
+}
+
+__global__ void k_fill_u32(uint32_t* p, int n, uint32_t value) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = value;
+}
+
+__global__ void k_cache_reset(int32_t* slot_of, int32_t* token_of, uint32_t* stamp, int Lmax, int S, int identity) {
+  const int b = blockIdx.y;
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < Lmax) slot_of[(size_t)b * Lmax + i] = identity ? i : -1;
+  if (i < S) {
+    token_of[(size_t)b * S + i] = identity ? i : -1;
+    stamp[(size_t)b * S + i] = 0;
+  }
+}
+
+}  // namespace
+
+int ess_launch_fill_u32(uint32_t* p, int n, uint32_t value, hipStream_t st) {
+  hipLaunchKernelGGL(k_fill_u32, dim3((n + 255) / 256), dim3(256), 0, st, p, n, value);
+  ESS_HIP(hipGetLastError());
+  return ESS_OK;
+}
+
+int ess_launch_cache_reset(const ess_config& c, const ess_cache& cache, int B, hipStream_t st) {
+  const int n = c.max_ctx > c.slots_per_seq ? c.max_ctx : c.slots_per_seq;
+  hipLaunchKernelGGL(k_cache_reset, dim3((n + 255) / 256, B), dim3(256), 0, st, cache.slot_of, cache.token_of,
+                     cache.stamp, c.max_ctx, c.slots_per_seq, cache.host_pool_dev == nullptr ? 1 : 0);
+  ESS_HIP(hipGetLastError());
+  return ESS_OK;
+}
+
+int ess_launch_bookkeeping(ess_ctx* ctx, const ess_cache& cache, const int32_t* idx, int B, int T, int kk,
+                           uint32_t step, int32_t* slot_idx, int32_t* miss_count_out, hipStream_t st) {
+  const ess_config& c = ctx->cfg;
+  const size_t lds = (size_t)((c.max_ctx + 31) / 32) * sizeof(uint32_t);
+  const bool lists = (kk == c.topk);           // compacted lists have the pitch of the top-k
+  ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_bookkeeping), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)lds));
+  hipLaunchKernelGGL(k_bookkeeping, dim3(B), dim3(BT), lds, st, idx, T, kk, c.max_ctx, c.slots_per_seq,
+                     cache.slot_of, cache.token_of, cache.stamp, step, slot_idx,
+                     lists ? ctx->hit_list : nullptr, lists ? ctx->miss_list : nullptr, ctx->n_hit, ctx->n_miss,
+                     ctx->fill_tok, ctx->fill_slot, c.max_q_tokens * c.topk, ctx->miss_cnt, miss_count_out,
+                     ctx->stats, c.row_stride);
+  ESS_HIP(hipGetLastError());
+  return ESS_OK;
+}
+
+int ess_launch_fill(ess_ctx* ctx, const ess_cache& cache, int B, int per_seq_cap, hipStream_t st) {
+  const ess_config& c = ctx->cfg;
+  (void)per_seq_cap;
+  hipLaunchKernelGGL(k_fill, dim3(32, B), dim3(256), 0, st, cache.host_pool_dev, cache.slot_pool, ctx->fill_tok,
+                     ctx->fill_slot, c.max_q_tokens * c.topk, ctx->miss_cnt, c.max_ctx, c.slots_per_seq,
+                     c.row_stride);
+  ESS_HIP(hipGetLastError());
+  return ESS_OK;
+}
+
+int ess_launch_gather_rows(const ess_config& c, const uint8_t* slot_pool, const int32_t* slot_idx, int B, int T,
+                           uint8_t* rows_out, hipStream_t st) {
+  hipLaunchKernelGGL(k_gather_rows, dim3(64, B), dim3(256), 0, st, slot_pool, slot_idx, T * c.topk,
+                     c.slots_per_seq, c.row_stride, rows_out);
+  ESS_HIP(hipGetLastError());
+  return ESS_OK;
+}

@@ -1,0 +1,354 @@
+// C ABI of libess: argument validation, context life cycle and the stream
+// choreography of one layer-step (ESS paper Sec. 3.3: without overlap the
+// miss fetch serialises between indexer and attention; with DA overlap Attn0
+// over the resident entries runs while the fetch is in flight, Attn1 waits
+// for it, and the two are merged).
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "ess_internal.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int entry_bytes(int fmt) { return fmt == ESS_FMT_BF16 ? 1152 : 648; }
+
+int validate_config(const ess_config* c) {
+  if (!c) return ess_fail(ESS_ERR_INVALID_ARG, "config is NULL");
+  if (c->struct_size != sizeof(ess_config))
+    return ess_fail(ESS_ERR_INVALID_ARG, "struct_size %u != %zu", c->struct_size, sizeof(ess_config));
+  if (c->max_batch < 1 || c->max_batch > 65535) return ess_fail(ESS_ERR_INVALID_ARG, "max_batch %d", c->max_batch);
+  if (c->max_q_tokens < 1 || c->max_q_tokens > 2)
+    return ess_fail(ESS_ERR_UNSUPPORTED, "max_q_tokens %d (supported: 1, 2)", c->max_q_tokens);
+  if (c->max_ctx < 1 || c->max_ctx > ESS_MAX_CTX)
+    return ess_fail(ESS_ERR_INVALID_ARG, "max_ctx %d outside [1, %d]", c->max_ctx, ESS_MAX_CTX);
+  if (c->idx_heads < 1 || c->idx_heads > 64)
+    return ess_fail(ESS_ERR_UNSUPPORTED, "idx_heads %d outside [1, 64]", c->idx_heads);
+  if (c->idx_dim != 32 && c->idx_dim != 64 && c->idx_dim != 128)
+    return ess_fail(ESS_ERR_UNSUPPORTED, "idx_dim %d (supported: 32, 64, 128)", c->idx_dim);
+  if (c->topk < 1 || c->topk > ESS_MAX_TOPK)
+    return ess_fail(ESS_ERR_INVALID_ARG, "topk %d outside [1, %d]", c->topk, ESS_MAX_TOPK);
+  if (c->max_q_tokens * c->topk > ESS_MAX_SEL)
+    return ess_fail(ESS_ERR_CAPACITY, "T*k = %d exceeds %d", c->max_q_tokens * c->topk, ESS_MAX_SEL);
+  if (c->attn_heads < 1 || c->attn_heads > 128)
+    return ess_fail(ESS_ERR_UNSUPPORTED, "attn_heads %d outside [1, 128]", c->attn_heads);
+  if (c->latent_fmt != ESS_FMT_BF16 && c->latent_fmt != ESS_FMT_FP8)
+    return ess_fail(ESS_ERR_UNSUPPORTED, "latent_fmt %d", c->latent_fmt);
+  if (c->row_stride < entry_bytes(c->latent_fmt) || (c->row_stride & 15))
+    return ess_fail(ESS_ERR_INVALID_ARG, "row_stride %d must be a multiple of 16 and >= %d", c->row_stride,
+                    entry_bytes(c->latent_fmt));
+  if (c->slots_per_seq < 1 || c->slots_per_seq > c->max_ctx)
+    return ess_fail(ESS_ERR_INVALID_ARG, "slots_per_seq %d outside [1, max_ctx]", c->slots_per_seq);
+  const long need = (long)c->max_q_tokens * c->topk;
+  if (c->slots_per_seq < need && c->slots_per_seq < c->max_ctx)
+    return ess_fail(ESS_ERR_CAPACITY, "slots_per_seq %d cannot hold one step's selection (T*k = %ld)",
+                    c->slots_per_seq, need);
+  if (!(c->sm_scale > 0.f)) return ess_fail(ESS_ERR_INVALID_ARG, "sm_scale must be positive");
+  return ESS_OK;
+}
+
+struct WsLayout {
+  size_t score, slot_idx, hit, miss, n_hit, n_miss, fill_tok, fill_slot, miss_cnt, o_part, lse_part, stats, total;
+};
+
+size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+WsLayout ws_layout(const ess_config& c) {
+  const size_t B = c.max_batch, T = c.max_q_tokens, k = c.topk, H = c.attn_heads, L = c.max_ctx;
+  WsLayout w;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += up256(bytes); return o; };
+  w.score = take(B * T * L * 4);
+  w.slot_idx = take(B * T * k * 4);
+  w.hit = take(B * T * k * 4);
+  w.miss = take(B * T * k * 4);
+  w.n_hit = take(B * T * 4);
+  w.n_miss = take(B * T * 4);
+  w.fill_tok = take(B * T * k * 4);
+  w.fill_slot = take(B * T * k * 4);
+  w.miss_cnt = take(B * 4);
+  w.o_part = take(B * T * ESS_MAX_SPLITS * H * ESS_LATENT_DIM * 4);
+  w.lse_part = take(B * T * ESS_MAX_SPLITS * H * 4);
+  w.stats = take(4 * 8);
+  w.total = off;
+  return w;
+}
+
+int check_bt(const ess_ctx* ctx, int B, int T) {
+  if (!ctx) return ess_fail(ESS_ERR_INVALID_ARG, "context is NULL");
+  if (B < 1 || B > ctx->cfg.max_batch) return ess_fail(ESS_ERR_INVALID_ARG, "B %d outside [1, %d]", B, ctx->cfg.max_batch);
+  if (T < 1 || T > ctx->cfg.max_q_tokens)
+    return ess_fail(ESS_ERR_INVALID_ARG, "T %d outside [1, %d]", T, ctx->cfg.max_q_tokens);
+  return ESS_OK;
+}
+
+int check_cache(const ess_ctx* ctx, const ess_cache* c) {
+  if (!c) return ess_fail(ESS_ERR_INVALID_ARG, "cache is NULL");
+  if (!c->slot_pool || !c->slot_of || !c->token_of || !c->stamp)
+    return ess_fail(ESS_ERR_INVALID_ARG, "cache has a NULL array");
+  if (!aligned16(c->slot_pool) || !aligned16(c->host_pool_dev))
+    return ess_fail(ESS_ERR_INVALID_ARG, "slot_pool / host_pool_dev must be 16-byte aligned");
+  if (!c->host_pool_dev && ctx->cfg.slots_per_seq != ctx->cfg.max_ctx)
+    return ess_fail(ESS_ERR_INVALID_ARG, "without a host pool slots_per_seq must equal max_ctx");
+  return ESS_OK;
+}
+
+// number of attention splits for a list of up to k entries
+int pick_splits(const ess_config& c, int B, int T, int cap) {
+  const int tiles = (c.topk + ESS_ATTN_TILE - 1) / ESS_ATTN_TILE;
+  const int hgroups = ((c.attn_heads + 15) / 16 + 3) / 4;
+  int want = (1024 + B * T * hgroups - 1) / (B * T * hgroups);   // aim at >= 1024 workgroups (4 per CU)
+  if (want > tiles) want = tiles;
+  if (want > cap) want = cap;
+  return want < 1 ? 1 : want;
+}
+
+// bookkeeping + fetch, with the fetch on the side stream unless serial.  After return, work
+// enqueued on `st` is ordered after the bookkeeping; *fill_pending tells whether ev_fill must
+// still be waited for before the fetched rows are read.
+int run_cache_step(ess_ctx* ctx, const ess_cache& cache, const int32_t* idx, int B, int T, int kk, uint32_t step,
+                   int32_t* slot_idx, int32_t* miss_count, hipStream_t st, bool* fill_pending) {
+  *fill_pending = false;
+  int rc = ess_launch_bookkeeping(ctx, cache, idx, B, T, kk, step, slot_idx, miss_count, st);
+  if (rc != ESS_OK) return rc;
+  if (!cache.host_pool_dev) return ESS_OK;      // nothing offloaded: no entry can be missing
+  if (ctx->cfg.flags & ESS_FLAG_SERIAL) return ess_launch_fill(ctx, cache, B, T * kk, st);
+  ESS_HIP(hipEventRecord(ctx->ev_book, st));
+  ESS_HIP(hipStreamWaitEvent(ctx->side, ctx->ev_book, 0));
+  rc = ess_launch_fill(ctx, cache, B, T * kk, ctx->side);
+  if (rc != ESS_OK) return rc;
+  ESS_HIP(hipEventRecord(ctx->ev_fill, ctx->side));
+  *fill_pending = true;
+  return ESS_OK;
+}
+
+}  // namespace
+
+int ess_fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+extern "C" {
+
+const char* ess_last_error(void) { return g_err; }
+
+int ess_workspace_bytes(const ess_config* cfg, size_t* out) {
+  int rc = validate_config(cfg);
+  if (rc != ESS_OK) return rc;
+  if (!out) return ess_fail(ESS_ERR_INVALID_ARG, "out is NULL");
+  *out = ws_layout(*cfg).total;
+  return ESS_OK;
+}
+
+int ess_create(const ess_config* cfg, ess_ctx** out) {
+  int rc = validate_config(cfg);
+  if (rc != ESS_OK) return rc;
+  if (!out) return ess_fail(ESS_ERR_INVALID_ARG, "out is NULL");
+  *out = nullptr;
+  ess_ctx* ctx = new (std::nothrow) ess_ctx();
+  if (!ctx) return ess_fail(ESS_ERR_NOMEM, "host allocation failed");
+  memset(ctx, 0, sizeof(*ctx));
+  ctx->cfg = *cfg;
+  hipError_t e = hipGetDevice(&ctx->device);
+  if (e != hipSuccess) { delete ctx; return ess_fail(ESS_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e)); }
+  const WsLayout w = ws_layout(*cfg);
+  uint8_t* base = nullptr;
+  e = hipMalloc(reinterpret_cast<void**>(&base), w.total);
+  if (e != hipSuccess) {
+    delete ctx;
+    (void)hipGetLastError();
+    return ess_fail(ESS_ERR_NOMEM, "workspace of %zu bytes: %s", w.total, hipGetErrorString(e));
+  }
+  ctx->ws_bytes = w.total;
+  ctx->score_ws = reinterpret_cast<float*>(base + w.score);
+  ctx->slot_idx_ws = reinterpret_cast<int32_t*>(base + w.slot_idx);
+  ctx->hit_list = reinterpret_cast<int32_t*>(base + w.hit);
+  ctx->miss_list = reinterpret_cast<int32_t*>(base + w.miss);
+  ctx->n_hit = reinterpret_cast<int32_t*>(base + w.n_hit);
+  ctx->n_miss = reinterpret_cast<int32_t*>(base + w.n_miss);
+  ctx->fill_tok = reinterpret_cast<int32_t*>(base + w.fill_tok);
+  ctx->fill_slot = reinterpret_cast<int32_t*>(base + w.fill_slot);
+  ctx->miss_cnt = reinterpret_cast<int32_t*>(base + w.miss_cnt);
+  ctx->o_part = reinterpret_cast<float*>(base + w.o_part);
+  ctx->lse_part = reinterpret_cast<float*>(base + w.lse_part);
+  ctx->stats = reinterpret_cast<unsigned long long*>(base + w.stats);
+  auto bail = [&](const char* what, hipError_t err) {
+    if (ctx->ev_book) (void)hipEventDestroy(ctx->ev_book);
+    if (ctx->ev_fill) (void)hipEventDestroy(ctx->ev_fill);
+    if (ctx->side) (void)hipStreamDestroy(ctx->side);
+    (void)hipFree(base);
+    delete ctx;
+    return ess_fail(ESS_ERR_HIP, "%s: %s", what, hipGetErrorString(err));
+  };
+  if ((e = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking)) != hipSuccess) return bail("hipStreamCreate", e);
+  if ((e = hipEventCreateWithFlags(&ctx->ev_book, hipEventDisableTiming)) != hipSuccess) return bail("hipEventCreate", e);
+  if ((e = hipEventCreateWithFlags(&ctx->ev_fill, hipEventDisableTiming)) != hipSuccess) return bail("hipEventCreate", e);
+  if ((e = hipMemset(ctx->stats, 0, 32)) != hipSuccess) return bail("hipMemset", e);
+  *out = ctx;
+  return ESS_OK;
+}
+
+int ess_destroy(ess_ctx* ctx) {
+  if (!ctx) return ESS_OK;
+  (void)hipStreamSynchronize(ctx->side);
+  (void)hipEventDestroy(ctx->ev_book);
+  (void)hipEventDestroy(ctx->ev_fill);
+  (void)hipStreamDestroy(ctx->side);
+  (void)hipFree(ctx->score_ws);                 // base of the workspace
+  delete ctx;
+  return ESS_OK;
+}
+
+int ess_cache_reset(ess_ctx* ctx, const ess_cache* cache, int32_t B, void* stream) {
+  int rc = check_bt(ctx, B, 1);
+  if (rc != ESS_OK) return rc;
+  if ((rc = check_cache(ctx, cache)) != ESS_OK) return rc;
+  return ess_launch_cache_reset(ctx->cfg, *cache, B, static_cast<hipStream_t>(stream));
+}
+
+int ess_cache_admit(ess_ctx* ctx, const ess_cache* cache, const int32_t* tok, int32_t B, int32_t n, uint32_t step,
+                    void* stream) {
+  int rc = check_bt(ctx, B, 1);
+  if (rc != ESS_OK) return rc;
+  if ((rc = check_cache(ctx, cache)) != ESS_OK) return rc;
+  if (!tok) return ess_fail(ESS_ERR_INVALID_ARG, "tok is NULL");
+  if (n < 1 || n > ctx->cfg.max_q_tokens * ctx->cfg.topk)
+    return ess_fail(ESS_ERR_CAPACITY, "n %d outside [1, T*k = %d]", n, ctx->cfg.max_q_tokens * ctx->cfg.topk);
+  if (n > ctx->cfg.slots_per_seq) return ess_fail(ESS_ERR_CAPACITY, "n %d exceeds the slot pool", n);
+  if (step < 1) return ess_fail(ESS_ERR_INVALID_ARG, "step must be >= 1");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  bool pending = false;
+  // one list of n entries per sequence, no per-query outputs
+  rc = run_cache_step(ctx, *cache, tok, B, 1, n, step, nullptr, nullptr, st, &pending);
+  if (rc != ESS_OK) return rc;
+  if (pending) ESS_HIP(hipStreamWaitEvent(st, ctx->ev_fill, 0));
+  return ESS_OK;
+}
+
+int ess_index_score(ess_ctx* ctx, const uint8_t* q, const float* w, const uint8_t* key, const int32_t* ctx_len,
+                    int32_t B, int32_t T, float* score, void* stream) {
+  int rc = check_bt(ctx, B, T);
+  if (rc != ESS_OK) return rc;
+  if (!q || !w || !key || !ctx_len || !score) return ess_fail(ESS_ERR_INVALID_ARG, "NULL argument");
+  if (!aligned16(q) || !aligned16(key) || !aligned16(score))
+    return ess_fail(ESS_ERR_INVALID_ARG, "q, key and score must be 16-byte aligned");
+  return ess_launch_index_score(ctx->cfg, q, w, key, ctx_len, B, T, score, static_cast<hipStream_t>(stream));
+}
+
+int ess_topk(ess_ctx* ctx, const float* score, const int32_t* ctx_len, int32_t B, int32_t T, int32_t* idx,
+             void* stream) {
+  int rc = check_bt(ctx, B, T);
+  if (rc != ESS_OK) return rc;
+  if (!score || !ctx_len || !idx) return ess_fail(ESS_ERR_INVALID_ARG, "NULL argument");
+  return ess_launch_topk(ctx->cfg, score, ctx_len, B, T, idx, static_cast<hipStream_t>(stream));
+}
+
+int ess_gather_latent(ess_ctx* ctx, const ess_cache* cache, const int32_t* idx, const int32_t* ctx_len, int32_t B,
+                      int32_t T, uint32_t step, int32_t* slot_idx, uint8_t* rows_out, int32_t* miss_count,
+                      void* stream) {
+  int rc = check_bt(ctx, B, T);
+  if (rc != ESS_OK) return rc;
+  if ((rc = check_cache(ctx, cache)) != ESS_OK) return rc;
+  if (!idx || !slot_idx) return ess_fail(ESS_ERR_INVALID_ARG, "idx / slot_idx is NULL");
+  if (!aligned16(rows_out)) return ess_fail(ESS_ERR_INVALID_ARG, "rows_out must be 16-byte aligned");
+  if (step < 1) return ess_fail(ESS_ERR_INVALID_ARG, "step must be >= 1");
+  (void)ctx_len;                                // visibility was already applied by the selection
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  bool pending = false;
+  rc = run_cache_step(ctx, *cache, idx, B, T, ctx->cfg.topk, step, slot_idx, miss_count, st, &pending);
+  if (rc != ESS_OK) return rc;
+  if (pending) ESS_HIP(hipStreamWaitEvent(st, ctx->ev_fill, 0));
+  if (rows_out) return ess_launch_gather_rows(ctx->cfg, cache->slot_pool, slot_idx, B, T, rows_out, st);
+  return ESS_OK;
+}
+
+int ess_sparse_mla_decode(ess_ctx* ctx, const void* q_bf16, const uint8_t* slot_pool, const int32_t* slot_idx,
+                          int32_t B, int32_t T, void* out_bf16, float* lse, void* stream) {
+  int rc = check_bt(ctx, B, T);
+  if (rc != ESS_OK) return rc;
+  if (!q_bf16 || !slot_pool || !slot_idx || !out_bf16) return ess_fail(ESS_ERR_INVALID_ARG, "NULL argument");
+  if (!aligned16(q_bf16) || !aligned16(slot_pool) || !aligned16(out_bf16))
+    return ess_fail(ESS_ERR_INVALID_ARG, "q, slot_pool and out must be 16-byte aligned");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int ns = pick_splits(ctx->cfg, B, T, 16);
+  rc = ess_launch_attn_partial(ctx, q_bf16, slot_pool, slot_idx, nullptr, B, T, 0, ns, st);
+  if (rc != ESS_OK) return rc;
+  return ess_launch_attn_merge(ctx, B, T, ns, out_bf16, lse, st);
+}
+
+int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a, void* stream) {
+  if (!a) return ess_fail(ESS_ERR_INVALID_ARG, "args is NULL");
+  int rc = check_bt(ctx, a->B, a->T);
+  if (rc != ESS_OK) return rc;
+  if ((rc = check_cache(ctx, cache)) != ESS_OK) return rc;
+  if (!a->q_idx_fp8 || !a->w || !a->key_fp8 || !a->ctx_len || !a->q_bf16 || !a->idx_out || !a->out_bf16)
+    return ess_fail(ESS_ERR_INVALID_ARG, "NULL argument");
+  if (!aligned16(a->q_idx_fp8) || !aligned16(a->key_fp8) || !aligned16(a->q_bf16) || !aligned16(a->out_bf16))
+    return ess_fail(ESS_ERR_INVALID_ARG, "q_idx_fp8, key_fp8, q_bf16 and out_bf16 must be 16-byte aligned");
+  if (a->step < 1) return ess_fail(ESS_ERR_INVALID_ARG, "step must be >= 1");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const ess_config& c = ctx->cfg;
+  const int B = a->B, T = a->T;
+
+  // stages 1-2
+  rc = ess_launch_index_score(c, a->q_idx_fp8, a->w, a->key_fp8, a->ctx_len, B, T, ctx->score_ws, st);
+  if (rc != ESS_OK) return rc;
+  rc = ess_launch_topk(c, ctx->score_ws, a->ctx_len, B, T, a->idx_out, st);
+  if (rc != ESS_OK) return rc;
+  const int32_t* used = a->topk_override ? a->topk_override : a->idx_out;
+
+  if (!cache->host_pool_dev) {
+    // nothing offloaded: slot == position, attention straight over the selection
+    const int ns = pick_splits(c, B, T, 16);
+    rc = ess_launch_attn_partial(ctx, a->q_bf16, cache->slot_pool, used, nullptr, B, T, 0, ns, st);
+    if (rc != ESS_OK) return rc;
+    if (a->miss_count && (rc = ess_launch_fill_u32(reinterpret_cast<uint32_t*>(a->miss_count), B, 0u, st)) != ESS_OK) return rc;
+    return ess_launch_attn_merge(ctx, B, T, ns, a->out_bf16, a->lse, st);
+  }
+
+  // stages 3 + 5, fetch on the side stream
+  bool pending = false;
+  rc = run_cache_step(ctx, *cache, used, B, T, c.topk, a->step, ctx->slot_idx_ws, a->miss_count, st, &pending);
+  if (rc != ESS_OK) return rc;
+  // stage 4: Attn0 over resident entries while the fetch runs, Attn1 over fetched ones, merge
+  const int ns0 = pick_splits(c, B, T, 16);
+  int ns1 = ns0 / 4;
+  if (ns1 < 1) ns1 = 1;
+  if (ns1 > ESS_MAX_SPLITS - 16) ns1 = ESS_MAX_SPLITS - 16;
+  rc = ess_launch_attn_partial(ctx, a->q_bf16, cache->slot_pool, ctx->hit_list, ctx->n_hit, B, T, 0, ns0, st);
+  if (rc != ESS_OK) return rc;
+  if (pending) ESS_HIP(hipStreamWaitEvent(st, ctx->ev_fill, 0));
+  rc = ess_launch_attn_partial(ctx, a->q_bf16, cache->slot_pool, ctx->miss_list, ctx->n_miss, B, T, ns0, ns1, st);
+  if (rc != ESS_OK) return rc;
+  return ess_launch_attn_merge(ctx, B, T, ns0 + ns1, a->out_bf16, a->lse, st);
+}
+
+int ess_get_stats(ess_ctx* ctx, ess_stats* host_out, void* stream) {
+  if (!ctx || !host_out) return ess_fail(ESS_ERR_INVALID_ARG, "NULL argument");
+  ESS_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+  ESS_HIP(hipStreamSynchronize(ctx->side));
+  unsigned long long h[4];
+  ESS_HIP(hipMemcpy(h, ctx->stats, sizeof(h), hipMemcpyDeviceToHost));
+  host_out->steps = h[0];
+  host_out->selected = h[1];
+  host_out->misses = h[2];
+  host_out->bytes_filled = h[3];
+  return ESS_OK;
+}
+
+int ess_reset_stats(ess_ctx* ctx, void* stream) {
+  if (!ctx) return ess_fail(ESS_ERR_INVALID_ARG, "context is NULL");
+  return ess_launch_fill_u32(reinterpret_cast<uint32_t*>(ctx->stats), 8, 0u, static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

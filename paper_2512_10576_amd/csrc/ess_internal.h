@@ -1,0 +1,64 @@
+// Internal declarations shared by the translation units of libess (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "ess.h"
+
+#define ESS_MAX_CTX 524288      // selection bitmap of one sequence must fit in LDS (64 KiB)
+#define ESS_MAX_TOPK 4096
+#define ESS_MAX_SEL 8192        // T * k
+#define ESS_ATTN_TILE 32        // entries per attention tile
+#define ESS_MAX_SPLITS 20       // partial results per (b,t): Attn0 splits + Attn1 splits
+#define ESS_ROW_DIM 576
+
+struct ess_ctx {
+  ess_config cfg;
+  int device;
+  hipStream_t side;             // miss fetch stream (default priority)
+  hipEvent_t ev_book, ev_fill;  // bookkeeping done / fetch done
+  // workspace (device)
+  float* score_ws;              // [B,T,Lmax]
+  int32_t* slot_idx_ws;         // [B,T,k]
+  int32_t* hit_list;            // [B,T,k] slots of entries resident before the step, compacted
+  int32_t* miss_list;           // [B,T,k] slots of entries fetched in this step, compacted
+  int32_t* n_hit;               // [B,T]
+  int32_t* n_miss;              // [B,T]
+  int32_t* fill_tok;            // [B,T*k] token to fetch
+  int32_t* fill_slot;           // [B,T*k] slot to fetch into
+  int32_t* miss_cnt;            // [B]
+  float* o_part;                // [B*T, ESS_MAX_SPLITS, H, 512]
+  float* lse_part;              // [B*T, ESS_MAX_SPLITS, H]
+  unsigned long long* stats;    // [4]
+  size_t ws_bytes;
+};
+
+int ess_fail(int code, const char* fmt, ...);
+
+#define ESS_HIP(call)                                                                       \
+  do {                                                                                      \
+    hipError_t e_ = (call);                                                                 \
+    if (e_ != hipSuccess)                                                                   \
+      return ess_fail(ESS_ERR_HIP, "%s failed: %s (%s:%d)", #call, hipGetErrorString(e_),   \
+                      __FILE__, __LINE__);                                                  \
+  } while (0)
+
+// Stage launchers.  All enqueue on `st` and return an ess_status.
+int ess_launch_index_score(const ess_config& c, const uint8_t* q, const float* w, const uint8_t* key,
+                           const int32_t* ctx_len, int B, int T, float* score, hipStream_t st);
+int ess_launch_topk(const ess_config& c, const float* score, const int32_t* ctx_len, int B, int T,
+                    int32_t* idx, hipStream_t st);
+// fill kernel (used instead of hipMemsetAsync so that callers may capture the stream in a graph)
+int ess_launch_fill_u32(uint32_t* p, int n, uint32_t value, hipStream_t st);
+int ess_launch_cache_reset(const ess_config& c, const ess_cache& cache, int B, hipStream_t st);
+// look-up + LRU update + lists; n_sel = entries per sequence in idx ([B,n_sel], T lists of n_sel/T)
+int ess_launch_bookkeeping(ess_ctx* ctx, const ess_cache& cache, const int32_t* idx, int B, int T, int kk,
+                           uint32_t step, int32_t* slot_idx, int32_t* miss_count_out, hipStream_t st);
+int ess_launch_fill(ess_ctx* ctx, const ess_cache& cache, int B, int per_seq_cap, hipStream_t st);
+int ess_launch_gather_rows(const ess_config& c, const uint8_t* slot_pool, const int32_t* slot_idx, int B, int T,
+                           uint8_t* rows_out, hipStream_t st);
+// attention over list[b,t,0..n) (n = n_list[b,t], or k when n_list is NULL), written as `nsplit`
+// partial results starting at partial index `split0`
+int ess_launch_attn_partial(ess_ctx* ctx, const void* q, const uint8_t* slot_pool, const int32_t* list,
+                            const int32_t* n_list, int B, int T, int split0, int nsplit, hipStream_t st);
+int ess_launch_attn_merge(ess_ctx* ctx, int B, int T, int nsplit_total, void* out_bf16, float* lse,
+                          hipStream_t st);

@@ -1,0 +1,196 @@
+// Stage 1: indexer score over the whole Indexer-Cache (ESS paper Sec. 3).
+//
+//   score[b,t,s] = sum_j w[b,t,j] * max(0, sum_d q[b,t,j,d] * key[b,s,d])
+//
+// The kernel is a key stream: every 128-byte key is read from HBM exactly
+// once (for all T query tokens), the q.k contraction runs on the fp8 matrix
+// cores (v_mfma_f32_16x16x32_fp8_fp8, heads = M, tokens = N, dim = K) and the
+// ReLU / head-weighted reduction stays in registers.
+//
+// Register layout.  A wave handles 16 tokens per MFMA tile.  Lane l = 16*g + n
+// (g = 0..3, n = 0..15) owns token n of the tile and the g-th quarter of the
+// contraction dimension.  Because a dot product does not depend on the order
+// of its terms, the hardware's k index is mapped onto the key dimension so
+// that each lane's share is contiguous in memory: for Di = 128 lane (g,n)
+// loads bytes [16g,16g+16) and [64+16g,64+16g+16) of its key row with two
+// 16-byte loads, which makes every load instruction of the wave touch 64
+// contiguous bytes per row; q is loaded with the same mapping.  The
+// accumulator of lane (g,n) holds heads 16*mb + 4g + i (i = 0..3) of token n,
+// so the head reduction is 4*HB fused multiply-adds in the lane plus two
+// cross-lane steps (xor 16, xor 32).
+#include "ess_internal.h"
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr int kWaves = 4;                 // waves per workgroup
+constexpr int kTilesPerBatch = 4;         // 4 tiles x 16 tokens = 64 scores = one coalesced 256-byte store per wave
+constexpr int kBatchTokens = 16 * kTilesPerBatch;
+
+template <int KS>
+struct KeyRegs {                          // one tile's key bytes held by a lane: KS x 8 bytes
+  long v[KS];
+};
+
+template <int DI>
+__device__ __forceinline__ void load_row_share(const uint8_t* row, int g, long (&dst)[DI / 32]) {
+  constexpr int KS = DI / 32;
+  if constexpr (KS == 1) {
+    dst[0] = *reinterpret_cast<const long*>(row + g * 8);
+  } else {
+#pragma unroll
+    for (int c = 0; c < KS / 2; ++c) {
+      const uint4 x = *reinterpret_cast<const uint4*>(row + c * 64 + g * 16);
+      dst[2 * c] = (long)(((unsigned long)x.y << 32) | x.x);
+      dst[2 * c + 1] = (long)(((unsigned long)x.w << 32) | x.z);
+    }
+  }
+}
+
+// HB = 16-head blocks (Hi padded up), DI = indexer dim, T = query tokens per sequence
+template <int HB, int DI, int T>
+__global__ __launch_bounds__(kWaves * 64) void k_index_score(const uint8_t* __restrict__ q,
+                                                              const float* __restrict__ w,
+                                                              const uint8_t* __restrict__ key,
+                                                              const int32_t* __restrict__ ctx_len,
+                                                              float* __restrict__ score, int Lmax, int Hi,
+                                                              int chunk_tokens) {
+  constexpr int KS = DI / 32;
+  const int b = blockIdx.y;
+  const int len = min(ctx_len[b], Lmax);
+  const int blk_base = blockIdx.x * chunk_tokens;
+  if (blk_base >= len) return;
+  const int blk_end = min(blk_base + chunk_tokens, len);
+
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int g = lane >> 4;
+  const int n = lane & 15;
+
+  // stationary operands: q as the A matrix (row = head), w per accumulator row
+  long qa[T][HB][KS];
+  float wr[T][HB][4];
+#pragma unroll
+  for (int t = 0; t < T; ++t) {
+#pragma unroll
+    for (int mb = 0; mb < HB; ++mb) {
+      const int head = mb * 16 + n;
+      if (head < Hi) {
+        load_row_share<DI>(q + ((size_t)(b * T + t) * Hi + head) * DI, g, qa[t][mb]);
+      } else {
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) qa[t][mb][kk] = 0;
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int hrow = mb * 16 + g * 4 + i;
+        wr[t][mb][i] = hrow < Hi ? w[(size_t)(b * T + t) * Hi + hrow] : 0.f;
+      }
+    }
+  }
+
+  const uint8_t* kbase = key + (size_t)b * Lmax * DI;
+  const int last_row = Lmax - 1;
+
+  auto load_batch = [&](int base, KeyRegs<KS> (&dst)[kTilesPerBatch]) {
+#pragma unroll
+    for (int u = 0; u < kTilesPerBatch; ++u) {
+      const int row = min(base + u * 16 + n, last_row);       // clamp keeps ragged tails in bounds
+      load_row_share<DI>(kbase + (size_t)row * DI, g, dst[u].v);
+    }
+  };
+
+  auto compute_batch = [&](int base, const KeyRegs<KS> (&kr)[kTilesPerBatch]) {
+    float res[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) res[t] = 0.f;
+#pragma unroll
+    for (int u = 0; u < kTilesPerBatch; ++u) {
+#pragma unroll
+      for (int t = 0; t < T; ++t) {
+        float s = 0.f;
+#pragma unroll
+        for (int mb = 0; mb < HB; ++mb) {
+          floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int kk = 0; kk < KS; ++kk)
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(qa[t][mb][kk], kr[u].v[kk], acc, 0, 0, 0);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) s = fmaf(wr[t][mb][i], fmaxf(acc[i], 0.f), s);
+        }
+        s += __shfl_xor(s, 16, 64);
+        s += __shfl_xor(s, 32, 64);
+        res[t] = (g == u) ? s : res[t];                       // lane (g,n) keeps tile g's token n
+      }
+    }
+    const int tok = base + lane;                              // = base + 16*g + n
+    if (tok < blk_end) {
+#pragma unroll
+      for (int t = 0; t < T; ++t) score[(size_t)(b * T + t) * Lmax + tok] = res[t];
+    }
+  };
+
+  // two register buffers: the loads of batch i+1 are in flight while batch i is computed
+  constexpr int kStride = kWaves * kBatchTokens;
+  int base = blk_base + wave * kBatchTokens;
+  if (base >= blk_end) return;
+  KeyRegs<KS> bufA[kTilesPerBatch], bufB[kTilesPerBatch];
+  load_batch(base, bufA);
+  for (;;) {
+    const bool moreB = base + kStride < blk_end;
+    if (moreB) load_batch(base + kStride, bufB);
+    compute_batch(base, bufA);
+    if (!moreB) break;
+    base += kStride;
+    const bool moreA = base + kStride < blk_end;
+    if (moreA) load_batch(base + kStride, bufA);
+    compute_batch(base, bufB);
+    if (!moreA) break;
+    base += kStride;
+  }
+}
+
+template <int HB, int DI>
+int launch_t(int T, dim3 grid, hipStream_t st, const uint8_t* q, const float* w, const uint8_t* key,
+             const int32_t* ctx_len, float* score, int Lmax, int Hi, int chunk) {
+  if (T == 1)
+    hipLaunchKernelGGL((k_index_score<HB, DI, 1>), grid, dim3(kWaves * 64), 0, st, q, w, key, ctx_len, score,
+                       Lmax, Hi, chunk);
+  else
+    hipLaunchKernelGGL((k_index_score<HB, DI, 2>), grid, dim3(kWaves * 64), 0, st, q, w, key, ctx_len, score,
+                       Lmax, Hi, chunk);
+  return ESS_OK;
+}
+
+template <int DI>
+int launch_hb(int HB, int T, dim3 grid, hipStream_t st, const uint8_t* q, const float* w, const uint8_t* key,
+              const int32_t* ctx_len, float* score, int Lmax, int Hi, int chunk) {
+  switch (HB) {
+    case 1: return launch_t<1, DI>(T, grid, st, q, w, key, ctx_len, score, Lmax, Hi, chunk);
+    case 2: return launch_t<2, DI>(T, grid, st, q, w, key, ctx_len, score, Lmax, Hi, chunk);
+    case 3: return launch_t<3, DI>(T, grid, st, q, w, key, ctx_len, score, Lmax, Hi, chunk);
+    default: return launch_t<4, DI>(T, grid, st, q, w, key, ctx_len, score, Lmax, Hi, chunk);
+  }
+}
+
+}  // namespace
+
+int ess_launch_index_score(const ess_config& c, const uint8_t* q, const float* w, const uint8_t* key,
+                           const int32_t* ctx_len, int B, int T, float* score, hipStream_t st) {
+  const int Hi = c.idx_heads, Di = c.idx_dim, Lmax = c.max_ctx;
+  const int HB = (Hi + 15) / 16;
+  // tokens per workgroup: a multiple of the 256 tokens the four waves cover per round
+  const int chunk = 1024;
+  dim3 grid((Lmax + chunk - 1) / chunk, B);
+  int rc;
+  switch (Di) {
+    case 32: rc = launch_hb<32>(HB, T, grid, st, q, w, key, ctx_len, score, Lmax, Hi, chunk); break;
+    case 64: rc = launch_hb<64>(HB, T, grid, st, q, w, key, ctx_len, score, Lmax, Hi, chunk); break;
+    case 128: rc = launch_hb<128>(HB, T, grid, st, q, w, key, ctx_len, score, Lmax, Hi, chunk); break;
+    default: return ess_fail(ESS_ERR_UNSUPPORTED, "idx_dim %d (supported: 32, 64, 128)", Di);
+  }
+  if (rc != ESS_OK) return rc;
+  ESS_HIP(hipGetLastError());
+  return ESS_OK;
+}

@@ -1,0 +1,318 @@
+// Stage 4: SparseMLA decode over the selected Latent-Cache entries (ESS paper
+// Sec. 3.3), absorbed form: the 576 values of an entry are the key, the first
+// 512 the value.  Flash-decoding layout: every (b,t) is cut into `nsplit`
+// ranges of its entry list; each workgroup produces a softmax-normalised
+// partial output and its log-sum-exp, and a merge kernel combines the partial
+// results -- the same merge that joins Attn0 (resident entries) and Attn1
+// (fetched entries) of the DA overlap.
+//
+// Matrix-core mapping (v_mfma_f32_16x16x32_bf16, wave64).  A wave owns 16
+// heads.  Both products are computed transposed so that nothing has to be
+// re-laid out between them:
+//   S^T[r,h] = sum_d K[r,d] Q[h,d]   A = entry rows from LDS (row-major),
+//                                    B = Q^T, stationary in registers (72 VGPRs)
+//   O^T[v,h] = sum_r V^T[v,r] P^T[r,h]  A = V^T from LDS, B = P^T
+// The accumulator of S^T gives lane (g,h) the eight logits of head h for tile
+// rows {4g..4g+3} and {16+4g..16+4g+3}; in exactly that order they are the
+// eight k-values a lane supplies for the B operand of the second product, so
+// P^T never leaves registers.  The softmax state (running max, running sum)
+// is per lane = per head; the max needs two cross-lane steps per tile.
+// The second product needs V^T with the tile rows contiguous, so every tile
+// is stored twice in LDS while it is staged: row-major for the first product
+// and transposed (rows permuted to match the order above, 16-byte granules
+// XOR-swizzled against bank conflicts) for the second.
+#include "ess_internal.h"
+#include <hip/hip_bf16.h>
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+namespace {
+
+constexpr int TILE = ESS_ATTN_TILE;            // 32 entries
+constexpr int KPITCH = 1152 + 16;              // bytes; +16 spreads the 16 rows of an A fragment over the banks
+constexpr int KSTEPS = ESS_ROW_DIM / 32;       // 18
+constexpr int VBLOCKS = ESS_LATENT_DIM / 16;   // 32
+constexpr int KT_BYTES = TILE * KPITCH;        // 37376
+constexpr int VT_BYTES = ESS_LATENT_DIM * 64;  // 32768: V^T[v][32 positions] bf16
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+__device__ __forceinline__ int vt_granule(int v, int gran) { return gran ^ (((v >> 1) ^ (v >> 3)) & 3); }
+
+__device__ __forceinline__ float fp8_e4m3_to_f32(uint32_t byte) {
+  // OCP E4M3: 1-4-3, bias 7, subnormals at exponent 0 (NaN pattern is not produced by the quantiser)
+  const uint32_t s = (byte & 0x80u) << 24;
+  const uint32_t e = (byte >> 3) & 0xFu;
+  const uint32_t m = byte & 0x7u;
+  float mag;
+  if (e == 0) mag = (float)m * 0.001953125f;                     // m/8 * 2^-6
+  else mag = __uint_as_float(((e + 120u) << 23) | (m << 20));   // (1 + m/8) * 2^(e-7)
+  return __uint_as_float(__float_as_uint(mag) | s);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  const __hip_bfloat16 x = __float2bfloat16(a), y = __float2bfloat16(b);
+  return (uint32_t)(*reinterpret_cast<const uint16_t*>(&x)) | ((uint32_t)(*reinterpret_cast<const uint16_t*>(&y)) << 16);
+}
+
+// One 16-byte piece (8 bf16 values, dims [8*cc, 8*cc+8)) of an entry, whatever its storage format.
+template <int FMT>
+__device__ __forceinline__ uint4 load_piece(const uint8_t* row, int cc) {
+  if constexpr (FMT == ESS_FMT_BF16) {
+    return *reinterpret_cast<const uint4*>(row + cc * 16);
+  } else {
+    if (cc >= 64) return *reinterpret_cast<const uint4*>(row + 520 + (cc - 64) * 16);  // rope, stored as bf16
+    const uint2 raw = *reinterpret_cast<const uint2*>(row + cc * 8);
+    const uint16_t sbits = *reinterpret_cast<const uint16_t*>(row + 512 + (cc >> 4) * 2);
+    const float sc = __uint_as_float((uint32_t)sbits << 16);
+    float f[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      f[i] = fp8_e4m3_to_f32((raw.x >> (8 * i)) & 0xFFu) * sc;
+      f[4 + i] = fp8_e4m3_to_f32((raw.y >> (8 * i)) & 0xFFu) * sc;
+    }
+    return make_uint4(pack_bf16(f[0], f[1]), pack_bf16(f[2], f[3]), pack_bf16(f[4], f[5]), pack_bf16(f[6], f[7]));
+  }
+}
+
+// NW waves per workgroup, 16 heads each.
+template <int NW, int FMT>
+__global__ __launch_bounds__(NW * 64, 2) void k_attn_partial(
+    const uint16_t* __restrict__ q, const uint8_t* __restrict__ pool, const int32_t* __restrict__ list,
+    const int32_t* __restrict__ n_list, int T, int H, int kk, int S, int row_stride, float scale_log2e, int split0,
+    int nsplit, float* __restrict__ o_part, float* __restrict__ lse_part) {
+  extern __shared__ __align__(16) uint8_t lds[];
+  uint8_t* Kt = lds;
+  uint8_t* Vt = lds + KT_BYTES;
+  int32_t* tile_slot = reinterpret_cast<int32_t*>(lds + KT_BYTES + VT_BYTES);   // [32]
+
+  constexpr int NTH = NW * 64;
+  const int split = blockIdx.x;
+  const int bt = blockIdx.y;
+  const int b = bt / T;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = lane >> 4, n16 = lane & 15;
+  const int head = (blockIdx.z * NW + wave) * 16 + n16;
+
+  const int n = n_list ? min(n_list[bt], kk) : kk;
+  const int tiles_total = (n + TILE - 1) / TILE;
+  const int tps = (tiles_total + nsplit - 1) / nsplit;
+  const int tile_begin = split * tps;
+  const int tile_end = min(tile_begin + tps, tiles_total);
+
+  // Q^T fragments: lane (g,h) holds Q[h][32*ks + 8g .. +8)
+  bf16x8 qb[KSTEPS];
+  {
+    const uint16_t* qrow = q + ((size_t)bt * H + min(head, H - 1)) * ESS_ROW_DIM;
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+      uint4 x = *reinterpret_cast<const uint4*>(qrow + ks * 32 + g * 8);
+      if (head >= H) x = make_uint4(0, 0, 0, 0);
+      qb[ks] = *reinterpret_cast<bf16x8*>(&x);
+    }
+  }
+
+  floatx4 acc[VBLOCKS];
+#pragma unroll
+  for (int vb = 0; vb < VBLOCKS; ++vb) acc[vb] = floatx4{0.f, 0.f, 0.f, 0.f};
+  float m_run = -__builtin_inff();             // running max of the scaled logits (log2 domain)
+  float l_run = 0.f;                           // this lane's share of the running sum
+
+  const int32_t* lrow = list + (size_t)bt * kk;
+  const uint8_t* pbase = pool + (size_t)b * S * row_stride;
+
+  for (int tile = tile_begin; tile < tile_end; ++tile) {
+    __syncthreads();                           // everyone is done with the previous tile
+    if (tid < TILE) {
+      const int e = tile * TILE + tid;
+      int sl = e < n ? lrow[e] : -1;
+      if (sl >= S) sl = -1;
+      tile_slot[tid] = sl;
+    }
+    __syncthreads();
+    // ---- stage: latent part, 4 rows x 8 dims per unit, row-major copy + transposed copy
+    for (int u = tid; u < 512; u += NTH) {
+      const int rg = u >> 6, cc = u & 63;      // row group (4 rows), 16-byte column piece
+      uint4 x[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int sl = tile_slot[rg * 4 + r];
+        x[r] = sl >= 0 ? load_piece<FMT>(pbase + (size_t)sl * row_stride, cc) : make_uint4(0, 0, 0, 0);
+        *reinterpret_cast<uint4*>(Kt + (rg * 4 + r) * KPITCH + cc * 16) = x[r];
+      }
+      // rows 4g'..4g'+3 sit at positions 8g'..8g'+3, rows 16+4g'.. at 8g'+4..8g'+7
+      const int gq = rg & 3, half = rg >> 2;
+      const uint32_t* xr0 = reinterpret_cast<const uint32_t*>(&x[0]);
+      const uint32_t* xr1 = reinterpret_cast<const uint32_t*>(&x[1]);
+      const uint32_t* xr2 = reinterpret_cast<const uint32_t*>(&x[2]);
+      const uint32_t* xr3 = reinterpret_cast<const uint32_t*>(&x[3]);
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        const uint32_t a0 = xr0[p], a1 = xr1[p], a2 = xr2[p], a3 = xr3[p];
+        const uint2 even = make_uint2((a0 & 0xffffu) | (a1 << 16), (a2 & 0xffffu) | (a3 << 16));
+        const uint2 odd = make_uint2((a0 >> 16) | (a1 & 0xffff0000u), (a2 >> 16) | (a3 & 0xffff0000u));
+        const int v0 = cc * 8 + 2 * p, v1 = v0 + 1;
+        *reinterpret_cast<uint2*>(Vt + v0 * 64 + vt_granule(v0, gq) * 16 + half * 8) = even;
+        *reinterpret_cast<uint2*>(Vt + v1 * 64 + vt_granule(v1, gq) * 16 + half * 8) = odd;
+      }
+    }
+    // ---- stage: rope part (key only)
+    for (int u = tid; u < 256; u += NTH) {
+      const int r = u >> 3, cc = 64 + (u & 7);
+      const int sl = tile_slot[r];
+      const uint4 x = sl >= 0 ? load_piece<FMT>(pbase + (size_t)sl * row_stride, cc) : make_uint4(0, 0, 0, 0);
+      *reinterpret_cast<uint4*>(Kt + r * KPITCH + cc * 16) = x;
+    }
+    __syncthreads();
+
+    // ---- S^T = K Q^T for the 32 rows of the tile
+    floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+      const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(Kt + n16 * KPITCH + ks * 64 + g * 16);
+      const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(Kt + (16 + n16) * KPITCH + ks * 64 + g * 16);
+      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, qb[ks], s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, qb[ks], s1, 0, 0, 0);
+    }
+    // lane (g,h): s0[i] = logit of row 4g+i, s1[i] = logit of row 16+4g+i
+    const int4 v0 = *reinterpret_cast<const int4*>(tile_slot + g * 4);
+    const int4 v1 = *reinterpret_cast<const int4*>(tile_slot + 16 + g * 4);
+    float z[8];
+    z[0] = v0.x >= 0 ? s0[0] * scale_log2e : -__builtin_inff();
+    z[1] = v0.y >= 0 ? s0[1] * scale_log2e : -__builtin_inff();
+    z[2] = v0.z >= 0 ? s0[2] * scale_log2e : -__builtin_inff();
+    z[3] = v0.w >= 0 ? s0[3] * scale_log2e : -__builtin_inff();
+    z[4] = v1.x >= 0 ? s1[0] * scale_log2e : -__builtin_inff();
+    z[5] = v1.y >= 0 ? s1[1] * scale_log2e : -__builtin_inff();
+    z[6] = v1.z >= 0 ? s1[2] * scale_log2e : -__builtin_inff();
+    z[7] = v1.w >= 0 ? s1[3] * scale_log2e : -__builtin_inff();
+    float tmax = fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])), fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7])));
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+    const float m_new = fmaxf(m_run, tmax);
+    const float m_safe = (m_new == -__builtin_inff()) ? 0.f : m_new;
+    const float alpha = exp2f(m_run - m_safe);              // 0 while nothing has been seen
+    float p[8], psum = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      p[j] = exp2f(z[j] - m_safe);
+      psum += p[j];
+    }
+    l_run = l_run * alpha + psum;
+    m_run = m_new;
+    if (__any(alpha != 1.0f)) {
+#pragma unroll
+      for (int vb = 0; vb < VBLOCKS; ++vb) {
+        acc[vb][0] *= alpha; acc[vb][1] *= alpha; acc[vb][2] *= alpha; acc[vb][3] *= alpha;
+      }
+    }
+    uint4 pw = make_uint4(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7]));
+    const bf16x8 pb = *reinterpret_cast<bf16x8*>(&pw);
+    // ---- O^T += V^T P^T
+#pragma unroll
+    for (int vb = 0; vb < VBLOCKS; ++vb) {
+      const int v = vb * 16 + n16;
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(Vt + v * 64 + vt_granule(v, g) * 16);
+      acc[vb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb, acc[vb], 0, 0, 0);
+    }
+  }
+
+  // ---- finish: total sum over the four lane groups, normalise, write the partial result
+  float l_tot = l_run;
+  l_tot += __shfl_xor(l_tot, 16, 64);
+  l_tot += __shfl_xor(l_tot, 32, 64);
+  const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+  if (head < H) {
+    const size_t prow = ((size_t)bt * ESS_MAX_SPLITS + split0 + split) * H + head;
+    float* op = o_part + prow * ESS_LATENT_DIM;
+#pragma unroll
+    for (int vb = 0; vb < VBLOCKS; ++vb) {
+      const float4 o = make_float4(acc[vb][0] * inv, acc[vb][1] * inv, acc[vb][2] * inv, acc[vb][3] * inv);
+      *reinterpret_cast<float4*>(op + vb * 16 + g * 4) = o;
+    }
+    if (g == 0) lse_part[prow] = l_tot > 0.f ? (m_run + log2f(l_tot)) * kLn2 : -__builtin_inff();
+  }
+}
+
+// out[bt,h,:] = sum_s exp(lse_s - lse) * o_s ;  lse = log sum_s exp(lse_s).  One wave per (bt,h).
+__global__ __launch_bounds__(256) void k_attn_merge(const float* __restrict__ o_part, const float* __restrict__ lse_part,
+                                                    int H, int nsplit, int total_rows, uint16_t* __restrict__ out,
+                                                    float* __restrict__ lse_out) {
+  const int rowi = blockIdx.x * 4 + (threadIdx.x >> 6);      // bt*H + h
+  if (rowi >= total_rows) return;
+  const int lane = threadIdx.x & 63;
+  const int bt = rowi / H, h = rowi % H;
+  const size_t base = ((size_t)bt * ESS_MAX_SPLITS) * H + h;
+  float mx = -__builtin_inff();
+  for (int s = 0; s < nsplit; ++s) mx = fmaxf(mx, lse_part[base + (size_t)s * H]);
+  float den = 0.f;
+  float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (mx > -__builtin_inff()) {
+    for (int s = 0; s < nsplit; ++s) {
+      const float ls = lse_part[base + (size_t)s * H];
+      if (ls == -__builtin_inff()) continue;
+      const float wgt = __expf(ls - mx);
+      den += wgt;
+      const float4* op = reinterpret_cast<const float4*>(o_part + (base + (size_t)s * H) * ESS_LATENT_DIM + lane * 8);
+      const float4 x = op[0], y = op[1];
+      a[0] += wgt * x.x; a[1] += wgt * x.y; a[2] += wgt * x.z; a[3] += wgt * x.w;
+      a[4] += wgt * y.x; a[5] += wgt * y.y; a[6] += wgt * y.z; a[7] += wgt * y.w;
+    }
+  }
+  const float inv = den > 0.f ? 1.0f / den : 0.f;
+  uint4 o = make_uint4(pack_bf16(a[0] * inv, a[1] * inv), pack_bf16(a[2] * inv, a[3] * inv),
+                       pack_bf16(a[4] * inv, a[5] * inv), pack_bf16(a[6] * inv, a[7] * inv));
+  *reinterpret_cast<uint4*>(out + (size_t)rowi * ESS_LATENT_DIM + lane * 8) = o;
+  if (lse_out && lane == 0) lse_out[rowi] = den > 0.f ? mx + __logf(den) : -__builtin_inff();
+}
+
+template <int NW>
+int launch_fmt(int fmt, dim3 grid, size_t lds, hipStream_t st, const uint16_t* q, const uint8_t* pool,
+               const int32_t* list, const int32_t* n_list, int T, int H, int kk, int S, int row_stride, float sc,
+               int split0, int nsplit, float* o_part, float* lse_part) {
+  if (fmt == ESS_FMT_BF16) {
+    ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_partial<NW, ESS_FMT_BF16>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL((k_attn_partial<NW, ESS_FMT_BF16>), grid, dim3(NW * 64), lds, st, q, pool, list, n_list, T, H,
+                       kk, S, row_stride, sc, split0, nsplit, o_part, lse_part);
+  } else {
+    ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_partial<NW, ESS_FMT_FP8>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL((k_attn_partial<NW, ESS_FMT_FP8>), grid, dim3(NW * 64), lds, st, q, pool, list, n_list, T, H,
+                       kk, S, row_stride, sc, split0, nsplit, o_part, lse_part);
+  }
+  return ESS_OK;
+}
+
+}  // namespace
+
+int ess_launch_attn_partial(ess_ctx* ctx, const void* q, const uint8_t* slot_pool, const int32_t* list,
+                            const int32_t* n_list, int B, int T, int split0, int nsplit, hipStream_t st) {
+  const ess_config& c = ctx->cfg;
+  const int H = c.attn_heads;
+  const int hb = (H + 15) / 16;                // 16-head blocks
+  int NW = hb >= 4 ? 4 : (hb >= 2 ? 2 : 1);    // waves per workgroup
+  const int hgroups = (hb + NW - 1) / NW;
+  dim3 grid(nsplit, B * T, hgroups);
+  const size_t lds = KT_BYTES + VT_BYTES + TILE * sizeof(int32_t);
+  const float sc = c.sm_scale * kLog2e;
+  const uint16_t* qq = static_cast<const uint16_t*>(q);
+  int rc;
+  switch (NW) {
+    case 1: rc = launch_fmt<1>(c.latent_fmt, grid, lds, st, qq, slot_pool, list, n_list, T, H, c.topk, c.slots_per_seq, c.row_stride, sc, split0, nsplit, ctx->o_part, ctx->lse_part); break;
+    case 2: rc = launch_fmt<2>(c.latent_fmt, grid, lds, st, qq, slot_pool, list, n_list, T, H, c.topk, c.slots_per_seq, c.row_stride, sc, split0, nsplit, ctx->o_part, ctx->lse_part); break;
+    default: rc = launch_fmt<4>(c.latent_fmt, grid, lds, st, qq, slot_pool, list, n_list, T, H, c.topk, c.slots_per_seq, c.row_stride, sc, split0, nsplit, ctx->o_part, ctx->lse_part); break;
+  }
+  if (rc != ESS_OK) return rc;
+  ESS_HIP(hipGetLastError());
+  return ESS_OK;
+}
+
+int ess_launch_attn_merge(ess_ctx* ctx, int B, int T, int nsplit_total, void* out_bf16, float* lse, hipStream_t st) {
+  const int rows = B * T * ctx->cfg.attn_heads;
+  hipLaunchKernelGGL(k_attn_merge, dim3((rows + 3) / 4), dim3(256), 0, st, ctx->o_part, ctx->lse_part,
+                     ctx->cfg.attn_heads, nsplit_total, rows, static_cast<uint16_t*>(out_bf16), lse);
+  ESS_HIP(hipGetLastError());
+  return ESS_OK;
+}

@@ -1,0 +1,68 @@
+"""CPU-side checks of the C ABI: the library loads, exports every symbol the
+header declares, struct layouts match, and configuration errors are reported
+without touching a GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import torch  # noqa: F401  (HIP runtime first)
+    from paper_2512_10576_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2512_10576_amd import build
+        build.build()
+    return binding.load()
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "ess.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ess_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared()
+    assert {"ess_index_score", "ess_topk", "ess_gather_latent", "ess_sparse_mla_decode", "ess_decode_step"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_struct_layouts():
+    from paper_2512_10576_amd import binding as b
+    assert C.sizeof(b.EssConfig) == 13 * 4
+    assert C.sizeof(b.EssCache) == 5 * 8
+    assert C.sizeof(b.EssStats) == 4 * 8
+    assert b.EssStepArgs.B.offset == 48 and b.EssStepArgs.idx_out.offset == 64 and C.sizeof(b.EssStepArgs) == 96
+
+
+def test_config_validation_reports_errors(lib):
+    from paper_2512_10576_amd import binding as b
+    good = b.make_config(64, 1, 131072, 64, 128, 2048, 128, slots_per_seq=13108)
+    n = b.workspace_bytes(good)
+    assert n > 64 * 131072 * 4
+    cases = [
+        (dict(idx_dim=96), b.ESS_ERR_UNSUPPORTED),
+        (dict(max_q_tokens=3), b.ESS_ERR_UNSUPPORTED),
+        (dict(slots_per_seq=1000), b.ESS_ERR_CAPACITY),
+        (dict(row_stride=1150), b.ESS_ERR_INVALID_ARG),
+        (dict(max_ctx=1 << 20), b.ESS_ERR_INVALID_ARG),
+        (dict(topk=0), b.ESS_ERR_INVALID_ARG),
+        (dict(attn_heads=129), b.ESS_ERR_UNSUPPORTED),
+    ]
+    for change, code in cases:
+        kw = dict(max_batch=64, max_q_tokens=1, max_ctx=131072, idx_heads=64, idx_dim=128, topk=2048,
+                  attn_heads=128, slots_per_seq=13108)
+        kw.update(change)
+        with pytest.raises(b.EssError) as ei:
+            b.workspace_bytes(b.make_config(**kw))
+        assert ei.value.code == code and str(ei.value)
+    bad = b.make_config(1, 1, 64, 4, 32, 8, 8)
+    bad.struct_size = 8
+    with pytest.raises(b.EssError):
+        b.workspace_bytes(bad)
