@@ -1,0 +1,232 @@
+#!/usr/bin/env python3
+"""Benchmark of the ESS decode-step hot path on one MI355X.
+
+One "step" = one layer-step: index score -> top-k -> Sparse Memory Pool
+look-up / LRU update -> miss fetch from pinned host memory -> sparse MLA decode
+(Attn0 / Attn1 / merge), for the whole batch of one layer, through
+`ess_decode_step`.  Inputs are synthetic (seeded), resident in HBM / pinned
+host memory before the timed region starts.
+
+Prints ONE JSON line (see the keys below).  `roofline` is for the dominant
+kernel, the index-score key stream; its duration is measured with HIP events
+recorded by the library on the launch stream during the timed steps.
+`cpu_baseline` times the CPU oracle on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+HOST_LINK_PEAK_GBS = 64.0    # PCIe Gen5 x16, one direction
+
+# indexer 64 heads x 128 fp8, top-2048, 128 attention heads x 576 bf16 (all workloads)
+COMMON = dict(Hi=64, Di=128, k=2048, H=128, qk_max=8, w_levels=8, w_den=16)
+WORKLOADS = {
+    # name: batch, query tokens, context, per-sequence lengths, slot ratio (None = resident), step-to-step overlap
+    "cfg2": dict(cfg=2, B=32, T=1, L=32768, lens=None, ratio=None, rho=None,
+                 desc="B32 ctx32768 T1, Latent-Cache resident in HBM"),
+    "cfg3": dict(cfg=3, B=64, T=1, L=32768, lens=None, ratio=0.25, rho=0.8,
+                 desc="B64 ctx32768 T1, Latent-Cache in pinned host memory, 25% GPU slots, 80% top-k overlap"),
+    "cfg4": dict(cfg=4, B=64, T=1, L=131072, lens=(98304, 131072), ratio=0.10, rho=0.7,
+                 desc="B64 ctx in [98304,131072] T1, Latent-Cache in pinned host memory, 10% GPU slots, 70% top-k overlap"),
+}
+# HBM bytes per launch of the index-score kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (see profiles/); None until measured for that workload
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def build_workload(name, steps_needed):
+    import torch
+    from paper_2512_10576_amd import binding as bnd, synth
+    wl = dict(WORKLOADS[name]); wl.update(COMMON)
+    B, T, L, k, H = wl["B"], wl["T"], wl["L"], wl["k"], wl["H"]
+    seed = 1000 * wl["cfg"]
+    dev = "cuda"
+    q_idx, w, key = synth.indexer_inputs(seed, B, T, wl["Hi"], wl["Di"], L, wl["qk_max"], wl["w_levels"], wl["w_den"], device=dev)
+    q_attn = synth.attn_query(seed, B, T, H, device=dev)
+    if wl["lens"] is None:
+        ctx_len = torch.full((B,), L, dtype=torch.int32, device=dev)
+    else:
+        ctx_len = synth.ctx_lengths(seed, B, wl["lens"][0], wl["lens"][1], device=dev)
+    S = L if wl["ratio"] is None else int(math.ceil(wl["ratio"] * L - 1e-9))
+    cfg = bnd.make_config(B, T, L, wl["Hi"], wl["Di"], k, H, slots_per_seq=S)
+    ctx = bnd.Context(cfg)
+    host_pool = None
+    if wl["ratio"] is None:
+        pool = torch.empty((B, L, 1152), dtype=torch.uint8, device=dev)
+        for b in range(B):
+            synth.latent_rows_bf16(seed + b, L, device=dev, out=pool[b])
+        cache = bnd.Cache.allocate(cfg, B, slot_pool=pool)
+    else:
+        host_pool = torch.empty((B, L, 1152), dtype=torch.uint8, pin_memory=True)
+        for b in range(B):
+            host_pool[b].copy_(synth.latent_rows_bf16(seed + b, L, device=dev))
+        torch.cuda.synchronize()
+        cache = bnd.Cache.allocate(cfg, B, host_pool=host_pool)
+    ctx.cache_reset(cache, B)
+    trace = None
+    if wl["rho"] is not None:
+        tr = synth.TopkTrace(seed, ctx_len, T, k, wl["rho"], device=dev)
+        trace = [tr.next() for _ in range(steps_needed)]
+    torch.cuda.synchronize()
+    return dict(wl=wl, name=name, ctx=ctx, cfg=cfg, cache=cache, q_idx=q_idx, w=w, key=key, q_attn=q_attn,
+                ctx_len=ctx_len, host_pool=host_pool, trace=trace, S=S,
+                idx_out=torch.empty((B, T, k), dtype=torch.int32, device=dev),
+                out=torch.empty((B, T, H, 512), dtype=torch.bfloat16, device=dev),
+                lse=torch.empty((B, T, H), dtype=torch.float32, device=dev),
+                miss=torch.empty((B,), dtype=torch.int32, device=dev))
+
+
+def run_steps(W, first_step, n):
+    ctx = W["ctx"]
+    for i in range(n):
+        s = first_step + i
+        ov = W["trace"][s - 1] if W["trace"] is not None else None
+        ctx.decode_step(W["cache"], W["q_idx"], W["w"], W["key"], W["ctx_len"], W["q_attn"], s, W["idx_out"],
+                        W["out"], W["lse"], W["miss"], ov)
+
+
+def algorithmic_bytes(W, misses_per_step):
+    """Bytes the method must move per layer-step, by stage."""
+    wl = W["wl"]
+    lens = W["ctx_len"].cpu().numpy().astype("int64")
+    B, T, k, H = wl["B"], wl["T"], wl["k"], wl["H"]
+    a1 = int(lens.sum()) * (wl["Di"] + 4 * T) + B * T * wl["Hi"] * (wl["Di"] + 4)
+    a2 = int(lens.sum()) * 4 * T + B * T * k * 4
+    a4 = B * T * k * 1152 + B * T * H * (576 * 2 + 512 * 2 + 4)
+    fill = int(misses_per_step * 1152)
+    return dict(index_score=a1, topk=a2, attention_rows=a4, fill=fill)
+
+
+def measure(name, steps, warmup):
+    import torch
+    W = build_workload(name, warmup + steps)
+    ctx = W["ctx"]
+    run_steps(W, 1, warmup)
+    torch.cuda.synchronize()
+    ctx.reset_stats()
+    ctx.profile_enable(steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_steps(W, warmup + 1, steps)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = ctx.profile_read()
+    ctx.profile_enable(0)
+    stats = ctx.get_stats()
+    stage = [sum(p[i] for p in prof) / len(prof) for i in range(6)]
+    misses_per_step = stats["misses"] / max(steps, 1)
+    ab = algorithmic_bytes(W, misses_per_step)
+    ms_step = dt / steps * 1e3
+    hbm_stream_bytes = ab["index_score"] + ab["topk"] + ab["attention_rows"]
+    hbm_stream_ms = stage[0] + stage[1] + stage[3] + stage[4]
+    res = dict(
+        layer_steps_per_s=steps / dt, ms_per_step=ms_step,
+        stage_ms=dict(index_score=stage[0], topk=stage[1], bookkeeping=stage[2], attn0=stage[3], attn1_merge=stage[4],
+                      fetch=stage[5]),
+        index_score_GBs=ab["index_score"] / (stage[0] * 1e-3) / 1e9,
+        hbm_stream_GBs=hbm_stream_bytes / (hbm_stream_ms * 1e-3) / 1e9,
+        hbm_stream_frac_of_peak=hbm_stream_bytes / (hbm_stream_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        whole_step_hbm_frac=(hbm_stream_bytes / (ms_step * 1e-3) / 1e9) / HBM_PEAK_GBS,
+        misses_per_step=misses_per_step,
+        host_link_GBs=(ab["fill"] / (stage[5] * 1e-3) / 1e9) if stage[5] > 0 else None,
+        host_link_frac_of_peak=(ab["fill"] / (stage[5] * 1e-3) / 1e9 / HOST_LINK_PEAK_GBS) if stage[5] > 0 else None,
+        algorithmic_bytes=ab,
+    )
+    return W, res
+
+
+def cpu_baseline(W, budget_seqs):
+    """The CPU oracle, as it stands, on the first `budget_seqs` sequences of the workload (one step)."""
+    import numpy as np
+    from oracle import ess_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count()
+    wl = W["wl"]
+    n = min(budget_seqs, wl["B"])
+    q_idx = W["q_idx"][:n].cpu().numpy(); w = W["w"][:n].cpu().numpy(); key = W["key"][:n].cpu().numpy()
+    ctx_len = W["ctx_len"][:n].cpu().numpy()
+    q_bits = W["q_attn"][:n].view(__import__("torch").int16).cpu().numpy().view(np.uint16)
+    L, S = wl["L"], W["S"]
+    if W["host_pool"] is not None:
+        host = W["host_pool"][:n].numpy()
+        cache = O.SlotCache(n, L, S)
+        pool = np.zeros((n, S, 1152), np.uint8)
+        ov = W["trace"][0][:n].cpu().numpy()
+    else:
+        host = None
+        cache = O.SlotCache(n, L, L); cache.make_resident_identity()
+        pool = W["cache"].slot_pool[:n].cpu().numpy()
+        ov = None
+    t0 = time.perf_counter()
+    O.decode_step(q_idx, w, key, ctx_len, wl["k"], cache, pool, host, q_bits, O.FMT_BF16, 576 ** -0.5, 1, ov)
+    dt = time.perf_counter() - t0
+    return dict(value=1.0 / (dt * wl["B"] / n), unit="layer-steps/s", cores=int(threads), kind="oracle",
+                sample="%d of %d sequences of %s, one layer-step (cold cache), scaled linearly to the batch; %.1f s of CPU time"
+                       % (n, wl["B"], W["name"], dt))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=32)
+    ap.add_argument("--workload", default="cfg4", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-32k", action="store_true", help="skip the extra 32K-context measurement (cfg2)")
+    ap.add_argument("--cpu-seqs", type=int, default=16)
+    a = ap.parse_args()
+    if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (the path shards by sequence with no collective); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2512_10576_amd import binding
+    binding.load()                                   # fails loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+
+    W, res = measure(a.workload, a.steps, a.warmup)
+    ab = res["algorithmic_bytes"]
+    roof = dict(bound="hbm", kernel="k_index_score", achieved=res["index_score_GBs"], peak=HBM_PEAK_GBS, unit="GB/s",
+                frac=res["index_score_GBs"] / HBM_PEAK_GBS, traffic=MEASURED_TRAFFIC_BYTES.get(a.workload),
+                algorithmic_bytes_per_launch=ab["index_score"], avg_launch_ms=res["stage_ms"]["index_score"])
+    out = {
+        "metric": "decode-step sparse-attn layer-steps/sec", "value": res["layer_steps_per_s"], "unit": "layer-steps/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": res["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "fp8 indexer / bf16 attention",
+        "data": "synthetic",
+        "config": {"workload": "%s: %s" % (a.workload, W["wl"]["desc"]), "indexer": "64 heads x 128 fp8 e4m3",
+                   "topk": 2048, "attention": "128 heads x 576 bf16 absorbed MLA", "slots_per_seq": W["S"]},
+        "roofline": roof,
+        "stages": {k: res[k] for k in ("stage_ms", "hbm_stream_GBs", "hbm_stream_frac_of_peak", "whole_step_hbm_frac",
+                                       "misses_per_step", "host_link_GBs", "host_link_frac_of_peak")},
+        "paper_context": "simulated whole-model gains of the paper: +69.4% at 32K, +123% at 128K (not comparable)",
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(W, a.cpu_seqs)
+    W["ctx"].close()
+    del W
+    torch.cuda.empty_cache()
+    if not a.no_32k and a.workload != "cfg2":
+        W2, r2 = measure("cfg2", a.steps, min(a.warmup, 8))
+        out["ctx32k"] = {"workload": "cfg2: " + W2["wl"]["desc"], "layer_steps_per_s": r2["layer_steps_per_s"],
+                         "ms_per_step": r2["ms_per_step"], "stage_ms": r2["stage_ms"],
+                         "index_score_GBs": r2["index_score_GBs"], "hbm_stream_frac_of_peak": r2["hbm_stream_frac_of_peak"]}
+        W2["ctx"].close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

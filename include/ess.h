@@ -66,10 +66,10 @@ typedef struct {
   uint32_t struct_size;   /* sizeof(ess_config), checked */
   int32_t max_batch;      /* largest B any call will pass */
   int32_t max_q_tokens;   /* largest T (1 or 2) */
-  int32_t max_ctx;        /* Lmax: row pitch of key, score and slot_of; <= 1048576 */
+  int32_t max_ctx;        /* Lmax: row pitch of key, score and slot_of; <= 524288 */
   int32_t idx_heads;      /* Hi, 1..64 */
   int32_t idx_dim;        /* Di, 32 | 64 | 128 */
-  int32_t topk;           /* k, 1..4096 */
+  int32_t topk;           /* k, 1..4096, with T*k <= 4096 */
   int32_t attn_heads;     /* H, 1..128 */
   int32_t latent_fmt;     /* ESS_FMT_BF16 | ESS_FMT_FP8 */
   int32_t row_stride;     /* bytes between entries in slot pool and host pool (>= entry size, multiple of 16) */
@@ -179,6 +179,16 @@ typedef struct {
 } ess_stats;
 int ess_get_stats(ess_ctx* ctx, ess_stats* host_out, void* stream);
 int ess_reset_stats(ess_ctx* ctx, void* stream);
+
+/* Measurement support.  After ess_profile_enable(ctx, n) every ess_decode_step records HIP
+ * events on its stream between the stages (up to n steps; n = 0 disables and frees them).
+ * ess_profile_read WAITS for the recorded events and returns, per recorded step, the
+ * milliseconds of: [0] index score, [1] top-k, [2] cache bookkeeping, [3] Attn0,
+ * [4] Attn1 (including any wait for the fetch) + merge, [5] the miss fetch kernel on its own
+ * stream (0 when nothing is offloaded).  host_ms holds n*6 floats. */
+#define ESS_PROFILE_STAGES 6
+int ess_profile_enable(ess_ctx* ctx, int32_t max_steps);
+int ess_profile_read(ess_ctx* ctx, float* host_ms, int32_t* n_steps);
 
 #ifdef __cplusplus
 }

@@ -77,6 +77,8 @@ def load() -> C.CDLL:
         "ess_decode_step": [vp, C.POINTER(EssCache), C.POINTER(EssStepArgs), vp],
         "ess_get_stats": [vp, C.POINTER(EssStats), vp],
         "ess_reset_stats": [vp, vp],
+        "ess_profile_enable": [vp, i32],
+        "ess_profile_read": [vp, C.POINTER(C.c_float), C.POINTER(i32)],
     }
     for name, args in sigs.items():
         fn = getattr(lib, name)
@@ -213,6 +215,17 @@ class Context:
         s = EssStats()
         _check(self.lib.ess_get_stats(self.h, C.byref(s), _stream()))
         return dict(steps=s.steps, selected=s.selected, misses=s.misses, bytes_filled=s.bytes_filled)
+
+    def profile_enable(self, max_steps):
+        self._prof_cap = max_steps
+        _check(self.lib.ess_profile_enable(self.h, max_steps))
+
+    def profile_read(self):
+        """list of per-step [index_score, topk, bookkeeping, attn0, attn1+merge, fetch] milliseconds"""
+        buf = (C.c_float * (self._prof_cap * 6))()
+        n = C.c_int32(0)
+        _check(self.lib.ess_profile_read(self.h, buf, C.byref(n)))
+        return [[buf[s * 6 + i] for i in range(6)] for s in range(n.value)]
 
     def reset_stats(self):
         _check(self.lib.ess_reset_stats(self.h, _stream()))

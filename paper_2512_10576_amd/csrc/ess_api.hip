@@ -113,16 +113,24 @@ int pick_splits(const ess_config& c, int B, int T, int cap) {
 // enqueued on `st` is ordered after the bookkeeping; *fill_pending tells whether ev_fill must
 // still be waited for before the fetched rows are read.
 int run_cache_step(ess_ctx* ctx, const ess_cache& cache, const int32_t* idx, int B, int T, int kk, uint32_t step,
-                   int32_t* slot_idx, int32_t* miss_count, hipStream_t st, bool* fill_pending) {
+                   int32_t* slot_idx, int32_t* miss_count, hipStream_t st, bool* fill_pending,
+                   hipEvent_t* fill_ev = nullptr) {
   *fill_pending = false;
   int rc = ess_launch_bookkeeping(ctx, cache, idx, B, T, kk, step, slot_idx, miss_count, st);
   if (rc != ESS_OK) return rc;
   if (!cache.host_pool_dev) return ESS_OK;      // nothing offloaded: no entry can be missing
-  if (ctx->cfg.flags & ESS_FLAG_SERIAL) return ess_launch_fill(ctx, cache, B, T * kk, st);
+  if (ctx->cfg.flags & ESS_FLAG_SERIAL) {
+    if (fill_ev) ESS_HIP(hipEventRecord(fill_ev[0], st));
+    rc = ess_launch_fill(ctx, cache, B, T * kk, st);
+    if (rc == ESS_OK && fill_ev) ESS_HIP(hipEventRecord(fill_ev[1], st));
+    return rc;
+  }
   ESS_HIP(hipEventRecord(ctx->ev_book, st));
   ESS_HIP(hipStreamWaitEvent(ctx->side, ctx->ev_book, 0));
+  if (fill_ev) ESS_HIP(hipEventRecord(fill_ev[0], ctx->side));
   rc = ess_launch_fill(ctx, cache, B, T * kk, ctx->side);
   if (rc != ESS_OK) return rc;
+  if (fill_ev) ESS_HIP(hipEventRecord(fill_ev[1], ctx->side));
   ESS_HIP(hipEventRecord(ctx->ev_fill, ctx->side));
   *fill_pending = true;
   return ESS_OK;
@@ -201,6 +209,7 @@ int ess_create(const ess_config* cfg, ess_ctx** out) {
 int ess_destroy(ess_ctx* ctx) {
   if (!ctx) return ESS_OK;
   (void)hipStreamSynchronize(ctx->side);
+  (void)ess_profile_enable(ctx, 0);
   (void)hipEventDestroy(ctx->ev_book);
   (void)hipEventDestroy(ctx->ev_fill);
   (void)hipStreamDestroy(ctx->side);
@@ -300,26 +309,39 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
   const ess_config& c = ctx->cfg;
   const int B = a->B, T = a->T;
 
+  hipEvent_t* pev = nullptr;                    // stage marks of this step, when profiling
+  if (ctx->prof_ev && ctx->prof_n < ctx->prof_cap) pev = ctx->prof_ev + (size_t)(ctx->prof_n++) * ESS_PROF_EVENTS;
+#define ESS_MARK(i) do { if (pev) ESS_HIP(hipEventRecord(pev[i], st)); } while (0)
+  ESS_MARK(0);
   // stages 1-2
   rc = ess_launch_index_score(c, a->q_idx_fp8, a->w, a->key_fp8, a->ctx_len, B, T, ctx->score_ws, st);
   if (rc != ESS_OK) return rc;
+  ESS_MARK(1);
   rc = ess_launch_topk(c, ctx->score_ws, a->ctx_len, B, T, a->idx_out, st);
   if (rc != ESS_OK) return rc;
+  ESS_MARK(2);
   const int32_t* used = a->topk_override ? a->topk_override : a->idx_out;
 
   if (!cache->host_pool_dev) {
     // nothing offloaded: slot == position, attention straight over the selection
     const int ns = pick_splits(c, B, T, 16);
+    ESS_MARK(3);
     rc = ess_launch_attn_partial(ctx, a->q_bf16, cache->slot_pool, used, nullptr, B, T, 0, ns, st);
     if (rc != ESS_OK) return rc;
+    ESS_MARK(4);
     if (a->miss_count && (rc = ess_launch_fill_u32(reinterpret_cast<uint32_t*>(a->miss_count), B, 0u, st)) != ESS_OK) return rc;
-    return ess_launch_attn_merge(ctx, B, T, ns, a->out_bf16, a->lse, st);
+    rc = ess_launch_attn_merge(ctx, B, T, ns, a->out_bf16, a->lse, st);
+    if (rc != ESS_OK) return rc;
+    ESS_MARK(5);
+    return ESS_OK;
   }
 
   // stages 3 + 5, fetch on the side stream
   bool pending = false;
-  rc = run_cache_step(ctx, *cache, used, B, T, c.topk, a->step, ctx->slot_idx_ws, a->miss_count, st, &pending);
+  rc = run_cache_step(ctx, *cache, used, B, T, c.topk, a->step, ctx->slot_idx_ws, a->miss_count, st, &pending,
+                      pev ? pev + 6 : nullptr);
   if (rc != ESS_OK) return rc;
+  ESS_MARK(3);
   // stage 4: Attn0 over resident entries while the fetch runs, Attn1 over fetched ones, merge
   const int ns0 = pick_splits(c, B, T, 16);
   int ns1 = ns0 / 4;
@@ -327,10 +349,58 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
   if (ns1 > ESS_MAX_SPLITS - 16) ns1 = ESS_MAX_SPLITS - 16;
   rc = ess_launch_attn_partial(ctx, a->q_bf16, cache->slot_pool, ctx->hit_list, ctx->n_hit, B, T, 0, ns0, st);
   if (rc != ESS_OK) return rc;
+  ESS_MARK(4);
   if (pending) ESS_HIP(hipStreamWaitEvent(st, ctx->ev_fill, 0));
   rc = ess_launch_attn_partial(ctx, a->q_bf16, cache->slot_pool, ctx->miss_list, ctx->n_miss, B, T, ns0, ns1, st);
   if (rc != ESS_OK) return rc;
-  return ess_launch_attn_merge(ctx, B, T, ns0 + ns1, a->out_bf16, a->lse, st);
+  rc = ess_launch_attn_merge(ctx, B, T, ns0 + ns1, a->out_bf16, a->lse, st);
+  if (rc != ESS_OK) return rc;
+  ESS_MARK(5);
+  return ESS_OK;
+#undef ESS_MARK
+}
+
+int ess_profile_enable(ess_ctx* ctx, int32_t max_steps) {
+  if (!ctx) return ess_fail(ESS_ERR_INVALID_ARG, "context is NULL");
+  if (max_steps < 0 || max_steps > 65536) return ess_fail(ESS_ERR_INVALID_ARG, "max_steps %d", max_steps);
+  if (ctx->prof_ev) {
+    for (int i = 0; i < ctx->prof_cap * ESS_PROF_EVENTS; ++i) (void)hipEventDestroy(ctx->prof_ev[i]);
+    delete[] ctx->prof_ev;
+    ctx->prof_ev = nullptr;
+  }
+  ctx->prof_cap = ctx->prof_n = 0;
+  if (max_steps == 0) return ESS_OK;
+  const int n = max_steps * ESS_PROF_EVENTS;
+  ctx->prof_ev = new (std::nothrow) hipEvent_t[n];
+  if (!ctx->prof_ev) return ess_fail(ESS_ERR_NOMEM, "host allocation failed");
+  for (int i = 0; i < n; ++i) {
+    hipError_t e = hipEventCreate(&ctx->prof_ev[i]);
+    if (e != hipSuccess) {
+      for (int j = 0; j < i; ++j) (void)hipEventDestroy(ctx->prof_ev[j]);
+      delete[] ctx->prof_ev;
+      ctx->prof_ev = nullptr;
+      return ess_fail(ESS_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(e));
+    }
+  }
+  ctx->prof_cap = max_steps;
+  return ESS_OK;
+}
+
+int ess_profile_read(ess_ctx* ctx, float* host_ms, int32_t* n_steps) {
+  if (!ctx || !host_ms || !n_steps) return ess_fail(ESS_ERR_INVALID_ARG, "NULL argument");
+  *n_steps = ctx->prof_n;
+  for (int s = 0; s < ctx->prof_n; ++s) {
+    hipEvent_t* ev = ctx->prof_ev + (size_t)s * ESS_PROF_EVENTS;
+    ESS_HIP(hipEventSynchronize(ev[5]));
+    for (int i = 0; i < 5; ++i) ESS_HIP(hipEventElapsedTime(&host_ms[s * ESS_PROFILE_STAGES + i], ev[i], ev[i + 1]));
+    host_ms[s * ESS_PROFILE_STAGES + 5] = 0.f;
+    if (hipEventQuery(ev[7]) == hipSuccess && hipEventElapsedTime(&host_ms[s * ESS_PROFILE_STAGES + 5], ev[6], ev[7]) != hipSuccess) {
+      host_ms[s * ESS_PROFILE_STAGES + 5] = 0.f;
+      (void)hipGetLastError();
+    }
+  }
+  ctx->prof_n = 0;
+  return ESS_OK;
 }
 
 int ess_get_stats(ess_ctx* ctx, ess_stats* host_out, void* stream) {

@@ -10,6 +10,7 @@
 #define ESS_ATTN_TILE 32        // entries per attention tile
 #define ESS_MAX_SPLITS 20       // partial results per (b,t): Attn0 splits + Attn1 splits
 #define ESS_ROW_DIM 576
+#define ESS_PROF_EVENTS 8
 
 struct ess_ctx {
   ess_config cfg;
@@ -30,6 +31,9 @@ struct ess_ctx {
   float* lse_part;              // [B*T, ESS_MAX_SPLITS, H]
   unsigned long long* stats;    // [4]
   size_t ws_bytes;
+  // optional stage timing (ess_profile_enable)
+  hipEvent_t* prof_ev;          // [prof_cap][ESS_PROF_EVENTS]: 6 marks on the caller's stream, 2 around the fetch
+  int prof_cap, prof_n;
 };
 
 int ess_fail(int code, const char* fmt, ...);
