@@ -251,7 +251,10 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
   }
 }
 
-// Fetch: one wave per missed entry, rows copied host pool -> slot pool in 16-byte pieces.
+// Fetch: one wave per missed entry, rows copied host pool -> slot pool in 16-byte pieces.  Two
+// entries per wave are in flight at once.  The grid is kept small (about two waves per CU):
+// these waves spend their life waiting on the host link, and a large grid would occupy every
+// wave slot of the chip and starve the attention kernel that runs beside it.
 __global__ __launch_bounds__(256) void k_fill(const uint8_t* __restrict__ host_pool, uint8_t* __restrict__ slot_pool,
                                               const int32_t* __restrict__ fill_tok,
                                               const int32_t* __restrict__ fill_slot, int fill_cap,
@@ -260,13 +263,28 @@ __global__ __launch_bounds__(256) void k_fill(const uint8_t* __restrict__ host_p
   const int m = min(miss_cnt[b], fill_cap);
   const int lane = threadIdx.x & 63;
   const int nw = gridDim.x * 4;
-  const int chunks = row_stride >> 4;
-  for (int i = blockIdx.x * 4 + (threadIdx.x >> 6); i < m; i += nw) {
-    const int s = fill_tok[(size_t)b * fill_cap + i];
-    const int v = fill_slot[(size_t)b * fill_cap + i];
-    const uint4* src = reinterpret_cast<const uint4*>(host_pool + ((size_t)b * Lmax + s) * row_stride);
-    uint4* dst = reinterpret_cast<uint4*>(slot_pool + ((size_t)b * S + v) * row_stride);
-    for (int c = lane; c < chunks; c += 64) dst[c] = src[c];
+  const int chunks = row_stride >> 4;          // <= 128 for the supported entry sizes
+  const int32_t* ft = fill_tok + (size_t)b * fill_cap;
+  const int32_t* fs = fill_slot + (size_t)b * fill_cap;
+  const uint8_t* hp = host_pool + (size_t)b * Lmax * row_stride;
+  uint8_t* sp = slot_pool + (size_t)b * S * row_stride;
+  const int c0 = lane, c1 = lane + 64;
+  for (int i = blockIdx.x * 4 + (threadIdx.x >> 6); i < m; i += 2 * nw) {
+    const int j = i + nw;
+    const bool two = j < m;
+    const uint4* srcA = reinterpret_cast<const uint4*>(hp + (size_t)ft[i] * row_stride);
+    const uint4* srcB = reinterpret_cast<const uint4*>(hp + (size_t)ft[two ? j : i] * row_stride);
+    uint4* dstA = reinterpret_cast<uint4*>(sp + (size_t)fs[i] * row_stride);
+    uint4* dstB = reinterpret_cast<uint4*>(sp + (size_t)fs[two ? j : i] * row_stride);
+    uint4 a0 = make_uint4(0, 0, 0, 0), a1 = a0, b0 = a0, b1 = a0;
+    if (c0 < chunks) a0 = srcA[c0];
+    if (c1 < chunks) a1 = srcA[c1];
+    if (two && c0 < chunks) b0 = srcB[c0];
+    if (two && c1 < chunks) b1 = srcB[c1];
+    if (c0 < chunks) dstA[c0] = a0;
+    if (c1 < chunks) dstA[c1] = a1;
+    if (two && c0 < chunks) dstB[c0] = b0;
+    if (two && c1 < chunks) dstB[c1] = b1;
   }
 }
 
@@ -340,7 +358,9 @@ int ess_launch_bookkeeping(ess_ctx* ctx, const ess_cache& cache, const int32_t* 
 int ess_launch_fill(ess_ctx* ctx, const ess_cache& cache, int B, int per_seq_cap, hipStream_t st) {
   const ess_config& c = ctx->cfg;
   (void)per_seq_cap;
-  hipLaunchKernelGGL(k_fill, dim3(32, B), dim3(256), 0, st, cache.host_pool_dev, cache.slot_pool, ctx->fill_tok,
+  int gx = (512 + 4 * B - 1) / (4 * B);        // about 512 waves in total
+  if (gx > 32) gx = 32;
+  hipLaunchKernelGGL(k_fill, dim3(gx, B), dim3(256), 0, st, cache.host_pool_dev, cache.slot_pool, ctx->fill_tok,
                      ctx->fill_slot, c.max_q_tokens * c.topk, ctx->miss_cnt, c.max_ctx, c.slots_per_seq,
                      c.row_stride);
   ESS_HIP(hipGetLastError());

@@ -40,8 +40,8 @@ int validate_config(const ess_config* c) {
     return ess_fail(ESS_ERR_UNSUPPORTED, "attn_heads %d outside [1, 128]", c->attn_heads);
   if (c->latent_fmt != ESS_FMT_BF16 && c->latent_fmt != ESS_FMT_FP8)
     return ess_fail(ESS_ERR_UNSUPPORTED, "latent_fmt %d", c->latent_fmt);
-  if (c->row_stride < entry_bytes(c->latent_fmt) || (c->row_stride & 15))
-    return ess_fail(ESS_ERR_INVALID_ARG, "row_stride %d must be a multiple of 16 and >= %d", c->row_stride,
+  if (c->row_stride < entry_bytes(c->latent_fmt) || (c->row_stride & 15) || c->row_stride > 2048)
+    return ess_fail(ESS_ERR_INVALID_ARG, "row_stride %d must be a multiple of 16, >= %d and <= 2048", c->row_stride,
                     entry_bytes(c->latent_fmt));
   if (c->slots_per_seq < 1 || c->slots_per_seq > c->max_ctx)
     return ess_fail(ESS_ERR_INVALID_ARG, "slots_per_seq %d outside [1, max_ctx]", c->slots_per_seq);

@@ -78,14 +78,14 @@ __device__ __forceinline__ uint4 load_piece(const uint8_t* row, int cc) {
 
 // NW waves per workgroup, 16 heads each.
 template <int NW, int FMT>
-__global__ __launch_bounds__(NW * 64, 2) void k_attn_partial(
+__global__ __launch_bounds__(NW * 64, 1) void k_attn_partial(
     const uint16_t* __restrict__ q, const uint8_t* __restrict__ pool, const int32_t* __restrict__ list,
     const int32_t* __restrict__ n_list, int T, int H, int kk, int S, int row_stride, float scale_log2e, int split0,
     int nsplit, float* __restrict__ o_part, float* __restrict__ lse_part) {
   extern __shared__ __align__(16) uint8_t lds[];
   uint8_t* Kt = lds;
   uint8_t* Vt = lds + KT_BYTES;
-  int32_t* tile_slot = reinterpret_cast<int32_t*>(lds + KT_BYTES + VT_BYTES);   // [32]
+  int32_t* slot_cache = reinterpret_cast<int32_t*>(lds + KT_BYTES + VT_BYTES);  // [16 tiles][32]
 
   constexpr int NTH = NW * 64;
   const int split = blockIdx.x;
@@ -122,47 +122,75 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_partial(
   const int32_t* lrow = list + (size_t)bt * kk;
   const uint8_t* pbase = pool + (size_t)b * S * row_stride;
 
+  constexpr int SLOT_TILES = 16;               // tile slots are fetched 16 tiles (512 entries) at a time
+  constexpr int UPT = 512 / NTH;               // latent units (4 rows x 16 bytes) per thread and tile
+  constexpr int UCH = UPT > 2 ? 2 : UPT;       // units whose loads are in flight together
+  constexpr int RPT = 256 / NTH;               // rope pieces per thread and tile
+
   for (int tile = tile_begin; tile < tile_end; ++tile) {
+    const int trel = (tile - tile_begin) % SLOT_TILES;
     __syncthreads();                           // everyone is done with the previous tile
-    if (tid < TILE) {
-      const int e = tile * TILE + tid;
-      int sl = e < n ? lrow[e] : -1;
-      if (sl >= S) sl = -1;
-      tile_slot[tid] = sl;
-    }
-    __syncthreads();
-    // ---- stage: latent part, 4 rows x 8 dims per unit, row-major copy + transposed copy
-    for (int u = tid; u < 512; u += NTH) {
-      const int rg = u >> 6, cc = u & 63;      // row group (4 rows), 16-byte column piece
-      uint4 x[4];
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int sl = tile_slot[rg * 4 + r];
-        x[r] = sl >= 0 ? load_piece<FMT>(pbase + (size_t)sl * row_stride, cc) : make_uint4(0, 0, 0, 0);
-        *reinterpret_cast<uint4*>(Kt + (rg * 4 + r) * KPITCH + cc * 16) = x[r];
+    if (trel == 0) {
+      for (int j = tid; j < SLOT_TILES * TILE; j += NTH) {
+        const int e = tile * TILE + j;
+        int sl = e < n ? lrow[e] : -1;
+        if (sl >= S) sl = -1;
+        slot_cache[j] = sl;
       }
-      // rows 4g'..4g'+3 sit at positions 8g'..8g'+3, rows 16+4g'.. at 8g'+4..8g'+7
-      const int gq = rg & 3, half = rg >> 2;
-      const uint32_t* xr0 = reinterpret_cast<const uint32_t*>(&x[0]);
-      const uint32_t* xr1 = reinterpret_cast<const uint32_t*>(&x[1]);
-      const uint32_t* xr2 = reinterpret_cast<const uint32_t*>(&x[2]);
-      const uint32_t* xr3 = reinterpret_cast<const uint32_t*>(&x[3]);
+      __syncthreads();
+    }
+    const int32_t* tile_slot = slot_cache + trel * TILE;
+    // ---- stage.  All global loads of a chunk are issued before anything is written to LDS; rows
+    //      that are masked out load slot 0 (always valid memory) and are zeroed by a select.
+    uint4 xr[RPT];
 #pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        const uint32_t a0 = xr0[p], a1 = xr1[p], a2 = xr2[p], a3 = xr3[p];
-        const uint2 even = make_uint2((a0 & 0xffffu) | (a1 << 16), (a2 & 0xffffu) | (a3 << 16));
-        const uint2 odd = make_uint2((a0 >> 16) | (a1 & 0xffff0000u), (a2 >> 16) | (a3 & 0xffff0000u));
-        const int v0 = cc * 8 + 2 * p, v1 = v0 + 1;
-        *reinterpret_cast<uint2*>(Vt + v0 * 64 + vt_granule(v0, gq) * 16 + half * 8) = even;
-        *reinterpret_cast<uint2*>(Vt + v1 * 64 + vt_granule(v1, gq) * 16 + half * 8) = odd;
+    for (int i = 0; i < RPT; ++i) {            // rope part (key only)
+      const int u = tid + i * NTH;
+      const int sl = tile_slot[u >> 3];
+      xr[i] = load_piece<FMT>(pbase + (size_t)max(sl, 0) * row_stride, 64 + (u & 7));
+      if (sl < 0) xr[i] = make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int c0 = 0; c0 < UPT; c0 += UCH) {    // latent part: row-major copy + transposed copy
+      uint4 x[UCH][4];
+#pragma unroll
+      for (int i = 0; i < UCH; ++i) {
+        const int u = tid + (c0 + i) * NTH;
+        const int rg = u >> 6, cc = u & 63;    // row group (4 rows), 16-byte column piece
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int sl = tile_slot[rg * 4 + r];
+          x[i][r] = load_piece<FMT>(pbase + (size_t)max(sl, 0) * row_stride, cc);
+          if (sl < 0) x[i][r] = make_uint4(0, 0, 0, 0);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < UCH; ++i) {
+        const int u = tid + (c0 + i) * NTH;
+        const int rg = u >> 6, cc = u & 63;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) *reinterpret_cast<uint4*>(Kt + (rg * 4 + r) * KPITCH + cc * 16) = x[i][r];
+        // rows 4g'..4g'+3 sit at positions 8g'..8g'+3, rows 16+4g'.. at 8g'+4..8g'+7
+        const int gq = rg & 3, half = rg >> 2;
+        const uint32_t* xr0 = reinterpret_cast<const uint32_t*>(&x[i][0]);
+        const uint32_t* xr1 = reinterpret_cast<const uint32_t*>(&x[i][1]);
+        const uint32_t* xr2 = reinterpret_cast<const uint32_t*>(&x[i][2]);
+        const uint32_t* xr3 = reinterpret_cast<const uint32_t*>(&x[i][3]);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          const uint32_t a0 = xr0[p], a1 = xr1[p], a2 = xr2[p], a3 = xr3[p];
+          const uint2 even = make_uint2((a0 & 0xffffu) | (a1 << 16), (a2 & 0xffffu) | (a3 << 16));
+          const uint2 odd = make_uint2((a0 >> 16) | (a1 & 0xffff0000u), (a2 >> 16) | (a3 & 0xffff0000u));
+          const int v0 = cc * 8 + 2 * p, v1 = v0 + 1;
+          *reinterpret_cast<uint2*>(Vt + v0 * 64 + vt_granule(v0, gq) * 16 + half * 8) = even;
+          *reinterpret_cast<uint2*>(Vt + v1 * 64 + vt_granule(v1, gq) * 16 + half * 8) = odd;
+        }
       }
     }
-    // ---- stage: rope part (key only)
-    for (int u = tid; u < 256; u += NTH) {
-      const int r = u >> 3, cc = 64 + (u & 7);
-      const int sl = tile_slot[r];
-      const uint4 x = sl >= 0 ? load_piece<FMT>(pbase + (size_t)sl * row_stride, cc) : make_uint4(0, 0, 0, 0);
-      *reinterpret_cast<uint4*>(Kt + r * KPITCH + cc * 16) = x;
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) {
+      const int u = tid + i * NTH;
+      *reinterpret_cast<uint4*>(Kt + (u >> 3) * KPITCH + (64 + (u & 7)) * 16) = xr[i];
     }
     __syncthreads();
 
@@ -295,7 +323,7 @@ int ess_launch_attn_partial(ess_ctx* ctx, const void* q, const uint8_t* slot_poo
   int NW = hb >= 4 ? 4 : (hb >= 2 ? 2 : 1);    // waves per workgroup
   const int hgroups = (hb + NW - 1) / NW;
   dim3 grid(nsplit, B * T, hgroups);
-  const size_t lds = KT_BYTES + VT_BYTES + TILE * sizeof(int32_t);
+  const size_t lds = KT_BYTES + VT_BYTES + 16 * TILE * sizeof(int32_t);
   const float sc = c.sm_scale * kLog2e;
   const uint16_t* qq = static_cast<const uint16_t*>(q);
   int rc;
