@@ -173,7 +173,7 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
  * side stream. */
 typedef struct {
   uint64_t steps;        /* bookkeeping steps */
-  uint64_t selected;     /* distinct entries requested */
+  uint64_t selected;     /* valid entries requested (an entry selected by both query tokens counts twice) */
   uint64_t misses;       /* entries fetched from the host pool */
   uint64_t bytes_filled; /* misses * row_stride */
 } ess_stats;

@@ -81,6 +81,9 @@ __device__ void bitonic_sort_u64(unsigned long long* a, int n) {
 }
 
 // idx: [B, T, kk] selected positions (-1 = none).  Dynamic LDS: bitmap of Lmax bits.
+// REG: the slots a thread owns (S / 1024, rounded up, at most 16) are held in registers, so the
+// stamps are read from memory once, all loads of a thread in flight together.
+template <bool REG>
 __global__ __launch_bounds__(BT) void k_bookkeeping(
     const int32_t* __restrict__ idx, int T, int kk, int Lmax, int S, int32_t* __restrict__ slot_of,
     int32_t* __restrict__ token_of, uint32_t* __restrict__ stamp, uint32_t step, int32_t* __restrict__ slot_idx_out,
@@ -88,8 +91,9 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
     int32_t* __restrict__ n_miss, int32_t* __restrict__ fill_tok, int32_t* __restrict__ fill_slot, int fill_cap,
     int32_t* __restrict__ miss_cnt, int32_t* __restrict__ miss_count_out, unsigned long long* __restrict__ stats,
     int row_stride) {
-  extern __shared__ uint32_t bm[];             // [W] selection bitmap, later the miss bitmap
+  extern __shared__ uint32_t bm[];             // [W] bitmap of the missed positions
   __shared__ BookShared sm;
+  constexpr int RS = 16;                       // register-held stamps per thread
   const int b = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63;
   const int W = (Lmax + 31) >> 5;
@@ -101,31 +105,36 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
 
   for (int j = tid; j < W; j += BT) bm[j] = 0;
   __syncthreads();
-  for (int e = tid; e < nsel; e += BT) {
-    const int s = sel[e];
-    if (s >= 0 && s < Lmax) atomicOr(&bm[s >> 5], 1u << (s & 31));
+  // look-up straight from the selection list (all gathers of a thread in flight together): hits get
+  // their stamp, misses set their bit; duplicates across the T query tokens do the same thing twice
+  uint32_t my_valid = 0;
+  for (int e0 = 0; e0 < nsel; e0 += 4 * BT) {
+    int sv[4], slv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int e = e0 + u * BT + tid;
+      sv[u] = e < nsel ? sel[e] : -1;
+      if (sv[u] >= Lmax) sv[u] = -1;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) slv[u] = sv[u] >= 0 ? so[sv[u]] : -1;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (sv[u] < 0) continue;
+      ++my_valid;
+      if (slv[u] >= 0) stp[slv[u]] = step;
+      else atomicOr(&bm[sv[u] >> 5], 1u << (sv[u] & 31));
+    }
   }
   __syncthreads();
 
-  // hits get their stamp; the bitmap keeps the misses only
+  // misses in ascending position: prefix sum over the bitmap words
   const int wpt = (W + BT - 1) / BT;
   const int w0 = min(tid * wpt, W), w1 = min(w0 + wpt, W);
-  uint32_t my_miss = 0, my_sel = 0;
-  for (int wd = w0; wd < w1; ++wd) {
-    uint32_t bits = bm[wd], keep = bits;
-    my_sel += __popc(bits);
-    while (bits) {
-      const int bit = __ffs(bits) - 1;
-      bits &= bits - 1;
-      const int sl = so[wd * 32 + bit];
-      if (sl >= 0) { stp[sl] = step; keep &= ~(1u << bit); }
-    }
-    bm[wd] = keep;
-    my_miss += __popc(keep);
-  }
-  uint32_t m, nuniq;
-  const uint32_t sel_inc = block_incl_scan(my_sel, sm.wave_tot, &nuniq);
-  (void)sel_inc;
+  uint32_t my_miss = 0;
+  for (int wd = w0; wd < w1; ++wd) my_miss += __popc(bm[wd]);
+  uint32_t m, nvalid;
+  (void)block_incl_scan(my_valid, sm.wave_tot, &nvalid);
   const uint32_t miss_inc = block_incl_scan(my_miss, sm.wave_tot, &m);
   {
     uint32_t pos = miss_inc - my_miss;
@@ -139,17 +148,29 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
       }
     }
   }
-  __syncthreads();
+  __syncthreads();                               // also: the stamps of the hits are visible
 
   if (m > 0) {
+    // this thread's slots: [v0, v1), contiguous so that slot order is thread order
+    const int spt = (S + BT - 1) / BT;
+    const int v0 = min(tid * spt, S), v1 = min(v0 + spt, S);
+    uint32_t sr[RS];
+    if (REG) {
+#pragma unroll
+      for (int j = 0; j < RS; ++j) sr[j] = (v0 + j < v1) ? stp[v0 + j] : 0xffffffffu;   // never evictable
+    }
+    auto stamp_at = [&](int j) -> uint32_t { return REG ? sr[j] : stp[v0 + j]; };
+    const int nj = REG ? RS : spt;
     // ---- m-th smallest stamp among evictable slots (stamp < step): 4 x 8-bit MSD radix passes
     uint32_t prefix = 0, need = m;
     for (int pass = 0; pass < 4; ++pass) {
       const int shift = 24 - 8 * pass;
       for (int j = tid; j < 256 * 32; j += BT) sm.hist[j] = 0;
       __syncthreads();
-      for (int v = tid; v < S; v += BT) {
-        const uint32_t st = stp[v];
+#pragma unroll
+      for (int j = 0; j < nj; ++j) {
+        if (v0 + j >= v1) continue;
+        const uint32_t st = stamp_at(j);
         if (st < step && (pass == 0 || (st >> (shift + 8)) == prefix))
           atomicAdd(&sm.hist[((st >> shift) & 255u) * 32 + (lane & 31)], 1u);
       }
@@ -171,20 +192,22 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
     const uint32_t tau = prefix;               // threshold stamp; `need` slots with stamp == tau are taken, lowest slots first
     // ---- collect victims: stamp < tau, plus the first `need` slots (in slot order) with stamp == tau
     if (tid == 0) sm.vict_n = 0;
-    const int spt = (S + BT - 1) / BT;
-    const int v0 = min(tid * spt, S), v1 = min(v0 + spt, S);
     uint32_t my_eq = 0;
-    for (int v = v0; v < v1; ++v) my_eq += (stp[v] == tau) ? 1u : 0u;
+#pragma unroll
+    for (int j = 0; j < nj; ++j)
+      if (v0 + j < v1) my_eq += (stamp_at(j) == tau) ? 1u : 0u;
     uint32_t eq_total;
     const uint32_t eq_inc = block_incl_scan(my_eq, sm.wave_tot, &eq_total);   // also orders the vict_n reset
     uint32_t rank = eq_inc - my_eq;
-    for (int v = v0; v < v1; ++v) {
-      const uint32_t st = stp[v];
+#pragma unroll
+    for (int j = 0; j < nj; ++j) {
+      if (v0 + j >= v1) continue;
+      const uint32_t st = stamp_at(j);
       bool take = st < tau;
       if (st == tau) { take = rank < need; ++rank; }
       if (take) {
         const uint32_t p = atomicAdd(&sm.vict_n, 1u);
-        if (p < ESS_MAX_SEL) sm.vict[p] = ((unsigned long long)st << 32) | (uint32_t)v;
+        if (p < ESS_MAX_SEL) sm.vict[p] = ((unsigned long long)st << 32) | (uint32_t)(v0 + j);
       }
     }
     __syncthreads();
@@ -209,7 +232,7 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
     miss_cnt[b] = (int32_t)m;
     if (miss_count_out) miss_count_out[b] = (int32_t)m;
     if (b == 0) atomicAdd(&stats[0], 1ull);
-    atomicAdd(&stats[1], (unsigned long long)nuniq);
+    atomicAdd(&stats[1], (unsigned long long)nvalid);
     atomicAdd(&stats[2], (unsigned long long)m);
     atomicAdd(&stats[3], (unsigned long long)m * (unsigned long long)row_stride);
   }
@@ -344,9 +367,10 @@ int ess_launch_bookkeeping(ess_ctx* ctx, const ess_cache& cache, const int32_t* 
   const ess_config& c = ctx->cfg;
   const size_t lds = (size_t)((c.max_ctx + 31) / 32) * sizeof(uint32_t);
   const bool lists = (kk == c.topk);           // compacted lists have the pitch of the top-k
-  ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_bookkeeping), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)lds));
-  hipLaunchKernelGGL(k_bookkeeping, dim3(B), dim3(BT), lds, st, idx, T, kk, c.max_ctx, c.slots_per_seq,
+  const bool reg = c.slots_per_seq <= BT * 16;
+  auto kern = reg ? &k_bookkeeping<true> : &k_bookkeeping<false>;
+  ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  hipLaunchKernelGGL(kern, dim3(B), dim3(BT), lds, st, idx, T, kk, c.max_ctx, c.slots_per_seq,
                      cache.slot_of, cache.token_of, cache.stamp, step, slot_idx,
                      lists ? ctx->hit_list : nullptr, lists ? ctx->miss_list : nullptr, ctx->n_hit, ctx->n_miss,
                      ctx->fill_tok, ctx->fill_slot, c.max_q_tokens * c.topk, ctx->miss_cnt, miss_count_out,

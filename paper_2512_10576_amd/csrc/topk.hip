@@ -6,17 +6,23 @@
 // (IB = bits needed for a position), so "the k largest composite keys" is a
 // total order with no ties and any selection algorithm gives the same set.
 //
-// One workgroup per (b,t) row:
-//   1. MSD radix narrowing, 11 bits a pass, on the composite key: histogram
-//      the next digit of the positions that still match the decided prefix,
-//      find the digit that holds the k-th largest key, descend -- until the
-//      positions matching the prefix fit a candidate buffer in LDS.
-//   2. one collection pass: keys above the prefix are selected outright, keys
-//      matching it go to the candidate buffer;
-//   3. the candidates are sorted in LDS (bitonic) and the best `need` taken;
-//   4. the k positions are sorted ascending and written.
-// The histogram is kept in 8 interleaved copies (copy = lane & 7, one bank
-// apart) so that lanes hitting the same hot bin do not serialise.
+// One workgroup per (b,t) row finds the threshold key T* = the k-th largest
+// composite key, then emits every position whose key is >= T*:
+//   A. long rows: a 14-bit histogram of every 16th score gives a key that is
+//      below the k-th largest score with high probability yet keeps only a few
+//      thousand positions at or above it; one pass over the row collects those
+//      candidates (their composite keys) in LDS.  If their number is not in
+//      [k, buffer size] (an unlucky sample, massive ties) path B runs instead.
+//   B. general: MSD radix narrowing on the composite key straight from memory,
+//      11 bits a pass (histogram in 8 interleaved copies, copy = lane & 7, so
+//      that lanes hitting one hot bin do not serialise), until the positions
+//      matching the decided prefix fit the buffer; one pass collects them.
+//   C. both: radix select inside LDS over the candidates yields T* exactly.
+//   D. the selected positions are marked in an LDS bitmap of the row and read
+//      back in ascending order (a counting sort), so the output is ordered
+//      and deterministic.
+// Row passes keep four 16-byte loads per thread in flight; a workgroup that
+// issued one load per thread and round would crawl at memory latency.
 #include "ess_internal.h"
 
 namespace {
@@ -27,13 +33,21 @@ constexpr int NBINS = 1 << HBITS;
 constexpr int COPIES = 8;
 constexpr int CAND_CAP = 8192;
 
+constexpr int SBITS = 14;                  // sample histogram: top 14 bits of the orderable key
+constexpr int SBINS = 1 << SBITS;
+constexpr int SAMPLE_STRIDE = 16;
+constexpr int FAST_MIN_VIS = 16384;
+
 struct __align__(16) TopkShared {
   union {
     uint32_t hist[NBINS * COPIES];        // 64 KiB
+    uint32_t shist[SBINS];                // 64 KiB
     unsigned long long cand[CAND_CAP];    // 64 KiB
   };
   int32_t out_list[ESS_MAX_TOPK];         // 16 KiB
+  uint32_t lhist[NBINS];                  // 8 KiB: digit histogram of the candidates held in LDS
   uint32_t wave_tot[NT / 64];
+  unsigned long long red_and[NT / 64], red_or[NT / 64];
   uint32_t out_n, cand_n;
   uint32_t sel_digit, sel_above, sel_count;
 };
@@ -72,9 +86,9 @@ __device__ __forceinline__ uint32_t block_incl_scan(uint32_t v, uint32_t* wave_t
   return inc + off;
 }
 
-// append `val` for lanes with pred, one LDS atomic per wave
+// append `val` for lanes with pred, one LDS atomic per wave; entries past `cap` are counted, not stored
 template <typename V>
-__device__ __forceinline__ void wave_append(bool pred, V val, V* list, uint32_t* counter) {
+__device__ __forceinline__ void wave_append(bool pred, V val, V* list, uint32_t* counter, uint32_t cap = 0xffffffffu) {
   const unsigned long long mask = __ballot(pred);
   if (mask == 0) return;
   const int lane = threadIdx.x & 63;
@@ -82,7 +96,8 @@ __device__ __forceinline__ void wave_append(bool pred, V val, V* list, uint32_t*
   const int leader = __ffsll((long long)mask) - 1;
   if (lane == leader) base = atomicAdd(counter, (uint32_t)__popcll(mask));
   base = __shfl(base, leader, 64);
-  if (pred) list[base + __popcll(mask & ((1ull << lane) - 1ull))] = val;
+  const uint32_t pos = base + __popcll(mask & ((1ull << lane) - 1ull));
+  if (pred && pos < cap) list[pos] = val;
 }
 
 // ascending bitonic sort of a[0..n), n a power of two, by all NT threads
@@ -103,6 +118,85 @@ __device__ void bitonic_sort(V* a, int n) {
   __syncthreads();
 }
 
+// Calls f(position, score, valid) for every position of the row, by all threads the same number of
+// times (f may hold wave-wide operations).  Each thread has four 16-byte loads in flight per round,
+// which is what makes one workgroup able to pull a 512 KiB row at cache bandwidth, not at latency.
+template <typename F>
+__device__ __forceinline__ void scan_row(const float* __restrict__ srow, int vis, bool vec_ok, F&& f) {
+  constexpr int U = 4;
+  const int tid = threadIdx.x;
+  int done = 0;
+  if (vec_ok) {
+    const int nvec = vis >> 2;
+    const float4* v4 = reinterpret_cast<const float4*>(srow);
+    for (int base = 0; base < nvec; base += NT * U) {
+      float4 x[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int j = base + u * NT + tid;
+        x[u] = j < nvec ? v4[j] : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int j = base + u * NT + tid;
+        const bool ok = j < nvec;
+        f(4 * j + 0, x[u].x, ok);
+        f(4 * j + 1, x[u].y, ok);
+        f(4 * j + 2, x[u].z, ok);
+        f(4 * j + 3, x[u].w, ok);
+      }
+    }
+    done = nvec << 2;
+  }
+  for (int i0 = done; i0 < vis; i0 += NT) {
+    const int i = i0 + tid;
+    const bool ok = i < vis;
+    f(i, ok ? srow[i] : 0.f, ok);
+  }
+}
+
+// Same walk, handing f one round (16 positions of this thread) at a time.
+template <typename F>
+__device__ __forceinline__ void scan_row_rounds(const float* __restrict__ srow, int vis, bool vec_ok, F&& f) {
+  constexpr int U = 4;
+  const int tid = threadIdx.x;
+  int done = 0;
+  int pos[16];
+  float val[16];
+  bool ok[16];
+  if (vec_ok) {
+    const int nvec = vis >> 2;
+    const float4* v4 = reinterpret_cast<const float4*>(srow);
+    for (int base = 0; base < nvec; base += NT * U) {
+      float4 x[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int j = base + u * NT + tid;
+        x[u] = j < nvec ? v4[j] : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int j = base + u * NT + tid;
+        const bool in = j < nvec;
+        pos[4 * u + 0] = 4 * j + 0; val[4 * u + 0] = x[u].x; ok[4 * u + 0] = in;
+        pos[4 * u + 1] = 4 * j + 1; val[4 * u + 1] = x[u].y; ok[4 * u + 1] = in;
+        pos[4 * u + 2] = 4 * j + 2; val[4 * u + 2] = x[u].z; ok[4 * u + 2] = in;
+        pos[4 * u + 3] = 4 * j + 3; val[4 * u + 3] = x[u].w; ok[4 * u + 3] = in;
+      }
+      f(pos, val, ok);
+    }
+    done = nvec << 2;
+  }
+  for (int i0 = done; i0 < vis; i0 += 16 * NT) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int i = i0 + e * NT + tid;
+      pos[e] = i; ok[e] = i < vis; val[e] = ok[e] ? srow[i] : 0.f;
+    }
+    f(pos, val, ok);
+  }
+}
+
 __global__ __launch_bounds__(NT) void k_topk(const float* __restrict__ score, const int32_t* __restrict__ ctx_len,
                                              int T, int Lmax, int k, int IB, int32_t* __restrict__ idx_out) {
   __shared__ TopkShared sm;
@@ -120,38 +214,171 @@ __global__ __launch_bounds__(NT) void k_topk(const float* __restrict__ score, co
   }
 
   const unsigned long long imask = (1ull << IB) - 1ull;
-  auto comp = [&](int i) -> unsigned long long {
-    return ((unsigned long long)orderable(srow[i]) << IB) | (imask - (unsigned long long)i);
+  const bool vec_ok = ((Lmax & 3) == 0) && ((reinterpret_cast<uintptr_t>(score) & 15) == 0);
+  auto comp_of = [&](int i, float v) -> unsigned long long {
+    return ((unsigned long long)orderable(v) << IB) | (imask - (unsigned long long)i);
   };
 
-  int rem = 32 + IB;                       // undecided low bits of the composite key
-  unsigned long long prefix = 0;           // decided high bits
-  uint32_t need = (uint32_t)k;             // how many keys matching the prefix are still to be taken
-  uint32_t cnt_match = (uint32_t)vis;
+  // decided high bits of T* (`prefix`), number of undecided low bits (`rem`), and how many of the
+  // keys matching the prefix are still to be taken (`need`); candidates matching it sit in sm.cand
+  int rem = 32 + IB;
+  unsigned long long prefix = 0;
+  uint32_t need = (uint32_t)k;
+  bool have_cand = false;                   // sm.cand[0..nc) holds every key matching the prefix
+  bool all_in_cand = false;                 // ... and every key above it as well (path A)
+  int nc = 0;
 
-  while (cnt_match > (uint32_t)CAND_CAP && rem > 0) {
+  // ---- A: sampled one-pass collection for long rows
+  if (vis >= FAST_MIN_VIS) {
+    const int ns = vis / SAMPLE_STRIDE;
+    for (int j = tid; j < SBINS; j += NT) sm.shist[j] = 0;
+    if (tid == 0) { sm.cand_n = 0; sm.sel_digit = 0xffffffffu; }
+    __syncthreads();
+    for (int j0 = 0; j0 < ns; j0 += 4 * NT) {
+      float sv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int j = j0 + u * NT + tid;
+        sv[u] = j < ns ? srow[j * SAMPLE_STRIDE + 7] : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (j0 + u * NT + tid < ns) atomicAdd(&sm.shist[orderable(sv[u]) >> (32 - SBITS)], 1u);
+    }
+    __syncthreads();
+    // expected number of samples above the k-th largest score, plus a margin of about 4 sigma
+    const float expct = (float)k * (float)ns / (float)vis;
+    const uint32_t target = (uint32_t)(expct + 4.0f * sqrtf(expct) + 8.0f);
+    constexpr int BPT = SBINS / NT;          // bins per thread, descending
+    const int top_bin = SBINS - 1 - tid * BPT;
+    uint32_t mine = 0;
+#pragma unroll
+    for (int r = 0; r < BPT; ++r) mine += sm.shist[top_bin - r];
+    uint32_t total;
+    const uint32_t inc = block_incl_scan(mine, sm.wave_tot, &total);
+    uint32_t above = inc - mine;
+    if (above < target && inc >= target) {    // the crossing bin is one of mine
+      for (int r = 0; r < BPT; ++r) {
+        above += sm.shist[top_bin - r];
+        if (above >= target) { sm.sel_digit = (uint32_t)(top_bin - r); break; }
+      }
+    }
+    __syncthreads();
+    const uint32_t lo_bin = sm.sel_digit;
+    __syncthreads();                          // shist is dead from here: cand may overwrite it
+    if (lo_bin != 0xffffffffu) {
+      const uint32_t tau = lo_bin << (32 - SBITS);
+      scan_row_rounds(srow, vis, vec_ok, [&](const int (&pos)[16], const float (&val)[16], const bool (&ok)[16]) {
+        unsigned long long c[16];
+        uint32_t cnt = 0, flags = 0;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const uint32_t u = orderable(val[e]);
+          c[e] = ((unsigned long long)u << IB) | (imask - (unsigned long long)pos[e]);
+          if (ok[e] && u >= tau) { flags |= 1u << e; ++cnt; }
+        }
+        // one LDS atomic per wave and round
+        const uint32_t winc = wave_incl_scan(cnt, lane);
+        uint32_t base = 0;
+        if (lane == 63 && winc) base = atomicAdd(&sm.cand_n, winc);
+        base = __shfl(base, 63, 64) + winc - cnt;
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          if (flags & (1u << e)) {
+            if (base < (uint32_t)CAND_CAP) sm.cand[base] = c[e];
+            ++base;
+          }
+      });
+      __syncthreads();
+      nc = (int)sm.cand_n;
+      if (nc >= k && nc <= CAND_CAP) {
+        // bits on which the candidates differ: everything above is common and decided
+        unsigned long long a = ~0ull, o = 0ull;
+        for (int j = tid; j < nc; j += NT) { a &= sm.cand[j]; o |= sm.cand[j]; }
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) { a &= __shfl_xor(a, d, 64); o |= __shfl_xor(o, d, 64); }
+        if (lane == 0) { sm.red_and[tid >> 6] = a; sm.red_or[tid >> 6] = o; }
+        __syncthreads();
+        a = ~0ull; o = 0ull;
+#pragma unroll
+        for (int i = 0; i < NT / 64; ++i) { a &= sm.red_and[i]; o |= sm.red_or[i]; }
+        const unsigned long long diff = a ^ o;
+        rem = diff ? 64 - __clzll((long long)diff) : 0;
+        prefix = rem < 64 ? (o >> rem) : 0;
+        have_cand = true;
+        all_in_cand = true;
+      }
+      __syncthreads();
+    }
+  }
+
+  // ---- B: general narrowing from memory
+  if (!have_cand) {
+    uint32_t cnt_match = (uint32_t)vis;
+    while (cnt_match > (uint32_t)CAND_CAP && rem > 0) {
+      const int bits = min(HBITS, rem);
+      const int shift = rem - bits;
+      const uint32_t dmask = (1u << bits) - 1u;
+      for (int j = tid; j < NBINS * COPIES; j += NT) sm.hist[j] = 0;
+      __syncthreads();
+      scan_row(srow, vis, vec_ok, [&](int i, float v, bool ok) {
+        const unsigned long long c = comp_of(i, v);
+        if (ok && (c >> rem) == prefix)
+          atomicAdd(&sm.hist[(((uint32_t)(c >> shift)) & dmask) * COPIES + (lane & 7)], 1u);
+      });
+      __syncthreads();
+      // thread tid owns digits NBINS-1-2*tid and NBINS-2-2*tid (descending), scan = suffix counts
+      const int d_hi = NBINS - 1 - 2 * tid, d_lo = d_hi - 1;
+      uint32_t c_hi = 0, c_lo = 0;
+#pragma unroll
+      for (int r = 0; r < COPIES; ++r) {
+        c_hi += sm.hist[d_hi * COPIES + r];
+        c_lo += sm.hist[d_lo * COPIES + r];
+      }
+      uint32_t total;
+      const uint32_t inc = block_incl_scan(c_hi + c_lo, sm.wave_tot, &total);
+      const uint32_t above_hi = inc - c_hi - c_lo;      // keys with a digit > d_hi
+      const uint32_t above_lo = above_hi + c_hi;        // keys with a digit > d_lo
+      if (above_hi < need && above_hi + c_hi >= need) {
+        sm.sel_digit = d_hi; sm.sel_above = above_hi; sm.sel_count = c_hi;
+      } else if (above_lo < need && above_lo + c_lo >= need) {
+        sm.sel_digit = d_lo; sm.sel_above = above_lo; sm.sel_count = c_lo;
+      }
+      __syncthreads();
+      need -= sm.sel_above;
+      prefix = (prefix << bits) | sm.sel_digit;
+      cnt_match = sm.sel_count;
+      rem = shift;
+      __syncthreads();
+    }
+    if (tid == 0) sm.cand_n = 0;
+    __syncthreads();
+    scan_row(srow, vis, vec_ok, [&](int i, float v, bool ok) {
+      const unsigned long long c = comp_of(i, v);
+      wave_append<unsigned long long>(ok && (c >> rem) == prefix, c, sm.cand, &sm.cand_n, CAND_CAP);
+    });
+    __syncthreads();
+    nc = (int)sm.cand_n;
+  }
+
+  // ---- C: radix select inside LDS: the need-th largest candidate among those matching the prefix
+  while (rem > 0) {
     const int bits = min(HBITS, rem);
     const int shift = rem - bits;
     const uint32_t dmask = (1u << bits) - 1u;
-    for (int j = tid; j < NBINS * COPIES; j += NT) sm.hist[j] = 0;
+    for (int j = tid; j < NBINS; j += NT) sm.lhist[j] = 0;
     __syncthreads();
-    for (int i = tid; i < vis; i += NT) {
-      const unsigned long long c = comp(i);
-      if ((c >> rem) == prefix) atomicAdd(&sm.hist[(((uint32_t)(c >> shift)) & dmask) * COPIES + (lane & 7)], 1u);
+    for (int j = tid; j < nc; j += NT) {
+      const unsigned long long c = sm.cand[j];
+      if ((c >> rem) == prefix) atomicAdd(&sm.lhist[((uint32_t)(c >> shift)) & dmask], 1u);
     }
     __syncthreads();
-    // thread tid owns digits NBINS-1-2*tid and NBINS-2-2*tid (descending), scan = suffix counts
     const int d_hi = NBINS - 1 - 2 * tid, d_lo = d_hi - 1;
-    uint32_t c_hi = 0, c_lo = 0;
-#pragma unroll
-    for (int r = 0; r < COPIES; ++r) {
-      c_hi += sm.hist[d_hi * COPIES + r];
-      c_lo += sm.hist[d_lo * COPIES + r];
-    }
+    const uint32_t c_hi = sm.lhist[d_hi], c_lo = sm.lhist[d_lo];
     uint32_t total;
     const uint32_t inc = block_incl_scan(c_hi + c_lo, sm.wave_tot, &total);
-    const uint32_t above_hi = inc - c_hi - c_lo;      // keys with a digit > d_hi
-    const uint32_t above_lo = above_hi + c_hi;        // keys with a digit > d_lo
+    const uint32_t above_hi = inc - c_hi - c_lo;
+    const uint32_t above_lo = above_hi + c_hi;
     if (above_hi < need && above_hi + c_hi >= need) {
       sm.sel_digit = d_hi; sm.sel_above = above_hi; sm.sel_count = c_hi;
     } else if (above_lo < need && above_lo + c_lo >= need) {
@@ -160,41 +387,55 @@ __global__ __launch_bounds__(NT) void k_topk(const float* __restrict__ score, co
     __syncthreads();
     need -= sm.sel_above;
     prefix = (prefix << bits) | sm.sel_digit;
-    cnt_match = sm.sel_count;
+    const uint32_t cnt = sm.sel_count;
     rem = shift;
     __syncthreads();
+    if (cnt == need) break;                  // every key with this prefix is taken
   }
+  const unsigned long long t_star = rem < 64 ? (prefix << rem) : 0ull;
 
-  // collection
-  if (tid == 0) { sm.out_n = 0; sm.cand_n = 0; }
-  __syncthreads();
-  for (int i0 = 0; i0 < vis; i0 += NT) {
-    const int i = i0 + tid;
-    bool sel = false, cnd = false;
-    unsigned long long c = 0;
-    if (i < vis) {
-      c = comp(i);
-      const unsigned long long top = c >> rem;
-      sel = top > prefix;
-      cnd = top == prefix;
+  // ---- D: mark the selected positions in a bitmap of the row, read them back in ascending order
+  uint32_t* bmp = sm.hist;                   // aliases cand: the keys are moved out first
+  const int W = (vis + 31) >> 5;             // <= 16384 words
+  if (all_in_cand) {
+    if (tid == 0) sm.out_n = 0;
+    __syncthreads();
+    for (int j0 = 0; j0 < nc; j0 += NT) {
+      const int j = j0 + tid;
+      const unsigned long long c = j < nc ? sm.cand[j] : 0ull;
+      wave_append<int32_t>(j < nc && c >= t_star, (int32_t)(imask - (c & imask)), sm.out_list, &sm.out_n, ESS_MAX_TOPK);
     }
-    wave_append<int32_t>(sel, i, sm.out_list, &sm.out_n);
-    wave_append<unsigned long long>(cnd, c, sm.cand, &sm.cand_n);
+    __syncthreads();
+    for (int j = tid; j < W; j += NT) bmp[j] = 0;
+    __syncthreads();
+    for (int j = tid; j < k; j += NT) {
+      const int pos = sm.out_list[j];
+      atomicOr(&bmp[pos >> 5], 1u << (pos & 31));
+    }
+  } else {
+    __syncthreads();
+    for (int j = tid; j < W; j += NT) bmp[j] = 0;
+    __syncthreads();
+    scan_row(srow, vis, vec_ok, [&](int i, float v, bool ok) {
+      if (ok && comp_of(i, v) >= t_star) atomicOr(&bmp[i >> 5], 1u << (i & 31));
+    });
   }
   __syncthreads();
-  const int nc = (int)sm.cand_n;
-  int np = 1;
-  while (np < nc) np <<= 1;
-  for (int j = nc + tid; j < np; j += NT) sm.cand[j] = 0ull;   // below every real key
-  bitonic_sort<unsigned long long>(sm.cand, np);               // ascending: best keys at the end
-  const uint32_t got = sm.out_n;                               // = k - need
-  for (uint32_t j = tid; j < need; j += NT)
-    sm.out_list[got + j] = (int32_t)(imask - (sm.cand[np - 1 - j] & imask));
-  int kp = 1;
-  while (kp < k) kp <<= 1;
-  for (int j = k + tid; j < kp; j += NT) sm.out_list[j] = 0x7fffffff;
-  bitonic_sort<int32_t>(sm.out_list, kp);
-  for (int j = tid; j < k; j += NT) orow[j] = sm.out_list[j];
+  const int wpt = (W + NT - 1) / NT;
+  const int w0 = min(tid * wpt, W), w1 = min(w0 + wpt, W);
+  uint32_t mine = 0;
+  for (int wd = w0; wd < w1; ++wd) mine += __popc(bmp[wd]);
+  uint32_t total;
+  uint32_t outp = block_incl_scan(mine, sm.wave_tot, &total) - mine;
+  for (int wd = w0; wd < w1; ++wd) {
+    uint32_t bits = bmp[wd];
+    while (bits) {
+      const int bit = __ffs(bits) - 1;
+      bits &= bits - 1;
+      if (outp < (uint32_t)k) orow[outp] = wd * 32 + bit;
+      ++outp;
+    }
+  }
 }
 
 }  // namespace
