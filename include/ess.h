@@ -64,7 +64,7 @@ typedef struct ess_ctx ess_ctx;
 /* Fixed for the life of a context. */
 typedef struct {
   uint32_t struct_size;   /* sizeof(ess_config), checked */
-  int32_t max_batch;      /* largest B any call will pass */
+  int32_t max_batch;      /* largest B any call will pass; <= 4096 */
   int32_t max_q_tokens;   /* largest T (1 or 2) */
   int32_t max_ctx;        /* Lmax: row pitch of key, score and slot_of; <= 524288 */
   int32_t idx_heads;      /* Hi, 1..64 */

@@ -274,31 +274,58 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
   }
 }
 
-// Fetch: one wave per missed entry, rows copied host pool -> slot pool in 16-byte pieces.  Two
-// entries per wave are in flight at once.  The grid is kept small (about two waves per CU):
-// these waves spend their life waiting on the host link, and a large grid would occupy every
-// wave slot of the chip and starve the attention kernel that runs beside it.
-__global__ __launch_bounds__(256) void k_fill(const uint8_t* __restrict__ host_pool, uint8_t* __restrict__ slot_pool,
-                                              const int32_t* __restrict__ fill_tok,
-                                              const int32_t* __restrict__ fill_slot, int fill_cap,
-                                              const int32_t* __restrict__ miss_cnt, int Lmax, int S, int row_stride) {
-  const int b = blockIdx.y;
-  const int m = min(miss_cnt[b], fill_cap);
-  const int lane = threadIdx.x & 63;
-  const int nw = gridDim.x * 4;
-  const int chunks = row_stride >> 4;          // <= 128 for the supported entry sizes
-  const int32_t* ft = fill_tok + (size_t)b * fill_cap;
-  const int32_t* fs = fill_slot + (size_t)b * fill_cap;
-  const uint8_t* hp = host_pool + (size_t)b * Lmax * row_stride;
-  uint8_t* sp = slot_pool + (size_t)b * S * row_stride;
+// Fetch: one wave per missed entry, rows copied host pool -> slot pool in 16-byte pieces, two
+// entries per wave in flight at once.  The kernel is a handful of 1024-thread workgroups that loop
+// over all sequences: its waves spend their life waiting on the host link, and the attention kernel
+// that runs beside it needs whole CUs (one wave per SIMD with a large register file), so the fetch
+// must stay on a few CUs instead of sprinkling one wave onto every SIMD of the chip.
+constexpr int FILL_WGS = 64;
+constexpr int FILL_WPB = 8;                                 // waves per workgroup
+constexpr int FILL_WAVES = FILL_WGS * FILL_WPB;
+constexpr int FILL_MAX_B = 4096;
+
+__global__ __launch_bounds__(FILL_WPB * 64) void k_fill(const uint8_t* __restrict__ host_pool, uint8_t* __restrict__ slot_pool,
+                                               const int32_t* __restrict__ fill_tok,
+                                               const int32_t* __restrict__ fill_slot, int fill_cap,
+                                               const int32_t* __restrict__ miss_cnt, int B, int Lmax, int S,
+                                               int row_stride) {
+  __shared__ int32_t pref[FILL_MAX_B + 1];                   // pref[b] = entries of sequences < b
+  __shared__ uint32_t wave_tot[16];
+  const int tid = threadIdx.x, lane = tid & 63;
+  // exclusive prefix sum of the per-sequence miss counts (B <= 4096), by the first wave
+  (void)wave_tot;
+  if (tid < 64) {
+    int run = 0;
+    for (int b0 = 0; b0 <= B; b0 += 64) {
+      const int b = b0 + lane;
+      const int cnt = b < B ? min(miss_cnt[b], fill_cap) : 0;
+      const int inc = (int)wave_incl_scan((uint32_t)cnt, lane);
+      if (b <= B) pref[b] = run + inc - cnt;
+      run += __shfl(inc, 63, 64);
+    }
+  }
+  __syncthreads();
+  const int M = pref[B];
+  const int gw = blockIdx.x * FILL_WPB + (tid >> 6);         // wave index in the grid
+  const int chunks = row_stride >> 4;                        // <= 128 for the supported entry sizes
   const int c0 = lane, c1 = lane + 64;
-  for (int i = blockIdx.x * 4 + (threadIdx.x >> 6); i < m; i += 2 * nw) {
-    const int j = i + nw;
-    const bool two = j < m;
-    const uint4* srcA = reinterpret_cast<const uint4*>(hp + (size_t)ft[i] * row_stride);
-    const uint4* srcB = reinterpret_cast<const uint4*>(hp + (size_t)ft[two ? j : i] * row_stride);
-    uint4* dstA = reinterpret_cast<uint4*>(sp + (size_t)fs[i] * row_stride);
-    uint4* dstB = reinterpret_cast<uint4*>(sp + (size_t)fs[two ? j : i] * row_stride);
+  auto locate = [&](int r, const uint4*& src, uint4*& dst) { // r-th entry of the flattened list
+    int lo = 0, hi = B;                                      // largest b with pref[b] <= r
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (pref[mid] <= r) lo = mid; else hi = mid;
+    }
+    const int i = r - pref[lo];
+    const int tok = fill_tok[(size_t)lo * fill_cap + i], slot = fill_slot[(size_t)lo * fill_cap + i];
+    src = reinterpret_cast<const uint4*>(host_pool + ((size_t)lo * Lmax + tok) * row_stride);
+    dst = reinterpret_cast<uint4*>(slot_pool + ((size_t)lo * S + slot) * row_stride);
+  };
+  for (int r = gw; r < M; r += 2 * FILL_WAVES) {             // two entries of this wave in flight
+    const bool two = r + FILL_WAVES < M;
+    const uint4 *srcA, *srcB;
+    uint4 *dstA, *dstB;
+    locate(r, srcA, dstA);
+    locate(two ? r + FILL_WAVES : r, srcB, dstB);
     uint4 a0 = make_uint4(0, 0, 0, 0), a1 = a0, b0 = a0, b1 = a0;
     if (c0 < chunks) a0 = srcA[c0];
     if (c1 < chunks) a1 = srcA[c1];
@@ -382,10 +409,8 @@ int ess_launch_bookkeeping(ess_ctx* ctx, const ess_cache& cache, const int32_t* 
 int ess_launch_fill(ess_ctx* ctx, const ess_cache& cache, int B, int per_seq_cap, hipStream_t st) {
   const ess_config& c = ctx->cfg;
   (void)per_seq_cap;
-  int gx = (512 + 4 * B - 1) / (4 * B);        // about 512 waves in total
-  if (gx > 32) gx = 32;
-  hipLaunchKernelGGL(k_fill, dim3(gx, B), dim3(256), 0, st, cache.host_pool_dev, cache.slot_pool, ctx->fill_tok,
-                     ctx->fill_slot, c.max_q_tokens * c.topk, ctx->miss_cnt, c.max_ctx, c.slots_per_seq,
+  hipLaunchKernelGGL(k_fill, dim3(FILL_WGS), dim3(FILL_WPB * 64), 0, st, cache.host_pool_dev, cache.slot_pool, ctx->fill_tok,
+                     ctx->fill_slot, c.max_q_tokens * c.topk, ctx->miss_cnt, B, c.max_ctx, c.slots_per_seq,
                      c.row_stride);
   ESS_HIP(hipGetLastError());
   return ESS_OK;

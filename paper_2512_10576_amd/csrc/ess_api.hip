@@ -23,7 +23,7 @@ int validate_config(const ess_config* c) {
   if (!c) return ess_fail(ESS_ERR_INVALID_ARG, "config is NULL");
   if (c->struct_size != sizeof(ess_config))
     return ess_fail(ESS_ERR_INVALID_ARG, "struct_size %u != %zu", c->struct_size, sizeof(ess_config));
-  if (c->max_batch < 1 || c->max_batch > 65535) return ess_fail(ESS_ERR_INVALID_ARG, "max_batch %d", c->max_batch);
+  if (c->max_batch < 1 || c->max_batch > 4096) return ess_fail(ESS_ERR_INVALID_ARG, "max_batch %d outside [1, 4096]", c->max_batch);
   if (c->max_q_tokens < 1 || c->max_q_tokens > 2)
     return ess_fail(ESS_ERR_UNSUPPORTED, "max_q_tokens %d (supported: 1, 2)", c->max_q_tokens);
   if (c->max_ctx < 1 || c->max_ctx > ESS_MAX_CTX)
@@ -99,13 +99,16 @@ int check_cache(const ess_ctx* ctx, const ess_cache* c) {
   return ESS_OK;
 }
 
-// number of attention splits for a list of up to k entries
+// number of attention splits for a list of up to k entries: a workgroup is sized to own a CU, so aim at
+// a small multiple of the CU count; never fewer than the kernel's tiles-per-split limit allows
 int pick_splits(const ess_config& c, int B, int T, int cap) {
   const int tiles = (c.topk + ESS_ATTN_TILE - 1) / ESS_ATTN_TILE;
-  const int hgroups = ((c.attn_heads + 15) / 16 + 3) / 4;
-  int want = (1024 + B * T * hgroups - 1) / (B * T * hgroups);   // aim at >= 1024 workgroups (4 per CU)
+  const int hgroups = (c.attn_heads + 63) / 64;
+  int want = (512 + B * T * hgroups - 1) / (B * T * hgroups);   // two rounds of one workgroup per CU
   if (want > tiles) want = tiles;
   if (want > cap) want = cap;
+  const int lo = ess_attn_min_splits(c);
+  if (want < lo) want = lo;
   return want < 1 ? 1 : want;
 }
 
@@ -345,6 +348,7 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
   // stage 4: Attn0 over resident entries while the fetch runs, Attn1 over fetched ones, merge
   const int ns0 = pick_splits(c, B, T, 16);
   int ns1 = ns0 / 4;
+  if (ns1 < ess_attn_min_splits(c)) ns1 = ess_attn_min_splits(c);
   if (ns1 < 1) ns1 = 1;
   if (ns1 > ESS_MAX_SPLITS - 16) ns1 = ESS_MAX_SPLITS - 16;
   rc = ess_launch_attn_partial(ctx, a->q_bf16, cache->slot_pool, ctx->hit_list, ctx->n_hit, B, T, 0, ns0, st);

@@ -2,25 +2,32 @@
 // Sec. 3.3), absorbed form: the 576 values of an entry are the key, the first
 // 512 the value.  Flash-decoding layout: every (b,t) is cut into `nsplit`
 // ranges of its entry list; each workgroup produces a softmax-normalised
-// partial output and its log-sum-exp, and a merge kernel combines the partial
-// results -- the same merge that joins Attn0 (resident entries) and Attn1
-// (fetched entries) of the DA overlap.
+// partial output and its log-sum-exp for all heads, and a merge kernel
+// combines the partial results -- the same merge that joins Attn0 (resident
+// entries) and Attn1 (fetched entries) of the DA overlap.
 //
-// Matrix-core mapping (v_mfma_f32_16x16x32_bf16, wave64).  A wave owns 16
-// heads.  Both products are computed transposed so that nothing has to be
-// re-laid out between them:
-//   S^T[r,h] = sum_d K[r,d] Q[h,d]   A = entry rows from LDS (row-major),
-//                                    B = Q^T, stationary in registers (72 VGPRs)
-//   O^T[v,h] = sum_r V^T[v,r] P^T[r,h]  A = V^T from LDS, B = P^T
-// The accumulator of S^T gives lane (g,h) the eight logits of head h for tile
-// rows {4g..4g+3} and {16+4g..16+4g+3}; in exactly that order they are the
-// eight k-values a lane supplies for the B operand of the second product, so
-// P^T never leaves registers.  The softmax state (running max, running sum)
-// is per lane = per head; the max needs two cross-lane steps per tile.
-// The second product needs V^T with the tile rows contiguous, so every tile
-// is stored twice in LDS while it is staged: row-major for the first product
-// and transposed (rows permuted to match the order above, 16-byte granules
-// XOR-swizzled against bank conflicts) for the second.
+// Matrix-core mapping (v_mfma_f32_16x16x32_bf16, wave64).  A workgroup is four
+// waves, one per SIMD, each owning 16 heads with the whole 512-wide output row
+// in registers (128 accumulator VGPRs) and its queries stationary (72 VGPRs);
+// 64 heads per workgroup, head groups in grid.z.  The kernel is built for one
+// wave per SIMD and the large register budget that comes with it (a variant
+// with 32 heads per wave, which would halve LDS traffic per flop, is kept as a
+// template parameter but does not fit the register file without spilling).
+// Both products are computed transposed so that
+// nothing is re-laid out between them:
+//   S^T[r,h] = sum_d K[r,d] Q[h,d]      A = entry rows from LDS (row-major), B = Q^T (registers)
+//   O^T[v,h] = sum_r V^T[v,r] P^T[r,h]  A = V^T from LDS,                    B = P^T (registers)
+// The accumulator of S^T gives lane (g,h) the eight logits of head h for tile rows
+// {4g..4g+3} and {16+4g..16+4g+3}; in exactly that order they are the eight
+// k-values the lane supplies for the B operand of the second product, so P^T
+// never leaves registers.  Softmax state is per lane = per head; the running
+// max needs two cross-lane steps per tile.
+// The second product needs V^T with the tile rows contiguous, so a tile is
+// stored twice in LDS while it is staged: row-major (pitch padded by 16 B)
+// and transposed (rows permuted to the order above, 16-byte granules
+// XOR-swizzled against bank conflicts).  Tiles are double-buffered in LDS and
+// the gathered row loads of tile i+1 are in flight, in registers, while tile
+// i is computed, so one workgroup per CU hides the gather latency by itself.
 #include "ess_internal.h"
 #include <hip/hip_bf16.h>
 
@@ -30,18 +37,24 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 namespace {
 
 constexpr int TILE = ESS_ATTN_TILE;            // 32 entries
+constexpr int NTH = 256;                       // four waves
 constexpr int KPITCH = 1152 + 16;              // bytes; +16 spreads the 16 rows of an A fragment over the banks
 constexpr int KSTEPS = ESS_ROW_DIM / 32;       // 18
 constexpr int VBLOCKS = ESS_LATENT_DIM / 16;   // 32
 constexpr int KT_BYTES = TILE * KPITCH;        // 37376
 constexpr int VT_BYTES = ESS_LATENT_DIM * 64;  // 32768: V^T[v][32 positions] bf16
+constexpr int BUF_BYTES = KT_BYTES + VT_BYTES; // one staged tile
+constexpr int MAX_TPS = 32;                    // tiles per split (the launcher picks nsplit accordingly)
+constexpr int LDS_BYTES = 2 * BUF_BYTES + MAX_TPS * TILE * 4;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
+constexpr int UPT = 512 / NTH;                 // latent units (4 rows x 16 bytes) per thread and tile
+constexpr int RPT = 256 / NTH;                 // rope pieces per thread and tile
 
 __device__ __forceinline__ int vt_granule(int v, int gran) { return gran ^ (((v >> 1) ^ (v >> 3)) & 3); }
 
 __device__ __forceinline__ float fp8_e4m3_to_f32(uint32_t byte) {
-  // OCP E4M3: 1-4-3, bias 7, subnormals at exponent 0 (NaN pattern is not produced by the quantiser)
+  // OCP E4M3: 1-4-3, bias 7, subnormals at exponent 0 (the NaN pattern is not produced by a quantiser)
   const uint32_t s = (byte & 0x80u) << 24;
   const uint32_t e = (byte >> 3) & 0xFu;
   const uint32_t m = byte & 0x7u;
@@ -56,210 +69,272 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   return (uint32_t)(*reinterpret_cast<const uint16_t*>(&x)) | ((uint32_t)(*reinterpret_cast<const uint16_t*>(&y)) << 16);
 }
 
-// One 16-byte piece (8 bf16 values, dims [8*cc, 8*cc+8)) of an entry, whatever its storage format.
+// One piece = the 8 values of dims [8*cc, 8*cc+8) of an entry as it sits in memory (what a
+// prefetch keeps in registers), and its conversion to 8 bf16.
+template <int FMT> struct RawPiece;
+template <> struct RawPiece<ESS_FMT_BF16> { uint4 d; };
+template <> struct RawPiece<ESS_FMT_FP8> { uint2 d; uint32_t scale; };
+
 template <int FMT>
-__device__ __forceinline__ uint4 load_piece(const uint8_t* row, int cc) {
+__device__ __forceinline__ RawPiece<FMT> load_raw(const uint8_t* row, int cc) {
+  RawPiece<FMT> r;
   if constexpr (FMT == ESS_FMT_BF16) {
-    return *reinterpret_cast<const uint4*>(row + cc * 16);
+    r.d = *reinterpret_cast<const uint4*>(row + cc * 16);
   } else {
-    if (cc >= 64) return *reinterpret_cast<const uint4*>(row + 520 + (cc - 64) * 16);  // rope, stored as bf16
-    const uint2 raw = *reinterpret_cast<const uint2*>(row + cc * 8);
-    const uint16_t sbits = *reinterpret_cast<const uint16_t*>(row + 512 + (cc >> 4) * 2);
-    const float sc = __uint_as_float((uint32_t)sbits << 16);
+    r.d = *reinterpret_cast<const uint2*>(row + cc * 8);
+    r.scale = *reinterpret_cast<const uint16_t*>(row + 512 + (cc >> 4) * 2);
+  }
+  return r;
+}
+
+template <int FMT>
+__device__ __forceinline__ uint4 to_bf16x8(const RawPiece<FMT>& r, bool keep) {
+  uint4 out;
+  if constexpr (FMT == ESS_FMT_BF16) {
+    out = r.d;
+  } else {
+    const float sc = __uint_as_float(r.scale << 16);
     float f[8];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      f[i] = fp8_e4m3_to_f32((raw.x >> (8 * i)) & 0xFFu) * sc;
-      f[4 + i] = fp8_e4m3_to_f32((raw.y >> (8 * i)) & 0xFFu) * sc;
+      f[i] = fp8_e4m3_to_f32((r.d.x >> (8 * i)) & 0xFFu) * sc;
+      f[4 + i] = fp8_e4m3_to_f32((r.d.y >> (8 * i)) & 0xFFu) * sc;
     }
-    return make_uint4(pack_bf16(f[0], f[1]), pack_bf16(f[2], f[3]), pack_bf16(f[4], f[5]), pack_bf16(f[6], f[7]));
+    out = make_uint4(pack_bf16(f[0], f[1]), pack_bf16(f[2], f[3]), pack_bf16(f[4], f[5]), pack_bf16(f[6], f[7]));
+  }
+  return keep ? out : make_uint4(0, 0, 0, 0);
+}
+
+// rope piece (dims 512 + 8*rc ..): bf16 in both formats
+template <int FMT>
+__device__ __forceinline__ uint4 load_rope(const uint8_t* row, int rc) {
+  return *reinterpret_cast<const uint4*>(row + (FMT == ESS_FMT_BF16 ? 1024 : 520) + rc * 16);
+}
+
+template <int FMT>
+struct Staged {                                // one tile's share of a thread, as loaded
+  RawPiece<FMT> lat[UPT][4];
+  uint4 rope[RPT];
+};
+
+// Issue every global load of this thread for a tile.  Masked rows read slot 0 (always valid
+// memory); they are zeroed when stored.
+template <int FMT>
+__device__ __forceinline__ void stage_load(Staged<FMT>& st, const int32_t* tile_slot, const uint8_t* pbase,
+                                           int row_stride, int tid) {
+#pragma unroll
+  for (int i = 0; i < RPT; ++i) {
+    const int u = tid + i * NTH;
+    st.rope[i] = load_rope<FMT>(pbase + (size_t)max(tile_slot[u >> 3], 0) * row_stride, u & 7);
+  }
+#pragma unroll
+  for (int i = 0; i < UPT; ++i) {
+    const int u = tid + i * NTH;
+    const int rg = u >> 6, cc = u & 63;        // row group (4 rows), 16-byte column piece
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      st.lat[i][r] = load_raw<FMT>(pbase + (size_t)max(tile_slot[rg * 4 + r], 0) * row_stride, cc);
   }
 }
 
-// NW waves per workgroup, 16 heads each.
-template <int NW, int FMT>
-__global__ __launch_bounds__(NW * 64, 1) void k_attn_partial(
+// Write a loaded tile into an LDS buffer: row-major copy (Kt) and transposed copy (Vt).
+template <int FMT>
+__device__ __forceinline__ void stage_store(const Staged<FMT>& st, const int32_t* tile_slot, uint8_t* Kt, uint8_t* Vt,
+                                            int tid) {
+#pragma unroll
+  for (int i = 0; i < UPT; ++i) {
+    const int u = tid + i * NTH;
+    const int rg = u >> 6, cc = u & 63;
+    uint4 x[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      x[r] = to_bf16x8<FMT>(st.lat[i][r], tile_slot[rg * 4 + r] >= 0);
+      *reinterpret_cast<uint4*>(Kt + (rg * 4 + r) * KPITCH + cc * 16) = x[r];
+    }
+    // rows 4g'..4g'+3 sit at positions 8g'..8g'+3 of V^T, rows 16+4g'.. at 8g'+4..8g'+7
+    const int gq = rg & 3, half = rg >> 2;
+    const uint32_t* x0 = reinterpret_cast<const uint32_t*>(&x[0]);
+    const uint32_t* x1 = reinterpret_cast<const uint32_t*>(&x[1]);
+    const uint32_t* x2 = reinterpret_cast<const uint32_t*>(&x[2]);
+    const uint32_t* x3 = reinterpret_cast<const uint32_t*>(&x[3]);
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const uint32_t a0 = x0[p], a1 = x1[p], a2 = x2[p], a3 = x3[p];
+      const uint2 even = make_uint2((a0 & 0xffffu) | (a1 << 16), (a2 & 0xffffu) | (a3 << 16));
+      const uint2 odd = make_uint2((a0 >> 16) | (a1 & 0xffff0000u), (a2 >> 16) | (a3 & 0xffff0000u));
+      const int v0 = cc * 8 + 2 * p, v1 = v0 + 1;
+      *reinterpret_cast<uint2*>(Vt + v0 * 64 + vt_granule(v0, gq) * 16 + half * 8) = even;
+      *reinterpret_cast<uint2*>(Vt + v1 * 64 + vt_granule(v1, gq) * 16 + half * 8) = odd;
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < RPT; ++i) {
+    const int u = tid + i * NTH;
+    const uint4 x = tile_slot[u >> 3] >= 0 ? st.rope[i] : make_uint4(0, 0, 0, 0);
+    *reinterpret_cast<uint4*>(Kt + (u >> 3) * KPITCH + (64 + (u & 7)) * 16) = x;
+  }
+}
+
+// HB = 16-head blocks per wave (1: 64 heads per workgroup, 2: 128)
+template <int FMT, int HB>
+__global__ __launch_bounds__(NTH, 1) void k_attn_partial(
     const uint16_t* __restrict__ q, const uint8_t* __restrict__ pool, const int32_t* __restrict__ list,
     const int32_t* __restrict__ n_list, int T, int H, int kk, int S, int row_stride, float scale_log2e, int split0,
     int nsplit, float* __restrict__ o_part, float* __restrict__ lse_part) {
   extern __shared__ __align__(16) uint8_t lds[];
-  uint8_t* Kt = lds;
-  uint8_t* Vt = lds + KT_BYTES;
-  int32_t* slot_cache = reinterpret_cast<int32_t*>(lds + KT_BYTES + VT_BYTES);  // [16 tiles][32]
+  int32_t* slot_cache = reinterpret_cast<int32_t*>(lds + 2 * BUF_BYTES);       // [MAX_TPS][32]
 
-  constexpr int NTH = NW * 64;
   const int split = blockIdx.x;
   const int bt = blockIdx.y;
   const int b = bt / T;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 4, n16 = lane & 15;
-  const int head = (blockIdx.z * NW + wave) * 16 + n16;
+  constexpr int HPW = 16 * HB;                 // heads per wave
+  const int head0 = (blockIdx.z * 4 + wave) * HPW;
+  const bool wave_active = head0 < H;          // idle waves still help staging
 
   const int n = n_list ? min(n_list[bt], kk) : kk;
   const int tiles_total = (n + TILE - 1) / TILE;
-  const int tps = (tiles_total + nsplit - 1) / nsplit;
+  const int tps = min((tiles_total + nsplit - 1) / nsplit, MAX_TPS);
   const int tile_begin = split * tps;
   const int tile_end = min(tile_begin + tps, tiles_total);
+  const int my_tiles = max(tile_end - tile_begin, 0);
 
-  // Q^T fragments: lane (g,h) holds Q[h][32*ks + 8g .. +8)
-  bf16x8 qb[KSTEPS];
-  {
+  // Q^T fragments: lane (g,h) holds Q[h][32*ks + 8g .. +8) for its two head blocks
+  bf16x8 qb[HB][KSTEPS];
+#pragma unroll
+  for (int hb = 0; hb < HB; ++hb) {
+    const int head = head0 + hb * 16 + n16;
     const uint16_t* qrow = q + ((size_t)bt * H + min(head, H - 1)) * ESS_ROW_DIM;
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks) {
       uint4 x = *reinterpret_cast<const uint4*>(qrow + ks * 32 + g * 8);
       if (head >= H) x = make_uint4(0, 0, 0, 0);
-      qb[ks] = *reinterpret_cast<bf16x8*>(&x);
+      qb[hb][ks] = *reinterpret_cast<bf16x8*>(&x);
     }
   }
 
-  floatx4 acc[VBLOCKS];
+  floatx4 acc[HB][VBLOCKS];
 #pragma unroll
-  for (int vb = 0; vb < VBLOCKS; ++vb) acc[vb] = floatx4{0.f, 0.f, 0.f, 0.f};
-  float m_run = -__builtin_inff();             // running max of the scaled logits (log2 domain)
-  float l_run = 0.f;                           // this lane's share of the running sum
+  for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+    for (int vb = 0; vb < VBLOCKS; ++vb) acc[hb][vb] = floatx4{0.f, 0.f, 0.f, 0.f};
+  float m_run[HB], l_run[HB];                  // running max of the scaled logits (log2 domain); this lane's share of the running sum
+#pragma unroll
+  for (int hb = 0; hb < HB; ++hb) { m_run[hb] = -__builtin_inff(); l_run[hb] = 0.f; }
 
   const int32_t* lrow = list + (size_t)bt * kk;
   const uint8_t* pbase = pool + (size_t)b * S * row_stride;
 
-  constexpr int SLOT_TILES = 16;               // tile slots are fetched 16 tiles (512 entries) at a time
-  constexpr int UPT = 512 / NTH;               // latent units (4 rows x 16 bytes) per thread and tile
-  constexpr int UCH = UPT > 2 ? 2 : UPT;       // units whose loads are in flight together
-  constexpr int RPT = 256 / NTH;               // rope pieces per thread and tile
+  // slots of every tile of this split
+  for (int j = tid; j < my_tiles * TILE; j += NTH) {
+    const int e = tile_begin * TILE + j;
+    int sl = e < n ? lrow[e] : -1;
+    if (sl >= S) sl = -1;
+    slot_cache[j] = sl;
+  }
+  __syncthreads();
 
-  for (int tile = tile_begin; tile < tile_end; ++tile) {
-    const int trel = (tile - tile_begin) % SLOT_TILES;
-    __syncthreads();                           // everyone is done with the previous tile
-    if (trel == 0) {
-      for (int j = tid; j < SLOT_TILES * TILE; j += NTH) {
-        const int e = tile * TILE + j;
-        int sl = e < n ? lrow[e] : -1;
-        if (sl >= S) sl = -1;
-        slot_cache[j] = sl;
-      }
-      __syncthreads();
-    }
-    const int32_t* tile_slot = slot_cache + trel * TILE;
-    // ---- stage.  All global loads of a chunk are issued before anything is written to LDS; rows
-    //      that are masked out load slot 0 (always valid memory) and are zeroed by a select.
-    uint4 xr[RPT];
+  Staged<FMT> st;
+  if (my_tiles > 0) {
+    stage_load<FMT>(st, slot_cache, pbase, row_stride, tid);
+    stage_store<FMT>(st, slot_cache, lds, lds + KT_BYTES, tid);
+  }
+  __syncthreads();
+
+  for (int it = 0; it < my_tiles; ++it) {
+    const uint8_t* Kt = lds + (it & 1) * BUF_BYTES;
+    const uint8_t* Vt = Kt + KT_BYTES;
+    const int32_t* tile_slot = slot_cache + it * TILE;
+    const bool more = it + 1 < my_tiles;
+    if (more) stage_load<FMT>(st, tile_slot + TILE, pbase, row_stride, tid);   // in flight during the compute
+
+    if (wave_active) {
+      // ---- S^T = K Q^T for the 32 rows of the tile, both head blocks
+      floatx4 s[HB][2];
 #pragma unroll
-    for (int i = 0; i < RPT; ++i) {            // rope part (key only)
-      const int u = tid + i * NTH;
-      const int sl = tile_slot[u >> 3];
-      xr[i] = load_piece<FMT>(pbase + (size_t)max(sl, 0) * row_stride, 64 + (u & 7));
-      if (sl < 0) xr[i] = make_uint4(0, 0, 0, 0);
-    }
+      for (int hb = 0; hb < HB; ++hb) s[hb][0] = s[hb][1] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int c0 = 0; c0 < UPT; c0 += UCH) {    // latent part: row-major copy + transposed copy
-      uint4 x[UCH][4];
+      for (int ks = 0; ks < KSTEPS; ++ks) {
+        const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(Kt + n16 * KPITCH + ks * 64 + g * 16);
+        const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(Kt + (16 + n16) * KPITCH + ks * 64 + g * 16);
 #pragma unroll
-      for (int i = 0; i < UCH; ++i) {
-        const int u = tid + (c0 + i) * NTH;
-        const int rg = u >> 6, cc = u & 63;    // row group (4 rows), 16-byte column piece
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int sl = tile_slot[rg * 4 + r];
-          x[i][r] = load_piece<FMT>(pbase + (size_t)max(sl, 0) * row_stride, cc);
-          if (sl < 0) x[i][r] = make_uint4(0, 0, 0, 0);
+        for (int hb = 0; hb < HB; ++hb) {
+          s[hb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, qb[hb][ks], s[hb][0], 0, 0, 0);
+          s[hb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, qb[hb][ks], s[hb][1], 0, 0, 0);
         }
       }
+      // lane (g,h): s[hb][0][i] = logit of row 4g+i, s[hb][1][i] = logit of row 16+4g+i
+      const int4 v0 = *reinterpret_cast<const int4*>(tile_slot + g * 4);
+      const int4 v1 = *reinterpret_cast<const int4*>(tile_slot + 16 + g * 4);
+      const bool ok[8] = {v0.x >= 0, v0.y >= 0, v0.z >= 0, v0.w >= 0, v1.x >= 0, v1.y >= 0, v1.z >= 0, v1.w >= 0};
+      bf16x8 pb[HB];
 #pragma unroll
-      for (int i = 0; i < UCH; ++i) {
-        const int u = tid + (c0 + i) * NTH;
-        const int rg = u >> 6, cc = u & 63;
+      for (int hb = 0; hb < HB; ++hb) {
+        float z[8];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) *reinterpret_cast<uint4*>(Kt + (rg * 4 + r) * KPITCH + cc * 16) = x[i][r];
-        // rows 4g'..4g'+3 sit at positions 8g'..8g'+3, rows 16+4g'.. at 8g'+4..8g'+7
-        const int gq = rg & 3, half = rg >> 2;
-        const uint32_t* xr0 = reinterpret_cast<const uint32_t*>(&x[i][0]);
-        const uint32_t* xr1 = reinterpret_cast<const uint32_t*>(&x[i][1]);
-        const uint32_t* xr2 = reinterpret_cast<const uint32_t*>(&x[i][2]);
-        const uint32_t* xr3 = reinterpret_cast<const uint32_t*>(&x[i][3]);
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-          const uint32_t a0 = xr0[p], a1 = xr1[p], a2 = xr2[p], a3 = xr3[p];
-          const uint2 even = make_uint2((a0 & 0xffffu) | (a1 << 16), (a2 & 0xffffu) | (a3 << 16));
-          const uint2 odd = make_uint2((a0 >> 16) | (a1 & 0xffff0000u), (a2 >> 16) | (a3 & 0xffff0000u));
-          const int v0 = cc * 8 + 2 * p, v1 = v0 + 1;
-          *reinterpret_cast<uint2*>(Vt + v0 * 64 + vt_granule(v0, gq) * 16 + half * 8) = even;
-          *reinterpret_cast<uint2*>(Vt + v1 * 64 + vt_granule(v1, gq) * 16 + half * 8) = odd;
+        for (int i = 0; i < 4; ++i) {
+          z[i] = ok[i] ? s[hb][0][i] * scale_log2e : -__builtin_inff();
+          z[4 + i] = ok[4 + i] ? s[hb][1][i] * scale_log2e : -__builtin_inff();
         }
+        float tmax = fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])), fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7])));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+        const float m_new = fmaxf(m_run[hb], tmax);
+        const float m_safe = (m_new == -__builtin_inff()) ? 0.f : m_new;
+        const float alpha = exp2f(m_run[hb] - m_safe);          // 0 while nothing has been seen
+        float p[8], psum = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          p[j] = exp2f(z[j] - m_safe);
+          psum += p[j];
+        }
+        l_run[hb] = l_run[hb] * alpha + psum;
+        m_run[hb] = m_new;
+        if (__any(alpha != 1.0f)) {
+#pragma unroll
+          for (int vb = 0; vb < VBLOCKS; ++vb) {
+            acc[hb][vb][0] *= alpha; acc[hb][vb][1] *= alpha; acc[hb][vb][2] *= alpha; acc[hb][vb][3] *= alpha;
+          }
+        }
+        uint4 pw = make_uint4(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7]));
+        pb[hb] = *reinterpret_cast<bf16x8*>(&pw);
       }
-    }
-#pragma unroll
-    for (int i = 0; i < RPT; ++i) {
-      const int u = tid + i * NTH;
-      *reinterpret_cast<uint4*>(Kt + (u >> 3) * KPITCH + (64 + (u & 7)) * 16) = xr[i];
-    }
-    __syncthreads();
-
-    // ---- S^T = K Q^T for the 32 rows of the tile
-    floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) {
-      const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(Kt + n16 * KPITCH + ks * 64 + g * 16);
-      const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(Kt + (16 + n16) * KPITCH + ks * 64 + g * 16);
-      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, qb[ks], s0, 0, 0, 0);
-      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, qb[ks], s1, 0, 0, 0);
-    }
-    // lane (g,h): s0[i] = logit of row 4g+i, s1[i] = logit of row 16+4g+i
-    const int4 v0 = *reinterpret_cast<const int4*>(tile_slot + g * 4);
-    const int4 v1 = *reinterpret_cast<const int4*>(tile_slot + 16 + g * 4);
-    float z[8];
-    z[0] = v0.x >= 0 ? s0[0] * scale_log2e : -__builtin_inff();
-    z[1] = v0.y >= 0 ? s0[1] * scale_log2e : -__builtin_inff();
-    z[2] = v0.z >= 0 ? s0[2] * scale_log2e : -__builtin_inff();
-    z[3] = v0.w >= 0 ? s0[3] * scale_log2e : -__builtin_inff();
-    z[4] = v1.x >= 0 ? s1[0] * scale_log2e : -__builtin_inff();
-    z[5] = v1.y >= 0 ? s1[1] * scale_log2e : -__builtin_inff();
-    z[6] = v1.z >= 0 ? s1[2] * scale_log2e : -__builtin_inff();
-    z[7] = v1.w >= 0 ? s1[3] * scale_log2e : -__builtin_inff();
-    float tmax = fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])), fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7])));
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-    const float m_new = fmaxf(m_run, tmax);
-    const float m_safe = (m_new == -__builtin_inff()) ? 0.f : m_new;
-    const float alpha = exp2f(m_run - m_safe);              // 0 while nothing has been seen
-    float p[8], psum = 0.f;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      p[j] = exp2f(z[j] - m_safe);
-      psum += p[j];
-    }
-    l_run = l_run * alpha + psum;
-    m_run = m_new;
-    if (__any(alpha != 1.0f)) {
+      // ---- O^T += V^T P^T
 #pragma unroll
       for (int vb = 0; vb < VBLOCKS; ++vb) {
-        acc[vb][0] *= alpha; acc[vb][1] *= alpha; acc[vb][2] *= alpha; acc[vb][3] *= alpha;
+        const int v = vb * 16 + n16;
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(Vt + v * 64 + vt_granule(v, g) * 16);
+#pragma unroll
+        for (int hb = 0; hb < HB; ++hb) acc[hb][vb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[hb], acc[hb][vb], 0, 0, 0);
       }
     }
-    uint4 pw = make_uint4(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7]));
-    const bf16x8 pb = *reinterpret_cast<bf16x8*>(&pw);
-    // ---- O^T += V^T P^T
-#pragma unroll
-    for (int vb = 0; vb < VBLOCKS; ++vb) {
-      const int v = vb * 16 + n16;
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(Vt + v * 64 + vt_granule(v, g) * 16);
-      acc[vb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb, acc[vb], 0, 0, 0);
+
+    if (more) {                                  // the other buffer was last read one iteration ago
+      uint8_t* Kn = lds + ((it + 1) & 1) * BUF_BYTES;
+      stage_store<FMT>(st, tile_slot + TILE, Kn, Kn + KT_BYTES, tid);
     }
+    __syncthreads();
   }
 
   // ---- finish: total sum over the four lane groups, normalise, write the partial result
-  float l_tot = l_run;
-  l_tot += __shfl_xor(l_tot, 16, 64);
-  l_tot += __shfl_xor(l_tot, 32, 64);
-  const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-  if (head < H) {
-    const size_t prow = ((size_t)bt * ESS_MAX_SPLITS + split0 + split) * H + head;
-    float* op = o_part + prow * ESS_LATENT_DIM;
 #pragma unroll
-    for (int vb = 0; vb < VBLOCKS; ++vb) {
-      const float4 o = make_float4(acc[vb][0] * inv, acc[vb][1] * inv, acc[vb][2] * inv, acc[vb][3] * inv);
-      *reinterpret_cast<float4*>(op + vb * 16 + g * 4) = o;
+  for (int hb = 0; hb < HB; ++hb) {
+    const int head = head0 + hb * 16 + n16;
+    float l_tot = l_run[hb];
+    l_tot += __shfl_xor(l_tot, 16, 64);
+    l_tot += __shfl_xor(l_tot, 32, 64);
+    const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+    if (head < H) {
+      const size_t prow = ((size_t)bt * ESS_MAX_SPLITS + split0 + split) * H + head;
+      float* op = o_part + prow * ESS_LATENT_DIM;
+#pragma unroll
+      for (int vb = 0; vb < VBLOCKS; ++vb) {
+        const float4 o = make_float4(acc[hb][vb][0] * inv, acc[hb][vb][1] * inv, acc[hb][vb][2] * inv, acc[hb][vb][3] * inv);
+        *reinterpret_cast<float4*>(op + vb * 16 + g * 4) = o;
+      }
+      if (g == 0) lse_part[prow] = l_tot > 0.f ? (m_run[hb] + log2f(l_tot)) * kLn2 : -__builtin_inff();
     }
-    if (g == 0) lse_part[prow] = l_tot > 0.f ? (m_run + log2f(l_tot)) * kLn2 : -__builtin_inff();
   }
 }
 
@@ -295,43 +370,38 @@ __global__ __launch_bounds__(256) void k_attn_merge(const float* __restrict__ o_
   if (lse_out && lane == 0) lse_out[rowi] = den > 0.f ? mx + __logf(den) : -__builtin_inff();
 }
 
-template <int NW>
-int launch_fmt(int fmt, dim3 grid, size_t lds, hipStream_t st, const uint16_t* q, const uint8_t* pool,
-               const int32_t* list, const int32_t* n_list, int T, int H, int kk, int S, int row_stride, float sc,
-               int split0, int nsplit, float* o_part, float* lse_part) {
-  if (fmt == ESS_FMT_BF16) {
-    ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_partial<NW, ESS_FMT_BF16>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    hipLaunchKernelGGL((k_attn_partial<NW, ESS_FMT_BF16>), grid, dim3(NW * 64), lds, st, q, pool, list, n_list, T, H,
-                       kk, S, row_stride, sc, split0, nsplit, o_part, lse_part);
-  } else {
-    ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_partial<NW, ESS_FMT_FP8>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    hipLaunchKernelGGL((k_attn_partial<NW, ESS_FMT_FP8>), grid, dim3(NW * 64), lds, st, q, pool, list, n_list, T, H,
-                       kk, S, row_stride, sc, split0, nsplit, o_part, lse_part);
-  }
+template <int FMT>
+int launch_fmt(dim3 grid, hipStream_t st, const uint16_t* q, const uint8_t* pool, const int32_t* list,
+               const int32_t* n_list, int T, int H, int kk, int S, int row_stride, float sc, int split0, int nsplit,
+               float* o_part, float* lse_part) {
+  ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_partial<FMT, 1>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES));
+  hipLaunchKernelGGL((k_attn_partial<FMT, 1>), grid, dim3(NTH), LDS_BYTES, st, q, pool, list, n_list, T, H, kk, S,
+                     row_stride, sc, split0, nsplit, o_part, lse_part);
   return ESS_OK;
 }
 
 }  // namespace
 
+int ess_attn_min_splits(const ess_config& c) {
+  const int tiles = (c.topk + TILE - 1) / TILE;
+  return (tiles + MAX_TPS - 1) / MAX_TPS;
+}
+
 int ess_launch_attn_partial(ess_ctx* ctx, const void* q, const uint8_t* slot_pool, const int32_t* list,
                             const int32_t* n_list, int B, int T, int split0, int nsplit, hipStream_t st) {
   const ess_config& c = ctx->cfg;
-  const int H = c.attn_heads;
-  const int hb = (H + 15) / 16;                // 16-head blocks
-  int NW = hb >= 4 ? 4 : (hb >= 2 ? 2 : 1);    // waves per workgroup
-  const int hgroups = (hb + NW - 1) / NW;
-  dim3 grid(nsplit, B * T, hgroups);
-  const size_t lds = KT_BYTES + VT_BYTES + 16 * TILE * sizeof(int32_t);
+  if (nsplit < ess_attn_min_splits(c)) return ess_fail(ESS_ERR_INVALID_ARG, "internal: too few attention splits");
+  dim3 grid(nsplit, B * T, (c.attn_heads + 63) / 64);   // 64 heads per workgroup
   const float sc = c.sm_scale * kLog2e;
   const uint16_t* qq = static_cast<const uint16_t*>(q);
   int rc;
-  switch (NW) {
-    case 1: rc = launch_fmt<1>(c.latent_fmt, grid, lds, st, qq, slot_pool, list, n_list, T, H, c.topk, c.slots_per_seq, c.row_stride, sc, split0, nsplit, ctx->o_part, ctx->lse_part); break;
-    case 2: rc = launch_fmt<2>(c.latent_fmt, grid, lds, st, qq, slot_pool, list, n_list, T, H, c.topk, c.slots_per_seq, c.row_stride, sc, split0, nsplit, ctx->o_part, ctx->lse_part); break;
-    default: rc = launch_fmt<4>(c.latent_fmt, grid, lds, st, qq, slot_pool, list, n_list, T, H, c.topk, c.slots_per_seq, c.row_stride, sc, split0, nsplit, ctx->o_part, ctx->lse_part); break;
-  }
+  if (c.latent_fmt == ESS_FMT_BF16)
+    rc = launch_fmt<ESS_FMT_BF16>(grid, st, qq, slot_pool, list, n_list, T, c.attn_heads, c.topk, c.slots_per_seq,
+                                  c.row_stride, sc, split0, nsplit, ctx->o_part, ctx->lse_part);
+  else
+    rc = launch_fmt<ESS_FMT_FP8>(grid, st, qq, slot_pool, list, n_list, T, c.attn_heads, c.topk, c.slots_per_seq,
+                                 c.row_stride, sc, split0, nsplit, ctx->o_part, ctx->lse_part);
   if (rc != ESS_OK) return rc;
   ESS_HIP(hipGetLastError());
   return ESS_OK;
