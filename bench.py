@@ -41,7 +41,7 @@ WORKLOADS = {
 }
 # HBM bytes per launch of the index-score kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (see profiles/); None until measured for that workload
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {"cfg4": 957862 * 1024}   # profiles/pmc_traffic_cfg4.md
 
 
 def build_workload(name, steps_needed):
@@ -187,6 +187,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-32k", action="store_true", help="skip the extra 32K-context measurement (cfg2)")
     ap.add_argument("--cpu-seqs", type=int, default=16)
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (known traffic) so that rocprofv3 --pmc counters can be scaled")
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the path shards by sequence with no collective); "
@@ -196,6 +198,14 @@ def main():
     from paper_2512_10576_amd import binding
     binding.load()                                   # fails loudly if the HIP library is missing
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+
+    if a.calib_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            binding.calib_copy(dst, src)             # k_calib_copy: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     W, res = measure(a.workload, a.steps, a.warmup)
     ab = res["algorithmic_bytes"]

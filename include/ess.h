@@ -189,6 +189,9 @@ int ess_reset_stats(ess_ctx* ctx, void* stream);
 #define ESS_PROFILE_STAGES 6
 int ess_profile_enable(ess_ctx* ctx, int32_t max_steps);
 int ess_profile_read(ess_ctx* ctx, float* host_ms, int32_t* n_steps);
+/* A plain device-to-device copy kernel (reads `bytes`, writes `bytes`; bytes a multiple of 16,
+ * pointers 16-byte aligned): known traffic against which hardware counters can be scaled. */
+int ess_calib_copy(void* dst, const void* src, size_t bytes, void* stream);
 
 #ifdef __cplusplus
 }

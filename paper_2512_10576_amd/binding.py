@@ -78,6 +78,7 @@ def load() -> C.CDLL:
         "ess_get_stats": [vp, C.POINTER(EssStats), vp],
         "ess_reset_stats": [vp, vp],
         "ess_profile_enable": [vp, i32],
+        "ess_calib_copy": [vp, vp, C.c_size_t, vp],
         "ess_profile_read": [vp, C.POINTER(C.c_float), C.POINTER(i32)],
     }
     for name, args in sigs.items():
@@ -129,6 +130,11 @@ def workspace_bytes(cfg: EssConfig) -> int:
     out = C.c_size_t(0)
     _check(load().ess_workspace_bytes(C.byref(cfg), C.byref(out)))
     return out.value
+
+
+def calib_copy(dst, src):
+    """plain copy kernel of known traffic (measurement support)"""
+    _check(load().ess_calib_copy(_ptr(dst, torch.uint8), _ptr(src, torch.uint8), src.numel(), _stream()))
 
 
 class Cache:

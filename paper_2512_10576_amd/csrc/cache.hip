@@ -358,6 +358,10 @@ __global__ __launch_bounds__(256) void k_gather_rows(const uint8_t* __restrict__
   }
 }
 
+__global__ __launch_bounds__(256) void k_calib_copy(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
 __global__ void k_fill_u32(uint32_t* p, int n, uint32_t value) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = value;
@@ -374,6 +378,13 @@ __global__ void k_cache_reset(int32_t* slot_of, int32_t* token_of, uint32_t* sta
 }
 
 }  // namespace
+
+int ess_launch_calib_copy(void* dst, const void* src, size_t bytes, hipStream_t st) {
+  hipLaunchKernelGGL(k_calib_copy, dim3(8192), dim3(256), 0, st, static_cast<uint4*>(dst), static_cast<const uint4*>(src),
+                     bytes / 16);
+  ESS_HIP(hipGetLastError());
+  return ESS_OK;
+}
 
 int ess_launch_fill_u32(uint32_t* p, int n, uint32_t value, hipStream_t st) {
   hipLaunchKernelGGL(k_fill_u32, dim3((n + 255) / 256), dim3(256), 0, st, p, n, value);

@@ -364,6 +364,12 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
 #undef ESS_MARK
 }
 
+int ess_calib_copy(void* dst, const void* src, size_t bytes, void* stream) {
+  if (!dst || !src || (bytes & 15) || !aligned16(dst) || !aligned16(src))
+    return ess_fail(ESS_ERR_INVALID_ARG, "calib copy needs 16-byte aligned pointers and size");
+  return ess_launch_calib_copy(dst, src, bytes, static_cast<hipStream_t>(stream));
+}
+
 int ess_profile_enable(ess_ctx* ctx, int32_t max_steps) {
   if (!ctx) return ess_fail(ESS_ERR_INVALID_ARG, "context is NULL");
   if (max_steps < 0 || max_steps > 65536) return ess_fail(ESS_ERR_INVALID_ARG, "max_steps %d", max_steps);
