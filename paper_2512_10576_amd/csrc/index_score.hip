@@ -131,24 +131,39 @@ __global__ __launch_bounds__(kWaves * 64) void k_index_score(const uint8_t* __re
     }
   };
 
-  // two register buffers: the loads of batch i+1 are in flight while batch i is computed
+  // Three register buffers: the loads of batches i+1 and i+2 are in flight while batch i is
+  // computed (16 KiB per wave for Di = 128).  Inside the loop every prefetch is unconditional, so the
+  // number of loads in flight is the same on every path (a prefetch under a branch makes the compiler
+  // wait for the newest loads before it uses the oldest); the last batches are peeled off.
   constexpr int kStride = kWaves * kBatchTokens;
-  int base = blk_base + wave * kBatchTokens;
-  if (base >= blk_end) return;
-  KeyRegs<KS> bufA[kTilesPerBatch], bufB[kTilesPerBatch];
-  load_batch(base, bufA);
-  for (;;) {
-    const bool moreB = base + kStride < blk_end;
-    if (moreB) load_batch(base + kStride, bufB);
-    compute_batch(base, bufA);
-    if (!moreB) break;
-    base += kStride;
-    const bool moreA = base + kStride < blk_end;
-    if (moreA) load_batch(base + kStride, bufA);
-    compute_batch(base, bufB);
-    if (!moreA) break;
-    base += kStride;
+  const int base0 = blk_base + wave * kBatchTokens;
+  if (base0 >= blk_end) return;
+  const int nb = (blk_end - base0 + kStride - 1) / kStride;
+  KeyRegs<KS> bufA[kTilesPerBatch], bufB[kTilesPerBatch], bufC[kTilesPerBatch];
+#define ESS_LOAD(buf, j) load_batch(base0 + (j) * kStride, buf)
+#define ESS_COMP(buf, j) compute_batch(base0 + (j) * kStride, buf)
+  ESS_LOAD(bufA, 0);
+  ESS_LOAD(bufB, min(1, nb - 1));            // invariant: A holds batch i, B batch i+1 (clamped)
+  int i = 0;
+  for (; i + 4 < nb; i += 3) {
+    ESS_LOAD(bufC, i + 2); ESS_COMP(bufA, i);
+    ESS_LOAD(bufA, i + 3); ESS_COMP(bufB, i + 1);
+    ESS_LOAD(bufB, i + 4); ESS_COMP(bufC, i + 2);
   }
+  const int r = nb - i;                      // 1..4 batches left
+  if (r == 1) {
+    ESS_COMP(bufA, i);
+  } else if (r == 2) {
+    ESS_COMP(bufA, i); ESS_COMP(bufB, i + 1);
+  } else if (r == 3) {
+    ESS_LOAD(bufC, i + 2); ESS_COMP(bufA, i); ESS_COMP(bufB, i + 1); ESS_COMP(bufC, i + 2);
+  } else {
+    ESS_LOAD(bufC, i + 2); ESS_COMP(bufA, i);
+    ESS_LOAD(bufA, i + 3); ESS_COMP(bufB, i + 1);
+    ESS_COMP(bufC, i + 2); ESS_COMP(bufA, i + 3);
+  }
+#undef ESS_LOAD
+#undef ESS_COMP
 }
 
 template <int HB, int DI>
@@ -180,8 +195,9 @@ int ess_launch_index_score(const ess_config& c, const uint8_t* q, const float* w
                            const int32_t* ctx_len, int B, int T, float* score, hipStream_t st) {
   const int Hi = c.idx_heads, Di = c.idx_dim, Lmax = c.max_ctx;
   const int HB = (Hi + 15) / 16;
-  // tokens per workgroup: a multiple of the 256 tokens the four waves cover per round
-  const int chunk = 1024;
+  // tokens per workgroup: a multiple of the 256 tokens the four waves cover per round; 2048 when
+  // that still leaves several workgroups per CU, else 1024
+  const int chunk = ((long)B * Lmax >= 2048L * 1024) ? 2048 : 1024;
   dim3 grid((Lmax + chunk - 1) / chunk, B);
   int rc;
   switch (Di) {
