@@ -1,0 +1,94 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times: the GPU result
+of sampled sequences is checked against the CPU oracle one by one, plus properties that hold for the
+whole batch.  Inputs come from bench.build_workload (seeded, synthetic)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ess_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+
+def _qbits(q):
+    return q.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def _attn_close(got_bf16, ref):
+    got = got_bf16.float().cpu().numpy().astype(np.float64)
+    err = np.abs(got - ref)
+    assert np.all(err <= 2e-2 + 2e-2 * np.abs(ref))
+    assert err.max() <= 3e-3, err.max()
+    assert np.linalg.norm(got - ref) / np.linalg.norm(ref) <= 1e-2
+
+
+def test_cfg2_full_size_sampled_sequences(ess_lib):
+    import bench
+    print("full-size cfg2 (B32, ctx 32768, resident)", flush=True)
+    W = bench.build_workload("cfg2", 0)
+    wl, ctx = W["wl"], W["ctx"]
+    B, L, k, H = wl["B"], wl["L"], wl["k"], wl["H"]
+    score = torch.empty((B, 1, L), dtype=torch.float32, device="cuda")
+    ctx.index_score(W["q_idx"], W["w"], W["key"], W["ctx_len"], score)
+    bench.run_steps(W, 1, 1)
+    torch.cuda.synchronize()
+    idx_gpu = W["idx_out"].cpu().numpy()
+    assert int(W["miss"].sum().item()) == 0
+    for b in (0, 17, 31):
+        print("  sequence", b, flush=True)
+        q_idx = W["q_idx"][b:b + 1].cpu().numpy(); w = W["w"][b:b + 1].cpu().numpy()
+        key = W["key"][b:b + 1].cpu().numpy(); cl = W["ctx_len"][b:b + 1].cpu().numpy()
+        ref_score = O.index_score(q_idx, w, key, cl)
+        assert np.array_equal(score[b].cpu().numpy(), ref_score[0])                    # bit-exact scores
+        ref_idx = O.topk(ref_score, cl, k)
+        assert np.array_equal(idx_gpu[b, 0], np.sort(ref_idx[0, 0]))                   # bit-exact selection
+        pool = W["cache"].slot_pool[b:b + 1].cpu().numpy()
+        ref_out, _ = O.sparse_mla(_qbits(W["q_attn"][b:b + 1]), pool, ref_idx, O.FMT_BF16, 576 ** -0.5)
+        _attn_close(W["out"][b:b + 1], ref_out)
+    # whole batch: every row holds k distinct ascending visible positions
+    assert np.all(np.diff(idx_gpu[:, 0, :], axis=1) > 0) and idx_gpu.min() >= 0 and idx_gpu.max() < L
+    ctx.close()
+
+
+def test_cfg4_full_size_sampled_sequences(ess_lib):
+    import bench
+    print("full-size cfg4 (B64, ctx up to 131072, offloaded, trace-driven)", flush=True)
+    steps = 3
+    W = bench.build_workload("cfg4", steps)
+    wl, ctx, cache = W["wl"], W["ctx"], W["cache"]
+    B, L, k, S = wl["B"], wl["L"], wl["k"], W["S"]
+    sample = (0, 40, 63)
+    oracles = {b: (O.SlotCache(1, L, S), np.zeros((1, S, 1152), np.uint8)) for b in sample}
+    lens = W["ctx_len"].cpu().numpy()
+    for step in range(1, steps + 1):
+        bench.run_steps(W, step, 1)
+        torch.cuda.synchronize()
+        ov = W["trace"][step - 1].cpu().numpy()
+        slot_of = cache.slot_of.cpu().numpy(); token_of = cache.token_of.cpu().numpy()
+        stamp = cache.stamp.cpu().numpy().view(np.uint32); miss = W["miss"].cpu().numpy()
+        for b in sample:
+            print("  step", step, "sequence", b, flush=True)
+            oc, opool = oracles[b]
+            host = W["host_pool"][b:b + 1].numpy()
+            r = oc.step(ov[b:b + 1], step)
+            O.fill_slots(opool, host, r["miss_tok"], r["victims"])
+            assert miss[b] == r["miss_count"][0]
+            assert np.array_equal(slot_of[b], oc.slot_of[0]) and np.array_equal(token_of[b], oc.token_of[0])
+            assert np.array_equal(stamp[b], oc.stamp[0])
+            occ = np.nonzero(oc.token_of[0] >= 0)[0]
+            gpu_rows = cache.slot_pool[b].cpu().numpy()
+            assert np.array_equal(gpu_rows[occ], opool[0, occ])                         # fetched bytes == host bytes
+            ref_out, _ = O.sparse_mla(_qbits(W["q_attn"][b:b + 1]), opool, r["slot_idx"], O.FMT_BF16, 576 ** -0.5)
+            _attn_close(W["out"][b:b + 1], ref_out)
+            if step == 1:                                                                # stages 1-2 ran on the real data
+                q_idx = W["q_idx"][b:b + 1].cpu().numpy(); w = W["w"][b:b + 1].cpu().numpy()
+                key = W["key"][b:b + 1].cpu().numpy()
+                ref_idx = O.topk(O.index_score(q_idx, w, key, lens[b:b + 1]), lens[b:b + 1], k)
+                assert np.array_equal(W["idx_out"][b, 0].cpu().numpy(), np.sort(ref_idx[0, 0]))
+        # whole batch: the selection is resident after the step; tables are mutually inverse
+        sel = torch.from_numpy(ov[:, 0, :].astype(np.int64)).cuda()
+        assert bool((torch.gather(cache.slot_of, 1, sel) >= 0).all())
+        res = cache.token_of >= 0
+        back = torch.gather(cache.slot_of, 1, cache.token_of.clamp(min=0).long())
+        assert bool((back[res] == torch.arange(S, device="cuda").expand(B, S)[res]).all())
+    ctx.close()
