@@ -44,7 +44,7 @@ WORKLOADS = {
 MEASURED_TRAFFIC_BYTES = {"cfg4": 957862 * 1024}   # profiles/pmc_traffic_cfg4.md
 
 
-def build_workload(name, steps_needed):
+def build_workload(name, steps_needed, overlap="auto"):
     import torch
     from paper_2512_10576_amd import binding as bnd, synth
     wl = dict(WORKLOADS[name]); wl.update(COMMON)
@@ -58,7 +58,10 @@ def build_workload(name, steps_needed):
     else:
         ctx_len = synth.ctx_lengths(seed, B, wl["lens"][0], wl["lens"][1], device=dev)
     S = L if wl["ratio"] is None else int(math.ceil(wl["ratio"] * L - 1e-9))
-    cfg = bnd.make_config(B, T, L, wl["Hi"], wl["Di"], k, H, slots_per_seq=S)
+    if overlap == "auto":
+        overlap = "da"
+    flags = {"da": 0, "serial": bnd.ESS_FLAG_SERIAL, "dba": bnd.ESS_FLAG_DBA}[overlap]
+    cfg = bnd.make_config(B, T, L, wl["Hi"], wl["Di"], k, H, slots_per_seq=S, flags=flags)
     ctx = bnd.Context(cfg)
     host_pool = None
     if wl["ratio"] is None:
@@ -78,7 +81,7 @@ def build_workload(name, steps_needed):
         tr = synth.TopkTrace(seed, ctx_len, T, k, wl["rho"], device=dev)
         trace = [tr.next() for _ in range(steps_needed)]
     torch.cuda.synchronize()
-    return dict(wl=wl, name=name, ctx=ctx, cfg=cfg, cache=cache, q_idx=q_idx, w=w, key=key, q_attn=q_attn,
+    return dict(wl=wl, name=name, overlap=overlap, ctx=ctx, cfg=cfg, cache=cache, q_idx=q_idx, w=w, key=key, q_attn=q_attn,
                 ctx_len=ctx_len, host_pool=host_pool, trace=trace, S=S,
                 idx_out=torch.empty((B, T, k), dtype=torch.int32, device=dev),
                 out=torch.empty((B, T, H, 512), dtype=torch.bfloat16, device=dev),
@@ -107,9 +110,9 @@ def algorithmic_bytes(W, misses_per_step):
     return dict(index_score=a1, topk=a2, attention_rows=a4, fill=fill)
 
 
-def measure(name, steps, warmup):
+def measure(name, steps, warmup, overlap="auto"):
     import torch
-    W = build_workload(name, warmup + steps)
+    W = build_workload(name, warmup + steps, overlap)
     ctx = W["ctx"]
     run_steps(W, 1, warmup)
     torch.cuda.synchronize()
@@ -184,6 +187,9 @@ def main():
     ap.add_argument("--steps", type=int, default=64)
     ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--workload", default="cfg4", choices=sorted(WORKLOADS))
+    ap.add_argument("--overlap", default="auto", choices=["auto", "da", "dba", "serial"],
+                    help="overlap of the miss fetch (paper Sec. 3.3); auto = da (DBA is built and exact, but on this GPU the\n"
+                         "fetch slows the concurrent indexer enough to cancel its gain; see DESIGN.md)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-32k", action="store_true", help="skip the extra 32K-context measurement (cfg2)")
     ap.add_argument("--cpu-seqs", type=int, default=16)
@@ -207,7 +213,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    W, res = measure(a.workload, a.steps, a.warmup)
+    W, res = measure(a.workload, a.steps, a.warmup, a.overlap)
     ab = res["algorithmic_bytes"]
     roof = dict(bound="hbm", kernel="k_index_score", achieved=res["index_score_GBs"], peak=HBM_PEAK_GBS, unit="GB/s",
                 frac=res["index_score_GBs"] / HBM_PEAK_GBS, traffic=MEASURED_TRAFFIC_BYTES.get(a.workload),
@@ -218,7 +224,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "fp8 indexer / bf16 attention",
         "data": "synthetic",
         "config": {"workload": "%s: %s" % (a.workload, W["wl"]["desc"]), "indexer": "64 heads x 128 fp8 e4m3",
-                   "topk": 2048, "attention": "128 heads x 576 bf16 absorbed MLA", "slots_per_seq": W["S"]},
+                   "topk": 2048, "attention": "128 heads x 576 bf16 absorbed MLA", "slots_per_seq": W["S"],
+                   "overlap": W["overlap"]},
         "roofline": roof,
         "stages": {k: res[k] for k in ("stage_ms", "hbm_stream_GBs", "hbm_stream_frac_of_peak", "whole_step_hbm_frac",
                                        "misses_per_step", "host_link_GBs", "host_link_frac_of_peak")},

@@ -58,6 +58,8 @@ typedef enum {
 #define ESS_FMT_FP8 1      /* entry = 512 e4m3 + 4 bf16 scales (one per 128) + 64 bf16 rope (648 bytes) */
 
 #define ESS_FLAG_SERIAL 1u /* run the miss fill on the caller's stream (no side stream, no overlap) */
+#define ESS_FLAG_DBA 2u    /* ess_decode_step: DualBatch-Attention overlap (Sec. 3.3): the batch is processed in two
+                              halves so that the second half's indexer and top-k overlap the first half's fetch */
 
 typedef struct ess_ctx ess_ctx;
 
@@ -165,7 +167,9 @@ int ess_sparse_mla_decode(ess_ctx* ctx, const void* q_bf16, const uint8_t* slot_
                           void* stream);
 
 /* One layer-step: stages 1-5 chained on `stream`, the miss fetch on the side
- * stream overlapping Attn0 (Sec. 3.3, DA overlap), Attn1 after it, merged. */
+ * stream overlapping Attn0 (Sec. 3.3, DA overlap), Attn1 after it, merged.  With
+ * ESS_FLAG_DBA the fetch of the first half of the batch also overlaps the second
+ * half's indexer and top-k (DBA overlap); results are identical in all modes. */
 int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* args, void* stream);
 
 /* Counters accumulated by ess_gather_latent / ess_cache_admit / ess_decode_step

@@ -20,6 +20,7 @@ ESS_OK = 0
 ESS_ERR_INVALID_ARG, ESS_ERR_UNSUPPORTED, ESS_ERR_CAPACITY, ESS_ERR_NOMEM, ESS_ERR_HIP = -1, -2, -3, -4, -5
 ESS_FMT_BF16, ESS_FMT_FP8 = 0, 1
 ESS_FLAG_SERIAL = 1
+ESS_FLAG_DBA = 2
 
 
 class EssConfig(C.Structure):

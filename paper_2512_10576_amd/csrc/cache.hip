@@ -90,7 +90,7 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
     int32_t* __restrict__ hit_list, int32_t* __restrict__ miss_list, int32_t* __restrict__ n_hit,
     int32_t* __restrict__ n_miss, int32_t* __restrict__ fill_tok, int32_t* __restrict__ fill_slot, int fill_cap,
     int32_t* __restrict__ miss_cnt, int32_t* __restrict__ miss_count_out, unsigned long long* __restrict__ stats,
-    int row_stride) {
+    int row_stride, int count_step) {
   extern __shared__ uint32_t bm[];             // [W] bitmap of the missed positions
   __shared__ BookShared sm;
   constexpr int RS = 16;                       // register-held stamps per thread
@@ -231,7 +231,7 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
   if (tid == 0) {
     miss_cnt[b] = (int32_t)m;
     if (miss_count_out) miss_count_out[b] = (int32_t)m;
-    if (b == 0) atomicAdd(&stats[0], 1ull);
+    if (b == 0 && count_step) atomicAdd(&stats[0], 1ull);
     atomicAdd(&stats[1], (unsigned long long)nvalid);
     atomicAdd(&stats[2], (unsigned long long)m);
     atomicAdd(&stats[3], (unsigned long long)m * (unsigned long long)row_stride);
@@ -401,28 +401,32 @@ int ess_launch_cache_reset(const ess_config& c, const ess_cache& cache, int B, h
 }
 
 int ess_launch_bookkeeping(ess_ctx* ctx, const ess_cache& cache, const int32_t* idx, int B, int T, int kk,
-                           uint32_t step, int32_t* slot_idx, int32_t* miss_count_out, hipStream_t st) {
+                           uint32_t step, int32_t* slot_idx, int32_t* miss_count_out, hipStream_t st, int b0,
+                           bool count_step) {
   const ess_config& c = ctx->cfg;
   const size_t lds = (size_t)((c.max_ctx + 31) / 32) * sizeof(uint32_t);
   const bool lists = (kk == c.topk);           // compacted lists have the pitch of the top-k
+  const int cap = c.max_q_tokens * c.topk;
+  const size_t lo = (size_t)b0 * T * c.topk;   // offset of this sub-batch in the per-(b,t) lists
   const bool reg = c.slots_per_seq <= BT * 16;
   auto kern = reg ? &k_bookkeeping<true> : &k_bookkeeping<false>;
   ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   hipLaunchKernelGGL(kern, dim3(B), dim3(BT), lds, st, idx, T, kk, c.max_ctx, c.slots_per_seq,
                      cache.slot_of, cache.token_of, cache.stamp, step, slot_idx,
-                     lists ? ctx->hit_list : nullptr, lists ? ctx->miss_list : nullptr, ctx->n_hit, ctx->n_miss,
-                     ctx->fill_tok, ctx->fill_slot, c.max_q_tokens * c.topk, ctx->miss_cnt, miss_count_out,
-                     ctx->stats, c.row_stride);
+                     lists ? ctx->hit_list + lo : nullptr, lists ? ctx->miss_list + lo : nullptr,
+                     ctx->n_hit + (size_t)b0 * T, ctx->n_miss + (size_t)b0 * T, ctx->fill_tok + (size_t)b0 * cap,
+                     ctx->fill_slot + (size_t)b0 * cap, cap, ctx->miss_cnt + b0, miss_count_out, ctx->stats,
+                     c.row_stride, count_step ? 1 : 0);
   ESS_HIP(hipGetLastError());
   return ESS_OK;
 }
 
-int ess_launch_fill(ess_ctx* ctx, const ess_cache& cache, int B, int per_seq_cap, hipStream_t st) {
+int ess_launch_fill(ess_ctx* ctx, const ess_cache& cache, int B, hipStream_t st, int b0) {
   const ess_config& c = ctx->cfg;
-  (void)per_seq_cap;
-  hipLaunchKernelGGL(k_fill, dim3(FILL_WGS), dim3(FILL_WPB * 64), 0, st, cache.host_pool_dev, cache.slot_pool, ctx->fill_tok,
-                     ctx->fill_slot, c.max_q_tokens * c.topk, ctx->miss_cnt, B, c.max_ctx, c.slots_per_seq,
-                     c.row_stride);
+  const int cap = c.max_q_tokens * c.topk;
+  hipLaunchKernelGGL(k_fill, dim3(FILL_WGS), dim3(FILL_WPB * 64), 0, st, cache.host_pool_dev, cache.slot_pool,
+                     ctx->fill_tok + (size_t)b0 * cap, ctx->fill_slot + (size_t)b0 * cap, cap, ctx->miss_cnt + b0, B,
+                     c.max_ctx, c.slots_per_seq, c.row_stride);
   ESS_HIP(hipGetLastError());
   return ESS_OK;
 }

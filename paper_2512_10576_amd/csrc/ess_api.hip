@@ -112,29 +112,41 @@ int pick_splits(const ess_config& c, int B, int T, int cap) {
   return want < 1 ? 1 : want;
 }
 
-// bookkeeping + fetch, with the fetch on the side stream unless serial.  After return, work
-// enqueued on `st` is ordered after the bookkeeping; *fill_pending tells whether ev_fill must
-// still be waited for before the fetched rows are read.
+// A view of the caller's cache arrays starting at sequence b0.
+ess_cache shift_cache(const ess_config& c, const ess_cache& in, int b0) {
+  ess_cache o = in;
+  o.slot_pool = in.slot_pool + (size_t)b0 * c.slots_per_seq * c.row_stride;
+  if (in.host_pool_dev) o.host_pool_dev = in.host_pool_dev + (size_t)b0 * c.max_ctx * c.row_stride;
+  o.slot_of = in.slot_of + (size_t)b0 * c.max_ctx;
+  o.token_of = in.token_of + (size_t)b0 * c.slots_per_seq;
+  o.stamp = in.stamp + (size_t)b0 * c.slots_per_seq;
+  return o;
+}
+
+// Bookkeeping + fetch of the sub-batch [b0, b0+B) (`cache`, `idx`, `slot_idx`, `miss_count` already
+// point at sequence b0), the fetch on the side stream unless serial, tracked by event pair `half`.
+// After return, work enqueued on `st` is ordered after the bookkeeping; *fill_pending tells whether
+// ev_fill[half] must still be waited for before the fetched rows are read.
 int run_cache_step(ess_ctx* ctx, const ess_cache& cache, const int32_t* idx, int B, int T, int kk, uint32_t step,
-                   int32_t* slot_idx, int32_t* miss_count, hipStream_t st, bool* fill_pending,
-                   hipEvent_t* fill_ev = nullptr) {
+                   int32_t* slot_idx, int32_t* miss_count, hipStream_t st, bool* fill_pending, int b0 = 0,
+                   int half = 0, hipEvent_t* fill_ev = nullptr) {
   *fill_pending = false;
-  int rc = ess_launch_bookkeeping(ctx, cache, idx, B, T, kk, step, slot_idx, miss_count, st);
+  int rc = ess_launch_bookkeeping(ctx, cache, idx, B, T, kk, step, slot_idx, miss_count, st, b0, half == 0);
   if (rc != ESS_OK) return rc;
   if (!cache.host_pool_dev) return ESS_OK;      // nothing offloaded: no entry can be missing
   if (ctx->cfg.flags & ESS_FLAG_SERIAL) {
     if (fill_ev) ESS_HIP(hipEventRecord(fill_ev[0], st));
-    rc = ess_launch_fill(ctx, cache, B, T * kk, st);
+    rc = ess_launch_fill(ctx, cache, B, st, b0);
     if (rc == ESS_OK && fill_ev) ESS_HIP(hipEventRecord(fill_ev[1], st));
     return rc;
   }
-  ESS_HIP(hipEventRecord(ctx->ev_book, st));
-  ESS_HIP(hipStreamWaitEvent(ctx->side, ctx->ev_book, 0));
+  ESS_HIP(hipEventRecord(ctx->ev_book[half], st));
+  ESS_HIP(hipStreamWaitEvent(ctx->side, ctx->ev_book[half], 0));
   if (fill_ev) ESS_HIP(hipEventRecord(fill_ev[0], ctx->side));
-  rc = ess_launch_fill(ctx, cache, B, T * kk, ctx->side);
+  rc = ess_launch_fill(ctx, cache, B, ctx->side, b0);
   if (rc != ESS_OK) return rc;
   if (fill_ev) ESS_HIP(hipEventRecord(fill_ev[1], ctx->side));
-  ESS_HIP(hipEventRecord(ctx->ev_fill, ctx->side));
+  ESS_HIP(hipEventRecord(ctx->ev_fill[half], ctx->side));
   *fill_pending = true;
   return ESS_OK;
 }
@@ -194,16 +206,20 @@ int ess_create(const ess_config* cfg, ess_ctx** out) {
   ctx->lse_part = reinterpret_cast<float*>(base + w.lse_part);
   ctx->stats = reinterpret_cast<unsigned long long*>(base + w.stats);
   auto bail = [&](const char* what, hipError_t err) {
-    if (ctx->ev_book) (void)hipEventDestroy(ctx->ev_book);
-    if (ctx->ev_fill) (void)hipEventDestroy(ctx->ev_fill);
+    for (int h = 0; h < 2; ++h) {
+      if (ctx->ev_book[h]) (void)hipEventDestroy(ctx->ev_book[h]);
+      if (ctx->ev_fill[h]) (void)hipEventDestroy(ctx->ev_fill[h]);
+    }
     if (ctx->side) (void)hipStreamDestroy(ctx->side);
     (void)hipFree(base);
     delete ctx;
     return ess_fail(ESS_ERR_HIP, "%s: %s", what, hipGetErrorString(err));
   };
   if ((e = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking)) != hipSuccess) return bail("hipStreamCreate", e);
-  if ((e = hipEventCreateWithFlags(&ctx->ev_book, hipEventDisableTiming)) != hipSuccess) return bail("hipEventCreate", e);
-  if ((e = hipEventCreateWithFlags(&ctx->ev_fill, hipEventDisableTiming)) != hipSuccess) return bail("hipEventCreate", e);
+  for (int h = 0; h < 2; ++h) {
+    if ((e = hipEventCreateWithFlags(&ctx->ev_book[h], hipEventDisableTiming)) != hipSuccess) return bail("hipEventCreate", e);
+    if ((e = hipEventCreateWithFlags(&ctx->ev_fill[h], hipEventDisableTiming)) != hipSuccess) return bail("hipEventCreate", e);
+  }
   if ((e = hipMemset(ctx->stats, 0, 32)) != hipSuccess) return bail("hipMemset", e);
   *out = ctx;
   return ESS_OK;
@@ -213,8 +229,10 @@ int ess_destroy(ess_ctx* ctx) {
   if (!ctx) return ESS_OK;
   (void)hipStreamSynchronize(ctx->side);
   (void)ess_profile_enable(ctx, 0);
-  (void)hipEventDestroy(ctx->ev_book);
-  (void)hipEventDestroy(ctx->ev_fill);
+  for (int h = 0; h < 2; ++h) {
+    (void)hipEventDestroy(ctx->ev_book[h]);
+    (void)hipEventDestroy(ctx->ev_fill[h]);
+  }
   (void)hipStreamDestroy(ctx->side);
   (void)hipFree(ctx->score_ws);                 // base of the workspace
   delete ctx;
@@ -243,7 +261,7 @@ int ess_cache_admit(ess_ctx* ctx, const ess_cache* cache, const int32_t* tok, in
   // one list of n entries per sequence, no per-query outputs
   rc = run_cache_step(ctx, *cache, tok, B, 1, n, step, nullptr, nullptr, st, &pending);
   if (rc != ESS_OK) return rc;
-  if (pending) ESS_HIP(hipStreamWaitEvent(st, ctx->ev_fill, 0));
+  if (pending) ESS_HIP(hipStreamWaitEvent(st, ctx->ev_fill[0], 0));
   return ESS_OK;
 }
 
@@ -279,7 +297,7 @@ int ess_gather_latent(ess_ctx* ctx, const ess_cache* cache, const int32_t* idx, 
   bool pending = false;
   rc = run_cache_step(ctx, *cache, idx, B, T, ctx->cfg.topk, step, slot_idx, miss_count, st, &pending);
   if (rc != ESS_OK) return rc;
-  if (pending) ESS_HIP(hipStreamWaitEvent(st, ctx->ev_fill, 0));
+  if (pending) ESS_HIP(hipStreamWaitEvent(st, ctx->ev_fill[0], 0));
   if (rows_out) return ess_launch_gather_rows(ctx->cfg, cache->slot_pool, slot_idx, B, T, rows_out, st);
   return ESS_OK;
 }
@@ -312,54 +330,108 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
   const ess_config& c = ctx->cfg;
   const int B = a->B, T = a->T;
 
-  hipEvent_t* pev = nullptr;                    // stage marks of this step, when profiling
-  if (ctx->prof_ev && ctx->prof_n < ctx->prof_cap) pev = ctx->prof_ev + (size_t)(ctx->prof_n++) * ESS_PROF_EVENTS;
-#define ESS_MARK(i) do { if (pev) ESS_HIP(hipEventRecord(pev[i], st)); } while (0)
-  ESS_MARK(0);
-  // stages 1-2
-  rc = ess_launch_index_score(c, a->q_idx_fp8, a->w, a->key_fp8, a->ctx_len, B, T, ctx->score_ws, st);
-  if (rc != ESS_OK) return rc;
-  ESS_MARK(1);
-  rc = ess_launch_topk(c, ctx->score_ws, a->ctx_len, B, T, a->idx_out, st);
-  if (rc != ESS_OK) return rc;
-  ESS_MARK(2);
-  const int32_t* used = a->topk_override ? a->topk_override : a->idx_out;
+  // stage marks of this step, when profiling: a mark closes the interval since the previous mark and
+  // books it under `tag` (0 index score, 1 top-k, 2 bookkeeping, 3 Attn0, 4 Attn1 + merge)
+  hipEvent_t* pev = nullptr;
+  int8_t* ptag = nullptr;
+  int pslot = -1, nmark = 0;
+  if (ctx->prof_ev && ctx->prof_n < ctx->prof_cap) {
+    pslot = ctx->prof_n++;
+    pev = ctx->prof_ev + (size_t)pslot * ESS_PROF_EVENTS;
+    ptag = ctx->prof_tag + (size_t)pslot * ESS_PROF_MAIN;
+    ctx->prof_nmark[pslot] = 0;
+    ctx->prof_nfill[pslot] = 0;
+  }
+#define ESS_MARK(tag)                                          \
+  do {                                                         \
+    if (pev && nmark < ESS_PROF_MAIN) {                        \
+      ESS_HIP(hipEventRecord(pev[nmark], st));                 \
+      ptag[nmark] = (int8_t)(tag);                             \
+      ctx->prof_nmark[pslot] = ++nmark;                        \
+    }                                                          \
+  } while (0)
+  ESS_MARK(-1);
 
-  if (!cache->host_pool_dev) {
+  const bool offloaded = cache->host_pool_dev != nullptr;
+  // DualBatch-Attention overlap (Sec. 3.3): the batch is cut in two halves so that the second half's
+  // indexer and top-k run while the first half's fetch is in flight
+  const bool dba = offloaded && (c.flags & ESS_FLAG_DBA) && !(c.flags & ESS_FLAG_SERIAL) && B >= 2;
+  const int nh = dba ? 2 : 1;
+  const int hb0[2] = {0, B / 2};
+  const int hB[2] = {dba ? B / 2 : B, B - B / 2};
+  const size_t k = (size_t)c.topk;
+  bool pending[2] = {false, false};
+
+  // attention splits: the same for both halves, one merge over the whole batch at the end
+  const int ns0 = pick_splits(c, B, T, 16);    // from the whole batch, so that every mode sums in the same order
+  int ns1 = 0;
+  if (offloaded) {
+    ns1 = ns0 / 4;
+    if (ns1 < ess_attn_min_splits(c)) ns1 = ess_attn_min_splits(c);
+    if (ns1 < 1) ns1 = 1;
+    if (ns1 > ESS_MAX_SPLITS - 16) ns1 = ESS_MAX_SPLITS - 16;
+  }
+
+  // stages 1-2 (+ 3, 5 when offloaded) per half; the fetch goes to the side stream
+  for (int h = 0; h < nh; ++h) {
+    const int b0 = hb0[h], Bh = hB[h];
+    const size_t bt0 = (size_t)b0 * T;
+    float* sc = ctx->score_ws + bt0 * c.max_ctx;
+    int32_t* idx_h = a->idx_out + bt0 * k;
+    rc = ess_launch_index_score(c, a->q_idx_fp8 + bt0 * c.idx_heads * c.idx_dim, a->w + bt0 * c.idx_heads,
+                                a->key_fp8 + (size_t)b0 * c.max_ctx * c.idx_dim, a->ctx_len + b0, Bh, T, sc, st);
+    if (rc != ESS_OK) return rc;
+    ESS_MARK(0);
+    rc = ess_launch_topk(c, sc, a->ctx_len + b0, Bh, T, idx_h, st);
+    if (rc != ESS_OK) return rc;
+    ESS_MARK(1);
+    if (!offloaded) continue;
+    const int32_t* used = a->topk_override ? a->topk_override + bt0 * k : idx_h;
+    const ess_cache ch = shift_cache(c, *cache, b0);
+    hipEvent_t* fev = (pev && h < ESS_PROF_FILL) ? pev + ESS_PROF_MAIN + 2 * h : nullptr;
+    rc = run_cache_step(ctx, ch, used, Bh, T, c.topk, a->step, ctx->slot_idx_ws + bt0 * k,
+                        a->miss_count ? a->miss_count + b0 : nullptr, st, &pending[h], b0, h, fev);
+    if (rc != ESS_OK) return rc;
+    if (fev) ctx->prof_nfill[pslot] = h + 1;
+    ESS_MARK(2);
+  }
+
+  if (!offloaded) {
     // nothing offloaded: slot == position, attention straight over the selection
-    const int ns = pick_splits(c, B, T, 16);
+    const int32_t* used = a->topk_override ? a->topk_override : a->idx_out;
+    rc = ess_launch_attn_partial(ctx, a->q_bf16, cache->slot_pool, used, nullptr, B, T, 0, ns0, st);
+    if (rc != ESS_OK) return rc;
     ESS_MARK(3);
-    rc = ess_launch_attn_partial(ctx, a->q_bf16, cache->slot_pool, used, nullptr, B, T, 0, ns, st);
+    if (a->miss_count && (rc = ess_launch_fill_u32(reinterpret_cast<uint32_t*>(a->miss_count), B, 0u, st)) != ESS_OK) return rc;
+    rc = ess_launch_attn_merge(ctx, B, T, ns0, a->out_bf16, a->lse, st);
     if (rc != ESS_OK) return rc;
     ESS_MARK(4);
-    if (a->miss_count && (rc = ess_launch_fill_u32(reinterpret_cast<uint32_t*>(a->miss_count), B, 0u, st)) != ESS_OK) return rc;
-    rc = ess_launch_attn_merge(ctx, B, T, ns, a->out_bf16, a->lse, st);
-    if (rc != ESS_OK) return rc;
-    ESS_MARK(5);
     return ESS_OK;
   }
 
-  // stages 3 + 5, fetch on the side stream
-  bool pending = false;
-  rc = run_cache_step(ctx, *cache, used, B, T, c.topk, a->step, ctx->slot_idx_ws, a->miss_count, st, &pending,
-                      pev ? pev + 6 : nullptr);
-  if (rc != ESS_OK) return rc;
+  // stage 4: Attn0 over resident entries while the fetches run, Attn1 over fetched ones, merge
+  const uint16_t* q16 = static_cast<const uint16_t*>(a->q_bf16);
+  for (int h = 0; h < nh; ++h) {
+    const int b0 = hb0[h], Bh = hB[h];
+    const size_t bt0 = (size_t)b0 * T;
+    const ess_cache ch = shift_cache(c, *cache, b0);
+    rc = ess_launch_attn_partial(ctx, q16 + bt0 * c.attn_heads * ESS_ROW_DIM, ch.slot_pool, ctx->hit_list + bt0 * k,
+                                 ctx->n_hit + bt0, Bh, T, 0, ns0, st, b0);
+    if (rc != ESS_OK) return rc;
+  }
   ESS_MARK(3);
-  // stage 4: Attn0 over resident entries while the fetch runs, Attn1 over fetched ones, merge
-  const int ns0 = pick_splits(c, B, T, 16);
-  int ns1 = ns0 / 4;
-  if (ns1 < ess_attn_min_splits(c)) ns1 = ess_attn_min_splits(c);
-  if (ns1 < 1) ns1 = 1;
-  if (ns1 > ESS_MAX_SPLITS - 16) ns1 = ESS_MAX_SPLITS - 16;
-  rc = ess_launch_attn_partial(ctx, a->q_bf16, cache->slot_pool, ctx->hit_list, ctx->n_hit, B, T, 0, ns0, st);
-  if (rc != ESS_OK) return rc;
-  ESS_MARK(4);
-  if (pending) ESS_HIP(hipStreamWaitEvent(st, ctx->ev_fill, 0));
-  rc = ess_launch_attn_partial(ctx, a->q_bf16, cache->slot_pool, ctx->miss_list, ctx->n_miss, B, T, ns0, ns1, st);
-  if (rc != ESS_OK) return rc;
+  for (int h = 0; h < nh; ++h) {
+    const int b0 = hb0[h], Bh = hB[h];
+    const size_t bt0 = (size_t)b0 * T;
+    const ess_cache ch = shift_cache(c, *cache, b0);
+    if (pending[h]) ESS_HIP(hipStreamWaitEvent(st, ctx->ev_fill[h], 0));
+    rc = ess_launch_attn_partial(ctx, q16 + bt0 * c.attn_heads * ESS_ROW_DIM, ch.slot_pool, ctx->miss_list + bt0 * k,
+                                 ctx->n_miss + bt0, Bh, T, ns0, ns1, st, b0);
+    if (rc != ESS_OK) return rc;
+  }
   rc = ess_launch_attn_merge(ctx, B, T, ns0 + ns1, a->out_bf16, a->lse, st);
   if (rc != ESS_OK) return rc;
-  ESS_MARK(5);
+  ESS_MARK(4);
   return ESS_OK;
 #undef ESS_MARK
 }
@@ -376,18 +448,28 @@ int ess_profile_enable(ess_ctx* ctx, int32_t max_steps) {
   if (ctx->prof_ev) {
     for (int i = 0; i < ctx->prof_cap * ESS_PROF_EVENTS; ++i) (void)hipEventDestroy(ctx->prof_ev[i]);
     delete[] ctx->prof_ev;
+    delete[] ctx->prof_tag;
+    delete[] ctx->prof_nmark;
+    delete[] ctx->prof_nfill;
     ctx->prof_ev = nullptr;
   }
   ctx->prof_cap = ctx->prof_n = 0;
   if (max_steps == 0) return ESS_OK;
   const int n = max_steps * ESS_PROF_EVENTS;
   ctx->prof_ev = new (std::nothrow) hipEvent_t[n];
-  if (!ctx->prof_ev) return ess_fail(ESS_ERR_NOMEM, "host allocation failed");
+  ctx->prof_tag = new (std::nothrow) int8_t[(size_t)max_steps * ESS_PROF_MAIN];
+  ctx->prof_nmark = new (std::nothrow) int[max_steps]();
+  ctx->prof_nfill = new (std::nothrow) int[max_steps]();
+  if (!ctx->prof_ev || !ctx->prof_tag || !ctx->prof_nmark || !ctx->prof_nfill) {
+    delete[] ctx->prof_ev; delete[] ctx->prof_tag; delete[] ctx->prof_nmark; delete[] ctx->prof_nfill;
+    ctx->prof_ev = nullptr;
+    return ess_fail(ESS_ERR_NOMEM, "host allocation failed");
+  }
   for (int i = 0; i < n; ++i) {
     hipError_t e = hipEventCreate(&ctx->prof_ev[i]);
     if (e != hipSuccess) {
       for (int j = 0; j < i; ++j) (void)hipEventDestroy(ctx->prof_ev[j]);
-      delete[] ctx->prof_ev;
+      delete[] ctx->prof_ev; delete[] ctx->prof_tag; delete[] ctx->prof_nmark; delete[] ctx->prof_nfill;
       ctx->prof_ev = nullptr;
       return ess_fail(ESS_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(e));
     }
@@ -401,12 +483,21 @@ int ess_profile_read(ess_ctx* ctx, float* host_ms, int32_t* n_steps) {
   *n_steps = ctx->prof_n;
   for (int s = 0; s < ctx->prof_n; ++s) {
     hipEvent_t* ev = ctx->prof_ev + (size_t)s * ESS_PROF_EVENTS;
-    ESS_HIP(hipEventSynchronize(ev[5]));
-    for (int i = 0; i < 5; ++i) ESS_HIP(hipEventElapsedTime(&host_ms[s * ESS_PROFILE_STAGES + i], ev[i], ev[i + 1]));
-    host_ms[s * ESS_PROFILE_STAGES + 5] = 0.f;
-    if (hipEventQuery(ev[7]) == hipSuccess && hipEventElapsedTime(&host_ms[s * ESS_PROFILE_STAGES + 5], ev[6], ev[7]) != hipSuccess) {
-      host_ms[s * ESS_PROFILE_STAGES + 5] = 0.f;
-      (void)hipGetLastError();
+    const int8_t* tag = ctx->prof_tag + (size_t)s * ESS_PROF_MAIN;
+    float* out = host_ms + (size_t)s * ESS_PROFILE_STAGES;
+    for (int i = 0; i < ESS_PROFILE_STAGES; ++i) out[i] = 0.f;
+    const int nm = ctx->prof_nmark[s];
+    if (nm > 0) ESS_HIP(hipEventSynchronize(ev[nm - 1]));
+    for (int m = 1; m < nm; ++m) {
+      float ms = 0.f;
+      ESS_HIP(hipEventElapsedTime(&ms, ev[m - 1], ev[m]));
+      if (tag[m] >= 0 && tag[m] < 5) out[tag[m]] += ms;
+    }
+    for (int f = 0; f < ctx->prof_nfill[s]; ++f) {
+      float ms = 0.f;
+      ESS_HIP(hipEventSynchronize(ev[ESS_PROF_MAIN + 2 * f + 1]));
+      ESS_HIP(hipEventElapsedTime(&ms, ev[ESS_PROF_MAIN + 2 * f], ev[ESS_PROF_MAIN + 2 * f + 1]));
+      out[5] += ms;
     }
   }
   ctx->prof_n = 0;

@@ -10,13 +10,15 @@
 #define ESS_ATTN_TILE 32        // entries per attention tile
 #define ESS_MAX_SPLITS 20       // partial results per (b,t): Attn0 splits + Attn1 splits
 #define ESS_ROW_DIM 576
-#define ESS_PROF_EVENTS 8
+#define ESS_PROF_MAIN 16        // stage marks on the caller's stream per step
+#define ESS_PROF_FILL 2         // fetch kernels per step (one per batch half)
+#define ESS_PROF_EVENTS (ESS_PROF_MAIN + 2 * ESS_PROF_FILL)
 
 struct ess_ctx {
   ess_config cfg;
   int device;
   hipStream_t side;             // miss fetch stream (default priority)
-  hipEvent_t ev_book, ev_fill;  // bookkeeping done / fetch done
+  hipEvent_t ev_book[2], ev_fill[2];  // bookkeeping done / fetch done, per batch half
   // workspace (device)
   float* score_ws;              // [B,T,Lmax]
   int32_t* slot_idx_ws;         // [B,T,k]
@@ -32,7 +34,10 @@ struct ess_ctx {
   unsigned long long* stats;    // [4]
   size_t ws_bytes;
   // optional stage timing (ess_profile_enable)
-  hipEvent_t* prof_ev;          // [prof_cap][ESS_PROF_EVENTS]: 6 marks on the caller's stream, 2 around the fetch
+  hipEvent_t* prof_ev;          // [prof_cap][ESS_PROF_EVENTS]: marks on the caller's stream, then pairs around each fetch
+  int8_t* prof_tag;             // [prof_cap][ESS_PROF_MAIN] stage a mark closes (-1 = start)
+  int* prof_nmark;              // [prof_cap] marks recorded
+  int* prof_nfill;              // [prof_cap] fetch pairs recorded
   int prof_cap, prof_n;
 };
 
@@ -56,15 +61,18 @@ int ess_launch_calib_copy(void* dst, const void* src, size_t bytes, hipStream_t 
 int ess_launch_fill_u32(uint32_t* p, int n, uint32_t value, hipStream_t st);
 int ess_launch_cache_reset(const ess_config& c, const ess_cache& cache, int B, hipStream_t st);
 // look-up + LRU update + lists; n_sel = entries per sequence in idx ([B,n_sel], T lists of n_sel/T)
+// b0 = first sequence of the (sub-)batch: caller-owned pointers are passed already shifted, the
+// library's workspace arrays are shifted inside
 int ess_launch_bookkeeping(ess_ctx* ctx, const ess_cache& cache, const int32_t* idx, int B, int T, int kk,
-                           uint32_t step, int32_t* slot_idx, int32_t* miss_count_out, hipStream_t st);
-int ess_launch_fill(ess_ctx* ctx, const ess_cache& cache, int B, int per_seq_cap, hipStream_t st);
+                           uint32_t step, int32_t* slot_idx, int32_t* miss_count_out, hipStream_t st, int b0 = 0,
+                           bool count_step = true);
+int ess_launch_fill(ess_ctx* ctx, const ess_cache& cache, int B, hipStream_t st, int b0 = 0);
 int ess_launch_gather_rows(const ess_config& c, const uint8_t* slot_pool, const int32_t* slot_idx, int B, int T,
                            uint8_t* rows_out, hipStream_t st);
 // attention over list[b,t,0..n) (n = n_list[b,t], or k when n_list is NULL), written as `nsplit`
 // partial results starting at partial index `split0`
 int ess_launch_attn_partial(ess_ctx* ctx, const void* q, const uint8_t* slot_pool, const int32_t* list,
-                            const int32_t* n_list, int B, int T, int split0, int nsplit, hipStream_t st);
+                            const int32_t* n_list, int B, int T, int split0, int nsplit, hipStream_t st, int b0 = 0);
 int ess_attn_min_splits(const ess_config& c);   // fewest splits a list of k entries may be cut into
 int ess_launch_attn_merge(ess_ctx* ctx, int B, int T, int nsplit_total, void* out_bf16, float* lse,
                           hipStream_t st);

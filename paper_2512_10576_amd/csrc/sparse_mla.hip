@@ -389,19 +389,22 @@ int ess_attn_min_splits(const ess_config& c) {
 }
 
 int ess_launch_attn_partial(ess_ctx* ctx, const void* q, const uint8_t* slot_pool, const int32_t* list,
-                            const int32_t* n_list, int B, int T, int split0, int nsplit, hipStream_t st) {
+                            const int32_t* n_list, int B, int T, int split0, int nsplit, hipStream_t st, int b0) {
   const ess_config& c = ctx->cfg;
   if (nsplit < ess_attn_min_splits(c)) return ess_fail(ESS_ERR_INVALID_ARG, "internal: too few attention splits");
   dim3 grid(nsplit, B * T, (c.attn_heads + 63) / 64);   // 64 heads per workgroup
   const float sc = c.sm_scale * kLog2e;
   const uint16_t* qq = static_cast<const uint16_t*>(q);
+  // partial results of sequence b0 onward
+  float* op = ctx->o_part + (size_t)b0 * T * ESS_MAX_SPLITS * c.attn_heads * ESS_LATENT_DIM;
+  float* lp = ctx->lse_part + (size_t)b0 * T * ESS_MAX_SPLITS * c.attn_heads;
   int rc;
   if (c.latent_fmt == ESS_FMT_BF16)
     rc = launch_fmt<ESS_FMT_BF16>(grid, st, qq, slot_pool, list, n_list, T, c.attn_heads, c.topk, c.slots_per_seq,
-                                  c.row_stride, sc, split0, nsplit, ctx->o_part, ctx->lse_part);
+                                  c.row_stride, sc, split0, nsplit, op, lp);
   else
     rc = launch_fmt<ESS_FMT_FP8>(grid, st, qq, slot_pool, list, n_list, T, c.attn_heads, c.topk, c.slots_per_seq,
-                                 c.row_stride, sc, split0, nsplit, ctx->o_part, ctx->lse_part);
+                                 c.row_stride, sc, split0, nsplit, op, lp);
   if (rc != ESS_OK) return rc;
   ESS_HIP(hipGetLastError());
   return ESS_OK;

@@ -243,13 +243,13 @@ def test_sparse_mla_decode_vs_oracle(ess_lib, name, B, T, H, L, k, fmt, scale):
 
 
 # ---------------------------------------------------------------- whole step
-@pytest.mark.parametrize("flags", [0, 1])
+@pytest.mark.parametrize("flags", [0, 1, 2])
 def test_decode_step_offloaded_vs_oracle(ess_lib, flags):
     from paper_2512_10576_amd import binding as bnd
     print("decode_step offload flags", flags, flush=True)
-    B, T, Hi, Di, L, k, H, S = 2, 2, 64, 128, 6000, 512, 128, 1500
+    B, T, Hi, Di, L, k, H, S = 3, 2, 64, 128, 6000, 512, 128, 1500
     qi, w, key = synth.indexer_inputs(41, B, T, Hi, Di, L, 8, 8, 16)
-    ctx_len = torch.tensor([6000, 4321], dtype=torch.int32)
+    ctx_len = torch.tensor([6000, 4321, 5555], dtype=torch.int32)
     host = synth.latent_rows_bf16(41, B * L).reshape(B, L, 1152)
     hp = torch.empty((B, L, 1152), dtype=torch.uint8, pin_memory=True)
     hp.copy_(host)
@@ -285,9 +285,10 @@ def test_decode_step_offloaded_vs_oracle(ess_lib, flags):
     test_decode_step_offloaded_vs_oracle.results = getattr(test_decode_step_offloaded_vs_oracle, "results", {})
     test_decode_step_offloaded_vs_oracle.results[flags] = outs
     res = test_decode_step_offloaded_vs_oracle.results
-    if 0 in res and 1 in res:                                        # overlapped and serial runs agree bit for bit
-        for (o0, l0), (o1, l1) in zip(res[0], res[1]):
-            assert torch.equal(o0, o1) and torch.equal(l0, l1)
+    for other in (1, 2):                                             # DA, serial and DBA runs agree bit for bit
+        if 0 in res and other in res:
+            for (o0, l0), (o1, l1) in zip(res[0], res[other]):
+                assert torch.equal(o0, o1) and torch.equal(l0, l1)
 
 
 def test_decode_step_resident_cfg1(ess_lib):
