@@ -38,20 +38,29 @@ WORKLOADS = {
                  desc="B64 ctx32768 T1, Latent-Cache in pinned host memory, 25% GPU slots, 80% top-k overlap"),
     "cfg4": dict(cfg=4, B=64, T=1, L=131072, lens=(98304, 131072), ratio=0.10, rho=0.7,
                  desc="B64 ctx in [98304,131072] T1, Latent-Cache in pinned host memory, 10% GPU slots, 70% top-k overlap"),
+    # multi-token decode over 61 layers run back to back: one step = 61 layer-steps; per layer its own
+    # Indexer-Cache, slot pool and cache state; ONE host pool aliased by all layers (61 x 11 GB of pinned
+    # memory cannot exist) and one access trace replayed by every layer
+    "cfg5": dict(cfg=5, B=128, T=2, L=131072, lens=None, ratio=0.10, rho=0.7, layers=61, fmt="fp8",
+                 desc="B128 ctx131072 T2 (causal offset), fp8 e4m3 Latent-Cache entries (656 B) in pinned host memory, "
+                      "10% GPU slots, 70% top-k overlap, 61 layers back to back"),
 }
 # HBM bytes per launch of the index-score kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (see profiles/); None until measured for that workload
 MEASURED_TRAFFIC_BYTES = {"cfg4": 957862 * 1024}   # profiles/pmc_traffic_cfg4.md
 
 
-def build_workload(name, steps_needed, overlap="auto"):
+def build_workload(name, steps_needed, overlap="auto", layers=None):
     import torch
     from paper_2512_10576_amd import binding as bnd, synth
     wl = dict(WORKLOADS[name]); wl.update(COMMON)
     B, T, L, k, H = wl["B"], wl["T"], wl["L"], wl["k"], wl["H"]
+    n_layers = layers if layers is not None else wl.get("layers", 1)
+    wl["layers"] = n_layers
+    fp8 = wl.get("fmt") == "fp8"
+    stride = 656 if fp8 else 1152
     seed = 1000 * wl["cfg"]
     dev = "cuda"
-    q_idx, w, key = synth.indexer_inputs(seed, B, T, wl["Hi"], wl["Di"], L, wl["qk_max"], wl["w_levels"], wl["w_den"], device=dev)
     q_attn = synth.attn_query(seed, B, T, H, device=dev)
     if wl["lens"] is None:
         ctx_len = torch.full((B,), L, dtype=torch.int32, device=dev)
@@ -61,28 +70,38 @@ def build_workload(name, steps_needed, overlap="auto"):
     if overlap == "auto":
         overlap = "da"
     flags = {"da": 0, "serial": bnd.ESS_FLAG_SERIAL, "dba": bnd.ESS_FLAG_DBA}[overlap]
-    cfg = bnd.make_config(B, T, L, wl["Hi"], wl["Di"], k, H, slots_per_seq=S, flags=flags)
+    cfg = bnd.make_config(B, T, L, wl["Hi"], wl["Di"], k, H, latent_fmt=bnd.ESS_FMT_FP8 if fp8 else bnd.ESS_FMT_BF16,
+                          row_stride=stride, slots_per_seq=S, flags=flags)
     ctx = bnd.Context(cfg)
+    rows = synth.latent_rows_fp8 if fp8 else synth.latent_rows_bf16
     host_pool = None
-    if wl["ratio"] is None:
-        pool = torch.empty((B, L, 1152), dtype=torch.uint8, device=dev)
+    if wl["ratio"] is not None:
+        host_pool = torch.empty((B, L, stride), dtype=torch.uint8, pin_memory=True)
         for b in range(B):
-            synth.latent_rows_bf16(seed + b, L, device=dev, out=pool[b])
-        cache = bnd.Cache.allocate(cfg, B, slot_pool=pool)
-    else:
-        host_pool = torch.empty((B, L, 1152), dtype=torch.uint8, pin_memory=True)
-        for b in range(B):
-            host_pool[b].copy_(synth.latent_rows_bf16(seed + b, L, device=dev))
+            host_pool[b].copy_(rows(seed + b, L, device=dev))
         torch.cuda.synchronize()
-        cache = bnd.Cache.allocate(cfg, B, host_pool=host_pool)
-    ctx.cache_reset(cache, B)
+    q_idx, w, keys, caches = None, None, [], []
+    for layer in range(n_layers):                    # seed = 1000 * cfg + layer
+        q_idx, w, key = synth.indexer_inputs(seed + layer, B, T, wl["Hi"], wl["Di"], L, wl["qk_max"], wl["w_levels"],
+                                             wl["w_den"], device=dev)
+        keys.append(key)
+        if wl["ratio"] is None:
+            pool = torch.empty((B, L, stride), dtype=torch.uint8, device=dev)
+            for b in range(B):
+                pool[b].copy_(rows(seed + b, L, device=dev))
+            cache = bnd.Cache.allocate(cfg, B, slot_pool=pool)
+        else:
+            cache = bnd.Cache.allocate(cfg, B, host_pool=host_pool)
+        ctx.cache_reset(cache, B)
+        caches.append(cache)
     trace = None
     if wl["rho"] is not None:
         tr = synth.TopkTrace(seed, ctx_len, T, k, wl["rho"], device=dev)
         trace = [tr.next() for _ in range(steps_needed)]
     torch.cuda.synchronize()
-    return dict(wl=wl, name=name, overlap=overlap, ctx=ctx, cfg=cfg, cache=cache, q_idx=q_idx, w=w, key=key, q_attn=q_attn,
-                ctx_len=ctx_len, host_pool=host_pool, trace=trace, S=S,
+    return dict(wl=wl, name=name, overlap=overlap, ctx=ctx, cfg=cfg, cache=caches[0], caches=caches, q_idx=q_idx, w=w,
+                key=keys[0], keys=keys, q_attn=q_attn, ctx_len=ctx_len, host_pool=host_pool, trace=trace, S=S,
+                stride=stride, fmt=1 if fp8 else 0,
                 idx_out=torch.empty((B, T, k), dtype=torch.int32, device=dev),
                 out=torch.empty((B, T, H, 512), dtype=torch.bfloat16, device=dev),
                 lse=torch.empty((B, T, H), dtype=torch.float32, device=dev),
@@ -90,12 +109,14 @@ def build_workload(name, steps_needed, overlap="auto"):
 
 
 def run_steps(W, first_step, n):
+    """n steps; a step runs every layer once (one layer-step each), each layer on its own cache and keys"""
     ctx = W["ctx"]
     for i in range(n):
         s = first_step + i
         ov = W["trace"][s - 1] if W["trace"] is not None else None
-        ctx.decode_step(W["cache"], W["q_idx"], W["w"], W["key"], W["ctx_len"], W["q_attn"], s, W["idx_out"],
-                        W["out"], W["lse"], W["miss"], ov)
+        for cache, key in zip(W["caches"], W["keys"]):
+            ctx.decode_step(cache, W["q_idx"], W["w"], key, W["ctx_len"], W["q_attn"], s, W["idx_out"],
+                            W["out"], W["lse"], W["miss"], ov)
 
 
 def algorithmic_bytes(W, misses_per_step):
@@ -105,19 +126,20 @@ def algorithmic_bytes(W, misses_per_step):
     B, T, k, H = wl["B"], wl["T"], wl["k"], wl["H"]
     a1 = int(lens.sum()) * (wl["Di"] + 4 * T) + B * T * wl["Hi"] * (wl["Di"] + 4)
     a2 = int(lens.sum()) * 4 * T + B * T * k * 4
-    a4 = B * T * k * 1152 + B * T * H * (576 * 2 + 512 * 2 + 4)
-    fill = int(misses_per_step * 1152)
+    a4 = B * T * k * W["stride"] + B * T * H * (576 * 2 + 512 * 2 + 4)
+    fill = int(misses_per_step * W["stride"])
     return dict(index_score=a1, topk=a2, attention_rows=a4, fill=fill)
 
 
-def measure(name, steps, warmup, overlap="auto"):
+def measure(name, steps, warmup, overlap="auto", layers=None):
     import torch
-    W = build_workload(name, warmup + steps, overlap)
+    W = build_workload(name, warmup + steps, overlap, layers)
+    nl = W["wl"]["layers"]
     ctx = W["ctx"]
     run_steps(W, 1, warmup)
     torch.cuda.synchronize()
     ctx.reset_stats()
-    ctx.profile_enable(steps)
+    ctx.profile_enable(steps * nl)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     run_steps(W, warmup + 1, steps)
@@ -127,13 +149,14 @@ def measure(name, steps, warmup, overlap="auto"):
     ctx.profile_enable(0)
     stats = ctx.get_stats()
     stage = [sum(p[i] for p in prof) / len(prof) for i in range(6)]
-    misses_per_step = stats["misses"] / max(steps, 1)
+    misses_per_step = stats["misses"] / max(steps * nl, 1)     # per layer-step
     ab = algorithmic_bytes(W, misses_per_step)
-    ms_step = dt / steps * 1e3
+    ms_step = dt / (steps * nl) * 1e3                            # per layer-step
+    ms_model_step = dt / steps * 1e3                             # per step (all layers)
     hbm_stream_bytes = ab["index_score"] + ab["topk"] + ab["attention_rows"]
     hbm_stream_ms = stage[0] + stage[1] + stage[3] + stage[4]
     res = dict(
-        layer_steps_per_s=steps / dt, ms_per_step=ms_step,
+        layer_steps_per_s=steps * nl / dt, ms_per_step=ms_model_step, ms_per_layer_step=ms_step, layers=nl,
         stage_ms=dict(index_score=stage[0], topk=stage[1], bookkeeping=stage[2], attn0=stage[3], attn1_merge=stage[4],
                       fetch=stage[5]),
         index_score_GBs=ab["index_score"] / (stage[0] * 1e-3) / 1e9,
@@ -166,7 +189,7 @@ def cpu_baseline(W, budget_seqs):
     if W["host_pool"] is not None:
         host = W["host_pool"][:n].numpy()
         cache = O.SlotCache(n, L, S)
-        pool = np.zeros((n, S, 1152), np.uint8)
+        pool = np.zeros((n, S, W["stride"]), np.uint8)
         ov = W["trace"][0][:n].cpu().numpy()
     else:
         host = None
@@ -174,7 +197,7 @@ def cpu_baseline(W, budget_seqs):
         pool = W["cache"].slot_pool[:n].cpu().numpy()
         ov = None
     t0 = time.perf_counter()
-    O.decode_step(q_idx, w, key, ctx_len, wl["k"], cache, pool, host, q_bits, O.FMT_BF16, 576 ** -0.5, 1, ov)
+    O.decode_step(q_idx, w, key, ctx_len, wl["k"], cache, pool, host, q_bits, W["fmt"], 576 ** -0.5, 1, ov)
     dt = time.perf_counter() - t0
     return dict(value=1.0 / (dt * wl["B"] / n), unit="layer-steps/s", cores=int(threads), kind="oracle",
                 sample="%d of %d sequences of %s, one layer-step (cold cache), scaled linearly to the batch; %.1f s of CPU time"
@@ -190,6 +213,7 @@ def main():
     ap.add_argument("--overlap", default="auto", choices=["auto", "da", "dba", "serial"],
                     help="overlap of the miss fetch (paper Sec. 3.3); auto = da (DBA is built and exact, but on this GPU the\n"
                          "fetch slows the concurrent indexer enough to cancel its gain; see DESIGN.md)")
+    ap.add_argument("--layers", type=int, default=None, help="layers run back to back per step (default: the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-32k", action="store_true", help="skip the extra 32K-context measurement (cfg2)")
     ap.add_argument("--cpu-seqs", type=int, default=16)
@@ -213,19 +237,19 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    W, res = measure(a.workload, a.steps, a.warmup, a.overlap)
+    W, res = measure(a.workload, a.steps, a.warmup, a.overlap, a.layers)
     ab = res["algorithmic_bytes"]
     roof = dict(bound="hbm", kernel="k_index_score", achieved=res["index_score_GBs"], peak=HBM_PEAK_GBS, unit="GB/s",
                 frac=res["index_score_GBs"] / HBM_PEAK_GBS, traffic=MEASURED_TRAFFIC_BYTES.get(a.workload),
                 algorithmic_bytes_per_launch=ab["index_score"], avg_launch_ms=res["stage_ms"]["index_score"])
     out = {
         "metric": "decode-step sparse-attn layer-steps/sec", "value": res["layer_steps_per_s"], "unit": "layer-steps/s",
-        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": res["ms_per_step"],
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": res["ms_per_step"], "ms_per_layer_step": res["ms_per_layer_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "fp8 indexer / bf16 attention",
         "data": "synthetic",
         "config": {"workload": "%s: %s" % (a.workload, W["wl"]["desc"]), "indexer": "64 heads x 128 fp8 e4m3",
                    "topk": 2048, "attention": "128 heads x 576 bf16 absorbed MLA", "slots_per_seq": W["S"],
-                   "overlap": W["overlap"]},
+                   "overlap": W["overlap"], "layers_per_step": res["layers"], "q_tokens": W["wl"]["T"]},
         "roofline": roof,
         "stages": {k: res[k] for k in ("stage_ms", "hbm_stream_GBs", "hbm_stream_frac_of_peak", "whole_step_hbm_frac",
                                        "misses_per_step", "host_link_GBs", "host_link_frac_of_peak")},

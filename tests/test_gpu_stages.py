@@ -243,23 +243,28 @@ def test_sparse_mla_decode_vs_oracle(ess_lib, name, B, T, H, L, k, fmt, scale):
 
 
 # ---------------------------------------------------------------- whole step
-@pytest.mark.parametrize("flags", [0, 1, 2])
-def test_decode_step_offloaded_vs_oracle(ess_lib, flags):
+@pytest.mark.parametrize("flags,fmt", [(0, 0), (1, 0), (2, 0), (0, 1), (2, 1)])
+def test_decode_step_offloaded_vs_oracle(ess_lib, flags, fmt):
+    """T = 2 (causal offset), offloaded entries in both storage formats, all overlap modes"""
     from paper_2512_10576_amd import binding as bnd
-    print("decode_step offload flags", flags, flush=True)
+    print("decode_step offload flags", flags, "fmt", fmt, flush=True)
     B, T, Hi, Di, L, k, H, S = 3, 2, 64, 128, 6000, 512, 128, 1500
+    stride = 1152 if fmt == 0 else 656
     qi, w, key = synth.indexer_inputs(41, B, T, Hi, Di, L, 8, 8, 16)
     ctx_len = torch.tensor([6000, 4321, 5555], dtype=torch.int32)
-    host = synth.latent_rows_bf16(41, B * L).reshape(B, L, 1152)
-    hp = torch.empty((B, L, 1152), dtype=torch.uint8, pin_memory=True)
+    host = (synth.latent_rows_bf16(41, B * L) if fmt == 0 else synth.latent_rows_fp8(41, B * L)).reshape(B, L, stride)
+    hp = torch.empty((B, L, stride), dtype=torch.uint8, pin_memory=True)
     hp.copy_(host)
     ctx = _ctx(ess_lib, max_batch=B, max_q_tokens=T, max_ctx=L, idx_heads=Hi, idx_dim=Di, topk=k, attn_heads=H,
-               slots_per_seq=S, flags=flags)
+               slots_per_seq=S, flags=flags, latent_fmt=fmt)
+    # poison: a NaN pattern for bf16 entries; for quantised entries 0x7E (448, finite) -- a never-filled slot
+    # must not be read at all, but a NaN byte there would make the dequantised zero-weight product NaN
+    poison = 0x7F if fmt == 0 else 0x7E
     cache = bnd.Cache.allocate(ctx.cfg, B, host_pool=hp,
-                               slot_pool=torch.full((B, S, 1152), 0x7F, dtype=torch.uint8, device="cuda"))
+                               slot_pool=torch.full((B, S, stride), poison, dtype=torch.uint8, device="cuda"))
     ctx.cache_reset(cache, B)
     oc = O.SlotCache(B, L, S)
-    opool = np.full((B, S, 1152), 0x7F, np.uint8)
+    opool = np.full((B, S, stride), poison, np.uint8)
     trace = synth.TopkTrace(9, ctx_len, T, k, 0.7)
     idx_out = torch.empty((B, T, k), dtype=torch.int32, device="cuda")
     out = torch.empty((B, T, H, 512), dtype=torch.bfloat16, device="cuda")
@@ -271,7 +276,7 @@ def test_decode_step_offloaded_vs_oracle(ess_lib, flags):
         q = synth.attn_query(50 + step, B, T, H)
         ov = trace.next() if step != 3 else None                     # step 3 uses the real top-k
         r = O.decode_step(qi.numpy(), w.numpy(), key.numpy(), ctx_len.numpy(), k, oc, opool, host.numpy(),
-                          _qbits(q), O.FMT_BF16, 576 ** -0.5, step, None if ov is None else ov.numpy())
+                          _qbits(q), fmt, 576 ** -0.5, step, None if ov is None else ov.numpy())
         ctx.decode_step(cache, dev[0], dev[1], dev[2], dev[3], q.cuda(), step, idx_out, out, lse, mc,
                         None if ov is None else ov.cuda())
         torch.cuda.synchronize()
@@ -283,11 +288,11 @@ def test_decode_step_offloaded_vs_oracle(ess_lib, flags):
         outs.append((out.clone(), lse.clone()))
     ctx.close()
     test_decode_step_offloaded_vs_oracle.results = getattr(test_decode_step_offloaded_vs_oracle, "results", {})
-    test_decode_step_offloaded_vs_oracle.results[flags] = outs
+    test_decode_step_offloaded_vs_oracle.results[(flags, fmt)] = outs
     res = test_decode_step_offloaded_vs_oracle.results
     for other in (1, 2):                                             # DA, serial and DBA runs agree bit for bit
-        if 0 in res and other in res:
-            for (o0, l0), (o1, l1) in zip(res[0], res[other]):
+        if (0, fmt) in res and (other, fmt) in res:
+            for (o0, l0), (o1, l1) in zip(res[(0, fmt)], res[(other, fmt)]):
                 assert torch.equal(o0, o1) and torch.equal(l0, l1)
 
 
