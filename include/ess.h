@@ -193,6 +193,11 @@ int ess_reset_stats(ess_ctx* ctx, void* stream);
 #define ESS_PROFILE_STAGES 6
 int ess_profile_enable(ess_ctx* ctx, int32_t max_steps);
 int ess_profile_read(ess_ctx* ctx, float* host_ms, int32_t* n_steps);
+/* Restrict the timing to some stages (bit i = stage i above; default all) and to every `every`-th
+ * ess_decode_step (default 1): recorded events cost a few percent of a step, so a run whose
+ * throughput matters samples one kernel on a few steps.  ess_profile_read then returns the sampled
+ * steps only. */
+int ess_profile_select(ess_ctx* ctx, uint32_t stage_mask, int32_t every);
 /* A plain device-to-device copy kernel (reads `bytes`, writes `bytes`; bytes a multiple of 16,
  * pointers 16-byte aligned): known traffic against which hardware counters can be scaled. */
 int ess_calib_copy(void* dst, const void* src, size_t bytes, void* stream);

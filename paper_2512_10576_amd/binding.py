@@ -79,6 +79,7 @@ def load() -> C.CDLL:
         "ess_get_stats": [vp, C.POINTER(EssStats), vp],
         "ess_reset_stats": [vp, vp],
         "ess_profile_enable": [vp, i32],
+        "ess_profile_select": [vp, u32, i32],
         "ess_calib_copy": [vp, vp, C.c_size_t, vp],
         "ess_profile_read": [vp, C.POINTER(C.c_float), C.POINTER(i32)],
     }
@@ -223,8 +224,9 @@ class Context:
         _check(self.lib.ess_get_stats(self.h, C.byref(s), _stream()))
         return dict(steps=s.steps, selected=s.selected, misses=s.misses, bytes_filled=s.bytes_filled)
 
-    def profile_enable(self, max_steps):
+    def profile_enable(self, max_steps, stage_mask=0x3F, every=1):
         self._prof_cap = max_steps
+        _check(self.lib.ess_profile_select(self.h, stage_mask, every))
         _check(self.lib.ess_profile_enable(self.h, max_steps))
 
     def profile_read(self):

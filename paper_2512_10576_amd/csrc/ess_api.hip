@@ -182,6 +182,8 @@ int ess_create(const ess_config* cfg, ess_ctx** out) {
   if (!ctx) return ess_fail(ESS_ERR_NOMEM, "host allocation failed");
   memset(ctx, 0, sizeof(*ctx));
   ctx->cfg = *cfg;
+  ctx->prof_mask = 0x3Fu;
+  ctx->prof_every = 1;
   hipError_t e = hipGetDevice(&ctx->device);
   if (e != hipSuccess) { delete ctx; return ess_fail(ESS_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e)); }
   const WsLayout w = ws_layout(*cfg);
@@ -335,22 +337,30 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
   hipEvent_t* pev = nullptr;
   int8_t* ptag = nullptr;
   int pslot = -1, nmark = 0;
-  if (ctx->prof_ev && ctx->prof_n < ctx->prof_cap) {
+  if (ctx->prof_ev && ctx->prof_n < ctx->prof_cap && (ctx->prof_calls++ % ctx->prof_every) == 0) {
     pslot = ctx->prof_n++;
     pev = ctx->prof_ev + (size_t)pslot * ESS_PROF_EVENTS;
     ptag = ctx->prof_tag + (size_t)pslot * ESS_PROF_MAIN;
     ctx->prof_nmark[pslot] = 0;
     ctx->prof_nfill[pslot] = 0;
   }
-#define ESS_MARK(tag)                                          \
+  // ESS_BEGIN(tag) / ESS_END(tag) bracket the launches of one stage; only selected stages are timed
+  bool adjacent = false;                        // the last recorded mark sits right before this point
+#define ESS_RECORD(tag)                                        \
   do {                                                         \
-    if (pev && nmark < ESS_PROF_MAIN) {                        \
+    if (nmark < ESS_PROF_MAIN) {                               \
       ESS_HIP(hipEventRecord(pev[nmark], st));                 \
       ptag[nmark] = (int8_t)(tag);                             \
       ctx->prof_nmark[pslot] = ++nmark;                        \
     }                                                          \
+    adjacent = true;                                           \
   } while (0)
-  ESS_MARK(-1);
+#define ESS_BEGIN(tag) do { if (pev && ((ctx->prof_mask >> (tag)) & 1u) && !adjacent) ESS_RECORD(-1); } while (0)
+#define ESS_END(tag)                                           \
+  do {                                                         \
+    if (pev && ((ctx->prof_mask >> (tag)) & 1u)) ESS_RECORD(tag); \
+    else adjacent = false;                                     \
+  } while (0)
 
   const bool offloaded = cache->host_pool_dev != nullptr;
   // DualBatch-Attention overlap (Sec. 3.3): the batch is cut in two halves so that the second half's
@@ -378,39 +388,45 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     const size_t bt0 = (size_t)b0 * T;
     float* sc = ctx->score_ws + bt0 * c.max_ctx;
     int32_t* idx_h = a->idx_out + bt0 * k;
+    ESS_BEGIN(0);
     rc = ess_launch_index_score(c, a->q_idx_fp8 + bt0 * c.idx_heads * c.idx_dim, a->w + bt0 * c.idx_heads,
                                 a->key_fp8 + (size_t)b0 * c.max_ctx * c.idx_dim, a->ctx_len + b0, Bh, T, sc, st);
     if (rc != ESS_OK) return rc;
-    ESS_MARK(0);
+    ESS_END(0);
+    ESS_BEGIN(1);
     rc = ess_launch_topk(c, sc, a->ctx_len + b0, Bh, T, idx_h, st);
     if (rc != ESS_OK) return rc;
-    ESS_MARK(1);
+    ESS_END(1);
     if (!offloaded) continue;
     const int32_t* used = a->topk_override ? a->topk_override + bt0 * k : idx_h;
     const ess_cache ch = shift_cache(c, *cache, b0);
-    hipEvent_t* fev = (pev && h < ESS_PROF_FILL) ? pev + ESS_PROF_MAIN + 2 * h : nullptr;
+    hipEvent_t* fev = (pev && h < ESS_PROF_FILL && ((ctx->prof_mask >> 5) & 1u)) ? pev + ESS_PROF_MAIN + 2 * h : nullptr;
+    ESS_BEGIN(2);
     rc = run_cache_step(ctx, ch, used, Bh, T, c.topk, a->step, ctx->slot_idx_ws + bt0 * k,
                         a->miss_count ? a->miss_count + b0 : nullptr, st, &pending[h], b0, h, fev);
     if (rc != ESS_OK) return rc;
     if (fev) ctx->prof_nfill[pslot] = h + 1;
-    ESS_MARK(2);
+    ESS_END(2);
   }
 
   if (!offloaded) {
     // nothing offloaded: slot == position, attention straight over the selection
     const int32_t* used = a->topk_override ? a->topk_override : a->idx_out;
+    ESS_BEGIN(3);
     rc = ess_launch_attn_partial(ctx, a->q_bf16, cache->slot_pool, used, nullptr, B, T, 0, ns0, st);
     if (rc != ESS_OK) return rc;
-    ESS_MARK(3);
+    ESS_END(3);
+    ESS_BEGIN(4);
     if (a->miss_count && (rc = ess_launch_fill_u32(reinterpret_cast<uint32_t*>(a->miss_count), B, 0u, st)) != ESS_OK) return rc;
     rc = ess_launch_attn_merge(ctx, B, T, ns0, a->out_bf16, a->lse, st);
     if (rc != ESS_OK) return rc;
-    ESS_MARK(4);
+    ESS_END(4);
     return ESS_OK;
   }
 
   // stage 4: Attn0 over resident entries while the fetches run, Attn1 over fetched ones, merge
   const uint16_t* q16 = static_cast<const uint16_t*>(a->q_bf16);
+  ESS_BEGIN(3);
   for (int h = 0; h < nh; ++h) {
     const int b0 = hb0[h], Bh = hB[h];
     const size_t bt0 = (size_t)b0 * T;
@@ -419,7 +435,8 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
                                  ctx->n_hit + bt0, Bh, T, 0, ns0, st, b0);
     if (rc != ESS_OK) return rc;
   }
-  ESS_MARK(3);
+  ESS_END(3);
+  ESS_BEGIN(4);
   for (int h = 0; h < nh; ++h) {
     const int b0 = hb0[h], Bh = hB[h];
     const size_t bt0 = (size_t)b0 * T;
@@ -431,15 +448,26 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
   }
   rc = ess_launch_attn_merge(ctx, B, T, ns0 + ns1, a->out_bf16, a->lse, st);
   if (rc != ESS_OK) return rc;
-  ESS_MARK(4);
+  ESS_END(4);
   return ESS_OK;
-#undef ESS_MARK
+#undef ESS_RECORD
+#undef ESS_BEGIN
+#undef ESS_END
 }
 
 int ess_calib_copy(void* dst, const void* src, size_t bytes, void* stream) {
   if (!dst || !src || (bytes & 15) || !aligned16(dst) || !aligned16(src))
     return ess_fail(ESS_ERR_INVALID_ARG, "calib copy needs 16-byte aligned pointers and size");
   return ess_launch_calib_copy(dst, src, bytes, static_cast<hipStream_t>(stream));
+}
+
+int ess_profile_select(ess_ctx* ctx, uint32_t stage_mask, int32_t every) {
+  if (!ctx) return ess_fail(ESS_ERR_INVALID_ARG, "context is NULL");
+  if (every < 1) return ess_fail(ESS_ERR_INVALID_ARG, "every must be >= 1");
+  ctx->prof_mask = stage_mask & 0x3Fu;
+  ctx->prof_every = every;
+  ctx->prof_calls = 0;
+  return ESS_OK;
 }
 
 int ess_profile_enable(ess_ctx* ctx, int32_t max_steps) {

@@ -39,6 +39,8 @@ struct ess_ctx {
   int* prof_nmark;              // [prof_cap] marks recorded
   int* prof_nfill;              // [prof_cap] fetch pairs recorded
   int prof_cap, prof_n;
+  uint32_t prof_mask;           // stages that are timed (bit i = stage i of ess_profile_read)
+  int prof_every, prof_calls;   // every prof_every-th ess_decode_step is timed
 };
 
 int ess_fail(int code, const char* fmt, ...);
