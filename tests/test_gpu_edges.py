@@ -1,0 +1,130 @@
+"""GPU edge cases: empty and tiny contexts, odd sizes, maximum sizes, the non-register bookkeeping path."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ess_oracle as O
+from paper_2512_10576_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _ctx(**kw):
+    from paper_2512_10576_amd import binding as b
+    return b.Context(b.make_config(**kw))
+
+
+def _qbits(q):
+    return q.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def test_decode_step_with_empty_and_tiny_contexts(ess_lib):
+    """ctx_len 0, 1, 2 (T = 2: query 0 of a length-1 context sees nothing), k not a multiple of the tile"""
+    from paper_2512_10576_amd import binding as bnd
+    print("edges: empty / tiny contexts", flush=True)
+    B, T, Hi, Di, L, k, H = 5, 2, 64, 128, 300, 100, 24
+    qi, w, key = synth.indexer_inputs(61, B, T, Hi, Di, L, 8, 8, 16)
+    ctx_len = torch.tensor([0, 1, 2, 300, 57], dtype=torch.int32)
+    pool = synth.latent_rows_bf16(61, B * L).reshape(B, L, 1152)
+    q = synth.attn_query(61, B, T, H)
+    oc = O.SlotCache(B, L, L)
+    oc.make_resident_identity()
+    r = O.decode_step(qi.numpy(), w.numpy(), key.numpy(), ctx_len.numpy(), k, oc, pool.numpy().copy(), None,
+                      _qbits(q), O.FMT_BF16, 576 ** -0.5, 1)
+    ctx = _ctx(max_batch=B, max_q_tokens=T, max_ctx=L, idx_heads=Hi, idx_dim=Di, topk=k, attn_heads=H)
+    cache = bnd.Cache.allocate(ctx.cfg, B, slot_pool=pool.cuda())
+    ctx.cache_reset(cache, B)
+    idx_out = torch.empty((B, T, k), dtype=torch.int32, device="cuda")
+    out = torch.full((B, T, H, 512), 7.0, dtype=torch.bfloat16, device="cuda")
+    lse = torch.full((B, T, H), 7.0, dtype=torch.float32, device="cuda")
+    ctx.decode_step(cache, qi.cuda(), w.cuda(), key.cuda(), ctx_len.cuda(), q.cuda(), 1, idx_out, out, lse)
+    torch.cuda.synchronize()
+    got = idx_out.cpu().numpy()
+    for b in range(B):
+        for t in range(T):
+            ref = r["idx"][b, t]
+            nv = int((ref >= 0).sum())
+            assert np.array_equal(got[b, t, :nv], np.sort(ref[:nv])) and np.all(got[b, t, nv:] == -1)
+    o = out.float().cpu().numpy().astype(np.float64)
+    # outputs here reach O(1) (a one- or two-row selection returns the rows themselves), so the bound
+    # carries the bf16 output rounding: 2^-8 relative
+    assert np.all(np.abs(o - r["out"]) <= 3e-3 + 2.0 ** -8 * np.abs(r["out"]))
+    lg = lse.cpu().numpy()
+    assert np.array_equal(np.isneginf(lg), np.isneginf(r["lse"]))          # empty selections: lse = -inf, out = 0
+    assert not o[0].any() and not o[1, 0].any()
+    ctx.close()
+
+
+def test_topk_at_maximum_context_and_k(ess_lib):
+    """one row of 524288 scores (the largest context the library accepts), k = 4096"""
+    print("edges: top-k at max_ctx 524288, k 4096", flush=True)
+    L, k = 524288, 4096
+    rng = np.random.default_rng(5)
+    sc = (np.rint(rng.normal(30000, 6000, (1, 1, L))).clip(0) / 16).astype(np.float32)
+    ctx = _ctx(max_batch=1, max_q_tokens=1, max_ctx=L, idx_heads=4, idx_dim=32, topk=k, attn_heads=8)
+    idx = torch.empty((1, 1, k), dtype=torch.int32, device="cuda")
+    for n in (L, L - 3, 70001):
+        ctx.topk(torch.from_numpy(sc).cuda(), torch.tensor([n], dtype=torch.int32).cuda(), idx)
+        torch.cuda.synchronize()
+        ref = O.topk(sc, np.array([n]), k)
+        assert np.array_equal(idx.cpu().numpy()[0, 0], np.sort(ref[0, 0])), n
+    ctx.close()
+
+
+def test_bookkeeping_large_pool_path(ess_lib):
+    """more than 16384 slots per sequence: stamps are re-read from memory instead of held in registers"""
+    from paper_2512_10576_amd import binding as bnd
+    print("edges: bookkeeping with 20000 slots", flush=True)
+    B, T, L, S, k = 2, 1, 50000, 20000, 2048
+    host = synth.latent_rows_fp8(13, B * L).reshape(B, L, 656)
+    hp = torch.empty((B, L, 656), dtype=torch.uint8, pin_memory=True)
+    hp.copy_(host)
+    ctx_len = torch.full((B,), L, dtype=torch.int32)
+    ctx = _ctx(max_batch=B, max_q_tokens=T, max_ctx=L, idx_heads=4, idx_dim=32, topk=k, attn_heads=8, slots_per_seq=S,
+               latent_fmt=1)
+    cache = bnd.Cache.allocate(ctx.cfg, B, host_pool=hp)
+    ctx.cache_reset(cache, B)
+    oc = O.SlotCache(B, L, S)
+    opool = np.zeros((B, S, 656), np.uint8)
+    trace = synth.TopkTrace(6, ctx_len, T, k, 0.1, zipf_s=0.2)     # nearly uniform, 90 % new entries per step
+    slot_idx = torch.empty((B, T, k), dtype=torch.int32, device="cuda")
+    mc = torch.empty((B,), dtype=torch.int32, device="cuda")
+    for step in range(1, 25):                                   # enough steps to fill the pool and start evicting
+        idx = trace.next()
+        r = oc.step(idx.numpy(), step)
+        O.fill_slots(opool, host.numpy(), r["miss_tok"], r["victims"])
+        ctx.gather_latent(cache, idx.cuda(), ctx_len.cuda(), step, slot_idx, None, mc)
+        torch.cuda.synchronize()
+        assert np.array_equal(mc.cpu().numpy(), r["miss_count"]), step
+        assert np.array_equal(slot_idx.cpu().numpy(), r["slot_idx"]), step
+        assert np.array_equal(cache.token_of.cpu().numpy(), oc.token_of), step
+    assert np.array_equal(cache.slot_pool.cpu().numpy(), opool)
+    assert (oc.token_of >= 0).all()                              # the pool filled up, so victims were evicted
+    ctx.close()
+
+
+def test_single_sequence_single_head_block(ess_lib):
+    """B = 1, H = 1, k = 1: the smallest shapes"""
+    from paper_2512_10576_amd import binding as bnd
+    print("edges: B=1 H=1 k=1", flush=True)
+    B, T, Hi, Di, L, k, H = 1, 1, 1, 32, 64, 1, 1
+    qi, w, key = synth.indexer_inputs(71, B, T, Hi, Di, L, 4, 4, 8)
+    ctx_len = torch.tensor([64], dtype=torch.int32)
+    pool = synth.latent_rows_bf16(71, L).reshape(1, L, 1152)
+    q = synth.attn_query(71, B, T, H)
+    oc = O.SlotCache(B, L, L)
+    oc.make_resident_identity()
+    r = O.decode_step(qi.numpy(), w.numpy(), key.numpy(), ctx_len.numpy(), k, oc, pool.numpy().copy(), None,
+                      _qbits(q), O.FMT_BF16, 0.3, 1)
+    ctx = _ctx(max_batch=B, max_q_tokens=T, max_ctx=L, idx_heads=Hi, idx_dim=Di, topk=k, attn_heads=H, sm_scale=0.3)
+    cache = bnd.Cache.allocate(ctx.cfg, B, slot_pool=pool.cuda())
+    ctx.cache_reset(cache, B)
+    idx_out = torch.empty((B, T, k), dtype=torch.int32, device="cuda")
+    out = torch.empty((B, T, H, 512), dtype=torch.bfloat16, device="cuda")
+    ctx.decode_step(cache, qi.cuda(), w.cuda(), key.cuda(), ctx_len.cuda(), q.cuda(), 1, idx_out, out)
+    torch.cuda.synchronize()
+    assert idx_out.cpu().numpy().tolist() == r["idx"].tolist()
+    # one selected row with softmax weight 1: the output is that row (exactly, it is already bf16)
+    row = pool.view(torch.bfloat16).reshape(L, 576)[int(r["idx"][0, 0, 0]), :512].float().numpy()
+    assert np.array_equal(out.float().cpu().numpy()[0, 0, 0], row)
+    ctx.close()
