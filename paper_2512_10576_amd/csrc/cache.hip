@@ -289,11 +289,10 @@ __global__ __launch_bounds__(FILL_WPB * 64) void k_fill(const uint8_t* __restric
                                                const int32_t* __restrict__ fill_slot, int fill_cap,
                                                const int32_t* __restrict__ miss_cnt, int B, int Lmax, int S,
                                                int row_stride) {
-  __shared__ int32_t pref[FILL_MAX_B + 1];                   // pref[b] = entries of sequences < b
-  __shared__ uint32_t wave_tot[16];
+  extern __shared__ int32_t pref[];                          // [B + 1] pref[b] = entries of sequences < b (kept small:
+                                                             // the kernel must fit beside workgroups that fill the LDS)
   const int tid = threadIdx.x, lane = tid & 63;
-  // exclusive prefix sum of the per-sequence miss counts (B <= 4096), by the first wave
-  (void)wave_tot;
+  // exclusive prefix sum of the per-sequence miss counts, by the first wave
   if (tid < 64) {
     int run = 0;
     for (int b0 = 0; b0 <= B; b0 += 64) {
@@ -424,7 +423,7 @@ int ess_launch_bookkeeping(ess_ctx* ctx, const ess_cache& cache, const int32_t* 
 int ess_launch_fill(ess_ctx* ctx, const ess_cache& cache, int B, hipStream_t st, int b0) {
   const ess_config& c = ctx->cfg;
   const int cap = c.max_q_tokens * c.topk;
-  hipLaunchKernelGGL(k_fill, dim3(FILL_WGS), dim3(FILL_WPB * 64), 0, st, cache.host_pool_dev, cache.slot_pool,
+  hipLaunchKernelGGL(k_fill, dim3(FILL_WGS), dim3(FILL_WPB * 64), (size_t)(B + 1) * sizeof(int32_t), st, cache.host_pool_dev, cache.slot_pool,
                      ctx->fill_tok + (size_t)b0 * cap, ctx->fill_slot + (size_t)b0 * cap, cap, ctx->miss_cnt + b0, B,
                      c.max_ctx, c.slots_per_seq, c.row_stride);
   ESS_HIP(hipGetLastError());

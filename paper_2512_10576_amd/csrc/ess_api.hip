@@ -11,6 +11,10 @@
 
 #include "ess_internal.h"
 
+#ifndef ESS_ATTN0_WGS
+#define ESS_ATTN0_WGS 128
+#endif
+
 namespace {
 
 thread_local char g_err[512] = "";
@@ -101,10 +105,10 @@ int check_cache(const ess_ctx* ctx, const ess_cache* c) {
 
 // number of attention splits for a list of up to k entries: a workgroup is sized to own a CU, so aim at
 // a small multiple of the CU count; never fewer than the kernel's tiles-per-split limit allows
-int pick_splits(const ess_config& c, int B, int T, int cap) {
+int pick_splits(const ess_config& c, int B, int T, int cap, int target_wgs = 256) {
   const int tiles = (c.topk + ESS_ATTN_TILE - 1) / ESS_ATTN_TILE;
   const int hgroups = (c.attn_heads + 63) / 64;
-  int want = (512 + B * T * hgroups - 1) / (B * T * hgroups);   // two rounds of one workgroup per CU
+  int want = (target_wgs + B * T * hgroups - 1) / (B * T * hgroups);   // one workgroup per CU: fewer partial results to merge
   if (want > tiles) want = tiles;
   if (want > cap) want = cap;
   const int lo = ess_attn_min_splits(c);
@@ -373,7 +377,9 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
   bool pending[2] = {false, false};
 
   // attention splits: the same for both halves, one merge over the whole batch at the end
-  const int ns0 = pick_splits(c, B, T, 16);    // from the whole batch, so that every mode sums in the same order
+  // from the whole batch, so that every mode sums in the same order; beside a fetch Attn0 is kept to
+  // half the chip: it has the whole fetch time to finish, and a chip-wide gather slows the fetch down
+  const int ns0 = pick_splits(c, B, T, 16, offloaded ? ESS_ATTN0_WGS : 256);
   int ns1 = 0;
   if (offloaded) {
     ns1 = ns0 / 4;
