@@ -162,8 +162,10 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
     auto stamp_at = [&](int j) -> uint32_t { return REG ? sr[j] : stp[v0 + j]; };
     const int nj = REG ? RS : spt;
     // ---- m-th smallest stamp among evictable slots (stamp < step): 4 x 8-bit MSD radix passes
+    // evictable stamps are < step, so digits above step's top byte are zero for all of them: skip those passes
     uint32_t prefix = 0, need = m;
-    for (int pass = 0; pass < 4; ++pass) {
+    const int first_pass = step < (1u << 8) ? 3 : (step < (1u << 16) ? 2 : (step < (1u << 24) ? 1 : 0));
+    for (int pass = first_pass; pass < 4; ++pass) {
       const int shift = 24 - 8 * pass;
       for (int j = tid; j < 256 * 32; j += BT) sm.hist[j] = 0;
       __syncthreads();
@@ -171,7 +173,7 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
       for (int j = 0; j < nj; ++j) {
         if (v0 + j >= v1) continue;
         const uint32_t st = stamp_at(j);
-        if (st < step && (pass == 0 || (st >> (shift + 8)) == prefix))
+        if (st < step && (pass == first_pass || (st >> (shift + 8)) == prefix))
           atomicAdd(&sm.hist[((st >> shift) & 255u) * 32 + (lane & 31)], 1u);
       }
       __syncthreads();
@@ -211,10 +213,27 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
       }
     }
     __syncthreads();
-    int np = 1;
-    while (np < (int)m) np <<= 1;
-    for (int j = (int)m + tid; j < np; j += BT) sm.vict[j] = ~0ull;
-    bitonic_sort_u64(sm.vict, np);
+    // order the victims by (stamp, slot).  Up to 1024 of them: every thread ranks one victim by counting
+    // the smaller keys (keys are distinct; no barriers, LDS broadcast reads); more: bitonic sort.
+    const bool by_rank = m <= (uint32_t)BT;
+    int my_rank = -1;
+    unsigned long long my_key = 0;
+    if (by_rank) {
+      if (tid < (int)m) {
+        my_key = sm.vict[tid];
+        int rk = 0;
+        for (uint32_t j = 0; j < m; ++j) rk += sm.vict[j] < my_key ? 1 : 0;
+        my_rank = rk;
+      }
+      __syncthreads();
+      if (my_rank >= 0) sm.vict[my_rank] = my_key;
+      __syncthreads();
+    } else {
+      int np = 1;
+      while (np < (int)m) np <<= 1;
+      for (int j = (int)m + tid; j < np; j += BT) sm.vict[j] = ~0ull;
+      bitonic_sort_u64(sm.vict, np);
+    }
     // ---- pair the i-th miss with the i-th victim
     for (uint32_t i = tid; i < m; i += BT) {
       const int s = sm.miss_tok[i];

@@ -35,7 +35,7 @@ constexpr int CAND_CAP = 8192;
 
 constexpr int SBITS = 14;                  // sample histogram: top 14 bits of the orderable key
 constexpr int SBINS = 1 << SBITS;
-constexpr int SAMPLE_STRIDE = 16;
+constexpr int SAMPLE_TARGET = 4096;         // about this many samples per row, at least every 16th score
 constexpr int FAST_MIN_VIS = 16384;
 
 struct __align__(16) TopkShared {
@@ -155,7 +155,9 @@ __device__ __forceinline__ void scan_row(const float* __restrict__ srow, int vis
   }
 }
 
-// Same walk, handing f one round (16 positions of this thread) at a time.
+// Same walk, handing f one round (16 positions of this thread) at a time.  The loads of the next
+// round are issued before the current round is processed (two register sets); indices past the end
+// are clamped, not predicated, so that every load is unconditional.
 template <typename F>
 __device__ __forceinline__ void scan_row_rounds(const float* __restrict__ srow, int vis, bool vec_ok, F&& f) {
   constexpr int U = 4;
@@ -164,16 +166,14 @@ __device__ __forceinline__ void scan_row_rounds(const float* __restrict__ srow, 
   int pos[16];
   float val[16];
   bool ok[16];
-  if (vec_ok) {
+  if (vec_ok && vis >= 4) {
     const int nvec = vis >> 2;
     const float4* v4 = reinterpret_cast<const float4*>(srow);
-    for (int base = 0; base < nvec; base += NT * U) {
-      float4 x[U];
+    auto load = [&](int base, float4 (&x)[U]) {
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int j = base + u * NT + tid;
-        x[u] = j < nvec ? v4[j] : make_float4(0.f, 0.f, 0.f, 0.f);
-      }
+      for (int u = 0; u < U; ++u) x[u] = v4[min(base + u * NT + tid, nvec - 1)];
+    };
+    auto process = [&](int base, const float4 (&x)[U]) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int j = base + u * NT + tid;
@@ -184,6 +184,16 @@ __device__ __forceinline__ void scan_row_rounds(const float* __restrict__ srow, 
         pos[4 * u + 3] = 4 * j + 3; val[4 * u + 3] = x[u].w; ok[4 * u + 3] = in;
       }
       f(pos, val, ok);
+    };
+    constexpr int R = NT * U;                    // float4s per round
+    float4 xa[U], xb[U];
+    load(0, xa);
+    for (int base = 0; base < nvec; base += 2 * R) {
+      load(base + R, xb);
+      process(base, xa);
+      if (base + R >= nvec) break;
+      load(base + 2 * R, xa);
+      process(base + R, xb);
     }
     done = nvec << 2;
   }
@@ -230,7 +240,9 @@ __global__ __launch_bounds__(NT) void k_topk(const float* __restrict__ score, co
 
   // ---- A: sampled one-pass collection for long rows
   if (vis >= FAST_MIN_VIS) {
-    const int ns = vis / SAMPLE_STRIDE;
+    int sstride = 16;
+    while (vis / sstride > SAMPLE_TARGET) sstride <<= 1;
+    const int ns = vis / sstride;
     for (int j = tid; j < SBINS; j += NT) sm.shist[j] = 0;
     if (tid == 0) { sm.cand_n = 0; sm.sel_digit = 0xffffffffu; }
     __syncthreads();
@@ -239,7 +251,7 @@ __global__ __launch_bounds__(NT) void k_topk(const float* __restrict__ score, co
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int j = j0 + u * NT + tid;
-        sv[u] = j < ns ? srow[j * SAMPLE_STRIDE + 7] : 0.f;
+        sv[u] = j < ns ? srow[j * sstride + 7] : 0.f;
       }
 #pragma unroll
       for (int u = 0; u < 4; ++u)
@@ -268,15 +280,16 @@ __global__ __launch_bounds__(NT) void k_topk(const float* __restrict__ score, co
     __syncthreads();                          // shist is dead from here: cand may overwrite it
     if (lo_bin != 0xffffffffu) {
       const uint32_t tau = lo_bin << (32 - SBITS);
+      // The pass only compares floats and stores (position, score) of the few positions at or above
+      // the key: v >= tau_f is the same predicate as orderable(v) >= tau (NaN fails both, -0 == +0),
+      // and the composite keys are computed afterwards, densely, for the candidates alone.
+      const float tau_f = __uint_as_float((tau & 0x80000000u) ? (tau & 0x7fffffffu) : ~tau);
+      uint2* raw = reinterpret_cast<uint2*>(sm.cand);
       scan_row_rounds(srow, vis, vec_ok, [&](const int (&pos)[16], const float (&val)[16], const bool (&ok)[16]) {
-        unsigned long long c[16];
         uint32_t cnt = 0, flags = 0;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const uint32_t u = orderable(val[e]);
-          c[e] = ((unsigned long long)u << IB) | (imask - (unsigned long long)pos[e]);
-          if (ok[e] && u >= tau) { flags |= 1u << e; ++cnt; }
-        }
+        for (int e = 0; e < 16; ++e)
+          if (ok[e] && val[e] >= tau_f) { flags |= 1u << e; ++cnt; }
         // one LDS atomic per wave and round
         const uint32_t winc = wave_incl_scan(cnt, lane);
         uint32_t base = 0;
@@ -285,10 +298,16 @@ __global__ __launch_bounds__(NT) void k_topk(const float* __restrict__ score, co
 #pragma unroll
         for (int e = 0; e < 16; ++e)
           if (flags & (1u << e)) {
-            if (base < (uint32_t)CAND_CAP) sm.cand[base] = c[e];
+            if (base < (uint32_t)CAND_CAP) raw[base] = make_uint2((uint32_t)pos[e], __float_as_uint(val[e]));
             ++base;
           }
       });
+      __syncthreads();
+      if ((int)sm.cand_n <= CAND_CAP)
+        for (int j = tid; j < (int)sm.cand_n; j += NT) {
+          const uint2 pv = raw[j];
+          sm.cand[j] = comp_of((int)pv.x, __uint_as_float(pv.y));
+        }
       __syncthreads();
       nc = (int)sm.cand_n;
       if (nc >= k && nc <= CAND_CAP) {
