@@ -50,10 +50,14 @@ WORKLOADS = {
 MEASURED_TRAFFIC_BYTES = {"cfg4": 958772 * 1024}   # profiles/pmc_traffic_cfg4.md
 
 
-def build_workload(name, steps_needed, overlap="auto", layers=None):
+def build_workload(name, steps_needed, overlap="auto", layers=None, rho=None, ratio=None):
     import torch
     from paper_2512_10576_amd import binding as bnd, synth
     wl = dict(WORKLOADS[name]); wl.update(COMMON)
+    if rho is not None:
+        wl["rho"] = rho
+    if ratio is not None:
+        wl["ratio"] = ratio
     B, T, L, k, H = wl["B"], wl["T"], wl["L"], wl["k"], wl["H"]
     n_layers = layers if layers is not None else wl.get("layers", 1)
     wl["layers"] = n_layers
@@ -67,9 +71,7 @@ def build_workload(name, steps_needed, overlap="auto", layers=None):
     else:
         ctx_len = synth.ctx_lengths(seed, B, wl["lens"][0], wl["lens"][1], device=dev)
     S = L if wl["ratio"] is None else int(math.ceil(wl["ratio"] * L - 1e-9))
-    if overlap == "auto":
-        overlap = "da"
-    flags = {"da": 0, "serial": bnd.ESS_FLAG_SERIAL, "dba": bnd.ESS_FLAG_DBA}[overlap]
+    flags = {"da": 0, "serial": bnd.ESS_FLAG_SERIAL, "dba": bnd.ESS_FLAG_DBA, "auto": bnd.ESS_FLAG_AUTO}[overlap]
     cfg = bnd.make_config(B, T, L, wl["Hi"], wl["Di"], k, H, latent_fmt=bnd.ESS_FMT_FP8 if fp8 else bnd.ESS_FMT_BF16,
                           row_stride=stride, slots_per_seq=S, flags=flags)
     ctx = bnd.Context(cfg)
@@ -131,9 +133,9 @@ def algorithmic_bytes(W, misses_per_step):
     return dict(index_score=a1, topk=a2, attention_rows=a4, fill=fill)
 
 
-def measure(name, steps, warmup, overlap="auto", layers=None):
+def measure(name, steps, warmup, overlap="auto", layers=None, rho=None, ratio=None):
     import torch
-    W = build_workload(name, warmup + 2 * steps, overlap, layers)
+    W = build_workload(name, warmup + 2 * steps, overlap, layers, rho, ratio)
     nl = W["wl"]["layers"]
     ctx = W["ctx"]
     run_steps(W, 1, warmup)
@@ -177,7 +179,7 @@ def measure(name, steps, warmup, overlap="auto", layers=None):
         hbm_stream_GBs=hbm_stream_bytes / (hbm_stream_ms * 1e-3) / 1e9,
         hbm_stream_frac_of_peak=hbm_stream_bytes / (hbm_stream_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         whole_step_hbm_frac=(hbm_stream_bytes / (ms_step * 1e-3) / 1e9) / HBM_PEAK_GBS,
-        misses_per_step=misses_per_step,
+        misses_per_step=misses_per_step, overlap_used=("da", "dba", "serial")[ctx.last_overlap()],
         host_link_GBs=(ab["fill"] / (stage[5] * 1e-3) / 1e9) if stage[5] > 0 else None,
         host_link_frac_of_peak=(ab["fill"] / (stage[5] * 1e-3) / 1e9 / HOST_LINK_PEAK_GBS) if stage[5] > 0 else None,
         algorithmic_bytes=ab,
@@ -218,6 +220,110 @@ def cpu_baseline(W, budget_seqs):
                        % (n, wl["B"], W["name"], dt))
 
 
+def sweep_overlap(name, steps, warmup):
+    """Fetch overlap modes against the miss count (paper Sec. 3.3, the DA / DBA comparison): the step-to-step
+    overlap rho of the top-k sets sets the misses per sequence; every mode runs the same traces."""
+    import torch
+    rows = []
+    for rho in (0.98, 0.95, 0.9, 0.8, 0.7, 0.5, 0.3):
+        row = {"rho": rho}
+        for ov in ("serial", "da", "dba", "auto"):
+            W, r = measure(name, steps, warmup, ov, rho=rho)
+            row["misses_per_seq"] = r["misses_per_step"] / W["wl"]["B"]
+            row[ov + "_ms"] = r["ms_per_layer_step"]
+            if ov == "auto":
+                row["auto_used"] = r["overlap_used"]
+            W["ctx"].close(); del W
+            torch.cuda.empty_cache()
+        rows.append(row)
+        print("rho %.2f misses/seq %.0f serial %.3f da %.3f dba %.3f auto %.3f (%s) ms" % (
+            rho, row["misses_per_seq"], row["serial_ms"], row["da_ms"], row["dba_ms"], row["auto_ms"], row["auto_used"]),
+            file=sys.stderr, flush=True)
+    return rows
+
+
+def sweep_ratio(name, steps, warmup):
+    """Misses and step time against the Sparse Memory Ratio (paper Sec. 3.2 / 4), with the pool warmed by
+    `warmup` steps, and the misses of the first steps after a reset with and without LRU-Warmup (the sets of
+    32 earlier steps admitted through ess_cache_admit, oldest first)."""
+    import torch
+    rows = []
+    for ratio in (0.05, 0.1, 0.2, 0.3, 0.5, 1.0):
+        W, r = measure(name, steps, warmup, "da", ratio=ratio)
+        ctx, cache, B = W["ctx"], W["cache"], W["wl"]["B"]
+        first = {}
+        for mode in ("cold", "lru_warmup"):
+            ctx.cache_reset(cache, B)
+            if mode == "lru_warmup":
+                for s in range(32):
+                    ctx.cache_admit(cache, W["trace"][s][:, -1].contiguous(), s + 1)
+            torch.cuda.synchronize()
+            per_step = []
+            for s in range(4):
+                ctx.reset_stats()
+                run_steps(W, 33 + s, 1)
+                per_step.append(ctx.get_stats()["misses"] / B)
+            first[mode] = per_step
+        rows.append({"ratio": ratio, "slots_per_seq": W["S"], "misses_per_seq": r["misses_per_step"] / B,
+                     "ms_per_layer_step": r["ms_per_layer_step"], "fetch_ms": r["stage_ms"]["fetch"],
+                     "host_link_GBs": r["host_link_GBs"], "first_steps_cold": first["cold"],
+                     "first_steps_lru_warmup": first["lru_warmup"]})
+        print(json.dumps(rows[-1]), file=sys.stderr, flush=True)
+        ctx.close(); del W
+        torch.cuda.empty_cache()
+    return rows
+
+
+def sweep_granularity():
+    """Host-to-device rate of scattered Latent-Cache entries (paper Sec. 3.2): one memcpy call per entry
+    against the fetch kernel that reads the pinned pool through its device mapping, at both entry sizes."""
+    import torch
+    from paper_2512_10576_amd import binding as bnd
+    rows = []
+    B, L, k = 8, 131072, 2048
+    g = torch.Generator().manual_seed(7)
+    for stride, fmt in ((656, bnd.ESS_FMT_FP8), (1152, bnd.ESS_FMT_BF16)):
+        n = B * k
+        host = torch.empty((B, L, stride), dtype=torch.uint8, pin_memory=True)
+        host.random_(0, 255, generator=g)
+        dst = torch.empty((n, stride), dtype=torch.uint8, device="cuda")
+        pos = torch.stack([torch.randperm(L, generator=g)[:k] for _ in range(B)])             # [B,k] distinct per sequence
+        flat = (pos + torch.arange(B).unsqueeze(1) * L).reshape(-1).to(torch.int64).contiguous()
+        for rep in range(2):                                                                   # second pass timed
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            bnd.calib_memcpy_rows(dst, host, flat, stride, stride)
+            torch.cuda.synchronize()
+            dt_memcpy = time.perf_counter() - t0
+        ok = bool((dst.cpu() == host.view(-1, stride)[flat]).all())
+        # the fetch kernel on the same entries: an empty slot cache makes every selected entry a miss
+        cfg = bnd.make_config(B, 1, L, 64, 128, k, 128, latent_fmt=fmt, row_stride=stride, slots_per_seq=2 * k)
+        ctx = bnd.Context(cfg)
+        cache = bnd.Cache.allocate(cfg, B, host_pool=host)
+        ctx_len = torch.full((B,), L, dtype=torch.int32, device="cuda")
+        slot_idx = torch.empty((B, 1, k), dtype=torch.int32, device="cuda")
+        idx = pos.to(torch.int32).reshape(B, 1, k).cuda()
+        times = []
+        for rep in range(3):
+            ctx.cache_reset(cache, B)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            ctx.gather_latent(cache, idx, ctx_len, 1, slot_idx, None, None)
+            torch.cuda.synchronize()
+            times.append(time.perf_counter() - t0)
+        got = torch.gather(cache.slot_pool.view(B, 2 * k, stride), 1,
+                           slot_idx.view(B, k, 1).long().expand(B, k, stride)).reshape(n, stride)
+        ok = ok and bool((got.cpu() == host.view(-1, stride)[flat]).all())
+        rows.append({"entry_bytes": stride, "entries": n, "memcpy_per_entry_GBs": n * stride / dt_memcpy / 1e9,
+                     "memcpy_us_per_entry": dt_memcpy / n * 1e6, "fetch_kernel_GBs": n * stride / min(times) / 1e9,
+                     "fetch_includes": "bookkeeping kernel + fetch kernel, wall clock", "bytes_verified": ok})
+        print(json.dumps(rows[-1]), file=sys.stderr, flush=True)
+        ctx.close()
+        del host, dst, cache
+        torch.cuda.empty_cache()
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -225,14 +331,18 @@ def main():
     ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--workload", default="cfg4", choices=sorted(WORKLOADS))
     ap.add_argument("--overlap", default="auto", choices=["auto", "da", "dba", "serial"],
-                    help="overlap of the miss fetch (paper Sec. 3.3); auto = da (DBA is built and exact, but on this GPU the\n"
-                         "fetch slows the concurrent indexer enough to cancel its gain; see DESIGN.md)")
+                    help="overlap of the miss fetch (paper Sec. 3.3): da = fetch beside Attn0, dba = split batch, auto = the\n"
+                         "library picks one of the two per step from the previous step's miss count")
     ap.add_argument("--layers", type=int, default=None, help="layers run back to back per step (default: the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-32k", action="store_true", help="skip the extra 32K-context measurement (cfg2)")
     ap.add_argument("--cpu-seqs", type=int, default=16)
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic) so that rocprofv3 --pmc counters can be scaled")
+    ap.add_argument("--sweep", default=None, choices=["overlap", "ratio", "granularity"],
+                    help="instead of the benchmark line: overlap = serial / DA / DBA step time against the miss count; "
+                         "ratio = misses and step time against the Sparse Memory Ratio, with and without LRU-Warmup; "
+                         "granularity = per-entry memcpy against the fetch kernel (prints one JSON object)")
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the path shards by sequence with no collective); "
@@ -242,6 +352,13 @@ def main():
     from paper_2512_10576_amd import binding
     binding.load()                                   # fails loudly if the HIP library is missing
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+
+    if a.sweep:
+        rows = {"overlap": lambda: sweep_overlap(a.workload, a.steps, a.warmup),
+                "ratio": lambda: sweep_ratio(a.workload, a.steps, a.warmup),
+                "granularity": sweep_granularity}[a.sweep]()
+        print(json.dumps({"sweep": a.sweep, "workload": a.workload, "steps": a.steps, "warmup": a.warmup, "rows": rows}))
+        return
 
     if a.calib_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
@@ -263,7 +380,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": "%s: %s" % (a.workload, W["wl"]["desc"]), "indexer": "64 heads x 128 fp8 e4m3",
                    "topk": 2048, "attention": "128 heads x 576 bf16 absorbed MLA", "slots_per_seq": W["S"],
-                   "overlap": W["overlap"], "layers_per_step": res["layers"], "q_tokens": W["wl"]["T"]},
+                   "overlap": W["overlap"] + (" (ran %s)" % res["overlap_used"] if W["overlap"] == "auto" else ""),
+                   "layers_per_step": res["layers"], "q_tokens": W["wl"]["T"]},
         "roofline": roof,
         "stages": {k: res[k] for k in ("stage_ms", "hbm_stream_GBs", "hbm_stream_frac_of_peak", "whole_step_hbm_frac",
                                        "misses_per_step", "host_link_GBs", "host_link_frac_of_peak")},

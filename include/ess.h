@@ -61,6 +61,10 @@ typedef enum {
 #define ESS_FLAG_DBA 2u    /* ess_decode_step: DualBatch-Attention overlap (Sec. 3.3): the batch is processed in two
                               halves so that the second half's indexer and top-k overlap the first half's fetch */
 
+#define ESS_FLAG_AUTO 4u   /* ess_decode_step chooses per step between the DA and the DBA schedule from the miss
+                              counts of the previous step (the paper's switch on the number of misses, Sec. 3.3);
+                              threshold: ess_set_overlap_threshold.  Ignored with ESS_FLAG_SERIAL. */
+
 typedef struct ess_ctx ess_ctx;
 
 /* Fixed for the life of a context. */
@@ -172,6 +176,15 @@ int ess_sparse_mla_decode(ess_ctx* ctx, const void* q_bf16, const uint8_t* slot_
  * half's indexer and top-k (DBA overlap); results are identical in all modes. */
 int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* args, void* stream);
 
+/* ESS_FLAG_AUTO: the DBA schedule is used for a step when the previous bookkeeping of this context
+ * saw more than `misses_per_seq` misses per sequence on average (Sec. 3.3: DBA pays when the fetch is
+ * long), else the DA schedule.  The counts travel through pinned host memory and are read without
+ * waiting for the GPU, so the decision may lag by a step; results do not depend on it.  Default 400
+ * (measured crossover for 1152-byte entries, batch 64, 128K context on MI355X).
+ * ess_last_overlap: schedule the latest ess_decode_step used: 0 DA, 1 DBA, 2 serial. */
+int ess_set_overlap_threshold(ess_ctx* ctx, int32_t misses_per_seq);
+int ess_last_overlap(const ess_ctx* ctx, int32_t* mode);
+
 /* Counters accumulated by ess_gather_latent / ess_cache_admit / ess_decode_step
  * since the last ess_reset_stats.  ess_get_stats WAITS for `stream` and the
  * side stream. */
@@ -201,6 +214,13 @@ int ess_profile_select(ess_ctx* ctx, uint32_t stage_mask, int32_t every);
 /* A plain device-to-device copy kernel (reads `bytes`, writes `bytes`; bytes a multiple of 16,
  * pointers 16-byte aligned): known traffic against which hardware counters can be scaled. */
 int ess_calib_copy(void* dst, const void* src, size_t bytes, void* stream);
+/* The transfer the paper starts from (Sec. 3.2, the per-block copy that FlashTrans replaces): one
+ * hipMemcpyAsync per entry, n entries of row_bytes each, entry i from
+ * host_pool + host_rows[i] * row_stride (pinned host memory, HOST pointer) to
+ * dst + i * row_stride (device).  host_rows is a HOST array.  Enqueues on `stream`, returns without
+ * synchronizing.  For the granularity comparison only; no stage of the path uses it. */
+int ess_calib_memcpy_rows(void* dst, const void* host_pool, const int64_t* host_rows, int64_t n,
+                          int32_t row_bytes, int32_t row_stride, void* stream);
 
 #ifdef __cplusplus
 }

@@ -21,6 +21,7 @@ ESS_ERR_INVALID_ARG, ESS_ERR_UNSUPPORTED, ESS_ERR_CAPACITY, ESS_ERR_NOMEM, ESS_E
 ESS_FMT_BF16, ESS_FMT_FP8 = 0, 1
 ESS_FLAG_SERIAL = 1
 ESS_FLAG_DBA = 2
+ESS_FLAG_AUTO = 4
 
 
 class EssConfig(C.Structure):
@@ -81,6 +82,9 @@ def load() -> C.CDLL:
         "ess_profile_enable": [vp, i32],
         "ess_profile_select": [vp, u32, i32],
         "ess_calib_copy": [vp, vp, C.c_size_t, vp],
+        "ess_set_overlap_threshold": [vp, i32],
+        "ess_last_overlap": [vp, C.POINTER(i32)],
+        "ess_calib_memcpy_rows": [vp, vp, vp, C.c_int64, i32, i32, vp],
         "ess_profile_read": [vp, C.POINTER(C.c_float), C.POINTER(i32)],
     }
     for name, args in sigs.items():
@@ -137,6 +141,14 @@ def workspace_bytes(cfg: EssConfig) -> int:
 def calib_copy(dst, src):
     """plain copy kernel of known traffic (measurement support)"""
     _check(load().ess_calib_copy(_ptr(dst, torch.uint8), _ptr(src, torch.uint8), src.numel(), _stream()))
+
+
+def calib_memcpy_rows(dst, host_pool, host_rows, row_bytes, row_stride):
+    """one hipMemcpyAsync per entry: pinned `host_pool` rows `host_rows` (CPU int64 tensor) -> `dst` rows 0..n-1"""
+    assert host_pool.is_pinned() and host_rows.dtype == torch.int64 and not host_rows.is_cuda and host_rows.is_contiguous()
+    _check(load().ess_calib_memcpy_rows(_ptr(dst, torch.uint8), C.c_void_p(host_pool.data_ptr()),
+                                        C.c_void_p(host_rows.data_ptr()), host_rows.numel(), row_bytes, row_stride,
+                                        _stream()))
 
 
 class Cache:
@@ -218,6 +230,15 @@ class Context:
                         _ptr(out_bf16, torch.bfloat16), _ptr(lse, torch.float32, optional=True),
                         _ptr(miss_count, torch.int32, optional=True))
         _check(self.lib.ess_decode_step(self.h, C.byref(cache.c), C.byref(a), _stream()))
+
+    def set_overlap_threshold(self, misses_per_seq):
+        _check(self.lib.ess_set_overlap_threshold(self.h, misses_per_seq))
+
+    def last_overlap(self) -> int:
+        """schedule of the latest decode_step: 0 DA, 1 DBA, 2 serial"""
+        m = C.c_int32(-1)
+        _check(self.lib.ess_last_overlap(self.h, C.byref(m)))
+        return m.value
 
     def get_stats(self) -> dict:
         s = EssStats()

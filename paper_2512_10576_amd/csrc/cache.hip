@@ -90,7 +90,7 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
     int32_t* __restrict__ hit_list, int32_t* __restrict__ miss_list, int32_t* __restrict__ n_hit,
     int32_t* __restrict__ n_miss, int32_t* __restrict__ fill_tok, int32_t* __restrict__ fill_slot, int fill_cap,
     int32_t* __restrict__ miss_cnt, int32_t* __restrict__ miss_count_out, unsigned long long* __restrict__ stats,
-    int row_stride, int count_step) {
+    int row_stride, int count_step, int32_t* __restrict__ host_miss) {
   extern __shared__ uint32_t bm[];             // [W] bitmap of the missed positions
   __shared__ BookShared sm;
   constexpr int RS = 16;                       // register-held stamps per thread
@@ -250,6 +250,7 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
   if (tid == 0) {
     miss_cnt[b] = (int32_t)m;
     if (miss_count_out) miss_count_out[b] = (int32_t)m;
+    if (host_miss) host_miss[b] = (int32_t)m;       // pinned host memory: the host's view for the overlap switch
     if (b == 0 && count_step) atomicAdd(&stats[0], 1ull);
     atomicAdd(&stats[1], (unsigned long long)nvalid);
     atomicAdd(&stats[2], (unsigned long long)m);
@@ -294,13 +295,15 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
 }
 
 // Fetch: one wave per missed entry, rows copied host pool -> slot pool in 16-byte pieces, two
-// entries per wave in flight at once.  The kernel is a handful of 1024-thread workgroups that loop
-// over all sequences: its waves spend their life waiting on the host link, and the attention kernel
-// that runs beside it needs whole CUs (one wave per SIMD with a large register file), so the fetch
-// must stay on a few CUs instead of sprinkling one wave onto every SIMD of the chip.
-constexpr int FILL_WGS = 64;
+// entries per wave in flight at once.  The kernel is a handful of 512-thread workgroups that loop
+// over all sequences: its waves spend their life waiting on the host link.  The number of workgroups
+// sets how many bytes are in flight on the link: 64 (1.2 MB in flight) reach 53 GB/s, 32 reach
+// 50 GB/s, 16 reach 48 GB/s, 8 only 27 GB/s.  Requests waiting for the link also hold up the other
+// kernels' HBM traffic: beside a 64-workgroup fetch every kernel measured (index score, top-k,
+// attention) takes about 2.2x its time alone, beside a 32-workgroup fetch about 1.3x.  With one fetch
+// per step only Attn0 runs beside it and has time to spare, so the fetch gets 64 workgroups; the
+// split-batch schedule puts critical-path kernels beside the fetch and asks for 32.
 constexpr int FILL_WPB = 8;                                 // waves per workgroup
-constexpr int FILL_WAVES = FILL_WGS * FILL_WPB;
 constexpr int FILL_MAX_B = 4096;
 
 __global__ __launch_bounds__(FILL_WPB * 64) void k_fill(const uint8_t* __restrict__ host_pool, uint8_t* __restrict__ slot_pool,
@@ -325,6 +328,7 @@ __global__ __launch_bounds__(FILL_WPB * 64) void k_fill(const uint8_t* __restric
   __syncthreads();
   const int M = pref[B];
   const int gw = blockIdx.x * FILL_WPB + (tid >> 6);         // wave index in the grid
+  const int FILL_WAVES = gridDim.x * FILL_WPB;
   const int chunks = row_stride >> 4;                        // <= 128 for the supported entry sizes
   const int c0 = lane, c1 = lane + 64;
   auto locate = [&](int r, const uint4*& src, uint4*& dst) { // r-th entry of the flattened list
@@ -434,15 +438,16 @@ int ess_launch_bookkeeping(ess_ctx* ctx, const ess_cache& cache, const int32_t* 
                      lists ? ctx->hit_list + lo : nullptr, lists ? ctx->miss_list + lo : nullptr,
                      ctx->n_hit + (size_t)b0 * T, ctx->n_miss + (size_t)b0 * T, ctx->fill_tok + (size_t)b0 * cap,
                      ctx->fill_slot + (size_t)b0 * cap, cap, ctx->miss_cnt + b0, miss_count_out, ctx->stats,
-                     c.row_stride, count_step ? 1 : 0);
+                     c.row_stride, count_step ? 1 : 0, (c.flags & ESS_FLAG_AUTO) ? ctx->host_miss_dev + b0 : nullptr);
   ESS_HIP(hipGetLastError());
   return ESS_OK;
 }
 
-int ess_launch_fill(ess_ctx* ctx, const ess_cache& cache, int B, hipStream_t st, int b0) {
+int ess_launch_fill(ess_ctx* ctx, const ess_cache& cache, int B, hipStream_t st, int b0, int wgs) {
+  wgs = wgs < 1 ? 1 : (wgs > 256 ? 256 : wgs);
   const ess_config& c = ctx->cfg;
   const int cap = c.max_q_tokens * c.topk;
-  hipLaunchKernelGGL(k_fill, dim3(FILL_WGS), dim3(FILL_WPB * 64), (size_t)(B + 1) * sizeof(int32_t), st, cache.host_pool_dev, cache.slot_pool,
+  hipLaunchKernelGGL(k_fill, dim3(wgs), dim3(FILL_WPB * 64), (size_t)(B + 1) * sizeof(int32_t), st, cache.host_pool_dev, cache.slot_pool,
                      ctx->fill_tok + (size_t)b0 * cap, ctx->fill_slot + (size_t)b0 * cap, cap, ctx->miss_cnt + b0, B,
                      c.max_ctx, c.slots_per_seq, c.row_stride);
   ESS_HIP(hipGetLastError());

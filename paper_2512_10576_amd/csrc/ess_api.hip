@@ -133,21 +133,21 @@ ess_cache shift_cache(const ess_config& c, const ess_cache& in, int b0) {
 // ev_fill[half] must still be waited for before the fetched rows are read.
 int run_cache_step(ess_ctx* ctx, const ess_cache& cache, const int32_t* idx, int B, int T, int kk, uint32_t step,
                    int32_t* slot_idx, int32_t* miss_count, hipStream_t st, bool* fill_pending, int b0 = 0,
-                   int half = 0, hipEvent_t* fill_ev = nullptr) {
+                   int half = 0, hipEvent_t* fill_ev = nullptr, int fill_wgs = 64) {
   *fill_pending = false;
   int rc = ess_launch_bookkeeping(ctx, cache, idx, B, T, kk, step, slot_idx, miss_count, st, b0, half == 0);
   if (rc != ESS_OK) return rc;
   if (!cache.host_pool_dev) return ESS_OK;      // nothing offloaded: no entry can be missing
   if (ctx->cfg.flags & ESS_FLAG_SERIAL) {
     if (fill_ev) ESS_HIP(hipEventRecord(fill_ev[0], st));
-    rc = ess_launch_fill(ctx, cache, B, st, b0);
+    rc = ess_launch_fill(ctx, cache, B, st, b0, fill_wgs);
     if (rc == ESS_OK && fill_ev) ESS_HIP(hipEventRecord(fill_ev[1], st));
     return rc;
   }
   ESS_HIP(hipEventRecord(ctx->ev_book[half], st));
   ESS_HIP(hipStreamWaitEvent(ctx->side, ctx->ev_book[half], 0));
   if (fill_ev) ESS_HIP(hipEventRecord(fill_ev[0], ctx->side));
-  rc = ess_launch_fill(ctx, cache, B, ctx->side, b0);
+  rc = ess_launch_fill(ctx, cache, B, ctx->side, b0, fill_wgs);
   if (rc != ESS_OK) return rc;
   if (fill_ev) ESS_HIP(hipEventRecord(fill_ev[1], ctx->side));
   ESS_HIP(hipEventRecord(ctx->ev_fill[half], ctx->side));
@@ -217,6 +217,7 @@ int ess_create(const ess_config* cfg, ess_ctx** out) {
       if (ctx->ev_fill[h]) (void)hipEventDestroy(ctx->ev_fill[h]);
     }
     if (ctx->side) (void)hipStreamDestroy(ctx->side);
+    if (ctx->host_miss) (void)hipHostFree(ctx->host_miss);
     (void)hipFree(base);
     delete ctx;
     return ess_fail(ESS_ERR_HIP, "%s: %s", what, hipGetErrorString(err));
@@ -227,6 +228,12 @@ int ess_create(const ess_config* cfg, ess_ctx** out) {
     if ((e = hipEventCreateWithFlags(&ctx->ev_fill[h], hipEventDisableTiming)) != hipSuccess) return bail("hipEventCreate", e);
   }
   if ((e = hipMemset(ctx->stats, 0, 32)) != hipSuccess) return bail("hipMemset", e);
+  if ((e = hipHostMalloc(reinterpret_cast<void**>(&ctx->host_miss), (size_t)cfg->max_batch * sizeof(int32_t),
+                         hipHostMallocMapped)) != hipSuccess) return bail("hipHostMalloc", e);
+  memset(ctx->host_miss, 0, (size_t)cfg->max_batch * sizeof(int32_t));
+  if ((e = hipHostGetDevicePointer(reinterpret_cast<void**>(&ctx->host_miss_dev), ctx->host_miss, 0)) != hipSuccess)
+    return bail("hipHostGetDevicePointer", e);
+  ctx->auto_threshold = 400;
   *out = ctx;
   return ESS_OK;
 }
@@ -240,6 +247,7 @@ int ess_destroy(ess_ctx* ctx) {
     (void)hipEventDestroy(ctx->ev_fill[h]);
   }
   (void)hipStreamDestroy(ctx->side);
+  (void)hipHostFree(ctx->host_miss);
   (void)hipFree(ctx->score_ws);                 // base of the workspace
   delete ctx;
   return ESS_OK;
@@ -369,7 +377,16 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
   const bool offloaded = cache->host_pool_dev != nullptr;
   // DualBatch-Attention overlap (Sec. 3.3): the batch is cut in two halves so that the second half's
   // indexer and top-k run while the first half's fetch is in flight
-  const bool dba = offloaded && (c.flags & ESS_FLAG_DBA) && !(c.flags & ESS_FLAG_SERIAL) && B >= 2;
+  bool want_dba = (c.flags & ESS_FLAG_DBA) != 0;
+  if ((c.flags & ESS_FLAG_AUTO) && offloaded) {
+    // miss counts of the latest bookkeeping as the host sees them now (no wait: possibly a step old)
+    const volatile int32_t* hm = ctx->host_miss;
+    long sum = 0;
+    for (int b = 0; b < B; ++b) sum += hm[b];
+    want_dba = sum > (long)ctx->auto_threshold * B;
+  }
+  const bool dba = offloaded && want_dba && !(c.flags & ESS_FLAG_SERIAL) && B >= 2;
+  ctx->last_overlap = (c.flags & ESS_FLAG_SERIAL) ? 2 : (dba ? 1 : 0);
   const int nh = dba ? 2 : 1;
   const int hb0[2] = {0, B / 2};
   const int hB[2] = {dba ? B / 2 : B, B - B / 2};
@@ -409,7 +426,7 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     hipEvent_t* fev = (pev && h < ESS_PROF_FILL && ((ctx->prof_mask >> 5) & 1u)) ? pev + ESS_PROF_MAIN + 2 * h : nullptr;
     ESS_BEGIN(2);
     rc = run_cache_step(ctx, ch, used, Bh, T, c.topk, a->step, ctx->slot_idx_ws + bt0 * k,
-                        a->miss_count ? a->miss_count + b0 : nullptr, st, &pending[h], b0, h, fev);
+                        a->miss_count ? a->miss_count + b0 : nullptr, st, &pending[h], b0, h, fev, dba ? 32 : 64);
     if (rc != ESS_OK) return rc;
     if (fev) ctx->prof_nfill[pslot] = h + 1;
     ESS_END(2);
@@ -465,6 +482,33 @@ int ess_calib_copy(void* dst, const void* src, size_t bytes, void* stream) {
   if (!dst || !src || (bytes & 15) || !aligned16(dst) || !aligned16(src))
     return ess_fail(ESS_ERR_INVALID_ARG, "calib copy needs 16-byte aligned pointers and size");
   return ess_launch_calib_copy(dst, src, bytes, static_cast<hipStream_t>(stream));
+}
+
+int ess_set_overlap_threshold(ess_ctx* ctx, int32_t misses_per_seq) {
+  if (!ctx) return ess_fail(ESS_ERR_INVALID_ARG, "context is NULL");
+  if (misses_per_seq < 0) return ess_fail(ESS_ERR_INVALID_ARG, "threshold %d", misses_per_seq);
+  ctx->auto_threshold = misses_per_seq;
+  return ESS_OK;
+}
+
+int ess_last_overlap(const ess_ctx* ctx, int32_t* mode) {
+  if (!ctx || !mode) return ess_fail(ESS_ERR_INVALID_ARG, "NULL argument");
+  *mode = ctx->last_overlap;
+  return ESS_OK;
+}
+
+int ess_calib_memcpy_rows(void* dst, const void* host_pool, const int64_t* host_rows, int64_t n, int32_t row_bytes,
+                          int32_t row_stride, void* stream) {
+  if (!dst || !host_pool || !host_rows || n < 0 || row_bytes < 1 || row_stride < row_bytes)
+    return ess_fail(ESS_ERR_INVALID_ARG, "memcpy rows: bad argument");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  for (int64_t i = 0; i < n; ++i) {
+    if (host_rows[i] < 0) return ess_fail(ESS_ERR_INVALID_ARG, "memcpy rows: negative row index");
+    ESS_HIP(hipMemcpyAsync(static_cast<uint8_t*>(dst) + (size_t)i * row_stride,
+                           static_cast<const uint8_t*>(host_pool) + (size_t)host_rows[i] * row_stride, (size_t)row_bytes,
+                           hipMemcpyHostToDevice, st));
+  }
+  return ESS_OK;
 }
 
 int ess_profile_select(ess_ctx* ctx, uint32_t stage_mask, int32_t every) {

@@ -33,6 +33,12 @@ struct ess_ctx {
   float* lse_part;              // [B*T, ESS_MAX_SPLITS, H]
   unsigned long long* stats;    // [4]
   size_t ws_bytes;
+  // overlap switch (ESS_FLAG_AUTO): per-sequence miss counts of the latest bookkeeping, written by the
+  // kernel into pinned host memory and read by the host, without a synchronisation, at the next step
+  int32_t* host_miss;           // [max_batch] host address
+  int32_t* host_miss_dev;       // device alias of the same memory
+  int32_t auto_threshold;       // mean misses per sequence above which the split-batch schedule is used
+  int32_t last_overlap;         // schedule of the latest ess_decode_step: 0 DA, 1 DBA, 2 serial
   // optional stage timing (ess_profile_enable)
   hipEvent_t* prof_ev;          // [prof_cap][ESS_PROF_EVENTS]: marks on the caller's stream, then pairs around each fetch
   int8_t* prof_tag;             // [prof_cap][ESS_PROF_MAIN] stage a mark closes (-1 = start)
@@ -68,7 +74,7 @@ int ess_launch_cache_reset(const ess_config& c, const ess_cache& cache, int B, h
 int ess_launch_bookkeeping(ess_ctx* ctx, const ess_cache& cache, const int32_t* idx, int B, int T, int kk,
                            uint32_t step, int32_t* slot_idx, int32_t* miss_count_out, hipStream_t st, int b0 = 0,
                            bool count_step = true);
-int ess_launch_fill(ess_ctx* ctx, const ess_cache& cache, int B, hipStream_t st, int b0 = 0);
+int ess_launch_fill(ess_ctx* ctx, const ess_cache& cache, int B, hipStream_t st, int b0 = 0, int wgs = 64);
 int ess_launch_gather_rows(const ess_config& c, const uint8_t* slot_pool, const int32_t* slot_idx, int B, int T,
                            uint8_t* rows_out, hipStream_t st);
 // attention over list[b,t,0..n) (n = n_list[b,t], or k when n_list is NULL), written as `nsplit`

@@ -134,7 +134,8 @@ class TopkTrace:
         return torch.cat([kept, fresh], dim=1)
 
     def next(self):
-        """int32 [B,T,k] index sets for the next step (order within a set is arbitrary)."""
+        """int32 [B,T,k] index sets for the next step, each in ascending order (the order in which the
+        top-k kernel emits its selection)."""
         sets = []
         for t in range(self.T):
             vis = (self.ctx_len - (self.T - 1 - t)).clamp(min=0)
@@ -145,4 +146,4 @@ class TopkTrace:
             sets.append(self._draw(vis, base, frac))
         cur = torch.stack(sets, dim=1)
         self.prev = cur
-        return cur.to(torch.int32)
+        return cur.sort(dim=-1).values.to(torch.int32)

@@ -243,9 +243,10 @@ def test_sparse_mla_decode_vs_oracle(ess_lib, name, B, T, H, L, k, fmt, scale):
 
 
 # ---------------------------------------------------------------- whole step
-@pytest.mark.parametrize("flags,fmt", [(0, 0), (1, 0), (2, 0), (0, 1), (2, 1)])
+@pytest.mark.parametrize("flags,fmt", [(0, 0), (1, 0), (2, 0), (4, 0), (0, 1), (2, 1)])
 def test_decode_step_offloaded_vs_oracle(ess_lib, flags, fmt):
-    """T = 2 (causal offset), offloaded entries in both storage formats, all overlap modes"""
+    """T = 2 (causal offset), offloaded entries in both storage formats, all overlap modes (4 = switch
+    between DA and DBA on the miss count of the previous step)"""
     from paper_2512_10576_amd import binding as bnd
     print("decode_step offload flags", flags, "fmt", fmt, flush=True)
     B, T, Hi, Di, L, k, H, S = 3, 2, 64, 128, 6000, 512, 128, 1500
@@ -263,6 +264,9 @@ def test_decode_step_offloaded_vs_oracle(ess_lib, flags, fmt):
     cache = bnd.Cache.allocate(ctx.cfg, B, host_pool=hp,
                                slot_pool=torch.full((B, S, stride), poison, dtype=torch.uint8, device="cuda"))
     ctx.cache_reset(cache, B)
+    if flags == 4:
+        ctx.set_overlap_threshold(400)       # step 1 misses everything, later steps about a third of it
+    modes = []
     oc = O.SlotCache(B, L, S)
     opool = np.full((B, S, stride), poison, np.uint8)
     trace = synth.TopkTrace(9, ctx_len, T, k, 0.7)
@@ -280,6 +284,7 @@ def test_decode_step_offloaded_vs_oracle(ess_lib, flags, fmt):
         ctx.decode_step(cache, dev[0], dev[1], dev[2], dev[3], q.cuda(), step, idx_out, out, lse, mc,
                         None if ov is None else ov.cuda())
         torch.cuda.synchronize()
+        modes.append((ctx.last_overlap(), float(r["miss_count"].mean())))
         _topk_sets_equal(idx_out.cpu().numpy(), r["idx"])
         assert np.array_equal(mc.cpu().numpy(), r["miss_count"])
         assert np.array_equal(cache.slot_of.cpu().numpy(), oc.slot_of)
@@ -287,10 +292,17 @@ def test_decode_step_offloaded_vs_oracle(ess_lib, flags, fmt):
         _check_attn(out, lse, r["out"], r["lse"])
         outs.append((out.clone(), lse.clone()))
     ctx.close()
+    if flags == 4:                           # the schedule follows the previous step's misses
+        assert modes[0][0] == 0
+        for (mode, _), (_, prev_miss) in zip(modes[1:], modes[:-1]):
+            assert mode == (1 if prev_miss > 400 else 0), modes
+        assert {m for m, _ in modes} == {0, 1}, modes
+    else:
+        assert all(m == {0: 0, 1: 2, 2: 1}[flags] for m, _ in modes), modes
     test_decode_step_offloaded_vs_oracle.results = getattr(test_decode_step_offloaded_vs_oracle, "results", {})
     test_decode_step_offloaded_vs_oracle.results[(flags, fmt)] = outs
     res = test_decode_step_offloaded_vs_oracle.results
-    for other in (1, 2):                                             # DA, serial and DBA runs agree bit for bit
+    for other in (1, 2, 4):                                          # DA, serial, DBA and switching runs agree bit for bit
         if (0, fmt) in res and (other, fmt) in res:
             for (o0, l0), (o1, l1) in zip(res[(0, fmt)], res[(other, fmt)]):
                 assert torch.equal(o0, o1) and torch.equal(l0, l1)
