@@ -29,7 +29,10 @@ Pins (see tests/test_oracle_*.py): every function below is pinned to
 something other than itself -- int64 brute force, exhaustive Python sort,
 torch's scaled_dot_product_attention on the CPU with an additive mask,
 torch's float8_e4m3fn / bfloat16 casts, a textbook OrderedDict LRU in the
-one-access-per-step special case, closed forms and invariants.  The LRU
+one-access-per-step special case, closed forms and invariants; the append
+against a hand-worked example (tests/golden), the same OrderedDict LRU, and
+a decode loop over an appended context against the same loop over a context
+built whole.  The LRU
 bookkeeping for several accesses per step has no counterpart printed in the
 paper: beyond the special case and the invariants it is "parity unpinned"
 against the paper.
@@ -350,6 +353,60 @@ def merge_partials(o0, l0, o1, l1):
         w1 = np.where(np.isneginf(l1), 0.0, np.exp(l1 - lse))
     out = w0[..., None] * np.asarray(o0, dtype=np.float64) + w1[..., None] * np.asarray(o1, dtype=np.float64)
     return out, lse
+
+
+# --------------------------------------------------------------------------
+# append: the entries the step itself produces
+# --------------------------------------------------------------------------
+def append_tokens(cache: SlotCache, key_u8, host_pool, slot_pool, ctx_len,
+                  new_key_u8, new_rows, step_no: int) -> np.ndarray:
+    """Sec. 3.3: after a step the newly generated entries go into the caches.
+    For sequence b with L0 = ctx_len[b], the t-th of its T new tokens gets
+    position p = L0 + t (tokens that would pass Lmax are dropped):
+
+      * its index key is written into the Indexer-Cache (GPU): key[b,p] = new_key[b,t];
+      * its Latent-Cache entry is written back to the CPU-side Total Memory
+        Pool (the paper's D2H transfer): host_pool[b,p] = new_rows[b,t];
+      * reading (the paper does not say whether the new entry also enters the
+        GPU pool): it is admitted to the Sparse Memory Pool as the most
+        recently used entry -- the slot smallest in (stamp, slot index) among
+        slots with stamp < step_no is taken, exactly the victim rule of
+        SlotCache.step; its former token becomes non-resident; the slot gets
+        stamp step_no and the entry's bytes.  With no slot below step_no the
+        entry simply stays non-resident (it is in the host pool);
+      * fully resident mode (host_pool None, S = Lmax, slot = position):
+        the entry goes to slot p;
+      * ctx_len[b] = L0 + (number of tokens placed).
+
+    All arrays are updated in place; returns int32 [B,T] with the slot each
+    new token went to (-1 = dropped or not admitted)."""
+    B, T = new_key_u8.shape[:2]
+    Lmax = key_u8.shape[1]
+    placed = np.full((B, T), -1, dtype=np.int32)
+    for b in range(B):
+        L0 = int(ctx_len[b])
+        n = max(0, min(T, Lmax - L0))
+        for t in range(n):
+            p = L0 + t
+            key_u8[b, p] = new_key_u8[b, t]
+            if host_pool is None:
+                v = p
+            else:
+                host_pool[b, p] = new_rows[b, t]
+                cand = np.nonzero(cache.stamp[b] < step_no)[0]
+                if cand.size == 0:
+                    continue
+                v = int(cand[np.lexsort((cand, cache.stamp[b, cand]))[0]])
+            old = cache.token_of[b, v]
+            if old >= 0:
+                cache.slot_of[b, old] = -1
+            cache.token_of[b, v] = p
+            cache.slot_of[b, p] = v
+            cache.stamp[b, v] = step_no
+            slot_pool[b, v] = new_rows[b, t]
+            placed[b, t] = v
+        ctx_len[b] = L0 + n
+    return placed
 
 
 # --------------------------------------------------------------------------
