@@ -119,6 +119,8 @@ def run_steps(W, first_step, n):
         for cache, key in zip(W["caches"], W["keys"]):
             ctx.decode_step(cache, W["q_idx"], W["w"], key, W["ctx_len"], W["q_attn"], s, W["idx_out"],
                             W["out"], W["lse"], W["miss"], ov)
+            if W.get("append"):                      # the step's new entries enter the caches; the context grows
+                ctx.append(cache, W["new_key"], W["new_rows"], key, W["ctx_len"], s)
 
 
 def algorithmic_bytes(W, misses_per_step):
@@ -133,9 +135,19 @@ def algorithmic_bytes(W, misses_per_step):
     return dict(index_score=a1, topk=a2, attention_rows=a4, fill=fill)
 
 
-def measure(name, steps, warmup, overlap="auto", layers=None, rho=None, ratio=None):
+def measure(name, steps, warmup, overlap="auto", layers=None, rho=None, ratio=None, append=False):
     import torch
     W = build_workload(name, warmup + 2 * steps, overlap, layers, rho, ratio)
+    if append:
+        from paper_2512_10576_amd import synth
+        assert W["wl"]["layers"] == 1, "--append: one layer (the layers of a workload share ctx_len)"
+        wl = W["wl"]
+        _, _, nk = synth.indexer_inputs(77, wl["B"], 1, wl["Hi"], wl["Di"], wl["T"], wl["qk_max"], wl["w_levels"],
+                                        wl["w_den"], device="cuda")
+        rows = synth.latent_rows_fp8 if W["fmt"] == 1 else synth.latent_rows_bf16
+        W["new_key"] = nk.contiguous()
+        W["new_rows"] = rows(78, wl["B"] * wl["T"], device="cuda").reshape(wl["B"], wl["T"], W["stride"]).contiguous()
+        W["append"] = True
     nl = W["wl"]["layers"]
     ctx = W["ctx"]
     run_steps(W, 1, warmup)
@@ -314,7 +326,31 @@ def sweep_granularity():
         got = torch.gather(cache.slot_pool.view(B, 2 * k, stride), 1,
                            slot_idx.view(B, k, 1).long().expand(B, k, stride)).reshape(n, stride)
         ok = ok and bool((got.cpu() == host.view(-1, stride)[flat]).all())
+        # write-back direction: ess_append of 2 new entries for each of 4096 sequences (stores through the
+        # device mapping of the pinned pool), timed over the whole call
+        Ba, Ta, La = 4096, 2, 64
+        cfg_a = bnd.make_config(Ba, Ta, La, 4, 32, 8, 8, latent_fmt=fmt, row_stride=stride, slots_per_seq=16)
+        ctx_a = bnd.Context(cfg_a)
+        host_a = torch.zeros((Ba, La, stride), dtype=torch.uint8, pin_memory=True)
+        cache_a = bnd.Cache.allocate(cfg_a, Ba, host_pool=host_a)
+        ctx_a.cache_reset(cache_a, Ba)
+        key_a = torch.zeros((Ba, La, 32), dtype=torch.uint8, device="cuda")
+        nk_a = torch.ones((Ba, Ta, 32), dtype=torch.uint8, device="cuda")
+        nr_a = torch.empty((Ba, Ta, stride), dtype=torch.uint8, device="cuda").random_(0, 255)
+        len_a = torch.zeros((Ba,), dtype=torch.int32, device="cuda")
+        t_app = []
+        for rep in range(4):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            ctx_a.append(cache_a, nk_a, nr_a, key_a, len_a, rep + 1)
+            torch.cuda.synchronize()
+            t_app.append(time.perf_counter() - t0)
+        ok = ok and bool((host_a[:, 6:8] == nr_a.cpu()).all()) and int(len_a.min()) == 8
+        d2h = Ba * Ta * stride / min(t_app) / 1e9
+        ctx_a.close()
+        del host_a, cache_a
         rows.append({"entry_bytes": stride, "entries": n, "memcpy_per_entry_GBs": n * stride / dt_memcpy / 1e9,
+                     "append_writeback_GBs": d2h, "append_entries": Ba * Ta,
                      "memcpy_us_per_entry": dt_memcpy / n * 1e6, "fetch_kernel_GBs": n * stride / min(times) / 1e9,
                      "fetch_includes": "bookkeeping kernel + fetch kernel, wall clock", "bytes_verified": ok})
         print(json.dumps(rows[-1]), file=sys.stderr, flush=True)
@@ -339,6 +375,9 @@ def main():
     ap.add_argument("--cpu-seqs", type=int, default=16)
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic) so that rocprofv3 --pmc counters can be scaled")
+    ap.add_argument("--append", action="store_true",
+                    help="after every layer-step write the step's new entries into the caches (ess_append): the context "
+                         "grows by T per step (default: context held fixed, as the baseline workload states)")
     ap.add_argument("--sweep", default=None, choices=["overlap", "ratio", "granularity"],
                     help="instead of the benchmark line: overlap = serial / DA / DBA step time against the miss count; "
                          "ratio = misses and step time against the Sparse Memory Ratio, with and without LRU-Warmup; "
@@ -368,7 +407,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    W, res = measure(a.workload, a.steps, a.warmup, a.overlap, a.layers)
+    W, res = measure(a.workload, a.steps, a.warmup, a.overlap, a.layers, append=a.append)
     ab = res["algorithmic_bytes"]
     roof = dict(bound="hbm", kernel="k_index_score", achieved=res["index_score_GBs"], peak=HBM_PEAK_GBS, unit="GB/s",
                 frac=res["index_score_GBs"] / HBM_PEAK_GBS, traffic=MEASURED_TRAFFIC_BYTES.get(a.workload),
@@ -381,7 +420,8 @@ def main():
         "config": {"workload": "%s: %s" % (a.workload, W["wl"]["desc"]), "indexer": "64 heads x 128 fp8 e4m3",
                    "topk": 2048, "attention": "128 heads x 576 bf16 absorbed MLA", "slots_per_seq": W["S"],
                    "overlap": W["overlap"] + (" (ran %s)" % res["overlap_used"] if W["overlap"] == "auto" else ""),
-                   "layers_per_step": res["layers"], "q_tokens": W["wl"]["T"]},
+                   "layers_per_step": res["layers"], "q_tokens": W["wl"]["T"],
+                   "context": "grows by T per step (ess_append after every step)" if a.append else "fixed"},
         "roofline": roof,
         "stages": {k: res[k] for k in ("stage_ms", "hbm_stream_GBs", "hbm_stream_frac_of_peak", "whole_step_hbm_frac",
                                        "misses_per_step", "host_link_GBs", "host_link_frac_of_peak")},

@@ -185,6 +185,25 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
 int ess_set_overlap_threshold(ess_ctx* ctx, int32_t misses_per_seq);
 int ess_last_overlap(const ess_ctx* ctx, int32_t* mode);
 
+/* Append (Sec. 3.3, the write-back of newly generated entries): for each sequence b with
+ * L0 = ctx_len[b], the t-th of its T new tokens takes position p = L0 + t:
+ *   - key_fp8[b,p,:]  = new_key_fp8[b,t,:]            (Indexer-Cache, device, written)
+ *   - host pool[b,p,:] = new_rows[b,t,:]              (through cache->host_pool_dev, which must then be a
+ *                                                     writable mapping; skipped when it is NULL)
+ *   - the entry is admitted to the slot pool as most recently used: it takes the slot smallest in
+ *     (stamp, slot index) among slots with stamp < step (the victim rule of the bookkeeping; the
+ *     former token of that slot becomes non-resident), gets stamp `step` and its bytes are written
+ *     into the slot.  If every slot carries stamp `step` the entry is not admitted (it is in the host
+ *     pool).  Without a host pool the slot is p itself.
+ *   - ctx_len[b] = L0 + min(T, max_ctx - L0)  (device, in/out); tokens past max_ctx are dropped.
+ * new_key_fp8 [B,T,idx_dim], new_rows [B,T,row_stride] (entries in the pool's storage format), both
+ * device, 16-byte aligned.  placed [B,T] (device, may be NULL) receives the slot of each new token,
+ * -1 if dropped or not admitted.  Call it on the stream of the decode steps, after the step that
+ * produced the entries; `step` is that step's number or a later one. */
+int ess_append(ess_ctx* ctx, const ess_cache* cache, const uint8_t* new_key_fp8, const uint8_t* new_rows,
+               uint8_t* key_fp8, int32_t* ctx_len, int32_t B, int32_t T, uint32_t step, int32_t* placed,
+               void* stream);
+
 /* Counters accumulated by ess_gather_latent / ess_cache_admit / ess_decode_step
  * since the last ess_reset_stats.  ess_get_stats WAITS for `stream` and the
  * side stream. */

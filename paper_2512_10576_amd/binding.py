@@ -82,6 +82,7 @@ def load() -> C.CDLL:
         "ess_profile_enable": [vp, i32],
         "ess_profile_select": [vp, u32, i32],
         "ess_calib_copy": [vp, vp, C.c_size_t, vp],
+        "ess_append": [vp, C.POINTER(EssCache), vp, vp, vp, vp, i32, i32, u32, vp, vp],
         "ess_set_overlap_threshold": [vp, i32],
         "ess_last_overlap": [vp, C.POINTER(i32)],
         "ess_calib_memcpy_rows": [vp, vp, vp, C.c_int64, i32, i32, vp],
@@ -230,6 +231,13 @@ class Context:
                         _ptr(out_bf16, torch.bfloat16), _ptr(lse, torch.float32, optional=True),
                         _ptr(miss_count, torch.int32, optional=True))
         _check(self.lib.ess_decode_step(self.h, C.byref(cache.c), C.byref(a), _stream()))
+
+    def append(self, cache: Cache, new_key_fp8, new_rows, key_fp8, ctx_len, step, placed=None):
+        """write the step's new entries into the Indexer-Cache, the host pool and the slot pool; ctx_len grows"""
+        B, T = new_key_fp8.shape[:2]
+        _check(self.lib.ess_append(self.h, C.byref(cache.c), _ptr(new_key_fp8, torch.uint8), _ptr(new_rows, torch.uint8),
+                                   _ptr(key_fp8, torch.uint8), _ptr(ctx_len, torch.int32), B, T, step,
+                                   _ptr(placed, torch.int32, optional=True), _stream()))
 
     def set_overlap_threshold(self, misses_per_seq):
         _check(self.lib.ess_set_overlap_threshold(self.h, misses_per_seq))

@@ -380,6 +380,76 @@ __global__ __launch_bounds__(256) void k_gather_rows(const uint8_t* __restrict__
   }
 }
 
+// Append (Sec. 3.3): the entries a step produced enter the caches.  One workgroup per sequence; for each
+// of its T new tokens, in order: index key -> Indexer-Cache row p, entry -> host pool row p (stores
+// through the device mapping of the pinned pool: the write-back to the Total Memory Pool), and admission
+// to the slot pool as most recently used: the slot smallest in (stamp, slot) among slots with a stamp
+// below `step` is taken -- the victim rule of the bookkeeping -- or, with every slot on stamp `step`,
+// none (the entry then lives in the host pool only).  Without a host pool slot = position.
+constexpr int APPEND_NT = 1024;
+__global__ __launch_bounds__(APPEND_NT) void k_append(
+    const uint8_t* __restrict__ new_key, const uint8_t* __restrict__ new_rows, uint8_t* __restrict__ key,
+    uint8_t* __restrict__ host_pool, uint8_t* __restrict__ slot_pool, int32_t* __restrict__ slot_of,
+    int32_t* __restrict__ token_of, uint32_t* __restrict__ stamp, int32_t* __restrict__ ctx_len,
+    int32_t* __restrict__ placed, int T, int Di, int Lmax, int S, int row_stride, uint32_t step) {
+  __shared__ unsigned long long red[APPEND_NT / 64];
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
+  const int L0 = max(0, min(ctx_len[b], Lmax));
+  const int n = min(T, Lmax - L0);
+  const int kchunks = Di >> 4, rchunks = row_stride >> 4;
+  int32_t* so = slot_of + (size_t)b * Lmax;
+  int32_t* to = token_of + (size_t)b * S;
+  uint32_t* stp = stamp + (size_t)b * S;
+  for (int t = 0; t < T; ++t) {
+    if (t >= n) {                                  // no room left in the buffers: dropped
+      if (tid == 0 && placed) placed[(size_t)b * T + t] = -1;
+      continue;
+    }
+    const int p = L0 + t;
+    const uint4* krow = reinterpret_cast<const uint4*>(new_key + ((size_t)b * T + t) * Di);
+    const uint4* erow = reinterpret_cast<const uint4*>(new_rows + ((size_t)b * T + t) * row_stride);
+    if (tid < kchunks) reinterpret_cast<uint4*>(key + ((size_t)b * Lmax + p) * Di)[tid] = krow[tid];
+    if (host_pool && tid >= 64 && tid - 64 < rchunks)
+      reinterpret_cast<uint4*>(host_pool + ((size_t)b * Lmax + p) * row_stride)[tid - 64] = erow[tid - 64];
+    int v = p;
+    if (host_pool) {
+      unsigned long long best = ~0ull;
+      for (int s = tid; s < S; s += APPEND_NT) {
+        const uint32_t x = stp[s];
+        if (x < step) {
+          const unsigned long long cand = ((unsigned long long)x << 32) | (uint32_t)s;
+          best = cand < best ? cand : best;
+        }
+      }
+#pragma unroll
+      for (int d = 1; d < 64; d <<= 1) {
+        const unsigned long long o = __shfl_xor(best, d, 64);
+        best = o < best ? o : best;
+      }
+      if (lane == 0) red[tid >> 6] = best;
+      __syncthreads();
+      best = red[0];
+#pragma unroll
+      for (int i = 1; i < APPEND_NT / 64; ++i) best = red[i] < best ? red[i] : best;
+      v = best == ~0ull ? -1 : (int)(uint32_t)best;
+    }
+    if (v >= 0) {
+      if (tid >= 256 && tid - 256 < rchunks)
+        reinterpret_cast<uint4*>(slot_pool + ((size_t)b * S + v) * row_stride)[tid - 256] = erow[tid - 256];
+      if (tid == 0) {
+        const int old = to[v];
+        if (old >= 0) so[old] = -1;
+        to[v] = p;
+        so[p] = v;
+        stp[v] = step;
+      }
+    }
+    if (tid == 0 && placed) placed[(size_t)b * T + t] = v;
+    __syncthreads();                               // the next token's search sees this stamp; red is free again
+  }
+  if (tid == 0) ctx_len[b] = L0 + n;               // every thread read ctx_len before the first barrier or exit
+}
+
 __global__ __launch_bounds__(256) void k_calib_copy(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n) {
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
 }
@@ -400,6 +470,15 @@ __global__ void k_cache_reset(int32_t* slot_of, int32_t* token_of, uint32_t* sta
 }
 
 }  // namespace
+
+int ess_launch_append(const ess_config& c, const ess_cache& cache, const uint8_t* new_key, const uint8_t* new_rows,
+                      uint8_t* key, int32_t* ctx_len, int B, int T, uint32_t step, int32_t* placed, hipStream_t st) {
+  hipLaunchKernelGGL(k_append, dim3(B), dim3(APPEND_NT), 0, st, new_key, new_rows, key,
+                     const_cast<uint8_t*>(cache.host_pool_dev), cache.slot_pool, cache.slot_of, cache.token_of,
+                     cache.stamp, ctx_len, placed, T, c.idx_dim, c.max_ctx, c.slots_per_seq, c.row_stride, step);
+  ESS_HIP(hipGetLastError());
+  return ESS_OK;
+}
 
 int ess_launch_calib_copy(void* dst, const void* src, size_t bytes, hipStream_t st) {
   hipLaunchKernelGGL(k_calib_copy, dim3(8192), dim3(256), 0, st, static_cast<uint4*>(dst), static_cast<const uint4*>(src),

@@ -484,6 +484,19 @@ int ess_calib_copy(void* dst, const void* src, size_t bytes, void* stream) {
   return ess_launch_calib_copy(dst, src, bytes, static_cast<hipStream_t>(stream));
 }
 
+int ess_append(ess_ctx* ctx, const ess_cache* cache, const uint8_t* new_key_fp8, const uint8_t* new_rows,
+               uint8_t* key_fp8, int32_t* ctx_len, int32_t B, int32_t T, uint32_t step, int32_t* placed, void* stream) {
+  int rc = check_bt(ctx, B, T);
+  if (rc != ESS_OK) return rc;
+  if ((rc = check_cache(ctx, cache)) != ESS_OK) return rc;
+  if (!new_key_fp8 || !new_rows || !key_fp8 || !ctx_len) return ess_fail(ESS_ERR_INVALID_ARG, "NULL argument");
+  if (!aligned16(new_key_fp8) || !aligned16(new_rows) || !aligned16(key_fp8))
+    return ess_fail(ESS_ERR_INVALID_ARG, "new_key_fp8, new_rows and key_fp8 must be 16-byte aligned");
+  if (step < 1) return ess_fail(ESS_ERR_INVALID_ARG, "step must be >= 1");
+  return ess_launch_append(ctx->cfg, *cache, new_key_fp8, new_rows, key_fp8, ctx_len, B, T, step, placed,
+                           static_cast<hipStream_t>(stream));
+}
+
 int ess_set_overlap_threshold(ess_ctx* ctx, int32_t misses_per_seq) {
   if (!ctx) return ess_fail(ESS_ERR_INVALID_ARG, "context is NULL");
   if (misses_per_seq < 0) return ess_fail(ESS_ERR_INVALID_ARG, "threshold %d", misses_per_seq);
