@@ -155,6 +155,64 @@ def index_score(q_u8, w, key_u8, ctx_len) -> np.ndarray:
     return out
 
 
+PAGE_TOKENS = 64   # tokens per page of the paged Indexer-Cache
+
+
+def page_bytes(Di: int) -> int:
+    """One page: PAGE_TOKENS keys of Di E4M3 bytes, then PAGE_TOKENS float32
+    scales (little endian), one per key: (Di + 4) bytes per token, the 132
+    bytes per token behind the paper's 16.8 % = 132 / (132 + 656) (Sec. 3)."""
+    return PAGE_TOKENS * (Di + 4)
+
+
+def paged_keys(key_pages, block_table, b: int, n_tok: int, Di: int):
+    """Keys and scales of the first n_tok tokens of sequence b, through its
+    block table: token s lives in page block_table[b, s // 64], row s % 64.
+    key_pages uint8 [n_pages, page_bytes(Di)].  Returns (uint8 [n_tok,Di],
+    float32 [n_tok])."""
+    keys = np.zeros((n_tok, Di), dtype=np.uint8)
+    scales = np.zeros(n_tok, dtype=np.float32)
+    for s in range(n_tok):
+        page = key_pages[int(block_table[b, s // PAGE_TOKENS])]
+        r = s % PAGE_TOKENS
+        keys[s] = page[r * Di:(r + 1) * Di]
+        scales[s] = page[PAGE_TOKENS * Di + 4 * r: PAGE_TOKENS * Di + 4 * r + 4].view(np.float32)[0]
+    return keys, scales
+
+
+def index_score_paged(q_u8, w, key_pages, block_table, ctx_len) -> np.ndarray:
+    """Index score over a paged Indexer-Cache with one scale per key (the
+    layout behind the paper's `paged_mqa_logits` and its 132-byte Indexer
+    entries, Sec. 3 / 3.3).  The stored key of token s stands for
+    scale_s * key_s, scale_s > 0, so
+
+        score[b,t,s] = sum_j w_j * max(0, q_j . (scale_s * key_s))
+                     = scale_s * sum_j w_j * max(0, q_j . key_s).
+
+    Reading (the paper prints neither form): the second form is the
+    definition, evaluated as float32(sum) * float32(scale) rounded once to
+    float32 -- with integer-valued inputs the sum is exact, so the result does
+    not depend on the summation order.  Positions s >= vis(b,t): -inf.
+    Returns float32 [B,T,Lmax] with Lmax = 64 * block_table.shape[1]."""
+    q = decode_e4m3(q_u8)
+    w64 = np.asarray(w, dtype=np.float64)
+    B, T, Hi, Di = q.shape
+    Lmax = PAGE_TOKENS * block_table.shape[1]
+    out = np.full((B, T, Lmax), NEG_INF, dtype=np.float32)
+    for b in range(B):
+        n_tok = int(min(max(int(ctx_len[b]), 0), Lmax))
+        kb, sc = paged_keys(key_pages, block_table, b, n_tok, Di)
+        key = decode_e4m3(kb)
+        for t in range(T):
+            vis = int(visible(ctx_len, T, t)[b])
+            if vis <= 0:
+                continue
+            act = np.maximum(key[:vis] @ q[b, t].T, 0.0)
+            base = (act @ w64[b, t]).astype(np.float32)
+            out[b, t, :vis] = base * sc[:vis]              # float32 * float32, one rounding
+    return out
+
+
 # --------------------------------------------------------------------------
 # stage 2: top-k
 # --------------------------------------------------------------------------
@@ -359,7 +417,7 @@ def merge_partials(o0, l0, o1, l1):
 # append: the entries the step itself produces
 # --------------------------------------------------------------------------
 def append_tokens(cache: SlotCache, key_u8, host_pool, slot_pool, ctx_len,
-                  new_key_u8, new_rows, step_no: int) -> np.ndarray:
+                  new_key_u8, new_rows, step_no: int, paged=None) -> np.ndarray:
     """Sec. 3.3: after a step the newly generated entries go into the caches.
     For sequence b with L0 = ctx_len[b], the t-th of its T new tokens gets
     position p = L0 + t (tokens that would pass Lmax are dropped):
@@ -378,17 +436,36 @@ def append_tokens(cache: SlotCache, key_u8, host_pool, slot_pool, ctx_len,
         the entry goes to slot p;
       * ctx_len[b] = L0 + (number of tokens placed).
 
+    Paged Indexer-Cache: paged = (key_pages, block_table, new_scale) with
+    new_scale float32 [B,T]; key_u8 is then unused (None), Lmax = 64 * pages
+    per sequence, and the key and its scale go to row p % 64 of page
+    block_table[b, p // 64].  The caller maps pages ahead of the context; a
+    token whose page is unmapped (negative id) is dropped like one past Lmax,
+    and so are the tokens after it.
+
     All arrays are updated in place; returns int32 [B,T] with the slot each
     new token went to (-1 = dropped or not admitted)."""
-    B, T = new_key_u8.shape[:2]
-    Lmax = key_u8.shape[1]
+    B, T, Di = new_key_u8.shape
+    Lmax = key_u8.shape[1] if paged is None else PAGE_TOKENS * paged[1].shape[1]
     placed = np.full((B, T), -1, dtype=np.int32)
     for b in range(B):
         L0 = int(ctx_len[b])
         n = max(0, min(T, Lmax - L0))
+        if paged is not None:
+            for t in range(n):
+                if paged[1][b, (L0 + t) // PAGE_TOKENS] < 0:
+                    n = t
+                    break
         for t in range(n):
             p = L0 + t
-            key_u8[b, p] = new_key_u8[b, t]
+            if paged is None:
+                key_u8[b, p] = new_key_u8[b, t]
+            else:
+                page = paged[0][int(paged[1][b, p // PAGE_TOKENS])]
+                r = p % PAGE_TOKENS
+                page[r * Di:(r + 1) * Di] = new_key_u8[b, t]
+                page[PAGE_TOKENS * Di + 4 * r: PAGE_TOKENS * Di + 4 * r + 4] = \
+                    np.asarray(paged[2][b, t], dtype=np.float32).reshape(1).view(np.uint8)
             if host_pool is None:
                 v = p
             else:

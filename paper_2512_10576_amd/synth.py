@@ -147,3 +147,38 @@ class TopkTrace:
         cur = torch.stack(sets, dim=1)
         self.prev = cur
         return cur.sort(dim=-1).values.to(torch.int32)
+
+
+PAGE_TOKENS = 64
+
+
+def paged_indexer_cache(seed, key, ctx_len, n_spare_pages=3, scale_exp=(-6, 2), pow2=False, device="cpu"):
+    """Scatter flat index keys [B,Lmax,Di] (uint8) into a paged pool: pages of 64 keys followed by 64
+    float32 scales, placed in a seeded random order among `n_spare_pages` unused pages (filled with
+    0xFF keys and NaN scales, so reading a wrong page shows).  Only pages that hold visible tokens are
+    mapped; the rest of the block table is -1.  Scales are positive: 2^e * m with e uniform in
+    scale_exp and m uniform in [1,2) (m = 1 when pow2).  Returns (pages uint8 [n_pages, 64*(Di+4)],
+    block_table int32 [B, Lmax/64], scales float32 [B,Lmax])."""
+    g = _gen(seed + 7919, "cpu")
+    B, Lmax, Di = key.shape
+    assert Lmax % PAGE_TOKENS == 0
+    npp = Lmax // PAGE_TOKENS
+    lens = ctx_len.to("cpu", torch.int64)
+    used = [(int(lens[b]) + PAGE_TOKENS - 1) // PAGE_TOKENS for b in range(B)]
+    n_pages = sum(used) + n_spare_pages
+    perm = torch.randperm(n_pages, generator=g)
+    e = torch.randint(scale_exp[0], scale_exp[1] + 1, (B, Lmax), generator=g).to(torch.float32)
+    m = torch.ones((B, Lmax)) if pow2 else 1.0 + torch.rand((B, Lmax), generator=g)
+    scales = (torch.pow(torch.tensor(2.0), e) * m).to(torch.float32)
+    pages = torch.full((n_pages, PAGE_TOKENS * (Di + 4)), 0xFF, dtype=torch.uint8)
+    pages[:, PAGE_TOKENS * Di:] = torch.tensor([float("nan")] * PAGE_TOKENS, dtype=torch.float32).view(torch.uint8)
+    table = torch.full((B, npp), -1, dtype=torch.int32)
+    kcpu = key.to("cpu")
+    nxt = 0
+    for b in range(B):
+        for pg in range(used[b]):
+            pid = int(perm[nxt]); nxt += 1
+            table[b, pg] = pid
+            pages[pid, : PAGE_TOKENS * Di] = kcpu[b, pg * PAGE_TOKENS:(pg + 1) * PAGE_TOKENS].reshape(-1)
+            pages[pid, PAGE_TOKENS * Di:] = scales[b, pg * PAGE_TOKENS:(pg + 1) * PAGE_TOKENS].contiguous().view(torch.uint8)
+    return pages.to(device), table.to(device), scales.to(device)
