@@ -118,7 +118,7 @@ def run_steps(W, first_step, n):
         ov = W["trace"][s - 1] if W["trace"] is not None else None
         for cache, key in zip(W["caches"], W["keys"]):
             ctx.decode_step(cache, W["q_idx"], W["w"], key, W["ctx_len"], W["q_attn"], s, W["idx_out"],
-                            W["out"], W["lse"], W["miss"], ov)
+                            W["out"], W["lse"], W["miss"], ov, W.get("block_table"))
             if W.get("append"):                      # the step's new entries enter the caches; the context grows
                 ctx.append(cache, W["new_key"], W["new_rows"], key, W["ctx_len"], s)
 
@@ -128,14 +128,15 @@ def algorithmic_bytes(W, misses_per_step):
     wl = W["wl"]
     lens = W["ctx_len"].cpu().numpy().astype("int64")
     B, T, k, H = wl["B"], wl["T"], wl["k"], wl["H"]
-    a1 = int(lens.sum()) * (wl["Di"] + 4 * T) + B * T * wl["Hi"] * (wl["Di"] + 4)
+    key_bytes = wl["Di"] + (4 if W.get("paged") else 0)           # paged Indexer-Cache: one float32 scale per key
+    a1 = int(lens.sum()) * (key_bytes + 4 * T) + B * T * wl["Hi"] * (wl["Di"] + 4)
     a2 = int(lens.sum()) * 4 * T + B * T * k * 4
     a4 = B * T * k * W["stride"] + B * T * H * (576 * 2 + 512 * 2 + 4)
     fill = int(misses_per_step * W["stride"])
     return dict(index_score=a1, topk=a2, attention_rows=a4, fill=fill)
 
 
-def measure(name, steps, warmup, overlap="auto", layers=None, rho=None, ratio=None, append=False):
+def measure(name, steps, warmup, overlap="auto", layers=None, rho=None, ratio=None, append=False, paged=False):
     import torch
     W = build_workload(name, warmup + 2 * steps, overlap, layers, rho, ratio)
     if append:
@@ -148,6 +149,23 @@ def measure(name, steps, warmup, overlap="auto", layers=None, rho=None, ratio=No
         W["new_key"] = nk.contiguous()
         W["new_rows"] = rows(78, wl["B"] * wl["T"], device="cuda").reshape(wl["B"], wl["T"], W["stride"]).contiguous()
         W["append"] = True
+    if paged:
+        # the same keys in a paged pool (pages of 64 keys + 64 scales in random order, every page of max_ctx mapped)
+        assert W["wl"]["layers"] == 1 and not append, "--paged: one layer, fixed context"
+        wl = W["wl"]
+        B, L, Di = wl["B"], wl["L"], wl["Di"]
+        npp = L // 64
+        g = torch.Generator(device="cuda").manual_seed(123)
+        perm = torch.randperm(B * npp, generator=g, device="cuda")
+        pages = torch.empty((B * npp, 64 * (Di + 4)), dtype=torch.uint8, device="cuda")
+        pages[perm, : 64 * Di] = W["key"].view(B * npp, 64 * Di)
+        scales = (0.5 + torch.rand((B * npp, 64), generator=g, device="cuda")).to(torch.float32)
+        pages[perm, 64 * Di:] = scales.view(torch.uint8)
+        W["block_table"] = perm.to(torch.int32).view(B, npp).contiguous()
+        W["keys"] = [pages]
+        W["key"] = pages
+        W["paged"] = True
+        del scales
     nl = W["wl"]["layers"]
     ctx = W["ctx"]
     run_steps(W, 1, warmup)
@@ -378,6 +396,9 @@ def main():
     ap.add_argument("--append", action="store_true",
                     help="after every layer-step write the step's new entries into the caches (ess_append): the context "
                          "grows by T per step (default: context held fixed, as the baseline workload states)")
+    ap.add_argument("--paged", action="store_true",
+                    help="index keys in a paged pool with one scale per key (pages of 64 keys in random order, 132 bytes "
+                         "per key) instead of the flat array")
     ap.add_argument("--sweep", default=None, choices=["overlap", "ratio", "granularity"],
                     help="instead of the benchmark line: overlap = serial / DA / DBA step time against the miss count; "
                          "ratio = misses and step time against the Sparse Memory Ratio, with and without LRU-Warmup; "
@@ -407,7 +428,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    W, res = measure(a.workload, a.steps, a.warmup, a.overlap, a.layers, append=a.append)
+    W, res = measure(a.workload, a.steps, a.warmup, a.overlap, a.layers, append=a.append, paged=a.paged)
     ab = res["algorithmic_bytes"]
     roof = dict(bound="hbm", kernel="k_index_score", achieved=res["index_score_GBs"], peak=HBM_PEAK_GBS, unit="GB/s",
                 frac=res["index_score_GBs"] / HBM_PEAK_GBS, traffic=MEASURED_TRAFFIC_BYTES.get(a.workload),
@@ -421,7 +442,8 @@ def main():
                    "topk": 2048, "attention": "128 heads x 576 bf16 absorbed MLA", "slots_per_seq": W["S"],
                    "overlap": W["overlap"] + (" (ran %s)" % res["overlap_used"] if W["overlap"] == "auto" else ""),
                    "layers_per_step": res["layers"], "q_tokens": W["wl"]["T"],
-                   "context": "grows by T per step (ess_append after every step)" if a.append else "fixed"},
+                   "context": "grows by T per step (ess_append after every step)" if a.append else "fixed",
+                   "indexer_cache": "paged, 64 keys + 64 scales per page" if a.paged else "flat"},
         "roofline": roof,
         "stages": {k: res[k] for k in ("stage_ms", "hbm_stream_GBs", "hbm_stream_frac_of_peak", "whole_step_hbm_frac",
                                        "misses_per_step", "host_link_GBs", "host_link_frac_of_peak")},

@@ -112,6 +112,10 @@ typedef struct {
   void* out_bf16;               /* [B,T,H,512] attention output */
   float* lse;                   /* [B,T,H] log-sum-exp of the logits, or NULL */
   int32_t* miss_count;          /* [B] entries fetched from the host pool this step, or NULL */
+  const int32_t* block_table;   /* NULL: key_fp8 is flat [B,max_ctx,idx_dim].  Else [B, max_ctx/64] page ids and
+                                   key_fp8 is a page pool, see ess_index_score_paged */
+  int32_t n_pages;              /* pages in the pool (with block_table) */
+  int32_t reserved;             /* 0 */
 } ess_step_args;
 
 /* Create a context: validates the configuration, allocates the workspace
@@ -139,6 +143,21 @@ int ess_cache_admit(ess_ctx* ctx, const ess_cache* cache, const int32_t* tok, in
  * s >= vis(b,t) hold unspecified values. */
 int ess_index_score(ess_ctx* ctx, const uint8_t* q_idx_fp8, const float* w, const uint8_t* key_fp8,
                     const int32_t* ctx_len, int32_t B, int32_t T, float* score, void* stream);
+
+/* Stage 1 over a paged Indexer-Cache with one scale per key (Sec. 3: an Indexer-Cache entry is 132
+ * bytes, 128 fp8 + one float; Sec. 3.3 names the kernel paged_mqa_logits).  key_pages is a pool of
+ * n_pages pages of ESS_PAGE_TOKENS * (idx_dim + 4) bytes: 64 keys of idx_dim fp8 bytes, then 64
+ * float32 scales.  Token s of sequence b is row s % 64 of page block_table[b, s / 64]
+ * (block_table [B, max_ctx/64] int32, device; entries for pages at or past ctx_len are not read;
+ * ids outside [0, n_pages) are clamped into the pool).  The stored key stands for scale * key with
+ * scale > 0, and
+ *   score[b,t,s] = scale_s * sum_j w[b,t,j] * max(0, q[b,t,j,:] . key_s),
+ * the sum as in ess_index_score, then one float32 multiplication.  Needs max_ctx % 64 == 0 and
+ * key_pages 16-byte aligned. */
+#define ESS_PAGE_TOKENS 64
+int ess_index_score_paged(ess_ctx* ctx, const uint8_t* q_idx_fp8, const float* w, const uint8_t* key_pages,
+                          const int32_t* block_table, int32_t n_pages, const int32_t* ctx_len, int32_t B,
+                          int32_t T, float* score, void* stream);
 
 /* Stage 2, Top-K (Sec. 3: the top 2,048 entries): idx[b,t,:] = the min(k,vis)
  * positions largest under (score descending, position ascending), written in
@@ -199,10 +218,14 @@ int ess_last_overlap(const ess_ctx* ctx, int32_t* mode);
  * new_key_fp8 [B,T,idx_dim], new_rows [B,T,row_stride] (entries in the pool's storage format), both
  * device, 16-byte aligned.  placed [B,T] (device, may be NULL) receives the slot of each new token,
  * -1 if dropped or not admitted.  Call it on the stream of the decode steps, after the step that
- * produced the entries; `step` is that step's number or a later one. */
+ * produced the entries; `step` is that step's number or a later one.
+ * Paged Indexer-Cache: with block_table != NULL, key_fp8 is the page pool of ess_index_score_paged,
+ * the key goes to row p % 64 of page block_table[b, p / 64] and new_key_scale[b,t] (float32 [B,T],
+ * device, required then) beside it.  The caller maps pages ahead of the context: a token whose page
+ * id is outside [0, n_pages) is dropped like one past max_ctx, and so are the tokens after it. */
 int ess_append(ess_ctx* ctx, const ess_cache* cache, const uint8_t* new_key_fp8, const uint8_t* new_rows,
                uint8_t* key_fp8, int32_t* ctx_len, int32_t B, int32_t T, uint32_t step, int32_t* placed,
-               void* stream);
+               const float* new_key_scale, const int32_t* block_table, int32_t n_pages, void* stream);
 
 /* Counters accumulated by ess_gather_latent / ess_cache_admit / ess_decode_step
  * since the last ess_reset_stats.  ess_get_stats WAITS for `stream` and the

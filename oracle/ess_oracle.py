@@ -490,13 +490,16 @@ def append_tokens(cache: SlotCache, key_u8, host_pool, slot_pool, ctx_len,
 # whole step
 # --------------------------------------------------------------------------
 def decode_step(q_idx_u8, w, key_u8, ctx_len, k, cache: SlotCache, slot_pool,
-                host_pool, q_bits, fmt, sm_scale, step_no, topk_override=None):
+                host_pool, q_bits, fmt, sm_scale, step_no, topk_override=None, paged=None):
     """One layer-step: index score -> top-k -> (optional trace override) ->
     LRU bookkeeping -> miss fill -> sparse MLA.  `cache` and `slot_pool` are
     updated in place.  host_pool None means fully resident (no misses may
     occur).  Returns dict(score, idx, used_idx, slot_idx, fresh, miss_count,
     out, lse)."""
-    score = index_score(q_idx_u8, w, key_u8, ctx_len)
+    if paged is None:
+        score = index_score(q_idx_u8, w, key_u8, ctx_len)
+    else:                                   # (key_pages, block_table): paged Indexer-Cache, key_u8 unused
+        score = index_score_paged(q_idx_u8, w, paged[0], paged[1], ctx_len)
     idx = topk(score, ctx_len, k)
     used = idx if topk_override is None else np.asarray(topk_override, dtype=np.int32)
     bk = cache.step(used, step_no)

@@ -40,7 +40,8 @@ class EssStepArgs(C.Structure):
     _fields_ = [("q_idx_fp8", C.c_void_p), ("w", C.c_void_p), ("key_fp8", C.c_void_p), ("ctx_len", C.c_void_p),
                 ("q_bf16", C.c_void_p), ("topk_override", C.c_void_p), ("B", C.c_int32), ("T", C.c_int32),
                 ("step", C.c_uint32), ("idx_out", C.c_void_p), ("out_bf16", C.c_void_p), ("lse", C.c_void_p),
-                ("miss_count", C.c_void_p)]
+                ("miss_count", C.c_void_p), ("block_table", C.c_void_p), ("n_pages", C.c_int32),
+                ("reserved", C.c_int32)]
 
 
 class EssStats(C.Structure):
@@ -82,7 +83,8 @@ def load() -> C.CDLL:
         "ess_profile_enable": [vp, i32],
         "ess_profile_select": [vp, u32, i32],
         "ess_calib_copy": [vp, vp, C.c_size_t, vp],
-        "ess_append": [vp, C.POINTER(EssCache), vp, vp, vp, vp, i32, i32, u32, vp, vp],
+        "ess_append": [vp, C.POINTER(EssCache), vp, vp, vp, vp, i32, i32, u32, vp, vp, vp, i32, vp],
+        "ess_index_score_paged": [vp, vp, vp, vp, vp, i32, vp, i32, i32, vp, vp],
         "ess_set_overlap_threshold": [vp, i32],
         "ess_last_overlap": [vp, C.POINTER(i32)],
         "ess_calib_memcpy_rows": [vp, vp, vp, C.c_int64, i32, i32, vp],
@@ -223,21 +225,34 @@ class Context:
                                               _ptr(lse, torch.float32, optional=True), _stream()))
 
     def decode_step(self, cache: Cache, q_idx_fp8, w, key_fp8, ctx_len, q_bf16, step, idx_out, out_bf16, lse=None,
-                    miss_count=None, topk_override=None):
+                    miss_count=None, topk_override=None, block_table=None):
         B, T = q_idx_fp8.shape[:2]
         a = EssStepArgs(_ptr(q_idx_fp8, torch.uint8), _ptr(w, torch.float32), _ptr(key_fp8, torch.uint8),
                         _ptr(ctx_len, torch.int32), _ptr(q_bf16, torch.bfloat16),
                         _ptr(topk_override, torch.int32, optional=True), B, T, step, _ptr(idx_out, torch.int32),
                         _ptr(out_bf16, torch.bfloat16), _ptr(lse, torch.float32, optional=True),
-                        _ptr(miss_count, torch.int32, optional=True))
+                        _ptr(miss_count, torch.int32, optional=True), _ptr(block_table, torch.int32, optional=True),
+                        key_fp8.shape[0] if block_table is not None else 0, 0)
         _check(self.lib.ess_decode_step(self.h, C.byref(cache.c), C.byref(a), _stream()))
 
-    def append(self, cache: Cache, new_key_fp8, new_rows, key_fp8, ctx_len, step, placed=None):
-        """write the step's new entries into the Indexer-Cache, the host pool and the slot pool; ctx_len grows"""
+    def append(self, cache: Cache, new_key_fp8, new_rows, key_fp8, ctx_len, step, placed=None, new_key_scale=None,
+               block_table=None):
+        """write the step's new entries into the Indexer-Cache (flat, or paged with block_table and
+        new_key_scale), the host pool and the slot pool; ctx_len grows"""
         B, T = new_key_fp8.shape[:2]
+        n_pages = key_fp8.shape[0] if block_table is not None else 0
         _check(self.lib.ess_append(self.h, C.byref(cache.c), _ptr(new_key_fp8, torch.uint8), _ptr(new_rows, torch.uint8),
                                    _ptr(key_fp8, torch.uint8), _ptr(ctx_len, torch.int32), B, T, step,
-                                   _ptr(placed, torch.int32, optional=True), _stream()))
+                                   _ptr(placed, torch.int32, optional=True),
+                                   _ptr(new_key_scale, torch.float32, optional=True),
+                                   _ptr(block_table, torch.int32, optional=True), n_pages, _stream()))
+
+    def index_score_paged(self, q_idx_fp8, w, key_pages, block_table, ctx_len, score):
+        B, T = q_idx_fp8.shape[:2]
+        _check(self.lib.ess_index_score_paged(self.h, _ptr(q_idx_fp8, torch.uint8), _ptr(w, torch.float32),
+                                              _ptr(key_pages, torch.uint8), _ptr(block_table, torch.int32),
+                                              key_pages.shape[0], _ptr(ctx_len, torch.int32), B, T,
+                                              _ptr(score, torch.float32), _stream()))
 
     def set_overlap_threshold(self, misses_per_seq):
         _check(self.lib.ess_set_overlap_threshold(self.h, misses_per_seq))

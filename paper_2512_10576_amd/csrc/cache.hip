@@ -391,11 +391,19 @@ __global__ __launch_bounds__(APPEND_NT) void k_append(
     const uint8_t* __restrict__ new_key, const uint8_t* __restrict__ new_rows, uint8_t* __restrict__ key,
     uint8_t* __restrict__ host_pool, uint8_t* __restrict__ slot_pool, int32_t* __restrict__ slot_of,
     int32_t* __restrict__ token_of, uint32_t* __restrict__ stamp, int32_t* __restrict__ ctx_len,
-    int32_t* __restrict__ placed, int T, int Di, int Lmax, int S, int row_stride, uint32_t step) {
+    int32_t* __restrict__ placed, int T, int Di, int Lmax, int S, int row_stride, uint32_t step,
+    const float* __restrict__ new_scale, const int32_t* __restrict__ block_table, int n_pages) {
   __shared__ unsigned long long red[APPEND_NT / 64];
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
   const int L0 = max(0, min(ctx_len[b], Lmax));
-  const int n = min(T, Lmax - L0);
+  int n = min(T, Lmax - L0);
+  // paged Indexer-Cache: a token needs a mapped page; the first one without stops the append
+  const int32_t* bt = block_table ? block_table + (size_t)b * (Lmax / ESS_PAGE_TOKENS) : nullptr;
+  if (bt)
+    for (int t = 0; t < n; ++t) {
+      const int pid = bt[(L0 + t) / ESS_PAGE_TOKENS];
+      if (pid < 0 || pid >= n_pages) { n = t; break; }
+    }
   const int kchunks = Di >> 4, rchunks = row_stride >> 4;
   int32_t* so = slot_of + (size_t)b * Lmax;
   int32_t* to = token_of + (size_t)b * S;
@@ -408,7 +416,14 @@ __global__ __launch_bounds__(APPEND_NT) void k_append(
     const int p = L0 + t;
     const uint4* krow = reinterpret_cast<const uint4*>(new_key + ((size_t)b * T + t) * Di);
     const uint4* erow = reinterpret_cast<const uint4*>(new_rows + ((size_t)b * T + t) * row_stride);
-    if (tid < kchunks) reinterpret_cast<uint4*>(key + ((size_t)b * Lmax + p) * Di)[tid] = krow[tid];
+    if (bt) {
+      uint8_t* page = key + (size_t)bt[p / ESS_PAGE_TOKENS] * ((size_t)ESS_PAGE_TOKENS * (Di + 4));
+      const int r = p % ESS_PAGE_TOKENS;
+      if (tid < kchunks) reinterpret_cast<uint4*>(page + (size_t)r * Di)[tid] = krow[tid];
+      if (tid == 32) reinterpret_cast<float*>(page + (size_t)ESS_PAGE_TOKENS * Di)[r] = new_scale[(size_t)b * T + t];
+    } else if (tid < kchunks) {
+      reinterpret_cast<uint4*>(key + ((size_t)b * Lmax + p) * Di)[tid] = krow[tid];
+    }
     if (host_pool && tid >= 64 && tid - 64 < rchunks)
       reinterpret_cast<uint4*>(host_pool + ((size_t)b * Lmax + p) * row_stride)[tid - 64] = erow[tid - 64];
     int v = p;
@@ -472,10 +487,12 @@ __global__ void k_cache_reset(int32_t* slot_of, int32_t* token_of, uint32_t* sta
 }  // namespace
 
 int ess_launch_append(const ess_config& c, const ess_cache& cache, const uint8_t* new_key, const uint8_t* new_rows,
-                      uint8_t* key, int32_t* ctx_len, int B, int T, uint32_t step, int32_t* placed, hipStream_t st) {
+                      uint8_t* key, int32_t* ctx_len, int B, int T, uint32_t step, int32_t* placed,
+                      const float* new_scale, const int32_t* block_table, int n_pages, hipStream_t st) {
   hipLaunchKernelGGL(k_append, dim3(B), dim3(APPEND_NT), 0, st, new_key, new_rows, key,
                      const_cast<uint8_t*>(cache.host_pool_dev), cache.slot_pool, cache.slot_of, cache.token_of,
-                     cache.stamp, ctx_len, placed, T, c.idx_dim, c.max_ctx, c.slots_per_seq, c.row_stride, step);
+                     cache.stamp, ctx_len, placed, T, c.idx_dim, c.max_ctx, c.slots_per_seq, c.row_stride, step,
+                     new_scale, block_table, n_pages);
   ESS_HIP(hipGetLastError());
   return ESS_OK;
 }

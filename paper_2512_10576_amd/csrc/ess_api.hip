@@ -289,6 +289,28 @@ int ess_index_score(ess_ctx* ctx, const uint8_t* q, const float* w, const uint8_
   return ess_launch_index_score(ctx->cfg, q, w, key, ctx_len, B, T, score, static_cast<hipStream_t>(stream));
 }
 
+namespace {
+int check_paged(const ess_ctx* ctx, const uint8_t* pool, const int32_t* block_table, int n_pages) {
+  if (!block_table) return ess_fail(ESS_ERR_INVALID_ARG, "block_table is NULL");
+  if (ctx->cfg.max_ctx % ESS_PAGE_TOKENS) return ess_fail(ESS_ERR_UNSUPPORTED, "paged Indexer-Cache needs max_ctx %% 64 == 0");
+  if (n_pages < 1) return ess_fail(ESS_ERR_INVALID_ARG, "n_pages %d", n_pages);
+  if (!aligned16(pool)) return ess_fail(ESS_ERR_INVALID_ARG, "the page pool must be 16-byte aligned");
+  return ESS_OK;
+}
+}  // namespace
+
+int ess_index_score_paged(ess_ctx* ctx, const uint8_t* q, const float* w, const uint8_t* key_pages,
+                          const int32_t* block_table, int32_t n_pages, const int32_t* ctx_len, int32_t B, int32_t T,
+                          float* score, void* stream) {
+  int rc = check_bt(ctx, B, T);
+  if (rc != ESS_OK) return rc;
+  if (!q || !w || !key_pages || !ctx_len || !score) return ess_fail(ESS_ERR_INVALID_ARG, "NULL argument");
+  if (!aligned16(q) || !aligned16(score)) return ess_fail(ESS_ERR_INVALID_ARG, "q and score must be 16-byte aligned");
+  if ((rc = check_paged(ctx, key_pages, block_table, n_pages)) != ESS_OK) return rc;
+  return ess_launch_index_score(ctx->cfg, q, w, key_pages, ctx_len, B, T, score, static_cast<hipStream_t>(stream),
+                                block_table, n_pages);
+}
+
 int ess_topk(ess_ctx* ctx, const float* score, const int32_t* ctx_len, int32_t B, int32_t T, int32_t* idx,
              void* stream) {
   int rc = check_bt(ctx, B, T);
@@ -340,6 +362,7 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
   if (!aligned16(a->q_idx_fp8) || !aligned16(a->key_fp8) || !aligned16(a->q_bf16) || !aligned16(a->out_bf16))
     return ess_fail(ESS_ERR_INVALID_ARG, "q_idx_fp8, key_fp8, q_bf16 and out_bf16 must be 16-byte aligned");
   if (a->step < 1) return ess_fail(ESS_ERR_INVALID_ARG, "step must be >= 1");
+  if (a->block_table && (rc = check_paged(ctx, a->key_fp8, a->block_table, a->n_pages)) != ESS_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const ess_config& c = ctx->cfg;
   const int B = a->B, T = a->T;
@@ -412,8 +435,13 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     float* sc = ctx->score_ws + bt0 * c.max_ctx;
     int32_t* idx_h = a->idx_out + bt0 * k;
     ESS_BEGIN(0);
-    rc = ess_launch_index_score(c, a->q_idx_fp8 + bt0 * c.idx_heads * c.idx_dim, a->w + bt0 * c.idx_heads,
-                                a->key_fp8 + (size_t)b0 * c.max_ctx * c.idx_dim, a->ctx_len + b0, Bh, T, sc, st);
+    if (a->block_table)     // paged: one pool for the whole batch, the table rows of this sub-batch
+      rc = ess_launch_index_score(c, a->q_idx_fp8 + bt0 * c.idx_heads * c.idx_dim, a->w + bt0 * c.idx_heads, a->key_fp8,
+                                  a->ctx_len + b0, Bh, T, sc, st,
+                                  a->block_table + (size_t)b0 * (c.max_ctx / ESS_PAGE_TOKENS), a->n_pages);
+    else
+      rc = ess_launch_index_score(c, a->q_idx_fp8 + bt0 * c.idx_heads * c.idx_dim, a->w + bt0 * c.idx_heads,
+                                  a->key_fp8 + (size_t)b0 * c.max_ctx * c.idx_dim, a->ctx_len + b0, Bh, T, sc, st);
     if (rc != ESS_OK) return rc;
     ESS_END(0);
     ESS_BEGIN(1);
@@ -485,7 +513,8 @@ int ess_calib_copy(void* dst, const void* src, size_t bytes, void* stream) {
 }
 
 int ess_append(ess_ctx* ctx, const ess_cache* cache, const uint8_t* new_key_fp8, const uint8_t* new_rows,
-               uint8_t* key_fp8, int32_t* ctx_len, int32_t B, int32_t T, uint32_t step, int32_t* placed, void* stream) {
+               uint8_t* key_fp8, int32_t* ctx_len, int32_t B, int32_t T, uint32_t step, int32_t* placed,
+               const float* new_key_scale, const int32_t* block_table, int32_t n_pages, void* stream) {
   int rc = check_bt(ctx, B, T);
   if (rc != ESS_OK) return rc;
   if ((rc = check_cache(ctx, cache)) != ESS_OK) return rc;
@@ -493,8 +522,12 @@ int ess_append(ess_ctx* ctx, const ess_cache* cache, const uint8_t* new_key_fp8,
   if (!aligned16(new_key_fp8) || !aligned16(new_rows) || !aligned16(key_fp8))
     return ess_fail(ESS_ERR_INVALID_ARG, "new_key_fp8, new_rows and key_fp8 must be 16-byte aligned");
   if (step < 1) return ess_fail(ESS_ERR_INVALID_ARG, "step must be >= 1");
+  if (block_table) {
+    if ((rc = check_paged(ctx, key_fp8, block_table, n_pages)) != ESS_OK) return rc;
+    if (!new_key_scale) return ess_fail(ESS_ERR_INVALID_ARG, "new_key_scale is NULL");
+  }
   return ess_launch_append(ctx->cfg, *cache, new_key_fp8, new_rows, key_fp8, ctx_len, B, T, step, placed,
-                           static_cast<hipStream_t>(stream));
+                           new_key_scale, block_table, n_pages, static_cast<hipStream_t>(stream));
 }
 
 int ess_set_overlap_threshold(ess_ctx* ctx, int32_t misses_per_seq) {

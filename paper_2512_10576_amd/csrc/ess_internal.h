@@ -61,13 +61,15 @@ int ess_fail(int code, const char* fmt, ...);
 
 // Stage launchers.  All enqueue on `st` and return an ess_status.
 int ess_launch_index_score(const ess_config& c, const uint8_t* q, const float* w, const uint8_t* key,
-                           const int32_t* ctx_len, int B, int T, float* score, hipStream_t st);
+                           const int32_t* ctx_len, int B, int T, float* score, hipStream_t st,
+                           const int32_t* block_table = nullptr, int n_pages = 0);
 int ess_launch_topk(const ess_config& c, const float* score, const int32_t* ctx_len, int B, int T,
                     int32_t* idx, hipStream_t st);
 // fill kernel (used instead of hipMemsetAsync so that callers may capture the stream in a graph)
 int ess_launch_calib_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
 int ess_launch_append(const ess_config& c, const ess_cache& cache, const uint8_t* new_key, const uint8_t* new_rows,
-                      uint8_t* key, int32_t* ctx_len, int B, int T, uint32_t step, int32_t* placed, hipStream_t st);
+                      uint8_t* key, int32_t* ctx_len, int B, int T, uint32_t step, int32_t* placed,
+                      const float* new_scale, const int32_t* block_table, int n_pages, hipStream_t st);
 int ess_launch_fill_u32(uint32_t* p, int n, uint32_t value, hipStream_t st);
 int ess_launch_cache_reset(const ess_config& c, const ess_cache& cache, int B, hipStream_t st);
 // look-up + LRU update + lists; n_sel = entries per sequence in idx ([B,n_sel], T lists of n_sel/T)

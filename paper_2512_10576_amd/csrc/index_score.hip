@@ -48,15 +48,21 @@ __device__ __forceinline__ void load_row_share(const uint8_t* row, int g, long (
   }
 }
 
-// HB = 16-head blocks (Hi padded up), DI = indexer dim, T = query tokens per sequence
-template <int HB, int DI, int T>
+// HB = 16-head blocks (Hi padded up), DI = indexer dim, T = query tokens per sequence.
+// PAGED: `key` is a pool of pages (64 keys of DI bytes, then 64 float scales); token s of sequence b is
+// row s % 64 of page block_table[b, s / 64] and its score is multiplied by its scale (positive, so the
+// scale commutes with the ReLU and the head sum: one multiplication of the exact sum).  A wave's batch
+// of 64 tokens is exactly one page.
+template <int HB, int DI, int T, bool PAGED>
 __global__ __launch_bounds__(kWaves * 64) void k_index_score(const uint8_t* __restrict__ q,
                                                               const float* __restrict__ w,
                                                               const uint8_t* __restrict__ key,
                                                               const int32_t* __restrict__ ctx_len,
                                                               float* __restrict__ score, int Lmax, int Hi,
-                                                              int chunk_tokens) {
+                                                              int chunk_tokens,
+                                                              const int32_t* __restrict__ block_table, int n_pages) {
   constexpr int KS = DI / 32;
+  constexpr size_t kPageBytes = (size_t)kBatchTokens * (DI + 4);
   const int b = blockIdx.y;
   const int len = min(ctx_len[b], Lmax);
   const int blk_base = blockIdx.x * chunk_tokens;
@@ -92,16 +98,44 @@ __global__ __launch_bounds__(kWaves * 64) void k_index_score(const uint8_t* __re
 
   const uint8_t* kbase = key + (size_t)b * Lmax * DI;
   const int last_row = Lmax - 1;
+  constexpr int kStride = kWaves * kBatchTokens;
+  const int base0 = blk_base + wave * kBatchTokens;
+  if (base0 >= blk_end) return;
+  const int nb = (blk_end - base0 + kStride - 1) / kStride;
 
-  auto load_batch = [&](int base, KeyRegs<KS> (&dst)[kTilesPerBatch]) {
+  // paged: lane j holds the page of this wave's j-th batch (a workgroup covers at most 2048 tokens:
+  // 8 batches per wave), read once, handed out with readlane
+  int pidv = 0;
+  if constexpr (PAGED) {
+    if (lane < nb) {
+      const int pid = block_table[(size_t)b * (Lmax / kBatchTokens) + base0 / kBatchTokens + lane * kWaves];
+      pidv = min(max(pid, 0), n_pages - 1);                   // a bad table entry must not leave the pool
+    }
+  }
+
+  struct Batch {
+    KeyRegs<KS> k[kTilesPerBatch];
+    float sc;                                                 // PAGED: scale of token base + lane
+  };
+
+  auto load_batch = [&](int j, Batch& dst) {
+    const int base = base0 + j * kStride;
+    if constexpr (PAGED) {
+      const uint8_t* page = key + (size_t)__builtin_amdgcn_readlane(pidv, j) * kPageBytes;
 #pragma unroll
-    for (int u = 0; u < kTilesPerBatch; ++u) {
-      const int row = min(base + u * 16 + n, last_row);       // clamp keeps ragged tails in bounds
-      load_row_share<DI>(kbase + (size_t)row * DI, g, dst[u].v);
+      for (int u = 0; u < kTilesPerBatch; ++u) load_row_share<DI>(page + (size_t)(u * 16 + n) * DI, g, dst.k[u].v);
+      dst.sc = *reinterpret_cast<const float*>(page + (size_t)kBatchTokens * DI + lane * 4);
+    } else {
+#pragma unroll
+      for (int u = 0; u < kTilesPerBatch; ++u) {
+        const int row = min(base + u * 16 + n, last_row);     // clamp keeps ragged tails in bounds
+        load_row_share<DI>(kbase + (size_t)row * DI, g, dst.k[u].v);
+      }
     }
   };
 
-  auto compute_batch = [&](int base, const KeyRegs<KS> (&kr)[kTilesPerBatch]) {
+  auto compute_batch = [&](int j, const Batch& kr) {
+    const int base = base0 + j * kStride;
     float res[T];
 #pragma unroll
     for (int t = 0; t < T; ++t) res[t] = 0.f;
@@ -115,7 +149,7 @@ __global__ __launch_bounds__(kWaves * 64) void k_index_score(const uint8_t* __re
           floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
           for (int kk = 0; kk < KS; ++kk)
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(qa[t][mb][kk], kr[u].v[kk], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(qa[t][mb][kk], kr.k[u].v[kk], acc, 0, 0, 0);
 #pragma unroll
           for (int i = 0; i < 4; ++i) s = fmaf(wr[t][mb][i], fmaxf(acc[i], 0.f), s);
         }
@@ -127,7 +161,7 @@ __global__ __launch_bounds__(kWaves * 64) void k_index_score(const uint8_t* __re
     const int tok = base + lane;                              // = base + 16*g + n
     if (tok < blk_end) {
 #pragma unroll
-      for (int t = 0; t < T; ++t) score[(size_t)(b * T + t) * Lmax + tok] = res[t];
+      for (int t = 0; t < T; ++t) score[(size_t)(b * T + t) * Lmax + tok] = PAGED ? res[t] * kr.sc : res[t];
     }
   };
 
@@ -135,13 +169,9 @@ __global__ __launch_bounds__(kWaves * 64) void k_index_score(const uint8_t* __re
   // computed (16 KiB per wave for Di = 128).  Inside the loop every prefetch is unconditional, so the
   // number of loads in flight is the same on every path (a prefetch under a branch makes the compiler
   // wait for the newest loads before it uses the oldest); the last batches are peeled off.
-  constexpr int kStride = kWaves * kBatchTokens;
-  const int base0 = blk_base + wave * kBatchTokens;
-  if (base0 >= blk_end) return;
-  const int nb = (blk_end - base0 + kStride - 1) / kStride;
-  KeyRegs<KS> bufA[kTilesPerBatch], bufB[kTilesPerBatch], bufC[kTilesPerBatch];
-#define ESS_LOAD(buf, j) load_batch(base0 + (j) * kStride, buf)
-#define ESS_COMP(buf, j) compute_batch(base0 + (j) * kStride, buf)
+  Batch bufA, bufB, bufC;
+#define ESS_LOAD(buf, j) load_batch((j), buf)
+#define ESS_COMP(buf, j) compute_batch((j), buf)
   ESS_LOAD(bufA, 0);
   ESS_LOAD(bufB, min(1, nb - 1));            // invariant: A holds batch i, B batch i+1 (clamped)
   int i = 0;
@@ -166,47 +196,56 @@ __global__ __launch_bounds__(kWaves * 64) void k_index_score(const uint8_t* __re
 #undef ESS_COMP
 }
 
-template <int HB, int DI>
-int launch_t(int T, dim3 grid, hipStream_t st, const uint8_t* q, const float* w, const uint8_t* key,
-             const int32_t* ctx_len, float* score, int Lmax, int Hi, int chunk) {
-  if (T == 1)
-    hipLaunchKernelGGL((k_index_score<HB, DI, 1>), grid, dim3(kWaves * 64), 0, st, q, w, key, ctx_len, score,
-                       Lmax, Hi, chunk);
+struct IdxArgs {
+  const uint8_t* q; const float* w; const uint8_t* key; const int32_t* ctx_len; float* score;
+  int Lmax, Hi, chunk;
+  const int32_t* block_table; int n_pages;
+};
+
+template <int HB, int DI, int T>
+void launch_p(dim3 grid, hipStream_t st, const IdxArgs& a) {
+  if (a.block_table)
+    hipLaunchKernelGGL((k_index_score<HB, DI, T, true>), grid, dim3(kWaves * 64), 0, st, a.q, a.w, a.key, a.ctx_len,
+                       a.score, a.Lmax, a.Hi, a.chunk, a.block_table, a.n_pages);
   else
-    hipLaunchKernelGGL((k_index_score<HB, DI, 2>), grid, dim3(kWaves * 64), 0, st, q, w, key, ctx_len, score,
-                       Lmax, Hi, chunk);
-  return ESS_OK;
+    hipLaunchKernelGGL((k_index_score<HB, DI, T, false>), grid, dim3(kWaves * 64), 0, st, a.q, a.w, a.key, a.ctx_len,
+                       a.score, a.Lmax, a.Hi, a.chunk, a.block_table, a.n_pages);
+}
+
+template <int HB, int DI>
+void launch_t(int T, dim3 grid, hipStream_t st, const IdxArgs& a) {
+  if (T == 1) launch_p<HB, DI, 1>(grid, st, a);
+  else launch_p<HB, DI, 2>(grid, st, a);
 }
 
 template <int DI>
-int launch_hb(int HB, int T, dim3 grid, hipStream_t st, const uint8_t* q, const float* w, const uint8_t* key,
-              const int32_t* ctx_len, float* score, int Lmax, int Hi, int chunk) {
+void launch_hb(int HB, int T, dim3 grid, hipStream_t st, const IdxArgs& a) {
   switch (HB) {
-    case 1: return launch_t<1, DI>(T, grid, st, q, w, key, ctx_len, score, Lmax, Hi, chunk);
-    case 2: return launch_t<2, DI>(T, grid, st, q, w, key, ctx_len, score, Lmax, Hi, chunk);
-    case 3: return launch_t<3, DI>(T, grid, st, q, w, key, ctx_len, score, Lmax, Hi, chunk);
-    default: return launch_t<4, DI>(T, grid, st, q, w, key, ctx_len, score, Lmax, Hi, chunk);
+    case 1: launch_t<1, DI>(T, grid, st, a); break;
+    case 2: launch_t<2, DI>(T, grid, st, a); break;
+    case 3: launch_t<3, DI>(T, grid, st, a); break;
+    default: launch_t<4, DI>(T, grid, st, a); break;
   }
 }
 
 }  // namespace
 
 int ess_launch_index_score(const ess_config& c, const uint8_t* q, const float* w, const uint8_t* key,
-                           const int32_t* ctx_len, int B, int T, float* score, hipStream_t st) {
+                           const int32_t* ctx_len, int B, int T, float* score, hipStream_t st,
+                           const int32_t* block_table, int n_pages) {
   const int Hi = c.idx_heads, Di = c.idx_dim, Lmax = c.max_ctx;
   const int HB = (Hi + 15) / 16;
   // tokens per workgroup: a multiple of the 256 tokens the four waves cover per round; 2048 when
   // that still leaves several workgroups per CU, else 1024
   const int chunk = ((long)B * Lmax >= 2048L * 1024) ? 2048 : 1024;
   dim3 grid((Lmax + chunk - 1) / chunk, B);
-  int rc;
+  const IdxArgs a{q, w, key, ctx_len, score, Lmax, Hi, chunk, block_table, n_pages};
   switch (Di) {
-    case 32: rc = launch_hb<32>(HB, T, grid, st, q, w, key, ctx_len, score, Lmax, Hi, chunk); break;
-    case 64: rc = launch_hb<64>(HB, T, grid, st, q, w, key, ctx_len, score, Lmax, Hi, chunk); break;
-    case 128: rc = launch_hb<128>(HB, T, grid, st, q, w, key, ctx_len, score, Lmax, Hi, chunk); break;
+    case 32: launch_hb<32>(HB, T, grid, st, a); break;
+    case 64: launch_hb<64>(HB, T, grid, st, a); break;
+    case 128: launch_hb<128>(HB, T, grid, st, a); break;
     default: return ess_fail(ESS_ERR_UNSUPPORTED, "idx_dim %d (supported: 32, 64, 128)", Di);
   }
-  if (rc != ESS_OK) return rc;
   ESS_HIP(hipGetLastError());
   return ESS_OK;
 }

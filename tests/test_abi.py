@@ -38,7 +38,7 @@ def test_struct_layouts():
     assert C.sizeof(b.EssConfig) == 13 * 4
     assert C.sizeof(b.EssCache) == 5 * 8
     assert C.sizeof(b.EssStats) == 4 * 8
-    assert b.EssStepArgs.B.offset == 48 and b.EssStepArgs.idx_out.offset == 64 and C.sizeof(b.EssStepArgs) == 96
+    assert b.EssStepArgs.B.offset == 48 and b.EssStepArgs.idx_out.offset == 64 and C.sizeof(b.EssStepArgs) == 112 and b.EssStepArgs.block_table.offset == 96
 
 
 def test_config_validation_reports_errors(lib):
