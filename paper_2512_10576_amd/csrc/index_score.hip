@@ -54,7 +54,7 @@ __device__ __forceinline__ void load_row_share(const uint8_t* row, int g, long (
 // scale commutes with the ReLU and the head sum: one multiplication of the exact sum).  A wave's batch
 // of 64 tokens is exactly one page.
 template <int HB, int DI, int T, bool PAGED>
-__global__ __launch_bounds__(kWaves * 64) void k_index_score(const uint8_t* __restrict__ q,
+__global__ __launch_bounds__(kWaves * 64, T == 2 ? 2 : 1) void k_index_score(const uint8_t* __restrict__ q,
                                                               const float* __restrict__ w,
                                                               const uint8_t* __restrict__ key,
                                                               const int32_t* __restrict__ ctx_len,
