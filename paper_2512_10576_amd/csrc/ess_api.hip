@@ -58,7 +58,7 @@ int validate_config(const ess_config* c) {
 }
 
 struct WsLayout {
-  size_t score, slot_idx, hit, miss, n_hit, n_miss, fill_tok, fill_slot, miss_cnt, o_part, lse_part, stats, total;
+  size_t score, slot_idx, hit, miss, n_hit, n_miss, fill_tok, fill_slot, miss_cnt, o_part, lse_part, stats, zero_row, total;
 };
 
 size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -80,6 +80,7 @@ WsLayout ws_layout(const ess_config& c) {
   w.o_part = take(B * T * ESS_MAX_SPLITS * H * ESS_LATENT_DIM * 4);
   w.lse_part = take(B * T * ESS_MAX_SPLITS * H * 4);
   w.stats = take(4 * 8);
+  w.zero_row = take(ESS_ZERO_ROW_BYTES);
   w.total = off;
   return w;
 }
@@ -211,6 +212,7 @@ int ess_create(const ess_config* cfg, ess_ctx** out) {
   ctx->o_part = reinterpret_cast<float*>(base + w.o_part);
   ctx->lse_part = reinterpret_cast<float*>(base + w.lse_part);
   ctx->stats = reinterpret_cast<unsigned long long*>(base + w.stats);
+  ctx->zero_row = base + w.zero_row;
   auto bail = [&](const char* what, hipError_t err) {
     for (int h = 0; h < 2; ++h) {
       if (ctx->ev_book[h]) (void)hipEventDestroy(ctx->ev_book[h]);
@@ -228,6 +230,7 @@ int ess_create(const ess_config* cfg, ess_ctx** out) {
     if ((e = hipEventCreateWithFlags(&ctx->ev_fill[h], hipEventDisableTiming)) != hipSuccess) return bail("hipEventCreate", e);
   }
   if ((e = hipMemset(ctx->stats, 0, 32)) != hipSuccess) return bail("hipMemset", e);
+  if ((e = hipMemset(ctx->zero_row, 0, ESS_ZERO_ROW_BYTES)) != hipSuccess) return bail("hipMemset", e);
   if ((e = hipHostMalloc(reinterpret_cast<void**>(&ctx->host_miss), (size_t)cfg->max_batch * sizeof(int32_t),
                          hipHostMallocMapped)) != hipSuccess) return bail("hipHostMalloc", e);
   memset(ctx->host_miss, 0, (size_t)cfg->max_batch * sizeof(int32_t));

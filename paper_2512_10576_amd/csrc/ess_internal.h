@@ -10,6 +10,7 @@
 #define ESS_ATTN_TILE 32        // entries per attention tile
 #define ESS_MAX_SPLITS 20       // partial results per (b,t): Attn0 splits + Attn1 splits
 #define ESS_ROW_DIM 576
+#define ESS_ZERO_ROW_BYTES 2048  // >= the largest row_stride
 #define ESS_PROF_MAIN 16        // stage marks on the caller's stream per step
 #define ESS_PROF_FILL 2         // fetch kernels per step (one per batch half)
 #define ESS_PROF_EVENTS (ESS_PROF_MAIN + 2 * ESS_PROF_FILL)
@@ -32,6 +33,7 @@ struct ess_ctx {
   float* o_part;                // [B*T, ESS_MAX_SPLITS, H, 512]
   float* lse_part;              // [B*T, ESS_MAX_SPLITS, H]
   unsigned long long* stats;    // [4]
+  uint8_t* zero_row;            // ESS_ZERO_ROW_BYTES of zeros, never written: source of masked attention rows
   size_t ws_bytes;
   // overlap switch (ESS_FLAG_AUTO): per-sequence miss counts of the latest bookkeeping, written by the
   // kernel into pinned host memory and read by the host, without a synchronisation, at the next step

@@ -29,6 +29,7 @@
 // the gathered row loads of tile i+1 are in flight, in registers, while tile
 // i is computed, so one workgroup per CU hides the gather latency by itself.
 #include "ess_internal.h"
+#include <utility>
 #include <hip/hip_bf16.h>
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -596,6 +597,351 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_dma(
   }
 }
 
+// ---------------------------------------------------------------- bf16 entries, second generation
+// Same decomposition as k_attn_partial_dma (four waves x 16 heads, tiles of 32 entries gathered into LDS
+// by global_load_lds), restructured around what the phase timers showed (per tile and wave: ~1750
+// cycles in each product, both bound by LDS reads, and as much again in gather issue, waits and the
+// softmax's cross-lane steps, none of it overlapped):
+//  * V^T is never built.  The A operand of O^T += V^T P^T wants, per lane, 8 entries of one value
+//    column; ds_read_b64_tr_b16 delivers exactly that from rows stored entry-major: in each group
+//    of 16 lanes, source lane 4i+j points at 4 consecutive columns (4j..4j+3) of row i and lane n
+//    receives column n of rows 0..3.  Two such reads (rows 4g+i and 16+4g+i) make one A fragment
+//    whose k order is the order in which S^T leaves the first product.
+//  * Rows have no padding (pitch 1024 bytes); the 16-byte granules of a row are XOR-swizzled with
+//    f(row) = (row&3)<<2 | (row>>2)&3, applied on the way in by letting lane l of the gather fetch
+//    granule l ^ f(row).  The LDS has 64 banks (256 bytes per clock), so a group of 16 lanes is
+//    conflict-free when its 16-byte granules differ mod 16: K fragments (16 rows, one granule each)
+//    because f is a bijection of the row's low four bits, transposing reads (rows 4g..4g+3, 32
+//    bytes each) because f puts the row's low two bits above the granule pair.  (A three-bit f,
+//    enough for 32 banks, made both products 1.7x slower.)
+//  * The running maximum is only moved when a tile exceeds it by more than 2^8 (exponentials stay
+//    below 2^8 relative to the reference, far inside fp32 and bf16 range), so the 128 accumulator
+//    registers are rescaled a few times per split instead of once per tile.
+//  * Four raw buffers: the gathers of three tiles are in flight; those of tile it+3 are issued one at
+//    a time between the MFMAs of tile it, so that a gather instruction that waits for the texture
+//    path does so while the matrix and LDS pipes are busy.
+//  * Cross-lane maxima and sums over the four 16-lane groups use v_permlane32_swap / 16_swap, not LDS.
+// Masked entries (slot < 0) are gathered from a row of zeros, so that no product meets stale LDS.
+constexpr int TRP = 1024;                        // latent row pitch in LDS
+constexpr int TR_KL_BYTES = TILE * TRP;          // 32768
+constexpr int TR_RAW_BYTES = TR_KL_BYTES + RP_BYTES;
+constexpr int TR_NBUF = 4;
+constexpr int TR_LDS_BYTES = TR_NBUF * TR_RAW_BYTES + MAX_TPS * TILE * 4;   // 151552
+constexpr float kLazyMax = 8.0f;
+
+#ifdef ESS_ATTN_PHASE_TIMING
+__device__ unsigned long long ess_dbg_phase[8];
+#define ESS_PH(i)                                                                   \
+  do {                                                                              \
+    if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && tid == 0) {        \
+      const long long t_ = clock64();                                               \
+      ess_dbg_phase[i] += (unsigned long long)(t_ - ph_t);                          \
+      ph_t = t_;                                                                    \
+    }                                                                               \
+  } while (0)
+#else
+#define ESS_PH(i) do { } while (0)
+#endif
+
+// The 128 output accumulators of a wave live in AGPRs a0..a127 under fixed names, outside the
+// compiler's register allocation: every access is an asm statement that names them.  (Left to the
+// allocator they are copied to VGPRs and back once per tile, 256 moves, because the rare rescale
+// multiplies them with vector ALU instructions.)  The statements clobber what they write, so the
+// kernel's register count covers them.  This file is compiled with -amdgpu-mfma-vgpr-form, which
+// keeps the results of the compiler's own MFMAs (the first product) in VGPRs, and the kernel needs
+// fewer than 256 VGPRs, so the compiler itself uses no AGPR here; tests/test_abi.py checks in the
+// generated code that nothing but these statements names one.  368 registers per lane in all, which
+// leaves room on every SIMD for the waves of the fetch kernel that runs beside Attn0.
+#define ESS_ACC_TUPLES(X) X(0, 0, 1, 2, 3) X(1, 4, 5, 6, 7) X(2, 8, 9, 10, 11) X(3, 12, 13, 14, 15) X(4, 16, 17, 18, 19) X(5, 20, 21, 22, 23) X(6, 24, 25, 26, 27) X(7, 28, 29, 30, 31) X(8, 32, 33, 34, 35) X(9, 36, 37, 38, 39) X(10, 40, 41, 42, 43) X(11, 44, 45, 46, 47) X(12, 48, 49, 50, 51) X(13, 52, 53, 54, 55) X(14, 56, 57, 58, 59) X(15, 60, 61, 62, 63) X(16, 64, 65, 66, 67) X(17, 68, 69, 70, 71) X(18, 72, 73, 74, 75) X(19, 76, 77, 78, 79) X(20, 80, 81, 82, 83) X(21, 84, 85, 86, 87) X(22, 88, 89, 90, 91) X(23, 92, 93, 94, 95) X(24, 96, 97, 98, 99) X(25, 100, 101, 102, 103) X(26, 104, 105, 106, 107) X(27, 108, 109, 110, 111) X(28, 112, 113, 114, 115) X(29, 116, 117, 118, 119) X(30, 120, 121, 122, 123) X(31, 124, 125, 126, 127)
+#define ESS_ACC_REGS(X) X(0, 0) X(1, 1) X(2, 2) X(3, 3) X(4, 4) X(5, 5) X(6, 6) X(7, 7) X(8, 8) X(9, 9) X(10, 10) X(11, 11) X(12, 12) X(13, 13) X(14, 14) X(15, 15) X(16, 16) X(17, 17) X(18, 18) X(19, 19) X(20, 20) X(21, 21) X(22, 22) X(23, 23) X(24, 24) X(25, 25) X(26, 26) X(27, 27) X(28, 28) X(29, 29) X(30, 30) X(31, 31) X(32, 32) X(33, 33) X(34, 34) X(35, 35) X(36, 36) X(37, 37) X(38, 38) X(39, 39) X(40, 40) X(41, 41) X(42, 42) X(43, 43) X(44, 44) X(45, 45) X(46, 46) X(47, 47) X(48, 48) X(49, 49) X(50, 50) X(51, 51) X(52, 52) X(53, 53) X(54, 54) X(55, 55) X(56, 56) X(57, 57) X(58, 58) X(59, 59) X(60, 60) X(61, 61) X(62, 62) X(63, 63) X(64, 64) X(65, 65) X(66, 66) X(67, 67) X(68, 68) X(69, 69) X(70, 70) X(71, 71) X(72, 72) X(73, 73) X(74, 74) X(75, 75) X(76, 76) X(77, 77) X(78, 78) X(79, 79) X(80, 80) X(81, 81) X(82, 82) X(83, 83) X(84, 84) X(85, 85) X(86, 86) X(87, 87) X(88, 88) X(89, 89) X(90, 90) X(91, 91) X(92, 92) X(93, 93) X(94, 94) X(95, 95) X(96, 96) X(97, 97) X(98, 98) X(99, 99) X(100, 100) X(101, 101) X(102, 102) X(103, 103) X(104, 104) X(105, 105) X(106, 106) X(107, 107) X(108, 108) X(109, 109) X(110, 110) X(111, 111) X(112, 112) X(113, 113) X(114, 114) X(115, 115) X(116, 116) X(117, 117) X(118, 118) X(119, 119) X(120, 120) X(121, 121) X(122, 122) X(123, 123) X(124, 124) X(125, 125) X(126, 126) X(127, 127)
+
+template <int VB> __device__ __forceinline__ void pv_mfma(const bf16x8& a, const bf16x8& b);
+#define X(vb, r0, r1, r2, r3)                                                                        \
+  template <> __device__ __forceinline__ void pv_mfma<vb>(const bf16x8& a, const bf16x8& b) {        \
+    asm volatile("v_mfma_f32_16x16x32_bf16 a[" #r0 ":" #r3 "], %0, %1, a[" #r0 ":" #r3 "]"           \
+                 : : "v"(a), "v"(b) : "a" #r0, "a" #r1, "a" #r2, "a" #r3);                           \
+  }
+ESS_ACC_TUPLES(X)
+#undef X
+template <int BASE, int... I>
+__device__ __forceinline__ void pv_chunk(const bf16x8 (&fv)[sizeof...(I)], const bf16x8& pb, std::integer_sequence<int, I...>) {
+  (pv_mfma<BASE + I>(fv[I], pb), ...);
+}
+__device__ __forceinline__ void acc_zero() {
+#define X(n, r) asm volatile("v_accvgpr_write_b32 a" #r ", 0" : : : "a" #r);
+  ESS_ACC_REGS(X)
+#undef X
+}
+// a[4 vb + i] holds row 4g+i of value block vb for head n16: every register of a lane scales by the lane's alpha
+__device__ __forceinline__ void acc_scale(float alpha) {
+  float t;
+#define X(n, r) asm volatile("v_accvgpr_read_b32 %0, a" #r "\n\tv_mul_f32 %0, %0, %1\n\tv_accvgpr_write_b32 a" #r ", %0" \
+                             : "=&v"(t) : "v"(alpha) : "a" #r);
+  ESS_ACC_REGS(X)
+#undef X
+}
+__device__ __forceinline__ void acc_read(float (&o)[128]) {
+#define X(n, r) asm volatile("v_accvgpr_read_b32 %0, a" #r : "=v"(o[n]));
+  ESS_ACC_REGS(X)
+#undef X
+}
+
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) short4v lds_short4v;
+typedef unsigned uint2v __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ int tr_swz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+
+__device__ __forceinline__ bf16x8 tr_frag(uint32_t addr_lo, uint32_t addr_hi) {
+  const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<lds_short4v*>(addr_lo));
+  const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<lds_short4v*>(addr_hi));
+  typedef short short8v __attribute__((ext_vector_type(8)));
+  const short8v x = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, x);
+}
+
+// max / sum over the four lanes that share lane % 16 (one per 16-lane group), result in all four
+__device__ __forceinline__ float group_max(float x) {
+  uint2v a = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  const float y = fmaxf(__uint_as_float(a.x), __uint_as_float(a.y));
+  uint2v b = __builtin_amdgcn_permlane16_swap(__float_as_uint(y), __float_as_uint(y), false, false);
+  return fmaxf(__uint_as_float(b.x), __uint_as_float(b.y));
+}
+__device__ __forceinline__ float group_sum(float x) {
+  uint2v a = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  const float y = __uint_as_float(a.x) + __uint_as_float(a.y);
+  uint2v b = __builtin_amdgcn_permlane16_swap(__float_as_uint(y), __float_as_uint(y), false, false);
+  return __uint_as_float(b.x) + __uint_as_float(b.y);
+}
+
+__global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
+    const uint16_t* __restrict__ q, const uint8_t* __restrict__ pool, const int32_t* __restrict__ list,
+    const int32_t* __restrict__ n_list, int T, int H, int kk, int S, int row_stride, float scale_log2e, int split0,
+    int nsplit, float* __restrict__ o_part, float* __restrict__ lse_part, const uint8_t* __restrict__ zero_row) {
+  extern __shared__ __align__(16) uint8_t lds[];
+  int32_t* slot_cache = reinterpret_cast<int32_t*>(lds + TR_NBUF * TR_RAW_BYTES);   // [MAX_TPS][32]
+  const uint32_t lds0 = lds_addr_of(lds);
+
+  const int split = blockIdx.x;
+  const int bt = blockIdx.y;
+  const int b = bt / T;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = lane >> 4, n16 = lane & 15;
+  const int head0 = (blockIdx.z * 4 + wave) * 16;
+  const bool wave_active = head0 < H;
+
+  const int n = n_list ? min(n_list[bt], kk) : kk;
+  const int tiles_total = (n + TILE - 1) / TILE;
+  const int tps = min((tiles_total + nsplit - 1) / nsplit, MAX_TPS);
+  const int tile_begin = split * tps;
+  const int tile_end = min(tile_begin + tps, tiles_total);
+  const int my_tiles = max(tile_end - tile_begin, 0);
+
+  bf16x8 qb[KSTEPS];
+  {
+    const int head = head0 + n16;
+    const uint16_t* qrow = q + ((size_t)bt * H + min(head, H - 1)) * ESS_ROW_DIM;
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+      uint4 x = *reinterpret_cast<const uint4*>(qrow + ks * 32 + g * 8);
+      if (head >= H) x = make_uint4(0, 0, 0, 0);
+      qb[ks] = *reinterpret_cast<bf16x8*>(&x);
+    }
+  }
+  acc_zero();
+  float m_ref = -__builtin_inff(), l_run = 0.f;
+
+  const int32_t* lrow = list + (size_t)bt * kk;
+  const uint8_t* pbase = pool + (size_t)b * S * row_stride;
+  for (int j = tid; j < my_tiles * TILE; j += NTH) {
+    const int e = tile_begin * TILE + j;
+    int sl = e < n ? lrow[e] : -1;
+    if (sl >= S) sl = -1;
+    slot_cache[j] = sl;
+  }
+  wait_vmcnt<0>();                             // q and list loads are done: from here only the gathers count
+  __syncthreads();
+
+  // Gathers of one tile into raw buffer it % 4: this wave brings rows 8w..8w+7 (steps 0..7, one
+  // instruction per row) and the rope parts of the same rows (step 8).
+  const int rr = wave * 8 + (lane >> 3);
+  const int rope_off = 1024 + (((lane & 7) ^ (rr & 7)) * 16);
+  // source rows of one tile: read from LDS in one go, so that no gather waits on the LDS queue later
+  auto gather_sources = [&](int it, const uint8_t* (&src)[DMA_PER_TILE]) {
+    const int32_t* ts = slot_cache + it * TILE;
+    int sl[DMA_PER_TILE];
+#pragma unroll
+    for (int r8 = 0; r8 < 8; ++r8) sl[r8] = ts[wave * 8 + r8];
+    sl[8] = ts[rr];
+#pragma unroll
+    for (int r8 = 0; r8 < DMA_PER_TILE; ++r8) src[r8] = sl[r8] >= 0 ? pbase + (size_t)sl[r8] * row_stride : zero_row;
+  };
+  auto gather_step = [&](int it, int step, const uint8_t* const (&src)[DMA_PER_TILE]) {
+    const uint32_t raw = lds0 + (uint32_t)((it % TR_NBUF) * TR_RAW_BYTES);
+    if (step < 8) {
+      const int row = wave * 8 + step;
+      dma16(src[step] + ((lane ^ tr_swz(row)) << 4), raw + (uint32_t)(row * TRP));
+    } else {
+      dma16(src[8] + rope_off, raw + (uint32_t)(TR_KL_BYTES + wave * 1024));
+    }
+  };
+  for (int it = 0; it < min(my_tiles, TR_NBUF - 1); ++it) {
+    const uint8_t* src[DMA_PER_TILE];
+    gather_sources(it, src);
+#pragma unroll
+    for (int step = 0; step < DMA_PER_TILE; ++step) gather_step(it, step, src);
+  }
+
+  // lane constants of the two LDS access patterns
+  const int fk = tr_swz(n16);                                   // K fragments: row n16 (and 16 + n16)
+  uint32_t koff[4];                                             // by ks & 3; + 256 * (ks >> 2) is an immediate
+#pragma unroll
+  for (int c = 0; c < 4; ++c) koff[c] = (uint32_t)(n16 * TRP + (((4 * c + g) ^ fk) << 4));
+  const int ti = n16 >> 2, tj = n16 & 3;                        // transposing reads: source row 4g + ti, columns 4 tj ..
+  const int trow = 4 * g + ti;
+  const uint32_t c4 = (uint32_t)((((tj >> 1) ^ tr_swz(trow)) & 15) << 4);
+  uint32_t voff[8];                                             // by vb & 7; + 256 * (vb >> 3) is an immediate
+#pragma unroll
+  for (int c = 0; c < 8; ++c) voff[c] = (uint32_t)(trow * TRP + (tj & 1) * 8) + (((uint32_t)(32 * c)) ^ c4);
+
+#ifdef ESS_ATTN_PHASE_TIMING
+  long long ph_t = clock64();
+#endif
+  for (int it = 0; it < my_tiles; ++it) {
+    const uint32_t KLa = lds0 + (uint32_t)((it % TR_NBUF) * TR_RAW_BYTES);
+    const uint8_t* KL = lds + (it % TR_NBUF) * TR_RAW_BYTES;
+    const uint8_t* RP = KL + TR_KL_BYTES;
+    const int32_t* tile_slot = slot_cache + it * TILE;
+    // this wave's gathers of tile `it` have landed when at most those of the later tiles are outstanding
+    const int later = min(my_tiles - 1 - it, TR_NBUF - 2);
+    if (later >= 2) wait_vmcnt<2 * DMA_PER_TILE>(); else if (later == 1) wait_vmcnt<DMA_PER_TILE>(); else wait_vmcnt<0>();
+    ESS_PH(4);
+    __syncthreads();                           // ... everyone's did; and everyone is done with tile it-1
+    ESS_PH(5);
+    const bool more = it + TR_NBUF - 1 < my_tiles;   // tile it+3 goes into the buffer tile it-1 used
+    const uint8_t* src[DMA_PER_TILE];
+    if (more) gather_sources(it + TR_NBUF - 1, src);
+    if (!wave_active) {
+      if (more) {
+#pragma unroll
+        for (int step = 0; step < DMA_PER_TILE; ++step) gather_step(it + TR_NBUF - 1, step, src);
+      }
+      continue;
+    }
+    ESS_PH(0);
+
+    // ---- S^T = K Q^T; A fragments read six k-steps ahead of the MFMAs that use them; three gather
+    // instructions of tile it+3 after each chunk of fragment reads
+    floatx4 s0 = floatx4{0.f, 0.f, 0.f, 0.f}, s1 = s0;
+    constexpr int CH = 6;
+    bf16x8 fa[2][CH], fb[2][CH];
+    auto load_chunk = [&](int c, bf16x8 (&da)[CH], bf16x8 (&db)[CH]) {
+#pragma unroll
+      for (int j = 0; j < CH; ++j) {
+        const int ks = c * CH + j;
+        if (ks < 16) {
+          da[j] = *reinterpret_cast<const bf16x8*>(KL + koff[ks & 3] + 256 * (ks >> 2));
+          db[j] = *reinterpret_cast<const bf16x8*>(KL + koff[ks & 3] + 256 * (ks >> 2) + 16 * TRP);
+        } else {
+          const int p = (ks - 16) * 4 + g;
+          da[j] = *reinterpret_cast<const bf16x8*>(RP + n16 * 128 + ((p ^ (n16 & 7)) * 16));
+          db[j] = *reinterpret_cast<const bf16x8*>(RP + (16 + n16) * 128 + ((p ^ (n16 & 7)) * 16));
+        }
+      }
+    };
+    load_chunk(0, fa[0], fb[0]);
+#pragma unroll
+    for (int c = 0; c < KSTEPS / CH; ++c) {
+      if (c + 1 < KSTEPS / CH) load_chunk(c + 1, fa[(c + 1) & 1], fb[(c + 1) & 1]);
+      if (more) {
+#pragma unroll
+        for (int step = 3 * c; step < 3 * c + 3; ++step) gather_step(it + TR_NBUF - 1, step, src);
+      }
+#pragma unroll
+      for (int j = 0; j < CH; ++j) {
+        s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[c & 1][j], qb[c * CH + j], s0, 0, 0, 0);
+        s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[c & 1][j], qb[c * CH + j], s1, 0, 0, 0);
+      }
+    }
+    const int4 v0 = *reinterpret_cast<const int4*>(tile_slot + g * 4);
+    const int4 v1 = *reinterpret_cast<const int4*>(tile_slot + 16 + g * 4);
+    const bool ok[8] = {v0.x >= 0, v0.y >= 0, v0.z >= 0, v0.w >= 0, v1.x >= 0, v1.y >= 0, v1.z >= 0, v1.w >= 0};
+    float z[8];
+    ESS_PH(1);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      z[i] = ok[i] ? s0[i] * scale_log2e : -__builtin_inff();
+      z[4 + i] = ok[4 + i] ? s1[i] * scale_log2e : -__builtin_inff();
+    }
+    const float tmax = group_max(fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])), fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7]))));
+    // move the reference only when this tile exceeds it by more than 2^kLazyMax (always from -inf)
+    const bool move = tmax > m_ref + kLazyMax;
+    if (__any(move)) {
+      const float m_new = move ? tmax : m_ref;
+      const float alpha = m_new == -__builtin_inff() ? 1.f : exp2f(m_ref - m_new);   // m_ref = -inf: 0, acc is 0 anyway
+      l_run *= alpha;
+      m_ref = m_new;
+      acc_scale(alpha);
+    }
+    const float m_safe = (m_ref == -__builtin_inff()) ? 0.f : m_ref;
+    float p[8], psum = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      p[j] = exp2f(z[j] - m_safe);
+      psum += p[j];
+    }
+    l_run += psum;
+    uint4 pw = make_uint4(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7]));
+    const bf16x8 pb = *reinterpret_cast<bf16x8*>(&pw);
+    ESS_PH(2);
+
+    // ---- O^T += V^T P^T, A fragments by transposing reads, eight blocks ahead
+    constexpr int CV = 8;
+    bf16x8 fv[2][CV];
+    auto load_v = [&](int c, bf16x8 (&d)[CV]) {
+#pragma unroll
+      for (int j = 0; j < CV; ++j) {
+        const int vb = c * CV + j;
+        const uint32_t a = KLa + voff[vb & 7] + 256u * (uint32_t)(vb >> 3);
+        d[j] = tr_frag(a, a + 16 * TRP);
+      }
+    };
+    static_assert(VBLOCKS / CV == 4, "four chunks of value blocks");
+    constexpr auto seq = std::make_integer_sequence<int, CV>{};
+    load_v(0, fv[0]);
+    load_v(1, fv[1]);
+    pv_chunk<0 * CV>(fv[0], pb, seq);
+    load_v(2, fv[0]);
+    pv_chunk<1 * CV>(fv[1], pb, seq);
+    load_v(3, fv[1]);
+    pv_chunk<2 * CV>(fv[0], pb, seq);
+    pv_chunk<3 * CV>(fv[1], pb, seq);
+    ESS_PH(3);
+  }
+  // the hazard logic does not see the MFMAs inside the asm statements: let the last ones retire
+  // before their results are read
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+
+  {
+    const int head = head0 + n16;
+    const float l_tot = group_sum(l_run);
+    const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+    float o[128];
+    acc_read(o);
+    if (head < H) {
+      const size_t prow = ((size_t)bt * ESS_MAX_SPLITS + split0 + split) * H + head;
+      float* op = o_part + prow * ESS_LATENT_DIM;
+#pragma unroll
+      for (int vb = 0; vb < VBLOCKS; ++vb) {
+        const float4 ov = make_float4(o[4 * vb] * inv, o[4 * vb + 1] * inv, o[4 * vb + 2] * inv, o[4 * vb + 3] * inv);
+        *reinterpret_cast<float4*>(op + vb * 16 + g * 4) = ov;
+      }
+      if (g == 0) lse_part[prow] = l_tot > 0.f ? (m_ref + log2f(l_tot)) * kLn2 : -__builtin_inff();
+    }
+  }
+}
+
 // out[bt,h,:] = sum_s exp(lse_s - lse) * o_s ;  lse = log sum_s exp(lse_s).  One wave per (bt,h).
 __global__ __launch_bounds__(256) void k_attn_merge(const float* __restrict__ o_part, const float* __restrict__ lse_part,
                                                     int H, int nsplit, int total_rows, uint16_t* __restrict__ out,
@@ -658,10 +1004,18 @@ int ess_launch_attn_partial(ess_ctx* ctx, const void* q, const uint8_t* slot_poo
   float* lp = ctx->lse_part + (size_t)b0 * T * ESS_MAX_SPLITS * c.attn_heads;
   int rc;
   if (c.latent_fmt == ESS_FMT_BF16) {
-    ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_partial_dma<1>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, DMA_LDS_BYTES));
-    hipLaunchKernelGGL((k_attn_partial_dma<1>), grid, dim3(NTH), DMA_LDS_BYTES, st, qq, slot_pool, list, n_list, T,
-                       c.attn_heads, c.topk, c.slots_per_seq, c.row_stride, sc, split0, nsplit, op, lp);
+    static const bool old_path = getenv("ESS_ATTN_OLD") != nullptr;
+    if (old_path) {
+      ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_partial_dma<1>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, DMA_LDS_BYTES));
+      hipLaunchKernelGGL((k_attn_partial_dma<1>), grid, dim3(NTH), DMA_LDS_BYTES, st, qq, slot_pool, list, n_list, T,
+                         c.attn_heads, c.topk, c.slots_per_seq, c.row_stride, sc, split0, nsplit, op, lp);
+    } else {
+      ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_partial_tr),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, TR_LDS_BYTES));
+      hipLaunchKernelGGL(k_attn_partial_tr, grid, dim3(NTH), TR_LDS_BYTES, st, qq, slot_pool, list, n_list, T,
+                         c.attn_heads, c.topk, c.slots_per_seq, c.row_stride, sc, split0, nsplit, op, lp, ctx->zero_row);
+    }
     rc = ESS_OK;
   } else
     rc = launch_fmt<ESS_FMT_FP8>(grid, st, qq, slot_pool, list, n_list, T, c.attn_heads, c.topk, c.slots_per_seq,

@@ -66,3 +66,32 @@ def test_config_validation_reports_errors(lib):
     bad.struct_size = 8
     with pytest.raises(b.EssError):
         b.workspace_bytes(bad)
+
+
+def test_attention_kernel_agprs_are_only_named_by_its_own_asm(tmp_path):
+    """k_attn_partial_tr keeps its 128 output accumulators in AGPRs a0..a127 that it names itself; the
+    compiler must not use any AGPR in that kernel.  Checked in the ISA the build flags produce."""
+    import collections
+    import subprocess
+    from paper_2512_10576_amd import build
+    out = tmp_path / "sparse_mla.s"
+    cmd = [build._hipcc(), *build.compile_flags("sparse_mla.hip"), "-S", "--cuda-device-only",
+           os.path.join(build.CSRC, "sparse_mla.hip"), "-o", str(out)]
+    subprocess.run(cmd, check=True, stdout=subprocess.PIPE, stderr=subprocess.STDOUT)
+    lines = out.read_text().split("\n")
+    start = [i for i, l in enumerate(lines) if re.match(r"^_ZN\S*k_attn_partial_tr\S*:", l)][0]
+    end = [i for i in range(start, len(lines)) if "s_endpgm" in lines[i]][0]
+    seen = collections.Counter()
+    for l in lines[start:end]:
+        t = l.strip()
+        if not t or t.startswith((";", ".")):
+            continue
+        if re.search(r"\ba\d+\b|\ba\[\d+:\d+\]", t):
+            seen[t.split()[0]] += 1
+            if t.startswith("v_mfma"):      # accumulate in place: a[x:y], v, v, a[x:y]
+                assert re.search(r"a\[(\d+):(\d+)\], v\[\d+:\d+\], v\[\d+:\d+\], a\[\1:\2\]", t), t
+    # 32 accumulating MFMAs; 128 zero writes + 128 rescale writes; 128 rescale reads + 128 final reads
+    assert seen == {"v_mfma_f32_16x16x32_bf16": 32, "v_accvgpr_write_b32": 256, "v_accvgpr_read_b32": 256}, seen
+    text = "\n".join(lines[end:end + 60])
+    m = re.search(r"\.amdhsa_accum_offset (\d+)", text)
+    assert m is not None
