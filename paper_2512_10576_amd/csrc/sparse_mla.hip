@@ -343,16 +343,11 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial(
 // bf16 entries: the same computation with the rows brought into LDS by the memory system itself
 // (global_load_lds_dwordx4: a wave instruction moves 64 x 16 bytes from per-lane global addresses to
 // consecutive LDS addresses, no registers involved).  One wave instruction per 1024-byte latent
-// part of a row, one per eight 128-byte rope parts; three raw-row buffers so that the gathers of
-// tiles i+1 and i+2 are in flight while tile i is computed; V^T is produced LDS -> LDS.  The loads
-// are issued through inline assembly because the compiler, seeing an LDS-writing load, would wait
-// for every outstanding one before the next LDS read; completion is tracked by hand with
-// s_waitcnt vmcnt (memory loads complete in issue order, 9 of them per wave and tile).
-constexpr int KLP = 1024 + 16;                 // pitch of a raw latent row in LDS
-constexpr int KL_BYTES = TILE * KLP;           // 33280
+// part of a row, one per eight 128-byte rope parts.  The loads are issued through inline assembly
+// because the compiler, seeing an LDS-writing load, would wait for every outstanding one before the
+// next LDS read; completion is tracked by hand with s_waitcnt vmcnt (memory loads complete in issue
+// order, 9 of them per wave and tile).
 constexpr int RP_BYTES = TILE * 128;           // 4096: rope parts, 16-byte pieces XOR-swizzled by row
-constexpr int RAW_BYTES = KL_BYTES + RP_BYTES; // one raw tile
-constexpr int DMA_LDS_BYTES = 3 * RAW_BYTES + VT_BYTES + MAX_TPS * TILE * 4;   // 148992
 constexpr int DMA_PER_TILE = 9;                // wave instructions per tile: 8 latent rows + 1 rope group
 
 __device__ __forceinline__ uint32_t lds_addr_of(const void* p) {
@@ -369,239 +364,10 @@ __device__ __forceinline__ void wait_vmcnt() {     // vmcnt <= N, other counters
   __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
 }
 
-template <int HB>
-__global__ __launch_bounds__(NTH, 1) void k_attn_partial_dma(
-    const uint16_t* __restrict__ q, const uint8_t* __restrict__ pool, const int32_t* __restrict__ list,
-    const int32_t* __restrict__ n_list, int T, int H, int kk, int S, int row_stride, float scale_log2e, int split0,
-    int nsplit, float* __restrict__ o_part, float* __restrict__ lse_part) {
-  extern __shared__ __align__(16) uint8_t lds[];
-  uint8_t* Vt = lds + 3 * RAW_BYTES;
-  int32_t* slot_cache = reinterpret_cast<int32_t*>(lds + 3 * RAW_BYTES + VT_BYTES);   // [MAX_TPS][32]
-  const uint32_t lds0 = lds_addr_of(lds);
-
-  const int split = blockIdx.x;
-  const int bt = blockIdx.y;
-  const int b = bt / T;
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int g = lane >> 4, n16 = lane & 15;
-  constexpr int HPW = 16 * HB;
-  const int head0 = (blockIdx.z * 4 + wave) * HPW;
-  const bool wave_active = head0 < H;
-
-  const int n = n_list ? min(n_list[bt], kk) : kk;
-  const int tiles_total = (n + TILE - 1) / TILE;
-  const int tps = min((tiles_total + nsplit - 1) / nsplit, MAX_TPS);
-  const int tile_begin = split * tps;
-  const int tile_end = min(tile_begin + tps, tiles_total);
-  const int my_tiles = max(tile_end - tile_begin, 0);
-
-  bf16x8 qb[HB][KSTEPS];
-#pragma unroll
-  for (int hb = 0; hb < HB; ++hb) {
-    const int head = head0 + hb * 16 + n16;
-    const uint16_t* qrow = q + ((size_t)bt * H + min(head, H - 1)) * ESS_ROW_DIM;
-#pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) {
-      uint4 x = *reinterpret_cast<const uint4*>(qrow + ks * 32 + g * 8);
-      if (head >= H) x = make_uint4(0, 0, 0, 0);
-      qb[hb][ks] = *reinterpret_cast<bf16x8*>(&x);
-    }
-  }
-  floatx4 acc[HB][VBLOCKS];
-#pragma unroll
-  for (int hb = 0; hb < HB; ++hb)
-#pragma unroll
-    for (int vb = 0; vb < VBLOCKS; ++vb) acc[hb][vb] = floatx4{0.f, 0.f, 0.f, 0.f};
-  float m_run[HB], l_run[HB];
-#pragma unroll
-  for (int hb = 0; hb < HB; ++hb) { m_run[hb] = -__builtin_inff(); l_run[hb] = 0.f; }
-
-  const int32_t* lrow = list + (size_t)bt * kk;
-  const uint8_t* pbase = pool + (size_t)b * S * row_stride;
-  for (int j = tid; j < my_tiles * TILE; j += NTH) {
-    const int e = tile_begin * TILE + j;
-    int sl = e < n ? lrow[e] : -1;
-    if (sl >= S) sl = -1;
-    slot_cache[j] = sl;
-  }
-  wait_vmcnt<0>();                             // q and list loads are done: from here only the gathers count
-  __syncthreads();
-
-  // gathers of tile `it` into raw buffer it % 3: this wave brings rows 8w..8w+7 and rope group w
-  auto issue_tile = [&](int it) {
-    const int32_t* ts = slot_cache + it * TILE;
-    const uint32_t raw = lds0 + (uint32_t)((it % 3) * RAW_BYTES);
-    int sl[9];                                 // all slot reads first, then the nine gathers back to back
-#pragma unroll
-    for (int r8 = 0; r8 < 8; ++r8) sl[r8] = max(ts[wave * 8 + r8], 0);   // masked rows read slot 0 (valid memory)
-    const int rr = wave * 8 + (lane >> 3);
-    sl[8] = max(ts[rr], 0);
-#pragma unroll
-    for (int r8 = 0; r8 < 8; ++r8)
-      dma16(pbase + (size_t)sl[r8] * row_stride + lane * 16, raw + (uint32_t)((wave * 8 + r8) * KLP));
-    dma16(pbase + (size_t)sl[8] * row_stride + 1024 + (((lane & 7) ^ (rr & 7)) * 16),
-          raw + (uint32_t)(KL_BYTES + wave * 1024));
-  };
-
-  if (my_tiles > 0) issue_tile(0);
-  if (my_tiles > 1) issue_tile(1);
-
-  for (int it = 0; it < my_tiles; ++it) {
-    const uint8_t* KL = lds + (it % 3) * RAW_BYTES;
-    const uint8_t* RP = KL + KL_BYTES;
-    const int32_t* tile_slot = slot_cache + it * TILE;
-    if (it + 1 < my_tiles) wait_vmcnt<DMA_PER_TILE>(); else wait_vmcnt<0>();   // this wave's gathers of tile `it` landed
-    __syncthreads();                           // ... everyone's did; and everyone is done with tile it-1
-    if (it + 2 < my_tiles) issue_tile(it + 2); // into the buffer tile it-1 used
-
-    // ---- V^T from the raw rows: 4 rows x 8 dims per unit, rows permuted, granules swizzled
-#pragma unroll
-    for (int i = 0; i < UPT; ++i) {
-      const int u = tid + i * NTH;
-      const int rg = u & 7, cc = u >> 3;       // row group (4 rows), 16-byte column piece
-      uint4 x[4];
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        x[r] = *reinterpret_cast<const uint4*>(KL + (rg * 4 + r) * KLP + cc * 16);
-        if (tile_slot[rg * 4 + r] < 0) x[r] = make_uint4(0, 0, 0, 0);
-      }
-      const int gq = rg & 3, half = rg >> 2;
-      const uint32_t* x0 = reinterpret_cast<const uint32_t*>(&x[0]);
-      const uint32_t* x1 = reinterpret_cast<const uint32_t*>(&x[1]);
-      const uint32_t* x2 = reinterpret_cast<const uint32_t*>(&x[2]);
-      const uint32_t* x3 = reinterpret_cast<const uint32_t*>(&x[3]);
-#pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        const uint32_t a0 = x0[p], a1 = x1[p], a2 = x2[p], a3 = x3[p];
-        const uint2 even = make_uint2((a0 & 0xffffu) | (a1 << 16), (a2 & 0xffffu) | (a3 << 16));
-        const uint2 odd = make_uint2((a0 >> 16) | (a1 & 0xffff0000u), (a2 >> 16) | (a3 & 0xffff0000u));
-        const int v0 = cc * 8 + 2 * p, v1 = v0 + 1;
-        *reinterpret_cast<uint2*>(Vt + v0 * 64 + vt_granule(v0, gq) * 16 + half * 8) = even;
-        *reinterpret_cast<uint2*>(Vt + v1 * 64 + vt_granule(v1, gq) * 16 + half * 8) = odd;
-      }
-    }
-
-    bf16x8 pb[HB];
-    if (wave_active) {
-      // ---- S^T = K Q^T; A fragments read six k-steps ahead of the MFMAs that use them
-      floatx4 s[HB][2];
-#pragma unroll
-      for (int hb = 0; hb < HB; ++hb) s[hb][0] = s[hb][1] = floatx4{0.f, 0.f, 0.f, 0.f};
-      constexpr int CH = 6;
-      bf16x8 fa[2][CH], fb[2][CH];
-      auto load_chunk = [&](int c, bf16x8 (&da)[CH], bf16x8 (&db)[CH]) {
-#pragma unroll
-        for (int j = 0; j < CH; ++j) {
-          const int ks = c * CH + j;
-          if (ks < 16) {
-            da[j] = *reinterpret_cast<const bf16x8*>(KL + n16 * KLP + ks * 64 + g * 16);
-            db[j] = *reinterpret_cast<const bf16x8*>(KL + (16 + n16) * KLP + ks * 64 + g * 16);
-          } else {
-            const int p = (ks - 16) * 4 + g;
-            da[j] = *reinterpret_cast<const bf16x8*>(RP + n16 * 128 + ((p ^ (n16 & 7)) * 16));
-            db[j] = *reinterpret_cast<const bf16x8*>(RP + (16 + n16) * 128 + ((p ^ (n16 & 7)) * 16));
-          }
-        }
-      };
-      load_chunk(0, fa[0], fb[0]);
-#pragma unroll
-      for (int c = 0; c < KSTEPS / CH; ++c) {
-        if (c + 1 < KSTEPS / CH) load_chunk(c + 1, fa[(c + 1) & 1], fb[(c + 1) & 1]);
-#pragma unroll
-        for (int j = 0; j < CH; ++j) {
-#pragma unroll
-          for (int hb = 0; hb < HB; ++hb) {
-            s[hb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[c & 1][j], qb[hb][c * CH + j], s[hb][0], 0, 0, 0);
-            s[hb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[c & 1][j], qb[hb][c * CH + j], s[hb][1], 0, 0, 0);
-          }
-        }
-      }
-      const int4 v0 = *reinterpret_cast<const int4*>(tile_slot + g * 4);
-      const int4 v1 = *reinterpret_cast<const int4*>(tile_slot + 16 + g * 4);
-      const bool ok[8] = {v0.x >= 0, v0.y >= 0, v0.z >= 0, v0.w >= 0, v1.x >= 0, v1.y >= 0, v1.z >= 0, v1.w >= 0};
-#pragma unroll
-      for (int hb = 0; hb < HB; ++hb) {
-        float z[8];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          z[i] = ok[i] ? s[hb][0][i] * scale_log2e : -__builtin_inff();
-          z[4 + i] = ok[4 + i] ? s[hb][1][i] * scale_log2e : -__builtin_inff();
-        }
-        float tmax = fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])), fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7])));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-        const float m_new = fmaxf(m_run[hb], tmax);
-        const float m_safe = (m_new == -__builtin_inff()) ? 0.f : m_new;
-        const float alpha = exp2f(m_run[hb] - m_safe);
-        float p[8], psum = 0.f;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          p[j] = exp2f(z[j] - m_safe);
-          psum += p[j];
-        }
-        l_run[hb] = l_run[hb] * alpha + psum;
-        m_run[hb] = m_new;
-        if (__any(alpha != 1.0f)) {
-#pragma unroll
-          for (int vb = 0; vb < VBLOCKS; ++vb) {
-            acc[hb][vb][0] *= alpha; acc[hb][vb][1] *= alpha; acc[hb][vb][2] *= alpha; acc[hb][vb][3] *= alpha;
-          }
-        }
-        uint4 pw = make_uint4(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7]));
-        pb[hb] = *reinterpret_cast<bf16x8*>(&pw);
-      }
-    }
-    __syncthreads();                           // V^T is complete
-    if (wave_active) {
-      // ---- O^T += V^T P^T, A fragments read eight blocks ahead
-      constexpr int CV = 8;
-      bf16x8 fv[2][CV];
-      auto load_v = [&](int c, bf16x8 (&d)[CV]) {
-#pragma unroll
-        for (int j = 0; j < CV; ++j) {
-          const int v = (c * CV + j) * 16 + n16;
-          d[j] = *reinterpret_cast<const bf16x8*>(Vt + v * 64 + vt_granule(v, g) * 16);
-        }
-      };
-      load_v(0, fv[0]);
-#pragma unroll
-      for (int c = 0; c < VBLOCKS / CV; ++c) {
-        if (c + 1 < VBLOCKS / CV) load_v(c + 1, fv[(c + 1) & 1]);
-#pragma unroll
-        for (int j = 0; j < CV; ++j)
-#pragma unroll
-          for (int hb = 0; hb < HB; ++hb)
-            acc[hb][c * CV + j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fv[c & 1][j], pb[hb], acc[hb][c * CV + j], 0, 0, 0);
-      }
-    }
-  }
-
-#pragma unroll
-  for (int hb = 0; hb < HB; ++hb) {
-    const int head = head0 + hb * 16 + n16;
-    float l_tot = l_run[hb];
-    l_tot += __shfl_xor(l_tot, 16, 64);
-    l_tot += __shfl_xor(l_tot, 32, 64);
-    const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-    if (head < H) {
-      const size_t prow = ((size_t)bt * ESS_MAX_SPLITS + split0 + split) * H + head;
-      float* op = o_part + prow * ESS_LATENT_DIM;
-#pragma unroll
-      for (int vb = 0; vb < VBLOCKS; ++vb) {
-        const float4 o = make_float4(acc[hb][vb][0] * inv, acc[hb][vb][1] * inv, acc[hb][vb][2] * inv, acc[hb][vb][3] * inv);
-        *reinterpret_cast<float4*>(op + vb * 16 + g * 4) = o;
-      }
-      if (g == 0) lse_part[prow] = l_tot > 0.f ? (m_run[hb] + log2f(l_tot)) * kLn2 : -__builtin_inff();
-    }
-  }
-}
-
-// ---------------------------------------------------------------- bf16 entries, second generation
-// Same decomposition as k_attn_partial_dma (four waves x 16 heads, tiles of 32 entries gathered into LDS
-// by global_load_lds), restructured around what the phase timers showed (per tile and wave: ~1750
-// cycles in each product, both bound by LDS reads, and as much again in gather issue, waits and the
-// softmax's cross-lane steps, none of it overlapped):
+// ---------------------------------------------------------------- bf16 entries
+// Four waves x 16 heads, tiles of 32 entries gathered into LDS by global_load_lds.  What the kernel is
+// built around (a first version that built V^T in LDS, rescaled every tile and left the accumulators
+// to the register allocator spent 1100 instructions per tile and wave, 68 of them MFMAs):
 //  * V^T is never built.  The A operand of O^T += V^T P^T wants, per lane, 8 entries of one value
 //    column; ds_read_b64_tr_b16 delivers exactly that from rows stored entry-major: in each group
 //    of 16 lanes, source lane 4i+j points at 4 consecutive columns (4j..4j+3) of row i and lane n
@@ -1004,18 +770,10 @@ int ess_launch_attn_partial(ess_ctx* ctx, const void* q, const uint8_t* slot_poo
   float* lp = ctx->lse_part + (size_t)b0 * T * ESS_MAX_SPLITS * c.attn_heads;
   int rc;
   if (c.latent_fmt == ESS_FMT_BF16) {
-    static const bool old_path = getenv("ESS_ATTN_OLD") != nullptr;
-    if (old_path) {
-      ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_partial_dma<1>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, DMA_LDS_BYTES));
-      hipLaunchKernelGGL((k_attn_partial_dma<1>), grid, dim3(NTH), DMA_LDS_BYTES, st, qq, slot_pool, list, n_list, T,
-                         c.attn_heads, c.topk, c.slots_per_seq, c.row_stride, sc, split0, nsplit, op, lp);
-    } else {
-      ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_partial_tr),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, TR_LDS_BYTES));
-      hipLaunchKernelGGL(k_attn_partial_tr, grid, dim3(NTH), TR_LDS_BYTES, st, qq, slot_pool, list, n_list, T,
-                         c.attn_heads, c.topk, c.slots_per_seq, c.row_stride, sc, split0, nsplit, op, lp, ctx->zero_row);
-    }
+    ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_partial_tr),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, TR_LDS_BYTES));
+    hipLaunchKernelGGL(k_attn_partial_tr, grid, dim3(NTH), TR_LDS_BYTES, st, qq, slot_pool, list, n_list, T,
+                       c.attn_heads, c.topk, c.slots_per_seq, c.row_stride, sc, split0, nsplit, op, lp, ctx->zero_row);
     rc = ESS_OK;
   } else
     rc = launch_fmt<ESS_FMT_FP8>(grid, st, qq, slot_pool, list, n_list, T, c.attn_heads, c.topk, c.slots_per_seq,
