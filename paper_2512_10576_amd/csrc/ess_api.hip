@@ -381,6 +381,7 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     ptag = ctx->prof_tag + (size_t)pslot * ESS_PROF_MAIN;
     ctx->prof_nmark[pslot] = 0;
     ctx->prof_nfill[pslot] = 0;
+    ctx->prof_pair_stage[pslot] = 5;
   }
   // ESS_BEGIN(tag) / ESS_END(tag) bracket the launches of one stage; only selected stages are timed
   bool adjacent = false;                        // the last recorded mark sits right before this point
@@ -413,6 +414,7 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
   }
   const bool dba = offloaded && want_dba && !(c.flags & ESS_FLAG_SERIAL) && B >= 2;
   ctx->last_overlap = (c.flags & ESS_FLAG_SERIAL) ? 2 : (dba ? 1 : 0);
+  const bool da_swap = offloaded && !dba && !(c.flags & ESS_FLAG_SERIAL);
   const int nh = dba ? 2 : 1;
   const int hb0[2] = {0, B / 2};
   const int hB[2] = {dba ? B / 2 : B, B - B / 2};
@@ -456,10 +458,16 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     const ess_cache ch = shift_cache(c, *cache, b0);
     hipEvent_t* fev = (pev && h < ESS_PROF_FILL && ((ctx->prof_mask >> 5) & 1u)) ? pev + ESS_PROF_MAIN + 2 * h : nullptr;
     ESS_BEGIN(2);
-    rc = run_cache_step(ctx, ch, used, Bh, T, c.topk, a->step, ctx->slot_idx_ws + bt0 * k,
-                        a->miss_count ? a->miss_count + b0 : nullptr, st, &pending[h], b0, h, fev, dba ? 32 : 64);
-    if (rc != ESS_OK) return rc;
-    if (fev) ctx->prof_nfill[pslot] = h + 1;
+    if (da_swap) {      // bookkeeping only; the fetch follows on this stream further down
+      rc = ess_launch_bookkeeping(ctx, ch, used, Bh, T, c.topk, a->step, ctx->slot_idx_ws + bt0 * k,
+                                  a->miss_count ? a->miss_count + b0 : nullptr, st, b0, true);
+      if (rc != ESS_OK) return rc;
+    } else {
+      rc = run_cache_step(ctx, ch, used, Bh, T, c.topk, a->step, ctx->slot_idx_ws + bt0 * k,
+                          a->miss_count ? a->miss_count + b0 : nullptr, st, &pending[h], b0, h, fev, dba ? 32 : 64);
+      if (rc != ESS_OK) return rc;
+      if (fev) { ctx->prof_nfill[pslot] = h + 1; ctx->prof_pair_stage[pslot] = 5; }
+    }
     ESS_END(2);
   }
 
@@ -478,8 +486,40 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     return ESS_OK;
   }
 
-  // stage 4: Attn0 over resident entries while the fetches run, Attn1 over fetched ones, merge
   const uint16_t* q16 = static_cast<const uint16_t*>(a->q_bf16);
+  if (da_swap) {
+    // DA schedule.  The fetch is the critical path, so it stays on the caller's stream, right behind the
+    // bookkeeping and right before Attn1; Attn0, which has time to spare, goes to the side stream.  A
+    // wait on another stream's event costs several microseconds when the event fires late and almost
+    // nothing when it has fired long before: this way both waits of the step are of the second kind
+    // (the side stream's wait for the bookkeeping delays only Attn0).
+    ESS_HIP(hipEventRecord(ctx->ev_book[0], st));
+    ESS_HIP(hipStreamWaitEvent(ctx->side, ctx->ev_book[0], 0));
+    hipEvent_t* aev = (pev && ((ctx->prof_mask >> 3) & 1u)) ? pev + ESS_PROF_MAIN : nullptr;
+    if (aev) ESS_HIP(hipEventRecord(aev[0], ctx->side));
+    rc = ess_launch_attn_partial(ctx, q16, cache->slot_pool, ctx->hit_list, ctx->n_hit, B, T, 0, ns0, ctx->side, 0);
+    if (rc != ESS_OK) return rc;
+    if (aev) {
+      ESS_HIP(hipEventRecord(aev[1], ctx->side));
+      ctx->prof_nfill[pslot] = 1;
+      ctx->prof_pair_stage[pslot] = 3;
+    }
+    ESS_HIP(hipEventRecord(ctx->ev_fill[0], ctx->side));          // here: Attn0 done
+    ESS_BEGIN(5);
+    rc = ess_launch_fill(ctx, *cache, B, st, 0, 64);
+    if (rc != ESS_OK) return rc;
+    ESS_END(5);
+    ESS_BEGIN(4);
+    ESS_HIP(hipStreamWaitEvent(st, ctx->ev_fill[0], 0));
+    rc = ess_launch_attn_partial(ctx, q16, cache->slot_pool, ctx->miss_list, ctx->n_miss, B, T, ns0, ns1, st, 0);
+    if (rc != ESS_OK) return rc;
+    rc = ess_launch_attn_merge(ctx, B, T, ns0 + ns1, a->out_bf16, a->lse, st);
+    if (rc != ESS_OK) return rc;
+    ESS_END(4);
+    return ESS_OK;
+  }
+
+  // stage 4: Attn0 over resident entries while the fetches run, Attn1 over fetched ones, merge
   ESS_BEGIN(3);
   for (int h = 0; h < nh; ++h) {
     const int b0 = hb0[h], Bh = hB[h];
@@ -578,6 +618,7 @@ int ess_profile_enable(ess_ctx* ctx, int32_t max_steps) {
     delete[] ctx->prof_tag;
     delete[] ctx->prof_nmark;
     delete[] ctx->prof_nfill;
+    delete[] ctx->prof_pair_stage;
     ctx->prof_ev = nullptr;
   }
   ctx->prof_cap = ctx->prof_n = 0;
@@ -587,8 +628,10 @@ int ess_profile_enable(ess_ctx* ctx, int32_t max_steps) {
   ctx->prof_tag = new (std::nothrow) int8_t[(size_t)max_steps * ESS_PROF_MAIN];
   ctx->prof_nmark = new (std::nothrow) int[max_steps]();
   ctx->prof_nfill = new (std::nothrow) int[max_steps]();
-  if (!ctx->prof_ev || !ctx->prof_tag || !ctx->prof_nmark || !ctx->prof_nfill) {
+  ctx->prof_pair_stage = new (std::nothrow) int[max_steps]();
+  if (!ctx->prof_ev || !ctx->prof_tag || !ctx->prof_nmark || !ctx->prof_nfill || !ctx->prof_pair_stage) {
     delete[] ctx->prof_ev; delete[] ctx->prof_tag; delete[] ctx->prof_nmark; delete[] ctx->prof_nfill;
+    delete[] ctx->prof_pair_stage;
     ctx->prof_ev = nullptr;
     return ess_fail(ESS_ERR_NOMEM, "host allocation failed");
   }
@@ -597,6 +640,7 @@ int ess_profile_enable(ess_ctx* ctx, int32_t max_steps) {
     if (e != hipSuccess) {
       for (int j = 0; j < i; ++j) (void)hipEventDestroy(ctx->prof_ev[j]);
       delete[] ctx->prof_ev; delete[] ctx->prof_tag; delete[] ctx->prof_nmark; delete[] ctx->prof_nfill;
+      delete[] ctx->prof_pair_stage;
       ctx->prof_ev = nullptr;
       return ess_fail(ESS_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(e));
     }
@@ -618,13 +662,13 @@ int ess_profile_read(ess_ctx* ctx, float* host_ms, int32_t* n_steps) {
     for (int m = 1; m < nm; ++m) {
       float ms = 0.f;
       ESS_HIP(hipEventElapsedTime(&ms, ev[m - 1], ev[m]));
-      if (tag[m] >= 0 && tag[m] < 5) out[tag[m]] += ms;
+      if (tag[m] >= 0 && tag[m] < ESS_PROFILE_STAGES) out[tag[m]] += ms;
     }
     for (int f = 0; f < ctx->prof_nfill[s]; ++f) {
       float ms = 0.f;
       ESS_HIP(hipEventSynchronize(ev[ESS_PROF_MAIN + 2 * f + 1]));
       ESS_HIP(hipEventElapsedTime(&ms, ev[ESS_PROF_MAIN + 2 * f], ev[ESS_PROF_MAIN + 2 * f + 1]));
-      out[5] += ms;
+      out[ctx->prof_pair_stage[s]] += ms;
     }
   }
   ctx->prof_n = 0;

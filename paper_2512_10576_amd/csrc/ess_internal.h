@@ -45,7 +45,8 @@ struct ess_ctx {
   hipEvent_t* prof_ev;          // [prof_cap][ESS_PROF_EVENTS]: marks on the caller's stream, then pairs around each fetch
   int8_t* prof_tag;             // [prof_cap][ESS_PROF_MAIN] stage a mark closes (-1 = start)
   int* prof_nmark;              // [prof_cap] marks recorded
-  int* prof_nfill;              // [prof_cap] fetch pairs recorded
+  int* prof_nfill;              // [prof_cap] event pairs recorded off the caller's stream
+  int* prof_pair_stage;         // [prof_cap] stage those pairs time: 5 fetch, or 3 Attn0 when that runs on the side stream
   int prof_cap, prof_n;
   uint32_t prof_mask;           // stages that are timed (bit i = stage i of ess_profile_read)
   int prof_every, prof_calls;   // every prof_every-th ess_decode_step is timed
