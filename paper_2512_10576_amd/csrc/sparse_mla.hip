@@ -8,26 +8,16 @@
 //
 // Matrix-core mapping (v_mfma_f32_16x16x32_bf16, wave64).  A workgroup is four
 // waves, one per SIMD, each owning 16 heads with the whole 512-wide output row
-// in registers (128 accumulator VGPRs) and its queries stationary (72 VGPRs);
-// 64 heads per workgroup, head groups in grid.z.  The kernel is built for one
-// wave per SIMD and the large register budget that comes with it (a variant
-// with 32 heads per wave, which would halve LDS traffic per flop, is kept as a
-// template parameter but does not fit the register file without spilling).
-// Both products are computed transposed so that
-// nothing is re-laid out between them:
+// in 128 accumulator registers and its queries stationary (72 VGPRs); 64 heads
+// per workgroup, head groups in grid.z.  The kernel is built for one wave per
+// SIMD and the large register budget that comes with it.  Both products are
+// computed transposed so that nothing is re-laid out between them:
 //   S^T[r,h] = sum_d K[r,d] Q[h,d]      A = entry rows from LDS (row-major), B = Q^T (registers)
-//   O^T[v,h] = sum_r V^T[v,r] P^T[r,h]  A = V^T from LDS,                    B = P^T (registers)
+//   O^T[v,h] = sum_r V^T[v,r] P^T[r,h]  A = V^T, read transposed from the same rows, B = P^T (registers)
 // The accumulator of S^T gives lane (g,h) the eight logits of head h for tile rows
 // {4g..4g+3} and {16+4g..16+4g+3}; in exactly that order they are the eight
 // k-values the lane supplies for the B operand of the second product, so P^T
-// never leaves registers.  Softmax state is per lane = per head; the running
-// max needs two cross-lane steps per tile.
-// The second product needs V^T with the tile rows contiguous, so a tile is
-// stored twice in LDS while it is staged: row-major (pitch padded by 16 B)
-// and transposed (rows permuted to the order above, 16-byte granules
-// XOR-swizzled against bank conflicts).  Tiles are double-buffered in LDS and
-// the gathered row loads of tile i+1 are in flight, in registers, while tile
-// i is computed, so one workgroup per CU hides the gather latency by itself.
+// never leaves registers.  Softmax state is per lane = per head.
 #include "ess_internal.h"
 #include <utility>
 #include <hip/hip_bf16.h>
@@ -39,71 +29,15 @@ namespace {
 
 constexpr int TILE = ESS_ATTN_TILE;            // 32 entries
 constexpr int NTH = 256;                       // four waves
-constexpr int KPITCH = 1152 + 16;              // bytes; +16 spreads the 16 rows of an A fragment over the banks
 constexpr int KSTEPS = ESS_ROW_DIM / 32;       // 18
 constexpr int VBLOCKS = ESS_LATENT_DIM / 16;   // 32
-constexpr int KT_BYTES = TILE * KPITCH;        // 37376
-constexpr int VT_BYTES = ESS_LATENT_DIM * 64;  // 32768: V^T[v][32 positions] bf16
-constexpr int BUF_BYTES = KT_BYTES + VT_BYTES; // one staged tile
 constexpr int MAX_TPS = 32;                    // tiles per split (the launcher picks nsplit accordingly)
-constexpr int LDS_BYTES = 2 * BUF_BYTES + MAX_TPS * TILE * 4;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-constexpr int UPT = 512 / NTH;                 // latent units (4 rows x 16 bytes) per thread and tile
-constexpr int RPT = 256 / NTH;                 // rope pieces per thread and tile
-
-__device__ __forceinline__ int vt_granule(int v, int gran) { return gran ^ (((v >> 1) ^ (v >> 3)) & 3); }
-
-__device__ __forceinline__ float fp8_e4m3_to_f32(uint32_t byte) {
-  // OCP E4M3: 1-4-3, bias 7, subnormals at exponent 0 (the NaN pattern is not produced by a quantiser)
-  const uint32_t s = (byte & 0x80u) << 24;
-  const uint32_t e = (byte >> 3) & 0xFu;
-  const uint32_t m = byte & 0x7u;
-  float mag;
-  if (e == 0) mag = (float)m * 0.001953125f;                     // m/8 * 2^-6
-  else mag = __uint_as_float(((e + 120u) << 23) | (m << 20));   // (1 + m/8) * 2^(e-7)
-  return __uint_as_float(__float_as_uint(mag) | s);
-}
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   const __hip_bfloat16 x = __float2bfloat16(a), y = __float2bfloat16(b);
   return (uint32_t)(*reinterpret_cast<const uint16_t*>(&x)) | ((uint32_t)(*reinterpret_cast<const uint16_t*>(&y)) << 16);
-}
-
-// One piece = the 8 values of dims [8*cc, 8*cc+8) of an entry as it sits in memory (what a
-// prefetch keeps in registers), and its conversion to 8 bf16.
-template <int FMT> struct RawPiece;
-template <> struct RawPiece<ESS_FMT_BF16> { uint4 d; };
-template <> struct RawPiece<ESS_FMT_FP8> { uint2 d; uint32_t scale; };
-
-template <int FMT>
-__device__ __forceinline__ RawPiece<FMT> load_raw(const uint8_t* row, int cc) {
-  RawPiece<FMT> r;
-  if constexpr (FMT == ESS_FMT_BF16) {
-    r.d = *reinterpret_cast<const uint4*>(row + cc * 16);
-  } else {
-    r.d = *reinterpret_cast<const uint2*>(row + cc * 8);
-    r.scale = *reinterpret_cast<const uint16_t*>(row + 512 + (cc >> 4) * 2);
-  }
-  return r;
-}
-
-template <int FMT>
-__device__ __forceinline__ uint4 to_bf16x8(const RawPiece<FMT>& r, bool keep) {
-  uint4 out;
-  if constexpr (FMT == ESS_FMT_BF16) {
-    out = r.d;
-  } else {
-    const float sc = __uint_as_float(r.scale << 16);
-    float f[8];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      f[i] = fp8_e4m3_to_f32((r.d.x >> (8 * i)) & 0xFFu) * sc;
-      f[4 + i] = fp8_e4m3_to_f32((r.d.y >> (8 * i)) & 0xFFu) * sc;
-    }
-    out = make_uint4(pack_bf16(f[0], f[1]), pack_bf16(f[2], f[3]), pack_bf16(f[4], f[5]), pack_bf16(f[6], f[7]));
-  }
-  return keep ? out : make_uint4(0, 0, 0, 0);
 }
 
 // rope piece (dims 512 + 8*rc ..): bf16 in both formats
@@ -112,235 +46,8 @@ __device__ __forceinline__ uint4 load_rope(const uint8_t* row, int rc) {
   return *reinterpret_cast<const uint4*>(row + (FMT == ESS_FMT_BF16 ? 1024 : 520) + rc * 16);
 }
 
-template <int FMT>
-struct Staged {                                // one tile's share of a thread, as loaded
-  RawPiece<FMT> lat[UPT][4];
-  uint4 rope[RPT];
-};
-
-// Issue every global load of this thread for a tile.  Masked rows read slot 0 (always valid
-// memory); they are zeroed when stored.
-template <int FMT>
-__device__ __forceinline__ void stage_load(Staged<FMT>& st, const int32_t* tile_slot, const uint8_t* pbase,
-                                           int row_stride, int tid) {
-#pragma unroll
-  for (int i = 0; i < RPT; ++i) {
-    const int u = tid + i * NTH;
-    st.rope[i] = load_rope<FMT>(pbase + (size_t)max(tile_slot[u >> 3], 0) * row_stride, u & 7);
-  }
-#pragma unroll
-  for (int i = 0; i < UPT; ++i) {
-    const int u = tid + i * NTH;
-    const int rg = u >> 6, cc = u & 63;        // row group (4 rows), 16-byte column piece
-#pragma unroll
-    for (int r = 0; r < 4; ++r)
-      st.lat[i][r] = load_raw<FMT>(pbase + (size_t)max(tile_slot[rg * 4 + r], 0) * row_stride, cc);
-  }
-}
-
-// Write a loaded tile into an LDS buffer: row-major copy (Kt) and transposed copy (Vt).
-template <int FMT>
-__device__ __forceinline__ void stage_store(const Staged<FMT>& st, const int32_t* tile_slot, uint8_t* Kt, uint8_t* Vt,
-                                            int tid) {
-#pragma unroll
-  for (int i = 0; i < UPT; ++i) {
-    const int u = tid + i * NTH;
-    const int rg = u >> 6, cc = u & 63;
-    uint4 x[4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      x[r] = to_bf16x8<FMT>(st.lat[i][r], tile_slot[rg * 4 + r] >= 0);
-      *reinterpret_cast<uint4*>(Kt + (rg * 4 + r) * KPITCH + cc * 16) = x[r];
-    }
-    // rows 4g'..4g'+3 sit at positions 8g'..8g'+3 of V^T, rows 16+4g'.. at 8g'+4..8g'+7
-    const int gq = rg & 3, half = rg >> 2;
-    const uint32_t* x0 = reinterpret_cast<const uint32_t*>(&x[0]);
-    const uint32_t* x1 = reinterpret_cast<const uint32_t*>(&x[1]);
-    const uint32_t* x2 = reinterpret_cast<const uint32_t*>(&x[2]);
-    const uint32_t* x3 = reinterpret_cast<const uint32_t*>(&x[3]);
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const uint32_t a0 = x0[p], a1 = x1[p], a2 = x2[p], a3 = x3[p];
-      const uint2 even = make_uint2((a0 & 0xffffu) | (a1 << 16), (a2 & 0xffffu) | (a3 << 16));
-      const uint2 odd = make_uint2((a0 >> 16) | (a1 & 0xffff0000u), (a2 >> 16) | (a3 & 0xffff0000u));
-      const int v0 = cc * 8 + 2 * p, v1 = v0 + 1;
-      *reinterpret_cast<uint2*>(Vt + v0 * 64 + vt_granule(v0, gq) * 16 + half * 8) = even;
-      *reinterpret_cast<uint2*>(Vt + v1 * 64 + vt_granule(v1, gq) * 16 + half * 8) = odd;
-    }
-  }
-#pragma unroll
-  for (int i = 0; i < RPT; ++i) {
-    const int u = tid + i * NTH;
-    const uint4 x = tile_slot[u >> 3] >= 0 ? st.rope[i] : make_uint4(0, 0, 0, 0);
-    *reinterpret_cast<uint4*>(Kt + (u >> 3) * KPITCH + (64 + (u & 7)) * 16) = x;
-  }
-}
-
-// HB = 16-head blocks per wave (1: 64 heads per workgroup, 2: 128)
-template <int FMT, int HB>
-__global__ __launch_bounds__(NTH, 1) void k_attn_partial(
-    const uint16_t* __restrict__ q, const uint8_t* __restrict__ pool, const int32_t* __restrict__ list,
-    const int32_t* __restrict__ n_list, int T, int H, int kk, int S, int row_stride, float scale_log2e, int split0,
-    int nsplit, float* __restrict__ o_part, float* __restrict__ lse_part) {
-  extern __shared__ __align__(16) uint8_t lds[];
-  int32_t* slot_cache = reinterpret_cast<int32_t*>(lds + 2 * BUF_BYTES);       // [MAX_TPS][32]
-
-  const int split = blockIdx.x;
-  const int bt = blockIdx.y;
-  const int b = bt / T;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int g = lane >> 4, n16 = lane & 15;
-  constexpr int HPW = 16 * HB;                 // heads per wave
-  const int head0 = (blockIdx.z * 4 + wave) * HPW;
-  const bool wave_active = head0 < H;          // idle waves still help staging
-
-  const int n = n_list ? min(n_list[bt], kk) : kk;
-  const int tiles_total = (n + TILE - 1) / TILE;
-  const int tps = min((tiles_total + nsplit - 1) / nsplit, MAX_TPS);
-  const int tile_begin = split * tps;
-  const int tile_end = min(tile_begin + tps, tiles_total);
-  const int my_tiles = max(tile_end - tile_begin, 0);
-
-  // Q^T fragments: lane (g,h) holds Q[h][32*ks + 8g .. +8) for its two head blocks
-  bf16x8 qb[HB][KSTEPS];
-#pragma unroll
-  for (int hb = 0; hb < HB; ++hb) {
-    const int head = head0 + hb * 16 + n16;
-    const uint16_t* qrow = q + ((size_t)bt * H + min(head, H - 1)) * ESS_ROW_DIM;
-#pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) {
-      uint4 x = *reinterpret_cast<const uint4*>(qrow + ks * 32 + g * 8);
-      if (head >= H) x = make_uint4(0, 0, 0, 0);
-      qb[hb][ks] = *reinterpret_cast<bf16x8*>(&x);
-    }
-  }
-
-  floatx4 acc[HB][VBLOCKS];
-#pragma unroll
-  for (int hb = 0; hb < HB; ++hb)
-#pragma unroll
-    for (int vb = 0; vb < VBLOCKS; ++vb) acc[hb][vb] = floatx4{0.f, 0.f, 0.f, 0.f};
-  float m_run[HB], l_run[HB];                  // running max of the scaled logits (log2 domain); this lane's share of the running sum
-#pragma unroll
-  for (int hb = 0; hb < HB; ++hb) { m_run[hb] = -__builtin_inff(); l_run[hb] = 0.f; }
-
-  const int32_t* lrow = list + (size_t)bt * kk;
-  const uint8_t* pbase = pool + (size_t)b * S * row_stride;
-
-  // slots of every tile of this split
-  for (int j = tid; j < my_tiles * TILE; j += NTH) {
-    const int e = tile_begin * TILE + j;
-    int sl = e < n ? lrow[e] : -1;
-    if (sl >= S) sl = -1;
-    slot_cache[j] = sl;
-  }
-  __syncthreads();
-
-  Staged<FMT> st;
-  if (my_tiles > 0) {
-    stage_load<FMT>(st, slot_cache, pbase, row_stride, tid);
-    stage_store<FMT>(st, slot_cache, lds, lds + KT_BYTES, tid);
-  }
-  __syncthreads();
-
-  for (int it = 0; it < my_tiles; ++it) {
-    const uint8_t* Kt = lds + (it & 1) * BUF_BYTES;
-    const uint8_t* Vt = Kt + KT_BYTES;
-    const int32_t* tile_slot = slot_cache + it * TILE;
-    const bool more = it + 1 < my_tiles;
-    if (more) stage_load<FMT>(st, tile_slot + TILE, pbase, row_stride, tid);   // in flight during the compute
-
-    if (wave_active) {
-      // ---- S^T = K Q^T for the 32 rows of the tile, both head blocks
-      floatx4 s[HB][2];
-#pragma unroll
-      for (int hb = 0; hb < HB; ++hb) s[hb][0] = s[hb][1] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int ks = 0; ks < KSTEPS; ++ks) {
-        const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(Kt + n16 * KPITCH + ks * 64 + g * 16);
-        const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(Kt + (16 + n16) * KPITCH + ks * 64 + g * 16);
-#pragma unroll
-        for (int hb = 0; hb < HB; ++hb) {
-          s[hb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, qb[hb][ks], s[hb][0], 0, 0, 0);
-          s[hb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, qb[hb][ks], s[hb][1], 0, 0, 0);
-        }
-      }
-      // lane (g,h): s[hb][0][i] = logit of row 4g+i, s[hb][1][i] = logit of row 16+4g+i
-      const int4 v0 = *reinterpret_cast<const int4*>(tile_slot + g * 4);
-      const int4 v1 = *reinterpret_cast<const int4*>(tile_slot + 16 + g * 4);
-      const bool ok[8] = {v0.x >= 0, v0.y >= 0, v0.z >= 0, v0.w >= 0, v1.x >= 0, v1.y >= 0, v1.z >= 0, v1.w >= 0};
-      bf16x8 pb[HB];
-#pragma unroll
-      for (int hb = 0; hb < HB; ++hb) {
-        float z[8];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          z[i] = ok[i] ? s[hb][0][i] * scale_log2e : -__builtin_inff();
-          z[4 + i] = ok[4 + i] ? s[hb][1][i] * scale_log2e : -__builtin_inff();
-        }
-        float tmax = fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])), fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7])));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-        const float m_new = fmaxf(m_run[hb], tmax);
-        const float m_safe = (m_new == -__builtin_inff()) ? 0.f : m_new;
-        const float alpha = exp2f(m_run[hb] - m_safe);          // 0 while nothing has been seen
-        float p[8], psum = 0.f;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          p[j] = exp2f(z[j] - m_safe);
-          psum += p[j];
-        }
-        l_run[hb] = l_run[hb] * alpha + psum;
-        m_run[hb] = m_new;
-        if (__any(alpha != 1.0f)) {
-#pragma unroll
-          for (int vb = 0; vb < VBLOCKS; ++vb) {
-            acc[hb][vb][0] *= alpha; acc[hb][vb][1] *= alpha; acc[hb][vb][2] *= alpha; acc[hb][vb][3] *= alpha;
-          }
-        }
-        uint4 pw = make_uint4(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7]));
-        pb[hb] = *reinterpret_cast<bf16x8*>(&pw);
-      }
-      // ---- O^T += V^T P^T
-#pragma unroll
-      for (int vb = 0; vb < VBLOCKS; ++vb) {
-        const int v = vb * 16 + n16;
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(Vt + v * 64 + vt_granule(v, g) * 16);
-#pragma unroll
-        for (int hb = 0; hb < HB; ++hb) acc[hb][vb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[hb], acc[hb][vb], 0, 0, 0);
-      }
-    }
-
-    if (more) {                                  // the other buffer was last read one iteration ago
-      uint8_t* Kn = lds + ((it + 1) & 1) * BUF_BYTES;
-      stage_store<FMT>(st, tile_slot + TILE, Kn, Kn + KT_BYTES, tid);
-    }
-    __syncthreads();
-  }
-
-  // ---- finish: total sum over the four lane groups, normalise, write the partial result
-#pragma unroll
-  for (int hb = 0; hb < HB; ++hb) {
-    const int head = head0 + hb * 16 + n16;
-    float l_tot = l_run[hb];
-    l_tot += __shfl_xor(l_tot, 16, 64);
-    l_tot += __shfl_xor(l_tot, 32, 64);
-    const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-    if (head < H) {
-      const size_t prow = ((size_t)bt * ESS_MAX_SPLITS + split0 + split) * H + head;
-      float* op = o_part + prow * ESS_LATENT_DIM;
-#pragma unroll
-      for (int vb = 0; vb < VBLOCKS; ++vb) {
-        const float4 o = make_float4(acc[hb][vb][0] * inv, acc[hb][vb][1] * inv, acc[hb][vb][2] * inv, acc[hb][vb][3] * inv);
-        *reinterpret_cast<float4*>(op + vb * 16 + g * 4) = o;
-      }
-      if (g == 0) lse_part[prow] = l_tot > 0.f ? (m_run[hb] + log2f(l_tot)) * kLn2 : -__builtin_inff();
-    }
-  }
-}
-
 // ---------------------------------------------------------------------------------------------
-// bf16 entries: the same computation with the rows brought into LDS by the memory system itself
+// bf16 entries are brought into LDS by the memory system itself
 // (global_load_lds_dwordx4: a wave instruction moves 64 x 16 bytes from per-lane global addresses to
 // consecutive LDS addresses, no registers involved).  One wave instruction per 1024-byte latent
 // part of a row, one per eight 128-byte rope parts.  The loads are issued through inline assembly
@@ -364,8 +71,10 @@ __device__ __forceinline__ void wait_vmcnt() {     // vmcnt <= N, other counters
   __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
 }
 
-// ---------------------------------------------------------------- bf16 entries
-// Four waves x 16 heads, tiles of 32 entries gathered into LDS by global_load_lds.  What the kernel is
+// ---------------------------------------------------------------- the partial-attention kernel
+// Four waves x 16 heads, tiles of 32 entries in LDS as bf16 rows: bf16 entries gathered by
+// global_load_lds, quantised entries (512 fp8 + 4 scales + rope) loaded into registers a tile ahead,
+// dequantised and written in the same layout.  What the kernel is
 // built around (a first version that built V^T in LDS, rescaled every tile and left the accumulators
 // to the register allocator spent 1100 instructions per tile and wave, 68 of them MFMAs):
 //  * V^T is never built.  The A operand of O^T += V^T P^T wants, per lane, 8 entries of one value
@@ -391,8 +100,8 @@ __device__ __forceinline__ void wait_vmcnt() {     // vmcnt <= N, other counters
 constexpr int TRP = 1024;                        // latent row pitch in LDS
 constexpr int TR_KL_BYTES = TILE * TRP;          // 32768
 constexpr int TR_RAW_BYTES = TR_KL_BYTES + RP_BYTES;
-constexpr int TR_NBUF = 4;
-constexpr int TR_LDS_BYTES = TR_NBUF * TR_RAW_BYTES + MAX_TPS * TILE * 4;   // 151552
+constexpr int tr_nbuf(int fmt) { return fmt == ESS_FMT_BF16 ? 4 : 2; }
+constexpr int tr_lds_bytes(int fmt) { return tr_nbuf(fmt) * TR_RAW_BYTES + MAX_TPS * TILE * 4; }   // 151552 | 77824
 constexpr float kLazyMax = 8.0f;
 
 #ifdef ESS_ATTN_PHASE_TIMING
@@ -480,12 +189,15 @@ __device__ __forceinline__ float group_sum(float x) {
   return __uint_as_float(b.x) + __uint_as_float(b.y);
 }
 
+template <int FMT>
 __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
     const uint16_t* __restrict__ q, const uint8_t* __restrict__ pool, const int32_t* __restrict__ list,
     const int32_t* __restrict__ n_list, int T, int H, int kk, int S, int row_stride, float scale_log2e, int split0,
     int nsplit, float* __restrict__ o_part, float* __restrict__ lse_part, const uint8_t* __restrict__ zero_row) {
   extern __shared__ __align__(16) uint8_t lds[];
-  int32_t* slot_cache = reinterpret_cast<int32_t*>(lds + TR_NBUF * TR_RAW_BYTES);   // [MAX_TPS][32]
+  constexpr bool kDma = FMT == ESS_FMT_BF16;       // rows go to LDS as they are; else through registers, dequantised
+  constexpr int NBUF = tr_nbuf(FMT);
+  int32_t* slot_cache = reinterpret_cast<int32_t*>(lds + NBUF * TR_RAW_BYTES);   // [MAX_TPS][32]
   const uint32_t lds0 = lds_addr_of(lds);
 
   const int split = blockIdx.x;
@@ -544,7 +256,7 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
     for (int r8 = 0; r8 < DMA_PER_TILE; ++r8) src[r8] = sl[r8] >= 0 ? pbase + (size_t)sl[r8] * row_stride : zero_row;
   };
   auto gather_step = [&](int it, int step, const uint8_t* const (&src)[DMA_PER_TILE]) {
-    const uint32_t raw = lds0 + (uint32_t)((it % TR_NBUF) * TR_RAW_BYTES);
+    const uint32_t raw = lds0 + (uint32_t)((it % NBUF) * TR_RAW_BYTES);
     if (step < 8) {
       const int row = wave * 8 + step;
       dma16(src[step] + ((lane ^ tr_swz(row)) << 4), raw + (uint32_t)(row * TRP));
@@ -552,11 +264,54 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
       dma16(src[8] + rope_off, raw + (uint32_t)(TR_KL_BYTES + wave * 1024));
     }
   };
-  for (int it = 0; it < min(my_tiles, TR_NBUF - 1); ++it) {
-    const uint8_t* src[DMA_PER_TILE];
-    gather_sources(it, src);
+  // Quantised entries: a tile's share of a thread -- row tid/8: four 16-byte pieces of fp8 values (piece
+  // c + 8j, c = tid%8, belongs to scale group j), the row's four bf16 scales, one 16-byte rope piece --
+  // is loaded into registers two tiles ahead and written to LDS one tile ahead, as bf16 in the layout
+  // that the gathers of bf16 entries produce (two buffers).
+  struct StagedF8 { uint4 lat[4]; uint2 sc; uint4 rope; };
+  auto f8_load = [&](int it, StagedF8& st) {
+    const int row = tid >> 3, c = tid & 7;
+    const int sl = slot_cache[it * TILE + row];
+    const uint8_t* src = sl >= 0 ? pbase + (size_t)sl * row_stride : zero_row;
 #pragma unroll
-    for (int step = 0; step < DMA_PER_TILE; ++step) gather_step(it, step, src);
+    for (int jj = 0; jj < 4; ++jj) st.lat[jj] = *reinterpret_cast<const uint4*>(src + (c + 8 * jj) * 16);
+    st.sc = *reinterpret_cast<const uint2*>(src + 512);
+    st.rope = load_rope<ESS_FMT_FP8>(src, c);
+  };
+  auto f8_store = [&](int it, const StagedF8& st) {
+    uint8_t* KL = lds + (it % NBUF) * TR_RAW_BYTES;
+    const int row = tid >> 3, c = tid & 7;
+    const int f = tr_swz(row);
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      const uint32_t sbits = (jj < 2 ? st.sc.x : st.sc.y) >> (16 * (jj & 1));
+      const float sc = __uint_as_float(sbits << 16);
+      const uint32_t w[4] = {st.lat[jj].x, st.lat[jj].y, st.lat[jj].z, st.lat[jj].w};
+      uint32_t o[8];
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        const auto lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[d], false);
+        const auto hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[d], true);
+        o[2 * d] = pack_bf16(lo[0] * sc, lo[1] * sc);
+        o[2 * d + 1] = pack_bf16(hi[0] * sc, hi[1] * sc);
+      }
+      const int G = 2 * (c + 8 * jj);
+      *reinterpret_cast<uint4*>(KL + row * TRP + ((G ^ f) << 4)) = make_uint4(o[0], o[1], o[2], o[3]);
+      *reinterpret_cast<uint4*>(KL + row * TRP + (((G + 1) ^ f) << 4)) = make_uint4(o[4], o[5], o[6], o[7]);
+    }
+    *reinterpret_cast<uint4*>(KL + TR_KL_BYTES + row * 128 + ((c ^ (row & 7)) * 16)) = st.rope;
+  };
+  StagedF8 stg;
+  if constexpr (kDma) {
+    for (int it = 0; it < min(my_tiles, NBUF - 1); ++it) {
+      const uint8_t* src[DMA_PER_TILE];
+      gather_sources(it, src);
+#pragma unroll
+      for (int step = 0; step < DMA_PER_TILE; ++step) gather_step(it, step, src);
+    }
+  } else {
+    if (my_tiles > 0) { f8_load(0, stg); f8_store(0, stg); }
+    if (my_tiles > 1) f8_load(1, stg);
   }
 
   // lane constants of the two LDS access patterns
@@ -575,23 +330,29 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
   long long ph_t = clock64();
 #endif
   for (int it = 0; it < my_tiles; ++it) {
-    const uint32_t KLa = lds0 + (uint32_t)((it % TR_NBUF) * TR_RAW_BYTES);
-    const uint8_t* KL = lds + (it % TR_NBUF) * TR_RAW_BYTES;
+    const uint32_t KLa = lds0 + (uint32_t)((it % NBUF) * TR_RAW_BYTES);
+    const uint8_t* KL = lds + (it % NBUF) * TR_RAW_BYTES;
     const uint8_t* RP = KL + TR_KL_BYTES;
     const int32_t* tile_slot = slot_cache + it * TILE;
-    // this wave's gathers of tile `it` have landed when at most those of the later tiles are outstanding
-    const int later = min(my_tiles - 1 - it, TR_NBUF - 2);
-    if (later >= 2) wait_vmcnt<2 * DMA_PER_TILE>(); else if (later == 1) wait_vmcnt<DMA_PER_TILE>(); else wait_vmcnt<0>();
-    ESS_PH(4);
-    __syncthreads();                           // ... everyone's did; and everyone is done with tile it-1
-    ESS_PH(5);
-    const bool more = it + TR_NBUF - 1 < my_tiles;   // tile it+3 goes into the buffer tile it-1 used
+    const bool more = kDma && it + NBUF - 1 < my_tiles;   // tile it+3 goes into the buffer tile it-1 used
     const uint8_t* src[DMA_PER_TILE];
-    if (more) gather_sources(it + TR_NBUF - 1, src);
+    if constexpr (kDma) {
+      // this wave's gathers of tile `it` have landed when at most those of the later tiles are outstanding
+      const int later = min(my_tiles - 1 - it, NBUF - 2);
+      if (later >= 2) wait_vmcnt<2 * DMA_PER_TILE>(); else if (later == 1) wait_vmcnt<DMA_PER_TILE>(); else wait_vmcnt<0>();
+      ESS_PH(4);
+      __syncthreads();                         // ... everyone's did; and everyone is done with tile it-1
+      ESS_PH(5);
+      if (more) gather_sources(it + NBUF - 1, src);
+    } else {
+      __syncthreads();                         // tile `it` is in LDS (written a tile ago); everyone is done with tile it-1
+      if (it + 1 < my_tiles) f8_store(it + 1, stg);   // into the buffer tile it-1 used
+      if (it + 2 < my_tiles) f8_load(it + 2, stg);
+    }
     if (!wave_active) {
       if (more) {
 #pragma unroll
-        for (int step = 0; step < DMA_PER_TILE; ++step) gather_step(it + TR_NBUF - 1, step, src);
+        for (int step = 0; step < DMA_PER_TILE; ++step) gather_step(it + NBUF - 1, step, src);
       }
       continue;
     }
@@ -600,7 +361,7 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
     // ---- S^T = K Q^T; A fragments read six k-steps ahead of the MFMAs that use them; three gather
     // instructions of tile it+3 after each chunk of fragment reads
     floatx4 s0 = floatx4{0.f, 0.f, 0.f, 0.f}, s1 = s0;
-    constexpr int CH = 6;
+    constexpr int CH = kDma ? 6 : 3;           // quantised entries: the staged tile needs the registers
     bf16x8 fa[2][CH], fb[2][CH];
     auto load_chunk = [&](int c, bf16x8 (&da)[CH], bf16x8 (&db)[CH]) {
 #pragma unroll
@@ -622,7 +383,7 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
       if (c + 1 < KSTEPS / CH) load_chunk(c + 1, fa[(c + 1) & 1], fb[(c + 1) & 1]);
       if (more) {
 #pragma unroll
-        for (int step = 3 * c; step < 3 * c + 3; ++step) gather_step(it + TR_NBUF - 1, step, src);
+        for (int step = 9 * c / (KSTEPS / CH); step < 9 * (c + 1) / (KSTEPS / CH); ++step) gather_step(it + NBUF - 1, step, src);
       }
 #pragma unroll
       for (int j = 0; j < CH; ++j) {
@@ -740,17 +501,6 @@ __global__ __launch_bounds__(256) void k_attn_merge(const float* __restrict__ o_
   if (lse_out && lane == 0) lse_out[rowi] = den > 0.f ? mx + __logf(den) : -__builtin_inff();
 }
 
-template <int FMT>
-int launch_fmt(dim3 grid, hipStream_t st, const uint16_t* q, const uint8_t* pool, const int32_t* list,
-               const int32_t* n_list, int T, int H, int kk, int S, int row_stride, float sc, int split0, int nsplit,
-               float* o_part, float* lse_part) {
-  ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_partial<FMT, 1>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES));
-  hipLaunchKernelGGL((k_attn_partial<FMT, 1>), grid, dim3(NTH), LDS_BYTES, st, q, pool, list, n_list, T, H, kk, S,
-                     row_stride, sc, split0, nsplit, o_part, lse_part);
-  return ESS_OK;
-}
-
 }  // namespace
 
 int ess_attn_min_splits(const ess_config& c) {
@@ -770,14 +520,19 @@ int ess_launch_attn_partial(ess_ctx* ctx, const void* q, const uint8_t* slot_poo
   float* lp = ctx->lse_part + (size_t)b0 * T * ESS_MAX_SPLITS * c.attn_heads;
   int rc;
   if (c.latent_fmt == ESS_FMT_BF16) {
-    ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_partial_tr),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, TR_LDS_BYTES));
-    hipLaunchKernelGGL(k_attn_partial_tr, grid, dim3(NTH), TR_LDS_BYTES, st, qq, slot_pool, list, n_list, T,
+    constexpr int lds = tr_lds_bytes(ESS_FMT_BF16);
+    ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_partial_tr<ESS_FMT_BF16>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    hipLaunchKernelGGL(k_attn_partial_tr<ESS_FMT_BF16>, grid, dim3(NTH), lds, st, qq, slot_pool, list, n_list, T,
                        c.attn_heads, c.topk, c.slots_per_seq, c.row_stride, sc, split0, nsplit, op, lp, ctx->zero_row);
-    rc = ESS_OK;
-  } else
-    rc = launch_fmt<ESS_FMT_FP8>(grid, st, qq, slot_pool, list, n_list, T, c.attn_heads, c.topk, c.slots_per_seq,
-                                 c.row_stride, sc, split0, nsplit, op, lp);
+  } else {
+    constexpr int lds = tr_lds_bytes(ESS_FMT_FP8);
+    ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_partial_tr<ESS_FMT_FP8>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    hipLaunchKernelGGL(k_attn_partial_tr<ESS_FMT_FP8>, grid, dim3(NTH), lds, st, qq, slot_pool, list, n_list, T,
+                       c.attn_heads, c.topk, c.slots_per_seq, c.row_stride, sc, split0, nsplit, op, lp, ctx->zero_row);
+  }
+  rc = ESS_OK;
   if (rc != ESS_OK) return rc;
   ESS_HIP(hipGetLastError());
   return ESS_OK;
