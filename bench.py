@@ -47,7 +47,7 @@ WORKLOADS = {
 }
 # HBM bytes per launch of the index-score kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (see profiles/); None until measured for that workload
-MEASURED_TRAFFIC_BYTES = {"cfg4": 958772 * 1024}   # profiles/pmc_traffic_cfg4.md
+MEASURED_TRAFFIC_BYTES = {"cfg4": 958756 * 1024}   # HBM bytes of the index-score kernel per step, profiles/pmc_traffic_cfg4.md
 
 
 def build_workload(name, steps_needed, overlap="auto", layers=None, rho=None, ratio=None):
@@ -195,6 +195,22 @@ def measure(name, steps, warmup, overlap="auto", layers=None, rho=None, ratio=No
     else:
         prof = [[index_ms, 0, 0, 0, 0, 0]]
     ctx.profile_enable(0)
+    # the index-score kernel by itself on the same inputs (whole batch, nothing running beside it)
+    wl = W["wl"]
+    score = torch.empty((wl["B"], wl["T"], wl["L"]), dtype=torch.float32, device="cuda")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n_alone = 16
+    for i in range(3 + n_alone):
+        if i == 3:
+            e0.record()
+        if W.get("paged"):
+            ctx.index_score_paged(W["q_idx"], W["w"], W["key"], W["block_table"], W["ctx_len"], score)
+        else:
+            ctx.index_score(W["q_idx"], W["w"], W["key"], W["ctx_len"], score)
+    e1.record()
+    torch.cuda.synchronize()
+    index_alone_ms = e0.elapsed_time(e1) / n_alone
+    del score
     stage = [sum(p[i] for p in prof) / len(prof) for i in range(6)]
     misses_per_step = stats["misses"] / max(steps * nl, 1)     # per layer-step
     ab = algorithmic_bytes(W, misses_per_step)
@@ -207,6 +223,8 @@ def measure(name, steps, warmup, overlap="auto", layers=None, rho=None, ratio=No
         stage_ms=dict(index_score=stage[0], topk=stage[1], bookkeeping=stage[2], attn0=stage[3], attn1_merge=stage[4],
                       fetch=stage[5]),
         index_score_GBs=ab["index_score"] / (index_ms * 1e-3) / 1e9, index_ms_timed=index_ms,
+        index_alone_ms=index_alone_ms, index_alone_GBs=ab["index_score"] / (index_alone_ms * 1e-3) / 1e9,
+        index_launches_per_step=2 if ctx.last_overlap() == 1 else 1,
         hbm_stream_GBs=hbm_stream_bytes / (hbm_stream_ms * 1e-3) / 1e9,
         hbm_stream_frac_of_peak=hbm_stream_bytes / (hbm_stream_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         whole_step_hbm_frac=(hbm_stream_bytes / (ms_step * 1e-3) / 1e9) / HBM_PEAK_GBS,
@@ -392,7 +410,7 @@ def main():
     ap.add_argument("--layers", type=int, default=None, help="layers run back to back per step (default: the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-32k", action="store_true", help="skip the extra 32K-context measurement (cfg2)")
-    ap.add_argument("--cpu-seqs", type=int, default=16)
+    ap.add_argument("--cpu-seqs", type=int, default=64, help="sequences of the batch the CPU oracle is timed on")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic) so that rocprofv3 --pmc counters can be scaled")
     ap.add_argument("--append", action="store_true",
@@ -432,9 +450,17 @@ def main():
 
     W, res = measure(a.workload, a.steps, a.warmup, a.overlap, a.layers, append=a.append, paged=a.paged)
     ab = res["algorithmic_bytes"]
+    # In the timed region a DBA step launches the kernel twice, once per half of the batch, the second
+    # beside the first half's fetch; achieved = bytes of a step / time of its launches, which is also
+    # bytes per launch / average launch time.  `alone` is the same kernel on the whole batch with the GPU to itself.
+    nlaunch = res["index_launches_per_step"]
     roof = dict(bound="hbm", kernel="k_index_score", achieved=res["index_score_GBs"], peak=HBM_PEAK_GBS, unit="GB/s",
-                frac=res["index_score_GBs"] / HBM_PEAK_GBS, traffic=MEASURED_TRAFFIC_BYTES.get(a.workload),
-                algorithmic_bytes_per_launch=ab["index_score"], avg_launch_ms=res["index_ms_timed"])
+                frac=res["index_score_GBs"] / HBM_PEAK_GBS,
+                traffic=(MEASURED_TRAFFIC_BYTES[a.workload] / nlaunch) if a.workload in MEASURED_TRAFFIC_BYTES else None,
+                algorithmic_bytes_per_launch=ab["index_score"] / nlaunch, avg_launch_ms=res["index_ms_timed"] / nlaunch,
+                launches_per_step=nlaunch,
+                alone=dict(achieved=res["index_alone_GBs"], frac=res["index_alone_GBs"] / HBM_PEAK_GBS,
+                           algorithmic_bytes_per_launch=ab["index_score"], avg_launch_ms=res["index_alone_ms"]))
     out = {
         "metric": "decode-step sparse-attn layer-steps/sec", "value": res["layer_steps_per_s"], "unit": "layer-steps/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": res["ms_per_step"], "ms_per_layer_step": res["ms_per_layer_step"],

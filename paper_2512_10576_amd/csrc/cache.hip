@@ -302,7 +302,8 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
 // kernels' HBM traffic: beside a 64-workgroup fetch every kernel measured (index score, top-k,
 // attention) takes about 2.2x its time alone, beside a 32-workgroup fetch about 1.3x.  With one fetch
 // per step only Attn0 runs beside it and has time to spare, so the fetch gets 64 workgroups; the
-// split-batch schedule puts critical-path kernels beside the fetch and asks for 32.
+// split-batch schedule puts critical-path kernels beside the fetch and asks for 28 (best of a sweep
+// from 12 to 64 at batch 64, 128K context).
 constexpr int FILL_WPB = 8;                                 // waves per workgroup
 constexpr int FILL_MAX_B = 4096;
 

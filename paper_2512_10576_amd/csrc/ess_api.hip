@@ -236,7 +236,7 @@ int ess_create(const ess_config* cfg, ess_ctx** out) {
   memset(ctx->host_miss, 0, (size_t)cfg->max_batch * sizeof(int32_t));
   if ((e = hipHostGetDevicePointer(reinterpret_cast<void**>(&ctx->host_miss_dev), ctx->host_miss, 0)) != hipSuccess)
     return bail("hipHostGetDevicePointer", e);
-  ctx->auto_threshold = 400;
+  ctx->auto_threshold = 250;
   *out = ctx;
   return ESS_OK;
 }
@@ -464,7 +464,7 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
       if (rc != ESS_OK) return rc;
     } else {
       rc = run_cache_step(ctx, ch, used, Bh, T, c.topk, a->step, ctx->slot_idx_ws + bt0 * k,
-                          a->miss_count ? a->miss_count + b0 : nullptr, st, &pending[h], b0, h, fev, dba ? 32 : 64);
+                          a->miss_count ? a->miss_count + b0 : nullptr, st, &pending[h], b0, h, fev, dba ? 28 : 64);
       if (rc != ESS_OK) return rc;
       if (fev) { ctx->prof_nfill[pslot] = h + 1; ctx->prof_pair_stage[pslot] = 5; }
     }
