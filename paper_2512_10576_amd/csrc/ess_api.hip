@@ -58,7 +58,7 @@ int validate_config(const ess_config* c) {
 }
 
 struct WsLayout {
-  size_t score, slot_idx, hit, miss, n_hit, n_miss, fill_tok, fill_slot, miss_cnt, o_part, lse_part, stats, zero_row, total;
+  size_t score, slot_idx, hit, miss, n_hit, n_miss, fill_tok, fill_slot, miss_cnt, o_part, lse_part, stats, zero_row, topk_cand, topk_cnt, total;
 };
 
 size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -81,6 +81,8 @@ WsLayout ws_layout(const ess_config& c) {
   w.lse_part = take(B * T * ESS_MAX_SPLITS * H * 4);
   w.stats = take(4 * 8);
   w.zero_row = take(ESS_ZERO_ROW_BYTES);
+  w.topk_cand = take(ess_topk_cand_bytes());
+  w.topk_cnt = take(ESS_TOPK_SHARED_ROWS * sizeof(uint32_t));
   w.total = off;
   return w;
 }
@@ -213,6 +215,8 @@ int ess_create(const ess_config* cfg, ess_ctx** out) {
   ctx->lse_part = reinterpret_cast<float*>(base + w.lse_part);
   ctx->stats = reinterpret_cast<unsigned long long*>(base + w.stats);
   ctx->zero_row = base + w.zero_row;
+  ctx->topk_cand = reinterpret_cast<unsigned long long*>(base + w.topk_cand);
+  ctx->topk_cnt = reinterpret_cast<uint32_t*>(base + w.topk_cnt);
   auto bail = [&](const char* what, hipError_t err) {
     for (int h = 0; h < 2; ++h) {
       if (ctx->ev_book[h]) (void)hipEventDestroy(ctx->ev_book[h]);
@@ -231,6 +235,7 @@ int ess_create(const ess_config* cfg, ess_ctx** out) {
   }
   if ((e = hipMemset(ctx->stats, 0, 32)) != hipSuccess) return bail("hipMemset", e);
   if ((e = hipMemset(ctx->zero_row, 0, ESS_ZERO_ROW_BYTES)) != hipSuccess) return bail("hipMemset", e);
+  if ((e = hipMemset(ctx->topk_cnt, 0, ESS_TOPK_SHARED_ROWS * sizeof(uint32_t))) != hipSuccess) return bail("hipMemset", e);
   if ((e = hipHostMalloc(reinterpret_cast<void**>(&ctx->host_miss), (size_t)cfg->max_batch * sizeof(int32_t),
                          hipHostMallocMapped)) != hipSuccess) return bail("hipHostMalloc", e);
   memset(ctx->host_miss, 0, (size_t)cfg->max_batch * sizeof(int32_t));
@@ -319,7 +324,7 @@ int ess_topk(ess_ctx* ctx, const float* score, const int32_t* ctx_len, int32_t B
   int rc = check_bt(ctx, B, T);
   if (rc != ESS_OK) return rc;
   if (!score || !ctx_len || !idx) return ess_fail(ESS_ERR_INVALID_ARG, "NULL argument");
-  return ess_launch_topk(ctx->cfg, score, ctx_len, B, T, idx, static_cast<hipStream_t>(stream));
+  return ess_launch_topk(ctx, score, ctx_len, B, T, idx, static_cast<hipStream_t>(stream));
 }
 
 int ess_gather_latent(ess_ctx* ctx, const ess_cache* cache, const int32_t* idx, const int32_t* ctx_len, int32_t B,
@@ -450,7 +455,7 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     if (rc != ESS_OK) return rc;
     ESS_END(0);
     ESS_BEGIN(1);
-    rc = ess_launch_topk(c, sc, a->ctx_len + b0, Bh, T, idx_h, st);
+    rc = ess_launch_topk(ctx, sc, a->ctx_len + b0, Bh, T, idx_h, st);
     if (rc != ESS_OK) return rc;
     ESS_END(1);
     if (!offloaded) continue;

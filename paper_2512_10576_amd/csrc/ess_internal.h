@@ -11,6 +11,7 @@
 #define ESS_MAX_SPLITS 20       // partial results per (b,t): Attn0 splits + Attn1 splits
 #define ESS_ROW_DIM 576
 #define ESS_ZERO_ROW_BYTES 2048  // >= the largest row_stride
+#define ESS_TOPK_SHARED_ROWS 128 // rows (b,t) up to which a top-k row is shared by several workgroups
 #define ESS_PROF_MAIN 16        // stage marks on the caller's stream per step
 #define ESS_PROF_FILL 2         // fetch kernels per step (one per batch half)
 #define ESS_PROF_EVENTS (ESS_PROF_MAIN + 2 * ESS_PROF_FILL)
@@ -34,6 +35,8 @@ struct ess_ctx {
   float* lse_part;              // [B*T, ESS_MAX_SPLITS, H]
   unsigned long long* stats;    // [4]
   uint8_t* zero_row;            // ESS_ZERO_ROW_BYTES of zeros, never written: source of masked attention rows
+  unsigned long long* topk_cand; // [ESS_TOPK_SHARED_ROWS][8192] candidate keys of rows shared by several workgroups
+  uint32_t* topk_cnt;           // [ESS_TOPK_SHARED_ROWS] candidates listed per row: zero between steps
   size_t ws_bytes;
   // overlap switch (ESS_FLAG_AUTO): per-sequence miss counts of the latest bookkeeping, written by the
   // kernel into pinned host memory and read by the host, without a synchronisation, at the next step
@@ -66,8 +69,9 @@ int ess_fail(int code, const char* fmt, ...);
 int ess_launch_index_score(const ess_config& c, const uint8_t* q, const float* w, const uint8_t* key,
                            const int32_t* ctx_len, int B, int T, float* score, hipStream_t st,
                            const int32_t* block_table = nullptr, int n_pages = 0);
-int ess_launch_topk(const ess_config& c, const float* score, const int32_t* ctx_len, int B, int T,
-                    int32_t* idx, hipStream_t st);
+int ess_launch_topk(ess_ctx* ctx, const float* score, const int32_t* ctx_len, int B, int T, int32_t* idx,
+                    hipStream_t st);
+size_t ess_topk_cand_bytes();
 // fill kernel (used instead of hipMemsetAsync so that callers may capture the stream in a graph)
 int ess_launch_calib_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
 int ess_launch_append(const ess_config& c, const ess_cache& cache, const uint8_t* new_key, const uint8_t* new_rows,

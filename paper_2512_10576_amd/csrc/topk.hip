@@ -8,7 +8,7 @@
 //
 // One workgroup per (b,t) row finds the threshold key T* = the k-th largest
 // composite key, then emits every position whose key is >= T*:
-//   A. long rows: a 14-bit histogram of every 16th score gives a key that is
+//   A. long rows: a 14-bit histogram of a sample of the scores gives a key that is
 //      below the k-th largest score with high probability yet keeps only a few
 //      thousand positions at or above it; one pass over the row collects those
 //      candidates (their composite keys) in LDS.  If their number is not in
@@ -207,10 +207,22 @@ __device__ __forceinline__ void scan_row_rounds(const float* __restrict__ srow, 
   }
 }
 
+// MODE 0: one workgroup does the whole row (grid: rows).
+// MODE 1 + MODE 2, for small batches of long rows: the candidate pass of path A, the only part that
+// scales with the row, is spread over `parts` workgroups per row in a kernel of its own (MODE 1, grid
+// parts x rows: every workgroup finds the same threshold from the same samples, scans its slice and
+// appends its candidates to the row's list in global memory, g_cnt[row] counting them), and the
+// finishing kernel (MODE 2, grid rows) takes the list when its size is in [k, buffer] -- else it does
+// the row by itself like MODE 0.  The hand-over is the kernel boundary: workgroups of one kernel
+// never exchange data (an agent-scope fence inside a kernel costs tens of microseconds on this
+// multi-die part, where it writes the L2 back).  g_cnt is zero between steps: MODE 2 clears it.
+template <int MODE>
 __global__ __launch_bounds__(NT) void k_topk(const float* __restrict__ score, const int32_t* __restrict__ ctx_len,
-                                             int T, int Lmax, int k, int IB, int32_t* __restrict__ idx_out) {
+                                             int T, int Lmax, int k, int IB, int32_t* __restrict__ idx_out,
+                                             unsigned long long* __restrict__ g_cand, uint32_t* __restrict__ g_cnt) {
   __shared__ TopkShared sm;
-  const int row = blockIdx.x;
+  const int row = MODE == 1 ? blockIdx.y : blockIdx.x;
+  const int part = MODE == 1 ? blockIdx.x : 0, parts = MODE == 1 ? gridDim.x : 1;
   const int b = row / T, t = row % T;
   const int tid = threadIdx.x, lane = tid & 63;
   int vis = ctx_len[b] - (T - 1 - t);
@@ -218,6 +230,13 @@ __global__ __launch_bounds__(NT) void k_topk(const float* __restrict__ score, co
   const float* srow = score + (size_t)row * Lmax;
   int32_t* orow = idx_out + (size_t)row * k;
 
+  if (MODE == 1 && (vis <= k || vis < FAST_MIN_VIS)) return;      // nothing to prepare
+  uint32_t listed = 0;
+  if (MODE == 2) {                         // candidates prepared by the MODE 1 kernel (0 if none)
+    listed = g_cnt[row];
+    __syncthreads();
+    if (tid == 0) g_cnt[row] = 0;
+  }
   if (vis <= k) {                          // everything visible is selected
     for (int j = tid; j < k; j += NT) orow[j] = j < vis ? j : -1;
     return;
@@ -239,10 +258,23 @@ __global__ __launch_bounds__(NT) void k_topk(const float* __restrict__ score, co
   int nc = 0;
 
   // ---- A: sampled one-pass collection for long rows
+  const bool use_list = MODE == 2 && listed >= (uint32_t)k && listed <= (uint32_t)CAND_CAP;
+  if (use_list) {
+    const unsigned long long* grow = g_cand + (size_t)row * CAND_CAP;
+    for (int j = tid; j < (int)listed; j += NT) sm.cand[j] = grow[j];
+    if (tid == 0) sm.cand_n = listed;
+    __syncthreads();
+  }
   if (vis >= FAST_MIN_VIS) {
-    int sstride = 16;
-    while (vis / sstride > SAMPLE_TARGET) sstride <<= 1;
-    const int ns = vis / sstride;
+   uint32_t lo_bin = 0;
+   if (!use_list) {
+    // samples: blocks of 16 consecutive scores (one 64-byte piece of a cache line), every bstride-th block,
+    // about SAMPLE_TARGET scores in all.  (One score out of every 16th..32nd touches every cache line of the
+    // row: in cache-line traffic the sample then costs as much as the pass that follows.)
+    const int nblk_all = vis >> 4;
+    int bstride = 1;
+    while (nblk_all / bstride > SAMPLE_TARGET / 16) bstride <<= 1;
+    const int ns = (nblk_all / bstride) << 4;
     for (int j = tid; j < SBINS; j += NT) sm.shist[j] = 0;
     if (tid == 0) { sm.cand_n = 0; sm.sel_digit = 0xffffffffu; }
     __syncthreads();
@@ -251,7 +283,7 @@ __global__ __launch_bounds__(NT) void k_topk(const float* __restrict__ score, co
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int j = j0 + u * NT + tid;
-        sv[u] = j < ns ? srow[j * sstride + 7] : 0.f;
+        sv[u] = j < ns ? srow[(size_t)(j >> 4) * bstride * 16 + (j & 15)] : 0.f;
       }
 #pragma unroll
       for (int u = 0; u < 4; ++u)
@@ -276,16 +308,22 @@ __global__ __launch_bounds__(NT) void k_topk(const float* __restrict__ score, co
       }
     }
     __syncthreads();
-    const uint32_t lo_bin = sm.sel_digit;
+    lo_bin = sm.sel_digit;
     __syncthreads();                          // shist is dead from here: cand may overwrite it
-    if (lo_bin != 0xffffffffu) {
+   }
+    if (MODE == 1 && lo_bin == 0xffffffffu) return;   // no usable threshold: the finishing kernel takes path B
+    if (use_list || lo_bin != 0xffffffffu) {
+     if (!use_list) {
       const uint32_t tau = lo_bin << (32 - SBITS);
       // The pass only compares floats and stores (position, score) of the few positions at or above
       // the key: v >= tau_f is the same predicate as orderable(v) >= tau (NaN fails both, -0 == +0),
       // and the composite keys are computed afterwards, densely, for the candidates alone.
       const float tau_f = __uint_as_float((tau & 0x80000000u) ? (tau & 0x7fffffffu) : ~tau);
       uint2* raw = reinterpret_cast<uint2*>(sm.cand);
-      scan_row_rounds(srow, vis, vec_ok, [&](const int (&pos)[16], const float (&val)[16], const bool (&ok)[16]) {
+      // this workgroup's slice of the row (boundaries on 16-byte pieces)
+      const int s_lo = parts > 1 ? (int)(((long)vis * part / parts) & ~3L) : 0;
+      const int s_hi = (parts > 1 && part + 1 < parts) ? (int)(((long)vis * (part + 1) / parts) & ~3L) : vis;
+      scan_row_rounds(srow + s_lo, s_hi - s_lo, vec_ok, [&](const int (&pos)[16], const float (&val)[16], const bool (&ok)[16]) {
         uint32_t cnt = 0, flags = 0;
 #pragma unroll
         for (int e = 0; e < 16; ++e)
@@ -298,7 +336,7 @@ __global__ __launch_bounds__(NT) void k_topk(const float* __restrict__ score, co
 #pragma unroll
         for (int e = 0; e < 16; ++e)
           if (flags & (1u << e)) {
-            if (base < (uint32_t)CAND_CAP) raw[base] = make_uint2((uint32_t)pos[e], __float_as_uint(val[e]));
+            if (base < (uint32_t)CAND_CAP) raw[base] = make_uint2((uint32_t)(pos[e] + s_lo), __float_as_uint(val[e]));
             ++base;
           }
       });
@@ -309,7 +347,20 @@ __global__ __launch_bounds__(NT) void k_topk(const float* __restrict__ score, co
           sm.cand[j] = comp_of((int)pv.x, __uint_as_float(pv.y));
         }
       __syncthreads();
+     }
       nc = (int)sm.cand_n;
+      if (MODE == 1) {
+        // append this slice's candidates to the row's list; the true count is added even when it overflows,
+        // so that the finishing kernel sees the overflow
+        unsigned long long* grow = g_cand + (size_t)row * CAND_CAP;
+        if (tid == 0) sm.sel_above = atomicAdd(&g_cnt[row], (uint32_t)nc);
+        __syncthreads();
+        const uint32_t gbase = sm.sel_above;
+        if (nc <= CAND_CAP)
+          for (int j = tid; j < nc; j += NT)
+            if (gbase + (uint32_t)j < (uint32_t)CAND_CAP) grow[gbase + j] = sm.cand[j];
+        return;
+      }
       if (nc >= k && nc <= CAND_CAP) {
         // bits on which the candidates differ: everything above is common and decided
         unsigned long long a = ~0ull, o = 0ull;
@@ -459,11 +510,30 @@ __global__ __launch_bounds__(NT) void k_topk(const float* __restrict__ score, co
 
 }  // namespace
 
-int ess_launch_topk(const ess_config& c, const float* score, const int32_t* ctx_len, int B, int T, int32_t* idx,
+int ess_launch_topk(ess_ctx* ctx, const float* score, const int32_t* ctx_len, int B, int T, int32_t* idx,
                     hipStream_t st) {
+  const ess_config& c = ctx->cfg;
   int IB = 1;
   while ((1 << IB) < c.max_ctx) ++IB;
-  hipLaunchKernelGGL(k_topk, dim3(B * T), dim3(NT), 0, st, score, ctx_len, T, c.max_ctx, c.topk, IB, idx);
+  // small batches of long rows: the candidate pass goes to a kernel of its own that puts several
+  // workgroups on every row (as many as fill the chip, at most 8)
+  const int rows = B * T;
+  int parts = 1;
+  if (c.max_ctx >= 4 * FAST_MIN_VIS && rows <= ESS_TOPK_SHARED_ROWS) {
+    parts = 256 / rows;
+    if (parts > 8) parts = 8;
+  }
+  if (parts > 1) {
+    hipLaunchKernelGGL(k_topk<1>, dim3(parts, rows), dim3(NT), 0, st, score, ctx_len, T, c.max_ctx, c.topk, IB, idx,
+                       ctx->topk_cand, ctx->topk_cnt);
+    hipLaunchKernelGGL(k_topk<2>, dim3(rows), dim3(NT), 0, st, score, ctx_len, T, c.max_ctx, c.topk, IB, idx,
+                       ctx->topk_cand, ctx->topk_cnt);
+  } else {
+    hipLaunchKernelGGL(k_topk<0>, dim3(rows), dim3(NT), 0, st, score, ctx_len, T, c.max_ctx, c.topk, IB, idx,
+                       ctx->topk_cand, ctx->topk_cnt);
+  }
   ESS_HIP(hipGetLastError());
   return ESS_OK;
 }
+
+size_t ess_topk_cand_bytes() { return (size_t)ESS_TOPK_SHARED_ROWS * CAND_CAP * sizeof(unsigned long long); }
