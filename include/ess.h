@@ -118,6 +118,9 @@ typedef struct {
   int32_t reserved;             /* 0 */
 } ess_step_args;
 
+/* A context owns scratch memory that its calls share (scores, candidate lists and counters, partial
+ * attention results, event objects): calls on one context must not overlap in time -- enqueue them
+ * on one stream, or order the streams.  Different contexts are independent. */
 /* Create a context: validates the configuration, allocates the workspace
  * (see ess_workspace_bytes), a side stream and events on the current device.
  * ESS_ERR_INVALID_ARG / ESS_ERR_UNSUPPORTED / ESS_ERR_CAPACITY (S < T*k) / ESS_ERR_NOMEM. */

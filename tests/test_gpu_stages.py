@@ -136,6 +136,43 @@ def test_topk_full_size_row_with_boundary_ties(ess_lib):
     _topk_sets_equal(_run_topk(ess_lib, sc, lens, k, 1), O.topk(sc, np.array(lens), k))
 
 
+def test_topk_long_rows_shared_candidate_pass(ess_lib):
+    """rows long enough (and few enough) for the candidate pass to be spread over several workgroups per
+    row: inputs that make the shared list overflow, stay empty or hold massive ties must fall back cleanly,
+    and a second call must find the row counters clean"""
+    print("topk 128K adversarial", flush=True)
+    L, k = 131072, 2048
+    rng = np.random.default_rng(8)
+    rows = []
+    rows.append(np.full(L, 3.5, np.float32))                                          # all equal: the list overflows
+    rows.append(np.arange(L, 0, -1, dtype=np.float32))                                # strictly decreasing
+    tie = np.zeros(L, np.float32); tie[::7] = 2.0; tie[5::1000] = 9.0                 # a huge tie at the cut
+    rows.append(tie)
+    mixed = rng.integers(-3, 4, L).astype(np.float32) / 16
+    mixed[rng.integers(0, L, 50)] = np.nan
+    mixed[rng.integers(0, L, 50)] = -np.inf
+    rows.append(mixed)
+    rows.append((rng.standard_normal(L) * 10.0 ** rng.integers(-20, 20, L)).astype(np.float32))
+    rows.append((np.rint(rng.normal(40000, 7000, L)).clip(0) / 16).astype(np.float32))  # the ordinary case
+    sc = np.stack(rows)[:, None, :]
+    lens = [L, L - 3, L, 70001, L, 16385]
+    ref = O.topk(sc, np.array(lens), k)
+    _topk_sets_equal(_run_topk(ess_lib, sc, lens, k, 1), ref)
+    lens2 = [20000, L, 2048, L, 0, L]                                                 # short rows beside long ones
+    _topk_sets_equal(_run_topk(ess_lib, sc, lens2, k, 1), O.topk(sc, np.array(lens2), k))
+    # same context twice in a row (the per-row counters must be back at zero after a call)
+    from paper_2512_10576_amd import binding as bnd
+    ctx = _ctx(ess_lib, max_batch=len(rows), max_q_tokens=1, max_ctx=L, idx_heads=4, idx_dim=32, topk=k, attn_heads=8)
+    d_sc, d_len = torch.from_numpy(sc).cuda(), torch.tensor(lens, dtype=torch.int32).cuda()
+    idx = torch.empty((len(rows), 1, k), dtype=torch.int32, device="cuda")
+    for _ in range(3):
+        idx.fill_(-7)
+        ctx.topk(d_sc, d_len, idx)
+        torch.cuda.synchronize()
+        _topk_sets_equal(idx.cpu().numpy(), ref)
+    ctx.close()
+
+
 # ---------------------------------------------------------------- stages 3 + 5
 @pytest.mark.parametrize("B,T,L,S,k,steps,rho", [(3, 1, 4096, 1024, 256, 6, 0.75), (2, 2, 6000, 2500, 1024, 5, 0.5),
                                                  (1, 1, 20000, 2048, 2048, 4, 0.8)])
