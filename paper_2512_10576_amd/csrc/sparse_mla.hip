@@ -245,23 +245,25 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
   // instruction per row) and the rope parts of the same rows (step 8).
   const int rr = wave * 8 + (lane >> 3);
   const int rope_off = 1024 + (((lane & 7) ^ (rr & 7)) * 16);
-  // source rows of one tile: read from LDS in one go, so that no gather waits on the LDS queue later
-  auto gather_sources = [&](int it, const uint8_t* (&src)[DMA_PER_TILE]) {
+  // slots of one tile's rows: read from LDS in one go, so that no gather waits on the LDS queue later; the
+  // address of a row is computed when its gather is issued (scalar arithmetic for the eight whole-row
+  // gathers: it then runs while the matrix pipe is busy)
+  auto gather_sources = [&](int it, int (&sl)[DMA_PER_TILE]) {
     const int32_t* ts = slot_cache + it * TILE;
-    int sl[DMA_PER_TILE];
 #pragma unroll
     for (int r8 = 0; r8 < 8; ++r8) sl[r8] = ts[wave * 8 + r8];
     sl[8] = ts[rr];
-#pragma unroll
-    for (int r8 = 0; r8 < DMA_PER_TILE; ++r8) src[r8] = sl[r8] >= 0 ? pbase + (size_t)sl[r8] * row_stride : zero_row;
   };
-  auto gather_step = [&](int it, int step, const uint8_t* const (&src)[DMA_PER_TILE]) {
+  auto gather_step = [&](int it, int step, const int (&sl)[DMA_PER_TILE]) {
     const uint32_t raw = lds0 + (uint32_t)((it % NBUF) * TR_RAW_BYTES);
     if (step < 8) {
       const int row = wave * 8 + step;
-      dma16(src[step] + ((lane ^ tr_swz(row)) << 4), raw + (uint32_t)(row * TRP));
+      const int u = __builtin_amdgcn_readfirstlane(sl[step]);
+      const uint8_t* src = u >= 0 ? pbase + (size_t)u * row_stride : zero_row;
+      dma16(src + ((lane ^ tr_swz(row)) << 4), raw + (uint32_t)(row * TRP));
     } else {
-      dma16(src[8] + rope_off, raw + (uint32_t)(TR_KL_BYTES + wave * 1024));
+      const uint8_t* src = sl[8] >= 0 ? pbase + (size_t)sl[8] * row_stride : zero_row;
+      dma16(src + rope_off, raw + (uint32_t)(TR_KL_BYTES + wave * 1024));
     }
   };
   // Quantised entries: a tile's share of a thread -- row tid/8: four 16-byte pieces of fp8 values (piece
@@ -304,7 +306,7 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
   StagedF8 stg;
   if constexpr (kDma) {
     for (int it = 0; it < min(my_tiles, NBUF - 1); ++it) {
-      const uint8_t* src[DMA_PER_TILE];
+      int src[DMA_PER_TILE];
       gather_sources(it, src);
 #pragma unroll
       for (int step = 0; step < DMA_PER_TILE; ++step) gather_step(it, step, src);
@@ -335,7 +337,7 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
     const uint8_t* RP = KL + TR_KL_BYTES;
     const int32_t* tile_slot = slot_cache + it * TILE;
     const bool more = kDma && it + NBUF - 1 < my_tiles;   // tile it+3 goes into the buffer tile it-1 used
-    const uint8_t* src[DMA_PER_TILE];
+    int src[DMA_PER_TILE];
     if constexpr (kDma) {
       // this wave's gathers of tile `it` have landed when at most those of the later tiles are outstanding
       const int later = min(my_tiles - 1 - it, NBUF - 2);
@@ -393,6 +395,19 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
     }
     const int4 v0 = *reinterpret_cast<const int4*>(tile_slot + g * 4);
     const int4 v1 = *reinterpret_cast<const int4*>(tile_slot + 16 + g * 4);
+    // the first V fragments do not depend on the softmax: request them now, they arrive while it runs
+    constexpr int CV = 8;
+    bf16x8 fv[2][CV];
+    auto load_v = [&](int c, bf16x8 (&d)[CV]) {
+#pragma unroll
+      for (int j = 0; j < CV; ++j) {
+        const int vb = c * CV + j;
+        const uint32_t a = KLa + voff[vb & 7] + 256u * (uint32_t)(vb >> 3);
+        d[j] = tr_frag(a, a + 16 * TRP);
+      }
+    };
+    load_v(0, fv[0]);
+    load_v(1, fv[1]);
     const bool ok[8] = {v0.x >= 0, v0.y >= 0, v0.z >= 0, v0.w >= 0, v1.x >= 0, v1.y >= 0, v1.z >= 0, v1.w >= 0};
     float z[8];
     ESS_PH(1);
@@ -420,24 +435,16 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
     }
     l_run += psum;
     uint4 pw = make_uint4(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7]));
+    // The MFMAs below are asm statements, which the compiler's hazard logic does not look into, and a
+    // vector ALU write followed at once by an MFMA that reads the register gave the MFMA the old value.
+    // The statement is tied to the four registers so that it stays between their last write and the MFMAs.
+    asm volatile("s_nop 7" : "+v"(pw.x), "+v"(pw.y), "+v"(pw.z), "+v"(pw.w));
     const bf16x8 pb = *reinterpret_cast<bf16x8*>(&pw);
     ESS_PH(2);
 
     // ---- O^T += V^T P^T, A fragments by transposing reads, eight blocks ahead
-    constexpr int CV = 8;
-    bf16x8 fv[2][CV];
-    auto load_v = [&](int c, bf16x8 (&d)[CV]) {
-#pragma unroll
-      for (int j = 0; j < CV; ++j) {
-        const int vb = c * CV + j;
-        const uint32_t a = KLa + voff[vb & 7] + 256u * (uint32_t)(vb >> 3);
-        d[j] = tr_frag(a, a + 16 * TRP);
-      }
-    };
     static_assert(VBLOCKS / CV == 4, "four chunks of value blocks");
     constexpr auto seq = std::make_integer_sequence<int, CV>{};
-    load_v(0, fv[0]);
-    load_v(1, fv[1]);
     pv_chunk<0 * CV>(fv[0], pb, seq);
     load_v(2, fv[0]);
     pv_chunk<1 * CV>(fv[1], pb, seq);

@@ -94,3 +94,24 @@ def test_attention_kernel_agprs_are_only_named_by_its_own_asm(tmp_path):
                     assert re.search(r"a\[(\d+):(\d+)\], v\[\d+:\d+\], v\[\d+:\d+\], a\[\1:\2\]", t), t
         # 32 accumulating MFMAs; 128 zero writes + 128 rescale writes; 128 rescale reads + 128 final reads
         assert seen == {"v_mfma_f32_16x16x32_bf16": 32, "v_accvgpr_write_b32": 256, "v_accvgpr_read_b32": 256}, seen
+        # The compiler's hazard logic does not see inside those asm statements.  No vector ALU instruction
+        # may write a VGPR operand of such an MFMA in the instructions just before it unless wait states
+        # (s_nop) stand between: without them the MFMA was seen to read the register's old value.
+        body = [l.strip() for l in lines[start:end] if l.strip() and not l.strip().startswith((";", "."))]
+        for i, t in enumerate(body):
+            m = re.match(r"v_mfma\S* a\[\d+:\d+\], v\[(\d+):(\d+)\], v\[(\d+):(\d+)\], a\[", t)
+            if not m:
+                continue
+            used = set(range(int(m[1]), int(m[2]) + 1)) | set(range(int(m[3]), int(m[4]) + 1))
+            states = 0
+            for prev in reversed(body[max(0, i - 8):i]):
+                if prev.startswith("s_nop"):
+                    states += int(prev.split()[1]) + 1
+                    continue
+                states += 1
+                if states > 8 or not prev.startswith("v_") or prev.startswith("v_mfma"):
+                    continue
+                dst = re.match(r"v_\S+ v(?:\[(\d+):(\d+)\]|(\d+))", prev)
+                if dst:
+                    wr = set(range(int(dst[1]), int(dst[2]) + 1)) if dst[1] else {int(dst[3])}
+                    assert not (wr & used), (prev, t)
