@@ -444,16 +444,29 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     const size_t bt0 = (size_t)b0 * T;
     float* sc = ctx->score_ws + bt0 * c.max_ctx;
     int32_t* idx_h = a->idx_out + bt0 * k;
-    ESS_BEGIN(0);
+    // the index-score kernel is timed by its own start and end (events handed to the launch), not by
+    // marks on the stream, which would add the dispatch gaps to the figure the roofline is taken from
+    hipEvent_t ev_s = nullptr, ev_e = nullptr;
+    if (pev && (ctx->prof_mask & 1u) && nmark + 2 <= ESS_PROF_MAIN) {
+      ev_s = pev[nmark];
+      ev_e = pev[nmark + 1];
+      ptag[nmark] = -1;
+      ptag[nmark + 1] = 0;
+      nmark += 2;
+      ctx->prof_nmark[pslot] = nmark;
+      adjacent = true;
+    } else {
+      adjacent = false;
+    }
     if (a->block_table)     // paged: one pool for the whole batch, the table rows of this sub-batch
       rc = ess_launch_index_score(c, a->q_idx_fp8 + bt0 * c.idx_heads * c.idx_dim, a->w + bt0 * c.idx_heads, a->key_fp8,
                                   a->ctx_len + b0, Bh, T, sc, st,
-                                  a->block_table + (size_t)b0 * (c.max_ctx / ESS_PAGE_TOKENS), a->n_pages);
+                                  a->block_table + (size_t)b0 * (c.max_ctx / ESS_PAGE_TOKENS), a->n_pages, ev_s, ev_e);
     else
       rc = ess_launch_index_score(c, a->q_idx_fp8 + bt0 * c.idx_heads * c.idx_dim, a->w + bt0 * c.idx_heads,
-                                  a->key_fp8 + (size_t)b0 * c.max_ctx * c.idx_dim, a->ctx_len + b0, Bh, T, sc, st);
+                                  a->key_fp8 + (size_t)b0 * c.max_ctx * c.idx_dim, a->ctx_len + b0, Bh, T, sc, st,
+                                  nullptr, 0, ev_s, ev_e);
     if (rc != ESS_OK) return rc;
-    ESS_END(0);
     ESS_BEGIN(1);
     rc = ess_launch_topk(ctx, sc, a->ctx_len + b0, Bh, T, idx_h, st);
     if (rc != ESS_OK) return rc;

@@ -68,7 +68,9 @@ int ess_fail(int code, const char* fmt, ...);
 // Stage launchers.  All enqueue on `st` and return an ess_status.
 int ess_launch_index_score(const ess_config& c, const uint8_t* q, const float* w, const uint8_t* key,
                            const int32_t* ctx_len, int B, int T, float* score, hipStream_t st,
-                           const int32_t* block_table = nullptr, int n_pages = 0);
+                           const int32_t* block_table = nullptr, int n_pages = 0,
+                           // optional: events that take the kernel's own start and end times
+                           hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 int ess_launch_topk(ess_ctx* ctx, const float* score, const int32_t* ctx_len, int B, int T, int32_t* idx,
                     hipStream_t st);
 size_t ess_topk_cand_bytes();

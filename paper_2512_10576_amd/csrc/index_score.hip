@@ -19,6 +19,7 @@
 // so the head reduction is 4*HB fused multiply-adds in the lane plus two
 // cross-lane steps (xor 16, xor 32).
 #include "ess_internal.h"
+#include <hip/hip_ext.h>
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
@@ -200,16 +201,17 @@ struct IdxArgs {
   const uint8_t* q; const float* w; const uint8_t* key; const int32_t* ctx_len; float* score;
   int Lmax, Hi, chunk;
   const int32_t* block_table; int n_pages;
+  hipEvent_t ev_start, ev_stop;             // optional: take the kernel's own start and end times
 };
 
 template <int HB, int DI, int T>
 void launch_p(dim3 grid, hipStream_t st, const IdxArgs& a) {
   if (a.block_table)
-    hipLaunchKernelGGL((k_index_score<HB, DI, T, true>), grid, dim3(kWaves * 64), 0, st, a.q, a.w, a.key, a.ctx_len,
-                       a.score, a.Lmax, a.Hi, a.chunk, a.block_table, a.n_pages);
+    hipExtLaunchKernelGGL((k_index_score<HB, DI, T, true>), grid, dim3(kWaves * 64), 0, st, a.ev_start, a.ev_stop, 0, a.q,
+                          a.w, a.key, a.ctx_len, a.score, a.Lmax, a.Hi, a.chunk, a.block_table, a.n_pages);
   else
-    hipLaunchKernelGGL((k_index_score<HB, DI, T, false>), grid, dim3(kWaves * 64), 0, st, a.q, a.w, a.key, a.ctx_len,
-                       a.score, a.Lmax, a.Hi, a.chunk, a.block_table, a.n_pages);
+    hipExtLaunchKernelGGL((k_index_score<HB, DI, T, false>), grid, dim3(kWaves * 64), 0, st, a.ev_start, a.ev_stop, 0, a.q,
+                          a.w, a.key, a.ctx_len, a.score, a.Lmax, a.Hi, a.chunk, a.block_table, a.n_pages);
 }
 
 template <int HB, int DI>
@@ -232,14 +234,14 @@ void launch_hb(int HB, int T, dim3 grid, hipStream_t st, const IdxArgs& a) {
 
 int ess_launch_index_score(const ess_config& c, const uint8_t* q, const float* w, const uint8_t* key,
                            const int32_t* ctx_len, int B, int T, float* score, hipStream_t st,
-                           const int32_t* block_table, int n_pages) {
+                           const int32_t* block_table, int n_pages, hipEvent_t ev_start, hipEvent_t ev_stop) {
   const int Hi = c.idx_heads, Di = c.idx_dim, Lmax = c.max_ctx;
   const int HB = (Hi + 15) / 16;
   // tokens per workgroup: a multiple of the 256 tokens the four waves cover per round; 2048 when
   // that still leaves several workgroups per CU, else 1024
   const int chunk = ((long)B * Lmax >= 2048L * 1024) ? 2048 : 1024;
   dim3 grid((Lmax + chunk - 1) / chunk, B);
-  const IdxArgs a{q, w, key, ctx_len, score, Lmax, Hi, chunk, block_table, n_pages};
+  const IdxArgs a{q, w, key, ctx_len, score, Lmax, Hi, chunk, block_table, n_pages, ev_start, ev_stop};
   switch (Di) {
     case 32: launch_hb<32>(HB, T, grid, st, a); break;
     case 64: launch_hb<64>(HB, T, grid, st, a); break;

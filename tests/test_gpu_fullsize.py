@@ -92,3 +92,47 @@ def test_cfg4_full_size_sampled_sequences(ess_lib):
         back = torch.gather(cache.slot_of, 1, cache.token_of.clamp(min=0).long())
         assert bool((back[res] == torch.arange(S, device="cuda").expand(B, S)[res]).all())
     ctx.close()
+
+
+def test_cfg5_full_size_sampled_sequences(ess_lib):
+    """Multi-token decode at full size: batch 128, two query tokens with the causal offset, quantised
+    entries (656 bytes), one of the 61 layers (the layers differ only in their seeds)."""
+    import bench
+    print("full-size cfg5 (B128, T2, ctx 131072, fp8 entries, offloaded, trace-driven)", flush=True)
+    steps = 2
+    W = bench.build_workload("cfg5", steps, layers=1)
+    wl, ctx, cache = W["wl"], W["ctx"], W["cache"]
+    B, T, L, k, S = wl["B"], wl["T"], wl["L"], wl["k"], W["S"]
+    assert (B, T, W["stride"], W["fmt"]) == (128, 2, 656, 1)
+    sample = (0, 77, 127)
+    oracles = {b: (O.SlotCache(1, L, S), np.zeros((1, S, 656), np.uint8)) for b in sample}
+    lens = W["ctx_len"].cpu().numpy()
+    for step in range(1, steps + 1):
+        bench.run_steps(W, step, 1)
+        torch.cuda.synchronize()
+        ov = W["trace"][step - 1].cpu().numpy()
+        slot_of = cache.slot_of.cpu().numpy(); token_of = cache.token_of.cpu().numpy()
+        stamp = cache.stamp.cpu().numpy().view(np.uint32); miss = W["miss"].cpu().numpy()
+        for b in sample:
+            print("  step", step, "sequence", b, flush=True)
+            oc, opool = oracles[b]
+            host = W["host_pool"][b:b + 1].numpy()
+            r = oc.step(ov[b:b + 1], step)
+            O.fill_slots(opool, host, r["miss_tok"], r["victims"])
+            assert miss[b] == r["miss_count"][0]
+            assert np.array_equal(slot_of[b], oc.slot_of[0]) and np.array_equal(token_of[b], oc.token_of[0])
+            assert np.array_equal(stamp[b], oc.stamp[0])
+            occ = np.nonzero(oc.token_of[0] >= 0)[0]
+            gpu_rows = cache.slot_pool[b].cpu().numpy()
+            assert np.array_equal(gpu_rows[occ], opool[0, occ])
+            ref_out, _ = O.sparse_mla(_qbits(W["q_attn"][b:b + 1]), opool, r["slot_idx"], O.FMT_FP8, 576 ** -0.5)
+            _attn_close(W["out"][b:b + 1], ref_out)
+            if step == 1:                                                                # both query tokens, causal offset
+                q_idx = W["q_idx"][b:b + 1].cpu().numpy(); w = W["w"][b:b + 1].cpu().numpy()
+                key = W["key"][b:b + 1].cpu().numpy()
+                ref_idx = O.topk(O.index_score(q_idx, w, key, lens[b:b + 1]), lens[b:b + 1], k)
+                for t in range(T):
+                    assert np.array_equal(W["idx_out"][b, t].cpu().numpy(), np.sort(ref_idx[0, t]))
+        sel = torch.from_numpy(ov.reshape(B, T * k).astype(np.int64)).cuda()
+        assert bool((torch.gather(cache.slot_of, 1, sel) >= 0).all())
+    ctx.close()
