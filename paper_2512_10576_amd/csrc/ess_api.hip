@@ -497,8 +497,7 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     if (rc != ESS_OK) return rc;
     ESS_END(3);
     ESS_BEGIN(4);
-    if (a->miss_count && (rc = ess_launch_fill_u32(reinterpret_cast<uint32_t*>(a->miss_count), B, 0u, st)) != ESS_OK) return rc;
-    rc = ess_launch_attn_merge(ctx, B, T, ns0, a->out_bf16, a->lse, st);
+    rc = ess_launch_attn_merge(ctx, B, T, ns0, a->out_bf16, a->lse, st, a->miss_count, B);   // no misses: the counts are zero
     if (rc != ESS_OK) return rc;
     ESS_END(4);
     return ESS_OK;

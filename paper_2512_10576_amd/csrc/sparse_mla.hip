@@ -477,9 +477,15 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
 }
 
 // out[bt,h,:] = sum_s exp(lse_s - lse) * o_s ;  lse = log sum_s exp(lse_s).  One wave per (bt,h).
+// The partial results of four splits are requested before any is used (the kernel is a chain of
+// dependent loads otherwise).  `zero_cnt` (may be NULL): n_zero counters the first workgroup clears,
+// for steps that have no other kernel to do it in.
 __global__ __launch_bounds__(256) void k_attn_merge(const float* __restrict__ o_part, const float* __restrict__ lse_part,
                                                     int H, int nsplit, int total_rows, uint16_t* __restrict__ out,
-                                                    float* __restrict__ lse_out) {
+                                                    float* __restrict__ lse_out, int32_t* __restrict__ zero_cnt,
+                                                    int n_zero) {
+  if (zero_cnt && blockIdx.x == 0)
+    for (int i = threadIdx.x; i < n_zero; i += 256) zero_cnt[i] = 0;
   const int rowi = blockIdx.x * 4 + (threadIdx.x >> 6);      // bt*H + h
   if (rowi >= total_rows) return;
   const int lane = threadIdx.x & 63;
@@ -490,15 +496,25 @@ __global__ __launch_bounds__(256) void k_attn_merge(const float* __restrict__ o_
   float den = 0.f;
   float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   if (mx > -__builtin_inff()) {
-    for (int s = 0; s < nsplit; ++s) {
-      const float ls = lse_part[base + (size_t)s * H];
-      if (ls == -__builtin_inff()) continue;
-      const float wgt = __expf(ls - mx);
-      den += wgt;
-      const float4* op = reinterpret_cast<const float4*>(o_part + (base + (size_t)s * H) * ESS_LATENT_DIM + lane * 8);
-      const float4 x = op[0], y = op[1];
-      a[0] += wgt * x.x; a[1] += wgt * x.y; a[2] += wgt * x.z; a[3] += wgt * x.w;
-      a[4] += wgt * y.x; a[5] += wgt * y.y; a[6] += wgt * y.z; a[7] += wgt * y.w;
+    for (int s0 = 0; s0 < nsplit; s0 += 4) {
+      float ls[4];
+      float4 x[4], y[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int s = min(s0 + u, nsplit - 1);                // clamped copies get weight 0 below
+        ls[u] = lse_part[base + (size_t)s * H];
+        const float4* op = reinterpret_cast<const float4*>(o_part + (base + (size_t)s * H) * ESS_LATENT_DIM + lane * 8);
+        x[u] = op[0];
+        y[u] = op[1];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (s0 + u >= nsplit || ls[u] == -__builtin_inff()) continue;   // an empty split's partial result is not read as data
+        const float wgt = __expf(ls[u] - mx);
+        den += wgt;
+        a[0] += wgt * x[u].x; a[1] += wgt * x[u].y; a[2] += wgt * x[u].z; a[3] += wgt * x[u].w;
+        a[4] += wgt * y[u].x; a[5] += wgt * y[u].y; a[6] += wgt * y[u].z; a[7] += wgt * y[u].w;
+      }
     }
   }
   const float inv = den > 0.f ? 1.0f / den : 0.f;
@@ -545,10 +561,11 @@ int ess_launch_attn_partial(ess_ctx* ctx, const void* q, const uint8_t* slot_poo
   return ESS_OK;
 }
 
-int ess_launch_attn_merge(ess_ctx* ctx, int B, int T, int nsplit_total, void* out_bf16, float* lse, hipStream_t st) {
+int ess_launch_attn_merge(ess_ctx* ctx, int B, int T, int nsplit_total, void* out_bf16, float* lse, hipStream_t st,
+                          int32_t* zero_cnt, int n_zero) {
   const int rows = B * T * ctx->cfg.attn_heads;
   hipLaunchKernelGGL(k_attn_merge, dim3((rows + 3) / 4), dim3(256), 0, st, ctx->o_part, ctx->lse_part,
-                     ctx->cfg.attn_heads, nsplit_total, rows, static_cast<uint16_t*>(out_bf16), lse);
+                     ctx->cfg.attn_heads, nsplit_total, rows, static_cast<uint16_t*>(out_bf16), lse, zero_cnt, n_zero);
   ESS_HIP(hipGetLastError());
   return ESS_OK;
 }
