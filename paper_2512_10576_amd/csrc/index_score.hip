@@ -204,14 +204,21 @@ struct IdxArgs {
   hipEvent_t ev_start, ev_stop;             // optional: take the kernel's own start and end times
 };
 
+template <int HB, int DI, int T, bool PAGED>
+void launch_k(dim3 grid, hipStream_t st, const IdxArgs& a) {
+  const dim3 block(kWaves * 64);
+  if (a.ev_start || a.ev_stop)      // timed launch: the events take the kernel's own start and end
+    hipExtLaunchKernelGGL((k_index_score<HB, DI, T, PAGED>), grid, block, 0, st, a.ev_start, a.ev_stop, 0, a.q, a.w, a.key,
+                          a.ctx_len, a.score, a.Lmax, a.Hi, a.chunk, a.block_table, a.n_pages);
+  else
+    hipLaunchKernelGGL((k_index_score<HB, DI, T, PAGED>), grid, block, 0, st, a.q, a.w, a.key, a.ctx_len, a.score, a.Lmax,
+                       a.Hi, a.chunk, a.block_table, a.n_pages);
+}
+
 template <int HB, int DI, int T>
 void launch_p(dim3 grid, hipStream_t st, const IdxArgs& a) {
-  if (a.block_table)
-    hipExtLaunchKernelGGL((k_index_score<HB, DI, T, true>), grid, dim3(kWaves * 64), 0, st, a.ev_start, a.ev_stop, 0, a.q,
-                          a.w, a.key, a.ctx_len, a.score, a.Lmax, a.Hi, a.chunk, a.block_table, a.n_pages);
-  else
-    hipExtLaunchKernelGGL((k_index_score<HB, DI, T, false>), grid, dim3(kWaves * 64), 0, st, a.ev_start, a.ev_stop, 0, a.q,
-                          a.w, a.key, a.ctx_len, a.score, a.Lmax, a.Hi, a.chunk, a.block_table, a.n_pages);
+  if (a.block_table) launch_k<HB, DI, T, true>(grid, st, a);
+  else launch_k<HB, DI, T, false>(grid, st, a);
 }
 
 template <int HB, int DI>
