@@ -71,7 +71,8 @@ typedef struct ess_ctx ess_ctx;
 typedef struct {
   uint32_t struct_size;   /* sizeof(ess_config), checked */
   int32_t max_batch;      /* largest B any call will pass; <= 4096 */
-  int32_t max_q_tokens;   /* largest T (1 or 2) */
+  int32_t max_q_tokens;   /* largest T (1 to 4, and T * topk <= 8192); the index score handles two query
+                             tokens per pass over the keys, so T = 3, 4 read the Indexer-Cache twice */
   int32_t max_ctx;        /* Lmax: row pitch of key, score and slot_of; <= 524288 */
   int32_t idx_heads;      /* Hi, 1..64 */
   int32_t idx_dim;        /* Di, 32 | 64 | 128 */

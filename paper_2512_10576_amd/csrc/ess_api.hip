@@ -28,8 +28,8 @@ int validate_config(const ess_config* c) {
   if (c->struct_size != sizeof(ess_config))
     return ess_fail(ESS_ERR_INVALID_ARG, "struct_size %u != %zu", c->struct_size, sizeof(ess_config));
   if (c->max_batch < 1 || c->max_batch > 4096) return ess_fail(ESS_ERR_INVALID_ARG, "max_batch %d outside [1, 4096]", c->max_batch);
-  if (c->max_q_tokens < 1 || c->max_q_tokens > 2)
-    return ess_fail(ESS_ERR_UNSUPPORTED, "max_q_tokens %d (supported: 1, 2)", c->max_q_tokens);
+  if (c->max_q_tokens < 1 || c->max_q_tokens > 4)
+    return ess_fail(ESS_ERR_UNSUPPORTED, "max_q_tokens %d (supported: 1 to 4)", c->max_q_tokens);
   if (c->max_ctx < 1 || c->max_ctx > ESS_MAX_CTX)
     return ess_fail(ESS_ERR_INVALID_ARG, "max_ctx %d outside [1, %d]", c->max_ctx, ESS_MAX_CTX);
   if (c->idx_heads < 1 || c->idx_heads > 64)

@@ -49,7 +49,9 @@ __device__ __forceinline__ void load_row_share(const uint8_t* row, int g, long (
   }
 }
 
-// HB = 16-head blocks (Hi padded up), DI = indexer dim, T = query tokens per sequence.
+// HB = 16-head blocks (Hi padded up), DI = indexer dim, T = query tokens per sequence handled by this
+// launch (1 or 2): tokens t0 .. t0+T-1 of the Ttot the sequence has.  More than two tokens per
+// sequence take further launches, which read the keys again.
 // PAGED: `key` is a pool of pages (64 keys of DI bytes, then 64 float scales); token s of sequence b is
 // row s % 64 of page block_table[b, s / 64] and its score is multiplied by its scale (positive, so the
 // scale commutes with the ReLU and the head sum: one multiplication of the exact sum).  A wave's batch
@@ -61,7 +63,8 @@ __global__ __launch_bounds__(kWaves * 64, T == 2 ? 2 : 1) void k_index_score(con
                                                               const int32_t* __restrict__ ctx_len,
                                                               float* __restrict__ score, int Lmax, int Hi,
                                                               int chunk_tokens,
-                                                              const int32_t* __restrict__ block_table, int n_pages) {
+                                                              const int32_t* __restrict__ block_table, int n_pages,
+                                                              int Ttot, int t0) {
   constexpr int KS = DI / 32;
   constexpr size_t kPageBytes = (size_t)kBatchTokens * (DI + 4);
   const int b = blockIdx.y;
@@ -84,7 +87,7 @@ __global__ __launch_bounds__(kWaves * 64, T == 2 ? 2 : 1) void k_index_score(con
     for (int mb = 0; mb < HB; ++mb) {
       const int head = mb * 16 + n;
       if (head < Hi) {
-        load_row_share<DI>(q + ((size_t)(b * T + t) * Hi + head) * DI, g, qa[t][mb]);
+        load_row_share<DI>(q + ((size_t)(b * Ttot + t0 + t) * Hi + head) * DI, g, qa[t][mb]);
       } else {
 #pragma unroll
         for (int kk = 0; kk < KS; ++kk) qa[t][mb][kk] = 0;
@@ -92,7 +95,7 @@ __global__ __launch_bounds__(kWaves * 64, T == 2 ? 2 : 1) void k_index_score(con
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int hrow = mb * 16 + g * 4 + i;
-        wr[t][mb][i] = hrow < Hi ? w[(size_t)(b * T + t) * Hi + hrow] : 0.f;
+        wr[t][mb][i] = hrow < Hi ? w[(size_t)(b * Ttot + t0 + t) * Hi + hrow] : 0.f;
       }
     }
   }
@@ -162,7 +165,7 @@ __global__ __launch_bounds__(kWaves * 64, T == 2 ? 2 : 1) void k_index_score(con
     const int tok = base + lane;                              // = base + 16*g + n
     if (tok < blk_end) {
 #pragma unroll
-      for (int t = 0; t < T; ++t) score[(size_t)(b * T + t) * Lmax + tok] = PAGED ? res[t] * kr.sc : res[t];
+      for (int t = 0; t < T; ++t) score[(size_t)(b * Ttot + t0 + t) * Lmax + tok] = PAGED ? res[t] * kr.sc : res[t];
     }
   };
 
@@ -202,6 +205,7 @@ struct IdxArgs {
   int Lmax, Hi, chunk;
   const int32_t* block_table; int n_pages;
   hipEvent_t ev_start, ev_stop;             // optional: take the kernel's own start and end times
+  int Ttot, t0;                             // tokens per sequence in q / w / score, first token of this launch
 };
 
 template <int HB, int DI, int T, bool PAGED>
@@ -209,10 +213,10 @@ void launch_k(dim3 grid, hipStream_t st, const IdxArgs& a) {
   const dim3 block(kWaves * 64);
   if (a.ev_start || a.ev_stop)      // timed launch: the events take the kernel's own start and end
     hipExtLaunchKernelGGL((k_index_score<HB, DI, T, PAGED>), grid, block, 0, st, a.ev_start, a.ev_stop, 0, a.q, a.w, a.key,
-                          a.ctx_len, a.score, a.Lmax, a.Hi, a.chunk, a.block_table, a.n_pages);
+                          a.ctx_len, a.score, a.Lmax, a.Hi, a.chunk, a.block_table, a.n_pages, a.Ttot, a.t0);
   else
     hipLaunchKernelGGL((k_index_score<HB, DI, T, PAGED>), grid, block, 0, st, a.q, a.w, a.key, a.ctx_len, a.score, a.Lmax,
-                       a.Hi, a.chunk, a.block_table, a.n_pages);
+                       a.Hi, a.chunk, a.block_table, a.n_pages, a.Ttot, a.t0);
 }
 
 template <int HB, int DI, int T>
@@ -248,12 +252,17 @@ int ess_launch_index_score(const ess_config& c, const uint8_t* q, const float* w
   // that still leaves several workgroups per CU, else 1024
   const int chunk = ((long)B * Lmax >= 2048L * 1024) ? 2048 : 1024;
   dim3 grid((Lmax + chunk - 1) / chunk, B);
-  const IdxArgs a{q, w, key, ctx_len, score, Lmax, Hi, chunk, block_table, n_pages, ev_start, ev_stop};
-  switch (Di) {
-    case 32: launch_hb<32>(HB, T, grid, st, a); break;
-    case 64: launch_hb<64>(HB, T, grid, st, a); break;
-    case 128: launch_hb<128>(HB, T, grid, st, a); break;
-    default: return ess_fail(ESS_ERR_UNSUPPORTED, "idx_dim %d (supported: 32, 64, 128)", Di);
+  // two query tokens per launch; the events of a timed call bracket the whole series
+  for (int t0 = 0; t0 < T; t0 += 2) {
+    const int Tl = T - t0 < 2 ? T - t0 : 2;
+    const IdxArgs a{q, w, key, ctx_len, score, Lmax, Hi, chunk, block_table, n_pages,
+                    t0 == 0 ? ev_start : nullptr, t0 + 2 >= T ? ev_stop : nullptr, T, t0};
+    switch (Di) {
+      case 32: launch_hb<32>(HB, Tl, grid, st, a); break;
+      case 64: launch_hb<64>(HB, Tl, grid, st, a); break;
+      case 128: launch_hb<128>(HB, Tl, grid, st, a); break;
+      default: return ess_fail(ESS_ERR_UNSUPPORTED, "idx_dim %d (supported: 32, 64, 128)", Di);
+    }
   }
   ESS_HIP(hipGetLastError());
   return ESS_OK;

@@ -48,7 +48,7 @@ def test_config_validation_reports_errors(lib):
     assert n > 64 * 131072 * 4
     cases = [
         (dict(idx_dim=96), b.ESS_ERR_UNSUPPORTED),
-        (dict(max_q_tokens=3), b.ESS_ERR_UNSUPPORTED),
+        (dict(max_q_tokens=5), b.ESS_ERR_UNSUPPORTED),
         (dict(slots_per_seq=1000), b.ESS_ERR_CAPACITY),
         (dict(row_stride=1150), b.ESS_ERR_INVALID_ARG),
         (dict(max_ctx=1 << 20), b.ESS_ERR_INVALID_ARG),

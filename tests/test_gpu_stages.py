@@ -47,6 +47,8 @@ def _check_attn(out_gpu, lse_gpu, out_ref, lse_ref):
     ("mtp2", 2, 2, 64, 128, 3000, 8, 8, 16, [3000, 2051]),
     ("heads40_d64", 2, 1, 40, 64, 777, 8, 8, 16, [777, 300]),
     ("tiny", 1, 2, 4, 32, 40, 4, 4, 8, [17]),
+    ("mtp3", 2, 3, 64, 128, 3000, 8, 8, 16, [3000, 2051]),          # two launches: tokens 0-1, then token 2
+    ("mtp4_heads40", 2, 4, 40, 64, 777, 8, 8, 16, [777, 300]),
 ])
 def test_index_score_bit_exact(ess_lib, name, B, T, Hi, Di, Lmax, qk, wl, wd, lens):
     print("index_score", name, flush=True)
@@ -343,6 +345,48 @@ def test_decode_step_offloaded_vs_oracle(ess_lib, flags, fmt):
         if (0, fmt) in res and (other, fmt) in res:
             for (o0, l0), (o1, l1) in zip(res[(0, fmt)], res[(other, fmt)]):
                 assert torch.equal(o0, o1) and torch.equal(l0, l1)
+
+
+@pytest.mark.parametrize("T,k,L,S,fmt,flags", [(3, 512, 6000, 1800, 0, 0), (4, 2048, 12000, 8500, 1, 2)])
+def test_decode_step_three_and_four_query_tokens(ess_lib, T, k, L, S, fmt, flags):
+    """More than two query tokens per sequence (the index score then takes two passes over the keys);
+    T = 4 with k = 2048 is the largest selection a sequence can have (8192 entries)."""
+    from paper_2512_10576_amd import binding as bnd
+    print("decode_step T", T, "k", k, "fmt", fmt, "flags", flags, flush=True)
+    B, Hi, Di, H = 2, 64, 128, 128
+    stride = 1152 if fmt == 0 else 656
+    qi, w, key = synth.indexer_inputs(71, B, T, Hi, Di, L, 8, 8, 16)
+    ctx_len = torch.tensor([L, L - 1234], dtype=torch.int32)
+    host = (synth.latent_rows_bf16(71, B * L) if fmt == 0 else synth.latent_rows_fp8(71, B * L)).reshape(B, L, stride)
+    hp = torch.empty((B, L, stride), dtype=torch.uint8, pin_memory=True)
+    hp.copy_(host)
+    ctx = _ctx(ess_lib, max_batch=B, max_q_tokens=T, max_ctx=L, idx_heads=Hi, idx_dim=Di, topk=k, attn_heads=H,
+               slots_per_seq=S, flags=flags, latent_fmt=fmt)
+    cache = bnd.Cache.allocate(ctx.cfg, B, host_pool=hp)
+    ctx.cache_reset(cache, B)
+    oc = O.SlotCache(B, L, S)
+    opool = np.zeros((B, S, stride), np.uint8)
+    trace = synth.TopkTrace(19, ctx_len, T, k, 0.7)
+    idx_out = torch.empty((B, T, k), dtype=torch.int32, device="cuda")
+    out = torch.empty((B, T, H, 512), dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty((B, T, H), dtype=torch.float32, device="cuda")
+    mc = torch.empty((B,), dtype=torch.int32, device="cuda")
+    dev = [x.cuda() for x in (qi, w, key, ctx_len)]
+    for step in range(1, 4):
+        q = synth.attn_query(90 + step, B, T, H)
+        ov = trace.next() if step != 2 else None                     # step 2 uses the real top-k
+        r = O.decode_step(qi.numpy(), w.numpy(), key.numpy(), ctx_len.numpy(), k, oc, opool, host.numpy(),
+                          _qbits(q), fmt, 576 ** -0.5, step, None if ov is None else ov.numpy())
+        ctx.decode_step(cache, dev[0], dev[1], dev[2], dev[3], q.cuda(), step, idx_out, out, lse, mc,
+                        None if ov is None else ov.cuda())
+        torch.cuda.synchronize()
+        _topk_sets_equal(idx_out.cpu().numpy(), r["idx"])
+        assert np.array_equal(mc.cpu().numpy(), r["miss_count"])
+        assert np.array_equal(cache.slot_of.cpu().numpy(), oc.slot_of)
+        occ = oc.token_of >= 0
+        assert np.array_equal(cache.slot_pool.cpu().numpy()[occ], opool[occ])
+        _check_attn(out, lse, r["out"], r["lse"])
+    ctx.close()
 
 
 def test_decode_step_resident_cfg1(ess_lib):
