@@ -147,16 +147,22 @@ __global__ __launch_bounds__(kWaves * 64, T == 2 ? 2 : 1) void k_index_score(con
     for (int u = 0; u < kTilesPerBatch; ++u) {
 #pragma unroll
       for (int t = 0; t < T; ++t) {
+        // the HB head blocks are independent accumulation chains: stepping through them inside the
+        // contraction loop keeps dependent MFMAs HB instructions apart (head block outermost, the
+        // compiler issued each chain back to back and every MFMA waited for the one before)
         float s = 0.f;
+        floatx4 acc[HB];
 #pragma unroll
-        for (int mb = 0; mb < HB; ++mb) {
-          floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+        for (int mb = 0; mb < HB; ++mb) acc[mb] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-          for (int kk = 0; kk < KS; ++kk)
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(qa[t][mb][kk], kr.k[u].v[kk], acc, 0, 0, 0);
+        for (int kk = 0; kk < KS; ++kk)
 #pragma unroll
-          for (int i = 0; i < 4; ++i) s = fmaf(wr[t][mb][i], fmaxf(acc[i], 0.f), s);
-        }
+          for (int mb = 0; mb < HB; ++mb)
+            acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(qa[t][mb][kk], kr.k[u].v[kk], acc[mb], 0, 0, 0);
+#pragma unroll
+        for (int mb = 0; mb < HB; ++mb)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) s = fmaf(wr[t][mb][i], fmaxf(acc[mb][i], 0.f), s);
         s += __shfl_xor(s, 16, 64);
         s += __shfl_xor(s, 32, 64);
         res[t] = (g == u) ? s : res[t];                       // lane (g,n) keeps tile g's token n
