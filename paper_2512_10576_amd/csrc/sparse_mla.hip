@@ -541,7 +541,6 @@ int ess_launch_attn_partial(ess_ctx* ctx, const void* q, const uint8_t* slot_poo
   // partial results of sequence b0 onward
   float* op = ctx->o_part + (size_t)b0 * T * ESS_MAX_SPLITS * c.attn_heads * ESS_LATENT_DIM;
   float* lp = ctx->lse_part + (size_t)b0 * T * ESS_MAX_SPLITS * c.attn_heads;
-  int rc;
   if (c.latent_fmt == ESS_FMT_BF16) {
     constexpr int lds = tr_lds_bytes(ESS_FMT_BF16);
     ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_partial_tr<ESS_FMT_BF16>),
@@ -555,8 +554,6 @@ int ess_launch_attn_partial(ess_ctx* ctx, const void* q, const uint8_t* slot_poo
     hipLaunchKernelGGL(k_attn_partial_tr<ESS_FMT_FP8>, grid, dim3(NTH), lds, st, qq, slot_pool, list, n_list, T,
                        c.attn_heads, c.topk, c.slots_per_seq, c.row_stride, sc, split0, nsplit, op, lp, ctx->zero_row);
   }
-  rc = ESS_OK;
-  if (rc != ESS_OK) return rc;
   ESS_HIP(hipGetLastError());
   return ESS_OK;
 }
