@@ -11,8 +11,12 @@
 
 #include "ess_internal.h"
 
+// Workgroups that Attn0 of the whole batch aims at when entries are offloaded.  In the split-batch
+// schedule Attn0 of both halves sits behind the first fetch on the side stream and has to be done when
+// the second fetch ends: twice the chip (two launches of 256 workgroups at batch 64) measured best
+// there (128: +1.4 % step time, 1024: +3 %); the single-fetch schedule is indifferent (+-0.5 %).
 #ifndef ESS_ATTN0_WGS
-#define ESS_ATTN0_WGS 128
+#define ESS_ATTN0_WGS 512
 #endif
 
 namespace {
@@ -386,7 +390,7 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     ptag = ctx->prof_tag + (size_t)pslot * ESS_PROF_MAIN;
     ctx->prof_nmark[pslot] = 0;
     ctx->prof_nfill[pslot] = 0;
-    ctx->prof_pair_stage[pslot] = 5;
+    for (int f = 0; f < ESS_PROF_FILL; ++f) ctx->prof_pair_stage[(size_t)pslot * ESS_PROF_FILL + f] = 5;
   }
   // ESS_BEGIN(tag) / ESS_END(tag) bracket the launches of one stage; only selected stages are timed
   bool adjacent = false;                        // the last recorded mark sits right before this point
@@ -426,9 +430,8 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
   const size_t k = (size_t)c.topk;
   bool pending[2] = {false, false};
 
-  // attention splits: the same for both halves, one merge over the whole batch at the end
-  // from the whole batch, so that every mode sums in the same order; beside a fetch Attn0 is kept to
-  // half the chip: it has the whole fetch time to finish, and a chip-wide gather slows the fetch down
+  // attention splits: chosen from the whole batch and the same for both halves, so that every schedule
+  // sums in the same order and gives the same bits
   const int ns0 = pick_splits(c, B, T, 16, offloaded ? ESS_ATTN0_WGS : 256);
   int ns1 = 0;
   if (offloaded) {
@@ -476,15 +479,15 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     const ess_cache ch = shift_cache(c, *cache, b0);
     hipEvent_t* fev = (pev && h < ESS_PROF_FILL && ((ctx->prof_mask >> 5) & 1u)) ? pev + ESS_PROF_MAIN + 2 * h : nullptr;
     ESS_BEGIN(2);
-    if (da_swap) {      // bookkeeping only; the fetch follows on this stream further down
+    if (da_swap || (dba && h == 1)) {      // bookkeeping only; the fetch follows on this stream further down
       rc = ess_launch_bookkeeping(ctx, ch, used, Bh, T, c.topk, a->step, ctx->slot_idx_ws + bt0 * k,
-                                  a->miss_count ? a->miss_count + b0 : nullptr, st, b0, true);
+                                  a->miss_count ? a->miss_count + b0 : nullptr, st, b0, h == 0);
       if (rc != ESS_OK) return rc;
     } else {
       rc = run_cache_step(ctx, ch, used, Bh, T, c.topk, a->step, ctx->slot_idx_ws + bt0 * k,
                           a->miss_count ? a->miss_count + b0 : nullptr, st, &pending[h], b0, h, fev, dba ? 28 : 64);
       if (rc != ESS_OK) return rc;
-      if (fev) { ctx->prof_nfill[pslot] = h + 1; ctx->prof_pair_stage[pslot] = 5; }
+      if (fev) { ctx->prof_nfill[pslot] = h + 1; ctx->prof_pair_stage[(size_t)pslot * ESS_PROF_FILL + h] = 5; }
     }
     ESS_END(2);
   }
@@ -519,7 +522,7 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     if (aev) {
       ESS_HIP(hipEventRecord(aev[1], ctx->side));
       ctx->prof_nfill[pslot] = 1;
-      ctx->prof_pair_stage[pslot] = 3;
+      ctx->prof_pair_stage[(size_t)pslot * ESS_PROF_FILL] = 3;
     }
     ESS_HIP(hipEventRecord(ctx->ev_fill[0], ctx->side));          // here: Attn0 done
     ESS_BEGIN(5);
@@ -530,6 +533,53 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     ESS_HIP(hipStreamWaitEvent(st, ctx->ev_fill[0], 0));
     rc = ess_launch_attn_partial(ctx, q16, cache->slot_pool, ctx->miss_list, ctx->n_miss, B, T, ns0, ns1, st, 0);
     if (rc != ESS_OK) return rc;
+    rc = ess_launch_attn_merge(ctx, B, T, ns0 + ns1, a->out_bf16, a->lse, st);
+    if (rc != ESS_OK) return rc;
+    ESS_END(4);
+    return ESS_OK;
+  }
+
+  if (dba) {
+    // DBA schedule.  Two chains are critical: the two fetches, and the second half's index score, top-k
+    // and bookkeeping, which the second fetch waits for.  A wait on another stream's event costs several
+    // microseconds when the event fires late, so the second fetch follows its bookkeeping on the caller's
+    // stream (it may start while the first fetch is still finishing: the link just stays busy), and what
+    // has time to spare goes to the side stream behind the first fetch: Attn0 of both halves and Attn1 of
+    // the first half.  The caller's stream ends with Attn1 of the second half and the merge.
+    const ess_cache c0 = shift_cache(c, *cache, hb0[0]), c1 = shift_cache(c, *cache, hb0[1]);
+    const size_t bt1 = (size_t)hb0[1] * T;
+    ESS_HIP(hipEventRecord(ctx->ev_book[1], st));                    // second half's bookkeeping done
+    ESS_BEGIN(5);
+    rc = ess_launch_fill(ctx, c1, hB[1], st, hb0[1], 28);
+    if (rc != ESS_OK) return rc;
+    ESS_END(5);
+    // side-stream attention is timed by event pairs 1 and 2 (pair 0 brackets the first fetch): all three or none
+    hipEvent_t* aev = (pev && ctx->prof_nfill[pslot] == 1 && ((ctx->prof_mask >> 3) & 1u)) ? pev + ESS_PROF_MAIN + 2 : nullptr;
+    if (aev) ESS_HIP(hipEventRecord(aev[0], ctx->side));
+    rc = ess_launch_attn_partial(ctx, q16, c0.slot_pool, ctx->hit_list, ctx->n_hit, hB[0], T, 0, ns0, ctx->side, hb0[0]);
+    if (rc != ESS_OK) return rc;
+    ESS_HIP(hipStreamWaitEvent(ctx->side, ctx->ev_book[1], 0));
+    rc = ess_launch_attn_partial(ctx, q16 + bt1 * c.attn_heads * ESS_ROW_DIM, c1.slot_pool, ctx->hit_list + bt1 * k,
+                                 ctx->n_hit + bt1, hB[1], T, 0, ns0, ctx->side, hb0[1]);
+    if (rc != ESS_OK) return rc;
+    if (aev) {
+      ESS_HIP(hipEventRecord(aev[1], ctx->side));
+      ESS_HIP(hipEventRecord(aev[2], ctx->side));
+    }
+    rc = ess_launch_attn_partial(ctx, q16, c0.slot_pool, ctx->miss_list, ctx->n_miss, hB[0], T, ns0, ns1, ctx->side, hb0[0]);
+    if (rc != ESS_OK) return rc;
+    if (aev) {
+      ESS_HIP(hipEventRecord(aev[3], ctx->side));
+      ctx->prof_nfill[pslot] = 3;
+      ctx->prof_pair_stage[(size_t)pslot * ESS_PROF_FILL + 1] = 3;
+      ctx->prof_pair_stage[(size_t)pslot * ESS_PROF_FILL + 2] = 4;
+    }
+    ESS_HIP(hipEventRecord(ctx->ev_fill[1], ctx->side));           // here: everything on the side stream done
+    ESS_BEGIN(4);
+    rc = ess_launch_attn_partial(ctx, q16 + bt1 * c.attn_heads * ESS_ROW_DIM, c1.slot_pool, ctx->miss_list + bt1 * k,
+                                 ctx->n_miss + bt1, hB[1], T, ns0, ns1, st, hb0[1]);
+    if (rc != ESS_OK) return rc;
+    ESS_HIP(hipStreamWaitEvent(st, ctx->ev_fill[1], 0));
     rc = ess_launch_attn_merge(ctx, B, T, ns0 + ns1, a->out_bf16, a->lse, st);
     if (rc != ESS_OK) return rc;
     ESS_END(4);
@@ -645,7 +695,7 @@ int ess_profile_enable(ess_ctx* ctx, int32_t max_steps) {
   ctx->prof_tag = new (std::nothrow) int8_t[(size_t)max_steps * ESS_PROF_MAIN];
   ctx->prof_nmark = new (std::nothrow) int[max_steps]();
   ctx->prof_nfill = new (std::nothrow) int[max_steps]();
-  ctx->prof_pair_stage = new (std::nothrow) int[max_steps]();
+  ctx->prof_pair_stage = new (std::nothrow) int[(size_t)max_steps * ESS_PROF_FILL]();
   if (!ctx->prof_ev || !ctx->prof_tag || !ctx->prof_nmark || !ctx->prof_nfill || !ctx->prof_pair_stage) {
     delete[] ctx->prof_ev; delete[] ctx->prof_tag; delete[] ctx->prof_nmark; delete[] ctx->prof_nfill;
     delete[] ctx->prof_pair_stage;
@@ -685,7 +735,7 @@ int ess_profile_read(ess_ctx* ctx, float* host_ms, int32_t* n_steps) {
       float ms = 0.f;
       ESS_HIP(hipEventSynchronize(ev[ESS_PROF_MAIN + 2 * f + 1]));
       ESS_HIP(hipEventElapsedTime(&ms, ev[ESS_PROF_MAIN + 2 * f], ev[ESS_PROF_MAIN + 2 * f + 1]));
-      out[ctx->prof_pair_stage[s]] += ms;
+      out[ctx->prof_pair_stage[(size_t)s * ESS_PROF_FILL + f]] += ms;
     }
   }
   ctx->prof_n = 0;

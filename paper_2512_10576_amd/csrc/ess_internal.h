@@ -13,7 +13,7 @@
 #define ESS_ZERO_ROW_BYTES 2048  // >= the largest row_stride
 #define ESS_TOPK_SHARED_ROWS 128 // rows (b,t) up to which a top-k row is shared by several workgroups
 #define ESS_PROF_MAIN 16        // stage marks on the caller's stream per step
-#define ESS_PROF_FILL 2         // fetch kernels per step (one per batch half)
+#define ESS_PROF_FILL 3         // event pairs per step for work off the caller's stream (fetches, side-stream attention)
 #define ESS_PROF_EVENTS (ESS_PROF_MAIN + 2 * ESS_PROF_FILL)
 
 struct ess_ctx {
@@ -49,7 +49,7 @@ struct ess_ctx {
   int8_t* prof_tag;             // [prof_cap][ESS_PROF_MAIN] stage a mark closes (-1 = start)
   int* prof_nmark;              // [prof_cap] marks recorded
   int* prof_nfill;              // [prof_cap] event pairs recorded off the caller's stream
-  int* prof_pair_stage;         // [prof_cap] stage those pairs time: 5 fetch, or 3 Attn0 when that runs on the side stream
+  int* prof_pair_stage;         // [prof_cap][ESS_PROF_FILL] stage each pair times (5 fetch, 3 Attn0, 4 Attn1)
   int prof_cap, prof_n;
   uint32_t prof_mask;           // stages that are timed (bit i = stage i of ess_profile_read)
   int prof_every, prof_calls;   // every prof_every-th ess_decode_step is timed
