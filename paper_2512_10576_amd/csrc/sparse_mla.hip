@@ -478,7 +478,7 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
 
 // out[bt,h,:] = sum_s exp(lse_s - lse) * o_s ;  lse = log sum_s exp(lse_s).  One wave per (bt,h).
 // The partial results of four splits are requested before any is used (the kernel is a chain of
-// dependent loads otherwise).  `zero_cnt` (may be NULL): n_zero counters the first workgroup clears,
+// dependent loads otherwise); those of empty splits are not read at all.  `zero_cnt` (may be NULL): n_zero counters the first workgroup clears,
 // for steps that have no other kernel to do it in.
 __global__ __launch_bounds__(256) void k_attn_merge(const float* __restrict__ o_part, const float* __restrict__ lse_part,
                                                     int H, int nsplit, int total_rows, uint16_t* __restrict__ out,
@@ -491,26 +491,35 @@ __global__ __launch_bounds__(256) void k_attn_merge(const float* __restrict__ o_
   const int lane = threadIdx.x & 63;
   const int bt = rowi / H, h = rowi % H;
   const size_t base = ((size_t)bt * ESS_MAX_SPLITS) * H + h;
+  // the split weights first (one small load each, kept in registers), then only the partial results
+  // of splits that hold something: a miss list usually fills one of its splits and leaves the rest empty
+  float lsv[ESS_MAX_SPLITS];
   float mx = -__builtin_inff();
-  for (int s = 0; s < nsplit; ++s) mx = fmaxf(mx, lse_part[base + (size_t)s * H]);
+#pragma unroll
+  for (int s = 0; s < ESS_MAX_SPLITS; ++s) {
+    lsv[s] = s < nsplit ? lse_part[base + (size_t)s * H] : -__builtin_inff();
+    mx = fmaxf(mx, lsv[s]);
+  }
   float den = 0.f;
   float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   if (mx > -__builtin_inff()) {
-    for (int s0 = 0; s0 < nsplit; s0 += 4) {
-      float ls[4];
+#pragma unroll
+    for (int s0 = 0; s0 < ESS_MAX_SPLITS; s0 += 4) {
+      if (s0 >= nsplit) break;
       float4 x[4], y[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        const int s = min(s0 + u, nsplit - 1);                // clamped copies get weight 0 below
-        ls[u] = lse_part[base + (size_t)s * H];
-        const float4* op = reinterpret_cast<const float4*>(o_part + (base + (size_t)s * H) * ESS_LATENT_DIM + lane * 8);
-        x[u] = op[0];
-        y[u] = op[1];
+        x[u] = y[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (lsv[s0 + u] != -__builtin_inff()) {                 // same for the whole wave: one row per wave
+          const float4* op = reinterpret_cast<const float4*>(o_part + (base + (size_t)(s0 + u) * H) * ESS_LATENT_DIM + lane * 8);
+          x[u] = op[0];
+          y[u] = op[1];
+        }
       }
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        if (s0 + u >= nsplit || ls[u] == -__builtin_inff()) continue;   // an empty split's partial result is not read as data
-        const float wgt = __expf(ls[u] - mx);
+        if (lsv[s0 + u] == -__builtin_inff()) continue;
+        const float wgt = __expf(lsv[s0 + u] - mx);
         den += wgt;
         a[0] += wgt * x[u].x; a[1] += wgt * x[u].y; a[2] += wgt * x[u].z; a[3] += wgt * x[u].w;
         a[4] += wgt * y[u].x; a[5] += wgt * y[u].y; a[6] += wgt * y[u].z; a[7] += wgt * y[u].w;
