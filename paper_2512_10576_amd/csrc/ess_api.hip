@@ -11,12 +11,10 @@
 
 #include "ess_internal.h"
 
-// Workgroups that Attn0 of the whole batch aims at when entries are offloaded.  In the split-batch
-// schedule Attn0 of both halves sits behind the first fetch on the side stream and has to be done when
-// the second fetch ends: twice the chip (two launches of 256 workgroups at batch 64) measured best
-// there (128: +1.4 % step time, 1024: +3 %); the single-fetch schedule is indifferent (+-0.5 %).
+// Workgroups that Attn0 of the whole batch aims at when entries are offloaded: one per CU (with
+// twice as many the schedules with few misses, where Attn0 is most of the attention, lose 4-5 %).
 #ifndef ESS_ATTN0_WGS
-#define ESS_ATTN0_WGS 512
+#define ESS_ATTN0_WGS 256
 #endif
 
 namespace {
@@ -544,8 +542,8 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     // and bookkeeping, which the second fetch waits for.  A wait on another stream's event costs several
     // microseconds when the event fires late, so the second fetch follows its bookkeeping on the caller's
     // stream (it may start while the first fetch is still finishing: the link just stays busy), and what
-    // has time to spare goes to the side stream behind the first fetch: Attn0 of both halves and Attn1 of
-    // the first half.  The caller's stream ends with Attn1 of the second half and the merge.
+    // has time to spare goes to the side stream behind the first fetch: Attn0 of the whole batch and Attn1
+    // of the first half.  The caller's stream ends with Attn1 of the second half and the merge.
     const ess_cache c0 = shift_cache(c, *cache, hb0[0]), c1 = shift_cache(c, *cache, hb0[1]);
     const size_t bt1 = (size_t)hb0[1] * T;
     ESS_HIP(hipEventRecord(ctx->ev_book[1], st));                    // second half's bookkeeping done
@@ -555,12 +553,11 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     ESS_END(5);
     // side-stream attention is timed by event pairs 1 and 2 (pair 0 brackets the first fetch): all three or none
     hipEvent_t* aev = (pev && ctx->prof_nfill[pslot] == 1 && ((ctx->prof_mask >> 3) & 1u)) ? pev + ESS_PROF_MAIN + 2 : nullptr;
-    if (aev) ESS_HIP(hipEventRecord(aev[0], ctx->side));
-    rc = ess_launch_attn_partial(ctx, q16, c0.slot_pool, ctx->hit_list, ctx->n_hit, hB[0], T, 0, ns0, ctx->side, hb0[0]);
-    if (rc != ESS_OK) return rc;
     ESS_HIP(hipStreamWaitEvent(ctx->side, ctx->ev_book[1], 0));
-    rc = ess_launch_attn_partial(ctx, q16 + bt1 * c.attn_heads * ESS_ROW_DIM, c1.slot_pool, ctx->hit_list + bt1 * k,
-                                 ctx->n_hit + bt1, hB[1], T, 0, ns0, ctx->side, hb0[1]);
+    if (aev) ESS_HIP(hipEventRecord(aev[0], ctx->side));
+    // Attn0 of the whole batch in one launch (behind the first fetch it could not start much earlier
+    // anyway): one workgroup per CU, the same splits as in the other schedules
+    rc = ess_launch_attn_partial(ctx, q16, cache->slot_pool, ctx->hit_list, ctx->n_hit, B, T, 0, ns0, ctx->side, 0);
     if (rc != ESS_OK) return rc;
     if (aev) {
       ESS_HIP(hipEventRecord(aev[1], ctx->side));
