@@ -243,7 +243,8 @@ int ess_create(const ess_config* cfg, ess_ctx** out) {
   memset(ctx->host_miss, 0, (size_t)cfg->max_batch * sizeof(int32_t));
   if ((e = hipHostGetDevicePointer(reinterpret_cast<void**>(&ctx->host_miss_dev), ctx->host_miss, 0)) != hipSuccess)
     return bail("hipHostGetDevicePointer", e);
-  ctx->auto_threshold = 250;
+  ctx->auto_threshold = 100;
+  ctx->auto_calibrated = false;
   *out = ctx;
   return ESS_OK;
 }
@@ -417,7 +418,10 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     const volatile int32_t* hm = ctx->host_miss;
     long sum = 0;
     for (int b = 0; b < B; ++b) sum += hm[b];
-    want_dba = sum > (long)ctx->auto_threshold * B;
+    // the split pays by hiding half the batch's index score behind a fetch: it must be long enough to be
+    // worth two rounds of top-k and bookkeeping (at 32K context and batch 64 it is not, whatever the misses)
+    const double idx_half_us = 0.5 * B * (double)c.max_ctx * (c.idx_dim + 4.0 * T) / 5.3e6;   // at 5.3 TB/s
+    want_dba = sum > (long)ctx->auto_threshold * B && (ctx->auto_calibrated || idx_half_us >= 50.0);
   }
   const bool dba = offloaded && want_dba && !(c.flags & ESS_FLAG_SERIAL) && B >= 2;
   ctx->last_overlap = (c.flags & ESS_FLAG_SERIAL) ? 2 : (dba ? 1 : 0);
@@ -641,6 +645,7 @@ int ess_set_overlap_threshold(ess_ctx* ctx, int32_t misses_per_seq) {
   if (!ctx) return ess_fail(ESS_ERR_INVALID_ARG, "context is NULL");
   if (misses_per_seq < 0) return ess_fail(ESS_ERR_INVALID_ARG, "threshold %d", misses_per_seq);
   ctx->auto_threshold = misses_per_seq;
+  ctx->auto_calibrated = true;        // the caller's threshold is taken as measured for its workload: it applies alone
   return ESS_OK;
 }
 

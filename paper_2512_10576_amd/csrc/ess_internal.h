@@ -43,6 +43,7 @@ struct ess_ctx {
   int32_t* host_miss;           // [max_batch] host address
   int32_t* host_miss_dev;       // device alias of the same memory
   int32_t auto_threshold;       // mean misses per sequence above which the split-batch schedule is used
+  bool auto_calibrated;         // threshold set by the caller: no further condition on the index-score time
   int32_t last_overlap;         // schedule of the latest ess_decode_step: 0 DA, 1 DBA, 2 serial
   // optional stage timing (ess_profile_enable)
   hipEvent_t* prof_ev;          // [prof_cap][ESS_PROF_EVENTS]: marks on the caller's stream, then pairs around each fetch
