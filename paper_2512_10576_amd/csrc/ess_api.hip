@@ -569,6 +569,9 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     }
     rc = ess_launch_attn_partial(ctx, q16, c0.slot_pool, ctx->miss_list, ctx->n_miss, hB[0], T, ns0, ns1, ctx->side, hb0[0]);
     if (rc != ESS_OK) return rc;
+    // each half is merged on the stream its Attn1 ran on: only half a merge is left behind the last fetch
+    rc = ess_launch_attn_merge(ctx, hB[0], T, ns0 + ns1, a->out_bf16, a->lse, ctx->side, nullptr, 0, hb0[0]);
+    if (rc != ESS_OK) return rc;
     if (aev) {
       ESS_HIP(hipEventRecord(aev[3], ctx->side));
       ctx->prof_nfill[pslot] = 3;
@@ -580,8 +583,8 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     rc = ess_launch_attn_partial(ctx, q16 + bt1 * c.attn_heads * ESS_ROW_DIM, c1.slot_pool, ctx->miss_list + bt1 * k,
                                  ctx->n_miss + bt1, hB[1], T, ns0, ns1, st, hb0[1]);
     if (rc != ESS_OK) return rc;
-    ESS_HIP(hipStreamWaitEvent(st, ctx->ev_fill[1], 0));
-    rc = ess_launch_attn_merge(ctx, B, T, ns0 + ns1, a->out_bf16, a->lse, st);
+    ESS_HIP(hipStreamWaitEvent(st, ctx->ev_fill[1], 0));          // Attn0 of the second half ran on the side stream
+    rc = ess_launch_attn_merge(ctx, hB[1], T, ns0 + ns1, a->out_bf16, a->lse, st, nullptr, 0, hb0[1]);
     if (rc != ESS_OK) return rc;
     ESS_END(4);
     return ESS_OK;

@@ -96,6 +96,7 @@ int ess_launch_gather_rows(const ess_config& c, const uint8_t* slot_pool, const 
 int ess_launch_attn_partial(ess_ctx* ctx, const void* q, const uint8_t* slot_pool, const int32_t* list,
                             const int32_t* n_list, int B, int T, int split0, int nsplit, hipStream_t st, int b0 = 0);
 int ess_attn_min_splits(const ess_config& c);   // fewest splits a list of k entries may be cut into
-// zero_cnt (may be NULL): n_zero int32 counters that the merge kernel also clears
+// zero_cnt (may be NULL): n_zero int32 counters that the merge kernel also clears; b0 = first sequence of the
+// sub-batch of B sequences (out_bf16 and lse are the whole batch's arrays)
 int ess_launch_attn_merge(ess_ctx* ctx, int B, int T, int nsplit_total, void* out_bf16, float* lse,
-                          hipStream_t st, int32_t* zero_cnt = nullptr, int n_zero = 0);
+                          hipStream_t st, int32_t* zero_cnt = nullptr, int n_zero = 0, int b0 = 0);

@@ -568,10 +568,13 @@ int ess_launch_attn_partial(ess_ctx* ctx, const void* q, const uint8_t* slot_poo
 }
 
 int ess_launch_attn_merge(ess_ctx* ctx, int B, int T, int nsplit_total, void* out_bf16, float* lse, hipStream_t st,
-                          int32_t* zero_cnt, int n_zero) {
-  const int rows = B * T * ctx->cfg.attn_heads;
-  hipLaunchKernelGGL(k_attn_merge, dim3((rows + 3) / 4), dim3(256), 0, st, ctx->o_part, ctx->lse_part,
-                     ctx->cfg.attn_heads, nsplit_total, rows, static_cast<uint16_t*>(out_bf16), lse, zero_cnt, n_zero);
+                          int32_t* zero_cnt, int n_zero, int b0) {
+  const int H = ctx->cfg.attn_heads;
+  const int rows = B * T * H;
+  const size_t r0 = (size_t)b0 * T * H;                       // first (bt, h) row of the sub-batch
+  hipLaunchKernelGGL(k_attn_merge, dim3((rows + 3) / 4), dim3(256), 0, st, ctx->o_part + r0 * ESS_MAX_SPLITS * ESS_LATENT_DIM,
+                     ctx->lse_part + r0 * ESS_MAX_SPLITS, H, nsplit_total, rows,
+                     static_cast<uint16_t*>(out_bf16) + r0 * ESS_LATENT_DIM, lse ? lse + r0 : nullptr, zero_cnt, n_zero);
   ESS_HIP(hipGetLastError());
   return ESS_OK;
 }
