@@ -22,6 +22,7 @@
 #include <hip/hip_ext.h>
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef int intx8 __attribute__((ext_vector_type(8)));
 
 namespace {
 
@@ -154,11 +155,25 @@ __global__ __launch_bounds__(kWaves * 64, T == 2 ? 2 : 1) void k_index_score(con
         floatx4 acc[HB];
 #pragma unroll
         for (int mb = 0; mb < HB; ++mb) acc[mb] = floatx4{0.f, 0.f, 0.f, 0.f};
+        if constexpr (KS == 4) {
+          // 128-dimensional keys: one v_mfma_f32_16x16x128_f8f6f4 per head block (both formats e4m3, no
+          // block scales) in place of four 16x16x32 fp8 MFMAs -- a quarter of the instructions and, on
+          // gfx950, twice the rate.  A lane's 32 key bytes pair with its 32 query bytes as before.
+          const intx8 kv = __builtin_bit_cast(intx8, kr.k[u]);
 #pragma unroll
-        for (int kk = 0; kk < KS; ++kk)
+          for (int mb = 0; mb < HB; ++mb) {
+            KeyRegs<4> ql;
 #pragma unroll
-          for (int mb = 0; mb < HB; ++mb)
-            acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(qa[t][mb][kk], kr.k[u].v[kk], acc[mb], 0, 0, 0);
+            for (int kk = 0; kk < 4; ++kk) ql.v[kk] = qa[t][mb][kk];
+            acc[mb] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(__builtin_bit_cast(intx8, ql), kv, acc[mb], 0, 0, 0, 0, 0, 0);
+          }
+        } else {
+#pragma unroll
+          for (int kk = 0; kk < KS; ++kk)
+#pragma unroll
+            for (int mb = 0; mb < HB; ++mb)
+              acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(qa[t][mb][kk], kr.k[u].v[kk], acc[mb], 0, 0, 0);
+        }
 #pragma unroll
         for (int mb = 0; mb < HB; ++mb)
 #pragma unroll
