@@ -4,7 +4,8 @@
 //
 // The kernel is a key stream: every 128-byte key is read from HBM exactly
 // once (for all T query tokens), the q.k contraction runs on the fp8 matrix
-// cores (v_mfma_f32_16x16x32_fp8_fp8, heads = M, tokens = N, dim = K) and the
+// cores (v_mfma_f32_16x16x128_f8f6f4 for 128-dimensional keys, else
+// v_mfma_f32_16x16x32_fp8_fp8; heads = M, tokens = N, dim = K) and the
 // ReLU / head-weighted reduction stays in registers.
 //
 // Register layout.  A wave handles 16 tokens per MFMA tile.  Lane l = 16*g + n
