@@ -193,10 +193,12 @@ int ess_sparse_mla_decode(ess_ctx* ctx, const void* q_bf16, const uint8_t* slot_
                           const int32_t* slot_idx, int32_t B, int32_t T, void* out_bf16, float* lse,
                           void* stream);
 
-/* One layer-step: stages 1-5 chained on `stream`, the miss fetch on the side
- * stream overlapping Attn0 (Sec. 3.3, DA overlap), Attn1 after it, merged.  With
- * ESS_FLAG_DBA the fetch of the first half of the batch also overlaps the second
- * half's indexer and top-k (DBA overlap); results are identical in all modes. */
+/* One layer-step: stages 1-5 in order, with the miss fetch overlapping Attn0, the attention over the
+ * entries that were resident (Sec. 3.3, DA overlap), then Attn1 over the fetched ones, merged.  With
+ * ESS_FLAG_DBA the fetch of the first half of the batch also overlaps the second half's indexer,
+ * top-k and bookkeeping (DBA overlap).  Part of the work runs on the context's side stream; all of it
+ * is ordered after what was enqueued on `stream` before the call and before what is enqueued on it
+ * afterwards.  Results are identical, bit for bit, in all modes. */
 int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* args, void* stream);
 
 /* ESS_FLAG_AUTO: the DBA schedule is used for a step when the previous bookkeeping of this context
