@@ -110,13 +110,17 @@ int check_cache(const ess_ctx* ctx, const ess_cache* c) {
 
 // number of attention splits for a list of up to k entries: a workgroup is sized to own a CU, so aim at
 // a small multiple of the CU count; never fewer than the kernel's tiles-per-split limit allows
-int pick_splits(const ess_config& c, int B, int T, int cap, int target_wgs = 256) {
+// `long_lists`: the lists are about topk entries long (Attn0, resident attention); then no workgroup
+// gets more than 32 tiles: with several rounds of workgroups per CU, shorter ones overlap one's end
+// (the write of its partial result) with another's work (measured: 9 % at batch 128 x 2 tokens)
+int pick_splits(const ess_config& c, int B, int T, int cap, int target_wgs = 256, bool long_lists = true) {
   const int tiles = (c.topk + ESS_ATTN_TILE - 1) / ESS_ATTN_TILE;
   const int hgroups = (c.attn_heads + 63) / 64;
   int want = (target_wgs + B * T * hgroups - 1) / (B * T * hgroups);   // one workgroup per CU: fewer partial results to merge
   if (want > tiles) want = tiles;
   if (want > cap) want = cap;
-  const int lo = ess_attn_min_splits(c);
+  int lo = ess_attn_min_splits(c);
+  if (long_lists && lo < (tiles + 31) / 32) lo = (tiles + 31) / 32;
   if (want < lo) want = lo;
   return want < 1 ? 1 : want;
 }
@@ -437,10 +441,8 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
   const int ns0 = pick_splits(c, B, T, 16, offloaded ? ESS_ATTN0_WGS : 256);
   int ns1 = 0;
   if (offloaded) {
-    ns1 = ns0 / 4;
-    if (ns1 < ess_attn_min_splits(c)) ns1 = ess_attn_min_splits(c);
-    if (ns1 < 1) ns1 = 1;
-    if (ns1 > ESS_MAX_SPLITS - 16) ns1 = ESS_MAX_SPLITS - 16;
+    // Attn1 works on the short miss lists: as many splits as give the whole batch one workgroup per CU
+    ns1 = pick_splits(c, B, T, ESS_MAX_SPLITS - 16, 256, false);
   }
 
   // stages 1-2 (+ 3, 5 when offloaded) per half; the fetch goes to the side stream

@@ -31,7 +31,7 @@ constexpr int TILE = ESS_ATTN_TILE;            // 32 entries
 constexpr int NTH = 256;                       // four waves
 constexpr int KSTEPS = ESS_ROW_DIM / 32;       // 18
 constexpr int VBLOCKS = ESS_LATENT_DIM / 16;   // 32
-constexpr int MAX_TPS = 32;                    // tiles per split (the launcher picks nsplit accordingly)
+constexpr int MAX_TPS = 64;                    // tiles per split (the launcher picks nsplit accordingly): a list of 2048 entries fits one split
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -101,7 +101,7 @@ constexpr int TRP = 1024;                        // latent row pitch in LDS
 constexpr int TR_KL_BYTES = TILE * TRP;          // 32768
 constexpr int TR_RAW_BYTES = TR_KL_BYTES + RP_BYTES;
 constexpr int tr_nbuf(int fmt) { return fmt == ESS_FMT_BF16 ? 4 : 2; }
-constexpr int tr_lds_bytes(int fmt) { return tr_nbuf(fmt) * TR_RAW_BYTES + MAX_TPS * TILE * 4; }   // 151552 | 77824
+constexpr int tr_lds_bytes(int fmt) { return tr_nbuf(fmt) * TR_RAW_BYTES + MAX_TPS * TILE * 4; }   // 155648 | 81920
 constexpr float kLazyMax = 8.0f;
 
 #ifdef ESS_ATTN_PHASE_TIMING
