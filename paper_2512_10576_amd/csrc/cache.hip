@@ -90,11 +90,17 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
     int32_t* __restrict__ hit_list, int32_t* __restrict__ miss_list, int32_t* __restrict__ n_hit,
     int32_t* __restrict__ n_miss, int32_t* __restrict__ fill_tok, int32_t* __restrict__ fill_slot, int fill_cap,
     int32_t* __restrict__ miss_cnt, int32_t* __restrict__ miss_count_out, unsigned long long* __restrict__ stats,
-    int row_stride, int count_step, int32_t* __restrict__ host_miss) {
+    int row_stride, int count_step, int32_t* __restrict__ host_miss, ess_xcd xcd, int n_seq,
+    uint32_t* __restrict__ zero_tickets) {
   extern __shared__ uint32_t bm[];             // [W] bitmap of the missed positions
   __shared__ BookShared sm;
+  __shared__ int s_item;
   constexpr int RS = 16;                       // register-held stamps per thread
-  const int b = blockIdx.x;
+  // work counters of the kernels that follow this one beside the fetch it feeds: cleared here, by the first
+  // workgroup, so that no launch has to do it (this kernel itself never uses the counters it clears)
+  if (zero_tickets && blockIdx.x == 0 && threadIdx.x < ESS_N_TICKETS) zero_tickets[threadIdx.x] = 0;
+  const int b = ess_take_item(blockIdx.x, n_seq, xcd, &s_item);   // sequence: by workgroup index, or in arrival order
+  if (b < 0) return;
   const int tid = threadIdx.x, lane = tid & 63;
   const int W = (Lmax + 31) >> 5;
   const int nsel = T * kk;
@@ -311,7 +317,9 @@ __global__ __launch_bounds__(FILL_WPB * 64) void k_fill(const uint8_t* __restric
                                                const int32_t* __restrict__ fill_tok,
                                                const int32_t* __restrict__ fill_slot, int fill_cap,
                                                const int32_t* __restrict__ miss_cnt, int B, int Lmax, int S,
-                                               int row_stride) {
+                                               int row_stride, uint32_t only_xcds, uint32_t* __restrict__ ticket) {
+  // confined fetch: only workgroups on the XCDs in `only_xcds` work, entries are handed out through `ticket`
+  if (only_xcds && !((only_xcds >> ess_xcc_id()) & 1u)) return;
   extern __shared__ int32_t pref[];                          // [B + 1] pref[b] = entries of sequences < b (kept small:
                                                              // the kernel must fit beside workgroups that fill the LDS)
   const int tid = threadIdx.x, lane = tid & 63;
@@ -343,12 +351,22 @@ __global__ __launch_bounds__(FILL_WPB * 64) void k_fill(const uint8_t* __restric
     src = reinterpret_cast<const uint4*>(host_pool + ((size_t)lo * Lmax + tok) * row_stride);
     dst = reinterpret_cast<uint4*>(slot_pool + ((size_t)lo * S + slot) * row_stride);
   };
-  for (int r = gw; r < M; r += 2 * FILL_WAVES) {             // two entries of this wave in flight
-    const bool two = r + FILL_WAVES < M;
+  for (int r = gw;; r += 2 * FILL_WAVES) {                   // two entries of this wave in flight
+    int rB;
+    if (only_xcds) {                                         // entries r, r + 1 by ticket
+      uint32_t tk = 0;
+      if (lane == 0) tk = atomicAdd(ticket, 2u);
+      r = (int)__shfl(tk, 0, 64);
+      rB = r + 1;
+    } else {
+      rB = r + FILL_WAVES;
+    }
+    if (r >= M) break;
+    const bool two = rB < M;
     const uint4 *srcA, *srcB;
     uint4 *dstA, *dstB;
     locate(r, srcA, dstA);
-    locate(two ? r + FILL_WAVES : r, srcB, dstB);
+    locate(two ? rB : r, srcB, dstB);
     uint4 a0 = make_uint4(0, 0, 0, 0), a1 = a0, b0 = a0, b1 = a0;
     if (c0 < chunks) a0 = srcA[c0];
     if (c1 < chunks) a1 = srcA[c1];
@@ -505,6 +523,24 @@ int ess_launch_calib_copy(void* dst, const void* src, size_t bytes, hipStream_t 
   return ESS_OK;
 }
 
+// hist[x] += 1 for the XCD x this workgroup runs on
+__global__ void k_xcd_probe(uint32_t* hist) {
+  if (threadIdx.x == 0) atomicAdd(&hist[ess_xcc_id() & 7], 1u);
+}
+
+// Are 64 workgroups spread evenly over eight XCDs (8 each)?  Only then may a kernel count on finding
+// seven of any eight consecutive workgroups off one XCD.  `hist8`: eight zeroed counters, zero again on return.
+int ess_probe_xcds(uint32_t* hist8, bool* even) {
+  hipLaunchKernelGGL(k_xcd_probe, dim3(64), dim3(64), 0, 0, hist8);
+  ESS_HIP(hipGetLastError());
+  uint32_t h[8];
+  ESS_HIP(hipMemcpy(h, hist8, sizeof(h), hipMemcpyDeviceToHost));
+  ESS_HIP(hipMemset(hist8, 0, sizeof(h)));
+  *even = true;
+  for (int i = 0; i < 8; ++i) *even = *even && h[i] == 8u;
+  return ESS_OK;
+}
+
 int ess_launch_fill_u32(uint32_t* p, int n, uint32_t value, hipStream_t st) {
   hipLaunchKernelGGL(k_fill_u32, dim3((n + 255) / 256), dim3(256), 0, st, p, n, value);
   ESS_HIP(hipGetLastError());
@@ -521,7 +557,7 @@ int ess_launch_cache_reset(const ess_config& c, const ess_cache& cache, int B, h
 
 int ess_launch_bookkeeping(ess_ctx* ctx, const ess_cache& cache, const int32_t* idx, int B, int T, int kk,
                            uint32_t step, int32_t* slot_idx, int32_t* miss_count_out, hipStream_t st, int b0,
-                           bool count_step) {
+                           bool count_step, ess_xcd xcd, uint32_t* zero_tickets) {
   const ess_config& c = ctx->cfg;
   const size_t lds = (size_t)((c.max_ctx + 31) / 32) * sizeof(uint32_t);
   const bool lists = (kk == c.topk);           // compacted lists have the pitch of the top-k
@@ -530,23 +566,30 @@ int ess_launch_bookkeeping(ess_ctx* ctx, const ess_cache& cache, const int32_t* 
   const bool reg = c.slots_per_seq <= BT * 16;
   auto kern = reg ? &k_bookkeeping<true> : &k_bookkeeping<false>;
   ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-  hipLaunchKernelGGL(kern, dim3(B), dim3(BT), lds, st, idx, T, kk, c.max_ctx, c.slots_per_seq,
+  hipLaunchKernelGGL(kern, dim3(ess_xcd_grid(B, xcd)), dim3(BT), lds, st, idx, T, kk, c.max_ctx, c.slots_per_seq,
                      cache.slot_of, cache.token_of, cache.stamp, step, slot_idx,
                      lists ? ctx->hit_list + lo : nullptr, lists ? ctx->miss_list + lo : nullptr,
                      ctx->n_hit + (size_t)b0 * T, ctx->n_miss + (size_t)b0 * T, ctx->fill_tok + (size_t)b0 * cap,
                      ctx->fill_slot + (size_t)b0 * cap, cap, ctx->miss_cnt + b0, miss_count_out, ctx->stats,
-                     c.row_stride, count_step ? 1 : 0, (c.flags & ESS_FLAG_AUTO) ? ctx->host_miss_dev + b0 : nullptr);
+                     c.row_stride, count_step ? 1 : 0, (c.flags & ESS_FLAG_AUTO) ? ctx->host_miss_dev + b0 : nullptr, xcd, B,
+                     zero_tickets);
   ESS_HIP(hipGetLastError());
   return ESS_OK;
 }
 
-int ess_launch_fill(ess_ctx* ctx, const ess_cache& cache, int B, hipStream_t st, int b0, int wgs) {
+int ess_launch_fill(ess_ctx* ctx, const ess_cache& cache, int B, hipStream_t st, int b0, int wgs, uint32_t only_xcds,
+                    uint32_t* ticket) {
   wgs = wgs < 1 ? 1 : (wgs > 256 ? 256 : wgs);
+  if (only_xcds) {                             // `wgs` workgroups on the chosen XCDs: any 8 consecutive ones cover all XCDs
+    if (!ticket) return ess_fail(ESS_ERR_INVALID_ARG, "internal: confined fetch without a ticket");
+    const int on = __builtin_popcount(only_xcds & 0xffu);
+    wgs = (wgs + on - 1) / on * 8;
+  }
   const ess_config& c = ctx->cfg;
   const int cap = c.max_q_tokens * c.topk;
   hipLaunchKernelGGL(k_fill, dim3(wgs), dim3(FILL_WPB * 64), (size_t)(B + 1) * sizeof(int32_t), st, cache.host_pool_dev, cache.slot_pool,
                      ctx->fill_tok + (size_t)b0 * cap, ctx->fill_slot + (size_t)b0 * cap, cap, ctx->miss_cnt + b0, B,
-                     c.max_ctx, c.slots_per_seq, c.row_stride);
+                     c.max_ctx, c.slots_per_seq, c.row_stride, only_xcds, ticket);
   ESS_HIP(hipGetLastError());
   return ESS_OK;
 }

@@ -60,7 +60,7 @@ int validate_config(const ess_config* c) {
 }
 
 struct WsLayout {
-  size_t score, slot_idx, hit, miss, n_hit, n_miss, fill_tok, fill_slot, miss_cnt, o_part, lse_part, stats, zero_row, topk_cand, topk_cnt, total;
+  size_t score, slot_idx, hit, miss, n_hit, n_miss, fill_tok, fill_slot, miss_cnt, o_part, lse_part, stats, zero_row, topk_cand, topk_cnt, tickets, total;
 };
 
 size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -85,6 +85,7 @@ WsLayout ws_layout(const ess_config& c) {
   w.zero_row = take(ESS_ZERO_ROW_BYTES);
   w.topk_cand = take(ess_topk_cand_bytes());
   w.topk_cnt = take(ESS_TOPK_SHARED_ROWS * sizeof(uint32_t));
+  w.tickets = take(ESS_N_TICKETS * sizeof(uint32_t));
   w.total = off;
   return w;
 }
@@ -142,9 +143,12 @@ ess_cache shift_cache(const ess_config& c, const ess_cache& in, int b0) {
 // ev_fill[half] must still be waited for before the fetched rows are read.
 int run_cache_step(ess_ctx* ctx, const ess_cache& cache, const int32_t* idx, int B, int T, int kk, uint32_t step,
                    int32_t* slot_idx, int32_t* miss_count, hipStream_t st, bool* fill_pending, int b0 = 0,
-                   int half = 0, hipEvent_t* fill_ev = nullptr, int fill_wgs = 64) {
+                   int half = 0, hipEvent_t* fill_ev = nullptr, int fill_wgs = 64, bool confine = false) {
   *fill_pending = false;
-  int rc = ess_launch_bookkeeping(ctx, cache, idx, B, T, kk, step, slot_idx, miss_count, st, b0, half == 0);
+  // confine: the fetch runs on one XCD and the kernels beside it stay off that XCD, taking their work
+  // through counters that this bookkeeping clears (counter 0: the fetch itself)
+  int rc = ess_launch_bookkeeping(ctx, cache, idx, B, T, kk, step, slot_idx, miss_count, st, b0, half == 0,
+                                  ess_xcd{nullptr, 0}, confine ? ctx->tickets : nullptr);
   if (rc != ESS_OK) return rc;
   if (!cache.host_pool_dev) return ESS_OK;      // nothing offloaded: no entry can be missing
   if (ctx->cfg.flags & ESS_FLAG_SERIAL) {
@@ -156,7 +160,7 @@ int run_cache_step(ess_ctx* ctx, const ess_cache& cache, const int32_t* idx, int
   ESS_HIP(hipEventRecord(ctx->ev_book[half], st));
   ESS_HIP(hipStreamWaitEvent(ctx->side, ctx->ev_book[half], 0));
   if (fill_ev) ESS_HIP(hipEventRecord(fill_ev[0], ctx->side));
-  rc = ess_launch_fill(ctx, cache, B, ctx->side, b0, fill_wgs);
+  rc = ess_launch_fill(ctx, cache, B, ctx->side, b0, fill_wgs, confine ? ESS_FETCH_XCD_MASK : 0u, ctx->tickets);
   if (rc != ESS_OK) return rc;
   if (fill_ev) ESS_HIP(hipEventRecord(fill_ev[1], ctx->side));
   ESS_HIP(hipEventRecord(ctx->ev_fill[half], ctx->side));
@@ -223,6 +227,7 @@ int ess_create(const ess_config* cfg, ess_ctx** out) {
   ctx->zero_row = base + w.zero_row;
   ctx->topk_cand = reinterpret_cast<unsigned long long*>(base + w.topk_cand);
   ctx->topk_cnt = reinterpret_cast<uint32_t*>(base + w.topk_cnt);
+  ctx->tickets = reinterpret_cast<uint32_t*>(base + w.tickets);
   auto bail = [&](const char* what, hipError_t err) {
     for (int h = 0; h < 2; ++h) {
       if (ctx->ev_book[h]) (void)hipEventDestroy(ctx->ev_book[h]);
@@ -242,6 +247,9 @@ int ess_create(const ess_config* cfg, ess_ctx** out) {
   if ((e = hipMemset(ctx->stats, 0, 32)) != hipSuccess) return bail("hipMemset", e);
   if ((e = hipMemset(ctx->zero_row, 0, ESS_ZERO_ROW_BYTES)) != hipSuccess) return bail("hipMemset", e);
   if ((e = hipMemset(ctx->topk_cnt, 0, ESS_TOPK_SHARED_ROWS * sizeof(uint32_t))) != hipSuccess) return bail("hipMemset", e);
+  if ((e = hipMemset(ctx->tickets, 0, ESS_N_TICKETS * sizeof(uint32_t))) != hipSuccess) return bail("hipMemset", e);
+  ctx->xcds_even = false;
+  if (ess_probe_xcds(ctx->tickets, &ctx->xcds_even) != ESS_OK) return bail("XCD probe", hipGetLastError());
   if ((e = hipHostMalloc(reinterpret_cast<void**>(&ctx->host_miss), (size_t)cfg->max_batch * sizeof(int32_t),
                          hipHostMallocMapped)) != hipSuccess) return bail("hipHostMalloc", e);
   memset(ctx->host_miss, 0, (size_t)cfg->max_batch * sizeof(int32_t));
@@ -431,6 +439,8 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
   ctx->last_overlap = (c.flags & ESS_FLAG_SERIAL) ? 2 : (dba ? 1 : 0);
   const bool da_swap = offloaded && !dba && !(c.flags & ESS_FLAG_SERIAL);
   const int nh = dba ? 2 : 1;
+  // (one work counter serves one index-score launch: two query tokens at most)
+  const bool confine = dba && T <= 2 && ctx->xcds_even;
   const int hb0[2] = {0, B / 2};
   const int hB[2] = {dba ? B / 2 : B, B - B / 2};
   const size_t k = (size_t)c.topk;
@@ -465,17 +475,21 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     } else {
       adjacent = false;
     }
+    // second half of the split-batch schedule: these kernels run beside the first fetch, which is confined
+    // to one XCD; they stay off it (counters 1..4, cleared by the first half's bookkeeping)
+    const bool beside = confine && h == 1;
+    auto xcd_of = [&](int counter) { return beside ? ess_xcd{ctx->tickets + counter, ESS_FETCH_XCD_MASK} : ess_xcd{nullptr, 0}; };
     if (a->block_table)     // paged: one pool for the whole batch, the table rows of this sub-batch
       rc = ess_launch_index_score(c, a->q_idx_fp8 + bt0 * c.idx_heads * c.idx_dim, a->w + bt0 * c.idx_heads, a->key_fp8,
                                   a->ctx_len + b0, Bh, T, sc, st,
-                                  a->block_table + (size_t)b0 * (c.max_ctx / ESS_PAGE_TOKENS), a->n_pages, ev_s, ev_e);
+                                  a->block_table + (size_t)b0 * (c.max_ctx / ESS_PAGE_TOKENS), a->n_pages, ev_s, ev_e, xcd_of(1));
     else
       rc = ess_launch_index_score(c, a->q_idx_fp8 + bt0 * c.idx_heads * c.idx_dim, a->w + bt0 * c.idx_heads,
                                   a->key_fp8 + (size_t)b0 * c.max_ctx * c.idx_dim, a->ctx_len + b0, Bh, T, sc, st,
-                                  nullptr, 0, ev_s, ev_e);
+                                  nullptr, 0, ev_s, ev_e, xcd_of(1));
     if (rc != ESS_OK) return rc;
     ESS_BEGIN(1);
-    rc = ess_launch_topk(ctx, sc, a->ctx_len + b0, Bh, T, idx_h, st);
+    rc = ess_launch_topk(ctx, sc, a->ctx_len + b0, Bh, T, idx_h, st, xcd_of(2));
     if (rc != ESS_OK) return rc;
     ESS_END(1);
     if (!offloaded) continue;
@@ -485,11 +499,11 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     ESS_BEGIN(2);
     if (da_swap || (dba && h == 1)) {      // bookkeeping only; the fetch follows on this stream further down
       rc = ess_launch_bookkeeping(ctx, ch, used, Bh, T, c.topk, a->step, ctx->slot_idx_ws + bt0 * k,
-                                  a->miss_count ? a->miss_count + b0 : nullptr, st, b0, h == 0);
+                                  a->miss_count ? a->miss_count + b0 : nullptr, st, b0, h == 0, xcd_of(4));
       if (rc != ESS_OK) return rc;
     } else {
       rc = run_cache_step(ctx, ch, used, Bh, T, c.topk, a->step, ctx->slot_idx_ws + bt0 * k,
-                          a->miss_count ? a->miss_count + b0 : nullptr, st, &pending[h], b0, h, fev, dba ? 28 : 64);
+                          a->miss_count ? a->miss_count + b0 : nullptr, st, &pending[h], b0, h, fev, dba ? (confine ? ESS_FETCH_CONFINED_WGS : 28) : 64, confine);
       if (rc != ESS_OK) return rc;
       if (fev) { ctx->prof_nfill[pslot] = h + 1; ctx->prof_pair_stage[(size_t)pslot * ESS_PROF_FILL + h] = 5; }
     }

@@ -12,6 +12,13 @@
 #define ESS_ROW_DIM 576
 #define ESS_ZERO_ROW_BYTES 2048  // >= the largest row_stride
 #define ESS_TOPK_SHARED_ROWS 128 // rows (b,t) up to which a top-k row is shared by several workgroups
+#define ESS_N_TICKETS 8
+// The first fetch of the split-batch schedule is confined to these XCDs, and the kernels beside it stay
+// off them.  Measured at batch 64, 128K context (step time): one XCD 0.668 ms (the fetch drops to
+// 40 GB/s behind a single XCD's port when the other seven stream from HBM), two 0.614, three 0.605,
+// four 0.631 (the index score is short of CUs), unconfined 0.631; 48 workgroups on three XCDs.
+#define ESS_FETCH_XCD_MASK 7u
+#define ESS_FETCH_CONFINED_WGS 48
 #define ESS_PROF_MAIN 16        // stage marks on the caller's stream per step
 #define ESS_PROF_FILL 3         // event pairs per step for work off the caller's stream (fetches, side-stream attention)
 #define ESS_PROF_EVENTS (ESS_PROF_MAIN + 2 * ESS_PROF_FILL)
@@ -37,6 +44,8 @@ struct ess_ctx {
   uint8_t* zero_row;            // ESS_ZERO_ROW_BYTES of zeros, never written: source of masked attention rows
   unsigned long long* topk_cand; // [ESS_TOPK_SHARED_ROWS][8192] candidate keys of rows shared by several workgroups
   uint32_t* topk_cnt;           // [ESS_TOPK_SHARED_ROWS] candidates listed per row: zero between steps
+  uint32_t* tickets;            // [ESS_N_TICKETS] work counters of kernels that run beside a fetch (see ess_xcd)
+  bool xcds_even;               // workgroups go round the eight XCDs evenly (probed at creation): fetches may be confined
   size_t ws_bytes;
   // overlap switch (ESS_FLAG_AUTO): per-sequence miss counts of the latest bookkeeping, written by the
   // kernel into pinned host memory and read by the host, without a synchronisation, at the next step
@@ -56,6 +65,35 @@ struct ess_ctx {
   int prof_every, prof_calls;   // every prof_every-th ess_decode_step is timed
 };
 
+// A fetch from host memory slows every memory access of the XCD its workgroups run on (the long
+// reads fill that XCD's L2 request queues): a latency-bound kernel beside a 28-workgroup fetch spread
+// over the chip takes 3.4x its time, beside the same fetch confined to one XCD -- which costs the fetch
+// 3 % of its rate -- and kept off that XCD it is not slowed at all (measured).  A kernel launched with
+// an ess_xcd therefore does not map workgroups to work by their index: workgroups on the XCDs in
+// `avoid` exit, the others take work items in the order they arrive (`ticket`, zero at launch).
+struct ess_xcd {
+  uint32_t* ticket;
+  uint32_t avoid;               // bit i: XCD i takes no work
+};
+#ifdef __HIPCC__
+__device__ __forceinline__ int ess_xcc_id() { return __builtin_amdgcn_s_getreg(20 | (3 << 11)) & 15; }   // hwreg XCC_ID, bits 3:0
+// work item of this workgroup (all threads get the same), -1 if it has none; `slot` is a __shared__ int
+__device__ __forceinline__ int ess_take_item(int static_item, int items, const ess_xcd& x, int* slot) {
+  if (!x.ticket) return static_item < items ? static_item : -1;
+  if ((x.avoid >> ess_xcc_id()) & 1u) return -1;
+  if (threadIdx.x == 0) *slot = (int)atomicAdd(x.ticket, 1u);
+  __syncthreads();
+  const int it = *slot;
+  return it < items ? it : -1;
+}
+#endif
+// workgroups to launch so that `items` of them sit on XCDs that take work (any 8 consecutive workgroups cover all 8 XCDs)
+inline int ess_xcd_grid(int items, const ess_xcd& x) {
+  if (!x.ticket || !x.avoid) return items;
+  const int off = __builtin_popcount(x.avoid & 0xffu);
+  return (items + (8 - off) - 1) / (8 - off) * 8 + 8;
+}
+
 int ess_fail(int code, const char* fmt, ...);
 
 #define ESS_HIP(call)                                                                       \
@@ -71,9 +109,10 @@ int ess_launch_index_score(const ess_config& c, const uint8_t* q, const float* w
                            const int32_t* ctx_len, int B, int T, float* score, hipStream_t st,
                            const int32_t* block_table = nullptr, int n_pages = 0,
                            // optional: events that take the kernel's own start and end times
-                           hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
+                           hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr, ess_xcd xcd = ess_xcd{nullptr, 0});
+// xcd: ticket[0] and ticket[1] are used (two kernels)
 int ess_launch_topk(ess_ctx* ctx, const float* score, const int32_t* ctx_len, int B, int T, int32_t* idx,
-                    hipStream_t st);
+                    hipStream_t st, ess_xcd xcd = ess_xcd{nullptr, 0});
 size_t ess_topk_cand_bytes();
 // fill kernel (used instead of hipMemsetAsync so that callers may capture the stream in a graph)
 int ess_launch_calib_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
@@ -81,14 +120,17 @@ int ess_launch_append(const ess_config& c, const ess_cache& cache, const uint8_t
                       uint8_t* key, int32_t* ctx_len, int B, int T, uint32_t step, int32_t* placed,
                       const float* new_scale, const int32_t* block_table, int n_pages, hipStream_t st);
 int ess_launch_fill_u32(uint32_t* p, int n, uint32_t value, hipStream_t st);
+int ess_probe_xcds(uint32_t* hist8, bool* even);   // blocking; at context creation
 int ess_launch_cache_reset(const ess_config& c, const ess_cache& cache, int B, hipStream_t st);
 // look-up + LRU update + lists; n_sel = entries per sequence in idx ([B,n_sel], T lists of n_sel/T)
 // b0 = first sequence of the (sub-)batch: caller-owned pointers are passed already shifted, the
 // library's workspace arrays are shifted inside
 int ess_launch_bookkeeping(ess_ctx* ctx, const ess_cache& cache, const int32_t* idx, int B, int T, int kk,
                            uint32_t step, int32_t* slot_idx, int32_t* miss_count_out, hipStream_t st, int b0 = 0,
-                           bool count_step = true);
-int ess_launch_fill(ess_ctx* ctx, const ess_cache& cache, int B, hipStream_t st, int b0 = 0, int wgs = 64);
+                           bool count_step = true, ess_xcd xcd = ess_xcd{nullptr, 0}, uint32_t* zero_tickets = nullptr);
+// only_xcds != 0: the fetch runs on these XCDs alone (`wgs` workgroups there, rows handed out through `ticket`)
+int ess_launch_fill(ess_ctx* ctx, const ess_cache& cache, int B, hipStream_t st, int b0 = 0, int wgs = 64,
+                    uint32_t only_xcds = 0, uint32_t* ticket = nullptr);
 int ess_launch_gather_rows(const ess_config& c, const uint8_t* slot_pool, const int32_t* slot_idx, int B, int T,
                            uint8_t* rows_out, hipStream_t st);
 // attention over list[b,t,0..n) (n = n_list[b,t], or k when n_list is NULL), written as `nsplit`

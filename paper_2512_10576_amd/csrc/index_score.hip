@@ -66,12 +66,16 @@ __global__ __launch_bounds__(kWaves * 64, T == 2 ? 2 : 1) void k_index_score(con
                                                               float* __restrict__ score, int Lmax, int Hi,
                                                               int chunk_tokens,
                                                               const int32_t* __restrict__ block_table, int n_pages,
-                                                              int Ttot, int t0) {
+                                                              int Ttot, int t0, ess_xcd xcd, int nx, int nb_seq) {
   constexpr int KS = DI / 32;
   constexpr size_t kPageBytes = (size_t)kBatchTokens * (DI + 4);
-  const int b = blockIdx.y;
+  // work item = (chunk, sequence): by workgroup index, or in arrival order off the XCDs to be avoided
+  __shared__ int s_item;
+  const int item = ess_take_item(blockIdx.y * nx + blockIdx.x, nx * nb_seq, xcd, &s_item);
+  if (item < 0) return;
+  const int b = item / nx;
   const int len = min(ctx_len[b], Lmax);
-  const int blk_base = blockIdx.x * chunk_tokens;
+  const int blk_base = (item % nx) * chunk_tokens;
   if (blk_base >= len) return;
   const int blk_end = min(blk_base + chunk_tokens, len);
 
@@ -228,6 +232,7 @@ struct IdxArgs {
   const int32_t* block_table; int n_pages;
   hipEvent_t ev_start, ev_stop;             // optional: take the kernel's own start and end times
   int Ttot, t0;                             // tokens per sequence in q / w / score, first token of this launch
+  ess_xcd xcd; int nx, nb_seq;              // work distribution; chunks per sequence, sequences
 };
 
 template <int HB, int DI, int T, bool PAGED>
@@ -235,10 +240,10 @@ void launch_k(dim3 grid, hipStream_t st, const IdxArgs& a) {
   const dim3 block(kWaves * 64);
   if (a.ev_start || a.ev_stop)      // timed launch: the events take the kernel's own start and end
     hipExtLaunchKernelGGL((k_index_score<HB, DI, T, PAGED>), grid, block, 0, st, a.ev_start, a.ev_stop, 0, a.q, a.w, a.key,
-                          a.ctx_len, a.score, a.Lmax, a.Hi, a.chunk, a.block_table, a.n_pages, a.Ttot, a.t0);
+                          a.ctx_len, a.score, a.Lmax, a.Hi, a.chunk, a.block_table, a.n_pages, a.Ttot, a.t0, a.xcd, a.nx, a.nb_seq);
   else
     hipLaunchKernelGGL((k_index_score<HB, DI, T, PAGED>), grid, block, 0, st, a.q, a.w, a.key, a.ctx_len, a.score, a.Lmax,
-                       a.Hi, a.chunk, a.block_table, a.n_pages, a.Ttot, a.t0);
+                       a.Hi, a.chunk, a.block_table, a.n_pages, a.Ttot, a.t0, a.xcd, a.nx, a.nb_seq);
 }
 
 template <int HB, int DI, int T>
@@ -267,18 +272,21 @@ void launch_hb(int HB, int T, dim3 grid, hipStream_t st, const IdxArgs& a) {
 
 int ess_launch_index_score(const ess_config& c, const uint8_t* q, const float* w, const uint8_t* key,
                            const int32_t* ctx_len, int B, int T, float* score, hipStream_t st,
-                           const int32_t* block_table, int n_pages, hipEvent_t ev_start, hipEvent_t ev_stop) {
+                           const int32_t* block_table, int n_pages, hipEvent_t ev_start, hipEvent_t ev_stop, ess_xcd xcd) {
   const int Hi = c.idx_heads, Di = c.idx_dim, Lmax = c.max_ctx;
   const int HB = (Hi + 15) / 16;
   // tokens per workgroup: a multiple of the 256 tokens the four waves cover per round; 2048 when
   // that still leaves several workgroups per CU, else 1024
   const int chunk = ((long)B * Lmax >= 2048L * 1024) ? 2048 : 1024;
-  dim3 grid((Lmax + chunk - 1) / chunk, B);
+  const int nx = (Lmax + chunk - 1) / chunk;
+  if (xcd.ticket && T > 2) return ess_fail(ESS_ERR_UNSUPPORTED, "internal: one ticket serves one index-score launch");
+  dim3 grid(nx, B);
+  if (xcd.ticket) grid = dim3(ess_xcd_grid(nx * B, xcd));
   // two query tokens per launch; the events of a timed call bracket the whole series
   for (int t0 = 0; t0 < T; t0 += 2) {
     const int Tl = T - t0 < 2 ? T - t0 : 2;
     const IdxArgs a{q, w, key, ctx_len, score, Lmax, Hi, chunk, block_table, n_pages,
-                    t0 == 0 ? ev_start : nullptr, t0 + 2 >= T ? ev_stop : nullptr, T, t0};
+                    t0 == 0 ? ev_start : nullptr, t0 + 2 >= T ? ev_stop : nullptr, T, t0, xcd, nx, B};
     switch (Di) {
       case 32: launch_hb<32>(HB, Tl, grid, st, a); break;
       case 64: launch_hb<64>(HB, Tl, grid, st, a); break;

@@ -219,10 +219,16 @@ __device__ __forceinline__ void scan_row_rounds(const float* __restrict__ srow, 
 template <int MODE>
 __global__ __launch_bounds__(NT) void k_topk(const float* __restrict__ score, const int32_t* __restrict__ ctx_len,
                                              int T, int Lmax, int k, int IB, int32_t* __restrict__ idx_out,
-                                             unsigned long long* __restrict__ g_cand, uint32_t* __restrict__ g_cnt) {
+                                             unsigned long long* __restrict__ g_cand, uint32_t* __restrict__ g_cnt,
+                                             ess_xcd xcd, int rows, int parts_arg) {
   __shared__ TopkShared sm;
-  const int row = MODE == 1 ? blockIdx.y : blockIdx.x;
-  const int part = MODE == 1 ? blockIdx.x : 0, parts = MODE == 1 ? gridDim.x : 1;
+  // work item = (part, row): by workgroup index, or in arrival order off the XCDs to be avoided
+  __shared__ int s_item;
+  const int parts = MODE == 1 ? parts_arg : 1;
+  const int item = ess_take_item(MODE == 1 ? blockIdx.y * parts + blockIdx.x : blockIdx.x, rows * parts, xcd, &s_item);
+  if (item < 0) return;
+  const int row = item / parts;
+  const int part = item % parts;
   const int b = row / T, t = row % T;
   const int tid = threadIdx.x, lane = tid & 63;
   int vis = ctx_len[b] - (T - 1 - t);
@@ -511,7 +517,7 @@ __global__ __launch_bounds__(NT) void k_topk(const float* __restrict__ score, co
 }  // namespace
 
 int ess_launch_topk(ess_ctx* ctx, const float* score, const int32_t* ctx_len, int B, int T, int32_t* idx,
-                    hipStream_t st) {
+                    hipStream_t st, ess_xcd xcd) {
   const ess_config& c = ctx->cfg;
   int IB = 1;
   while ((1 << IB) < c.max_ctx) ++IB;
@@ -523,14 +529,16 @@ int ess_launch_topk(ess_ctx* ctx, const float* score, const int32_t* ctx_len, in
     parts = 256 / rows;
     if (parts > 8) parts = 8;
   }
+  const ess_xcd x0 = xcd, x1 = ess_xcd{xcd.ticket ? xcd.ticket + 1 : nullptr, xcd.avoid};
   if (parts > 1) {
-    hipLaunchKernelGGL(k_topk<1>, dim3(parts, rows), dim3(NT), 0, st, score, ctx_len, T, c.max_ctx, c.topk, IB, idx,
-                       ctx->topk_cand, ctx->topk_cnt);
-    hipLaunchKernelGGL(k_topk<2>, dim3(rows), dim3(NT), 0, st, score, ctx_len, T, c.max_ctx, c.topk, IB, idx,
-                       ctx->topk_cand, ctx->topk_cnt);
+    const dim3 g1 = xcd.ticket ? dim3(ess_xcd_grid(parts * rows, xcd)) : dim3(parts, rows);
+    hipLaunchKernelGGL(k_topk<1>, g1, dim3(NT), 0, st, score, ctx_len, T, c.max_ctx, c.topk, IB, idx,
+                       ctx->topk_cand, ctx->topk_cnt, x0, rows, parts);
+    hipLaunchKernelGGL(k_topk<2>, dim3(ess_xcd_grid(rows, xcd)), dim3(NT), 0, st, score, ctx_len, T, c.max_ctx, c.topk, IB, idx,
+                       ctx->topk_cand, ctx->topk_cnt, x1, rows, 1);
   } else {
-    hipLaunchKernelGGL(k_topk<0>, dim3(rows), dim3(NT), 0, st, score, ctx_len, T, c.max_ctx, c.topk, IB, idx,
-                       ctx->topk_cand, ctx->topk_cnt);
+    hipLaunchKernelGGL(k_topk<0>, dim3(ess_xcd_grid(rows, xcd)), dim3(NT), 0, st, score, ctx_len, T, c.max_ctx, c.topk, IB, idx,
+                       ctx->topk_cand, ctx->topk_cnt, x1, rows, 1);
   }
   ESS_HIP(hipGetLastError());
   return ESS_OK;
