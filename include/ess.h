@@ -204,7 +204,7 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
 /* ESS_FLAG_AUTO: the DBA schedule is used for a step when the previous bookkeeping of this context
  * saw more than `misses_per_seq` misses per sequence on average (Sec. 3.3: DBA pays when the fetch is
  * long), else the DA schedule.  The counts travel through pinned host memory and are read without
- * waiting for the GPU, so the decision may lag by a step; results do not depend on it.  Default 100
+ * waiting for the GPU, so the decision may lag by a step; results do not depend on it.  Default 150
  * (measured crossover for 1152-byte entries, batch 64, 128K context on MI355X).  With the default
  * threshold the DBA schedule is only chosen when the index score of half the batch is long enough to
  * be worth hiding (estimated from batch x max_ctx: at least about 50 us, i.e. not at batch 64 and 32K

@@ -91,14 +91,14 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
     int32_t* __restrict__ n_miss, int32_t* __restrict__ fill_tok, int32_t* __restrict__ fill_slot, int fill_cap,
     int32_t* __restrict__ miss_cnt, int32_t* __restrict__ miss_count_out, unsigned long long* __restrict__ stats,
     int row_stride, int count_step, int32_t* __restrict__ host_miss, ess_xcd xcd, int n_seq,
-    uint32_t* __restrict__ zero_tickets) {
+    uint32_t* __restrict__ zero_tickets, int n_zero_tickets) {
   extern __shared__ uint32_t bm[];             // [W] bitmap of the missed positions
   __shared__ BookShared sm;
   __shared__ int s_item;
   constexpr int RS = 16;                       // register-held stamps per thread
   // work counters of the kernels that follow this one beside the fetch it feeds: cleared here, by the first
   // workgroup, so that no launch has to do it (this kernel itself never uses the counters it clears)
-  if (zero_tickets && blockIdx.x == 0 && threadIdx.x < ESS_N_TICKETS) zero_tickets[threadIdx.x] = 0;
+  if (zero_tickets && blockIdx.x == 0 && (int)threadIdx.x < n_zero_tickets) zero_tickets[threadIdx.x] = 0;
   const int b = ess_take_item(blockIdx.x, n_seq, xcd, &s_item);   // sequence: by workgroup index, or in arrival order
   if (b < 0) return;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -557,7 +557,7 @@ int ess_launch_cache_reset(const ess_config& c, const ess_cache& cache, int B, h
 
 int ess_launch_bookkeeping(ess_ctx* ctx, const ess_cache& cache, const int32_t* idx, int B, int T, int kk,
                            uint32_t step, int32_t* slot_idx, int32_t* miss_count_out, hipStream_t st, int b0,
-                           bool count_step, ess_xcd xcd, uint32_t* zero_tickets) {
+                           bool count_step, ess_xcd xcd, uint32_t* zero_tickets, int n_zero_tickets) {
   const ess_config& c = ctx->cfg;
   const size_t lds = (size_t)((c.max_ctx + 31) / 32) * sizeof(uint32_t);
   const bool lists = (kk == c.topk);           // compacted lists have the pitch of the top-k
@@ -572,7 +572,7 @@ int ess_launch_bookkeeping(ess_ctx* ctx, const ess_cache& cache, const int32_t* 
                      ctx->n_hit + (size_t)b0 * T, ctx->n_miss + (size_t)b0 * T, ctx->fill_tok + (size_t)b0 * cap,
                      ctx->fill_slot + (size_t)b0 * cap, cap, ctx->miss_cnt + b0, miss_count_out, ctx->stats,
                      c.row_stride, count_step ? 1 : 0, (c.flags & ESS_FLAG_AUTO) ? ctx->host_miss_dev + b0 : nullptr, xcd, B,
-                     zero_tickets);
+                     zero_tickets, n_zero_tickets);
   ESS_HIP(hipGetLastError());
   return ESS_OK;
 }

@@ -148,7 +148,7 @@ int run_cache_step(ess_ctx* ctx, const ess_cache& cache, const int32_t* idx, int
   // confine: the fetch runs on one XCD and the kernels beside it stay off that XCD, taking their work
   // through counters that this bookkeeping clears (counter 0: the fetch itself)
   int rc = ess_launch_bookkeeping(ctx, cache, idx, B, T, kk, step, slot_idx, miss_count, st, b0, half == 0,
-                                  ess_xcd{nullptr, 0}, confine ? ctx->tickets : nullptr);
+                                  ess_xcd{nullptr, 0}, confine ? ctx->tickets : nullptr, 5);
   if (rc != ESS_OK) return rc;
   if (!cache.host_pool_dev) return ESS_OK;      // nothing offloaded: no entry can be missing
   if (ctx->cfg.flags & ESS_FLAG_SERIAL) {
@@ -255,7 +255,7 @@ int ess_create(const ess_config* cfg, ess_ctx** out) {
   memset(ctx->host_miss, 0, (size_t)cfg->max_batch * sizeof(int32_t));
   if ((e = hipHostGetDevicePointer(reinterpret_cast<void**>(&ctx->host_miss_dev), ctx->host_miss, 0)) != hipSuccess)
     return bail("hipHostGetDevicePointer", e);
-  ctx->auto_threshold = 100;
+  ctx->auto_threshold = 150;
   ctx->auto_calibrated = false;
   *out = ctx;
   return ESS_OK;
@@ -425,11 +425,13 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
   // DualBatch-Attention overlap (Sec. 3.3): the batch is cut in two halves so that the second half's
   // indexer and top-k run while the first half's fetch is in flight
   bool want_dba = (c.flags & ESS_FLAG_DBA) != 0;
+  long mean_miss = -1;                          // misses per sequence of the latest bookkeeping, if known
   if ((c.flags & ESS_FLAG_AUTO) && offloaded) {
     // miss counts of the latest bookkeeping as the host sees them now (no wait: possibly a step old)
     const volatile int32_t* hm = ctx->host_miss;
     long sum = 0;
     for (int b = 0; b < B; ++b) sum += hm[b];
+    mean_miss = sum / B;
     // the split pays by hiding half the batch's index score behind a fetch: it must be long enough to be
     // worth two rounds of top-k and bookkeeping (at 32K context and batch 64 it is not, whatever the misses)
     const double idx_half_us = 0.5 * B * (double)c.max_ctx * (c.idx_dim + 4.0 * T) / 5.3e6;   // at 5.3 TB/s
@@ -439,8 +441,20 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
   ctx->last_overlap = (c.flags & ESS_FLAG_SERIAL) ? 2 : (dba ? 1 : 0);
   const bool da_swap = offloaded && !dba && !(c.flags & ESS_FLAG_SERIAL);
   const int nh = dba ? 2 : 1;
+  // A fetch confined to three XCDs, with the kernels beside it kept off them (see ess_xcd), pays when the
+  // fetch is long: the kernels beside it then run as if alone, on five XCDs.  With few misses the lost CUs
+  // cost more (Attn0, two rounds of workgroups instead of one, becomes the longer side).  Measured at
+  // batch 64, 128K context, 1152-byte entries (step time, confined vs not): single-fetch schedule 0.436 vs
+  // 0.398 ms at 31 misses per sequence, 0.447 vs 0.482 at 114, 0.557 vs 0.570 at 195; split-batch, first
+  // fetch: 0.497 vs 0.476 at 114, 0.529 vs 0.529 at 195, 0.607 vs 0.631 at 289; second fetch as well: 0.546
+  // vs 0.529 at 195, 0.605 vs 0.607 at 289, 0.891 vs 0.933 at 494.  The miss count of the previous step
+  // is only known under ESS_FLAG_AUTO; without it nothing is confined.
   // (one work counter serves one index-score launch: two query tokens at most)
-  const bool confine = dba && T <= 2 && ctx->xcds_even;
+  const bool confine = dba && T <= 2 && ctx->xcds_even && mean_miss >= ESS_CONFINE_DBA1_MISSES;
+  const bool confine2 = confine && mean_miss >= ESS_CONFINE_DBA2_MISSES;   // the second fetch too, with the attention beside it
+  const bool confine_da = da_swap && ctx->xcds_even && mean_miss >= ESS_CONFINE_DA_MISSES;
+  const uint32_t mask2 = ESS_FETCH_XCD_MASK;
+  const int wgs2 = ESS_FETCH_CONFINED_WGS;
   const int hb0[2] = {0, B / 2};
   const int hB[2] = {dba ? B / 2 : B, B - B / 2};
   const size_t k = (size_t)c.topk;
@@ -499,7 +513,8 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     ESS_BEGIN(2);
     if (da_swap || (dba && h == 1)) {      // bookkeeping only; the fetch follows on this stream further down
       rc = ess_launch_bookkeeping(ctx, ch, used, Bh, T, c.topk, a->step, ctx->slot_idx_ws + bt0 * k,
-                                  a->miss_count ? a->miss_count + b0 : nullptr, st, b0, h == 0, xcd_of(4));
+                                  a->miss_count ? a->miss_count + b0 : nullptr, st, b0, h == 0, xcd_of(4),
+                                  (confine2 || (da_swap && confine_da)) ? ctx->tickets + (da_swap ? 0 : 5) : nullptr, da_swap ? 8 : 3);
       if (rc != ESS_OK) return rc;
     } else {
       rc = run_cache_step(ctx, ch, used, Bh, T, c.topk, a->step, ctx->slot_idx_ws + bt0 * k,
@@ -535,7 +550,8 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     ESS_HIP(hipStreamWaitEvent(ctx->side, ctx->ev_book[0], 0));
     hipEvent_t* aev = (pev && ((ctx->prof_mask >> 3) & 1u)) ? pev + ESS_PROF_MAIN : nullptr;
     if (aev) ESS_HIP(hipEventRecord(aev[0], ctx->side));
-    rc = ess_launch_attn_partial(ctx, q16, cache->slot_pool, ctx->hit_list, ctx->n_hit, B, T, 0, ns0, ctx->side, 0);
+    rc = ess_launch_attn_partial(ctx, q16, cache->slot_pool, ctx->hit_list, ctx->n_hit, B, T, 0, ns0, ctx->side, 0,
+                                 confine_da ? ess_xcd{ctx->tickets + 6, mask2} : ess_xcd{nullptr, 0});
     if (rc != ESS_OK) return rc;
     if (aev) {
       ESS_HIP(hipEventRecord(aev[1], ctx->side));
@@ -544,7 +560,7 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     }
     ESS_HIP(hipEventRecord(ctx->ev_fill[0], ctx->side));          // here: Attn0 done
     ESS_BEGIN(5);
-    rc = ess_launch_fill(ctx, *cache, B, st, 0, 64);
+    rc = confine_da ? ess_launch_fill(ctx, *cache, B, st, 0, wgs2, mask2, ctx->tickets) : ess_launch_fill(ctx, *cache, B, st, 0, 64);
     if (rc != ESS_OK) return rc;
     ESS_END(5);
     ESS_BEGIN(4);
@@ -568,7 +584,8 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     const size_t bt1 = (size_t)hb0[1] * T;
     ESS_HIP(hipEventRecord(ctx->ev_book[1], st));                    // second half's bookkeeping done
     ESS_BEGIN(5);
-    rc = ess_launch_fill(ctx, c1, hB[1], st, hb0[1], 28);
+    rc = confine2 ? ess_launch_fill(ctx, c1, hB[1], st, hb0[1], wgs2, mask2, ctx->tickets + 5)
+                  : ess_launch_fill(ctx, c1, hB[1], st, hb0[1], 28);
     if (rc != ESS_OK) return rc;
     ESS_END(5);
     // side-stream attention is timed by event pairs 1 and 2 (pair 0 brackets the first fetch): all three or none
@@ -577,13 +594,15 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     if (aev) ESS_HIP(hipEventRecord(aev[0], ctx->side));
     // Attn0 of the whole batch in one launch (behind the first fetch it could not start much earlier
     // anyway): one workgroup per CU, the same splits as in the other schedules
-    rc = ess_launch_attn_partial(ctx, q16, cache->slot_pool, ctx->hit_list, ctx->n_hit, B, T, 0, ns0, ctx->side, 0);
+    rc = ess_launch_attn_partial(ctx, q16, cache->slot_pool, ctx->hit_list, ctx->n_hit, B, T, 0, ns0, ctx->side, 0,
+                                 confine2 ? ess_xcd{ctx->tickets + 6, mask2} : ess_xcd{nullptr, 0});
     if (rc != ESS_OK) return rc;
     if (aev) {
       ESS_HIP(hipEventRecord(aev[1], ctx->side));
       ESS_HIP(hipEventRecord(aev[2], ctx->side));
     }
-    rc = ess_launch_attn_partial(ctx, q16, c0.slot_pool, ctx->miss_list, ctx->n_miss, hB[0], T, ns0, ns1, ctx->side, hb0[0]);
+    rc = ess_launch_attn_partial(ctx, q16, c0.slot_pool, ctx->miss_list, ctx->n_miss, hB[0], T, ns0, ns1, ctx->side, hb0[0],
+                                 confine2 ? ess_xcd{ctx->tickets + 7, mask2} : ess_xcd{nullptr, 0});
     if (rc != ESS_OK) return rc;
     // each half is merged on the stream its Attn1 ran on: only half a merge is left behind the last fetch
     rc = ess_launch_attn_merge(ctx, hB[0], T, ns0 + ns1, a->out_bf16, a->lse, ctx->side, nullptr, 0, hb0[0]);

@@ -19,6 +19,11 @@
 // four 0.631 (the index score is short of CUs), unconfined 0.631; 48 workgroups on three XCDs.
 #define ESS_FETCH_XCD_MASK 7u
 #define ESS_FETCH_CONFINED_WGS 48
+// misses per sequence (previous step) from which a fetch is confined: single-fetch schedule; split-batch
+// schedule, first fetch; second fetch as well
+#define ESS_CONFINE_DA_MISSES 70
+#define ESS_CONFINE_DBA1_MISSES 200
+#define ESS_CONFINE_DBA2_MISSES 300
 #define ESS_PROF_MAIN 16        // stage marks on the caller's stream per step
 #define ESS_PROF_FILL 3         // event pairs per step for work off the caller's stream (fetches, side-stream attention)
 #define ESS_PROF_EVENTS (ESS_PROF_MAIN + 2 * ESS_PROF_FILL)
@@ -127,7 +132,8 @@ int ess_launch_cache_reset(const ess_config& c, const ess_cache& cache, int B, h
 // library's workspace arrays are shifted inside
 int ess_launch_bookkeeping(ess_ctx* ctx, const ess_cache& cache, const int32_t* idx, int B, int T, int kk,
                            uint32_t step, int32_t* slot_idx, int32_t* miss_count_out, hipStream_t st, int b0 = 0,
-                           bool count_step = true, ess_xcd xcd = ess_xcd{nullptr, 0}, uint32_t* zero_tickets = nullptr);
+                           bool count_step = true, ess_xcd xcd = ess_xcd{nullptr, 0}, uint32_t* zero_tickets = nullptr,
+                           int n_zero_tickets = 0);
 // only_xcds != 0: the fetch runs on these XCDs alone (`wgs` workgroups there, rows handed out through `ticket`)
 int ess_launch_fill(ess_ctx* ctx, const ess_cache& cache, int B, hipStream_t st, int b0 = 0, int wgs = 64,
                     uint32_t only_xcds = 0, uint32_t* ticket = nullptr);
@@ -136,7 +142,8 @@ int ess_launch_gather_rows(const ess_config& c, const uint8_t* slot_pool, const 
 // attention over list[b,t,0..n) (n = n_list[b,t], or k when n_list is NULL), written as `nsplit`
 // partial results starting at partial index `split0`
 int ess_launch_attn_partial(ess_ctx* ctx, const void* q, const uint8_t* slot_pool, const int32_t* list,
-                            const int32_t* n_list, int B, int T, int split0, int nsplit, hipStream_t st, int b0 = 0);
+                            const int32_t* n_list, int B, int T, int split0, int nsplit, hipStream_t st, int b0 = 0,
+                            ess_xcd xcd = ess_xcd{nullptr, 0});
 int ess_attn_min_splits(const ess_config& c);   // fewest splits a list of k entries may be cut into
 // zero_cnt (may be NULL): n_zero int32 counters that the merge kernel also clears; b0 = first sequence of the
 // sub-batch of B sequences (out_bf16 and lse are the whole batch's arrays)

@@ -193,20 +193,26 @@ template <int FMT>
 __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
     const uint16_t* __restrict__ q, const uint8_t* __restrict__ pool, const int32_t* __restrict__ list,
     const int32_t* __restrict__ n_list, int T, int H, int kk, int S, int row_stride, float scale_log2e, int split0,
-    int nsplit, float* __restrict__ o_part, float* __restrict__ lse_part, const uint8_t* __restrict__ zero_row) {
+    int nsplit, float* __restrict__ o_part, float* __restrict__ lse_part, const uint8_t* __restrict__ zero_row,
+    ess_xcd xcd, int n_bt, int n_hg) {
   extern __shared__ __align__(16) uint8_t lds[];
+  // work item = (split, bt, head group): by workgroup index, or in arrival order off the XCDs to be avoided
+  __shared__ int s_item;
+  const int item = ess_take_item(blockIdx.x + nsplit * (blockIdx.y + n_bt * blockIdx.z), nsplit * n_bt * n_hg, xcd, &s_item);
+  if (item < 0) return;
   constexpr bool kDma = FMT == ESS_FMT_BF16;       // rows go to LDS as they are; else through registers, dequantised
   constexpr int NBUF = tr_nbuf(FMT);
   int32_t* slot_cache = reinterpret_cast<int32_t*>(lds + NBUF * TR_RAW_BYTES);   // [MAX_TPS][32]
   const uint32_t lds0 = lds_addr_of(lds);
 
-  const int split = blockIdx.x;
-  const int bt = blockIdx.y;
+  const int split = item % nsplit;
+  const int bt = (item / nsplit) % n_bt;
+  const int hg = item / (nsplit * n_bt);
   const int b = bt / T;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 4, n16 = lane & 15;
-  const int head0 = (blockIdx.z * 4 + wave) * 16;
+  const int head0 = (hg * 4 + wave) * 16;
   const bool wave_active = head0 < H;
 
   const int n = n_list ? min(n_list[bt], kk) : kk;
@@ -541,10 +547,12 @@ int ess_attn_min_splits(const ess_config& c) {
 }
 
 int ess_launch_attn_partial(ess_ctx* ctx, const void* q, const uint8_t* slot_pool, const int32_t* list,
-                            const int32_t* n_list, int B, int T, int split0, int nsplit, hipStream_t st, int b0) {
+                            const int32_t* n_list, int B, int T, int split0, int nsplit, hipStream_t st, int b0, ess_xcd xcd) {
   const ess_config& c = ctx->cfg;
   if (nsplit < ess_attn_min_splits(c)) return ess_fail(ESS_ERR_INVALID_ARG, "internal: too few attention splits");
-  dim3 grid(nsplit, B * T, (c.attn_heads + 63) / 64);   // 64 heads per workgroup
+  const int n_hg = (c.attn_heads + 63) / 64;            // 64 heads per workgroup
+  dim3 grid(nsplit, B * T, n_hg);
+  if (xcd.ticket) grid = dim3(ess_xcd_grid(nsplit * B * T * n_hg, xcd));
   const float sc = c.sm_scale * kLog2e;
   const uint16_t* qq = static_cast<const uint16_t*>(q);
   // partial results of sequence b0 onward
@@ -555,13 +563,13 @@ int ess_launch_attn_partial(ess_ctx* ctx, const void* q, const uint8_t* slot_poo
     ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_partial_tr<ESS_FMT_BF16>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds));
     hipLaunchKernelGGL(k_attn_partial_tr<ESS_FMT_BF16>, grid, dim3(NTH), lds, st, qq, slot_pool, list, n_list, T,
-                       c.attn_heads, c.topk, c.slots_per_seq, c.row_stride, sc, split0, nsplit, op, lp, ctx->zero_row);
+                       c.attn_heads, c.topk, c.slots_per_seq, c.row_stride, sc, split0, nsplit, op, lp, ctx->zero_row, xcd, B * T, n_hg);
   } else {
     constexpr int lds = tr_lds_bytes(ESS_FMT_FP8);
     ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_partial_tr<ESS_FMT_FP8>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds));
     hipLaunchKernelGGL(k_attn_partial_tr<ESS_FMT_FP8>, grid, dim3(NTH), lds, st, qq, slot_pool, list, n_list, T,
-                       c.attn_heads, c.topk, c.slots_per_seq, c.row_stride, sc, split0, nsplit, op, lp, ctx->zero_row);
+                       c.attn_heads, c.topk, c.slots_per_seq, c.row_stride, sc, split0, nsplit, op, lp, ctx->zero_row, xcd, B * T, n_hg);
   }
   ESS_HIP(hipGetLastError());
   return ESS_OK;
