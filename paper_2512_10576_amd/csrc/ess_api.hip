@@ -442,17 +442,32 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
   const bool da_swap = offloaded && !dba && !(c.flags & ESS_FLAG_SERIAL);
   const int nh = dba ? 2 : 1;
   // A fetch confined to three XCDs, with the kernels beside it kept off them (see ess_xcd), pays when the
-  // fetch is long: the kernels beside it then run as if alone, on five XCDs.  With few misses the lost CUs
-  // cost more (Attn0, two rounds of workgroups instead of one, becomes the longer side).  Measured at
-  // batch 64, 128K context, 1152-byte entries (step time, confined vs not): single-fetch schedule 0.436 vs
-  // 0.398 ms at 31 misses per sequence, 0.447 vs 0.482 at 114, 0.557 vs 0.570 at 195; split-batch, first
-  // fetch: 0.497 vs 0.476 at 114, 0.529 vs 0.529 at 195, 0.607 vs 0.631 at 289; second fetch as well: 0.546
-  // vs 0.529 at 195, 0.605 vs 0.607 at 289, 0.891 vs 0.933 at 494.  The miss count of the previous step
-  // is only known under ESS_FLAG_AUTO; without it nothing is confined.
-  // (one work counter serves one index-score launch: two query tokens at most)
-  const bool confine = dba && T <= 2 && ctx->xcds_even && mean_miss >= ESS_CONFINE_DBA1_MISSES;
-  const bool confine2 = confine && mean_miss >= ESS_CONFINE_DBA2_MISSES;   // the second fetch too, with the attention beside it
-  const bool confine_da = da_swap && ctx->xcds_even && mean_miss >= ESS_CONFINE_DA_MISSES;
+  // fetch is long: the kernels beside it then run as if alone, but on five XCDs.  With few misses the lost
+  // CUs cost more (Attn0, in more rounds of workgroups, becomes the longer side).  Measured at batch 64,
+  // 128K context, 1152-byte entries (step time, confined vs not): single-fetch schedule 0.436 vs 0.398 ms
+  // at 31 misses per sequence, 0.447 vs 0.482 at 114, 0.557 vs 0.570 at 195; split-batch, first fetch:
+  // 0.497 vs 0.476 at 114, 0.529 vs 0.529 at 195, 0.607 vs 0.631 at 289; second fetch as well: 0.546 vs
+  // 0.529 at 195, 0.605 vs 0.607 at 289, 0.891 vs 0.933 at 494; at batch 128 with two query tokens and
+  // quantised entries, where attention is as long as the fetches, the second confinement costs 5 %.
+  // The rules below compare rough times (microseconds) of the fetch and of what runs beside it; the miss
+  // count of the previous step is only known under ESS_FLAG_AUTO, without it nothing is confined.
+  bool confine = false, confine2 = false, confine_da = false;
+  if (mean_miss >= 0 && ctx->xcds_even) {
+    const double link = 50e3;                                       // bytes per microsecond
+    const double fetch_all = (double)B * mean_miss * c.row_stride / link, fetch_half = 0.5 * fetch_all;
+    const double idx_half = 0.5 * B * (double)c.max_ctx * (c.idx_dim + 4.0 * T) / 5.3e6;
+    // Attn0 on five XCDs (160 CUs, one workgroup each): rounds x (tiles x time per tile + start and end)
+    const int hg = (c.attn_heads + 63) / 64;
+    const int ns0e = pick_splits(c, B, T, 16, ESS_ATTN0_WGS);
+    const double hits = c.topk - (mean_miss / T < c.topk ? mean_miss / T : c.topk);
+    const double tiles_item = (hits / ESS_ATTN_TILE) / ns0e + 1.0;
+    const double rounds = (double)((long)B * T * hg * ns0e + 159) / 160;
+    const double attn5 = (double)(long)rounds * (tiles_item * (c.latent_fmt == ESS_FMT_BF16 ? 1.8 : 2.6) + 11.0);
+    // (one work counter serves one index-score launch: two query tokens at most)
+    confine = dba && T <= 2 && fetch_half >= 1.5 * idx_half;
+    confine2 = confine && attn5 + 40.0 <= 0.9 * fetch_half;         // + Attn1 and merge of the first half
+    confine_da = da_swap && attn5 <= 1.1 * fetch_all;
+  }
   const uint32_t mask2 = ESS_FETCH_XCD_MASK;
   const int wgs2 = ESS_FETCH_CONFINED_WGS;
   const int hb0[2] = {0, B / 2};

@@ -19,11 +19,6 @@
 // four 0.631 (the index score is short of CUs), unconfined 0.631; 48 workgroups on three XCDs.
 #define ESS_FETCH_XCD_MASK 7u
 #define ESS_FETCH_CONFINED_WGS 48
-// misses per sequence (previous step) from which a fetch is confined: single-fetch schedule; split-batch
-// schedule, first fetch; second fetch as well
-#define ESS_CONFINE_DA_MISSES 70
-#define ESS_CONFINE_DBA1_MISSES 200
-#define ESS_CONFINE_DBA2_MISSES 300
 #define ESS_PROF_MAIN 16        // stage marks on the caller's stream per step
 #define ESS_PROF_FILL 3         // event pairs per step for work off the caller's stream (fetches, side-stream attention)
 #define ESS_PROF_EVENTS (ESS_PROF_MAIN + 2 * ESS_PROF_FILL)
