@@ -304,12 +304,12 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
 // entries per wave in flight at once.  The kernel is a handful of 512-thread workgroups that loop
 // over all sequences: its waves spend their life waiting on the host link.  The number of workgroups
 // sets how many bytes are in flight on the link: 64 (1.2 MB in flight) reach 53 GB/s, 32 reach
-// 50 GB/s, 16 reach 48 GB/s, 8 only 27 GB/s.  Requests waiting for the link also hold up the other
-// kernels' HBM traffic: beside a 64-workgroup fetch every kernel measured (index score, top-k,
-// attention) takes about 2.2x its time alone, beside a 32-workgroup fetch about 1.3x.  With one fetch
-// per step only Attn0 runs beside it and has time to spare, so the fetch gets 64 workgroups; the
-// split-batch schedule puts critical-path kernels beside the fetch and asks for 28 (best of a sweep
-// from 12 to 64 at batch 64, 128K context).
+// 50 GB/s, 16 reach 48 GB/s, 8 only 27 GB/s.  The long host reads also fill the L2 request queues of
+// the XCDs the workgroups sit on, and every other memory access of those XCDs waits behind them: a
+// kernel beside a 64-workgroup fetch spread over the chip takes about 2.2x its time alone (a
+// latency-bound one more), beside 28-32 workgroups about 1.3x.  The launcher can therefore confine
+// the fetch to some XCDs (`only_xcds`: the other workgroups exit, entries are handed out by ticket),
+// and the kernels beside it stay off those (ess_xcd).
 constexpr int FILL_WPB = 8;                                 // waves per workgroup
 constexpr int FILL_MAX_B = 4096;
 
