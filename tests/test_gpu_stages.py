@@ -282,10 +282,11 @@ def test_sparse_mla_decode_vs_oracle(ess_lib, name, B, T, H, L, k, fmt, scale):
 
 
 # ---------------------------------------------------------------- whole step
-@pytest.mark.parametrize("flags,fmt", [(0, 0), (1, 0), (2, 0), (4, 0), (0, 1), (2, 1)])
+@pytest.mark.parametrize("flags,fmt", [(0, 0), (1, 0), (2, 0), (4, 0), (0, 1), (2, 1), (4, 1)])
 def test_decode_step_offloaded_vs_oracle(ess_lib, flags, fmt):
     """T = 2 (causal offset), offloaded entries in both storage formats, all overlap modes (4 = switch
-    between DA and DBA on the miss count of the previous step)"""
+    between DA and DBA on the miss count of the previous step; only this mode knows the miss count and
+    may confine a fetch to some XCDs, with the kernels beside it taking their work by ticket)"""
     from paper_2512_10576_amd import binding as bnd
     print("decode_step offload flags", flags, "fmt", fmt, flush=True)
     B, T, Hi, Di, L, k, H, S = 3, 2, 64, 128, 6000, 512, 128, 1500
