@@ -49,7 +49,9 @@ typedef enum {
   ESS_ERR_UNSUPPORTED = -2, /* a shape no kernel was compiled for */
   ESS_ERR_CAPACITY = -3,    /* slot pool smaller than one step's selection (S < T*k), or over a stated maximum */
   ESS_ERR_NOMEM = -4,       /* workspace allocation failed */
-  ESS_ERR_HIP = -5          /* a HIP runtime call failed; text in ess_last_error() */
+  ESS_ERR_HIP = -5,         /* a HIP runtime call failed; text in ess_last_error() */
+  ESS_ERR_INTERNAL = -6     /* a device-side self-check of an EARLIER ess_decode_step failed: that step's
+                               outputs are invalid (reported by the next ess_decode_step or ess_get_stats) */
 } ess_status;
 
 #define ESS_LATENT_DIM 512 /* value part of a Latent-Cache entry */
@@ -213,6 +215,21 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
  * ess_last_overlap: schedule the latest ess_decode_step used: 0 DA, 1 DBA, 2 serial. */
 int ess_set_overlap_threshold(ess_ctx* ctx, int32_t misses_per_seq);
 int ess_last_overlap(const ess_ctx* ctx, int32_t* mode);
+
+/* Under ESS_FLAG_AUTO a step may confine its fetches from host memory to three of the eight XCDs and
+ * keep the kernels that run beside them on the other five (FlashTrans reads, Sec. 3.1, slow every
+ * memory access of the XCD they are issued from).  Those kernels take their work items by ticket, one
+ * per workgroup, and the launch sizes count on workgroups being spread over the XCDs in turn, which
+ * ess_create probes.  Each such step ends with a device-side check that every launch had at least as
+ * many workgroups asking as it had work items; a failure is reported, as ESS_ERR_INTERNAL, by the next
+ * ess_decode_step or ess_get_stats on the context (the failed step's outputs are invalid), and the
+ * context confines nothing from then on.
+ * ess_last_confined: fetches of the latest ess_decode_step that were confined (0, 1 or 2).
+ * ess_selfcheck_inject: test hook.  The check of the next confined step expects `extra_items` more
+ * work items than there are, so that it fails (for extra_items > the spare workgroups of the launch,
+ * a few dozen) although the step itself is complete; every kernel runs and ends as usual. */
+int ess_last_confined(const ess_ctx* ctx, int32_t* fetches);
+int ess_selfcheck_inject(ess_ctx* ctx, int32_t extra_items);
 
 /* Append (Sec. 3.3, the write-back of newly generated entries): for each sequence b with
  * L0 = ctx_len[b], the t-th of its T new tokens takes position p = L0 + t:

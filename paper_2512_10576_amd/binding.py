@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libess.so")
 
 ESS_OK = 0
 ESS_ERR_INVALID_ARG, ESS_ERR_UNSUPPORTED, ESS_ERR_CAPACITY, ESS_ERR_NOMEM, ESS_ERR_HIP = -1, -2, -3, -4, -5
+ESS_ERR_INTERNAL = -6
 ESS_FMT_BF16, ESS_FMT_FP8 = 0, 1
 ESS_FLAG_SERIAL = 1
 ESS_FLAG_DBA = 2
@@ -87,6 +88,8 @@ def load() -> C.CDLL:
         "ess_index_score_paged": [vp, vp, vp, vp, vp, i32, vp, i32, i32, vp, vp],
         "ess_set_overlap_threshold": [vp, i32],
         "ess_last_overlap": [vp, C.POINTER(i32)],
+        "ess_last_confined": [vp, C.POINTER(i32)],
+        "ess_selfcheck_inject": [vp, i32],
         "ess_calib_memcpy_rows": [vp, vp, vp, C.c_int64, i32, i32, vp],
         "ess_profile_read": [vp, C.POINTER(C.c_float), C.POINTER(i32)],
     }
@@ -262,6 +265,16 @@ class Context:
         m = C.c_int32(-1)
         _check(self.lib.ess_last_overlap(self.h, C.byref(m)))
         return m.value
+
+    def last_confined(self) -> int:
+        """fetches of the latest decode_step that were confined to part of the XCDs (0, 1 or 2)"""
+        m = C.c_int32(-1)
+        _check(self.lib.ess_last_confined(self.h, C.byref(m)))
+        return m.value
+
+    def selfcheck_inject(self, extra_items: int) -> None:
+        """test hook: the self-check of the next confined step expects extra_items more work items"""
+        _check(self.lib.ess_selfcheck_inject(self.h, extra_items))
 
     def get_stats(self) -> dict:
         s = EssStats()

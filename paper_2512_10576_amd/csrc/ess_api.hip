@@ -148,7 +148,7 @@ int run_cache_step(ess_ctx* ctx, const ess_cache& cache, const int32_t* idx, int
   // confine: the fetch runs on one XCD and the kernels beside it stay off that XCD, taking their work
   // through counters that this bookkeeping clears (counter 0: the fetch itself)
   int rc = ess_launch_bookkeeping(ctx, cache, idx, B, T, kk, step, slot_idx, miss_count, st, b0, half == 0,
-                                  ess_xcd{nullptr, 0}, confine ? ctx->tickets : nullptr, 5);
+                                  ess_xcd{nullptr, 0, nullptr}, confine ? ctx->tickets : nullptr, 5);
   if (rc != ESS_OK) return rc;
   if (!cache.host_pool_dev) return ESS_OK;      // nothing offloaded: no entry can be missing
   if (ctx->cfg.flags & ESS_FLAG_SERIAL) {
@@ -250,13 +250,15 @@ int ess_create(const ess_config* cfg, ess_ctx** out) {
   if ((e = hipMemset(ctx->tickets, 0, ESS_N_TICKETS * sizeof(uint32_t))) != hipSuccess) return bail("hipMemset", e);
   ctx->xcds_even = false;
   if (ess_probe_xcds(ctx->tickets, &ctx->xcds_even) != ESS_OK) return bail("XCD probe", hipGetLastError());
-  if ((e = hipHostMalloc(reinterpret_cast<void**>(&ctx->host_miss), (size_t)cfg->max_batch * sizeof(int32_t),
+  if ((e = hipHostMalloc(reinterpret_cast<void**>(&ctx->host_miss), ((size_t)cfg->max_batch + 1) * sizeof(int32_t),
                          hipHostMallocMapped)) != hipSuccess) return bail("hipHostMalloc", e);
-  memset(ctx->host_miss, 0, (size_t)cfg->max_batch * sizeof(int32_t));
+  memset(ctx->host_miss, 0, ((size_t)cfg->max_batch + 1) * sizeof(int32_t));
   if ((e = hipHostGetDevicePointer(reinterpret_cast<void**>(&ctx->host_miss_dev), ctx->host_miss, 0)) != hipSuccess)
     return bail("hipHostGetDevicePointer", e);
   ctx->auto_threshold = 150;
   ctx->auto_calibrated = false;
+  ctx->last_confined = 0;
+  ctx->check_extra = 0;
   *out = ctx;
   return ESS_OK;
 }
@@ -313,6 +315,18 @@ int ess_index_score(ess_ctx* ctx, const uint8_t* q, const float* w, const uint8_
 }
 
 namespace {
+// The flag a step's last kernel raises when one of its ticket-fed launches had fewer workgroups asking
+// for work than there were work items (see ess_ticket_check): that step's outputs are incomplete.  Seen at
+// the next call; from then on nothing is confined, so no launch depends on where workgroups land.
+int check_tickets(ess_ctx* ctx) {
+  volatile int32_t* flag = ctx->host_miss + ctx->cfg.max_batch;
+  if (!*flag) return ESS_OK;
+  *flag = 0;
+  ctx->xcds_even = false;
+  return ess_fail(ESS_ERR_INTERNAL, "an earlier decode step left work items unserved (workgroups were not spread over the "
+                                    "XCDs as probed): its outputs are invalid; XCD-confined schedules are now off");
+}
+
 int check_paged(const ess_ctx* ctx, const uint8_t* pool, const int32_t* block_table, int n_pages) {
   if (!block_table) return ess_fail(ESS_ERR_INVALID_ARG, "block_table is NULL");
   if (ctx->cfg.max_ctx % ESS_PAGE_TOKENS) return ess_fail(ESS_ERR_UNSUPPORTED, "paged Indexer-Cache needs max_ctx %% 64 == 0");
@@ -389,6 +403,7 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
   hipStream_t st = static_cast<hipStream_t>(stream);
   const ess_config& c = ctx->cfg;
   const int B = a->B, T = a->T;
+  if ((rc = check_tickets(ctx)) != ESS_OK) return rc;
 
   // stage marks of this step, when profiling: a mark closes the interval since the previous mark and
   // books it under `tag` (0 index score, 1 top-k, 2 bookkeeping, 3 Attn0, 4 Attn1 + merge)
@@ -452,6 +467,9 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
   // The rules below compare rough times (microseconds) of the fetch and of what runs beside it; the miss
   // count of the previous step is only known under ESS_FLAG_AUTO, without it nothing is confined.
   bool confine = false, confine2 = false, confine_da = false;
+  ess_ticket_check chk{};                       // filled in by the launches that take their work by ticket
+  chk.tickets = ctx->tickets;
+  chk.flag = ctx->host_miss_dev + c.max_batch;
   if (mean_miss >= 0 && ctx->xcds_even) {
     const double link = 50e3;                                       // bytes per microsecond
     const double fetch_all = (double)B * mean_miss * c.row_stride / link, fetch_half = 0.5 * fetch_all;
@@ -468,6 +486,9 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     confine2 = confine && attn5 + 40.0 <= 0.9 * fetch_half;         // + Attn1 and merge of the first half
     confine_da = da_swap && attn5 <= 1.1 * fetch_all;
   }
+  ctx->last_confined = confine_da ? 1 : (confine2 ? 2 : (confine ? 1 : 0));
+  const uint32_t check_extra = ctx->last_confined ? ctx->check_extra : 0u;   // test hook, one confined step
+  if (ctx->last_confined) ctx->check_extra = 0;
   const uint32_t mask2 = ESS_FETCH_XCD_MASK;
   const int wgs2 = ESS_FETCH_CONFINED_WGS;
   const int hb0[2] = {0, B / 2};
@@ -507,7 +528,7 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     // second half of the split-batch schedule: these kernels run beside the first fetch, which is confined
     // to one XCD; they stay off it (counters 1..4, cleared by the first half's bookkeeping)
     const bool beside = confine && h == 1;
-    auto xcd_of = [&](int counter) { return beside ? ess_xcd{ctx->tickets + counter, ESS_FETCH_XCD_MASK} : ess_xcd{nullptr, 0}; };
+    auto xcd_of = [&](int counter) { return beside ? ess_xcd{ctx->tickets + counter, ESS_FETCH_XCD_MASK, chk.need + counter} : ess_xcd{nullptr, 0, nullptr}; };
     if (a->block_table)     // paged: one pool for the whole batch, the table rows of this sub-batch
       rc = ess_launch_index_score(c, a->q_idx_fp8 + bt0 * c.idx_heads * c.idx_dim, a->w + bt0 * c.idx_heads, a->key_fp8,
                                   a->ctx_len + b0, Bh, T, sc, st,
@@ -566,7 +587,7 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     hipEvent_t* aev = (pev && ((ctx->prof_mask >> 3) & 1u)) ? pev + ESS_PROF_MAIN : nullptr;
     if (aev) ESS_HIP(hipEventRecord(aev[0], ctx->side));
     rc = ess_launch_attn_partial(ctx, q16, cache->slot_pool, ctx->hit_list, ctx->n_hit, B, T, 0, ns0, ctx->side, 0,
-                                 confine_da ? ess_xcd{ctx->tickets + 6, mask2} : ess_xcd{nullptr, 0});
+                                 confine_da ? ess_xcd{ctx->tickets + 6, mask2, chk.need + 6} : ess_xcd{nullptr, 0, nullptr});
     if (rc != ESS_OK) return rc;
     if (aev) {
       ESS_HIP(hipEventRecord(aev[1], ctx->side));
@@ -582,7 +603,8 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     ESS_HIP(hipStreamWaitEvent(st, ctx->ev_fill[0], 0));
     rc = ess_launch_attn_partial(ctx, q16, cache->slot_pool, ctx->miss_list, ctx->n_miss, B, T, ns0, ns1, st, 0);
     if (rc != ESS_OK) return rc;
-    rc = ess_launch_attn_merge(ctx, B, T, ns0 + ns1, a->out_bf16, a->lse, st);
+    chk.need[6] += check_extra;
+    rc = ess_launch_attn_merge(ctx, B, T, ns0 + ns1, a->out_bf16, a->lse, st, nullptr, 0, 0, confine_da ? &chk : nullptr);
     if (rc != ESS_OK) return rc;
     ESS_END(4);
     return ESS_OK;
@@ -610,14 +632,14 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     // Attn0 of the whole batch in one launch (behind the first fetch it could not start much earlier
     // anyway): one workgroup per CU, the same splits as in the other schedules
     rc = ess_launch_attn_partial(ctx, q16, cache->slot_pool, ctx->hit_list, ctx->n_hit, B, T, 0, ns0, ctx->side, 0,
-                                 confine2 ? ess_xcd{ctx->tickets + 6, mask2} : ess_xcd{nullptr, 0});
+                                 confine2 ? ess_xcd{ctx->tickets + 6, mask2, chk.need + 6} : ess_xcd{nullptr, 0, nullptr});
     if (rc != ESS_OK) return rc;
     if (aev) {
       ESS_HIP(hipEventRecord(aev[1], ctx->side));
       ESS_HIP(hipEventRecord(aev[2], ctx->side));
     }
     rc = ess_launch_attn_partial(ctx, q16, c0.slot_pool, ctx->miss_list, ctx->n_miss, hB[0], T, ns0, ns1, ctx->side, hb0[0],
-                                 confine2 ? ess_xcd{ctx->tickets + 7, mask2} : ess_xcd{nullptr, 0});
+                                 confine2 ? ess_xcd{ctx->tickets + 7, mask2, chk.need + 7} : ess_xcd{nullptr, 0, nullptr});
     if (rc != ESS_OK) return rc;
     // each half is merged on the stream its Attn1 ran on: only half a merge is left behind the last fetch
     rc = ess_launch_attn_merge(ctx, hB[0], T, ns0 + ns1, a->out_bf16, a->lse, ctx->side, nullptr, 0, hb0[0]);
@@ -634,7 +656,8 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
                                  ctx->n_miss + bt1, hB[1], T, ns0, ns1, st, hb0[1]);
     if (rc != ESS_OK) return rc;
     ESS_HIP(hipStreamWaitEvent(st, ctx->ev_fill[1], 0));          // Attn0 of the second half ran on the side stream
-    rc = ess_launch_attn_merge(ctx, hB[1], T, ns0 + ns1, a->out_bf16, a->lse, st, nullptr, 0, hb0[1]);
+    chk.need[1] += check_extra;
+    rc = ess_launch_attn_merge(ctx, hB[1], T, ns0 + ns1, a->out_bf16, a->lse, st, nullptr, 0, hb0[1], confine ? &chk : nullptr);
     if (rc != ESS_OK) return rc;
     ESS_END(4);
     return ESS_OK;
@@ -699,6 +722,19 @@ int ess_set_overlap_threshold(ess_ctx* ctx, int32_t misses_per_seq) {
   if (misses_per_seq < 0) return ess_fail(ESS_ERR_INVALID_ARG, "threshold %d", misses_per_seq);
   ctx->auto_threshold = misses_per_seq;
   ctx->auto_calibrated = true;        // the caller's threshold is taken as measured for its workload: it applies alone
+  return ESS_OK;
+}
+
+int ess_last_confined(const ess_ctx* ctx, int32_t* fetches) {
+  if (!ctx || !fetches) return ess_fail(ESS_ERR_INVALID_ARG, "NULL argument");
+  *fetches = ctx->last_confined;
+  return ESS_OK;
+}
+
+int ess_selfcheck_inject(ess_ctx* ctx, int32_t extra_items) {
+  if (!ctx) return ess_fail(ESS_ERR_INVALID_ARG, "context is NULL");
+  if (extra_items < 0) return ess_fail(ESS_ERR_INVALID_ARG, "extra_items %d", extra_items);
+  ctx->check_extra = (uint32_t)extra_items;
   return ESS_OK;
 }
 
@@ -801,6 +837,8 @@ int ess_get_stats(ess_ctx* ctx, ess_stats* host_out, void* stream) {
   if (!ctx || !host_out) return ess_fail(ESS_ERR_INVALID_ARG, "NULL argument");
   ESS_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
   ESS_HIP(hipStreamSynchronize(ctx->side));
+  const int rc = check_tickets(ctx);
+  if (rc != ESS_OK) return rc;
   unsigned long long h[4];
   ESS_HIP(hipMemcpy(h, ctx->stats, sizeof(h), hipMemcpyDeviceToHost));
   host_out->steps = h[0];

@@ -46,6 +46,8 @@ struct ess_ctx {
   uint32_t* topk_cnt;           // [ESS_TOPK_SHARED_ROWS] candidates listed per row: zero between steps
   uint32_t* tickets;            // [ESS_N_TICKETS] work counters of kernels that run beside a fetch (see ess_xcd)
   bool xcds_even;               // workgroups go round the eight XCDs evenly (probed at creation): fetches may be confined
+  int last_confined;            // fetches of the latest decode step that were confined to ESS_FETCH_XCD_MASK
+  uint32_t check_extra;         // ess_selfcheck_inject: work items the next confined step's check expects on top
   size_t ws_bytes;
   // overlap switch (ESS_FLAG_AUTO): per-sequence miss counts of the latest bookkeeping, written by the
   // kernel into pinned host memory and read by the host, without a synchronisation, at the next step
@@ -74,6 +76,16 @@ struct ess_ctx {
 struct ess_xcd {
   uint32_t* ticket;
   uint32_t avoid;               // bit i: XCD i takes no work
+  uint32_t* host_need;          // host memory, may be null: the launcher leaves the number of work items here
+};
+// A workgroup takes one item at most, so every item is served only if the launch puts enough workgroups on
+// the XCDs that work: the launch size counts on workgroups going round the XCDs in turn.  The last kernel
+// of a step compares the counters (workgroups that asked) with the items there were, and raises `flag`
+// (pinned host memory) where a counter fell short, which the host reports at its next call.
+struct ess_ticket_check {
+  const uint32_t* tickets;      // null: no check
+  int32_t* flag;
+  uint32_t need[ESS_N_TICKETS];
 };
 #ifdef __HIPCC__
 __device__ __forceinline__ int ess_xcc_id() { return __builtin_amdgcn_s_getreg(20 | (3 << 11)) & 15; }   // hwreg XCC_ID, bits 3:0
@@ -89,6 +101,7 @@ __device__ __forceinline__ int ess_take_item(int static_item, int items, const e
 #endif
 // workgroups to launch so that `items` of them sit on XCDs that take work (any 8 consecutive workgroups cover all 8 XCDs)
 inline int ess_xcd_grid(int items, const ess_xcd& x) {
+  if (x.ticket && x.host_need) *x.host_need = (uint32_t)items;
   if (!x.ticket || !x.avoid) return items;
   const int off = __builtin_popcount(x.avoid & 0xffu);
   return (items + (8 - off) - 1) / (8 - off) * 8 + 8;
@@ -109,10 +122,10 @@ int ess_launch_index_score(const ess_config& c, const uint8_t* q, const float* w
                            const int32_t* ctx_len, int B, int T, float* score, hipStream_t st,
                            const int32_t* block_table = nullptr, int n_pages = 0,
                            // optional: events that take the kernel's own start and end times
-                           hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr, ess_xcd xcd = ess_xcd{nullptr, 0});
+                           hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr, ess_xcd xcd = ess_xcd{nullptr, 0, nullptr});
 // xcd: ticket[0] and ticket[1] are used (two kernels)
 int ess_launch_topk(ess_ctx* ctx, const float* score, const int32_t* ctx_len, int B, int T, int32_t* idx,
-                    hipStream_t st, ess_xcd xcd = ess_xcd{nullptr, 0});
+                    hipStream_t st, ess_xcd xcd = ess_xcd{nullptr, 0, nullptr});
 size_t ess_topk_cand_bytes();
 // fill kernel (used instead of hipMemsetAsync so that callers may capture the stream in a graph)
 int ess_launch_calib_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
@@ -127,7 +140,7 @@ int ess_launch_cache_reset(const ess_config& c, const ess_cache& cache, int B, h
 // library's workspace arrays are shifted inside
 int ess_launch_bookkeeping(ess_ctx* ctx, const ess_cache& cache, const int32_t* idx, int B, int T, int kk,
                            uint32_t step, int32_t* slot_idx, int32_t* miss_count_out, hipStream_t st, int b0 = 0,
-                           bool count_step = true, ess_xcd xcd = ess_xcd{nullptr, 0}, uint32_t* zero_tickets = nullptr,
+                           bool count_step = true, ess_xcd xcd = ess_xcd{nullptr, 0, nullptr}, uint32_t* zero_tickets = nullptr,
                            int n_zero_tickets = 0);
 // only_xcds != 0: the fetch runs on these XCDs alone (`wgs` workgroups there, rows handed out through `ticket`)
 int ess_launch_fill(ess_ctx* ctx, const ess_cache& cache, int B, hipStream_t st, int b0 = 0, int wgs = 64,
@@ -138,9 +151,10 @@ int ess_launch_gather_rows(const ess_config& c, const uint8_t* slot_pool, const 
 // partial results starting at partial index `split0`
 int ess_launch_attn_partial(ess_ctx* ctx, const void* q, const uint8_t* slot_pool, const int32_t* list,
                             const int32_t* n_list, int B, int T, int split0, int nsplit, hipStream_t st, int b0 = 0,
-                            ess_xcd xcd = ess_xcd{nullptr, 0});
+                            ess_xcd xcd = ess_xcd{nullptr, 0, nullptr});
 int ess_attn_min_splits(const ess_config& c);   // fewest splits a list of k entries may be cut into
 // zero_cnt (may be NULL): n_zero int32 counters that the merge kernel also clears; b0 = first sequence of the
 // sub-batch of B sequences (out_bf16 and lse are the whole batch's arrays)
 int ess_launch_attn_merge(ess_ctx* ctx, int B, int T, int nsplit_total, void* out_bf16, float* lse,
-                          hipStream_t st, int32_t* zero_cnt = nullptr, int n_zero = 0, int b0 = 0);
+                          hipStream_t st, int32_t* zero_cnt = nullptr, int n_zero = 0, int b0 = 0,
+                          const ess_ticket_check* check = nullptr);

@@ -489,9 +489,15 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
 __global__ __launch_bounds__(256) void k_attn_merge(const float* __restrict__ o_part, const float* __restrict__ lse_part,
                                                     int H, int nsplit, int total_rows, uint16_t* __restrict__ out,
                                                     float* __restrict__ lse_out, int32_t* __restrict__ zero_cnt,
-                                                    int n_zero) {
+                                                    int n_zero, ess_ticket_check chk) {
   if (zero_cnt && blockIdx.x == 0)
     for (int i = threadIdx.x; i < n_zero; i += 256) zero_cnt[i] = 0;
+  if (chk.tickets && blockIdx.x == 0 && threadIdx.x == 0) {
+    bool short_of = false;
+#pragma unroll
+    for (int i = 0; i < ESS_N_TICKETS; ++i) short_of |= chk.need[i] != 0 && chk.tickets[i] < chk.need[i];
+    if (short_of) *chk.flag = 1;
+  }
   const int rowi = blockIdx.x * 4 + (threadIdx.x >> 6);      // bt*H + h
   if (rowi >= total_rows) return;
   const int lane = threadIdx.x & 63;
@@ -576,13 +582,15 @@ int ess_launch_attn_partial(ess_ctx* ctx, const void* q, const uint8_t* slot_poo
 }
 
 int ess_launch_attn_merge(ess_ctx* ctx, int B, int T, int nsplit_total, void* out_bf16, float* lse, hipStream_t st,
-                          int32_t* zero_cnt, int n_zero, int b0) {
+                          int32_t* zero_cnt, int n_zero, int b0, const ess_ticket_check* check) {
   const int H = ctx->cfg.attn_heads;
+  ess_ticket_check chk{};
+  if (check) chk = *check;
   const int rows = B * T * H;
   const size_t r0 = (size_t)b0 * T * H;                       // first (bt, h) row of the sub-batch
   hipLaunchKernelGGL(k_attn_merge, dim3((rows + 3) / 4), dim3(256), 0, st, ctx->o_part + r0 * ESS_MAX_SPLITS * ESS_LATENT_DIM,
                      ctx->lse_part + r0 * ESS_MAX_SPLITS, H, nsplit_total, rows,
-                     static_cast<uint16_t*>(out_bf16) + r0 * ESS_LATENT_DIM, lse ? lse + r0 : nullptr, zero_cnt, n_zero);
+                     static_cast<uint16_t*>(out_bf16) + r0 * ESS_LATENT_DIM, lse ? lse + r0 : nullptr, zero_cnt, n_zero, chk);
   ESS_HIP(hipGetLastError());
   return ESS_OK;
 }

@@ -529,15 +529,16 @@ int ess_launch_topk(ess_ctx* ctx, const float* score, const int32_t* ctx_len, in
     parts = 256 / rows;
     if (parts > 8) parts = 8;
   }
-  const ess_xcd x0 = xcd, x1 = ess_xcd{xcd.ticket ? xcd.ticket + 1 : nullptr, xcd.avoid};
+  const ess_xcd x0 = xcd, x1 = ess_xcd{xcd.ticket ? xcd.ticket + 1 : nullptr, xcd.avoid,
+                                                       xcd.host_need ? xcd.host_need + 1 : nullptr};
   if (parts > 1) {
-    const dim3 g1 = xcd.ticket ? dim3(ess_xcd_grid(parts * rows, xcd)) : dim3(parts, rows);
+    const dim3 g1 = xcd.ticket ? dim3(ess_xcd_grid(parts * rows, x0)) : dim3(parts, rows);
     hipLaunchKernelGGL(k_topk<1>, g1, dim3(NT), 0, st, score, ctx_len, T, c.max_ctx, c.topk, IB, idx,
                        ctx->topk_cand, ctx->topk_cnt, x0, rows, parts);
-    hipLaunchKernelGGL(k_topk<2>, dim3(ess_xcd_grid(rows, xcd)), dim3(NT), 0, st, score, ctx_len, T, c.max_ctx, c.topk, IB, idx,
+    hipLaunchKernelGGL(k_topk<2>, dim3(ess_xcd_grid(rows, x1)), dim3(NT), 0, st, score, ctx_len, T, c.max_ctx, c.topk, IB, idx,
                        ctx->topk_cand, ctx->topk_cnt, x1, rows, 1);
   } else {
-    hipLaunchKernelGGL(k_topk<0>, dim3(ess_xcd_grid(rows, xcd)), dim3(NT), 0, st, score, ctx_len, T, c.max_ctx, c.topk, IB, idx,
+    hipLaunchKernelGGL(k_topk<0>, dim3(ess_xcd_grid(rows, x1)), dim3(NT), 0, st, score, ctx_len, T, c.max_ctx, c.topk, IB, idx,
                        ctx->topk_cand, ctx->topk_cnt, x1, rows, 1);
   }
   ESS_HIP(hipGetLastError());

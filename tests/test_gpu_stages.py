@@ -348,6 +348,59 @@ def test_decode_step_offloaded_vs_oracle(ess_lib, flags, fmt):
                 assert torch.equal(o0, o1) and torch.equal(l0, l1)
 
 
+def test_selfcheck_of_confined_step(ess_lib):
+    """A step that confines a fetch ends with a check that every ticket-fed launch had enough workgroups.
+    The test hook makes that check expect more work items than there are: the step itself is complete
+    (compared with the oracle), the NEXT call reports ESS_ERR_INTERNAL and does nothing, and the steps
+    after it run unconfined and still match the oracle."""
+    from paper_2512_10576_amd import binding as bnd
+    print("selfcheck of a confined step", flush=True)
+    B, T, Hi, Di, L, k, H, S = 3, 2, 64, 128, 6000, 512, 128, 1500
+    qi, w, key = synth.indexer_inputs(43, B, T, Hi, Di, L, 8, 8, 16)
+    ctx_len = torch.tensor([6000, 4321, 5555], dtype=torch.int32)
+    host = synth.latent_rows_bf16(43, B * L).reshape(B, L, 1152)
+    hp = torch.empty((B, L, 1152), dtype=torch.uint8, pin_memory=True)
+    hp.copy_(host)
+    ctx = _ctx(ess_lib, max_batch=B, max_q_tokens=T, max_ctx=L, idx_heads=Hi, idx_dim=Di, topk=k, attn_heads=H,
+               slots_per_seq=S, flags=4, latent_fmt=0)
+    cache = bnd.Cache.allocate(ctx.cfg, B, host_pool=hp,
+                               slot_pool=torch.full((B, S, 1152), 0x7F, dtype=torch.uint8, device="cuda"))
+    ctx.cache_reset(cache, B)
+    ctx.set_overlap_threshold(400)
+    oc = O.SlotCache(B, L, S)
+    opool = np.full((B, S, 1152), 0x7F, np.uint8)
+    trace = synth.TopkTrace(11, ctx_len, T, k, 0.7)
+    idx_out = torch.empty((B, T, k), dtype=torch.int32, device="cuda")
+    out = torch.empty((B, T, H, 512), dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty((B, T, H), dtype=torch.float32, device="cuda")
+    mc = torch.empty((B,), dtype=torch.int32, device="cuda")
+    dev = [x.cuda() for x in (qi, w, key, ctx_len)]
+    confined = []
+    for step in range(1, 5):
+        q = synth.attn_query(60 + step, B, T, H)
+        ov = trace.next()
+        r = O.decode_step(qi.numpy(), w.numpy(), key.numpy(), ctx_len.numpy(), k, oc, opool, host.numpy(),
+                          _qbits(q), 0, 576 ** -0.5, step, ov.numpy())
+        args = (cache, dev[0], dev[1], dev[2], dev[3], q.cuda(), step, idx_out, out, lse, mc, ov.cuda())
+        if step == 2:
+            ctx.selfcheck_inject(100000)         # step 1 missed everything: step 2 splits the batch and confines
+        if step == 3:                            # the flag of step 2 is seen here; nothing is launched
+            with pytest.raises(bnd.EssError) as err:
+                ctx.decode_step(*args)
+            assert err.value.code == bnd.ESS_ERR_INTERNAL
+        ctx.decode_step(*args)
+        torch.cuda.synchronize()
+        confined.append(ctx.last_confined())
+        assert np.array_equal(mc.cpu().numpy(), r["miss_count"])
+        assert np.array_equal(cache.slot_of.cpu().numpy(), oc.slot_of)
+        assert np.array_equal(cache.slot_pool.cpu().numpy(), opool)
+        _check_attn(out, lse, r["out"], r["lse"])
+    st = ctx.get_stats()                         # no flag pending: the later steps raised none
+    assert st["steps"] == 4
+    ctx.close()
+    assert confined[0] == 0 and confined[1] >= 1 and confined[2:] == [0, 0], confined
+
+
 @pytest.mark.parametrize("T,k,L,S,fmt,flags", [(3, 512, 6000, 1800, 0, 0), (4, 2048, 12000, 8500, 1, 2)])
 def test_decode_step_three_and_four_query_tokens(ess_lib, T, k, L, S, fmt, flags):
     """More than two query tokens per sequence (the index score then takes two passes over the keys);
