@@ -60,6 +60,7 @@ def test_cfg4_full_size_sampled_sequences(ess_lib):
     sample = (0, 40, 63)
     oracles = {b: (O.SlotCache(1, L, S), np.zeros((1, S, 1152), np.uint8)) for b in sample}
     lens = W["ctx_len"].cpu().numpy()
+    schedules = []
     for step in range(1, steps + 1):
         bench.run_steps(W, step, 1)
         torch.cuda.synchronize()
@@ -91,7 +92,10 @@ def test_cfg4_full_size_sampled_sequences(ess_lib):
         res = cache.token_of >= 0
         back = torch.gather(cache.slot_of, 1, cache.token_of.clamp(min=0).long())
         assert bool((back[res] == torch.arange(S, device="cuda").expand(B, S)[res]).all())
+        schedules.append((ctx.last_overlap(), ctx.last_confined()))
     ctx.close()
+    # the launch configuration bench.py times: split batch, both fetches confined, kernels beside them by ticket
+    assert schedules[0] == (0, 0) and schedules[-1] == (1, 2), schedules
 
 
 def test_cfg5_full_size_sampled_sequences(ess_lib):
@@ -135,4 +139,6 @@ def test_cfg5_full_size_sampled_sequences(ess_lib):
                     assert np.array_equal(W["idx_out"][b, t].cpu().numpy(), np.sort(ref_idx[0, t]))
         sel = torch.from_numpy(ov.reshape(B, T * k).astype(np.int64)).cuda()
         assert bool((torch.gather(cache.slot_of, 1, sel) >= 0).all())
+    schedule = (ctx.last_overlap(), ctx.last_confined())
     ctx.close()
+    assert schedule[0] == 1 and schedule[1] >= 1, schedule     # split batch with a confined fetch, as bench.py runs it
