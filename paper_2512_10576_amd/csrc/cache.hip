@@ -528,8 +528,8 @@ __global__ void k_xcd_probe(uint32_t* hist) {
   if (threadIdx.x == 0) atomicAdd(&hist[ess_xcc_id() & 7], 1u);
 }
 
-// Are 64 workgroups spread evenly over eight XCDs (8 each)?  Only then may a kernel count on finding
-// seven of any eight consecutive workgroups off one XCD.  `hist8`: eight zeroed counters, zero again on return.
+// Are 64 workgroups spread evenly over eight XCDs (8 each)?  Only then may a launch count on finding
+// eight minus n of any eight consecutive workgroups off a set of n XCDs.  `hist8`: eight zeroed counters, zero again on return.
 int ess_probe_xcds(uint32_t* hist8, bool* even) {
   hipLaunchKernelGGL(k_xcd_probe, dim3(64), dim3(64), 0, 0, hist8);
   ESS_HIP(hipGetLastError());

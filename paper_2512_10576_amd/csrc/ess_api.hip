@@ -145,7 +145,7 @@ int run_cache_step(ess_ctx* ctx, const ess_cache& cache, const int32_t* idx, int
                    int32_t* slot_idx, int32_t* miss_count, hipStream_t st, bool* fill_pending, int b0 = 0,
                    int half = 0, hipEvent_t* fill_ev = nullptr, int fill_wgs = 64, bool confine = false) {
   *fill_pending = false;
-  // confine: the fetch runs on one XCD and the kernels beside it stay off that XCD, taking their work
+  // confine: the fetch runs on the XCDs of ESS_FETCH_XCD_MASK and the kernels beside it stay off them, taking their work
   // through counters that this bookkeeping clears (counter 0: the fetch itself)
   int rc = ess_launch_bookkeeping(ctx, cache, idx, B, T, kk, step, slot_idx, miss_count, st, b0, half == 0,
                                   ess_xcd{nullptr, 0, nullptr}, confine ? ctx->tickets : nullptr, 5);
@@ -526,7 +526,7 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
       adjacent = false;
     }
     // second half of the split-batch schedule: these kernels run beside the first fetch, which is confined
-    // to one XCD; they stay off it (counters 1..4, cleared by the first half's bookkeeping)
+    // to the XCDs of ESS_FETCH_XCD_MASK; they stay off those (counters 1..4, cleared by the first half's bookkeeping)
     const bool beside = confine && h == 1;
     auto xcd_of = [&](int counter) { return beside ? ess_xcd{ctx->tickets + counter, ESS_FETCH_XCD_MASK, chk.need + counter} : ess_xcd{nullptr, 0, nullptr}; };
     if (a->block_table)     // paged: one pool for the whole batch, the table rows of this sub-batch
