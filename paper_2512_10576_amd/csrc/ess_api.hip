@@ -79,7 +79,7 @@ WsLayout ws_layout(const ess_config& c) {
   w.fill_tok = take(B * T * k * 4);
   w.fill_slot = take(B * T * k * 4);
   w.miss_cnt = take(B * 4);
-  w.o_part = take(B * T * ESS_MAX_SPLITS * H * ESS_LATENT_DIM * 4);
+  w.o_part = take(B * T * ESS_MAX_SPLITS * H * ESS_LATENT_DIM * 2);
   w.lse_part = take(B * T * ESS_MAX_SPLITS * H * 4);
   w.stats = take(4 * 8);
   w.zero_row = take(ESS_ZERO_ROW_BYTES);
@@ -221,7 +221,7 @@ int ess_create(const ess_config* cfg, ess_ctx** out) {
   ctx->fill_tok = reinterpret_cast<int32_t*>(base + w.fill_tok);
   ctx->fill_slot = reinterpret_cast<int32_t*>(base + w.fill_slot);
   ctx->miss_cnt = reinterpret_cast<int32_t*>(base + w.miss_cnt);
-  ctx->o_part = reinterpret_cast<float*>(base + w.o_part);
+  ctx->o_part = reinterpret_cast<uint16_t*>(base + w.o_part);
   ctx->lse_part = reinterpret_cast<float*>(base + w.lse_part);
   ctx->stats = reinterpret_cast<unsigned long long*>(base + w.stats);
   ctx->zero_row = base + w.zero_row;

@@ -38,7 +38,7 @@ struct ess_ctx {
   int32_t* fill_tok;            // [B,T*k] token to fetch
   int32_t* fill_slot;           // [B,T*k] slot to fetch into
   int32_t* miss_cnt;            // [B]
-  float* o_part;                // [B*T, ESS_MAX_SPLITS, H, 512]
+  uint16_t* o_part;             // [B*T, ESS_MAX_SPLITS, H, 512] partial attention results, fp16 bits
   float* lse_part;              // [B*T, ESS_MAX_SPLITS, H]
   unsigned long long* stats;    // [4]
   uint8_t* zero_row;            // ESS_ZERO_ROW_BYTES of zeros, never written: source of masked attention rows

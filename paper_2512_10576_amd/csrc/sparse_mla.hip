@@ -24,6 +24,12 @@
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+// Partial results travel from the partial-attention kernels to the merge kernel as fp16: they are
+// softmax-normalised (|value| <= the largest entry value), fp16 keeps 11 bits of them while the merged
+// output is rounded to bf16's 8, and the traffic between the two kernels, which is most of what both
+// cost beyond their tile loops, is halved.  The split weights (log-sum-exp) stay fp32.
+typedef _Float16 halfx4 __attribute__((ext_vector_type(4)));
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
 
 namespace {
 
@@ -193,7 +199,7 @@ template <int FMT>
 __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
     const uint16_t* __restrict__ q, const uint8_t* __restrict__ pool, const int32_t* __restrict__ list,
     const int32_t* __restrict__ n_list, int T, int H, int kk, int S, int row_stride, float scale_log2e, int split0,
-    int nsplit, float* __restrict__ o_part, float* __restrict__ lse_part, const uint8_t* __restrict__ zero_row,
+    int nsplit, _Float16* __restrict__ o_part, float* __restrict__ lse_part, const uint8_t* __restrict__ zero_row,
     ess_xcd xcd, int n_bt, int n_hg) {
   extern __shared__ __align__(16) uint8_t lds[];
   // work item = (split, bt, head group): by workgroup index, or in arrival order off the XCDs to be avoided
@@ -471,11 +477,13 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
     acc_read(o);
     if (head < H) {
       const size_t prow = ((size_t)bt * ESS_MAX_SPLITS + split0 + split) * H + head;
-      float* op = o_part + prow * ESS_LATENT_DIM;
+      _Float16* op = o_part + prow * ESS_LATENT_DIM;
 #pragma unroll
       for (int vb = 0; vb < VBLOCKS; ++vb) {
-        const float4 ov = make_float4(o[4 * vb] * inv, o[4 * vb + 1] * inv, o[4 * vb + 2] * inv, o[4 * vb + 3] * inv);
-        *reinterpret_cast<float4*>(op + vb * 16 + g * 4) = ov;
+        floatx4 ov = floatx4{o[4 * vb] * inv, o[4 * vb + 1] * inv, o[4 * vb + 2] * inv, o[4 * vb + 3] * inv};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) ov[i] = __builtin_amdgcn_fmed3f(ov[i], -65504.f, 65504.f);   // an average of entry values: saturate, never inf
+        *reinterpret_cast<halfx4*>(op + vb * 16 + g * 4) = __builtin_convertvector(ov, halfx4);   // round to nearest even
       }
       if (g == 0) lse_part[prow] = l_tot > 0.f ? (m_ref + log2f(l_tot)) * kLn2 : -__builtin_inff();
     }
@@ -486,7 +494,7 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
 // The partial results of four splits are requested before any is used (the kernel is a chain of
 // dependent loads otherwise); those of empty splits are not read at all.  `zero_cnt` (may be NULL): n_zero counters the first workgroup clears,
 // for steps that have no other kernel to do it in.
-__global__ __launch_bounds__(256) void k_attn_merge(const float* __restrict__ o_part, const float* __restrict__ lse_part,
+__global__ __launch_bounds__(256) void k_attn_merge(const _Float16* __restrict__ o_part, const float* __restrict__ lse_part,
                                                     int H, int nsplit, int total_rows, uint16_t* __restrict__ out,
                                                     float* __restrict__ lse_out, int32_t* __restrict__ zero_cnt,
                                                     int n_zero, ess_ticket_check chk) {
@@ -518,23 +526,20 @@ __global__ __launch_bounds__(256) void k_attn_merge(const float* __restrict__ o_
 #pragma unroll
     for (int s0 = 0; s0 < ESS_MAX_SPLITS; s0 += 4) {
       if (s0 >= nsplit) break;
-      float4 x[4], y[4];
+      halfx8 xy[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        x[u] = y[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (lsv[s0 + u] != -__builtin_inff()) {                 // same for the whole wave: one row per wave
-          const float4* op = reinterpret_cast<const float4*>(o_part + (base + (size_t)(s0 + u) * H) * ESS_LATENT_DIM + lane * 8);
-          x[u] = op[0];
-          y[u] = op[1];
-        }
+        xy[u] = halfx8{0, 0, 0, 0, 0, 0, 0, 0};
+        if (lsv[s0 + u] != -__builtin_inff())                   // same for the whole wave: one row per wave
+          xy[u] = *reinterpret_cast<const halfx8*>(o_part + (base + (size_t)(s0 + u) * H) * ESS_LATENT_DIM + lane * 8);
       }
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         if (lsv[s0 + u] == -__builtin_inff()) continue;
         const float wgt = __expf(lsv[s0 + u] - mx);
         den += wgt;
-        a[0] += wgt * x[u].x; a[1] += wgt * x[u].y; a[2] += wgt * x[u].z; a[3] += wgt * x[u].w;
-        a[4] += wgt * y[u].x; a[5] += wgt * y[u].y; a[6] += wgt * y[u].z; a[7] += wgt * y[u].w;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) a[i] += wgt * (float)xy[u][i];
       }
     }
   }
@@ -562,7 +567,7 @@ int ess_launch_attn_partial(ess_ctx* ctx, const void* q, const uint8_t* slot_poo
   const float sc = c.sm_scale * kLog2e;
   const uint16_t* qq = static_cast<const uint16_t*>(q);
   // partial results of sequence b0 onward
-  float* op = ctx->o_part + (size_t)b0 * T * ESS_MAX_SPLITS * c.attn_heads * ESS_LATENT_DIM;
+  _Float16* op = reinterpret_cast<_Float16*>(ctx->o_part) + (size_t)b0 * T * ESS_MAX_SPLITS * c.attn_heads * ESS_LATENT_DIM;
   float* lp = ctx->lse_part + (size_t)b0 * T * ESS_MAX_SPLITS * c.attn_heads;
   if (c.latent_fmt == ESS_FMT_BF16) {
     constexpr int lds = tr_lds_bytes(ESS_FMT_BF16);
@@ -588,7 +593,8 @@ int ess_launch_attn_merge(ess_ctx* ctx, int B, int T, int nsplit_total, void* ou
   if (check) chk = *check;
   const int rows = B * T * H;
   const size_t r0 = (size_t)b0 * T * H;                       // first (bt, h) row of the sub-batch
-  hipLaunchKernelGGL(k_attn_merge, dim3((rows + 3) / 4), dim3(256), 0, st, ctx->o_part + r0 * ESS_MAX_SPLITS * ESS_LATENT_DIM,
+  hipLaunchKernelGGL(k_attn_merge, dim3((rows + 3) / 4), dim3(256), 0, st,
+                     reinterpret_cast<const _Float16*>(ctx->o_part) + r0 * ESS_MAX_SPLITS * ESS_LATENT_DIM,
                      ctx->lse_part + r0 * ESS_MAX_SPLITS, H, nsplit_total, rows,
                      static_cast<uint16_t*>(out_bf16) + r0 * ESS_LATENT_DIM, lse ? lse + r0 : nullptr, zero_cnt, n_zero, chk);
   ESS_HIP(hipGetLastError());
