@@ -47,7 +47,7 @@ WORKLOADS = {
 }
 # HBM bytes per launch of the index-score kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (see profiles/); None until measured for that workload
-MEASURED_TRAFFIC_BYTES = {"cfg4": 958756 * 1024}   # HBM bytes of the index-score kernel per step, profiles/pmc_traffic_cfg4.md
+MEASURED_TRAFFIC_BYTES = {"cfg4": 958042 * 1024}   # HBM bytes of the index-score kernel per step, profiles/pmc_traffic_cfg4.md
 
 
 def build_workload(name, steps_needed, overlap="auto", layers=None, rho=None, ratio=None):
