@@ -348,13 +348,14 @@ def test_decode_step_offloaded_vs_oracle(ess_lib, flags, fmt):
                 assert torch.equal(o0, o1) and torch.equal(l0, l1)
 
 
-def test_selfcheck_of_confined_step(ess_lib):
+@pytest.mark.parametrize("via", ["decode_step", "get_stats"])
+def test_selfcheck_of_confined_step(ess_lib, via):
     """A step that confines a fetch ends with a check that every ticket-fed launch had enough workgroups.
     The test hook makes that check expect more work items than there are: the step itself is complete
-    (compared with the oracle), the NEXT call reports ESS_ERR_INTERNAL and does nothing, and the steps
-    after it run unconfined and still match the oracle."""
+    (compared with the oracle), the NEXT call (a decode step, which then does nothing, or a statistics
+    read) reports ESS_ERR_INTERNAL, and the steps after it run unconfined and still match the oracle."""
     from paper_2512_10576_amd import binding as bnd
-    print("selfcheck of a confined step", flush=True)
+    print("selfcheck of a confined step, reported by", via, flush=True)
     B, T, Hi, Di, L, k, H, S = 3, 2, 64, 128, 6000, 512, 128, 1500
     qi, w, key = synth.indexer_inputs(43, B, T, Hi, Di, L, 8, 8, 16)
     ctx_len = torch.tensor([6000, 4321, 5555], dtype=torch.int32)
@@ -386,7 +387,10 @@ def test_selfcheck_of_confined_step(ess_lib):
             ctx.selfcheck_inject(100000)         # step 1 missed everything: step 2 splits the batch and confines
         if step == 3:                            # the flag of step 2 is seen here; nothing is launched
             with pytest.raises(bnd.EssError) as err:
-                ctx.decode_step(*args)
+                if via == "decode_step":
+                    ctx.decode_step(*args)
+                else:
+                    ctx.get_stats()
             assert err.value.code == bnd.ESS_ERR_INTERNAL
         ctx.decode_step(*args)
         torch.cuda.synchronize()
