@@ -190,7 +190,10 @@ int ess_gather_latent(ess_ctx* ctx, const ess_cache* cache, const int32_t* idx, 
  *   z_s = sm_scale * q . c_s ; lse = log sum_s exp z_s ; out = sum_s exp(z_s - lse) c_s[:512]
  * over the entries slot_idx[b,t,:] >= 0 of slot_pool [B,S,row_stride].  bf16
  * operands (fp8 entries are dequantised to bf16), fp32 accumulation and softmax.
- * Empty selection: out = 0, lse = -inf. */
+ * The entry list is processed in several parts whose normalised results are
+ * merged; they are held as fp16 in between (11 significant bits, against the 8
+ * of the bf16 output) and saturate at +-65504, so entry values are expected to
+ * stay below that magnitude.  Empty selection: out = 0, lse = -inf. */
 int ess_sparse_mla_decode(ess_ctx* ctx, const void* q_bf16, const uint8_t* slot_pool,
                           const int32_t* slot_idx, int32_t B, int32_t T, void* out_bf16, float* lse,
                           void* stream);
