@@ -281,6 +281,32 @@ def test_sparse_mla_decode_vs_oracle(ess_lib, name, B, T, H, L, k, fmt, scale):
     ctx.close()
 
 
+def test_sparse_mla_large_values_saturate(ess_lib):
+    """Entry values beyond the fp16 range: the intermediate results saturate at +-65504 (documented limit),
+    the output stays finite; values inside the range are not affected by the clamp."""
+    print("sparse_mla large values", flush=True)
+    B, T, H, L, k = 1, 1, 128, 256, 64
+    vals = {0: 3.0e5, 1: -3.0e5, 2: 6.0e4}                     # value columns 0, 1: out of range; column 2: inside
+    rows = torch.zeros((B, L, 576), dtype=torch.bfloat16)
+    for col, v in vals.items():
+        rows[..., col] = v
+    pool = rows.view(torch.uint8).reshape(B, L, 1152)
+    q = torch.zeros((B, T, H, 576), dtype=torch.bfloat16)        # all logits 0: the output is the plain average
+    idx = np.arange(k, dtype=np.int32).reshape(B, T, k)
+    ctx = _ctx(ess_lib, max_batch=B, max_q_tokens=T, max_ctx=L, idx_heads=4, idx_dim=32, topk=k, attn_heads=H)
+    out = torch.full((B, T, H, 512), 9.0, dtype=torch.bfloat16, device="cuda")
+    lse = torch.full((B, T, H), 9.0, dtype=torch.float32, device="cuda")
+    ctx.sparse_mla_decode(q.cuda(), pool.cuda(), torch.from_numpy(idx).cuda(), out, lse)
+    torch.cuda.synchronize()
+    o = out.float().cpu().numpy()
+    assert np.all(np.isfinite(o))
+    assert np.all(o[..., 0] == 65536.0) and np.all(o[..., 1] == -65536.0)      # bf16 image of +-65504
+    assert np.all(np.abs(o[..., 2] - 6.0e4) <= 6.0e4 * 2.0 ** -8)
+    assert np.all(o[..., 3:] == 0.0)
+    assert np.allclose(lse.cpu().numpy(), np.log(k), atol=1e-4)
+    ctx.close()
+
+
 # ---------------------------------------------------------------- whole step
 @pytest.mark.parametrize("flags,fmt", [(0, 0), (1, 0), (2, 0), (4, 0), (0, 1), (2, 1), (4, 1)])
 def test_decode_step_offloaded_vs_oracle(ess_lib, flags, fmt):
