@@ -128,3 +128,55 @@ def test_single_sequence_single_head_block(ess_lib):
     row = pool.view(torch.bfloat16).reshape(L, 576)[int(r["idx"][0, 0, 0]), :512].float().numpy()
     assert np.array_equal(out.float().cpu().numpy()[0, 0, 0], row)
     ctx.close()
+
+
+@pytest.mark.parametrize("B,ctx_lens", [(1, [5000]), (2, [5000, 37]), (5, [5000, 4000, 0, 3000, 2111]), (17, None)])
+def test_switch_with_confined_fetches_at_odd_batch_sizes(ess_lib, B, ctx_lens):
+    """The overlap switch with a threshold of zero (split batch whenever there are two sequences, fetches
+    confined, kernels beside them by ticket) at batch sizes that do not divide evenly, with an empty
+    sequence among them, against the plain DA schedule: bit-identical outputs and cache state."""
+    from paper_2512_10576_amd import binding as bnd
+    print("edges: switch / confinement at batch", B, flush=True)
+    T, Hi, Di, L, k, H, S = 2, 64, 128, 5000, 512, 128, 1300
+    qi, w, key = synth.indexer_inputs(83, B, T, Hi, Di, L, 8, 8, 16)
+    ctx_len = torch.tensor(ctx_lens if ctx_lens else [L - 37 * b for b in range(B)], dtype=torch.int32)
+    host = synth.latent_rows_bf16(83, B * L).reshape(B, L, 1152)
+    hp = torch.empty((B, L, 1152), dtype=torch.uint8, pin_memory=True)
+    hp.copy_(host)
+    dev = [x.cuda() for x in (qi, w, key, ctx_len)]
+    # other index queries for the later steps (same keys): new selections, hence misses in every step
+    qws = [(qi.cuda(), w.cuda())] + [tuple(x.cuda() for x in synth.indexer_inputs(83 + s, B, T, Hi, Di, L, 8, 8, 16)[:2])
+                                     for s in (1, 2)]
+    results, confined, parts = {}, [], []
+    for flags in (0, 4):
+        ctx = _ctx(max_batch=B, max_q_tokens=T, max_ctx=L, idx_heads=Hi, idx_dim=Di, topk=k, attn_heads=H,
+                   slots_per_seq=S, flags=flags)
+        if flags == 4:
+            ctx.set_overlap_threshold(0)
+        cache = bnd.Cache.allocate(ctx.cfg, B, host_pool=hp,
+                                   slot_pool=torch.full((B, S, 1152), 0x7F, dtype=torch.uint8, device="cuda"))
+        ctx.cache_reset(cache, B)
+        idx_out = torch.empty((B, T, k), dtype=torch.int32, device="cuda")
+        out = torch.empty((B, T, H, 512), dtype=torch.bfloat16, device="cuda")
+        lse = torch.empty((B, T, H), dtype=torch.float32, device="cuda")
+        mc = torch.empty((B,), dtype=torch.int32, device="cuda")
+        steps = []
+        for step in range(1, 4):
+            q = synth.attn_query(90 + step, B, T, H)
+            ctx.decode_step(cache, qws[step - 1][0], qws[step - 1][1], dev[2], dev[3], q.cuda(), step, idx_out, out, lse, mc)
+            torch.cuda.synchronize()
+            if flags == 4:
+                confined.append(ctx.last_confined())
+                parts.append(ctx.last_overlap())
+            steps.append((idx_out.clone(), out.clone(), lse.clone(), mc.clone(), cache.slot_of.clone(),
+                          cache.slot_pool.clone()))
+        assert ctx.get_stats()["steps"] == 3                     # also: no self-check failure pending
+        ctx.close()
+        results[flags] = steps
+    for s0, s4 in zip(results[0], results[4]):
+        for x, y in zip(s0, s4):
+            assert torch.equal(x, y)
+    # step 1 has no miss counts yet (DA, nothing confined); later steps follow steps full of misses, so the
+    # fetch is long against everything beside it
+    assert confined[0] == 0 and min(confined[1:]) >= 1, confined
+    assert parts[1:] == [1 if B >= 2 else 0] * 2, parts
