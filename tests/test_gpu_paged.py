@@ -87,6 +87,49 @@ def test_decode_loop_paged_with_append(ess_lib):
     ctx.close()
 
 
+def test_paged_keys_under_the_switch_with_confined_fetches(ess_lib):
+    """Paged index keys in the split-batch schedule with a confined fetch (the paged index-score kernel then
+    takes its work by ticket): bit-identical to the DA schedule, which the loop test above holds against
+    the oracle."""
+    from paper_2512_10576_amd import binding as bnd
+    print("paged keys, switch with confinement", flush=True)
+    B, T, Hi, Di, L, k, H, S = 6, 2, 64, 128, 6016, 512, 128, 1500
+    qi, w, key = synth.indexer_inputs(73, B, T, Hi, Di, L, 8, 8, 16)
+    ctx_len = torch.tensor([5040, 4349, 6013, 64, 3000, 6016], dtype=torch.int32)
+    pages, table, _ = synth.paged_indexer_cache(33, key, ctx_len, n_spare_pages=4)
+    host = synth.latent_rows_bf16(73, B * L).reshape(B, L, 1152)
+    hp = torch.empty((B, L, 1152), dtype=torch.uint8, pin_memory=True); hp.copy_(host)
+    qws = [tuple(x.cuda() for x in synth.indexer_inputs(73 + s, B, T, Hi, Di, L, 8, 8, 16)[:2]) for s in range(3)]
+    dpages, dtable, dctx = pages.cuda(), table.cuda(), ctx_len.cuda()
+    results, confined = {}, []
+    for flags in (0, 4):
+        ctx = _ctx(ess_lib, max_batch=B, max_q_tokens=T, max_ctx=L, idx_heads=Hi, idx_dim=Di, topk=k, attn_heads=H,
+                   slots_per_seq=S, flags=flags)
+        if flags == 4:
+            ctx.set_overlap_threshold(0)
+        cache = bnd.Cache.allocate(ctx.cfg, B, host_pool=hp)
+        ctx.cache_reset(cache, B)
+        idx_out = torch.empty((B, T, k), dtype=torch.int32, device="cuda")
+        out = torch.empty((B, T, H, 512), dtype=torch.bfloat16, device="cuda")
+        lse = torch.empty((B, T, H), dtype=torch.float32, device="cuda")
+        steps = []
+        for step in range(1, 4):
+            q = synth.attn_query(80 + step, B, T, H)
+            ctx.decode_step(cache, qws[step - 1][0], qws[step - 1][1], dpages, dctx, q.cuda(), step, idx_out, out, lse,
+                            block_table=dtable)
+            torch.cuda.synchronize()
+            if flags == 4:
+                confined.append((ctx.last_overlap(), ctx.last_confined()))
+            steps.append((idx_out.clone(), out.clone(), lse.clone(), cache.slot_of.clone()))
+        assert ctx.get_stats()["steps"] == 3
+        ctx.close()
+        results[flags] = steps
+    for s0, s4 in zip(results[0], results[4]):
+        for x, y in zip(s0, s4):
+            assert torch.equal(x, y)
+    assert confined[0] == (0, 0) and all(m == 1 and c >= 1 for m, c in confined[1:]), confined
+
+
 def test_paged_argument_errors(ess_lib):
     from paper_2512_10576_amd import binding as bnd
     ctx = _ctx(ess_lib, max_batch=1, max_q_tokens=1, max_ctx=100, idx_heads=4, idx_dim=32, topk=8, attn_heads=8)
