@@ -50,8 +50,9 @@ typedef enum {
   ESS_ERR_CAPACITY = -3,    /* slot pool smaller than one step's selection (S < T*k), or over a stated maximum */
   ESS_ERR_NOMEM = -4,       /* workspace allocation failed */
   ESS_ERR_HIP = -5,         /* a HIP runtime call failed; text in ess_last_error() */
-  ESS_ERR_INTERNAL = -6     /* a device-side self-check of an EARLIER ess_decode_step failed: that step's
-                               outputs are invalid (reported by the next ess_decode_step or ess_get_stats) */
+  ESS_ERR_INTERNAL = -6     /* a device-side assertion of an EARLIER ess_decode_step failed (a defect in the library,
+                               not a property of the inputs or of the machine); reported by the next ess_decode_step
+                               or ess_get_stats */
 } ess_status;
 
 #define ESS_LATENT_DIM 512 /* value part of a Latent-Cache entry */
@@ -78,7 +79,7 @@ typedef struct {
   int32_t max_ctx;        /* Lmax: row pitch of key, score and slot_of; <= 524288 */
   int32_t idx_heads;      /* Hi, 1..64 */
   int32_t idx_dim;        /* Di, 32 | 64 | 128 */
-  int32_t topk;           /* k, 1..4096, with T*k <= 4096 */
+  int32_t topk;           /* k, 1..4096, with T*k <= 8192 */
   int32_t attn_heads;     /* H, 1..128 */
   int32_t latent_fmt;     /* ESS_FMT_BF16 | ESS_FMT_FP8 */
   int32_t row_stride;     /* bytes between entries in slot pool and host pool (>= entry size, multiple of 16) */
@@ -221,18 +222,24 @@ int ess_last_overlap(const ess_ctx* ctx, int32_t* mode);
 
 /* Under ESS_FLAG_AUTO a step may confine its fetches from host memory to three of the eight XCDs and
  * keep the kernels that run beside them on the other five (FlashTrans reads, Sec. 3.1, slow every
- * memory access of the XCD they are issued from).  Those kernels take their work items by ticket, one
- * per workgroup, and the launch sizes count on workgroups being spread over the XCDs in turn, which
- * ess_create probes.  Each such step ends with a device-side check that every launch had at least as
- * many workgroups asking as it had work items; a failure is reported, as ESS_ERR_INTERNAL, by the next
- * ess_decode_step or ess_get_stats on the context (the failed step's outputs are invalid), and the
- * context confines nothing from then on.
+ * memory access of the XCD they are issued from).  Those kernels take their work items by ticket:
+ * every workgroup that runs on an XCD that takes work draws items from a counter until none is left,
+ * and should no workgroup of a launch sit on such an XCD, the last one to arrive does all the work.
+ * The results therefore do not depend on where the hardware places workgroups; ess_create only
+ * probes whether workgroups go round the XCDs evenly, which is when confining pays.  Each such step
+ * ends with a device-side assertion that every launch handed out at least as many tickets as it had
+ * work items; a failure is reported, as ESS_ERR_INTERNAL, by the next ess_decode_step or
+ * ess_get_stats on the context, and the context confines nothing from then on.
  * ess_last_confined: fetches of the latest ess_decode_step that were confined (0, 1 or 2).
- * ess_selfcheck_inject: test hook.  The check of the next confined step expects `extra_items` more
- * work items than there are, so that it fails (for extra_items > the spare workgroups of the launch,
- * a few dozen) although the step itself is complete; every kernel runs and ends as usual. */
+ * ess_selfcheck_inject: test hook.  The assertion of the next confined step expects `extra_items`
+ * more work items than there are, so that it fails (for extra_items > the workgroups of the launch)
+ * although the step itself is complete; every kernel runs and ends as usual.
+ * ess_debug_ticket_grid: test hook.  Ticket-fed launches (and confined fetches) of later steps use
+ * exactly `workgroups` workgroups, whatever their number of work items (0 = the library's own
+ * sizing); results are the same for every value >= 1. */
 int ess_last_confined(const ess_ctx* ctx, int32_t* fetches);
 int ess_selfcheck_inject(ess_ctx* ctx, int32_t extra_items);
+int ess_debug_ticket_grid(ess_ctx* ctx, int32_t workgroups);
 
 /* Append (Sec. 3.3, the write-back of newly generated entries): for each sequence b with
  * L0 = ctx_len[b], the t-th of its T new tokens takes position p = L0 + t:
@@ -286,7 +293,7 @@ int ess_profile_select(ess_ctx* ctx, uint32_t stage_mask, int32_t every);
 /* A plain device-to-device copy kernel (reads `bytes`, writes `bytes`; bytes a multiple of 16,
  * pointers 16-byte aligned): known traffic against which hardware counters can be scaled. */
 int ess_calib_copy(void* dst, const void* src, size_t bytes, void* stream);
-/* The transfer the paper starts from (Sec. 3.2, the per-block copy that FlashTrans replaces): one
+/* The transfer the paper starts from (Sec. 3.1, the per-block copy that FlashTrans replaces): one
  * hipMemcpyAsync per entry, n entries of row_bytes each, entry i from
  * host_pool + host_rows[i] * row_stride (pinned host memory, HOST pointer) to
  * dst + i * row_stride (device).  host_rows is a HOST array.  Enqueues on `stream`, returns without

@@ -90,6 +90,7 @@ def load() -> C.CDLL:
         "ess_last_overlap": [vp, C.POINTER(i32)],
         "ess_last_confined": [vp, C.POINTER(i32)],
         "ess_selfcheck_inject": [vp, i32],
+        "ess_debug_ticket_grid": [vp, i32],
         "ess_calib_memcpy_rows": [vp, vp, vp, C.c_int64, i32, i32, vp],
         "ess_profile_read": [vp, C.POINTER(C.c_float), C.POINTER(i32)],
     }
@@ -275,6 +276,10 @@ class Context:
     def selfcheck_inject(self, extra_items: int) -> None:
         """test hook: the self-check of the next confined step expects extra_items more work items"""
         _check(self.lib.ess_selfcheck_inject(self.h, extra_items))
+
+    def debug_ticket_grid(self, workgroups: int) -> None:
+        """test hook: ticket-fed launches use exactly `workgroups` workgroups (0 = the library's own sizing)"""
+        _check(self.lib.ess_debug_ticket_grid(self.h, workgroups))
 
     def get_stats(self) -> dict:
         s = EssStats()

@@ -29,14 +29,24 @@ namespace {
 constexpr int BT = 1024;
 
 struct BookShared {
-  union {
-    uint32_t hist[256 * 32];                   // 32 KiB
-    unsigned long long vict[ESS_MAX_SEL];      // 32 KiB
-  };
-  int32_t miss_tok[ESS_MAX_SEL];               // 16 KiB
   uint32_t wave_tot[BT / 64];
   uint32_t sel_digit, sel_below, vict_n;
 };
+// The large arrays of the bookkeeping kernel live in dynamic LDS, sized by the configuration:
+//   bm [W]  bitmap of the missed positions (W = max_ctx / 32 words, rounded up to an even number)
+//   un      histogram of the radix passes (256 x 32 counters, 32 KiB), later the victims' (stamp, slot) keys
+//           (vict_cap = sel_cap rounded up to a power of two, 8 bytes each)
+//   mt [sel_cap]  missed positions in ascending order (sel_cap = max_q_tokens * topk)
+constexpr int BOOK_HIST_BYTES = 256 * 32 * 4;
+inline int book_pow2(int n) { int p = 1; while (p < n) p <<= 1; return p; }
+inline size_t book_words(int max_ctx) { return (size_t)(((max_ctx + 31) / 32 + 1) & ~1); }
+inline size_t book_union_bytes(int sel_cap) {
+  const size_t v = (size_t)book_pow2(sel_cap) * 8;
+  return v > (size_t)BOOK_HIST_BYTES ? v : (size_t)BOOK_HIST_BYTES;
+}
+inline size_t book_lds_bytes(int max_ctx, int sel_cap) {
+  return book_words(max_ctx) * 4 + book_union_bytes(sel_cap) + (size_t)sel_cap * 4;
+}
 
 __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v, int lane) {
 #pragma unroll
@@ -91,16 +101,21 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
     int32_t* __restrict__ n_miss, int32_t* __restrict__ fill_tok, int32_t* __restrict__ fill_slot, int fill_cap,
     int32_t* __restrict__ miss_cnt, int32_t* __restrict__ miss_count_out, unsigned long long* __restrict__ stats,
     int row_stride, int count_step, int32_t* __restrict__ host_miss, ess_xcd xcd, int n_seq,
-    uint32_t* __restrict__ zero_tickets, int n_zero_tickets) {
-  extern __shared__ uint32_t bm[];             // [W] bitmap of the missed positions
+    uint32_t* __restrict__ zero_tickets, int n_zero_tickets, int bm_words, int union_bytes) {
+  extern __shared__ __align__(16) uint32_t bm[];              // see the layout above
+  uint32_t* const s_hist = bm + bm_words;
+  unsigned long long* const s_vict = reinterpret_cast<unsigned long long*>(bm + bm_words);
+  int32_t* const s_miss_tok = reinterpret_cast<int32_t*>(bm + bm_words + union_bytes / 4);
+  const int vict_cap = union_bytes / 8;                       // >= the misses of one step, rounded up to a power of two
   __shared__ BookShared sm;
   __shared__ int s_item;
   constexpr int RS = 16;                       // register-held stamps per thread
   // work counters of the kernels that follow this one beside the fetch it feeds: cleared here, by the first
   // workgroup, so that no launch has to do it (this kernel itself never uses the counters it clears)
-  if (zero_tickets && blockIdx.x == 0 && (int)threadIdx.x < n_zero_tickets) zero_tickets[threadIdx.x] = 0;
-  const int b = ess_take_item(blockIdx.x, n_seq, xcd, &s_item);   // sequence: by workgroup index, or in arrival order
-  if (b < 0) return;
+  if (zero_tickets && blockIdx.x == 0)
+    for (int i = threadIdx.x; i < n_zero_tickets; i += BT) zero_tickets[i] = 0;
+  // work item = sequence: by workgroup index, or drawn from the launch's counter off the XCDs to be avoided
+  ESS_WORK_LOOP(xcd, blockIdx.x, n_seq, &s_item, b) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int W = (Lmax + 31) >> 5;
   const int nsel = T * kk;
@@ -149,7 +164,7 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
       while (bits) {
         const int bit = __ffs(bits) - 1;
         bits &= bits - 1;
-        if (pos < ESS_MAX_SEL) sm.miss_tok[pos] = wd * 32 + bit;
+        if (pos < (uint32_t)fill_cap) s_miss_tok[pos] = wd * 32 + bit;
         ++pos;
       }
     }
@@ -173,20 +188,20 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
     const int first_pass = step < (1u << 8) ? 3 : (step < (1u << 16) ? 2 : (step < (1u << 24) ? 1 : 0));
     for (int pass = first_pass; pass < 4; ++pass) {
       const int shift = 24 - 8 * pass;
-      for (int j = tid; j < 256 * 32; j += BT) sm.hist[j] = 0;
+      for (int j = tid; j < 256 * 32; j += BT) s_hist[j] = 0;
       __syncthreads();
 #pragma unroll
       for (int j = 0; j < nj; ++j) {
         if (v0 + j >= v1) continue;
         const uint32_t st = stamp_at(j);
         if (st < step && (pass == first_pass || (st >> (shift + 8)) == prefix))
-          atomicAdd(&sm.hist[((st >> shift) & 255u) * 32 + (lane & 31)], 1u);
+          atomicAdd(&s_hist[((st >> shift) & 255u) * 32 + (lane & 31)], 1u);
       }
       __syncthreads();
       uint32_t c = 0;
       if (tid < 256) {
 #pragma unroll
-        for (int r = 0; r < 32; ++r) c += sm.hist[tid * 32 + r];
+        for (int r = 0; r < 32; ++r) c += s_hist[tid * 32 + r];
       }
       uint32_t total;
       const uint32_t inc = block_incl_scan(c, sm.wave_tot, &total);
@@ -215,7 +230,7 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
       if (st == tau) { take = rank < need; ++rank; }
       if (take) {
         const uint32_t p = atomicAdd(&sm.vict_n, 1u);
-        if (p < ESS_MAX_SEL) sm.vict[p] = ((unsigned long long)st << 32) | (uint32_t)(v0 + j);
+        if (p < (uint32_t)vict_cap) s_vict[p] = ((unsigned long long)st << 32) | (uint32_t)(v0 + j);
       }
     }
     __syncthreads();
@@ -226,24 +241,24 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
     unsigned long long my_key = 0;
     if (by_rank) {
       if (tid < (int)m) {
-        my_key = sm.vict[tid];
+        my_key = s_vict[tid];
         int rk = 0;
-        for (uint32_t j = 0; j < m; ++j) rk += sm.vict[j] < my_key ? 1 : 0;
+        for (uint32_t j = 0; j < m; ++j) rk += s_vict[j] < my_key ? 1 : 0;
         my_rank = rk;
       }
       __syncthreads();
-      if (my_rank >= 0) sm.vict[my_rank] = my_key;
+      if (my_rank >= 0) s_vict[my_rank] = my_key;
       __syncthreads();
     } else {
       int np = 1;
       while (np < (int)m) np <<= 1;
-      for (int j = (int)m + tid; j < np; j += BT) sm.vict[j] = ~0ull;
-      bitonic_sort_u64(sm.vict, np);
+      for (int j = (int)m + tid; j < np; j += BT) s_vict[j] = ~0ull;
+      bitonic_sort_u64(s_vict, np);
     }
     // ---- pair the i-th miss with the i-th victim
     for (uint32_t i = tid; i < m; i += BT) {
-      const int s = sm.miss_tok[i];
-      const int v = (int)(uint32_t)sm.vict[i];
+      const int s = s_miss_tok[i];
+      const int v = (int)(uint32_t)s_vict[i];
       const int old = to[v];
       if (old >= 0) so[old] = -1;
       to[v] = s;
@@ -265,7 +280,7 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
   __syncthreads();                               // table updates visible to the whole workgroup
 
   // ---- per (b,t): slot of every selected entry, and the compacted hit / fetched lists
-  if (slot_idx_out == nullptr && hit_list == nullptr) return;
+  if (slot_idx_out == nullptr && hit_list == nullptr) continue;
   for (int t = 0; t < T; ++t) {
     const size_t rowoff = ((size_t)b * T + t) * kk;
     uint32_t base_hit = 0, base_miss = 0;
@@ -298,6 +313,7 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
       n_miss[b * T + t] = (int32_t)base_miss;
     }
   }
+  }
 }
 
 // Fetch: one wave per missed entry, rows copied host pool -> slot pool in 16-byte pieces, two
@@ -318,8 +334,10 @@ __global__ __launch_bounds__(FILL_WPB * 64) void k_fill(const uint8_t* __restric
                                                const int32_t* __restrict__ fill_slot, int fill_cap,
                                                const int32_t* __restrict__ miss_cnt, int B, int Lmax, int S,
                                                int row_stride, uint32_t only_xcds, uint32_t* __restrict__ ticket) {
-  // confined fetch: only workgroups on the XCDs in `only_xcds` work, entries are handed out through `ticket`
-  if (only_xcds && !((only_xcds >> ess_xcc_id()) & 1u)) return;
+  // confined fetch: only workgroups on the XCDs in `only_xcds` work (or, should none sit there, the last one to
+  // arrive), entries are handed out through `ticket`
+  __shared__ int s_join;
+  if (only_xcds && !ess_ticket_join(ticket, (only_xcds >> ess_xcc_id()) & 1u, &s_join)) return;
   extern __shared__ int32_t pref[];                          // [B + 1] pref[b] = entries of sequences < b (kept small:
                                                              // the kernel must fit beside workgroups that fill the LDS)
   const int tid = threadIdx.x, lane = tid & 63;
@@ -559,31 +577,49 @@ int ess_launch_bookkeeping(ess_ctx* ctx, const ess_cache& cache, const int32_t* 
                            uint32_t step, int32_t* slot_idx, int32_t* miss_count_out, hipStream_t st, int b0,
                            bool count_step, ess_xcd xcd, uint32_t* zero_tickets, int n_zero_tickets) {
   const ess_config& c = ctx->cfg;
-  const size_t lds = (size_t)((c.max_ctx + 31) / 32) * sizeof(uint32_t);
-  const bool lists = (kk == c.topk);           // compacted lists have the pitch of the top-k
+  if (!ctx->book_fits)
+    return ess_fail(ESS_ERR_UNSUPPORTED, "the cache bookkeeping of max_ctx %d with T*k = %d does not fit the LDS (max_ctx / 8 + "
+                    "12 * T*k bytes must stay below 160 KiB)", c.max_ctx, c.max_q_tokens * c.topk);
   const int cap = c.max_q_tokens * c.topk;
+  const size_t lds = book_lds_bytes(c.max_ctx, cap);
+  const bool lists = (kk == c.topk);           // compacted lists have the pitch of the top-k
   const size_t lo = (size_t)b0 * T * c.topk;   // offset of this sub-batch in the per-(b,t) lists
   const bool reg = c.slots_per_seq <= BT * 16;
   auto kern = reg ? &k_bookkeeping<true> : &k_bookkeeping<false>;
-  ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   hipLaunchKernelGGL(kern, dim3(ess_xcd_grid(B, xcd)), dim3(BT), lds, st, idx, T, kk, c.max_ctx, c.slots_per_seq,
                      cache.slot_of, cache.token_of, cache.stamp, step, slot_idx,
                      lists ? ctx->hit_list + lo : nullptr, lists ? ctx->miss_list + lo : nullptr,
                      ctx->n_hit + (size_t)b0 * T, ctx->n_miss + (size_t)b0 * T, ctx->fill_tok + (size_t)b0 * cap,
                      ctx->fill_slot + (size_t)b0 * cap, cap, ctx->miss_cnt + b0, miss_count_out, ctx->stats,
                      c.row_stride, count_step ? 1 : 0, (c.flags & ESS_FLAG_AUTO) ? ctx->host_miss_dev + b0 : nullptr, xcd, B,
-                     zero_tickets, n_zero_tickets);
+                     zero_tickets, n_zero_tickets, (int)book_words(c.max_ctx), (int)book_union_bytes(cap));
   ESS_HIP(hipGetLastError());
+  return ESS_OK;
+}
+
+// At context creation (on the context's device): the bookkeeping kernels keep their arrays in dynamic LDS (see
+// BookShared).  The limit is a property of the function, shared by all contexts: it only grows.  A configuration
+// whose arrays do not fit the CU's 160 KiB (a selection of 8192 entries per sequence together with a context
+// above 500K) cannot use the cache calls: *fits tells.
+int ess_init_cache_kernels(const ess_config& c, bool* fits) {
+  static size_t have = 0;
+  const size_t lds = book_lds_bytes(c.max_ctx, c.max_q_tokens * c.topk);
+  *fits = lds + 256 <= 160 * 1024;             // + the kernel's small static arrays
+  if (!*fits || lds <= have) return ESS_OK;
+  ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_bookkeeping<true>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_bookkeeping<false>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  have = lds;
   return ESS_OK;
 }
 
 int ess_launch_fill(ess_ctx* ctx, const ess_cache& cache, int B, hipStream_t st, int b0, int wgs, uint32_t only_xcds,
                     uint32_t* ticket) {
   wgs = wgs < 1 ? 1 : (wgs > 256 ? 256 : wgs);
-  if (only_xcds) {                             // `wgs` workgroups on the chosen XCDs: any 8 consecutive ones cover all XCDs
+  if (only_xcds) {                             // `wgs` workgroups on the chosen XCDs, if any 8 consecutive ones cover all XCDs
     if (!ticket) return ess_fail(ESS_ERR_INVALID_ARG, "internal: confined fetch without a ticket");
     const int on = __builtin_popcount(only_xcds & 0xffu);
     wgs = (wgs + on - 1) / on * 8;
+    if (ctx->ticket_grid > 0) wgs = ctx->ticket_grid;
   }
   const ess_config& c = ctx->cfg;
   const int cap = c.max_q_tokens * c.topk;

@@ -85,7 +85,7 @@ WsLayout ws_layout(const ess_config& c) {
   w.zero_row = take(ESS_ZERO_ROW_BYTES);
   w.topk_cand = take(ess_topk_cand_bytes());
   w.topk_cnt = take(ESS_TOPK_SHARED_ROWS * sizeof(uint32_t));
-  w.tickets = take(ESS_N_TICKETS * sizeof(uint32_t));
+  w.tickets = take(ESS_N_TICKETS * ESS_TICKET_WORDS * sizeof(uint32_t));
   w.total = off;
   return w;
 }
@@ -148,7 +148,7 @@ int run_cache_step(ess_ctx* ctx, const ess_cache& cache, const int32_t* idx, int
   // confine: the fetch runs on the XCDs of ESS_FETCH_XCD_MASK and the kernels beside it stay off them, taking their work
   // through counters that this bookkeeping clears (counter 0: the fetch itself)
   int rc = ess_launch_bookkeeping(ctx, cache, idx, B, T, kk, step, slot_idx, miss_count, st, b0, half == 0,
-                                  ess_xcd{nullptr, 0, nullptr}, confine ? ctx->tickets : nullptr, 5);
+                                  ess_xcd{nullptr, 0, nullptr, 0}, confine ? ctx->tickets : nullptr, 5 * ESS_TICKET_WORDS);
   if (rc != ESS_OK) return rc;
   if (!cache.host_pool_dev) return ESS_OK;      // nothing offloaded: no entry can be missing
   if (ctx->cfg.flags & ESS_FLAG_SERIAL) {
@@ -247,7 +247,18 @@ int ess_create(const ess_config* cfg, ess_ctx** out) {
   if ((e = hipMemset(ctx->stats, 0, 32)) != hipSuccess) return bail("hipMemset", e);
   if ((e = hipMemset(ctx->zero_row, 0, ESS_ZERO_ROW_BYTES)) != hipSuccess) return bail("hipMemset", e);
   if ((e = hipMemset(ctx->topk_cnt, 0, ESS_TOPK_SHARED_ROWS * sizeof(uint32_t))) != hipSuccess) return bail("hipMemset", e);
-  if ((e = hipMemset(ctx->tickets, 0, ESS_N_TICKETS * sizeof(uint32_t))) != hipSuccess) return bail("hipMemset", e);
+  if ((e = hipMemset(ctx->tickets, 0, ESS_N_TICKETS * ESS_TICKET_WORDS * sizeof(uint32_t))) != hipSuccess) return bail("hipMemset", e);
+  {
+    int irc = ess_init_cache_kernels(*cfg, &ctx->book_fits);
+    if (irc == ESS_OK) irc = ess_init_attn_kernels();
+    if (irc != ESS_OK) {                        // the text of the failure is already set
+      char keep[sizeof(g_err)];
+      memcpy(keep, g_err, sizeof(keep));
+      (void)bail("", hipSuccess);
+      memcpy(g_err, keep, sizeof(keep));
+      return irc;
+    }
+  }
   ctx->xcds_even = false;
   if (ess_probe_xcds(ctx->tickets, &ctx->xcds_even) != ESS_OK) return bail("XCD probe", hipGetLastError());
   if ((e = hipHostMalloc(reinterpret_cast<void**>(&ctx->host_miss), ((size_t)cfg->max_batch + 1) * sizeof(int32_t),
@@ -315,16 +326,16 @@ int ess_index_score(ess_ctx* ctx, const uint8_t* q, const float* w, const uint8_
 }
 
 namespace {
-// The flag a step's last kernel raises when one of its ticket-fed launches had fewer workgroups asking
-// for work than there were work items (see ess_ticket_check): that step's outputs are incomplete.  Seen at
-// the next call; from then on nothing is confined, so no launch depends on where workgroups land.
+// The assertion of a step that fed launches by ticket (see ess_ticket_check): every launch handed out at least as
+// many tickets as it had work items.  Workgroups draw tickets until none is left, wherever they run, so a
+// failure means a defect in the hand-out itself; it is seen at the next call, and nothing is confined afterwards.
 int check_tickets(ess_ctx* ctx) {
   volatile int32_t* flag = ctx->host_miss + ctx->cfg.max_batch;
   if (!*flag) return ESS_OK;
   *flag = 0;
   ctx->xcds_even = false;
-  return ess_fail(ESS_ERR_INTERNAL, "an earlier decode step left work items unserved (workgroups were not spread over the "
-                                    "XCDs as probed): its outputs are invalid; XCD-confined schedules are now off");
+  return ess_fail(ESS_ERR_INTERNAL, "assertion failed in an earlier decode step: a ticket-fed launch handed out fewer tickets "
+                                    "than it had work items; XCD-confined schedules are now off");
 }
 
 int check_paged(const ess_ctx* ctx, const uint8_t* pool, const int32_t* block_table, int n_pages) {
@@ -490,6 +501,10 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
   const uint32_t check_extra = ctx->last_confined ? ctx->check_extra : 0u;   // test hook, one confined step
   if (ctx->last_confined) ctx->check_extra = 0;
   const uint32_t mask2 = ESS_FETCH_XCD_MASK;
+  // launch `counter` of the step's ticket-fed launches: its counters, the XCDs it stays off, where its item count goes
+  auto tk_xcd = [&](int counter) {
+    return ess_xcd{ctx->tickets + counter * ESS_TICKET_WORDS, ESS_FETCH_XCD_MASK, chk.need + counter, ctx->ticket_grid};
+  };
   const int wgs2 = ESS_FETCH_CONFINED_WGS;
   const int hb0[2] = {0, B / 2};
   const int hB[2] = {dba ? B / 2 : B, B - B / 2};
@@ -528,7 +543,7 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     // second half of the split-batch schedule: these kernels run beside the first fetch, which is confined
     // to the XCDs of ESS_FETCH_XCD_MASK; they stay off those (counters 1..4, cleared by the first half's bookkeeping)
     const bool beside = confine && h == 1;
-    auto xcd_of = [&](int counter) { return beside ? ess_xcd{ctx->tickets + counter, ESS_FETCH_XCD_MASK, chk.need + counter} : ess_xcd{nullptr, 0, nullptr}; };
+    auto xcd_of = [&](int counter) { return beside ? tk_xcd(counter) : ess_xcd{nullptr, 0, nullptr, 0}; };
     if (a->block_table)     // paged: one pool for the whole batch, the table rows of this sub-batch
       rc = ess_launch_index_score(c, a->q_idx_fp8 + bt0 * c.idx_heads * c.idx_dim, a->w + bt0 * c.idx_heads, a->key_fp8,
                                   a->ctx_len + b0, Bh, T, sc, st,
@@ -550,7 +565,8 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     if (da_swap || (dba && h == 1)) {      // bookkeeping only; the fetch follows on this stream further down
       rc = ess_launch_bookkeeping(ctx, ch, used, Bh, T, c.topk, a->step, ctx->slot_idx_ws + bt0 * k,
                                   a->miss_count ? a->miss_count + b0 : nullptr, st, b0, h == 0, xcd_of(4),
-                                  (confine2 || (da_swap && confine_da)) ? ctx->tickets + (da_swap ? 0 : 5) : nullptr, da_swap ? 8 : 3);
+                                  (confine2 || (da_swap && confine_da)) ? ctx->tickets + (da_swap ? 0 : 5) * ESS_TICKET_WORDS : nullptr,
+                                  (da_swap ? 8 : 3) * ESS_TICKET_WORDS);
       if (rc != ESS_OK) return rc;
     } else {
       rc = run_cache_step(ctx, ch, used, Bh, T, c.topk, a->step, ctx->slot_idx_ws + bt0 * k,
@@ -587,7 +603,7 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     hipEvent_t* aev = (pev && ((ctx->prof_mask >> 3) & 1u)) ? pev + ESS_PROF_MAIN : nullptr;
     if (aev) ESS_HIP(hipEventRecord(aev[0], ctx->side));
     rc = ess_launch_attn_partial(ctx, q16, cache->slot_pool, ctx->hit_list, ctx->n_hit, B, T, 0, ns0, ctx->side, 0,
-                                 confine_da ? ess_xcd{ctx->tickets + 6, mask2, chk.need + 6} : ess_xcd{nullptr, 0, nullptr});
+                                 confine_da ? tk_xcd(6) : ess_xcd{nullptr, 0, nullptr, 0});
     if (rc != ESS_OK) return rc;
     if (aev) {
       ESS_HIP(hipEventRecord(aev[1], ctx->side));
@@ -621,7 +637,7 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     const size_t bt1 = (size_t)hb0[1] * T;
     ESS_HIP(hipEventRecord(ctx->ev_book[1], st));                    // second half's bookkeeping done
     ESS_BEGIN(5);
-    rc = confine2 ? ess_launch_fill(ctx, c1, hB[1], st, hb0[1], wgs2, mask2, ctx->tickets + 5)
+    rc = confine2 ? ess_launch_fill(ctx, c1, hB[1], st, hb0[1], wgs2, mask2, ctx->tickets + 5 * ESS_TICKET_WORDS)
                   : ess_launch_fill(ctx, c1, hB[1], st, hb0[1], 28);
     if (rc != ESS_OK) return rc;
     ESS_END(5);
@@ -632,14 +648,14 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     // Attn0 of the whole batch in one launch (behind the first fetch it could not start much earlier
     // anyway): one workgroup per CU, the same splits as in the other schedules
     rc = ess_launch_attn_partial(ctx, q16, cache->slot_pool, ctx->hit_list, ctx->n_hit, B, T, 0, ns0, ctx->side, 0,
-                                 confine2 ? ess_xcd{ctx->tickets + 6, mask2, chk.need + 6} : ess_xcd{nullptr, 0, nullptr});
+                                 confine2 ? tk_xcd(6) : ess_xcd{nullptr, 0, nullptr, 0});
     if (rc != ESS_OK) return rc;
     if (aev) {
       ESS_HIP(hipEventRecord(aev[1], ctx->side));
       ESS_HIP(hipEventRecord(aev[2], ctx->side));
     }
     rc = ess_launch_attn_partial(ctx, q16, c0.slot_pool, ctx->miss_list, ctx->n_miss, hB[0], T, ns0, ns1, ctx->side, hb0[0],
-                                 confine2 ? ess_xcd{ctx->tickets + 7, mask2, chk.need + 7} : ess_xcd{nullptr, 0, nullptr});
+                                 confine2 ? tk_xcd(7) : ess_xcd{nullptr, 0, nullptr, 0});
     if (rc != ESS_OK) return rc;
     // each half is merged on the stream its Attn1 ran on: only half a merge is left behind the last fetch
     rc = ess_launch_attn_merge(ctx, hB[0], T, ns0 + ns1, a->out_bf16, a->lse, ctx->side, nullptr, 0, hb0[0]);
@@ -735,6 +751,13 @@ int ess_selfcheck_inject(ess_ctx* ctx, int32_t extra_items) {
   if (!ctx) return ess_fail(ESS_ERR_INVALID_ARG, "context is NULL");
   if (extra_items < 0) return ess_fail(ESS_ERR_INVALID_ARG, "extra_items %d", extra_items);
   ctx->check_extra = (uint32_t)extra_items;
+  return ESS_OK;
+}
+
+int ess_debug_ticket_grid(ess_ctx* ctx, int32_t workgroups) {
+  if (!ctx) return ess_fail(ESS_ERR_INVALID_ARG, "context is NULL");
+  if (workgroups < 0 || workgroups > 65535) return ess_fail(ESS_ERR_INVALID_ARG, "workgroups %d outside [0, 65535]", workgroups);
+  ctx->ticket_grid = workgroups;
   return ESS_OK;
 }
 

@@ -12,7 +12,10 @@
 #define ESS_ROW_DIM 576
 #define ESS_ZERO_ROW_BYTES 2048  // >= the largest row_stride
 #define ESS_TOPK_SHARED_ROWS 128 // rows (b,t) up to which a top-k row is shared by several workgroups
-#define ESS_N_TICKETS 8
+#define ESS_N_TICKETS 8         // ticket-fed launches of one step
+#define ESS_TICKET_WORDS 16     // counters per such launch: [0] work items handed out, [1] workgroups arrived
+                                // (low half) and of those on XCDs that take work (high half), [2..9] per-XCD
+                                // counters of launches that hand out work XCD by XCD (attention)
 // The first fetch of the split-batch schedule is confined to these XCDs, and the kernels beside it stay
 // off them.  Measured at batch 64, 128K context (step time): one XCD 0.668 ms (the fetch drops to
 // 40 GB/s behind a single XCD's port when the other seven stream from HBM), two 0.614, three 0.605,
@@ -44,8 +47,10 @@ struct ess_ctx {
   uint8_t* zero_row;            // ESS_ZERO_ROW_BYTES of zeros, never written: source of masked attention rows
   unsigned long long* topk_cand; // [ESS_TOPK_SHARED_ROWS][8192] candidate keys of rows shared by several workgroups
   uint32_t* topk_cnt;           // [ESS_TOPK_SHARED_ROWS] candidates listed per row: zero between steps
-  uint32_t* tickets;            // [ESS_N_TICKETS] work counters of kernels that run beside a fetch (see ess_xcd)
-  bool xcds_even;               // workgroups go round the eight XCDs evenly (probed at creation): fetches may be confined
+  uint32_t* tickets;            // [ESS_N_TICKETS][ESS_TICKET_WORDS] work counters of kernels that run beside a fetch (see ess_xcd)
+  bool xcds_even;               // workgroups go round the eight XCDs evenly (probed at creation): confining a fetch pays
+  bool book_fits;               // the bookkeeping kernel's LDS arrays fit this configuration (else the cache calls are refused)
+  int ticket_grid;              // > 0: ticket-fed launches use exactly this many workgroups (ess_debug_ticket_grid)
   int last_confined;            // fetches of the latest decode step that were confined to ESS_FETCH_XCD_MASK
   uint32_t check_extra;         // ess_selfcheck_inject: work items the next confined step's check expects on top
   size_t ws_bytes;
@@ -72,16 +77,18 @@ struct ess_ctx {
 // over the chip takes 3.4x its time, beside the same fetch confined to one XCD -- which costs the fetch
 // 3 % of its rate -- and kept off that XCD it is not slowed at all (measured).  A kernel launched with
 // an ess_xcd therefore does not map workgroups to work by their index: workgroups on the XCDs in
-// `avoid` exit, the others take work items in the order they arrive (`ticket`, zero at launch).
+// `avoid` exit, the others take work items from a counter until it runs out, however many they are.
+// The launch is complete wherever the hardware puts its workgroups: should none of them sit on an XCD
+// that takes work, the last workgroup to arrive does all of it.
 struct ess_xcd {
-  uint32_t* ticket;
+  uint32_t* ticket;             // ESS_TICKET_WORDS counters, zero at launch; null: work by workgroup index
   uint32_t avoid;               // bit i: XCD i takes no work
   uint32_t* host_need;          // host memory, may be null: the launcher leaves the number of work items here
+  int grid_override;            // > 0: launch exactly this many workgroups (test hook)
 };
-// A workgroup takes one item at most, so every item is served only if the launch puts enough workgroups on
-// the XCDs that work: the launch size counts on workgroups going round the XCDs in turn.  The last kernel
-// of a step compares the counters (workgroups that asked) with the items there were, and raises `flag`
-// (pinned host memory) where a counter fell short, which the host reports at its next call.
+// The last kernel of a step that used such launches compares each launch's counters with its number of
+// work items, as an assertion: a counter below it means a bug in the hand-out, reported through `flag`
+// (pinned host memory) at the host's next call.
 struct ess_ticket_check {
   const uint32_t* tickets;      // null: no check
   int32_t* flag;
@@ -89,22 +96,61 @@ struct ess_ticket_check {
 };
 #ifdef __HIPCC__
 __device__ __forceinline__ int ess_xcc_id() { return __builtin_amdgcn_s_getreg(20 | (3 << 11)) & 15; }   // hwreg XCC_ID, bits 3:0
-// work item of this workgroup (all threads get the same), -1 if it has none; `slot` is a __shared__ int
-__device__ __forceinline__ int ess_take_item(int static_item, int items, const ess_xcd& x, int* slot) {
-  if (!x.ticket) return static_item < items ? static_item : -1;
-  if ((x.avoid >> ess_xcc_id()) & 1u) return -1;
-  if (threadIdx.x == 0) *slot = (int)atomicAdd(x.ticket, 1u);
+// Does this workgroup of a ticket-fed launch take work?  Same answer in all threads; `slot` is a __shared__ int.
+// `on`: this workgroup sits on an XCD that takes work.  Every workgroup counts itself in; one that sits elsewhere
+// leaves, unless it is the last of the whole launch to arrive and none before it took work.
+__device__ __forceinline__ bool ess_ticket_join(uint32_t* ticket, bool on, int* slot) {
+  if (on) {
+    if (threadIdx.x == 0) atomicAdd(ticket + 1, 0x10001u);
+    return true;
+  }
+  if (threadIdx.x == 0) {
+    const uint32_t a = atomicAdd(ticket + 1, 1u);
+    const uint32_t nwg = gridDim.x * gridDim.y * gridDim.z;
+    *slot = ((a & 0xffffu) + 1u == nwg && (a >> 16) == 0u) ? 1 : 0;
+  }
   __syncthreads();
-  const int it = *slot;
-  return it < items ? it : -1;
+  const int r = __builtin_amdgcn_readfirstlane(*slot);
+  __syncthreads();
+  return r != 0;
 }
+__device__ __forceinline__ bool ess_ticket_join(const ess_xcd& x, int* slot) {
+  return ess_ticket_join(x.ticket, !((x.avoid >> ess_xcc_id()) & 1u), slot);
+}
+// Thread 0 asks for the next work item of counter `c`; the value is needed only at ess_ticket_publish, so a
+// request made before an item is worked on costs no waiting.
+__device__ __forceinline__ uint32_t ess_ticket_request(uint32_t* c) { return threadIdx.x == 0 ? atomicAdd(c, 1u) : 0u; }
+// Hand thread 0's ticket to the whole workgroup (also a barrier between two work items): the item, or -1 past the end.
+__device__ __forceinline__ int ess_ticket_publish(uint32_t mine, int items, int* slot) {
+  __syncthreads();
+  if (threadIdx.x == 0) *slot = mine < (uint32_t)items ? (int)mine : -1;
+  __syncthreads();
+  return __builtin_amdgcn_readfirstlane(*slot);      // the same in every lane: let the compiler keep it in a scalar register
+}
+// ESS_WORK_LOOP(xcd, static_item, items, slot, item) { body } runs the body for the one work item of this
+// workgroup's index (no ticket), or for every item this workgroup draws (ticket-fed).
+#define ESS_WORK_LOOP(xcd, static_item, items, slot, item)                                                   \
+  const bool ess_dyn_ = (xcd).ticket != nullptr;                                                             \
+  if (ess_dyn_ && !ess_ticket_join((xcd), (slot))) return;                                                   \
+  uint32_t ess_tk_ = ess_dyn_ ? ess_ticket_request((xcd).ticket) : 0u;                                       \
+  for (int ess_round_ = 0, item = 0;                                                                         \
+       ess_dyn_ ? ((item = ess_ticket_publish(ess_tk_, (items), (slot))) >= 0 &&                             \
+                   ((ess_tk_ = ess_ticket_request((xcd).ticket)), true))                                     \
+                : (ess_round_ == 0 && (item = (static_item)) < (items));                                     \
+       ++ess_round_)
 #endif
-// workgroups to launch so that `items` of them sit on XCDs that take work (any 8 consecutive workgroups cover all 8 XCDs)
-inline int ess_xcd_grid(int items, const ess_xcd& x) {
+// Workgroups to launch for a ticket-fed kernel: enough to put `per_cu` of them on every CU of the XCDs that
+// take work (32 CUs each; any 8 consecutive workgroups are expected to cover the 8 XCDs, which only sizes the
+// launch -- it is complete under any placement), never more working ones than there are items.
+inline int ess_xcd_grid(int items, const ess_xcd& x, int per_cu = 1) {
   if (x.ticket && x.host_need) *x.host_need = (uint32_t)items;
-  if (!x.ticket || !x.avoid) return items;
+  if (!x.ticket) return items;
+  if (x.grid_override > 0) return x.grid_override;
   const int off = __builtin_popcount(x.avoid & 0xffu);
-  return (items + (8 - off) - 1) / (8 - off) * 8 + 8;
+  int want = 32 * per_cu * (8 - off);
+  if (want > items) want = items;
+  if (want < 1) want = 1;
+  return off ? (want + (8 - off) - 1) / (8 - off) * 8 : want;
 }
 
 int ess_fail(int code, const char* fmt, ...);
@@ -122,10 +168,10 @@ int ess_launch_index_score(const ess_config& c, const uint8_t* q, const float* w
                            const int32_t* ctx_len, int B, int T, float* score, hipStream_t st,
                            const int32_t* block_table = nullptr, int n_pages = 0,
                            // optional: events that take the kernel's own start and end times
-                           hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr, ess_xcd xcd = ess_xcd{nullptr, 0, nullptr});
+                           hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr, ess_xcd xcd = ess_xcd{nullptr, 0, nullptr, 0});
 // xcd: ticket[0] and ticket[1] are used (two kernels)
 int ess_launch_topk(ess_ctx* ctx, const float* score, const int32_t* ctx_len, int B, int T, int32_t* idx,
-                    hipStream_t st, ess_xcd xcd = ess_xcd{nullptr, 0, nullptr});
+                    hipStream_t st, ess_xcd xcd = ess_xcd{nullptr, 0, nullptr, 0});
 size_t ess_topk_cand_bytes();
 // fill kernel (used instead of hipMemsetAsync so that callers may capture the stream in a graph)
 int ess_launch_calib_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
@@ -134,13 +180,15 @@ int ess_launch_append(const ess_config& c, const ess_cache& cache, const uint8_t
                       const float* new_scale, const int32_t* block_table, int n_pages, hipStream_t st);
 int ess_launch_fill_u32(uint32_t* p, int n, uint32_t value, hipStream_t st);
 int ess_probe_xcds(uint32_t* hist8, bool* even);   // blocking; at context creation
+int ess_init_cache_kernels(const ess_config& c, bool* fits);                     // function attributes (dynamic LDS sizes); at context creation
+int ess_init_attn_kernels();
 int ess_launch_cache_reset(const ess_config& c, const ess_cache& cache, int B, hipStream_t st);
 // look-up + LRU update + lists; n_sel = entries per sequence in idx ([B,n_sel], T lists of n_sel/T)
 // b0 = first sequence of the (sub-)batch: caller-owned pointers are passed already shifted, the
 // library's workspace arrays are shifted inside
 int ess_launch_bookkeeping(ess_ctx* ctx, const ess_cache& cache, const int32_t* idx, int B, int T, int kk,
                            uint32_t step, int32_t* slot_idx, int32_t* miss_count_out, hipStream_t st, int b0 = 0,
-                           bool count_step = true, ess_xcd xcd = ess_xcd{nullptr, 0, nullptr}, uint32_t* zero_tickets = nullptr,
+                           bool count_step = true, ess_xcd xcd = ess_xcd{nullptr, 0, nullptr, 0}, uint32_t* zero_tickets = nullptr,
                            int n_zero_tickets = 0);
 // only_xcds != 0: the fetch runs on these XCDs alone (`wgs` workgroups there, rows handed out through `ticket`)
 int ess_launch_fill(ess_ctx* ctx, const ess_cache& cache, int B, hipStream_t st, int b0 = 0, int wgs = 64,
@@ -151,7 +199,7 @@ int ess_launch_gather_rows(const ess_config& c, const uint8_t* slot_pool, const 
 // partial results starting at partial index `split0`
 int ess_launch_attn_partial(ess_ctx* ctx, const void* q, const uint8_t* slot_pool, const int32_t* list,
                             const int32_t* n_list, int B, int T, int split0, int nsplit, hipStream_t st, int b0 = 0,
-                            ess_xcd xcd = ess_xcd{nullptr, 0, nullptr});
+                            ess_xcd xcd = ess_xcd{nullptr, 0, nullptr, 0});
 int ess_attn_min_splits(const ess_config& c);   // fewest splits a list of k entries may be cut into
 // zero_cnt (may be NULL): n_zero int32 counters that the merge kernel also clears; b0 = first sequence of the
 // sub-batch of B sequences (out_bf16 and lse are the whole batch's arrays)

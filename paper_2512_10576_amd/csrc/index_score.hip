@@ -69,39 +69,41 @@ __global__ __launch_bounds__(kWaves * 64, T == 2 ? 2 : 1) void k_index_score(con
                                                               int Ttot, int t0, ess_xcd xcd, int nx, int nb_seq) {
   constexpr int KS = DI / 32;
   constexpr size_t kPageBytes = (size_t)kBatchTokens * (DI + 4);
-  // work item = (chunk, sequence): by workgroup index, or in arrival order off the XCDs to be avoided
   __shared__ int s_item;
-  const int item = ess_take_item(blockIdx.y * nx + blockIdx.x, nx * nb_seq, xcd, &s_item);
-  if (item < 0) return;
-  const int b = item / nx;
-  const int len = min(ctx_len[b], Lmax);
-  const int blk_base = (item % nx) * chunk_tokens;
-  if (blk_base >= len) return;
-  const int blk_end = min(blk_base + chunk_tokens, len);
-
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int g = lane >> 4;
   const int n = lane & 15;
-
-  // stationary operands: q as the A matrix (row = head), w per accumulator row
+  // stationary operands: q as the A matrix (row = head), w per accumulator row; reloaded when the sequence changes
   long qa[T][HB][KS];
   float wr[T][HB][4];
+  int q_of = -1;
+  // work item = (chunk, sequence): by workgroup index, or drawn from the launch's counter off the XCDs to be avoided
+  ESS_WORK_LOOP(xcd, blockIdx.y * nx + blockIdx.x, nx * nb_seq, &s_item, item) {
+  const int b = item / nx;
+  const int len = min(ctx_len[b], Lmax);
+  const int blk_base = (item % nx) * chunk_tokens;
+  if (blk_base >= len) continue;
+  const int blk_end = min(blk_base + chunk_tokens, len);
+
+  if (b != q_of) {
+    q_of = b;
 #pragma unroll
-  for (int t = 0; t < T; ++t) {
+    for (int t = 0; t < T; ++t) {
 #pragma unroll
-    for (int mb = 0; mb < HB; ++mb) {
-      const int head = mb * 16 + n;
-      if (head < Hi) {
-        load_row_share<DI>(q + ((size_t)(b * Ttot + t0 + t) * Hi + head) * DI, g, qa[t][mb]);
-      } else {
+      for (int mb = 0; mb < HB; ++mb) {
+        const int head = mb * 16 + n;
+        if (head < Hi) {
+          load_row_share<DI>(q + ((size_t)(b * Ttot + t0 + t) * Hi + head) * DI, g, qa[t][mb]);
+        } else {
 #pragma unroll
-        for (int kk = 0; kk < KS; ++kk) qa[t][mb][kk] = 0;
-      }
+          for (int kk = 0; kk < KS; ++kk) qa[t][mb][kk] = 0;
+        }
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int hrow = mb * 16 + g * 4 + i;
-        wr[t][mb][i] = hrow < Hi ? w[(size_t)(b * Ttot + t0 + t) * Hi + hrow] : 0.f;
+        for (int i = 0; i < 4; ++i) {
+          const int hrow = mb * 16 + g * 4 + i;
+          wr[t][mb][i] = hrow < Hi ? w[(size_t)(b * Ttot + t0 + t) * Hi + hrow] : 0.f;
+        }
       }
     }
   }
@@ -110,7 +112,7 @@ __global__ __launch_bounds__(kWaves * 64, T == 2 ? 2 : 1) void k_index_score(con
   const int last_row = Lmax - 1;
   constexpr int kStride = kWaves * kBatchTokens;
   const int base0 = blk_base + wave * kBatchTokens;
-  if (base0 >= blk_end) return;
+  if (base0 >= blk_end) continue;
   const int nb = (blk_end - base0 + kStride - 1) / kStride;
 
   // paged: lane j holds the page of this wave's j-th batch (a workgroup covers at most 2048 tokens:
@@ -224,6 +226,7 @@ __global__ __launch_bounds__(kWaves * 64, T == 2 ? 2 : 1) void k_index_score(con
   }
 #undef ESS_LOAD
 #undef ESS_COMP
+  }
 }
 
 struct IdxArgs {
@@ -238,6 +241,16 @@ struct IdxArgs {
 template <int HB, int DI, int T, bool PAGED>
 void launch_k(dim3 grid, hipStream_t st, const IdxArgs& a) {
   const dim3 block(kWaves * 64);
+  if (a.xcd.ticket) {
+    // ticket-fed: as many workgroups as the working XCDs hold at once; each draws items until none is left
+    static int per_cu = 0;
+    if (per_cu == 0) {
+      int n = 0;
+      if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_index_score<HB, DI, T, PAGED>, kWaves * 64, 0) != hipSuccess || n < 1) n = 1;
+      per_cu = n;
+    }
+    grid = dim3(ess_xcd_grid(a.nx * a.nb_seq, a.xcd, per_cu));
+  }
   if (a.ev_start || a.ev_stop)      // timed launch: the events take the kernel's own start and end
     hipExtLaunchKernelGGL((k_index_score<HB, DI, T, PAGED>), grid, block, 0, st, a.ev_start, a.ev_stop, 0, a.q, a.w, a.key,
                           a.ctx_len, a.score, a.Lmax, a.Hi, a.chunk, a.block_table, a.n_pages, a.Ttot, a.t0, a.xcd, a.nx, a.nb_seq);
@@ -280,8 +293,7 @@ int ess_launch_index_score(const ess_config& c, const uint8_t* q, const float* w
   const int chunk = ((long)B * Lmax >= 2048L * 1024) ? 2048 : 1024;
   const int nx = (Lmax + chunk - 1) / chunk;
   if (xcd.ticket && T > 2) return ess_fail(ESS_ERR_UNSUPPORTED, "internal: one ticket serves one index-score launch");
-  dim3 grid(nx, B);
-  if (xcd.ticket) grid = dim3(ess_xcd_grid(nx * B, xcd));
+  const dim3 grid(nx, B);
   // two query tokens per launch; the events of a timed call bracket the whole series
   for (int t0 = 0; t0 < T; t0 += 2) {
     const int Tl = T - t0 < 2 ? T - t0 : 2;

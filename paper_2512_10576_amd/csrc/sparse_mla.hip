@@ -68,9 +68,14 @@ __device__ __forceinline__ uint32_t lds_addr_of(const void* p) {
 }
 
 // 64 lanes x 16 bytes from `gptr` (per lane) to LDS address `lds_dst` + 16 * lane (lds_dst wave-uniform)
+// The statement writes m0 and says so (m0 is reserved: the compiler never keeps a value of its own there across
+// statements, but the clobber makes the write visible to it; clang warns about reserved registers in clobber lists).
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_dst) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gptr), "s"(lds_dst) : "memory");
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gptr), "s"(lds_dst) : "memory", "m0");
 }
+#pragma clang diagnostic pop
 
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {     // vmcnt <= N, other counters untouched
@@ -110,20 +115,6 @@ constexpr int tr_nbuf(int fmt) { return fmt == ESS_FMT_BF16 ? 4 : 2; }
 constexpr int tr_lds_bytes(int fmt) { return tr_nbuf(fmt) * TR_RAW_BYTES + MAX_TPS * TILE * 4; }   // 155648 | 81920
 constexpr float kLazyMax = 8.0f;
 
-#ifdef ESS_ATTN_PHASE_TIMING
-__device__ unsigned long long ess_dbg_phase[8];
-#define ESS_PH(i)                                                                   \
-  do {                                                                              \
-    if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && tid == 0) {        \
-      const long long t_ = clock64();                                               \
-      ess_dbg_phase[i] += (unsigned long long)(t_ - ph_t);                          \
-      ph_t = t_;                                                                    \
-    }                                                                               \
-  } while (0)
-#else
-#define ESS_PH(i) do { } while (0)
-#endif
-
 // The 128 output accumulators of a wave live in AGPRs a0..a127 under fixed names, outside the
 // compiler's register allocation: every access is an asm statement that names them.  (Left to the
 // allocator they are copied to VGPRs and back once per tile, 256 moves, because the rare rescale
@@ -136,17 +127,25 @@ __device__ unsigned long long ess_dbg_phase[8];
 #define ESS_ACC_TUPLES(X) X(0, 0, 1, 2, 3) X(1, 4, 5, 6, 7) X(2, 8, 9, 10, 11) X(3, 12, 13, 14, 15) X(4, 16, 17, 18, 19) X(5, 20, 21, 22, 23) X(6, 24, 25, 26, 27) X(7, 28, 29, 30, 31) X(8, 32, 33, 34, 35) X(9, 36, 37, 38, 39) X(10, 40, 41, 42, 43) X(11, 44, 45, 46, 47) X(12, 48, 49, 50, 51) X(13, 52, 53, 54, 55) X(14, 56, 57, 58, 59) X(15, 60, 61, 62, 63) X(16, 64, 65, 66, 67) X(17, 68, 69, 70, 71) X(18, 72, 73, 74, 75) X(19, 76, 77, 78, 79) X(20, 80, 81, 82, 83) X(21, 84, 85, 86, 87) X(22, 88, 89, 90, 91) X(23, 92, 93, 94, 95) X(24, 96, 97, 98, 99) X(25, 100, 101, 102, 103) X(26, 104, 105, 106, 107) X(27, 108, 109, 110, 111) X(28, 112, 113, 114, 115) X(29, 116, 117, 118, 119) X(30, 120, 121, 122, 123) X(31, 124, 125, 126, 127)
 #define ESS_ACC_REGS(X) X(0, 0) X(1, 1) X(2, 2) X(3, 3) X(4, 4) X(5, 5) X(6, 6) X(7, 7) X(8, 8) X(9, 9) X(10, 10) X(11, 11) X(12, 12) X(13, 13) X(14, 14) X(15, 15) X(16, 16) X(17, 17) X(18, 18) X(19, 19) X(20, 20) X(21, 21) X(22, 22) X(23, 23) X(24, 24) X(25, 25) X(26, 26) X(27, 27) X(28, 28) X(29, 29) X(30, 30) X(31, 31) X(32, 32) X(33, 33) X(34, 34) X(35, 35) X(36, 36) X(37, 37) X(38, 38) X(39, 39) X(40, 40) X(41, 41) X(42, 42) X(43, 43) X(44, 44) X(45, 45) X(46, 46) X(47, 47) X(48, 48) X(49, 49) X(50, 50) X(51, 51) X(52, 52) X(53, 53) X(54, 54) X(55, 55) X(56, 56) X(57, 57) X(58, 58) X(59, 59) X(60, 60) X(61, 61) X(62, 62) X(63, 63) X(64, 64) X(65, 65) X(66, 66) X(67, 67) X(68, 68) X(69, 69) X(70, 70) X(71, 71) X(72, 72) X(73, 73) X(74, 74) X(75, 75) X(76, 76) X(77, 77) X(78, 78) X(79, 79) X(80, 80) X(81, 81) X(82, 82) X(83, 83) X(84, 84) X(85, 85) X(86, 86) X(87, 87) X(88, 88) X(89, 89) X(90, 90) X(91, 91) X(92, 92) X(93, 93) X(94, 94) X(95, 95) X(96, 96) X(97, 97) X(98, 98) X(99, 99) X(100, 100) X(101, 101) X(102, 102) X(103, 103) X(104, 104) X(105, 105) X(106, 106) X(107, 107) X(108, 108) X(109, 109) X(110, 110) X(111, 111) X(112, 112) X(113, 113) X(114, 114) X(115, 115) X(116, 116) X(117, 117) X(118, 118) X(119, 119) X(120, 120) X(121, 121) X(122, 122) X(123, 123) X(124, 124) X(125, 125) X(126, 126) X(127, 127)
 
-template <int VB> __device__ __forceinline__ void pv_mfma(const bf16x8& a, const bf16x8& b);
-#define X(vb, r0, r1, r2, r3)                                                                        \
-  template <> __device__ __forceinline__ void pv_mfma<vb>(const bf16x8& a, const bf16x8& b) {        \
-    asm volatile("v_mfma_f32_16x16x32_bf16 a[" #r0 ":" #r3 "], %0, %1, a[" #r0 ":" #r3 "]"           \
-                 : : "v"(a), "v"(b) : "a" #r0, "a" #r1, "a" #r2, "a" #r3);                           \
+// The compiler's hazard logic does not look into asm statements, and an MFMA that directly follows the vector
+// ALU instruction producing one of its VGPR operands was seen to read the register's previous contents.  The
+// first MFMA of every chunk (WAIT) therefore carries its wait states inside its own statement, where no
+// scheduling can separate them from it; the later ones of a chunk follow an MFMA.
+template <int VB, bool WAIT> __device__ __forceinline__ void pv_mfma(const bf16x8& a, const bf16x8& b);
+#define X(vb, r0, r1, r2, r3)                                                                            \
+  template <> __device__ __forceinline__ void pv_mfma<vb, false>(const bf16x8& a, const bf16x8& b) {     \
+    asm volatile("v_mfma_f32_16x16x32_bf16 a[" #r0 ":" #r3 "], %0, %1, a[" #r0 ":" #r3 "]"               \
+                 : : "v"(a), "v"(b) : "a" #r0, "a" #r1, "a" #r2, "a" #r3);                               \
+  }                                                                                                      \
+  template <> __device__ __forceinline__ void pv_mfma<vb, true>(const bf16x8& a, const bf16x8& b) {      \
+    asm volatile("s_nop 7\n\tv_mfma_f32_16x16x32_bf16 a[" #r0 ":" #r3 "], %0, %1, a[" #r0 ":" #r3 "]"    \
+                 : : "v"(a), "v"(b) : "a" #r0, "a" #r1, "a" #r2, "a" #r3);                               \
   }
 ESS_ACC_TUPLES(X)
 #undef X
 template <int BASE, int... I>
 __device__ __forceinline__ void pv_chunk(const bf16x8 (&fv)[sizeof...(I)], const bf16x8& pb, std::integer_sequence<int, I...>) {
-  (pv_mfma<BASE + I>(fv[I], pb), ...);
+  (pv_mfma<BASE + I, I == 0>(fv[I], pb), ...);
 }
 __device__ __forceinline__ void acc_zero() {
 #define X(n, r) asm volatile("v_accvgpr_write_b32 a" #r ", 0" : : : "a" #r);
@@ -202,20 +201,58 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
     int nsplit, _Float16* __restrict__ o_part, float* __restrict__ lse_part, const uint8_t* __restrict__ zero_row,
     ess_xcd xcd, int n_bt, int n_hg) {
   extern __shared__ __align__(16) uint8_t lds[];
-  // work item = (split, bt, head group): by workgroup index, or in arrival order off the XCDs to be avoided
   __shared__ int s_item;
-  const int item = ess_take_item(blockIdx.x + nsplit * (blockIdx.y + n_bt * blockIdx.z), nsplit * n_bt * n_hg, xcd, &s_item);
-  if (item < 0) return;
   constexpr bool kDma = FMT == ESS_FMT_BF16;       // rows go to LDS as they are; else through registers, dequantised
   constexpr int NBUF = tr_nbuf(FMT);
   int32_t* slot_cache = reinterpret_cast<int32_t*>(lds + NBUF * TR_RAW_BYTES);   // [MAX_TPS][32]
   const uint32_t lds0 = lds_addr_of(lds);
-
-  const int split = item % nsplit;
-  const int bt = (item / nsplit) % n_bt;
-  const int hg = item / (nsplit * n_bt);
+  // Work item = (split, bt, head group): by workgroup index, or drawn from counters off the XCDs to be avoided.
+  // The head groups of one (split, bt) read the same entries, so they should meet in one L2: every XCD that takes
+  // work has a counter of its own (class c of nw) that hands out pairs c, c + nw, c + 2 nw .. head group by head
+  // group; a workgroup whose class has run out goes on with the next class, so any one workgroup could finish
+  // the whole launch.
+  const int n_pairs = nsplit * n_bt, n_items = n_pairs * n_hg;
+  const bool dyn = xcd.ticket != nullptr;
+  int cls = 0, nw = 1, tried = 1;
+  if (dyn) {
+    if (!ess_ticket_join(xcd, &s_item)) return;
+    const uint32_t work = ~xcd.avoid & 0xffu;
+    const int x = ess_xcc_id() & 7;
+    nw = max(__popc(work), 1);
+    cls = ((work >> x) & 1u) ? __popc(work & ((1u << x) - 1u)) : 0;
+  }
+  uint32_t tk = dyn ? ess_ticket_request(xcd.ticket + 2 + cls) : 0u;
+  for (int round = 0;; ++round) {
+  int split, bt, hg;
+  if (dyn) {
+    int item;
+    for (;;) {
+      uint32_t mine = 0xffffffffu;
+      if (threadIdx.x == 0) {
+        const uint32_t pair = (tk / (uint32_t)n_hg) * (uint32_t)nw + (uint32_t)cls;
+        if (pair < (uint32_t)n_pairs) mine = pair * (uint32_t)n_hg + tk % (uint32_t)n_hg;
+      }
+      item = ess_ticket_publish(mine, n_items, &s_item);
+      if (item >= 0 || tried == nw) break;
+      ++tried;
+      cls = cls + 1 == nw ? 0 : cls + 1;
+      tk = ess_ticket_request(xcd.ticket + 2 + cls);
+    }
+    if (item < 0) break;
+    tk = ess_ticket_request(xcd.ticket + 2 + cls);      // the next item: the answer is needed only after this one
+    hg = item % n_hg;
+    split = (item / n_hg) % nsplit;
+    bt = item / (n_hg * nsplit);
+  } else {
+    if (round) break;
+    split = blockIdx.x; bt = blockIdx.y; hg = blockIdx.z;
+  }
   const int b = bt / T;
-  const int tid = threadIdx.x, lane = tid & 63;
+  // the thread index passes through an empty asm statement so that what is derived from it (lane constants, LDS
+  // offsets) is computed per work item, where it is needed, instead of being kept in registers across the loop
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 4, n16 = lane & 15;
   const int head0 = (hg * 4 + wave) * 16;
@@ -340,9 +377,6 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
 #pragma unroll
   for (int c = 0; c < 8; ++c) voff[c] = (uint32_t)(trow * TRP + (tj & 1) * 8) + (((uint32_t)(32 * c)) ^ c4);
 
-#ifdef ESS_ATTN_PHASE_TIMING
-  long long ph_t = clock64();
-#endif
   for (int it = 0; it < my_tiles; ++it) {
     const uint32_t KLa = lds0 + (uint32_t)((it % NBUF) * TR_RAW_BYTES);
     const uint8_t* KL = lds + (it % NBUF) * TR_RAW_BYTES;
@@ -354,9 +388,7 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
       // this wave's gathers of tile `it` have landed when at most those of the later tiles are outstanding
       const int later = min(my_tiles - 1 - it, NBUF - 2);
       if (later >= 2) wait_vmcnt<2 * DMA_PER_TILE>(); else if (later == 1) wait_vmcnt<DMA_PER_TILE>(); else wait_vmcnt<0>();
-      ESS_PH(4);
       __syncthreads();                         // ... everyone's did; and everyone is done with tile it-1
-      ESS_PH(5);
       if (more) gather_sources(it + NBUF - 1, src);
     } else {
       __syncthreads();                         // tile `it` is in LDS (written a tile ago); everyone is done with tile it-1
@@ -370,7 +402,6 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
       }
       continue;
     }
-    ESS_PH(0);
 
     // ---- S^T = K Q^T; A fragments read six k-steps ahead of the MFMAs that use them; three gather
     // instructions of tile it+3 after each chunk of fragment reads
@@ -422,7 +453,6 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
     load_v(1, fv[1]);
     const bool ok[8] = {v0.x >= 0, v0.y >= 0, v0.z >= 0, v0.w >= 0, v1.x >= 0, v1.y >= 0, v1.z >= 0, v1.w >= 0};
     float z[8];
-    ESS_PH(1);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       z[i] = ok[i] ? s0[i] * scale_log2e : -__builtin_inff();
@@ -447,12 +477,7 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
     }
     l_run += psum;
     uint4 pw = make_uint4(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7]));
-    // The MFMAs below are asm statements, which the compiler's hazard logic does not look into, and a
-    // vector ALU write followed at once by an MFMA that reads the register gave the MFMA the old value.
-    // The statement is tied to the four registers so that it stays between their last write and the MFMAs.
-    asm volatile("s_nop 7" : "+v"(pw.x), "+v"(pw.y), "+v"(pw.z), "+v"(pw.w));
     const bf16x8 pb = *reinterpret_cast<bf16x8*>(&pw);
-    ESS_PH(2);
 
     // ---- O^T += V^T P^T, A fragments by transposing reads, eight blocks ahead
     static_assert(VBLOCKS / CV == 4, "four chunks of value blocks");
@@ -463,7 +488,6 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
     load_v(3, fv[1]);
     pv_chunk<2 * CV>(fv[0], pb, seq);
     pv_chunk<3 * CV>(fv[1], pb, seq);
-    ESS_PH(3);
   }
   // the hazard logic does not see the MFMAs inside the asm statements: let the last ones retire
   // before their results are read
@@ -488,6 +512,7 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
       if (g == 0) lse_part[prow] = l_tot > 0.f ? (m_ref + log2f(l_tot)) * kLn2 : -__builtin_inff();
     }
   }
+  }
 }
 
 // out[bt,h,:] = sum_s exp(lse_s - lse) * o_s ;  lse = log sum_s exp(lse_s).  One wave per (bt,h).
@@ -503,7 +528,11 @@ __global__ __launch_bounds__(256) void k_attn_merge(const _Float16* __restrict__
   if (chk.tickets && blockIdx.x == 0 && threadIdx.x == 0) {
     bool short_of = false;
 #pragma unroll
-    for (int i = 0; i < ESS_N_TICKETS; ++i) short_of |= chk.need[i] != 0 && chk.tickets[i] < chk.need[i];
+    for (int i = 0; i < ESS_N_TICKETS; ++i) {
+      uint32_t handed = chk.tickets[i * ESS_TICKET_WORDS];               // the launch's counter, or its per-XCD counters
+      for (int c = 2; c < 10; ++c) handed += chk.tickets[i * ESS_TICKET_WORDS + c];
+      short_of |= chk.need[i] != 0 && handed < chk.need[i];
+    }
     if (short_of) *chk.flag = 1;
   }
   const int rowi = blockIdx.x * 4 + (threadIdx.x >> 6);      // bt*H + h
@@ -557,13 +586,22 @@ int ess_attn_min_splits(const ess_config& c) {
   return (tiles + MAX_TPS - 1) / MAX_TPS;
 }
 
+// At context creation (on the context's device): the partial-attention kernels use more dynamic LDS than the default limit.
+int ess_init_attn_kernels() {
+  ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_partial_tr<ESS_FMT_BF16>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, tr_lds_bytes(ESS_FMT_BF16)));
+  ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_partial_tr<ESS_FMT_FP8>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, tr_lds_bytes(ESS_FMT_FP8)));
+  return ESS_OK;
+}
+
 int ess_launch_attn_partial(ess_ctx* ctx, const void* q, const uint8_t* slot_pool, const int32_t* list,
                             const int32_t* n_list, int B, int T, int split0, int nsplit, hipStream_t st, int b0, ess_xcd xcd) {
   const ess_config& c = ctx->cfg;
   if (nsplit < ess_attn_min_splits(c)) return ess_fail(ESS_ERR_INVALID_ARG, "internal: too few attention splits");
   const int n_hg = (c.attn_heads + 63) / 64;            // 64 heads per workgroup
   dim3 grid(nsplit, B * T, n_hg);
-  if (xcd.ticket) grid = dim3(ess_xcd_grid(nsplit * B * T * n_hg, xcd));
+  if (xcd.ticket) grid = dim3(ess_xcd_grid(nsplit * B * T * n_hg, xcd));     // one workgroup per CU
   const float sc = c.sm_scale * kLog2e;
   const uint16_t* qq = static_cast<const uint16_t*>(q);
   // partial results of sequence b0 onward
@@ -571,14 +609,10 @@ int ess_launch_attn_partial(ess_ctx* ctx, const void* q, const uint8_t* slot_poo
   float* lp = ctx->lse_part + (size_t)b0 * T * ESS_MAX_SPLITS * c.attn_heads;
   if (c.latent_fmt == ESS_FMT_BF16) {
     constexpr int lds = tr_lds_bytes(ESS_FMT_BF16);
-    ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_partial_tr<ESS_FMT_BF16>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, lds));
     hipLaunchKernelGGL(k_attn_partial_tr<ESS_FMT_BF16>, grid, dim3(NTH), lds, st, qq, slot_pool, list, n_list, T,
                        c.attn_heads, c.topk, c.slots_per_seq, c.row_stride, sc, split0, nsplit, op, lp, ctx->zero_row, xcd, B * T, n_hg);
   } else {
     constexpr int lds = tr_lds_bytes(ESS_FMT_FP8);
-    ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_partial_tr<ESS_FMT_FP8>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, lds));
     hipLaunchKernelGGL(k_attn_partial_tr<ESS_FMT_FP8>, grid, dim3(NTH), lds, st, qq, slot_pool, list, n_list, T,
                        c.attn_heads, c.topk, c.slots_per_seq, c.row_stride, sc, split0, nsplit, op, lp, ctx->zero_row, xcd, B * T, n_hg);
   }

@@ -100,24 +100,6 @@ __device__ __forceinline__ void wave_append(bool pred, V val, V* list, uint32_t*
   if (pred && pos < cap) list[pos] = val;
 }
 
-// ascending bitonic sort of a[0..n), n a power of two, by all NT threads
-template <typename V>
-__device__ void bitonic_sort(V* a, int n) {
-  for (int size = 2; size <= n; size <<= 1) {
-    for (int stride = size >> 1; stride > 0; stride >>= 1) {
-      __syncthreads();
-      for (int t = threadIdx.x; t < (n >> 1); t += NT) {
-        const int lo = 2 * t - (t & (stride - 1));
-        const int hi = lo + stride;
-        const bool up = (lo & size) == 0;
-        const V x = a[lo], y = a[hi];
-        if ((x > y) == up) { a[lo] = y; a[hi] = x; }
-      }
-    }
-  }
-  __syncthreads();
-}
-
 // Calls f(position, score, valid) for every position of the row, by all threads the same number of
 // times (f may hold wave-wide operations).  Each thread has four 16-byte loads in flight per round,
 // which is what makes one workgroup able to pull a 512 KiB row at cache bandwidth, not at latency.
@@ -216,17 +198,12 @@ __device__ __forceinline__ void scan_row_rounds(const float* __restrict__ srow, 
 // the row by itself like MODE 0.  The hand-over is the kernel boundary: workgroups of one kernel
 // never exchange data (an agent-scope fence inside a kernel costs tens of microseconds on this
 // multi-die part, where it writes the L2 back).  g_cnt is zero between steps: MODE 2 clears it.
+// one work item = (part, row) of k_topk<MODE>; every field of `sm` is set before it is read, so items may follow each other
 template <int MODE>
-__global__ __launch_bounds__(NT) void k_topk(const float* __restrict__ score, const int32_t* __restrict__ ctx_len,
-                                             int T, int Lmax, int k, int IB, int32_t* __restrict__ idx_out,
-                                             unsigned long long* __restrict__ g_cand, uint32_t* __restrict__ g_cnt,
-                                             ess_xcd xcd, int rows, int parts_arg) {
-  __shared__ TopkShared sm;
-  // work item = (part, row): by workgroup index, or in arrival order off the XCDs to be avoided
-  __shared__ int s_item;
-  const int parts = MODE == 1 ? parts_arg : 1;
-  const int item = ess_take_item(MODE == 1 ? blockIdx.y * parts + blockIdx.x : blockIdx.x, rows * parts, xcd, &s_item);
-  if (item < 0) return;
+__device__ __forceinline__ void topk_item(TopkShared& sm, int item, int parts, const float* __restrict__ score,
+                                          const int32_t* __restrict__ ctx_len, int T, int Lmax, int k, int IB,
+                                          int32_t* __restrict__ idx_out, unsigned long long* __restrict__ g_cand,
+                                          uint32_t* __restrict__ g_cnt) {
   const int row = item / parts;
   const int part = item % parts;
   const int b = row / T, t = row % T;
@@ -514,6 +491,20 @@ __global__ __launch_bounds__(NT) void k_topk(const float* __restrict__ score, co
   }
 }
 
+template <int MODE>
+__global__ __launch_bounds__(NT) void k_topk(const float* __restrict__ score, const int32_t* __restrict__ ctx_len,
+                                             int T, int Lmax, int k, int IB, int32_t* __restrict__ idx_out,
+                                             unsigned long long* __restrict__ g_cand, uint32_t* __restrict__ g_cnt,
+                                             ess_xcd xcd, int rows, int parts_arg) {
+  __shared__ TopkShared sm;
+  __shared__ int s_item;
+  const int parts = MODE == 1 ? parts_arg : 1;
+  // work item = (part, row): by workgroup index, or drawn from the launch's counter off the XCDs to be avoided
+  ESS_WORK_LOOP(xcd, MODE == 1 ? blockIdx.y * parts + blockIdx.x : blockIdx.x, rows * parts, &s_item, item) {
+    topk_item<MODE>(sm, item, parts, score, ctx_len, T, Lmax, k, IB, idx_out, g_cand, g_cnt);
+  }
+}
+
 }  // namespace
 
 int ess_launch_topk(ess_ctx* ctx, const float* score, const int32_t* ctx_len, int B, int T, int32_t* idx,
@@ -529,8 +520,8 @@ int ess_launch_topk(ess_ctx* ctx, const float* score, const int32_t* ctx_len, in
     parts = 256 / rows;
     if (parts > 8) parts = 8;
   }
-  const ess_xcd x0 = xcd, x1 = ess_xcd{xcd.ticket ? xcd.ticket + 1 : nullptr, xcd.avoid,
-                                                       xcd.host_need ? xcd.host_need + 1 : nullptr};
+  const ess_xcd x0 = xcd, x1 = ess_xcd{xcd.ticket ? xcd.ticket + ESS_TICKET_WORDS : nullptr, xcd.avoid,
+                                       xcd.host_need ? xcd.host_need + 1 : nullptr, xcd.grid_override};
   if (parts > 1) {
     const dim3 g1 = xcd.ticket ? dim3(ess_xcd_grid(parts * rows, x0)) : dim3(parts, rows);
     hipLaunchKernelGGL(k_topk<1>, g1, dim3(NT), 0, st, score, ctx_len, T, c.max_ctx, c.topk, IB, idx,

@@ -180,3 +180,103 @@ def test_switch_with_confined_fetches_at_odd_batch_sizes(ess_lib, B, ctx_lens):
     # fetch is long against everything beside it
     assert confined[0] == 0 and min(confined[1:]) >= 1, confined
     assert parts[1:] == [1 if B >= 2 else 0] * 2, parts
+
+
+@pytest.mark.parametrize("grid", [1, 2, 7, 8, 24, 0])
+def test_ticket_fed_launches_complete_at_any_launch_size(ess_lib, grid):
+    """Confined schedules hand their work out by ticket and every working workgroup draws tickets until none is
+    left, so the result may not depend on how many workgroups a launch has nor on where the hardware puts
+    them.  The test hook fixes the size of every ticket-fed launch (1 = a single workgroup, which then does
+    all the work wherever it lands; 0 = the library's own sizing); outputs and cache state equal the plain DA
+    schedule bit for bit, and no assertion of the library fires."""
+    from paper_2512_10576_amd import binding as bnd
+    print("edges: ticket-fed launches with", grid, "workgroups", flush=True)
+    B, T, Hi, Di, L, k, H, S = 5, 2, 64, 128, 5000, 512, 128, 1300
+    qi, w, key = synth.indexer_inputs(87, B, T, Hi, Di, L, 8, 8, 16)
+    ctx_len = torch.tensor([5000, 4000, 0, 3000, 2111], dtype=torch.int32)
+    host = synth.latent_rows_bf16(87, B * L).reshape(B, L, 1152)
+    hp = torch.empty((B, L, 1152), dtype=torch.uint8, pin_memory=True)
+    hp.copy_(host)
+    dev = [x.cuda() for x in (qi, w, key, ctx_len)]
+    qws = [(qi.cuda(), w.cuda())] + [tuple(x.cuda() for x in synth.indexer_inputs(87 + s, B, T, Hi, Di, L, 8, 8, 16)[:2])
+                                     for s in (1, 2)]
+    results, confined = {}, []
+    for flags in (0, 4):
+        ctx = _ctx(max_batch=B, max_q_tokens=T, max_ctx=L, idx_heads=Hi, idx_dim=Di, topk=k, attn_heads=H,
+                   slots_per_seq=S, flags=flags)
+        if flags == 4:
+            ctx.set_overlap_threshold(0)
+            ctx.debug_ticket_grid(grid)
+        cache = bnd.Cache.allocate(ctx.cfg, B, host_pool=hp,
+                                   slot_pool=torch.full((B, S, 1152), 0x7F, dtype=torch.uint8, device="cuda"))
+        ctx.cache_reset(cache, B)
+        idx_out = torch.empty((B, T, k), dtype=torch.int32, device="cuda")
+        out = torch.empty((B, T, H, 512), dtype=torch.bfloat16, device="cuda")
+        lse = torch.empty((B, T, H), dtype=torch.float32, device="cuda")
+        mc = torch.empty((B,), dtype=torch.int32, device="cuda")
+        steps = []
+        for step in range(1, 4):
+            q = synth.attn_query(95 + step, B, T, H)
+            ctx.decode_step(cache, qws[step - 1][0], qws[step - 1][1], dev[2], dev[3], q.cuda(), step, idx_out, out, lse, mc)
+            torch.cuda.synchronize()
+            if flags == 4:
+                confined.append(ctx.last_confined())
+            steps.append((idx_out.clone(), out.clone(), lse.clone(), mc.clone(), cache.slot_of.clone(),
+                          cache.token_of.clone(), cache.stamp.clone(), cache.slot_pool.clone()))
+        assert ctx.get_stats()["steps"] == 3                     # also: no assertion of a confined step pending
+        ctx.close()
+        results[flags] = steps
+    for s0, s4 in zip(results[0], results[4]):
+        for x, y in zip(s0, s4):
+            assert torch.equal(x, y)
+    assert confined[0] == 0 and min(confined[1:]) >= 1, confined
+
+
+@pytest.mark.parametrize("stride,fmt", [(1152, 0), (656, 1)])
+def test_calib_memcpy_rows_delivers_host_pool_rows(ess_lib, stride, fmt):
+    """The per-entry copy the paper starts from (Sec. 3.1: one memcpy per block): the rows it delivers are the
+    host pool's bytes, and the same entries fetched by the library's own path (ess_gather_latent on an empty
+    pool: bookkeeping + fetch kernel reading the pinned pool by address) are the same bytes, which are also
+    what the oracle's fill delivers."""
+    from paper_2512_10576_amd import binding as bnd
+    print("calib_memcpy_rows, entry size", stride, flush=True)
+    B, L, k, S = 3, 4096, 300, 640
+    rng = np.random.default_rng(21)
+    host = torch.from_numpy(rng.integers(0, 256, (B, L, stride), dtype=np.uint8))
+    hp = torch.empty((B, L, stride), dtype=torch.uint8, pin_memory=True)
+    hp.copy_(host)
+    pos = np.stack([np.sort(rng.choice(L, k, replace=False)) for _ in range(B)]).astype(np.int32)     # [B,k]
+    flat = torch.from_numpy((pos.astype(np.int64) + np.arange(B)[:, None] * L).reshape(-1)).contiguous()
+    dst = torch.full((B * k, stride), 0xEE, dtype=torch.uint8, device="cuda")
+    bnd.calib_memcpy_rows(dst, hp, flat, stride, stride)
+    torch.cuda.synchronize()
+    want = host.numpy().reshape(B * L, stride)[flat.numpy()]
+    assert np.array_equal(dst.cpu().numpy(), want)
+    # a copy of fewer bytes than the stride leaves the rest of each destination row alone
+    dst2 = torch.full((B * k, stride), 0xEE, dtype=torch.uint8, device="cuda")
+    bnd.calib_memcpy_rows(dst2, hp, flat, stride - 16, stride)
+    torch.cuda.synchronize()
+    d2 = dst2.cpu().numpy()
+    assert np.array_equal(d2[:, :stride - 16], want[:, :stride - 16]) and np.all(d2[:, stride - 16:] == 0xEE)
+    # the library's fetch path on the same entries
+    ctx = _ctx(max_batch=B, max_q_tokens=1, max_ctx=L, idx_heads=4, idx_dim=32, topk=k, attn_heads=8, slots_per_seq=S,
+               latent_fmt=fmt, row_stride=stride)
+    cache = bnd.Cache.allocate(ctx.cfg, B, host_pool=hp)
+    ctx.cache_reset(cache, B)
+    slot_idx = torch.empty((B, 1, k), dtype=torch.int32, device="cuda")
+    rows = torch.empty((B, 1, k, stride), dtype=torch.uint8, device="cuda")
+    mc = torch.empty((B,), dtype=torch.int32, device="cuda")
+    ctx.gather_latent(cache, torch.from_numpy(pos).reshape(B, 1, k).cuda(), torch.full((B,), L, dtype=torch.int32).cuda(), 1,
+                      slot_idx, rows, mc)
+    torch.cuda.synchronize()
+    assert np.array_equal(rows.cpu().numpy().reshape(B * k, stride), want)
+    oc = O.SlotCache(B, L, S)
+    opool = np.zeros((B, S, stride), np.uint8)
+    r = oc.step(pos.reshape(B, 1, k), 1)
+    O.fill_slots(opool, host.numpy(), r["miss_tok"], r["victims"])
+    assert np.array_equal(O.gather_rows(opool, r["slot_idx"]).reshape(B * k, stride), want)
+    assert np.array_equal(mc.cpu().numpy(), r["miss_count"]) and np.array_equal(cache.slot_pool.cpu().numpy(), opool)
+    ctx.close()
+    with pytest.raises(bnd.EssError) as ei:                          # a negative row index is refused before any copy
+        bnd.calib_memcpy_rows(dst, hp, torch.tensor([3, -1], dtype=torch.int64), stride, stride)
+    assert ei.value.code == bnd.ESS_ERR_INVALID_ARG
