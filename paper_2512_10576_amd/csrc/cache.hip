@@ -93,7 +93,7 @@ __device__ void bitonic_sort_u64(unsigned long long* a, int n) {
 // idx: [B, T, kk] selected positions (-1 = none).  Dynamic LDS: bitmap of Lmax bits.
 // REG: the slots a thread owns (S / 1024, rounded up, at most 16) are held in registers, so the
 // stamps are read from memory once, all loads of a thread in flight together.
-template <bool REG>
+template <bool REG, bool DYN>
 __global__ __launch_bounds__(BT) void k_bookkeeping(
     const int32_t* __restrict__ idx, int T, int kk, int Lmax, int S, int32_t* __restrict__ slot_of,
     int32_t* __restrict__ token_of, uint32_t* __restrict__ stamp, uint32_t step, int32_t* __restrict__ slot_idx_out,
@@ -112,10 +112,11 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
   constexpr int RS = 16;                       // register-held stamps per thread
   // work counters of the kernels that follow this one beside the fetch it feeds: cleared here, by the first
   // workgroup, so that no launch has to do it (this kernel itself never uses the counters it clears)
-  if (zero_tickets && blockIdx.x == 0)
-    for (int i = threadIdx.x; i < n_zero_tickets; i += BT) zero_tickets[i] = 0;
+  if (zero_tickets && blockIdx.x == 0)            // n_zero_tickets launches' counters: the words in use
+    for (int i = threadIdx.x; i < n_zero_tickets * ESS_TICKET_USED; i += BT)
+      zero_tickets[(i / ESS_TICKET_USED) * ESS_TICKET_WORDS + (i % ESS_TICKET_USED) * ESS_TK_STRIDE] = 0;
   // work item = sequence: by workgroup index, or drawn from the launch's counter off the XCDs to be avoided
-  ESS_WORK_LOOP(xcd, blockIdx.x, n_seq, &s_item, b) {
+  ESS_WORK_LOOP(DYN, xcd, blockIdx.x, n_seq, &s_item, b) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int W = (Lmax + 31) >> 5;
   const int nsel = T * kk;
@@ -585,7 +586,8 @@ int ess_launch_bookkeeping(ess_ctx* ctx, const ess_cache& cache, const int32_t* 
   const bool lists = (kk == c.topk);           // compacted lists have the pitch of the top-k
   const size_t lo = (size_t)b0 * T * c.topk;   // offset of this sub-batch in the per-(b,t) lists
   const bool reg = c.slots_per_seq <= BT * 16;
-  auto kern = reg ? &k_bookkeeping<true> : &k_bookkeeping<false>;
+  auto kern = xcd.ticket ? (reg ? &k_bookkeeping<true, true> : &k_bookkeeping<false, true>)
+                         : (reg ? &k_bookkeeping<true, false> : &k_bookkeeping<false, false>);
   hipLaunchKernelGGL(kern, dim3(ess_xcd_grid(B, xcd)), dim3(BT), lds, st, idx, T, kk, c.max_ctx, c.slots_per_seq,
                      cache.slot_of, cache.token_of, cache.stamp, step, slot_idx,
                      lists ? ctx->hit_list + lo : nullptr, lists ? ctx->miss_list + lo : nullptr,
@@ -606,8 +608,10 @@ int ess_init_cache_kernels(const ess_config& c, bool* fits) {
   const size_t lds = book_lds_bytes(c.max_ctx, c.max_q_tokens * c.topk);
   *fits = lds + 256 <= 160 * 1024;             // + the kernel's small static arrays
   if (!*fits || lds <= have) return ESS_OK;
-  ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_bookkeeping<true>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-  ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_bookkeeping<false>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_bookkeeping<true, false>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_bookkeeping<false, false>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_bookkeeping<true, true>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_bookkeeping<false, true>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   have = lds;
   return ESS_OK;
 }

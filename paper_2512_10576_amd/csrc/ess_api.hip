@@ -148,7 +148,7 @@ int run_cache_step(ess_ctx* ctx, const ess_cache& cache, const int32_t* idx, int
   // confine: the fetch runs on the XCDs of ESS_FETCH_XCD_MASK and the kernels beside it stay off them, taking their work
   // through counters that this bookkeeping clears (counter 0: the fetch itself)
   int rc = ess_launch_bookkeeping(ctx, cache, idx, B, T, kk, step, slot_idx, miss_count, st, b0, half == 0,
-                                  ess_xcd{nullptr, 0, nullptr, 0}, confine ? ctx->tickets : nullptr, 5 * ESS_TICKET_WORDS);
+                                  ess_xcd{nullptr, 0, nullptr, 0}, confine ? ctx->tickets : nullptr, 5);
   if (rc != ESS_OK) return rc;
   if (!cache.host_pool_dev) return ESS_OK;      // nothing offloaded: no entry can be missing
   if (ctx->cfg.flags & ESS_FLAG_SERIAL) {
@@ -566,7 +566,7 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
       rc = ess_launch_bookkeeping(ctx, ch, used, Bh, T, c.topk, a->step, ctx->slot_idx_ws + bt0 * k,
                                   a->miss_count ? a->miss_count + b0 : nullptr, st, b0, h == 0, xcd_of(4),
                                   (confine2 || (da_swap && confine_da)) ? ctx->tickets + (da_swap ? 0 : 5) * ESS_TICKET_WORDS : nullptr,
-                                  (da_swap ? 8 : 3) * ESS_TICKET_WORDS);
+                                  da_swap ? 8 : 3);
       if (rc != ESS_OK) return rc;
     } else {
       rc = run_cache_step(ctx, ch, used, Bh, T, c.topk, a->step, ctx->slot_idx_ws + bt0 * k,

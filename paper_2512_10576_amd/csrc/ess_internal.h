@@ -13,9 +13,16 @@
 #define ESS_ZERO_ROW_BYTES 2048  // >= the largest row_stride
 #define ESS_TOPK_SHARED_ROWS 128 // rows (b,t) up to which a top-k row is shared by several workgroups
 #define ESS_N_TICKETS 8         // ticket-fed launches of one step
-#define ESS_TICKET_WORDS 16     // counters per such launch: [0] work items handed out, [1] workgroups arrived
-                                // (low half) and of those on XCDs that take work (high half), [2..9] per-XCD
-                                // counters of launches that hand out work XCD by XCD (attention)
+// Counters of one such launch.  They are device-scope atomics from all XCDs, which the memory side executes one
+// after the other per address range, so each counter has 256 bytes to itself: [ESS_TK_WORK] work items handed out,
+// [ESS_TK_ARRIVE] workgroups that arrived on XCDs that take no work, [ESS_TK_CLASS + 64 c] per-XCD counters of
+// launches that hand out work XCD by XCD (attention).  ESS_TICKET_USED counters at a stride of 64 words.
+#define ESS_TICKET_WORDS 1024
+#define ESS_TK_STRIDE 64
+#define ESS_TK_WORK 0
+#define ESS_TK_ARRIVE 64
+#define ESS_TK_CLASS 128
+#define ESS_TICKET_USED 10
 // The first fetch of the split-batch schedule is confined to these XCDs, and the kernels beside it stay
 // off them.  Measured at batch 64, 128K context (step time): one XCD 0.668 ms (the fetch drops to
 // 40 GB/s behind a single XCD's port when the other seven stream from HBM), two 0.614, three 0.605,
@@ -81,7 +88,7 @@ struct ess_ctx {
 // The launch is complete wherever the hardware puts its workgroups: should none of them sit on an XCD
 // that takes work, the last workgroup to arrive does all of it.
 struct ess_xcd {
-  uint32_t* ticket;             // ESS_TICKET_WORDS counters, zero at launch; null: work by workgroup index
+  uint32_t* ticket;             // the launch's counters (ESS_TICKET_WORDS words), zero at launch; null: work by workgroup index
   uint32_t avoid;               // bit i: XCD i takes no work
   uint32_t* host_need;          // host memory, may be null: the launcher leaves the number of work items here
   int grid_override;            // > 0: launch exactly this many workgroups (test hook)
@@ -97,17 +104,14 @@ struct ess_ticket_check {
 #ifdef __HIPCC__
 __device__ __forceinline__ int ess_xcc_id() { return __builtin_amdgcn_s_getreg(20 | (3 << 11)) & 15; }   // hwreg XCC_ID, bits 3:0
 // Does this workgroup of a ticket-fed launch take work?  Same answer in all threads; `slot` is a __shared__ int.
-// `on`: this workgroup sits on an XCD that takes work.  Every workgroup counts itself in; one that sits elsewhere
-// leaves, unless it is the last of the whole launch to arrive and none before it took work.
+// `on`: this workgroup sits on an XCD that takes work.  One that does not counts itself in and leaves -- unless it
+// finds that every workgroup of the launch has done the same (it is the last, and none sits where work is
+// taken): then it does the work.  Workgroups that take work touch no counter here.
 __device__ __forceinline__ bool ess_ticket_join(uint32_t* ticket, bool on, int* slot) {
-  if (on) {
-    if (threadIdx.x == 0) atomicAdd(ticket + 1, 0x10001u);
-    return true;
-  }
+  if (on) return true;
   if (threadIdx.x == 0) {
-    const uint32_t a = atomicAdd(ticket + 1, 1u);
-    const uint32_t nwg = gridDim.x * gridDim.y * gridDim.z;
-    *slot = ((a & 0xffffu) + 1u == nwg && (a >> 16) == 0u) ? 1 : 0;
+    const uint32_t a = atomicAdd(ticket + ESS_TK_ARRIVE, 1u);
+    *slot = (a + 1u == gridDim.x * gridDim.y * gridDim.z) ? 1 : 0;
   }
   __syncthreads();
   const int r = __builtin_amdgcn_readfirstlane(*slot);
@@ -117,26 +121,28 @@ __device__ __forceinline__ bool ess_ticket_join(uint32_t* ticket, bool on, int* 
 __device__ __forceinline__ bool ess_ticket_join(const ess_xcd& x, int* slot) {
   return ess_ticket_join(x.ticket, !((x.avoid >> ess_xcc_id()) & 1u), slot);
 }
-// Thread 0 asks for the next work item of counter `c`; the value is needed only at ess_ticket_publish, so a
-// request made before an item is worked on costs no waiting.
-__device__ __forceinline__ uint32_t ess_ticket_request(uint32_t* c) { return threadIdx.x == 0 ? atomicAdd(c, 1u) : 0u; }
-// Hand thread 0's ticket to the whole workgroup (also a barrier between two work items): the item, or -1 past the end.
-__device__ __forceinline__ int ess_ticket_publish(uint32_t mine, int items, int* slot) {
+// Thread 0 draws the next work item of counter `c` and hands it to the whole workgroup (also a barrier between two
+// work items): the item, or -1 past the end.  The ticket is asked for when it is needed, not ahead of time: memory
+// operations of a wave complete in order, so a ticket requested before an item's first loads makes those loads
+// wait for the atomic's round trip through the memory side (measured: 8 % on the index-score kernel).
+__device__ __forceinline__ int ess_ticket_take(uint32_t* c, int items, int* slot) {
   __syncthreads();
-  if (threadIdx.x == 0) *slot = mine < (uint32_t)items ? (int)mine : -1;
+  if (threadIdx.x == 0) {
+    const uint32_t mine = atomicAdd(c, 1u);
+    *slot = mine < (uint32_t)items ? (int)mine : -1;
+  }
   __syncthreads();
   return __builtin_amdgcn_readfirstlane(*slot);      // the same in every lane: let the compiler keep it in a scalar register
 }
-// ESS_WORK_LOOP(xcd, static_item, items, slot, item) { body } runs the body for the one work item of this
-// workgroup's index (no ticket), or for every item this workgroup draws (ticket-fed).
-#define ESS_WORK_LOOP(xcd, static_item, items, slot, item)                                                   \
-  const bool ess_dyn_ = (xcd).ticket != nullptr;                                                             \
-  if (ess_dyn_ && !ess_ticket_join((xcd), (slot))) return;                                                   \
-  uint32_t ess_tk_ = ess_dyn_ ? ess_ticket_request((xcd).ticket) : 0u;                                       \
+// ESS_WORK_LOOP(DYN, xcd, static_item, items, slot, item) { body } runs the body for the one work item of this
+// workgroup's index (DYN false: a compile-time constant, the loop folds away and the kernel is straight-line code),
+// or for every item this workgroup draws (DYN true: ticket-fed launch).  Kernels are compiled in both forms: in
+// the looping form the compiler keeps more in registers across items, which the plain launches should not pay for.
+#define ESS_WORK_LOOP(DYN, xcd, static_item, items, slot, item)                                              \
+  if ((DYN) && !ess_ticket_join((xcd), (slot))) return;                                                      \
   for (int ess_round_ = 0, item = 0;                                                                         \
-       ess_dyn_ ? ((item = ess_ticket_publish(ess_tk_, (items), (slot))) >= 0 &&                             \
-                   ((ess_tk_ = ess_ticket_request((xcd).ticket)), true))                                     \
-                : (ess_round_ == 0 && (item = (static_item)) < (items));                                     \
+       (DYN) ? ((item = ess_ticket_take((xcd).ticket + ESS_TK_WORK, (items), (slot))) >= 0)                  \
+             : (ess_round_ == 0 && (item = (static_item)) < (items));                                        \
        ++ess_round_)
 #endif
 // Workgroups to launch for a ticket-fed kernel: enough to put `per_cu` of them on every CU of the XCDs that

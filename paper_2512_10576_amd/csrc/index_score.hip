@@ -58,7 +58,7 @@ __device__ __forceinline__ void load_row_share(const uint8_t* row, int g, long (
 // row s % 64 of page block_table[b, s / 64] and its score is multiplied by its scale (positive, so the
 // scale commutes with the ReLU and the head sum: one multiplication of the exact sum).  A wave's batch
 // of 64 tokens is exactly one page.
-template <int HB, int DI, int T, bool PAGED>
+template <int HB, int DI, int T, bool PAGED, bool DYN>
 __global__ __launch_bounds__(kWaves * 64, T == 2 ? 2 : 1) void k_index_score(const uint8_t* __restrict__ q,
                                                               const float* __restrict__ w,
                                                               const uint8_t* __restrict__ key,
@@ -70,40 +70,42 @@ __global__ __launch_bounds__(kWaves * 64, T == 2 ? 2 : 1) void k_index_score(con
   constexpr int KS = DI / 32;
   constexpr size_t kPageBytes = (size_t)kBatchTokens * (DI + 4);
   __shared__ int s_item;
-  const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
-  const int g = lane >> 4;
-  const int n = lane & 15;
-  // stationary operands: q as the A matrix (row = head), w per accumulator row; reloaded when the sequence changes
-  long qa[T][HB][KS];
-  float wr[T][HB][4];
-  int q_of = -1;
   // work item = (chunk, sequence): by workgroup index, or drawn from the launch's counter off the XCDs to be avoided
-  ESS_WORK_LOOP(xcd, blockIdx.y * nx + blockIdx.x, nx * nb_seq, &s_item, item) {
+  ESS_WORK_LOOP(DYN, xcd, blockIdx.y * nx + blockIdx.x, nx * nb_seq, &s_item, item) {
   const int b = item / nx;
   const int len = min(ctx_len[b], Lmax);
   const int blk_base = (item % nx) * chunk_tokens;
   if (blk_base >= len) continue;
   const int blk_end = min(blk_base + chunk_tokens, len);
 
-  if (b != q_of) {
-    q_of = b;
+  // the thread index passes through an empty asm statement so that what is derived from it is computed per work
+  // item instead of being carried in registers across the loop
+  int tidx = threadIdx.x;
+  if constexpr (DYN) asm volatile("" : "+v"(tidx));
+  const int lane = tidx & 63;
+  const int wave = tidx >> 6;
+  const int g = lane >> 4;
+  const int n = lane & 15;
+
+  // stationary operands of the item: q as the A matrix (row = head), w per accumulator row (8 KiB per sequence
+  // and token, read from the L2 by every workgroup that works on the sequence)
+  long qa[T][HB][KS];
+  float wr[T][HB][4];
 #pragma unroll
-    for (int t = 0; t < T; ++t) {
+  for (int t = 0; t < T; ++t) {
 #pragma unroll
-      for (int mb = 0; mb < HB; ++mb) {
-        const int head = mb * 16 + n;
-        if (head < Hi) {
-          load_row_share<DI>(q + ((size_t)(b * Ttot + t0 + t) * Hi + head) * DI, g, qa[t][mb]);
-        } else {
+    for (int mb = 0; mb < HB; ++mb) {
+      const int head = mb * 16 + n;
+      if (head < Hi) {
+        load_row_share<DI>(q + ((size_t)(b * Ttot + t0 + t) * Hi + head) * DI, g, qa[t][mb]);
+      } else {
 #pragma unroll
-          for (int kk = 0; kk < KS; ++kk) qa[t][mb][kk] = 0;
-        }
+        for (int kk = 0; kk < KS; ++kk) qa[t][mb][kk] = 0;
+      }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int hrow = mb * 16 + g * 4 + i;
-          wr[t][mb][i] = hrow < Hi ? w[(size_t)(b * Ttot + t0 + t) * Hi + hrow] : 0.f;
-        }
+      for (int i = 0; i < 4; ++i) {
+        const int hrow = mb * 16 + g * 4 + i;
+        wr[t][mb][i] = hrow < Hi ? w[(size_t)(b * Ttot + t0 + t) * Hi + hrow] : 0.f;
       }
     }
   }
@@ -238,25 +240,31 @@ struct IdxArgs {
   ess_xcd xcd; int nx, nb_seq;              // work distribution; chunks per sequence, sequences
 };
 
-template <int HB, int DI, int T, bool PAGED>
-void launch_k(dim3 grid, hipStream_t st, const IdxArgs& a) {
+template <int HB, int DI, int T, bool PAGED, bool DYN>
+void launch_d(dim3 grid, hipStream_t st, const IdxArgs& a) {
   const dim3 block(kWaves * 64);
-  if (a.xcd.ticket) {
+  if constexpr (DYN) {
     // ticket-fed: as many workgroups as the working XCDs hold at once; each draws items until none is left
     static int per_cu = 0;
     if (per_cu == 0) {
       int n = 0;
-      if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_index_score<HB, DI, T, PAGED>, kWaves * 64, 0) != hipSuccess || n < 1) n = 1;
+      if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_index_score<HB, DI, T, PAGED, true>, kWaves * 64, 0) != hipSuccess || n < 1) n = 1;
       per_cu = n;
     }
     grid = dim3(ess_xcd_grid(a.nx * a.nb_seq, a.xcd, per_cu));
   }
   if (a.ev_start || a.ev_stop)      // timed launch: the events take the kernel's own start and end
-    hipExtLaunchKernelGGL((k_index_score<HB, DI, T, PAGED>), grid, block, 0, st, a.ev_start, a.ev_stop, 0, a.q, a.w, a.key,
+    hipExtLaunchKernelGGL((k_index_score<HB, DI, T, PAGED, DYN>), grid, block, 0, st, a.ev_start, a.ev_stop, 0, a.q, a.w, a.key,
                           a.ctx_len, a.score, a.Lmax, a.Hi, a.chunk, a.block_table, a.n_pages, a.Ttot, a.t0, a.xcd, a.nx, a.nb_seq);
   else
-    hipLaunchKernelGGL((k_index_score<HB, DI, T, PAGED>), grid, block, 0, st, a.q, a.w, a.key, a.ctx_len, a.score, a.Lmax,
+    hipLaunchKernelGGL((k_index_score<HB, DI, T, PAGED, DYN>), grid, block, 0, st, a.q, a.w, a.key, a.ctx_len, a.score, a.Lmax,
                        a.Hi, a.chunk, a.block_table, a.n_pages, a.Ttot, a.t0, a.xcd, a.nx, a.nb_seq);
+}
+
+template <int HB, int DI, int T, bool PAGED>
+void launch_k(dim3 grid, hipStream_t st, const IdxArgs& a) {
+  if (a.xcd.ticket) launch_d<HB, DI, T, PAGED, true>(grid, st, a);
+  else launch_d<HB, DI, T, PAGED, false>(grid, st, a);
 }
 
 template <int HB, int DI, int T>

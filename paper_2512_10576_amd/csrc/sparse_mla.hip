@@ -194,7 +194,7 @@ __device__ __forceinline__ float group_sum(float x) {
   return __uint_as_float(b.x) + __uint_as_float(b.y);
 }
 
-template <int FMT>
+template <int FMT, bool DYN>
 __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
     const uint16_t* __restrict__ q, const uint8_t* __restrict__ pool, const int32_t* __restrict__ list,
     const int32_t* __restrict__ n_list, int T, int H, int kk, int S, int row_stride, float scale_log2e, int split0,
@@ -212,7 +212,7 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
   // group; a workgroup whose class has run out goes on with the next class, so any one workgroup could finish
   // the whole launch.
   const int n_pairs = nsplit * n_bt, n_items = n_pairs * n_hg;
-  const bool dyn = xcd.ticket != nullptr;
+  constexpr bool dyn = DYN;
   int cls = 0, nw = 1, tried = 1;
   if (dyn) {
     if (!ess_ticket_join(xcd, &s_item)) return;
@@ -221,25 +221,25 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
     nw = max(__popc(work), 1);
     cls = ((work >> x) & 1u) ? __popc(work & ((1u << x) - 1u)) : 0;
   }
-  uint32_t tk = dyn ? ess_ticket_request(xcd.ticket + 2 + cls) : 0u;
   for (int round = 0;; ++round) {
   int split, bt, hg;
   if (dyn) {
     int item;
     for (;;) {
-      uint32_t mine = 0xffffffffu;
+      // ticket v of class cls stands for pair (v / n_hg) * nw + cls, head group v % n_hg
+      __syncthreads();
       if (threadIdx.x == 0) {
+        const uint32_t tk = atomicAdd(xcd.ticket + ESS_TK_CLASS + ESS_TK_STRIDE * cls, 1u);
         const uint32_t pair = (tk / (uint32_t)n_hg) * (uint32_t)nw + (uint32_t)cls;
-        if (pair < (uint32_t)n_pairs) mine = pair * (uint32_t)n_hg + tk % (uint32_t)n_hg;
+        s_item = pair < (uint32_t)n_pairs ? (int)(pair * (uint32_t)n_hg + tk % (uint32_t)n_hg) : -1;
       }
-      item = ess_ticket_publish(mine, n_items, &s_item);
+      __syncthreads();
+      item = __builtin_amdgcn_readfirstlane(s_item);
       if (item >= 0 || tried == nw) break;
       ++tried;
       cls = cls + 1 == nw ? 0 : cls + 1;
-      tk = ess_ticket_request(xcd.ticket + 2 + cls);
     }
     if (item < 0) break;
-    tk = ess_ticket_request(xcd.ticket + 2 + cls);      // the next item: the answer is needed only after this one
     hg = item % n_hg;
     split = (item / n_hg) % nsplit;
     bt = item / (n_hg * nsplit);
@@ -251,7 +251,7 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
   // the thread index passes through an empty asm statement so that what is derived from it (lane constants, LDS
   // offsets) is computed per work item, where it is needed, instead of being kept in registers across the loop
   int tid = threadIdx.x;
-  asm volatile("" : "+v"(tid));
+  if constexpr (DYN) asm volatile("" : "+v"(tid));
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 4, n16 = lane & 15;
@@ -529,8 +529,8 @@ __global__ __launch_bounds__(256) void k_attn_merge(const _Float16* __restrict__
     bool short_of = false;
 #pragma unroll
     for (int i = 0; i < ESS_N_TICKETS; ++i) {
-      uint32_t handed = chk.tickets[i * ESS_TICKET_WORDS];               // the launch's counter, or its per-XCD counters
-      for (int c = 2; c < 10; ++c) handed += chk.tickets[i * ESS_TICKET_WORDS + c];
+      uint32_t handed = chk.tickets[i * ESS_TICKET_WORDS + ESS_TK_WORK];   // the launch's counter, or its per-XCD counters
+      for (int c = 0; c < 8; ++c) handed += chk.tickets[i * ESS_TICKET_WORDS + ESS_TK_CLASS + ESS_TK_STRIDE * c];
       short_of |= chk.need[i] != 0 && handed < chk.need[i];
     }
     if (short_of) *chk.flag = 1;
@@ -588,9 +588,13 @@ int ess_attn_min_splits(const ess_config& c) {
 
 // At context creation (on the context's device): the partial-attention kernels use more dynamic LDS than the default limit.
 int ess_init_attn_kernels() {
-  ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_partial_tr<ESS_FMT_BF16>),
+  ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_partial_tr<ESS_FMT_BF16, false>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, tr_lds_bytes(ESS_FMT_BF16)));
-  ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_partial_tr<ESS_FMT_FP8>),
+  ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_partial_tr<ESS_FMT_BF16, true>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, tr_lds_bytes(ESS_FMT_BF16)));
+  ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_partial_tr<ESS_FMT_FP8, false>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, tr_lds_bytes(ESS_FMT_FP8)));
+  ESS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_partial_tr<ESS_FMT_FP8, true>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, tr_lds_bytes(ESS_FMT_FP8)));
   return ESS_OK;
 }
@@ -607,15 +611,16 @@ int ess_launch_attn_partial(ess_ctx* ctx, const void* q, const uint8_t* slot_poo
   // partial results of sequence b0 onward
   _Float16* op = reinterpret_cast<_Float16*>(ctx->o_part) + (size_t)b0 * T * ESS_MAX_SPLITS * c.attn_heads * ESS_LATENT_DIM;
   float* lp = ctx->lse_part + (size_t)b0 * T * ESS_MAX_SPLITS * c.attn_heads;
+#define ESS_ATTN_LAUNCH(FMT, DYN)                                                                                      \
+  hipLaunchKernelGGL((k_attn_partial_tr<FMT, DYN>), grid, dim3(NTH), tr_lds_bytes(FMT), st, qq, slot_pool, list, n_list, T, \
+                     c.attn_heads, c.topk, c.slots_per_seq, c.row_stride, sc, split0, nsplit, op, lp, ctx->zero_row, xcd,  \
+                     B * T, n_hg)
   if (c.latent_fmt == ESS_FMT_BF16) {
-    constexpr int lds = tr_lds_bytes(ESS_FMT_BF16);
-    hipLaunchKernelGGL(k_attn_partial_tr<ESS_FMT_BF16>, grid, dim3(NTH), lds, st, qq, slot_pool, list, n_list, T,
-                       c.attn_heads, c.topk, c.slots_per_seq, c.row_stride, sc, split0, nsplit, op, lp, ctx->zero_row, xcd, B * T, n_hg);
+    if (xcd.ticket) ESS_ATTN_LAUNCH(ESS_FMT_BF16, true); else ESS_ATTN_LAUNCH(ESS_FMT_BF16, false);
   } else {
-    constexpr int lds = tr_lds_bytes(ESS_FMT_FP8);
-    hipLaunchKernelGGL(k_attn_partial_tr<ESS_FMT_FP8>, grid, dim3(NTH), lds, st, qq, slot_pool, list, n_list, T,
-                       c.attn_heads, c.topk, c.slots_per_seq, c.row_stride, sc, split0, nsplit, op, lp, ctx->zero_row, xcd, B * T, n_hg);
+    if (xcd.ticket) ESS_ATTN_LAUNCH(ESS_FMT_FP8, true); else ESS_ATTN_LAUNCH(ESS_FMT_FP8, false);
   }
+#undef ESS_ATTN_LAUNCH
   ESS_HIP(hipGetLastError());
   return ESS_OK;
 }

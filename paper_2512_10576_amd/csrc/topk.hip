@@ -491,7 +491,7 @@ __device__ __forceinline__ void topk_item(TopkShared& sm, int item, int parts, c
   }
 }
 
-template <int MODE>
+template <int MODE, bool DYN>
 __global__ __launch_bounds__(NT) void k_topk(const float* __restrict__ score, const int32_t* __restrict__ ctx_len,
                                              int T, int Lmax, int k, int IB, int32_t* __restrict__ idx_out,
                                              unsigned long long* __restrict__ g_cand, uint32_t* __restrict__ g_cnt,
@@ -500,40 +500,54 @@ __global__ __launch_bounds__(NT) void k_topk(const float* __restrict__ score, co
   __shared__ int s_item;
   const int parts = MODE == 1 ? parts_arg : 1;
   // work item = (part, row): by workgroup index, or drawn from the launch's counter off the XCDs to be avoided
-  ESS_WORK_LOOP(xcd, MODE == 1 ? blockIdx.y * parts + blockIdx.x : blockIdx.x, rows * parts, &s_item, item) {
+  ESS_WORK_LOOP(DYN, xcd, MODE == 1 ? blockIdx.y * parts + blockIdx.x : blockIdx.x, rows * parts, &s_item, item) {
     topk_item<MODE>(sm, item, parts, score, ctx_len, T, Lmax, k, IB, idx_out, g_cand, g_cnt);
   }
 }
 
 }  // namespace
 
-int ess_launch_topk(ess_ctx* ctx, const float* score, const int32_t* ctx_len, int B, int T, int32_t* idx,
-                    hipStream_t st, ess_xcd xcd) {
-  const ess_config& c = ctx->cfg;
+namespace {
+// Launches of one top-k call.  cand / cnt: candidate lists [ESS_TOPK_SHARED_ROWS][CAND_CAP] and their counters
+// (zero at launch, zero again afterwards), only used when rows are shared by several workgroups.
+int launch_topk(int max_ctx, int k, const float* score, const int32_t* ctx_len, int B, int T, int32_t* idx,
+                unsigned long long* cand, uint32_t* cnt, hipStream_t st, ess_xcd xcd) {
   int IB = 1;
-  while ((1 << IB) < c.max_ctx) ++IB;
+  while ((1 << IB) < max_ctx) ++IB;
   // small batches of long rows: the candidate pass goes to a kernel of its own that puts several
   // workgroups on every row (as many as fill the chip, at most 8)
   const int rows = B * T;
   int parts = 1;
-  if (c.max_ctx >= 4 * FAST_MIN_VIS && rows <= ESS_TOPK_SHARED_ROWS) {
+  if (max_ctx >= 4 * FAST_MIN_VIS && rows <= ESS_TOPK_SHARED_ROWS) {
     parts = 256 / rows;
     if (parts > 8) parts = 8;
   }
   const ess_xcd x0 = xcd, x1 = ess_xcd{xcd.ticket ? xcd.ticket + ESS_TICKET_WORDS : nullptr, xcd.avoid,
                                        xcd.host_need ? xcd.host_need + 1 : nullptr, xcd.grid_override};
+  const bool dyn = xcd.ticket != nullptr;
+#define ESS_TOPK_LAUNCH(MODE, grid, x, np)                                                                           \
+  do {                                                                                                               \
+    if (dyn) hipLaunchKernelGGL((k_topk<MODE, true>), grid, dim3(NT), 0, st, score, ctx_len, T, max_ctx, k, IB, idx, \
+                                cand, cnt, x, rows, np);                                                             \
+    else hipLaunchKernelGGL((k_topk<MODE, false>), grid, dim3(NT), 0, st, score, ctx_len, T, max_ctx, k, IB, idx,    \
+                            cand, cnt, x, rows, np);                                                                 \
+  } while (0)
   if (parts > 1) {
-    const dim3 g1 = xcd.ticket ? dim3(ess_xcd_grid(parts * rows, x0)) : dim3(parts, rows);
-    hipLaunchKernelGGL(k_topk<1>, g1, dim3(NT), 0, st, score, ctx_len, T, c.max_ctx, c.topk, IB, idx,
-                       ctx->topk_cand, ctx->topk_cnt, x0, rows, parts);
-    hipLaunchKernelGGL(k_topk<2>, dim3(ess_xcd_grid(rows, x1)), dim3(NT), 0, st, score, ctx_len, T, c.max_ctx, c.topk, IB, idx,
-                       ctx->topk_cand, ctx->topk_cnt, x1, rows, 1);
+    const dim3 g1 = dyn ? dim3(ess_xcd_grid(parts * rows, x0)) : dim3(parts, rows);
+    ESS_TOPK_LAUNCH(1, g1, x0, parts);
+    ESS_TOPK_LAUNCH(2, dim3(ess_xcd_grid(rows, x1)), x1, 1);
   } else {
-    hipLaunchKernelGGL(k_topk<0>, dim3(ess_xcd_grid(rows, x1)), dim3(NT), 0, st, score, ctx_len, T, c.max_ctx, c.topk, IB, idx,
-                       ctx->topk_cand, ctx->topk_cnt, x1, rows, 1);
+    ESS_TOPK_LAUNCH(0, dim3(ess_xcd_grid(rows, x1)), x1, 1);
   }
+#undef ESS_TOPK_LAUNCH
   ESS_HIP(hipGetLastError());
   return ESS_OK;
+}
+}  // namespace
+
+int ess_launch_topk(ess_ctx* ctx, const float* score, const int32_t* ctx_len, int B, int T, int32_t* idx,
+                    hipStream_t st, ess_xcd xcd) {
+  return launch_topk(ctx->cfg.max_ctx, ctx->cfg.topk, score, ctx_len, B, T, idx, ctx->topk_cand, ctx->topk_cnt, st, xcd);
 }
 
 size_t ess_topk_cand_bytes() { return (size_t)ESS_TOPK_SHARED_ROWS * CAND_CAP * sizeof(unsigned long long); }
