@@ -172,6 +172,18 @@ int ess_index_score_paged(ess_ctx* ctx, const uint8_t* q_idx_fp8, const float* w
 int ess_topk(ess_ctx* ctx, const float* score, const int32_t* ctx_len, int32_t B, int32_t T,
              int32_t* idx, void* stream);
 
+/* ess_topk for callers that cannot allocate device memory and therefore cannot create a context: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same result as ess_topk for
+ * score [B,T,max_ctx] and k (idx [B,T,k]).  The call allocates nothing: its scratch memory (candidate
+ * lists of rows that several workgroups share, and their counters) is an array inside the library's
+ * image, 8 MiB + 512 bytes, which every GPU the library runs on holds until the process ends.  Limits:
+ * B*T <= ESS_TOPK_STATIC_MAX_ROWS, T <= 4, max_ctx <= 524288, k <= 4096; beyond them ESS_ERR_CAPACITY.
+ * All calls on one GPU share that array: calls that overlap in time on one GPU (different streams or
+ * threads) race; serialise them. */
+#define ESS_TOPK_STATIC_MAX_ROWS 128
+int ess_topk_static(const float* score, const int32_t* ctx_len, int32_t B, int32_t T, int32_t max_ctx, int32_t k,
+                    int32_t* idx, void* stream);
+
 /* Stages 3 + 5, Sparse Memory Pool look-up, LRU update and miss fetch
  * (Sec. 3.1, 3.2).  Per sequence: R = distinct valid entries of idx[b]; resident
  * ones are hits (stamp := step); the others, in ascending position, take the

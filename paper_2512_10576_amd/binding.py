@@ -76,6 +76,7 @@ def load() -> C.CDLL:
         "ess_cache_admit": [vp, C.POINTER(EssCache), vp, i32, i32, u32, vp],
         "ess_index_score": [vp, vp, vp, vp, vp, i32, i32, vp, vp],
         "ess_topk": [vp, vp, vp, i32, i32, vp, vp],
+        "ess_topk_static": [vp, vp, i32, i32, i32, i32, vp, vp],
         "ess_gather_latent": [vp, C.POINTER(EssCache), vp, vp, i32, i32, u32, vp, vp, vp, vp],
         "ess_sparse_mla_decode": [vp, vp, vp, vp, i32, i32, vp, vp, vp],
         "ess_decode_step": [vp, C.POINTER(EssCache), C.POINTER(EssStepArgs), vp],
@@ -156,6 +157,13 @@ def calib_memcpy_rows(dst, host_pool, host_rows, row_bytes, row_stride):
     _check(load().ess_calib_memcpy_rows(_ptr(dst, torch.uint8), C.c_void_p(host_pool.data_ptr()),
                                         C.c_void_p(host_rows.data_ptr()), host_rows.numel(), row_bytes, row_stride,
                                         _stream()))
+
+
+def topk_static(score, ctx_len, idx):
+    """ess_topk without a context and without any allocation: score [B,T,max_ctx], idx [B,T,k]"""
+    B, T, L = score.shape
+    _check(load().ess_topk_static(_ptr(score, torch.float32), _ptr(ctx_len, torch.int32), B, T, L, idx.shape[2],
+                                  _ptr(idx, torch.int32), _stream()))
 
 
 class Cache:

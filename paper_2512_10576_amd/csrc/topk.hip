@@ -24,6 +24,7 @@
 // Row passes keep four 16-byte loads per thread in flight; a workgroup that
 // issued one load per thread and round would crawl at memory latency.
 #include "ess_internal.h"
+#include <mutex>
 
 namespace {
 
@@ -551,3 +552,53 @@ int ess_launch_topk(ess_ctx* ctx, const float* score, const int32_t* ctx_len, in
 }
 
 size_t ess_topk_cand_bytes() { return (size_t)ESS_TOPK_SHARED_ROWS * CAND_CAP * sizeof(unsigned long long); }
+
+// ---------------------------------------------------------------------------------------------
+// ess_topk_static: the top-k for callers that cannot allocate.  Its scratch memory -- the candidate lists of rows
+// shared by several workgroups, and their counters -- is this array, part of the library's image on every
+// GPU it is loaded on (8 MiB + 512 bytes).  In host code the array's name is not a device address: the address
+// on the current device is asked for once per device and kept.
+namespace {
+constexpr size_t kStaticCand = (size_t)ESS_TOPK_SHARED_ROWS * CAND_CAP;          // candidate keys
+constexpr size_t kStaticWords = kStaticCand + ESS_TOPK_SHARED_ROWS / 2;          // + the rows' counters (uint32 each)
+constexpr int kMaxDevices = 64;
+static_assert(ESS_TOPK_STATIC_MAX_ROWS == ESS_TOPK_SHARED_ROWS, "the static scratch holds one candidate list per shared row");
+}  // namespace
+static __device__ __align__(256) unsigned long long ess_topk_scratch[kStaticWords];
+namespace {
+unsigned long long* g_static_ptr[kMaxDevices];                                   // per device: address of its copy of the array
+std::mutex g_static_mu;
+}  // namespace
+
+extern "C" int ess_topk_static(const float* score, const int32_t* ctx_len, int32_t B, int32_t T, int32_t max_ctx,
+                               int32_t k, int32_t* idx, void* stream) {
+  if (!score || !ctx_len || !idx) return ess_fail(ESS_ERR_INVALID_ARG, "NULL argument");
+  if (B < 1 || T < 1 || T > 4) return ess_fail(ESS_ERR_INVALID_ARG, "B %d, T %d (T: 1 to 4)", B, T);
+  if ((long)B * T > ESS_TOPK_STATIC_MAX_ROWS)
+    return ess_fail(ESS_ERR_CAPACITY, "ess_topk_static: B*T = %ld rows exceed the %d its static scratch memory holds",
+                    (long)B * T, ESS_TOPK_STATIC_MAX_ROWS);
+  if (max_ctx < 1 || max_ctx > ESS_MAX_CTX)
+    return ess_fail(ESS_ERR_CAPACITY, "ess_topk_static: max_ctx %d outside [1, %d]", max_ctx, ESS_MAX_CTX);
+  if (k < 1 || k > ESS_MAX_TOPK) return ess_fail(ESS_ERR_CAPACITY, "ess_topk_static: k %d outside [1, %d]", k, ESS_MAX_TOPK);
+  int dev = 0;
+  ESS_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return ess_fail(ESS_ERR_UNSUPPORTED, "ess_topk_static: device %d", dev);
+  unsigned long long* base;
+  {
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    if (!g_static_ptr[dev]) {                 // first call on this device: where does its copy of the array live?
+      void* p = nullptr;
+      ESS_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(ess_topk_scratch)));
+      if (!p) return ess_fail(ESS_ERR_HIP, "ess_topk_static: the scratch array has no address on device %d", dev);
+      g_static_ptr[dev] = static_cast<unsigned long long*>(p);
+    }
+    base = g_static_ptr[dev];
+  }
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  uint32_t* cnt = reinterpret_cast<uint32_t*>(base + kStaticCand);
+  // the array keeps what the last call left: the counters must start at zero (a fill kernel, not a memset node,
+  // so that the call may be captured in a graph)
+  int rc = ess_launch_fill_u32(cnt, ESS_TOPK_SHARED_ROWS, 0u, st);
+  if (rc != ESS_OK) return rc;
+  return launch_topk(max_ctx, k, score, ctx_len, B, T, idx, base, cnt, st, ess_xcd{nullptr, 0, nullptr, 0});
+}
