@@ -5,12 +5,17 @@ One "step" = one layer-step: index score -> top-k -> Sparse Memory Pool
 look-up / LRU update -> miss fetch from pinned host memory -> sparse MLA decode
 (Attn0 / Attn1 / merge), for the whole batch of one layer, through
 `ess_decode_step`.  Inputs are synthetic (seeded), resident in HBM / pinned
-host memory before the timed region starts.
+host memory before the timed region starts; the slot pool is brought to its
+steady state by admitting the 32 access-trace sets that precede the decode
+steps (LRU-Warmup, Sec. 3.2), whatever --warmup is.
 
 Prints ONE JSON line (see the keys below).  `roofline` is for the dominant
 kernel, the index-score key stream; its duration is measured with HIP events
 recorded by the library on the launch stream during the timed steps.
 `cpu_baseline` times the CPU oracle on a bounded sample of the same workload.
+Ratios are formed from one set of steps each: `value`, the roofline and
+`misses_per_step` from the timed steps, the stage table and the host-link
+rate from the stage pass that follows them.
 """
 from __future__ import annotations
 
@@ -45,9 +50,10 @@ WORKLOADS = {
                  desc="B128 ctx131072 T2 (causal offset), fp8 e4m3 Latent-Cache entries (656 B) in pinned host memory, "
                       "10% GPU slots, 70% top-k overlap, 61 layers back to back"),
 }
-# HBM bytes per launch of the index-score kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (see profiles/); None until measured for that workload
-MEASURED_TRAFFIC_BYTES = {"cfg4": 958042 * 1024}   # HBM bytes of the index-score kernel per step, profiles/pmc_traffic_cfg4.md
+# HBM bytes per launch of the index-score kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, keyed by the
+# exact workload and flags they were measured on: (workload, overlap, paged, append) -> (bytes per step, source)
+MEASURED_TRAFFIC = {}
+ADMIT_SETS = 32              # access-trace sets admitted (untimed) before any decode step: LRU-Warmup, Sec. 3.2
 
 
 def build_workload(name, steps_needed, overlap="auto", layers=None, rho=None, ratio=None):
@@ -99,7 +105,7 @@ def build_workload(name, steps_needed, overlap="auto", layers=None, rho=None, ra
     trace = None
     if wl["rho"] is not None:
         tr = synth.TopkTrace(seed, ctx_len, T, k, wl["rho"], device=dev)
-        trace = [tr.next() for _ in range(steps_needed)]
+        trace = [tr.next() for _ in range(steps_needed)]      # set s-1 drives LRU step s (admission or decode step)
     torch.cuda.synchronize()
     return dict(wl=wl, name=name, overlap=overlap, ctx=ctx, cfg=cfg, cache=caches[0], caches=caches, q_idx=q_idx, w=w,
                 key=keys[0], keys=keys, q_attn=q_attn, ctx_len=ctx_len, host_pool=host_pool, trace=trace, S=S,
@@ -136,9 +142,50 @@ def algorithmic_bytes(W, misses_per_step):
     return dict(index_score=a1, topk=a2, attention_rows=a4, fill=fill)
 
 
-def measure(name, steps, warmup, overlap="auto", layers=None, rho=None, ratio=None, append=False, paged=False):
+def warm_slot_pool(W):
+    """LRU-Warmup (Sec. 3.2): the ADMIT_SETS access-trace sets that precede the decode steps are admitted to every
+    layer's slot pool as LRU steps 1..ADMIT_SETS, so that the pool is in its steady state whatever --warmup is.
+    Returns (first decode step number, GB/s of the first admission: every entry a miss, scattered over the pool --
+    the rate the fetch kernel reaches on the host link with nothing beside it)."""
     import torch
-    W = build_workload(name, warmup + 2 * steps, overlap, layers, rho, ratio)
+    if W["trace"] is None:
+        return 1, None
+    ctx, wl = W["ctx"], W["wl"]
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    link = None
+    for li, cache in enumerate(W["caches"]):
+        for s in range(ADMIT_SETS):
+            tok = W["trace"][s].reshape(wl["B"], wl["T"] * wl["k"])
+            if li == 0 and s == 0:
+                torch.cuda.synchronize()
+                e0.record()
+            ctx.cache_admit(cache, tok, s + 1)
+            if li == 0 and s == 0:
+                e1.record()
+                torch.cuda.synchronize()
+                first = ctx.get_stats()["misses"]
+                link = first * W["stride"] / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    torch.cuda.synchronize()
+    return ADMIT_SETS + 1, link
+
+
+def _median(xs):
+    ys = sorted(xs)
+    n = len(ys)
+    return ys[n // 2] if n % 2 else 0.5 * (ys[n // 2 - 1] + ys[n // 2])
+
+
+def measure(name, steps, warmup, overlap="auto", layers=None, rho=None, ratio=None, append=False, paged=False,
+            stage_steps=None, alone=True):
+    """Timed region: `steps` steps after the slot-pool warm-up and `warmup` untimed steps.  Inside it the index-score
+    kernel carries its own start / stop events on at least 16 steps (all of them below 32 steps) and one event per
+    step marks the step boundaries (median / min).  A second, untimed pass over the following `stage_steps` steps
+    records every stage and reads its own miss count, so that each ratio is formed from one set of steps."""
+    import torch
+    if stage_steps is None:
+        stage_steps = max(16, min(steps, 64))
+    n_trace = ADMIT_SETS + warmup + steps + stage_steps
+    W = build_workload(name, n_trace, overlap, layers, rho, ratio)
     if append:
         from paper_2512_10576_amd import synth
         assert W["wl"]["layers"] == 1, "--append: one layer (the layers of a workload share ctx_len)"
@@ -168,73 +215,113 @@ def measure(name, steps, warmup, overlap="auto", layers=None, rho=None, ratio=No
         del scales
     nl = W["wl"]["layers"]
     ctx = W["ctx"]
-    run_steps(W, 1, warmup)
+    first, link_alone = warm_slot_pool(W)
+    run_steps(W, first, warmup)
     torch.cuda.synchronize()
     ctx.reset_stats()
-    # timed region: HIP events around the index-score kernel only, on every 8th layer-step (events cost
-    # about 4 % of a step on this chip when recorded on every step)
-    every = 8 if steps * nl >= 16 else 1
+    # ---- timed region
+    every = max(1, (steps * nl) // 16)
     ctx.profile_enable(steps * nl, stage_mask=0x01, every=every)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    dba_steps = 0
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    run_steps(W, warmup + 1, steps)
+    marks[0].record()
+    for i in range(steps):
+        run_steps(W, first + warmup + i, 1)
+        marks[i + 1].record()
+        dba_steps += 1 if ctx.last_overlap() == 1 else 0
     t_enq = time.perf_counter() - t0                 # host time to enqueue the timed steps (no waiting)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     prof_idx = ctx.profile_read()
     stats = ctx.get_stats()
-    index_ms = sum(p[0] for p in prof_idx) / len(prof_idx)
-    # second pass over the same steps' successors with every stage timed (stage table only; its extra
-    # events cost a few percent, so it is not the timed region)
-    extra = min(steps, max(len(W["trace"]) - warmup - steps, 0)) if W["trace"] is not None else steps
-    if extra > 0:
-        ctx.profile_enable(extra * nl, stage_mask=0x3F)
-        run_steps(W, warmup + steps + 1, extra)
-        torch.cuda.synchronize()
-        prof = ctx.profile_read()
-    else:
-        prof = [[index_ms, 0, 0, 0, 0, 0]]
-    ctx.profile_enable(0)
-    # the index-score kernel by itself on the same inputs (whole batch, nothing running beside it)
-    wl = W["wl"]
-    score = torch.empty((wl["B"], wl["T"], wl["L"]), dtype=torch.float32, device="cuda")
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    n_alone = 16
-    for i in range(3 + n_alone):
-        if i == 3:
-            e0.record()
-        if W.get("paged"):
-            ctx.index_score_paged(W["q_idx"], W["w"], W["key"], W["block_table"], W["ctx_len"], score)
-        else:
-            ctx.index_score(W["q_idx"], W["w"], W["key"], W["ctx_len"], score)
-    e1.record()
+    step_ms = [marks[i].elapsed_time(marks[i + 1]) / nl for i in range(steps)]       # per layer-step
+    index_ms = sum(p[0] for p in prof_idx) / len(prof_idx)        # all index-score launches of a sampled layer-step
+    launches = 1.0 + dba_steps / steps                            # a split-batch step launches the kernel twice
+    misses_timed = stats["misses"] / max(steps * nl, 1)
+    # ---- stage pass (untimed for `value`): every stage recorded, its own miss count
+    ctx.reset_stats()
+    ctx.profile_enable(stage_steps * nl, stage_mask=0x3F)
+    run_steps(W, first + warmup + steps, stage_steps)
     torch.cuda.synchronize()
-    index_alone_ms = e0.elapsed_time(e1) / n_alone
-    del score
+    prof = ctx.profile_read()
+    misses_stage = ctx.get_stats()["misses"] / max(stage_steps * nl, 1)
+    ctx.profile_enable(0)
     stage = [sum(p[i] for p in prof) / len(prof) for i in range(6)]
-    misses_per_step = stats["misses"] / max(steps * nl, 1)     # per layer-step
-    ab = algorithmic_bytes(W, misses_per_step)
+    # ---- the index-score kernel by itself on the same inputs (whole batch, nothing running beside it)
+    wl = W["wl"]
+    index_alone_ms = None
+    if alone:
+        score = torch.empty((wl["B"], wl["T"], wl["L"]), dtype=torch.float32, device="cuda")
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        n_alone = 16
+        for i in range(3 + n_alone):
+            if i == 3:
+                e0.record()
+            if W.get("paged"):
+                ctx.index_score_paged(W["q_idx"], W["w"], W["key"], W["block_table"], W["ctx_len"], score)
+            else:
+                ctx.index_score(W["q_idx"], W["w"], W["key"], W["ctx_len"], score)
+        e1.record()
+        torch.cuda.synchronize()
+        index_alone_ms = e0.elapsed_time(e1) / n_alone
+        del score
+    ab = algorithmic_bytes(W, misses_timed)
+    ab_stage = algorithmic_bytes(W, misses_stage)
     ms_step = dt / (steps * nl) * 1e3                            # per layer-step
-    ms_model_step = dt / steps * 1e3                             # per step (all layers)
     hbm_stream_bytes = ab["index_score"] + ab["topk"] + ab["attention_rows"]
     hbm_stream_ms = stage[0] + stage[1] + stage[3] + stage[4]
     res = dict(
-        layer_steps_per_s=steps * nl / dt, ms_per_step=ms_model_step, ms_per_layer_step=ms_step, layers=nl,
+        layer_steps_per_s=steps * nl / dt, ms_per_step=dt / steps * 1e3, ms_per_layer_step=ms_step, layers=nl,
+        ms_per_layer_step_median=_median(step_ms), ms_per_layer_step_min=min(step_ms),
         stage_ms=dict(index_score=stage[0], topk=stage[1], bookkeeping=stage[2], attn0=stage[3], attn1_merge=stage[4],
                       fetch=stage[5]),
-        index_score_GBs=ab["index_score"] / (index_ms * 1e-3) / 1e9, index_ms_timed=index_ms,
-        index_alone_ms=index_alone_ms, index_alone_GBs=ab["index_score"] / (index_alone_ms * 1e-3) / 1e9,
-        index_launches_per_step=2 if ctx.last_overlap() == 1 else 1,
+        stage_steps=stage_steps, misses_per_step_stage_pass=misses_stage,
+        index_score_GBs=ab["index_score"] / (index_ms * 1e-3) / 1e9, index_ms_timed=index_ms, index_samples=len(prof_idx),
+        index_alone_ms=index_alone_ms,
+        index_alone_GBs=(ab["index_score"] / (index_alone_ms * 1e-3) / 1e9) if index_alone_ms else None,
+        index_launches_per_step=launches,
         hbm_stream_GBs=hbm_stream_bytes / (hbm_stream_ms * 1e-3) / 1e9,
         hbm_stream_frac_of_peak=hbm_stream_bytes / (hbm_stream_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         whole_step_hbm_frac=(hbm_stream_bytes / (ms_step * 1e-3) / 1e9) / HBM_PEAK_GBS,
         host_enqueue_ms_per_layer_step=t_enq / (steps * nl) * 1e3,
-        misses_per_step=misses_per_step, overlap_used=("da", "dba", "serial")[ctx.last_overlap()],
-        host_link_GBs=(ab["fill"] / (stage[5] * 1e-3) / 1e9) if stage[5] > 0 else None,
-        host_link_frac_of_peak=(ab["fill"] / (stage[5] * 1e-3) / 1e9 / HOST_LINK_PEAK_GBS) if stage[5] > 0 else None,
+        misses_per_step=misses_timed, overlap_used=("da", "dba", "serial")[ctx.last_overlap()],
+        # fetch rate: bytes and time of the same (stage-pass) steps
+        host_link_GBs=(ab_stage["fill"] / (stage[5] * 1e-3) / 1e9) if stage[5] > 0 else None,
+        host_link_frac_of_peak=(ab_stage["fill"] / (stage[5] * 1e-3) / 1e9 / HOST_LINK_PEAK_GBS) if stage[5] > 0 else None,
+        host_link_alone_GBs=link_alone,
         algorithmic_bytes=ab,
     )
     return W, res
+
+
+def measured_peaks(W):
+    """What a plain kernel reaches on this GPU, beside the nominal peaks: a pure read stream and a copy (over the
+    workload's index keys, at most 1 GiB)."""
+    import torch
+    from paper_2512_10576_amd import binding as bnd
+    src = W["key"].view(-1)
+    n = min(src.numel(), 1 << 30) // 16 * 16
+    src = src[:n]
+    dst = torch.empty(n, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(bnd.CALIB_READ_WGS, dtype=torch.int32, device="cuda")
+    out = {}
+    for what in ("read", "copy"):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for i in range(2 + 8):
+            if i == 2:
+                e0.record()
+            if what == "read":
+                bnd.calib_read(src, sink)
+            else:
+                bnd.calib_copy(dst, src)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 8
+        out[what] = n * (1 if what == "read" else 2) / (ms * 1e-3) / 1e9
+    del dst
+    return out
 
 
 CPU_BASELINE_STEPS = 4       # about 10-15 s of CPU time for the whole cfg4 batch on 16 cores
@@ -329,7 +416,7 @@ def sweep_ratio(name, steps, warmup):
 
 
 def sweep_granularity():
-    """Host-to-device rate of scattered Latent-Cache entries (paper Sec. 3.2): one memcpy call per entry
+    """Host-to-device rate of scattered Latent-Cache entries (paper Sec. 3.1): one memcpy call per entry
     against the fetch kernel that reads the pinned pool through its device mapping, at both entry sizes."""
     import torch
     from paper_2512_10576_amd import binding as bnd
@@ -414,6 +501,8 @@ def main():
     ap.add_argument("--layers", type=int, default=None, help="layers run back to back per step (default: the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-32k", action="store_true", help="skip the extra 32K-context measurement (cfg2)")
+    ap.add_argument("--no-extra", action="store_true",
+                    help="skip the measurements of the other offloaded configurations (cfg3, cfg5 on 8 layers)")
     ap.add_argument("--cpu-seqs", type=int, default=64, help="sequences of the batch the CPU oracle is timed on")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic) so that rocprofv3 --pmc counters can be scaled")
@@ -454,20 +543,23 @@ def main():
 
     W, res = measure(a.workload, a.steps, a.warmup, a.overlap, a.layers, append=a.append, paged=a.paged)
     ab = res["algorithmic_bytes"]
-    # In the timed region a DBA step launches the kernel twice, once per half of the batch, the second
+    # In the timed region a split-batch (DBA) step launches the kernel twice, once per half of the batch, the second
     # beside the first half's fetch; achieved = bytes of a step / time of its launches, which is also
     # bytes per launch / average launch time.  `alone` is the same kernel on the whole batch with the GPU to itself.
     nlaunch = res["index_launches_per_step"]
+    traffic = MEASURED_TRAFFIC.get((a.workload, a.overlap, a.paged, a.append)) if a.layers is None else None
     roof = dict(bound="hbm", kernel="k_index_score", achieved=res["index_score_GBs"], peak=HBM_PEAK_GBS, unit="GB/s",
                 frac=res["index_score_GBs"] / HBM_PEAK_GBS,
-                traffic=(MEASURED_TRAFFIC_BYTES[a.workload] / nlaunch) if a.workload in MEASURED_TRAFFIC_BYTES else None,
+                traffic=(traffic[0] / nlaunch) if traffic else None, traffic_source=traffic[1] if traffic else None,
                 algorithmic_bytes_per_launch=ab["index_score"] / nlaunch, avg_launch_ms=res["index_ms_timed"] / nlaunch,
-                launches_per_step=nlaunch,
+                launches_per_step=nlaunch, sampled_steps=res["index_samples"],
                 alone=dict(achieved=res["index_alone_GBs"], frac=res["index_alone_GBs"] / HBM_PEAK_GBS,
                            algorithmic_bytes_per_launch=ab["index_score"], avg_launch_ms=res["index_alone_ms"]))
+    peaks = measured_peaks(W)
     out = {
         "metric": "decode-step sparse-attn layer-steps/sec", "value": res["layer_steps_per_s"], "unit": "layer-steps/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": res["ms_per_step"], "ms_per_layer_step": res["ms_per_layer_step"],
+        "ms_per_layer_step_median": res["ms_per_layer_step_median"], "ms_per_layer_step_min": res["ms_per_layer_step_min"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "fp8 indexer / bf16 attention",
         "data": "synthetic",
         "config": {"workload": "%s: %s" % (a.workload, W["wl"]["desc"]), "indexer": "64 heads x 128 fp8 e4m3",
@@ -475,9 +567,16 @@ def main():
                    "overlap": W["overlap"] + (" (ran %s)" % res["overlap_used"] if W["overlap"] == "auto" else ""),
                    "layers_per_step": res["layers"], "q_tokens": W["wl"]["T"],
                    "context": "grows by T per step (ess_append after every step)" if a.append else "fixed",
-                   "indexer_cache": "paged, 64 keys + 64 scales per page" if a.paged else "flat"},
+                   "indexer_cache": "paged, 64 keys + 64 scales per page" if a.paged else "flat",
+                   "slot_pool_warmup": ("%d access-trace sets admitted through ess_cache_admit before the %d warm-up steps"
+                                        % (ADMIT_SETS, a.warmup)) if W["trace"] is not None else "none (resident)"},
         "roofline": roof,
-        "stages": {k: res[k] for k in ("stage_ms", "host_enqueue_ms_per_layer_step", "hbm_stream_GBs", "hbm_stream_frac_of_peak", "whole_step_hbm_frac",
+        "peaks": {"hbm_nominal_GBs": HBM_PEAK_GBS, "hbm_read_measured_GBs": peaks["read"], "hbm_copy_measured_GBs": peaks["copy"],
+                  "host_link_nominal_GBs": HOST_LINK_PEAK_GBS, "host_link_measured_GBs": res["host_link_alone_GBs"],
+                  "note": "measured = a plain read / copy kernel over the index keys, and the first admission (every entry a "
+                          "miss: bookkeeping kernel + fetch kernel, nothing beside them)"},
+        "stages": {k: res[k] for k in ("stage_ms", "stage_steps", "misses_per_step_stage_pass", "host_enqueue_ms_per_layer_step",
+                                       "hbm_stream_GBs", "hbm_stream_frac_of_peak", "whole_step_hbm_frac",
                                        "misses_per_step", "host_link_GBs", "host_link_frac_of_peak")},
         "paper_context": "simulated whole-model gains of the paper: +69.4% at 32K, +123% at 128K (not comparable)",
     }
@@ -486,17 +585,31 @@ def main():
     W["ctx"].close()
     del W
     torch.cuda.empty_cache()
+
+    def leg(name, steps, warmup, **kw):
+        W2, r2 = measure(name, steps, warmup, alone=False, **kw)
+        d = {"workload": "%s: %s" % (name, W2["wl"]["desc"]), "steps": steps, "warmup": warmup, "layers_per_step": r2["layers"],
+             "layer_steps_per_s": r2["layer_steps_per_s"], "ms_per_layer_step": r2["ms_per_layer_step"],
+             "ms_per_layer_step_median": r2["ms_per_layer_step_median"], "ms_per_layer_step_min": r2["ms_per_layer_step_min"],
+             "stage_ms": r2["stage_ms"], "host_enqueue_ms_per_layer_step": r2["host_enqueue_ms_per_layer_step"],
+             "index_score_GBs": r2["index_score_GBs"], "hbm_stream_frac_of_peak": r2["hbm_stream_frac_of_peak"],
+             "misses_per_step": r2["misses_per_step"], "host_link_GBs": r2["host_link_GBs"],
+             "overlap_used": r2["overlap_used"]}
+        W2["ctx"].close()
+        del W2
+        torch.cuda.empty_cache()
+        return d
+
     if not a.no_32k and a.workload != "cfg2":
         # resident workload: nothing to warm in the caches, but a 0.1 ms step needs a few hundred untimed
         # steps before the GPU runs at its steady rate (+2.5 % against 32 of them)
-        warm32 = max(a.warmup, 256)
-        W2, r2 = measure("cfg2", a.steps, warm32)
-        out["ctx32k"] = {"workload": "cfg2: " + W2["wl"]["desc"], "steps": a.steps, "warmup": warm32,
-                         "layer_steps_per_s": r2["layer_steps_per_s"],
-                         "ms_per_step": r2["ms_per_step"], "stage_ms": r2["stage_ms"],
-                         "host_enqueue_ms_per_layer_step": r2["host_enqueue_ms_per_layer_step"],
-                         "index_score_GBs": r2["index_score_GBs"], "hbm_stream_frac_of_peak": r2["hbm_stream_frac_of_peak"]}
-        W2["ctx"].close()
+        out["ctx32k"] = leg("cfg2", a.steps, max(a.warmup, 256))
+    if not a.no_extra and a.workload == "cfg4" and not (a.append or a.paged):
+        # the other named configurations, so that each has a number from this run: 32K context with the
+        # Latent-Cache offloaded, and the multi-token configuration on a reduced number of layers (8 of 61, each
+        # with its own index keys, slot pool and cache state: 16 GiB of keys, far beyond the Infinity Cache)
+        out["ctx32k_offload"] = leg("cfg3", a.steps, a.warmup)
+        out["cfg5_8_layers"] = leg("cfg5", max(2, a.steps // 8), 2, layers=8, stage_steps=2)
     print(json.dumps(out))
 
 

@@ -305,6 +305,11 @@ int ess_profile_select(ess_ctx* ctx, uint32_t stage_mask, int32_t every);
 /* A plain device-to-device copy kernel (reads `bytes`, writes `bytes`; bytes a multiple of 16,
  * pointers 16-byte aligned): known traffic against which hardware counters can be scaled. */
 int ess_calib_copy(void* dst, const void* src, size_t bytes, void* stream);
+/* A plain read kernel (reads `bytes` once, 16-byte loads, four per thread in flight; bytes a multiple of 16, src
+ * 16-byte aligned): the rate a pure read stream reaches on the device, the measured counterpart of the nominal
+ * HBM peak.  sink: ESS_CALIB_READ_WGS uint32 words (device) that receive a checksum, so that the loads are used. */
+#define ESS_CALIB_READ_WGS 4096
+int ess_calib_read(const void* src, size_t bytes, uint32_t* sink, void* stream);
 /* The transfer the paper starts from (Sec. 3.1, the per-block copy that FlashTrans replaces): one
  * hipMemcpyAsync per entry, n entries of row_bytes each, entry i from
  * host_pool + host_rows[i] * row_stride (pinned host memory, HOST pointer) to

@@ -85,6 +85,7 @@ def load() -> C.CDLL:
         "ess_profile_enable": [vp, i32],
         "ess_profile_select": [vp, u32, i32],
         "ess_calib_copy": [vp, vp, C.c_size_t, vp],
+        "ess_calib_read": [vp, C.c_size_t, vp, vp],
         "ess_append": [vp, C.POINTER(EssCache), vp, vp, vp, vp, i32, i32, u32, vp, vp, vp, i32, vp],
         "ess_index_score_paged": [vp, vp, vp, vp, vp, i32, vp, i32, i32, vp, vp],
         "ess_set_overlap_threshold": [vp, i32],
@@ -149,6 +150,15 @@ def workspace_bytes(cfg: EssConfig) -> int:
 def calib_copy(dst, src):
     """plain copy kernel of known traffic (measurement support)"""
     _check(load().ess_calib_copy(_ptr(dst, torch.uint8), _ptr(src, torch.uint8), src.numel(), _stream()))
+
+
+CALIB_READ_WGS = 4096
+
+
+def calib_read(src, sink):
+    """plain read kernel over `src` (uint8, a multiple of 16 bytes); sink: int32 [CALIB_READ_WGS] on the device"""
+    assert sink.numel() >= CALIB_READ_WGS
+    _check(load().ess_calib_read(_ptr(src, torch.uint8), src.numel(), _ptr(sink, torch.int32), _stream()))
 
 
 def calib_memcpy_rows(dst, host_pool, host_rows, row_bytes, row_stride):

@@ -507,6 +507,31 @@ __global__ __launch_bounds__(256) void k_calib_copy(uint4* __restrict__ dst, con
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
 }
 
+// Reads `n` 16-byte pieces and leaves one word per workgroup, so that the loads are not dead.  A workgroup streams
+// one contiguous range (`per_wg` pieces); its four waves interleave 8 KiB pieces, each wave instruction covering
+// 1 KiB, eight of them in flight per wave -- the pattern with which a pure read stream is fastest on this chip.
+__global__ __launch_bounds__(256) void k_calib_read(const uint4* __restrict__ src, size_t n, size_t per_wg,
+                                                    uint32_t* __restrict__ sink) {
+  constexpr int U = 8;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const size_t lo = (size_t)blockIdx.x * per_wg;
+  const size_t hi = lo + per_wg < n ? lo + per_wg : n;
+  uint32_t acc = 0;
+  for (size_t base = lo + (size_t)wave * U * 64; base < hi; base += (size_t)4 * U * 64) {
+    uint4 x[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const size_t i = base + (size_t)u * 64 + lane;
+      x[u] = i < hi ? src[i] : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) acc ^= x[u].x ^ x[u].y ^ x[u].z ^ x[u].w;
+  }
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) acc ^= __shfl_xor(acc, d, 64);
+  if (lane == 0) atomicXor(&sink[blockIdx.x], acc);
+}
+
 __global__ void k_fill_u32(uint32_t* p, int n, uint32_t value) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = value;
@@ -538,6 +563,16 @@ int ess_launch_append(const ess_config& c, const ess_cache& cache, const uint8_t
 int ess_launch_calib_copy(void* dst, const void* src, size_t bytes, hipStream_t st) {
   hipLaunchKernelGGL(k_calib_copy, dim3(8192), dim3(256), 0, st, static_cast<uint4*>(dst), static_cast<const uint4*>(src),
                      bytes / 16);
+  ESS_HIP(hipGetLastError());
+  return ESS_OK;
+}
+
+int ess_launch_calib_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t st) {
+  const size_t n = bytes / 16;
+  size_t per_wg = 16384;                                     // 256 KiB per workgroup, more when that needs too many workgroups
+  while ((n + per_wg - 1) / per_wg > ESS_CALIB_READ_WGS) per_wg *= 2;
+  const unsigned grid = (unsigned)((n + per_wg - 1) / per_wg);
+  hipLaunchKernelGGL(k_calib_read, dim3(grid ? grid : 1), dim3(256), 0, st, static_cast<const uint4*>(src), n, per_wg, sink);
   ESS_HIP(hipGetLastError());
   return ESS_OK;
 }

@@ -715,6 +715,12 @@ int ess_calib_copy(void* dst, const void* src, size_t bytes, void* stream) {
   return ess_launch_calib_copy(dst, src, bytes, static_cast<hipStream_t>(stream));
 }
 
+int ess_calib_read(const void* src, size_t bytes, uint32_t* sink, void* stream) {
+  if (!src || !sink || (bytes & 15) || !aligned16(src))
+    return ess_fail(ESS_ERR_INVALID_ARG, "calib read needs a 16-byte aligned pointer and size, and a sink");
+  return ess_launch_calib_read(src, bytes, sink, static_cast<hipStream_t>(stream));
+}
+
 int ess_append(ess_ctx* ctx, const ess_cache* cache, const uint8_t* new_key_fp8, const uint8_t* new_rows,
                uint8_t* key_fp8, int32_t* ctx_len, int32_t B, int32_t T, uint32_t step, int32_t* placed,
                const float* new_key_scale, const int32_t* block_table, int32_t n_pages, void* stream) {

@@ -181,6 +181,7 @@ int ess_launch_topk(ess_ctx* ctx, const float* score, const int32_t* ctx_len, in
 size_t ess_topk_cand_bytes();
 // fill kernel (used instead of hipMemsetAsync so that callers may capture the stream in a graph)
 int ess_launch_calib_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
+int ess_launch_calib_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t st);
 int ess_launch_append(const ess_config& c, const ess_cache& cache, const uint8_t* new_key, const uint8_t* new_rows,
                       uint8_t* key, int32_t* ctx_len, int B, int T, uint32_t step, int32_t* placed,
                       const float* new_scale, const int32_t* block_table, int n_pages, hipStream_t st);

@@ -280,3 +280,18 @@ def test_calib_memcpy_rows_delivers_host_pool_rows(ess_lib, stride, fmt):
     with pytest.raises(bnd.EssError) as ei:                          # a negative row index is refused before any copy
         bnd.calib_memcpy_rows(dst, hp, torch.tensor([3, -1], dtype=torch.int64), stride, stride)
     assert ei.value.code == bnd.ESS_ERR_INVALID_ARG
+
+
+def test_calib_read_reads_every_byte_once(ess_lib):
+    """The plain read kernel that measures the achievable read rate: its checksum (xor of all 32-bit words, one
+    partial word per workgroup) equals the xor computed on the host, for sizes with ragged ends."""
+    from paper_2512_10576_amd import binding as bnd
+    rng = np.random.default_rng(3)
+    for n_bytes in (16, 4096 + 16, 3 * 262144 + 48, 40 * 1000 * 1000):
+        print("calib_read", n_bytes, flush=True)
+        host = rng.integers(0, 256, n_bytes, dtype=np.uint8)
+        sink = torch.zeros(bnd.CALIB_READ_WGS, dtype=torch.int32, device="cuda")
+        bnd.calib_read(torch.from_numpy(host).cuda(), sink)
+        torch.cuda.synchronize()
+        got = np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32))
+        assert got == np.bitwise_xor.reduce(host.view(np.uint32))
