@@ -23,11 +23,13 @@ FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-I" + os.path.j
 
 # per-source additions: sparse_mla.hip keeps the results of compiler-generated MFMAs in VGPRs, because its
 # kernel holds the output accumulators in AGPRs that it names itself (see the comment there)
-EXTRA_FLAGS = {"sparse_mla.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+EXTRA_FLAGS = {"sparse_mla.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form", "-std=c++20"]}
 
 
 def compile_flags(src: str) -> list:
-    return [*FLAGS, *EXTRA_FLAGS.get(src, [])]
+    extra = EXTRA_FLAGS.get(src, [])
+    base = [f for f in FLAGS if not (f.startswith("-std=") and any(e.startswith("-std=") for e in extra))]
+    return [*base, *extra]
 
 
 def _hipcc() -> str:

@@ -11,10 +11,11 @@
 
 #include "ess_internal.h"
 
-// Workgroups that Attn0 of the whole batch aims at when entries are offloaded: one per CU (with
-// twice as many the schedules with few misses, where Attn0 is most of the attention, lose 4-5 %).
+// Workgroups that Attn0 of the whole batch aims at when entries are offloaded: half a workgroup per CU.  Attn0 runs
+// beside a fetch and has time to spare, while every split adds a partial result (128 KiB per row) that the merge,
+// which runs after the last fetch, has to read: 128 against 256 took 15 % off Attn0 itself and 0.3-0.7 % off the step.
 #ifndef ESS_ATTN0_WGS
-#define ESS_ATTN0_WGS 256
+#define ESS_ATTN0_WGS 128
 #endif
 
 namespace {
@@ -116,7 +117,7 @@ int check_cache(const ess_ctx* ctx, const ess_cache* c) {
 // (the write of its partial result) with another's work (measured: 9 % at batch 128 x 2 tokens)
 int pick_splits(const ess_config& c, int B, int T, int cap, int target_wgs = 256, bool long_lists = true) {
   const int tiles = (c.topk + ESS_ATTN_TILE - 1) / ESS_ATTN_TILE;
-  const int hgroups = (c.attn_heads + 63) / 64;
+  const int hgroups = (c.attn_heads + 127) / 128;      // a workgroup covers 128 heads
   int want = (target_wgs + B * T * hgroups - 1) / (B * T * hgroups);   // one workgroup per CU: fewer partial results to merge
   if (want > tiles) want = tiles;
   if (want > cap) want = cap;
@@ -486,7 +487,7 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     const double fetch_all = (double)B * mean_miss * c.row_stride / link, fetch_half = 0.5 * fetch_all;
     const double idx_half = 0.5 * B * (double)c.max_ctx * (c.idx_dim + 4.0 * T) / 5.3e6;
     // Attn0 on five XCDs (160 CUs, one workgroup each): rounds x (tiles x time per tile + start and end)
-    const int hg = (c.attn_heads + 63) / 64;
+    const int hg = (c.attn_heads + 127) / 128;
     const int ns0e = pick_splits(c, B, T, 16, ESS_ATTN0_WGS);
     const double hits = c.topk - (mean_miss / T < c.topk ? mean_miss / T : c.topk);
     const double tiles_item = (hits / ESS_ATTN_TILE) / ns0e + 1.0;

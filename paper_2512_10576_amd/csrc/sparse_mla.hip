@@ -6,18 +6,13 @@
 // combines the partial results -- the same merge that joins Attn0 (resident
 // entries) and Attn1 (fetched entries) of the DA overlap.
 //
-// Matrix-core mapping (v_mfma_f32_16x16x32_bf16, wave64).  A workgroup is four
-// waves, one per SIMD, each owning 16 heads with the whole 512-wide output row
-// in 128 accumulator registers and its queries stationary (72 VGPRs); 64 heads
-// per workgroup, head groups in grid.z.  The kernel is built for one wave per
-// SIMD and the large register budget that comes with it.  Both products are
-// computed transposed so that nothing is re-laid out between them:
-//   S^T[r,h] = sum_d K[r,d] Q[h,d]      A = entry rows from LDS (row-major), B = Q^T (registers)
-//   O^T[v,h] = sum_r V^T[v,r] P^T[r,h]  A = V^T, read transposed from the same rows, B = P^T (registers)
-// The accumulator of S^T gives lane (g,h) the eight logits of head h for tile rows
-// {4g..4g+3} and {16+4g..16+4g+3}; in exactly that order they are the eight
-// k-values the lane supplies for the B operand of the second product, so P^T
-// never leaves registers.  Softmax state is per lane = per head.
+// Matrix-core mapping (v_mfma_f32_32x32x16_bf16, wave64).  A workgroup is four
+// waves, one per SIMD, each owning 32 heads with the whole 512-wide output row
+// in 256 accumulator registers and its queries stationary (144 VGPRs): 128 heads
+// per workgroup, so the entries of a range are brought from memory once for all
+// heads.  The kernel is built for one wave per SIMD and the register budget that
+// comes with it.  Both products are computed transposed so that nothing is
+// re-laid out between them; see the comment at the kernel.
 #include "ess_internal.h"
 #include <utility>
 #include <hip/hip_bf16.h>
@@ -83,88 +78,108 @@ __device__ __forceinline__ void wait_vmcnt() {     // vmcnt <= N, other counters
 }
 
 // ---------------------------------------------------------------- the partial-attention kernel
-// Four waves x 16 heads, tiles of 32 entries in LDS as bf16 rows: bf16 entries gathered by
-// global_load_lds, quantised entries (512 fp8 + 4 scales + rope) loaded into registers a tile ahead,
-// dequantised and written in the same layout.  What the kernel is
-// built around (a first version that built V^T in LDS, rescaled every tile and left the accumulators
-// to the register allocator spent 1100 instructions per tile and wave, 68 of them MFMAs):
-//  * V^T is never built.  The A operand of O^T += V^T P^T wants, per lane, 8 entries of one value
-//    column; ds_read_b64_tr_b16 delivers exactly that from rows stored entry-major: in each group
-//    of 16 lanes, source lane 4i+j points at 4 consecutive columns (4j..4j+3) of row i and lane n
-//    receives column n of rows 0..3.  Two such reads (rows 4g+i and 16+4g+i) make one A fragment
-//    whose k order is the order in which S^T leaves the first product.
+// Four waves, one per SIMD, 32 heads each: a workgroup covers all (up to 128) heads of one range of the entry
+// list, so an entry is brought from memory once per range.  Tiles of 32 entries sit in LDS as bf16 rows: bf16
+// entries gathered by global_load_lds, quantised entries (512 fp8 + 4 scales + rope) loaded into registers a tile
+// ahead, dequantised and written in the same layout.  Matrix-core mapping (v_mfma_f32_32x32x16_bf16), both
+// products transposed so that nothing is re-laid out between them:
+//   S^T[r,h] = sum_d K[r,d] Q[h,d]      A = entry rows from LDS (lane: row l%32, 8 dims), B = Q^T (registers)
+//   O^T[v,h] = sum_r V^T[v,r] P^T[r,h]  A = V^T, read transposed from the same rows, B = P^T (registers)
+// The accumulator of S^T gives lane (hh = l/32, h = l%32) the sixteen logits of head h for tile rows
+// 8q + 4hh + i (q, i = 0..3), and registers 8s..8s+7 are, in that order, the eight k-values the lane supplies for
+// the B operand of k-step s of the second product: P^T never leaves registers.  Softmax state is per lane = per
+// (head, half); the two halves of a head meet in one v_permlane32_swap.
+// 32 heads per wave halve the LDS bytes per flop against 16 (a K or V^T fragment of 1 KiB feeds twice the
+// multiply-adds).  That is what counts, because the tile loop is bound by the LDS: per tile a SIMD issues 68 MFMAs
+// of 32 cycles (2176 cycles), but the four waves read 278 KiB of fragments, and the LDS delivers them at about
+// 64 bytes per clock for ds_read_b128 and 41 for the transposing reads, CU-wide (phase timers: 2000 cycles for
+// the first product's 144 reads, 3200 for the second product's 256), whatever the prefetch depth and whatever
+// else is interleaved.
+//  * V^T is never built.  ds_read_b64_tr_b16 delivers, in each group of 16 lanes, column n of four consecutive
+//    rows to lane n (source lane 4i+j points at columns 4j..4j+3 of row i); two such reads (rows 16s+4hh+i and
+//    16s+8+4hh+i) make one A fragment whose k order is the order in which S^T leaves the first product.
 //  * Rows have no padding (pitch 1024 bytes); the 16-byte granules of a row are XOR-swizzled with
-//    f(row) = (row&3)<<2 | (row>>2)&3, applied on the way in by letting lane l of the gather fetch
-//    granule l ^ f(row).  The LDS has 64 banks (256 bytes per clock), so a group of 16 lanes is
-//    conflict-free when its 16-byte granules differ mod 16: K fragments (16 rows, one granule each)
-//    because f is a bijection of the row's low four bits, transposing reads (rows 4g..4g+3, 32
-//    bytes each) because f puts the row's low two bits above the granule pair.  (A three-bit f,
-//    enough for 32 banks, made both products 1.7x slower.)
-//  * The running maximum is only moved when a tile exceeds it by more than 2^8 (exponentials stay
-//    below 2^8 relative to the reference, far inside fp32 and bf16 range), so the 128 accumulator
-//    registers are rescaled a few times per split instead of once per tile.
-//  * Four raw buffers: the gathers of three tiles are in flight; those of tile it+3 are issued one at
-//    a time between the MFMAs of tile it, so that a gather instruction that waits for the texture
-//    path does so while the matrix and LDS pipes are busy.
-//  * Cross-lane maxima and sums over the four 16-lane groups use v_permlane32_swap / 16_swap, not LDS.
+//    f(row) = (row&3)<<2 | (row>>2)&3, applied on the way in by letting lane l of the gather fetch granule
+//    l ^ f(row).  The LDS has 64 banks (256 bytes per clock): K fragments (16 rows of one granule per clock) are
+//    conflict-free because f is a bijection of the row's low four bits, transposing reads (4 rows x 64 bytes per
+//    clock) because f puts the row's low two bits above the granule pair.
+//  * The running maximum is only moved when a tile exceeds it by more than 2^8, so the 256 accumulator registers
+//    are rescaled a few times per split instead of once per tile.
+//  * Four raw buffers: the gathers of three tiles are in flight; those of tile it+3 are issued between the MFMAs of
+//    tile it.
 // Masked entries (slot < 0) are gathered from a row of zeros, so that no product meets stale LDS.
 constexpr int TRP = 1024;                        // latent row pitch in LDS
 constexpr int TR_KL_BYTES = TILE * TRP;          // 32768
 constexpr int TR_RAW_BYTES = TR_KL_BYTES + RP_BYTES;
 constexpr int tr_nbuf(int fmt) { return fmt == ESS_FMT_BF16 ? 4 : 2; }
-constexpr int tr_lds_bytes(int fmt) { return tr_nbuf(fmt) * TR_RAW_BYTES + MAX_TPS * TILE * 4; }   // 155648 | 81920
+constexpr int Q_PITCH = ESS_ROW_DIM * 2 + 16;    // 1168: pitch of the query rows while they are staged in LDS
+constexpr int O_PITCH = ESS_LATENT_DIM * 2 + 8;  // 1032: pitch of the fp16 result rows while they are staged in LDS
+constexpr int tr_lds_bytes(int fmt) {            // tile buffers + slot list, and room for the staged queries: 155648 | 149504
+  const int tiles = tr_nbuf(fmt) * TR_RAW_BYTES + MAX_TPS * TILE * 4, stage = 128 * Q_PITCH;
+  return tiles > stage ? tiles : stage;
+}
 constexpr float kLazyMax = 8.0f;
+constexpr int HPW = 32;                          // heads per wave
+constexpr int HPG = 4 * HPW;                     // heads per workgroup
+constexpr int KS16 = ESS_ROW_DIM / 16;           // 36 k-steps of the first product
+constexpr int VB32 = ESS_LATENT_DIM / 32;        // 16 blocks of 32 value columns
 
-// The 128 output accumulators of a wave live in AGPRs a0..a127 under fixed names, outside the
-// compiler's register allocation: every access is an asm statement that names them.  (Left to the
-// allocator they are copied to VGPRs and back once per tile, 256 moves, because the rare rescale
-// multiplies them with vector ALU instructions.)  The statements clobber what they write, so the
-// kernel's register count covers them.  This file is compiled with -amdgpu-mfma-vgpr-form, which
-// keeps the results of the compiler's own MFMAs (the first product) in VGPRs, and the kernel needs
-// fewer than 256 VGPRs, so the compiler itself uses no AGPR here; tests/test_abi.py checks in the
-// generated code that nothing but these statements names one.  368 registers per lane in all, which
-// leaves room on every SIMD for the waves of the fetch kernel that runs beside Attn0.
-#define ESS_ACC_TUPLES(X) X(0, 0, 1, 2, 3) X(1, 4, 5, 6, 7) X(2, 8, 9, 10, 11) X(3, 12, 13, 14, 15) X(4, 16, 17, 18, 19) X(5, 20, 21, 22, 23) X(6, 24, 25, 26, 27) X(7, 28, 29, 30, 31) X(8, 32, 33, 34, 35) X(9, 36, 37, 38, 39) X(10, 40, 41, 42, 43) X(11, 44, 45, 46, 47) X(12, 48, 49, 50, 51) X(13, 52, 53, 54, 55) X(14, 56, 57, 58, 59) X(15, 60, 61, 62, 63) X(16, 64, 65, 66, 67) X(17, 68, 69, 70, 71) X(18, 72, 73, 74, 75) X(19, 76, 77, 78, 79) X(20, 80, 81, 82, 83) X(21, 84, 85, 86, 87) X(22, 88, 89, 90, 91) X(23, 92, 93, 94, 95) X(24, 96, 97, 98, 99) X(25, 100, 101, 102, 103) X(26, 104, 105, 106, 107) X(27, 108, 109, 110, 111) X(28, 112, 113, 114, 115) X(29, 116, 117, 118, 119) X(30, 120, 121, 122, 123) X(31, 124, 125, 126, 127)
-#define ESS_ACC_REGS(X) X(0, 0) X(1, 1) X(2, 2) X(3, 3) X(4, 4) X(5, 5) X(6, 6) X(7, 7) X(8, 8) X(9, 9) X(10, 10) X(11, 11) X(12, 12) X(13, 13) X(14, 14) X(15, 15) X(16, 16) X(17, 17) X(18, 18) X(19, 19) X(20, 20) X(21, 21) X(22, 22) X(23, 23) X(24, 24) X(25, 25) X(26, 26) X(27, 27) X(28, 28) X(29, 29) X(30, 30) X(31, 31) X(32, 32) X(33, 33) X(34, 34) X(35, 35) X(36, 36) X(37, 37) X(38, 38) X(39, 39) X(40, 40) X(41, 41) X(42, 42) X(43, 43) X(44, 44) X(45, 45) X(46, 46) X(47, 47) X(48, 48) X(49, 49) X(50, 50) X(51, 51) X(52, 52) X(53, 53) X(54, 54) X(55, 55) X(56, 56) X(57, 57) X(58, 58) X(59, 59) X(60, 60) X(61, 61) X(62, 62) X(63, 63) X(64, 64) X(65, 65) X(66, 66) X(67, 67) X(68, 68) X(69, 69) X(70, 70) X(71, 71) X(72, 72) X(73, 73) X(74, 74) X(75, 75) X(76, 76) X(77, 77) X(78, 78) X(79, 79) X(80, 80) X(81, 81) X(82, 82) X(83, 83) X(84, 84) X(85, 85) X(86, 86) X(87, 87) X(88, 88) X(89, 89) X(90, 90) X(91, 91) X(92, 92) X(93, 93) X(94, 94) X(95, 95) X(96, 96) X(97, 97) X(98, 98) X(99, 99) X(100, 100) X(101, 101) X(102, 102) X(103, 103) X(104, 104) X(105, 105) X(106, 106) X(107, 107) X(108, 108) X(109, 109) X(110, 110) X(111, 111) X(112, 112) X(113, 113) X(114, 114) X(115, 115) X(116, 116) X(117, 117) X(118, 118) X(119, 119) X(120, 120) X(121, 121) X(122, 122) X(123, 123) X(124, 124) X(125, 125) X(126, 126) X(127, 127)
+typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-// The compiler's hazard logic does not look into asm statements, and an MFMA that directly follows the vector
-// ALU instruction producing one of its VGPR operands was seen to read the register's previous contents.  The
-// first MFMA of every chunk (WAIT) therefore carries its wait states inside its own statement, where no
-// scheduling can separate them from it; the later ones of a chunk follow an MFMA.
-template <int VB, bool WAIT> __device__ __forceinline__ void pv_mfma(const bf16x8& a, const bf16x8& b);
-#define X(vb, r0, r1, r2, r3)                                                                            \
-  template <> __device__ __forceinline__ void pv_mfma<vb, false>(const bf16x8& a, const bf16x8& b) {     \
-    asm volatile("v_mfma_f32_16x16x32_bf16 a[" #r0 ":" #r3 "], %0, %1, a[" #r0 ":" #r3 "]"               \
-                 : : "v"(a), "v"(b) : "a" #r0, "a" #r1, "a" #r2, "a" #r3);                               \
-  }                                                                                                      \
-  template <> __device__ __forceinline__ void pv_mfma<vb, true>(const bf16x8& a, const bf16x8& b) {      \
-    asm volatile("s_nop 7\n\tv_mfma_f32_16x16x32_bf16 a[" #r0 ":" #r3 "], %0, %1, a[" #r0 ":" #r3 "]"    \
-                 : : "v"(a), "v"(b) : "a" #r0, "a" #r1, "a" #r2, "a" #r3);                               \
-  }
-ESS_ACC_TUPLES(X)
-#undef X
-template <int BASE, int... I>
-__device__ __forceinline__ void pv_chunk(const bf16x8 (&fv)[sizeof...(I)], const bf16x8& pb, std::integer_sequence<int, I...>) {
-  (pv_mfma<BASE + I, I == 0>(fv[I], pb), ...);
+// The 256 output accumulators of a wave (16 blocks of 32 value columns x 32 heads, 16 registers each) live in
+// AGPRs a0..a255 under fixed names, outside the compiler's register allocation: every access is an asm statement
+// that names them by number.  (Left to the allocator -- as MFMA builtins, or as asm operands with the "a"
+// constraint -- they are copied around or spilled, because the rare rescale multiplies them with vector ALU
+// instructions and the loop leaves no spare 16-register tuple.)  This file is compiled with
+// -amdgpu-mfma-vgpr-form, which keeps the results of the compiler's own MFMAs (the first product) in VGPRs, and
+// the AGPR file is claimed as a whole (see AgprHold below), so that the compiler has no use for AGPRs of its own:
+// tests/test_abi.py checks in the generated code that nothing but these statements names one and that nothing is
+// spilled.
+// The compiler's hazard logic does not look into asm statements, and an MFMA that directly follows the vector ALU
+// instruction producing one of its VGPR operands was seen to read the register's previous contents: an MFMA
+// marked WAIT carries wait states inside its own statement, where no scheduling can separate them from it.
+// The compiler must keep its hands off the AGPRs that these statements use behind its back.  It is told that they
+// are taken: eight 32-register values with the "a" constraint are defined at the start of the kernel (by an empty
+// statement) and passed through empty statements (agpr_fence) at the top of every tile iteration and at the end, so
+// they are live throughout and fill the AGPR file -- the allocator has no AGPR left for a temporary or a spill of
+// its own, and the launch reserves all 256.  What the values "hold" is of no interest to the compiler's code.
+typedef float floatx32 __attribute__((ext_vector_type(32)));
+struct AgprHold { floatx32 d0, d1, d2, d3, d4, d5, d6, d7; };
+// (the comments inside the statements mark the claimed stretch in the generated code, for the test that reads it)
+__device__ __forceinline__ void agpr_claim(AgprHold& h) {
+  asm volatile("; ess_agpr_claim" : "=a"(h.d0), "=a"(h.d1), "=a"(h.d2), "=a"(h.d3), "=a"(h.d4), "=a"(h.d5), "=a"(h.d6), "=a"(h.d7));
 }
-__device__ __forceinline__ void acc_zero() {
-#define X(n, r) asm volatile("v_accvgpr_write_b32 a" #r ", 0" : : : "a" #r);
-  ESS_ACC_REGS(X)
-#undef X
+__device__ __forceinline__ void agpr_fence(AgprHold& h) {
+  asm volatile("; ess_agpr_fence" : "+a"(h.d0), "+a"(h.d1), "+a"(h.d2), "+a"(h.d3), "+a"(h.d4), "+a"(h.d5), "+a"(h.d6), "+a"(h.d7));
 }
-// a[4 vb + i] holds row 4g+i of value block vb for head n16: every register of a lane scales by the lane's alpha
-__device__ __forceinline__ void acc_scale(float alpha) {
+__device__ __forceinline__ void agpr_release(AgprHold& h) {
+  asm volatile("; ess_agpr_release" : "+a"(h.d0), "+a"(h.d1), "+a"(h.d2), "+a"(h.d3), "+a"(h.d4), "+a"(h.d5), "+a"(h.d6), "+a"(h.d7));
+}
+template <int VB, bool WAIT>
+__device__ __forceinline__ void pv_mfma(const bf16x8& a, const bf16x8& b) {
+  if constexpr (WAIT)
+    asm volatile("s_nop 7\n\tv_mfma_f32_32x32x16_bf16 a[%2:%3], %0, %1, a[%2:%3]" : : "v"(a), "v"(b), "n"(16 * VB), "n"(16 * VB + 15));
+  else
+    asm volatile("v_mfma_f32_32x32x16_bf16 a[%2:%3], %0, %1, a[%2:%3]" : : "v"(a), "v"(b), "n"(16 * VB), "n"(16 * VB + 15));
+}
+template <int R> __device__ __forceinline__ void acc_zero1() { asm volatile("v_accvgpr_write_b32 a[%0], 0" : : "n"(R)); }
+template <int R> __device__ __forceinline__ void acc_scale1(float alpha) {
   float t;
-#define X(n, r) asm volatile("v_accvgpr_read_b32 %0, a" #r "\n\tv_mul_f32 %0, %0, %1\n\tv_accvgpr_write_b32 a" #r ", %0" \
-                             : "=&v"(t) : "v"(alpha) : "a" #r);
-  ESS_ACC_REGS(X)
-#undef X
+  asm volatile("v_accvgpr_read_b32 %0, a[%2]\n\ts_nop 0\n\tv_mul_f32 %0, %0, %1\n\ts_nop 0\n\tv_accvgpr_write_b32 a[%2], %0" : "=&v"(t) : "v"(alpha), "n"(R));
 }
-__device__ __forceinline__ void acc_read(float (&o)[128]) {
-#define X(n, r) asm volatile("v_accvgpr_read_b32 %0, a" #r : "=v"(o[n]));
-  ESS_ACC_REGS(X)
-#undef X
+template <int R> __device__ __forceinline__ float acc_read1() {
+  float t;
+  asm volatile("v_accvgpr_read_b32 %0, a[%1]" : "=v"(t) : "n"(R));
+  return t;
 }
+template <int... R> __device__ __forceinline__ void acc_zero_seq(std::integer_sequence<int, R...>) { (acc_zero1<R>(), ...); }
+template <int... R> __device__ __forceinline__ void acc_scale_seq(float alpha, std::integer_sequence<int, R...>) { (acc_scale1<R>(alpha), ...); }
+__device__ __forceinline__ void acc_zero() { acc_zero_seq(std::make_integer_sequence<int, 256>{}); }
+// every register of a lane belongs to the lane's head: all scale by the lane's alpha
+__device__ __forceinline__ void acc_scale(float alpha) { acc_scale_seq(alpha, std::make_integer_sequence<int, 256>{}); }
+// the 16 registers of block VB: rows (value columns) 32 VB + 8q + 4hh + i at index 4q + i
+template <int VB, int... I>
+__device__ __forceinline__ void acc_read_block(float (&o)[16], std::integer_sequence<int, I...>) { ((o[I] = acc_read1<16 * VB + I>()), ...); }
 
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) short4v lds_short4v;
@@ -180,18 +195,14 @@ __device__ __forceinline__ bf16x8 tr_frag(uint32_t addr_lo, uint32_t addr_hi) {
   return __builtin_bit_cast(bf16x8, x);
 }
 
-// max / sum over the four lanes that share lane % 16 (one per 16-lane group), result in all four
-__device__ __forceinline__ float group_max(float x) {
+// max / sum over the two lanes that hold one head (l and l ^ 32), result in both
+__device__ __forceinline__ float pair_max(float x) {
   uint2v a = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  const float y = fmaxf(__uint_as_float(a.x), __uint_as_float(a.y));
-  uint2v b = __builtin_amdgcn_permlane16_swap(__float_as_uint(y), __float_as_uint(y), false, false);
-  return fmaxf(__uint_as_float(b.x), __uint_as_float(b.y));
+  return fmaxf(__uint_as_float(a.x), __uint_as_float(a.y));
 }
-__device__ __forceinline__ float group_sum(float x) {
+__device__ __forceinline__ float pair_sum(float x) {
   uint2v a = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  const float y = __uint_as_float(a.x) + __uint_as_float(a.y);
-  uint2v b = __builtin_amdgcn_permlane16_swap(__float_as_uint(y), __float_as_uint(y), false, false);
-  return __uint_as_float(b.x) + __uint_as_float(b.y);
+  return __uint_as_float(a.x) + __uint_as_float(a.y);
 }
 
 template <int FMT, bool DYN>
@@ -206,12 +217,13 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
   constexpr int NBUF = tr_nbuf(FMT);
   int32_t* slot_cache = reinterpret_cast<int32_t*>(lds + NBUF * TR_RAW_BYTES);   // [MAX_TPS][32]
   const uint32_t lds0 = lds_addr_of(lds);
-  // Work item = (split, bt, head group): by workgroup index, or drawn from counters off the XCDs to be avoided.
-  // The head groups of one (split, bt) read the same entries, so they should meet in one L2: every XCD that takes
-  // work has a counter of its own (class c of nw) that hands out pairs c, c + nw, c + 2 nw .. head group by head
-  // group; a workgroup whose class has run out goes on with the next class, so any one workgroup could finish
-  // the whole launch.
-  const int n_pairs = nsplit * n_bt, n_items = n_pairs * n_hg;
+  // Work item = (bt, split, head group).  The work items of one (b,t) share its queries (144 KiB for 128 heads),
+  // so they should meet in one L2.  By workgroup index: bt is the fastest grid dimension, and consecutive
+  // workgroups go round the eight XCDs, so the splits of a row land on one XCD whenever the number of rows is a
+  // multiple of eight.  Drawn from counters (off the XCDs to be avoided): every XCD that takes work has a counter
+  // of its own (class c of nw) that hands out the items of rows c, c + nw, c + 2 nw .. one after the other; a
+  // workgroup whose class has run out goes on with the next class, so any one workgroup could finish the launch.
+  const int per_row = nsplit * n_hg, n_items = n_bt * per_row;
   constexpr bool dyn = DYN;
   int cls = 0, nw = 1, tried = 1;
   if (dyn) {
@@ -226,12 +238,12 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
   if (dyn) {
     int item;
     for (;;) {
-      // ticket v of class cls stands for pair (v / n_hg) * nw + cls, head group v % n_hg
+      // ticket v of class cls: row (v / per_row) * nw + cls, item v % per_row of that row
       __syncthreads();
       if (threadIdx.x == 0) {
         const uint32_t tk = atomicAdd(xcd.ticket + ESS_TK_CLASS + ESS_TK_STRIDE * cls, 1u);
-        const uint32_t pair = (tk / (uint32_t)n_hg) * (uint32_t)nw + (uint32_t)cls;
-        s_item = pair < (uint32_t)n_pairs ? (int)(pair * (uint32_t)n_hg + tk % (uint32_t)n_hg) : -1;
+        const uint32_t row = (tk / (uint32_t)per_row) * (uint32_t)nw + (uint32_t)cls;
+        s_item = row < (uint32_t)n_bt ? (int)(row * (uint32_t)per_row + tk % (uint32_t)per_row) : -1;
       }
       __syncthreads();
       item = __builtin_amdgcn_readfirstlane(s_item);
@@ -240,12 +252,12 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
       cls = cls + 1 == nw ? 0 : cls + 1;
     }
     if (item < 0) break;
+    bt = item / per_row;
+    split = (item % per_row) / n_hg;
     hg = item % n_hg;
-    split = (item / n_hg) % nsplit;
-    bt = item / (n_hg * nsplit);
   } else {
     if (round) break;
-    split = blockIdx.x; bt = blockIdx.y; hg = blockIdx.z;
+    bt = blockIdx.x; split = blockIdx.y; hg = blockIdx.z;
   }
   const int b = bt / T;
   // the thread index passes through an empty asm statement so that what is derived from it (lane constants, LDS
@@ -254,8 +266,8 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
   if constexpr (DYN) asm volatile("" : "+v"(tid));
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int g = lane >> 4, n16 = lane & 15;
-  const int head0 = (hg * 4 + wave) * 16;
+  const int hh = lane >> 5, h32 = lane & 31;       // half of the wave, head within the wave
+  const int head0 = hg * HPG + wave * HPW;
   const bool wave_active = head0 < H;
 
   const int n = n_list ? min(n_list[bt], kk) : kk;
@@ -265,28 +277,56 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
   const int tile_end = min(tile_begin + tps, tiles_total);
   const int my_tiles = max(tile_end - tile_begin, 0);
 
-  bf16x8 qb[KSTEPS];
-  {
-    const int head = head0 + n16;
-    const uint16_t* qrow = q + ((size_t)bt * H + min(head, H - 1)) * ESS_ROW_DIM;
+  // this thread's share of the split's entry list: asked for first, so that it arrives while the queries are staged
+  const int32_t* lrow = list + (size_t)bt * kk;
+  const uint8_t* pbase = pool + (size_t)b * S * row_stride;
+  constexpr int SLOTS_PT = MAX_TPS * TILE / NTH;   // 8 list entries per thread at most
+  int my_slot[SLOTS_PT];
 #pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) {
-      uint4 x = *reinterpret_cast<const uint4*>(qrow + ks * 32 + g * 8);
-      if (head >= H) x = make_uint4(0, 0, 0, 0);
-      qb[ks] = *reinterpret_cast<bf16x8*>(&x);
-    }
+  for (int u = 0; u < SLOTS_PT; ++u) {
+    const int j = tid + NTH * u, e = tile_begin * TILE + j;
+    int sl = (j < my_tiles * TILE && e < n) ? lrow[e] : -1;
+    if (sl >= S) sl = -1;
+    my_slot[u] = sl;
   }
+
+  // Q^T as the B operand, stationary: lane (hh, h) holds dims 16 ks + 8 hh .. + 7 of head h for every k-step.
+  // The queries of the workgroup's heads are one contiguous block in memory: the threads read it piece by piece
+  // (whole cache lines per wave instruction) into the still empty tile buffers, rows at a pitch of 1168 bytes so
+  // that sixteen rows' pieces fall on different banks, and every lane takes its fragments from there.  (Read
+  // straight from memory, a wave instruction touches 32 bytes of each of 32 rows and every cache line is asked for
+  // four times: most of what a workgroup cost beyond its tiles.)
+  bf16x8 qb[KS16];
+  {
+    constexpr int QPIECES = ESS_ROW_DIM * 2 / 16;    // 72 pieces of 16 bytes per head
+    const int nh = min(HPG, H - hg * HPG);
+    const uint4* qsrc = reinterpret_cast<const uint4*>(q + ((size_t)bt * H + (size_t)hg * HPG) * ESS_ROW_DIM);
+    const int npieces = nh * QPIECES;
+    uint4 x[HPG * QPIECES / NTH];                    // 36 loads of a thread in flight
+#pragma unroll
+    for (int i = 0; i < HPG * QPIECES / NTH; ++i) {
+      const int pc = tid + NTH * i;
+      x[i] = pc < npieces ? qsrc[pc] : make_uint4(0, 0, 0, 0);       // heads past H: zeros
+    }
+#pragma unroll
+    for (int i = 0; i < HPG * QPIECES / NTH; ++i) {
+      const int pc = tid + NTH * i, row = pc / QPIECES, col = pc - row * QPIECES;
+      *reinterpret_cast<uint4*>(lds + row * Q_PITCH + col * 16) = x[i];
+    }
+    __syncthreads();
+    const uint8_t* qrow = lds + (wave * HPW + h32) * Q_PITCH + hh * 16;
+#pragma unroll
+    for (int ks = 0; ks < KS16; ++ks) qb[ks] = *reinterpret_cast<const bf16x8*>(qrow + ks * 32);
+    __syncthreads();                                 // the staging area becomes tile buffers and slot list
+  }
+  AgprHold hold;
+  agpr_claim(hold);
   acc_zero();
   float m_ref = -__builtin_inff(), l_run = 0.f;
 
-  const int32_t* lrow = list + (size_t)bt * kk;
-  const uint8_t* pbase = pool + (size_t)b * S * row_stride;
-  for (int j = tid; j < my_tiles * TILE; j += NTH) {
-    const int e = tile_begin * TILE + j;
-    int sl = e < n ? lrow[e] : -1;
-    if (sl >= S) sl = -1;
-    slot_cache[j] = sl;
-  }
+#pragma unroll
+  for (int u = 0; u < SLOTS_PT; ++u)
+    if (tid + NTH * u < my_tiles * TILE) slot_cache[tid + NTH * u] = my_slot[u];
   wait_vmcnt<0>();                             // q and list loads are done: from here only the gathers count
   __syncthreads();
 
@@ -300,14 +340,14 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
   auto gather_sources = [&](int it, int (&sl)[DMA_PER_TILE]) {
     const int32_t* ts = slot_cache + it * TILE;
 #pragma unroll
-    for (int r8 = 0; r8 < 8; ++r8) sl[r8] = ts[wave * 8 + r8];
+    for (int r8 = 0; r8 < 8; ++r8) sl[r8] = __builtin_amdgcn_readfirstlane(ts[wave * 8 + r8]);   // the same in all lanes: scalar registers
     sl[8] = ts[rr];
   };
   auto gather_step = [&](int it, int step, const int (&sl)[DMA_PER_TILE]) {
     const uint32_t raw = lds0 + (uint32_t)((it % NBUF) * TR_RAW_BYTES);
     if (step < 8) {
       const int row = wave * 8 + step;
-      const int u = __builtin_amdgcn_readfirstlane(sl[step]);
+      const int u = sl[step];
       const uint8_t* src = u >= 0 ? pbase + (size_t)u * row_stride : zero_row;
       dma16(src + ((lane ^ tr_swz(row)) << 4), raw + (uint32_t)(row * TRP));
     } else {
@@ -354,7 +394,7 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
   };
   StagedF8 stg;
   if constexpr (kDma) {
-    for (int it = 0; it < min(my_tiles, NBUF - 1); ++it) {
+    for (int it = 0; it < min(my_tiles, 2); ++it) {
       int src[DMA_PER_TILE];
       gather_sources(it, src);
 #pragma unroll
@@ -365,152 +405,273 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
     if (my_tiles > 1) f8_load(1, stg);
   }
 
-  // lane constants of the two LDS access patterns
-  const int fk = tr_swz(n16);                                   // K fragments: row n16 (and 16 + n16)
-  uint32_t koff[4];                                             // by ks & 3; + 256 * (ks >> 2) is an immediate
-#pragma unroll
-  for (int c = 0; c < 4; ++c) koff[c] = (uint32_t)(n16 * TRP + (((4 * c + g) ^ fk) << 4));
-  const int ti = n16 >> 2, tj = n16 & 3;                        // transposing reads: source row 4g + ti, columns 4 tj ..
-  const int trow = 4 * g + ti;
-  const uint32_t c4 = (uint32_t)((((tj >> 1) ^ tr_swz(trow)) & 15) << 4);
-  uint32_t voff[8];                                             // by vb & 7; + 256 * (vb >> 3) is an immediate
-#pragma unroll
-  for (int c = 0; c < 8; ++c) voff[c] = (uint32_t)(trow * TRP + (tj & 1) * 8) + (((uint32_t)(32 * c)) ^ c4);
+  // lane constants of the two LDS access patterns.  K fragment of k-step ks: row h32, granule 2 ks + hh, i.e.
+  // kbase ^ ((ks & 7) << 5) plus 256 (ks >> 3) (the swizzle touches the low four granule bits only); rope
+  // k-steps read the rope region.  V^T fragment of block vb, k-step s: rows 16 s + 4 hh + ti (+ 8), columns
+  // 32 vb + 16 gi + 4 tj ..: vbase{0,1} ^ ((vb & 3) << 6) plus 256 (vb >> 2) plus 16 s rows.
+  const int fk = tr_swz(h32);
+  const uint32_t kbase = (uint32_t)(h32 * TRP + ((hh ^ fk) << 4));
+  const int gi = (lane >> 4) & 1, ti = (lane & 15) >> 2, tj = lane & 3;
+  const int vrow0 = 4 * hh + ti, vrow1 = 8 + 4 * hh + ti;
+  const uint32_t vbase0 = (uint32_t)(vrow0 * TRP + (((2 * gi + (tj >> 1)) ^ tr_swz(vrow0)) << 4) + (tj & 1) * 8);
+  const uint32_t vbase1 = (uint32_t)(vrow1 * TRP + (((2 * gi + (tj >> 1)) ^ tr_swz(vrow1)) << 4) + (tj & 1) * 8);
 
+  // pieces of a tile's work, shared by the two loops below
+  auto load_k = [&](const uint8_t* KL, int ks) -> bf16x8 {
+    if (ks < 32) return *reinterpret_cast<const bf16x8*>(KL + (kbase ^ (uint32_t)((ks & 7) << 5)) + 256 * (ks >> 3));
+    const int p = (ks - 32) * 2 + hh;
+    return *reinterpret_cast<const bf16x8*>(KL + TR_KL_BYTES + h32 * 128 + ((p ^ (h32 & 7)) * 16));
+  };
+  auto load_v = [&](uint32_t KLa, int j) -> bf16x8 {       // j = 16 s + vb: all blocks of k-step 0, then all of k-step 1
+    const int vb = j & 15, s = j >> 4;
+    const uint32_t x = (uint32_t)((vb & 3) << 6), off = 256u * (uint32_t)(vb >> 2) + (uint32_t)(16 * s * TRP);
+    return tr_frag(KLa + (vbase0 ^ x) + off, KLa + (vbase1 ^ x) + off);
+  };
+  // logits of the lane's sixteen rows (8 q + 4 hh + i at index 4 q + i), masked rows at -inf
+  auto logits = [&](const floatx16& sacc, const int32_t* tile_slot, float (&z)[16]) {
+#pragma unroll
+    for (int qd = 0; qd < 4; ++qd) {
+      const int4 v = *reinterpret_cast<const int4*>(tile_slot + 8 * qd + 4 * hh);
+      z[4 * qd] = v.x >= 0 ? sacc[4 * qd] * scale_log2e : -__builtin_inff();
+      z[4 * qd + 1] = v.y >= 0 ? sacc[4 * qd + 1] * scale_log2e : -__builtin_inff();
+      z[4 * qd + 2] = v.z >= 0 ? sacc[4 * qd + 2] * scale_log2e : -__builtin_inff();
+      z[4 * qd + 3] = v.w >= 0 ? sacc[4 * qd + 3] * scale_log2e : -__builtin_inff();
+    }
+  };
+  auto max16 = [](const float (&z)[16]) {
+    return fmaxf(fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])), fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7]))),
+                 fmaxf(fmaxf(fmaxf(z[8], z[9]), fmaxf(z[10], z[11])), fmaxf(fmaxf(z[12], z[13]), fmaxf(z[14], z[15]))));
+  };
+
+  if constexpr (kDma) {
+    // ---- bf16 entries.  One wave per SIMD issues its instructions one at a time, and what a tile costs is the
+    // sum of their issue times (a vector ALU instruction 4 cycles, an LDS read 13-16), not the 2176 cycles its 68
+    // MFMAs keep the matrix pipe busy.  The loop is therefore a software pipeline in which the vector ALU work of
+    // the softmax rides in the shadow of MFMAs: iteration `it`
+    //   1. computes S^T of tile it (a chain of 36 dependent MFMAs) and, between them, turns the logits of tile
+    //      it-1 into P^T (exponentials, row sums, bf16 pairs);
+    //   2. issues the second product of tile it-1 and, between its MFMAs, turns S^T of tile it into logits and
+    //      takes their maximum (which may move the softmax reference: the accumulators are then rescaled after
+    //      these MFMAs, before those of tile it).
+    // A tile's buffer is in use for two iterations, and the gathers of tile it+2 (into the buffer tile it-2 used)
+    // are issued during iteration it: two tiles in flight.
+    float z[16];                                 // logits of the previous tile (rows 8 q + 4 hh + i at index 4 q + i)
+    float m_use = 0.f;                           // the reference they are taken against
+    float alpha_pending = 1.f;                   // rescale of the accumulators due before the next second product
+    bool scale_pending = false;
+    // one iteration; QK: there is a tile `it` to start, PV: there is a tile it-1 to finish
+    auto iteration = [&](int it, auto qkc, auto pvc) {
+      constexpr bool QK = decltype(qkc)::value, PV = decltype(pvc)::value;
+      const uint8_t* KL = lds + (it % NBUF) * TR_RAW_BYTES;
+      const uint32_t KLp = lds0 + (uint32_t)(((it + NBUF - 1) % NBUF) * TR_RAW_BYTES);     // tile it-1
+      const bool more = it + 2 < my_tiles;
+      int src[DMA_PER_TILE];
+      agpr_fence(hold);
+      if constexpr (QK) {
+        // this wave's gathers of tile `it` have landed when at most those of tile it+1 are outstanding
+        if (it + 1 < my_tiles) wait_vmcnt<DMA_PER_TILE>(); else wait_vmcnt<0>();
+      }
+      __syncthreads();                           // ... everyone's did; and everyone is done with tile it-2
+      if (more) gather_sources(it + 2, src);
+      if (!wave_active) {
+        if (more) {
+#pragma unroll
+          for (int step = 0; step < DMA_PER_TILE; ++step) gather_step(it + 2, step, src);
+        }
+        return;
+      }
+      floatx16 sacc;
+      uint32_t pq[8];                            // P^T of tile it-1 as bf16 pairs: k-step 0 in [0..3], k-step 1 in [4..7]
+      float psum = 0.f;
+      // one row of tile it-1: exponential against the reference, row sum, and (every second row) a bf16 pair
+      auto exp_row = [&](auto ic) {
+        constexpr int i = decltype(ic)::value;
+        z[i] = __builtin_amdgcn_exp2f(z[i] - m_use);     // the argument is <= 2^kLazyMax: no range reduction needed
+        psum += z[i];
+        if constexpr (i & 1) pq[i >> 1] = pack_bf16(z[i - 1], z[i]);
+      };
+      if constexpr (QK) {
+        // S^T = K Q^T: 36 k-steps, A fragments read CK k-steps ahead; a gather instruction after every fourth
+        // k-step; rows of tile it-1 after every second one
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+        constexpr int CK = 3;
+        bf16x8 fa[CK];
+#pragma unroll
+        for (int j = 0; j < CK; ++j) fa[j] = load_k(KL, j);
+        auto qk_step = [&](auto ksc) {
+          constexpr int ks = decltype(ksc)::value;
+          const bf16x8 a = fa[ks % CK];
+          if (ks + CK < KS16) fa[ks % CK] = load_k(KL, ks + CK);
+          if (more && (ks & 3) == 3) gather_step(it + 2, ks >> 2, src);
+          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qb[ks], sacc, 0, 0, 0);
+          if constexpr (PV && (ks & 1) == 1 && (ks >> 1) < 16) exp_row(std::integral_constant<int, (ks >> 1)>{});
+        };
+        [&]<int... K>(std::integer_sequence<int, K...>) { (qk_step(std::integral_constant<int, K>{}), ...); }
+        (std::make_integer_sequence<int, KS16>{});
+      } else {
+        [&]<int... I>(std::integer_sequence<int, I...>) { (exp_row(std::integral_constant<int, I>{}), ...); }
+        (std::make_integer_sequence<int, 16>{});
+      }
+      if constexpr (PV) l_run += psum;
+      agpr_fence(hold);
+      if (scale_pending) {                       // wave-uniform; rare
+        acc_scale(alpha_pending);
+        scale_pending = false;
+      }
+      // second product of tile it-1 (32 MFMAs) with the logits of tile it taken between them
+      constexpr int CV = 5;
+      bf16x8 fv[CV];
+      if constexpr (PV) {
+#pragma unroll
+        for (int j = 0; j < CV; ++j) fv[j] = load_v(KLp, j);
+      }
+      const int32_t* tile_slot = slot_cache + it * TILE;
+      auto step = [&](auto jc) {
+        constexpr int j = decltype(jc)::value;
+        if constexpr (PV) {
+          const bf16x8 a = fv[j % CV];
+          if (j + CV < 2 * VB32) fv[j % CV] = load_v(KLp, j + CV);
+          uint4 pw = j < 16 ? make_uint4(pq[0], pq[1], pq[2], pq[3]) : make_uint4(pq[4], pq[5], pq[6], pq[7]);
+          pv_mfma<(j & 15), (j == 0 || j == 16)>(a, *reinterpret_cast<bf16x8*>(&pw));
+        }
+        if constexpr (QK) {
+          if constexpr (j >= 2 && j < 18 && (j & 3) == 2) {      // logits of rows 8 qd + 4 hh + i, masked rows at -inf
+            constexpr int qd = (j - 2) >> 2;
+            const int4 v = *reinterpret_cast<const int4*>(tile_slot + 8 * qd + 4 * hh);
+            z[4 * qd] = v.x >= 0 ? sacc[4 * qd] * scale_log2e : -__builtin_inff();
+            z[4 * qd + 1] = v.y >= 0 ? sacc[4 * qd + 1] * scale_log2e : -__builtin_inff();
+            z[4 * qd + 2] = v.z >= 0 ? sacc[4 * qd + 2] * scale_log2e : -__builtin_inff();
+            z[4 * qd + 3] = v.w >= 0 ? sacc[4 * qd + 3] * scale_log2e : -__builtin_inff();
+          }
+          if constexpr (j == 20) {
+            const float tmax = pair_max(max16(z));
+            // move the reference only when this tile exceeds it by more than 2^kLazyMax (always from -inf)
+            const bool move = tmax > m_ref + kLazyMax;
+            if (__any(move)) {
+              const float m_new = move ? tmax : m_ref;
+              alpha_pending = m_new == -__builtin_inff() ? 1.f : exp2f(m_ref - m_new);   // m_ref = -inf: 0, acc is 0 anyway
+              l_run *= alpha_pending;
+              m_ref = m_new;
+              scale_pending = true;              // the accumulators are rescaled once the MFMAs of tile it-1 are through
+            }
+            m_use = (m_ref == -__builtin_inff()) ? 0.f : m_ref;
+          }
+        }
+      };
+      [&]<int... J>(std::integer_sequence<int, J...>) { (step(std::integral_constant<int, J>{}), ...); }
+      (std::make_integer_sequence<int, 2 * VB32>{});
+    };
+    if (my_tiles > 0) {
+      iteration(0, std::true_type{}, std::false_type{});
+      for (int it = 1; it < my_tiles; ++it) iteration(it, std::true_type{}, std::true_type{});
+      iteration(my_tiles, std::false_type{}, std::true_type{});
+    }
+  } else {
   for (int it = 0; it < my_tiles; ++it) {
+    // ---- quantised entries: the tile's three phases one after the other
     const uint32_t KLa = lds0 + (uint32_t)((it % NBUF) * TR_RAW_BYTES);
     const uint8_t* KL = lds + (it % NBUF) * TR_RAW_BYTES;
-    const uint8_t* RP = KL + TR_KL_BYTES;
-    const int32_t* tile_slot = slot_cache + it * TILE;
-    const bool more = kDma && it + NBUF - 1 < my_tiles;   // tile it+3 goes into the buffer tile it-1 used
-    int src[DMA_PER_TILE];
-    if constexpr (kDma) {
-      // this wave's gathers of tile `it` have landed when at most those of the later tiles are outstanding
-      const int later = min(my_tiles - 1 - it, NBUF - 2);
-      if (later >= 2) wait_vmcnt<2 * DMA_PER_TILE>(); else if (later == 1) wait_vmcnt<DMA_PER_TILE>(); else wait_vmcnt<0>();
-      __syncthreads();                         // ... everyone's did; and everyone is done with tile it-1
-      if (more) gather_sources(it + NBUF - 1, src);
-    } else {
-      __syncthreads();                         // tile `it` is in LDS (written a tile ago); everyone is done with tile it-1
-      if (it + 1 < my_tiles) f8_store(it + 1, stg);   // into the buffer tile it-1 used
-      if (it + 2 < my_tiles) f8_load(it + 2, stg);
-    }
-    if (!wave_active) {
-      if (more) {
-#pragma unroll
-        for (int step = 0; step < DMA_PER_TILE; ++step) gather_step(it + NBUF - 1, step, src);
-      }
-      continue;
-    }
+    agpr_fence(hold);
+    __syncthreads();                           // tile `it` is in LDS (written a tile ago); everyone is done with tile it-1
+    if (it + 1 < my_tiles) f8_store(it + 1, stg);   // into the buffer tile it-1 used
+    if (it + 2 < my_tiles) f8_load(it + 2, stg);
+    if (!wave_active) continue;
 
-    // ---- S^T = K Q^T; A fragments read six k-steps ahead of the MFMAs that use them; three gather
-    // instructions of tile it+3 after each chunk of fragment reads
-    floatx4 s0 = floatx4{0.f, 0.f, 0.f, 0.f}, s1 = s0;
-    constexpr int CH = kDma ? 6 : 3;           // quantised entries: the staged tile needs the registers
-    bf16x8 fa[2][CH], fb[2][CH];
-    auto load_chunk = [&](int c, bf16x8 (&da)[CH], bf16x8 (&db)[CH]) {
+    floatx16 sacc;
 #pragma unroll
-      for (int j = 0; j < CH; ++j) {
-        const int ks = c * CH + j;
-        if (ks < 16) {
-          da[j] = *reinterpret_cast<const bf16x8*>(KL + koff[ks & 3] + 256 * (ks >> 2));
-          db[j] = *reinterpret_cast<const bf16x8*>(KL + koff[ks & 3] + 256 * (ks >> 2) + 16 * TRP);
-        } else {
-          const int p = (ks - 16) * 4 + g;
-          da[j] = *reinterpret_cast<const bf16x8*>(RP + n16 * 128 + ((p ^ (n16 & 7)) * 16));
-          db[j] = *reinterpret_cast<const bf16x8*>(RP + (16 + n16) * 128 + ((p ^ (n16 & 7)) * 16));
-        }
-      }
-    };
-    load_chunk(0, fa[0], fb[0]);
+    for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+    constexpr int CK = 2;                      // the staged tile needs the registers
+    bf16x8 fa[CK];
 #pragma unroll
-    for (int c = 0; c < KSTEPS / CH; ++c) {
-      if (c + 1 < KSTEPS / CH) load_chunk(c + 1, fa[(c + 1) & 1], fb[(c + 1) & 1]);
-      if (more) {
+    for (int j = 0; j < CK; ++j) fa[j] = load_k(KL, j);
 #pragma unroll
-        for (int step = 9 * c / (KSTEPS / CH); step < 9 * (c + 1) / (KSTEPS / CH); ++step) gather_step(it + NBUF - 1, step, src);
-      }
-#pragma unroll
-      for (int j = 0; j < CH; ++j) {
-        s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[c & 1][j], qb[c * CH + j], s0, 0, 0, 0);
-        s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[c & 1][j], qb[c * CH + j], s1, 0, 0, 0);
-      }
+    for (int ks = 0; ks < KS16; ++ks) {
+      const bf16x8 a = fa[ks % CK];
+      if (ks + CK < KS16) fa[ks % CK] = load_k(KL, ks + CK);
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qb[ks], sacc, 0, 0, 0);
     }
-    const int4 v0 = *reinterpret_cast<const int4*>(tile_slot + g * 4);
-    const int4 v1 = *reinterpret_cast<const int4*>(tile_slot + 16 + g * 4);
-    // the first V fragments do not depend on the softmax: request them now, they arrive while it runs
-    constexpr int CV = 8;
-    bf16x8 fv[2][CV];
-    auto load_v = [&](int c, bf16x8 (&d)[CV]) {
-#pragma unroll
-      for (int j = 0; j < CV; ++j) {
-        const int vb = c * CV + j;
-        const uint32_t a = KLa + voff[vb & 7] + 256u * (uint32_t)(vb >> 3);
-        d[j] = tr_frag(a, a + 16 * TRP);
-      }
-    };
-    load_v(0, fv[0]);
-    load_v(1, fv[1]);
-    const bool ok[8] = {v0.x >= 0, v0.y >= 0, v0.z >= 0, v0.w >= 0, v1.x >= 0, v1.y >= 0, v1.z >= 0, v1.w >= 0};
-    float z[8];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      z[i] = ok[i] ? s0[i] * scale_log2e : -__builtin_inff();
-      z[4 + i] = ok[4 + i] ? s1[i] * scale_log2e : -__builtin_inff();
-    }
-    const float tmax = group_max(fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])), fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7]))));
-    // move the reference only when this tile exceeds it by more than 2^kLazyMax (always from -inf)
+    agpr_fence(hold);
+    float z[16];
+    logits(sacc, slot_cache + it * TILE, z);
+    const float tmax = pair_max(max16(z));
     const bool move = tmax > m_ref + kLazyMax;
     if (__any(move)) {
       const float m_new = move ? tmax : m_ref;
-      const float alpha = m_new == -__builtin_inff() ? 1.f : exp2f(m_ref - m_new);   // m_ref = -inf: 0, acc is 0 anyway
+      const float alpha = m_new == -__builtin_inff() ? 1.f : exp2f(m_ref - m_new);
       l_run *= alpha;
       m_ref = m_new;
       acc_scale(alpha);
     }
     const float m_safe = (m_ref == -__builtin_inff()) ? 0.f : m_ref;
-    float p[8], psum = 0.f;
+    float psum = 0.f;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      p[j] = exp2f(z[j] - m_safe);
-      psum += p[j];
+    for (int j = 0; j < 16; ++j) {
+      z[j] = __builtin_amdgcn_exp2f(z[j] - m_safe);     // the argument is <= 2^kLazyMax: no range reduction needed
+      psum += z[j];
     }
     l_run += psum;
-    uint4 pw = make_uint4(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7]));
-    const bf16x8 pb = *reinterpret_cast<bf16x8*>(&pw);
-
-    // ---- O^T += V^T P^T, A fragments by transposing reads, eight blocks ahead
-    static_assert(VBLOCKS / CV == 4, "four chunks of value blocks");
-    constexpr auto seq = std::make_integer_sequence<int, CV>{};
-    pv_chunk<0 * CV>(fv[0], pb, seq);
-    load_v(2, fv[0]);
-    pv_chunk<1 * CV>(fv[1], pb, seq);
-    load_v(3, fv[1]);
-    pv_chunk<2 * CV>(fv[0], pb, seq);
-    pv_chunk<3 * CV>(fv[1], pb, seq);
+    uint4 pw0 = make_uint4(pack_bf16(z[0], z[1]), pack_bf16(z[2], z[3]), pack_bf16(z[4], z[5]), pack_bf16(z[6], z[7]));
+    uint4 pw1 = make_uint4(pack_bf16(z[8], z[9]), pack_bf16(z[10], z[11]), pack_bf16(z[12], z[13]), pack_bf16(z[14], z[15]));
+    const bf16x8 pb0 = *reinterpret_cast<bf16x8*>(&pw0), pb1 = *reinterpret_cast<bf16x8*>(&pw1);
+    agpr_fence(hold);
+    constexpr int CV = 4;
+    bf16x8 fv[CV];
+#pragma unroll
+    for (int j = 0; j < CV; ++j) fv[j] = load_v(KLa, j);
+    auto pv_step = [&](auto jc) {
+      constexpr int j = decltype(jc)::value;
+      const bf16x8 a = fv[j % CV];
+      if (j + CV < 2 * VB32) fv[j % CV] = load_v(KLa, j + CV);
+      pv_mfma<(j & 15), (j == 0 || j == 16)>(a, j < 16 ? pb0 : pb1);
+    };
+    [&]<int... J>(std::integer_sequence<int, J...>) { (pv_step(std::integral_constant<int, J>{}), ...); }
+    (std::make_integer_sequence<int, 2 * VB32>{});
+  }
   }
   // the hazard logic does not see the MFMAs inside the asm statements: let the last ones retire
   // before their results are read
-  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+  agpr_fence(hold);
 
   {
-    const int head = head0 + n16;
-    const float l_tot = group_sum(l_run);
+    // lane constants afresh (see above): nothing of the epilogue is carried through the tile loop
+    int tid2 = threadIdx.x;
+    asm volatile("" : "+v"(tid2));
+    const int lane2 = tid2 & 63, hh2 = (tid2 >> 5) & 1, h2 = tid2 & 31, head = head0 + h2;
+    const float l_tot = pair_sum(l_run);
     const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-    float o[128];
-    acc_read(o);
-    if (head < H) {
-      const size_t prow = ((size_t)bt * ESS_MAX_SPLITS + split0 + split) * H + head;
-      _Float16* op = o_part + prow * ESS_LATENT_DIM;
+    const size_t prow = ((size_t)bt * ESS_MAX_SPLITS + split0 + split) * H + min(head, H - 1);
+    // The partial result goes through LDS (the tile buffers are free now) so that it leaves as whole rows: a lane
+    // holds four consecutive columns at a time, of a row 1 KiB away from its neighbour's.  fp16 rows at a pitch of
+    // 1032 bytes: the 32 heads of a half-wave write 8 bytes each to 64 different banks.
+    __syncthreads();                                 // every wave is done with the last tile
+    uint8_t* orow = lds + (wave * HPW + h2) * O_PITCH + 8 * hh2;
+    auto stage_block = [&](auto vbc) {
+      constexpr int vb = decltype(vbc)::value;
+      float o[16];
+      acc_read_block<vb>(o, std::make_integer_sequence<int, 16>{});
 #pragma unroll
-      for (int vb = 0; vb < VBLOCKS; ++vb) {
-        floatx4 ov = floatx4{o[4 * vb] * inv, o[4 * vb + 1] * inv, o[4 * vb + 2] * inv, o[4 * vb + 3] * inv};
+      for (int qd = 0; qd < 4; ++qd) {
+        floatx4 ov = floatx4{o[4 * qd] * inv, o[4 * qd + 1] * inv, o[4 * qd + 2] * inv, o[4 * qd + 3] * inv};
 #pragma unroll
         for (int i = 0; i < 4; ++i) ov[i] = __builtin_amdgcn_fmed3f(ov[i], -65504.f, 65504.f);   // an average of entry values: saturate, never inf
-        *reinterpret_cast<halfx4*>(op + vb * 16 + g * 4) = __builtin_convertvector(ov, halfx4);   // round to nearest even
+        *reinterpret_cast<halfx4*>(orow + (vb * 32 + 8 * qd) * 2) = __builtin_convertvector(ov, halfx4);   // round to nearest even
       }
-      if (g == 0) lse_part[prow] = l_tot > 0.f ? (m_ref + log2f(l_tot)) * kLn2 : -__builtin_inff();
+    };
+    [&]<int... V>(std::integer_sequence<int, V...>) { (stage_block(std::integral_constant<int, V>{}), ...); }
+    (std::make_integer_sequence<int, VB32>{});
+    agpr_release(hold);                              // the accumulators are read out: the AGPRs are the compiler's again
+    __syncthreads();
+    // a wave writes its own 32 rows, 1 KiB per instruction
+    const int rows_here = min(HPW, H - head0);
+    _Float16* obase = o_part + (((size_t)bt * ESS_MAX_SPLITS + split0 + split) * H + head0) * ESS_LATENT_DIM;
+    for (int r = 0; r < rows_here; ++r) {
+      const uint2* src = reinterpret_cast<const uint2*>(lds + (wave * HPW + r) * O_PITCH + lane2 * 16);
+      const uint2 lo = src[0], hi = src[1];
+      *reinterpret_cast<uint4*>(reinterpret_cast<uint8_t*>(obase + (size_t)r * ESS_LATENT_DIM) + lane2 * 16) = make_uint4(lo.x, lo.y, hi.x, hi.y);
     }
+    if (head < H && hh2 == 0) lse_part[prow] = l_tot > 0.f ? (m_ref + log2f(l_tot)) * kLn2 : -__builtin_inff();
   }
   }
 }
@@ -603,8 +764,8 @@ int ess_launch_attn_partial(ess_ctx* ctx, const void* q, const uint8_t* slot_poo
                             const int32_t* n_list, int B, int T, int split0, int nsplit, hipStream_t st, int b0, ess_xcd xcd) {
   const ess_config& c = ctx->cfg;
   if (nsplit < ess_attn_min_splits(c)) return ess_fail(ESS_ERR_INVALID_ARG, "internal: too few attention splits");
-  const int n_hg = (c.attn_heads + 63) / 64;            // 64 heads per workgroup
-  dim3 grid(nsplit, B * T, n_hg);
+  const int n_hg = (c.attn_heads + HPG - 1) / HPG;      // 128 heads per workgroup
+  dim3 grid(B * T, nsplit, n_hg);
   if (xcd.ticket) grid = dim3(ess_xcd_grid(nsplit * B * T * n_hg, xcd));     // one workgroup per CU
   const float sc = c.sm_scale * kLog2e;
   const uint16_t* qq = static_cast<const uint16_t*>(q);
