@@ -205,8 +205,10 @@ int ess_gather_latent(ess_ctx* ctx, const ess_cache* cache, const int32_t* idx, 
  * operands (fp8 entries are dequantised to bf16), fp32 accumulation and softmax.
  * The entry list is processed in several parts whose normalised results are
  * merged; they are held as fp16 in between (11 significant bits, against the 8
- * of the bf16 output) and saturate at +-65504, so entry values are expected to
- * stay below that magnitude.  Empty selection: out = 0, lse = -inf. */
+ * of the bf16 output), each head's part divided by the power of two that keeps
+ * its largest value below 2^15, so entry values of any bf16 magnitude pass
+ * (values more than 2^29 below the largest one of their head and part are
+ * flushed to zero).  Empty selection: out = 0, lse = -inf. */
 int ess_sparse_mla_decode(ess_ctx* ctx, const void* q_bf16, const uint8_t* slot_pool,
                           const int32_t* slot_idx, int32_t B, int32_t T, void* out_bf16, float* lse,
                           void* stream);

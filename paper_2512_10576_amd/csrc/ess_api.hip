@@ -81,7 +81,7 @@ WsLayout ws_layout(const ess_config& c) {
   w.fill_slot = take(B * T * k * 4);
   w.miss_cnt = take(B * 4);
   w.o_part = take(B * T * ESS_MAX_SPLITS * H * ESS_LATENT_DIM * 2);
-  w.lse_part = take(B * T * ESS_MAX_SPLITS * H * 4);
+  w.lse_part = take(B * T * ESS_MAX_SPLITS * H * 8);
   w.stats = take(4 * 8);
   w.zero_row = take(ESS_ZERO_ROW_BYTES);
   w.topk_cand = take(ess_topk_cand_bytes());

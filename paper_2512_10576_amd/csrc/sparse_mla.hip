@@ -640,27 +640,43 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
     asm volatile("" : "+v"(tid2));
     const int lane2 = tid2 & 63, hh2 = (tid2 >> 5) & 1, h2 = tid2 & 31, head = head0 + h2;
     const float l_tot = pair_sum(l_run);
-    const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+    float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
     const size_t prow = ((size_t)bt * ESS_MAX_SPLITS + split0 + split) * H + min(head, H - 1);
     // The partial result goes through LDS (the tile buffers are free now) so that it leaves as whole rows: a lane
     // holds four consecutive columns at a time, of a row 1 KiB away from its neighbour's.  fp16 rows at a pitch of
     // 1032 bytes: the 32 heads of a half-wave write 8 bytes each to 64 different banks.
+    // fp16 holds magnitudes below 65504.  The rows are staged as they are, the largest magnitude noted on the way;
+    // should a head's reach 2^15 (entry values of that size: rare) the wave stages once more, such heads divided by
+    // the power of two that brings their largest value below 2^15 -- exact, and undone by the merge.
     __syncthreads();                                 // every wave is done with the last tile
     uint8_t* orow = lds + (wave * HPW + h2) * O_PITCH + 8 * hh2;
-    auto stage_block = [&](auto vbc) {
-      constexpr int vb = decltype(vbc)::value;
-      float o[16];
-      acc_read_block<vb>(o, std::make_integer_sequence<int, 16>{});
+    float amax = 0.f, down = 1.f;
+    auto stage_rows = [&]() {
+      auto stage_block = [&](auto vbc) {
+        constexpr int vb = decltype(vbc)::value;
+        float o[16];
+        acc_read_block<vb>(o, std::make_integer_sequence<int, 16>{});
 #pragma unroll
-      for (int qd = 0; qd < 4; ++qd) {
-        floatx4 ov = floatx4{o[4 * qd] * inv, o[4 * qd + 1] * inv, o[4 * qd + 2] * inv, o[4 * qd + 3] * inv};
+        for (int qd = 0; qd < 4; ++qd) {
+          floatx4 ov = floatx4{o[4 * qd] * inv, o[4 * qd + 1] * inv, o[4 * qd + 2] * inv, o[4 * qd + 3] * inv};
+          amax = fmaxf(fmaxf(amax, fmaxf(fabsf(ov[0]), fabsf(ov[1]))), fmaxf(fabsf(ov[2]), fabsf(ov[3])));
 #pragma unroll
-        for (int i = 0; i < 4; ++i) ov[i] = __builtin_amdgcn_fmed3f(ov[i], -65504.f, 65504.f);   // an average of entry values: saturate, never inf
-        *reinterpret_cast<halfx4*>(orow + (vb * 32 + 8 * qd) * 2) = __builtin_convertvector(ov, halfx4);   // round to nearest even
-      }
+          for (int i = 0; i < 4; ++i) ov[i] = __builtin_amdgcn_fmed3f(ov[i], -65504.f, 65504.f);   // never inf in the fp16 image
+          *reinterpret_cast<halfx4*>(orow + (vb * 32 + 8 * qd) * 2) = __builtin_convertvector(ov, halfx4);   // round to nearest even
+        }
+      };
+      [&]<int... V>(std::integer_sequence<int, V...>) { (stage_block(std::integral_constant<int, V>{}), ...); }
+      (std::make_integer_sequence<int, VB32>{});
     };
-    [&]<int... V>(std::integer_sequence<int, V...>) { (stage_block(std::integral_constant<int, V>{}), ...); }
-    (std::make_integer_sequence<int, VB32>{});
+    stage_rows();
+    amax = pair_max(amax);
+    if (__any(amax >= 32768.f)) {
+      int ex = 0;
+      (void)frexpf(amax, &ex);                       // amax < 2^ex
+      down = (amax >= 32768.f && amax <= 3.0e38f) ? ldexpf(1.f, ex - 15) : 1.f;
+      inv = inv / down;
+      stage_rows();
+    }
     agpr_release(hold);                              // the accumulators are read out: the AGPRs are the compiler's again
     __syncthreads();
     // a wave writes its own 32 rows, 1 KiB per instruction
@@ -671,7 +687,8 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
       const uint2 lo = src[0], hi = src[1];
       *reinterpret_cast<uint4*>(reinterpret_cast<uint8_t*>(obase + (size_t)r * ESS_LATENT_DIM) + lane2 * 16) = make_uint4(lo.x, lo.y, hi.x, hi.y);
     }
-    if (head < H && hh2 == 0) lse_part[prow] = l_tot > 0.f ? (m_ref + log2f(l_tot)) * kLn2 : -__builtin_inff();
+    if (head < H && hh2 == 0)
+      *reinterpret_cast<float2*>(lse_part + 2 * prow) = make_float2(l_tot > 0.f ? (m_ref + log2f(l_tot)) * kLn2 : -__builtin_inff(), down);
   }
   }
 }
@@ -703,11 +720,13 @@ __global__ __launch_bounds__(256) void k_attn_merge(const _Float16* __restrict__
   const size_t base = ((size_t)bt * ESS_MAX_SPLITS) * H + h;
   // the split weights first (one small load each, kept in registers), then only the partial results
   // of splits that hold something: a miss list usually fills one of its splits and leaves the rest empty
-  float lsv[ESS_MAX_SPLITS];
+  float lsv[ESS_MAX_SPLITS], up[ESS_MAX_SPLITS];     // up: the power of two a split's fp16 values were divided by
   float mx = -__builtin_inff();
 #pragma unroll
   for (int s = 0; s < ESS_MAX_SPLITS; ++s) {
-    lsv[s] = s < nsplit ? lse_part[base + (size_t)s * H] : -__builtin_inff();
+    const float2 lu = s < nsplit ? *reinterpret_cast<const float2*>(lse_part + 2 * (base + (size_t)s * H)) : make_float2(-__builtin_inff(), 1.f);
+    lsv[s] = lu.x;
+    up[s] = lu.y;
     mx = fmaxf(mx, lsv[s]);
   }
   float den = 0.f;
@@ -728,8 +747,9 @@ __global__ __launch_bounds__(256) void k_attn_merge(const _Float16* __restrict__
         if (lsv[s0 + u] == -__builtin_inff()) continue;
         const float wgt = __expf(lsv[s0 + u] - mx);
         den += wgt;
+        const float wu = wgt * up[s0 + u];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) a[i] += wgt * (float)xy[u][i];
+        for (int i = 0; i < 8; ++i) a[i] += wu * (float)xy[u][i];
       }
     }
   }
@@ -771,7 +791,7 @@ int ess_launch_attn_partial(ess_ctx* ctx, const void* q, const uint8_t* slot_poo
   const uint16_t* qq = static_cast<const uint16_t*>(q);
   // partial results of sequence b0 onward
   _Float16* op = reinterpret_cast<_Float16*>(ctx->o_part) + (size_t)b0 * T * ESS_MAX_SPLITS * c.attn_heads * ESS_LATENT_DIM;
-  float* lp = ctx->lse_part + (size_t)b0 * T * ESS_MAX_SPLITS * c.attn_heads;
+  float* lp = ctx->lse_part + (size_t)b0 * T * ESS_MAX_SPLITS * c.attn_heads * 2;
 #define ESS_ATTN_LAUNCH(FMT, DYN)                                                                                      \
   hipLaunchKernelGGL((k_attn_partial_tr<FMT, DYN>), grid, dim3(NTH), tr_lds_bytes(FMT), st, qq, slot_pool, list, n_list, T, \
                      c.attn_heads, c.topk, c.slots_per_seq, c.row_stride, sc, split0, nsplit, op, lp, ctx->zero_row, xcd,  \
@@ -795,7 +815,7 @@ int ess_launch_attn_merge(ess_ctx* ctx, int B, int T, int nsplit_total, void* ou
   const size_t r0 = (size_t)b0 * T * H;                       // first (bt, h) row of the sub-batch
   hipLaunchKernelGGL(k_attn_merge, dim3((rows + 3) / 4), dim3(256), 0, st,
                      reinterpret_cast<const _Float16*>(ctx->o_part) + r0 * ESS_MAX_SPLITS * ESS_LATENT_DIM,
-                     ctx->lse_part + r0 * ESS_MAX_SPLITS, H, nsplit_total, rows,
+                     ctx->lse_part + r0 * ESS_MAX_SPLITS * 2, H, nsplit_total, rows,
                      static_cast<uint16_t*>(out_bf16) + r0 * ESS_LATENT_DIM, lse ? lse + r0 : nullptr, zero_cnt, n_zero, chk);
   ESS_HIP(hipGetLastError());
   return ESS_OK;

@@ -281,30 +281,45 @@ def test_sparse_mla_decode_vs_oracle(ess_lib, name, B, T, H, L, k, fmt, scale):
     ctx.close()
 
 
-def test_sparse_mla_large_values_saturate(ess_lib):
-    """Entry values beyond the fp16 range: the intermediate results saturate at +-65504 (documented limit),
-    the output stays finite; values inside the range are not affected by the clamp."""
+def test_sparse_mla_large_values_keep_their_magnitude(ess_lib):
+    """Entry values far beyond the fp16 range.  The partial results travel as fp16; a head whose largest value
+    reaches 2^15 is divided by the power of two that brings it below 2^15, and the merge multiplies it back: nothing
+    saturates.  With all logits equal the output is the plain average of identical entries, i.e. the entry itself,
+    exactly (a bf16 value has 8 significant bits, fp16 keeps 11, every scaling is by a power of two) for every value
+    within 2^29 of the head's largest one; what lies further below it is flushed towards zero."""
     print("sparse_mla large values", flush=True)
     B, T, H, L, k = 1, 1, 128, 256, 64
-    vals = {0: 3.0e5, 1: -3.0e5, 2: 6.0e4}                     # value columns 0, 1: out of range; column 2: inside
-    rows = torch.zeros((B, L, 576), dtype=torch.bfloat16)
-    for col, v in vals.items():
-        rows[..., col] = v
-    pool = rows.view(torch.uint8).reshape(B, L, 1152)
-    q = torch.zeros((B, T, H, 576), dtype=torch.bfloat16)        # all logits 0: the output is the plain average
     idx = np.arange(k, dtype=np.int32).reshape(B, T, k)
-    ctx = _ctx(ess_lib, max_batch=B, max_q_tokens=T, max_ctx=L, idx_heads=4, idx_dim=32, topk=k, attn_heads=H)
-    out = torch.full((B, T, H, 512), 9.0, dtype=torch.bfloat16, device="cuda")
-    lse = torch.full((B, T, H), 9.0, dtype=torch.float32, device="cuda")
-    ctx.sparse_mla_decode(q.cuda(), pool.cuda(), torch.from_numpy(idx).cuda(), out, lse)
-    torch.cuda.synchronize()
-    o = out.float().cpu().numpy()
-    assert np.all(np.isfinite(o))
-    assert np.all(o[..., 0] == 65536.0) and np.all(o[..., 1] == -65536.0)      # bf16 image of +-65504
-    assert np.all(np.abs(o[..., 2] - 6.0e4) <= 6.0e4 * 2.0 ** -8)
-    assert np.all(o[..., 3:] == 0.0)
-    assert np.allclose(lse.cpu().numpy(), np.log(k), atol=1e-4)
-    ctx.close()
+    q = torch.zeros((B, T, H, 576), dtype=torch.bfloat16)        # all logits 0: the output is the plain average
+    cases = [
+        # values beyond fp16 beside ordinary ones: the head's scale is 2^10, every column stays a normal fp16 number
+        ({0: 3.0e5, 1: -3.0e5, 2: 6.0e4, 3: 2.5e7, 5: 0.5}, [0, 1, 2, 3, 5], []),
+        # near the top of the bf16 range: scale 2^85; 9.5e23 is 2^20 below the largest value and exact, 3.0e5 is
+        # 2^81 below it and comes out as zero
+        ({0: 1.0e30, 1: -7.5e29, 2: 9.5e23, 3: 3.0e5}, [0, 1, 2], [3]),
+        # ordinary values: no scale, small values keep fp16's full range
+        ({0: 100.0, 1: -3.0e4, 5: 1.5e-3}, [0, 1, 5], []),
+    ]
+    for vals, exact, flushed in cases:
+        rows = torch.zeros((B, L, 576), dtype=torch.bfloat16)
+        for col, v in vals.items():
+            rows[..., col] = v
+        pool = rows.view(torch.uint8).reshape(B, L, 1152)
+        ctx = _ctx(ess_lib, max_batch=B, max_q_tokens=T, max_ctx=L, idx_heads=4, idx_dim=32, topk=k, attn_heads=H)
+        out = torch.full((B, T, H, 512), 9.0, dtype=torch.bfloat16, device="cuda")
+        lse = torch.full((B, T, H), 9.0, dtype=torch.float32, device="cuda")
+        ctx.sparse_mla_decode(q.cuda(), pool.cuda(), torch.from_numpy(idx).cuda(), out, lse)
+        torch.cuda.synchronize()
+        o = out.float().cpu().numpy()
+        want = rows[0, 0, :512].float().numpy()
+        assert np.all(np.isfinite(o))
+        assert np.array_equal(o[0, 0][:, exact], np.broadcast_to(want[exact], (H, len(exact)))), (vals, o[0, 0, 0, :6])
+        rest = [c for c in range(512) if c not in exact]
+        assert np.all(o[0, 0][:, rest] == 0.0), (vals, flushed)
+        ref_out, ref_lse = O.sparse_mla(_qbits(q), pool.numpy(), idx, O.FMT_BF16, 576 ** -0.5)
+        assert np.allclose(o[0, 0][:, exact], ref_out[0, 0][:, exact], rtol=2.0 ** -8)
+        assert np.allclose(lse.cpu().numpy(), np.log(k), atol=1e-4)
+        ctx.close()
 
 
 # ---------------------------------------------------------------- whole step
