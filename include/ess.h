@@ -68,6 +68,9 @@ typedef enum {
                               counts of the previous step (the paper's switch on the number of misses, Sec. 3.3);
                               threshold: ess_set_overlap_threshold.  Ignored with ESS_FLAG_SERIAL. */
 
+#define ESS_FLAG_DENSE_SCORES 8u /* ess_decode_step computes stages 1 and 2 as ess_index_score + ess_topk do, through a full
+                              score array, instead of as ess_index_topk does.  Same result, slower. */
+
 typedef struct ess_ctx ess_ctx;
 
 /* Fixed for the life of a context. */
@@ -171,6 +174,19 @@ int ess_index_score_paged(ess_ctx* ctx, const uint8_t* q_idx_fp8, const float* w
  * ascending position order, then -1.  NaN ranks as -inf; +0 and -0 are equal. */
 int ess_topk(ess_ctx* ctx, const float* score, const int32_t* ctx_len, int32_t B, int32_t T,
              int32_t* idx, void* stream);
+
+/* Stages 1 and 2 as one: idx as ess_topk gives it for the scores ess_index_score (block_table NULL, key_fp8
+ * [B,Lmax,Di]) or ess_index_score_paged (block_table given, key_fp8 = the page pool) would give -- the same bits --
+ * without the score array (Sec. 3: only the top-k positions leave the indexer).  This is what ess_decode_step
+ * runs.  Four launches: the scores of a sample of each sequence's keys (one block of 64 in every 2048) give, per
+ * row (b,t), a lower bound that very probably leaves at least k and at most a few thousand scores at or above it;
+ * the main pass over all keys computes every score and keeps only (position, score) of those that reach the bound;
+ * the selection is finished among them, exactly.  A row whose candidates number fewer than k or more than 8192
+ * (a misleading sample, massive ties at the bound) is recomputed from all its scores by one workgroup: correct, but
+ * slow (about 0.2 ms for a row of 128K keys). */
+int ess_index_topk(ess_ctx* ctx, const uint8_t* q_idx_fp8, const float* w, const uint8_t* key_fp8,
+                   const int32_t* block_table, int32_t n_pages, const int32_t* ctx_len, int32_t B, int32_t T,
+                   int32_t* idx, void* stream);
 
 /* ess_topk for callers that cannot allocate device memory and therefore cannot create a context: code under
  * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same result as ess_topk for

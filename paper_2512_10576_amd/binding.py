@@ -23,6 +23,7 @@ ESS_FMT_BF16, ESS_FMT_FP8 = 0, 1
 ESS_FLAG_SERIAL = 1
 ESS_FLAG_DBA = 2
 ESS_FLAG_AUTO = 4
+ESS_FLAG_DENSE_SCORES = 8
 
 
 class EssConfig(C.Structure):
@@ -88,6 +89,7 @@ def load() -> C.CDLL:
         "ess_calib_read": [vp, C.c_size_t, vp, vp],
         "ess_append": [vp, C.POINTER(EssCache), vp, vp, vp, vp, i32, i32, u32, vp, vp, vp, i32, vp],
         "ess_index_score_paged": [vp, vp, vp, vp, vp, i32, vp, i32, i32, vp, vp],
+        "ess_index_topk": [vp, vp, vp, vp, vp, i32, vp, i32, i32, vp, vp],
         "ess_set_overlap_threshold": [vp, i32],
         "ess_last_overlap": [vp, C.POINTER(i32)],
         "ess_last_confined": [vp, C.POINTER(i32)],
@@ -268,6 +270,14 @@ class Context:
                                    _ptr(placed, torch.int32, optional=True),
                                    _ptr(new_key_scale, torch.float32, optional=True),
                                    _ptr(block_table, torch.int32, optional=True), n_pages, _stream()))
+
+    def index_topk(self, q_idx_fp8, w, key_fp8, ctx_len, idx, block_table=None):
+        """key_fp8: [B,Lmax,Di], or the page pool when block_table is given"""
+        B, T = q_idx_fp8.shape[:2]
+        _check(self.lib.ess_index_topk(self.h, _ptr(q_idx_fp8, torch.uint8), _ptr(w, torch.float32), _ptr(key_fp8, torch.uint8),
+                                       _ptr(block_table, torch.int32) if block_table is not None else None,
+                                       key_fp8.shape[0] if block_table is not None else 0,
+                                       _ptr(ctx_len, torch.int32), B, T, _ptr(idx, torch.int32), _stream()))
 
     def index_score_paged(self, q_idx_fp8, w, key_pages, block_table, ctx_len, score):
         B, T = q_idx_fp8.shape[:2]

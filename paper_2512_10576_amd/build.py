@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libess.so")
-SOURCES = ["ess_api.hip", "index_score.hip", "topk.hip", "cache.hip", "sparse_mla.hip"]
+SOURCES = ["ess_api.hip", "index_score.hip", "index_select.hip", "index_sample.hip", "topk.hip", "cache.hip", "sparse_mla.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-I" + os.path.join(ROOT, "include"),
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 
@@ -58,7 +58,7 @@ def build(verbose: bool = False) -> str:
         src, obj = pair
         return _run([hipcc, *compile_flags(src), "-c", os.path.join(CSRC, src), "-o", obj])
 
-    with ThreadPoolExecutor(max_workers=min(4, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(6, len(SOURCES))) as ex:
         logs = list(ex.map(one, zip(SOURCES, objs)))
     logs.append(_run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", OUT]))
     if verbose:

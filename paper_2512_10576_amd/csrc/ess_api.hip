@@ -9,7 +9,7 @@
 
 #include <new>
 
-#include "ess_internal.h"
+#include "index_tile.h"
 
 // Workgroups that Attn0 of the whole batch aims at when entries are offloaded: half a workgroup per CU.  Attn0 runs
 // beside a fetch and has time to spare, while every split adds a partial result (128 KiB per row) that the merge,
@@ -61,7 +61,7 @@ int validate_config(const ess_config* c) {
 }
 
 struct WsLayout {
-  size_t score, slot_idx, hit, miss, n_hit, n_miss, fill_tok, fill_slot, miss_cnt, o_part, lse_part, stats, zero_row, topk_cand, topk_cnt, tickets, total;
+  size_t score, slot_idx, hit, miss, n_hit, n_miss, fill_tok, fill_slot, miss_cnt, o_part, lse_part, stats, zero_row, topk_cand, topk_cnt, sel_sample, sel_tau, sel_cand, sel_cnt, tickets, total;
 };
 
 size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -86,6 +86,10 @@ WsLayout ws_layout(const ess_config& c) {
   w.zero_row = take(ESS_ZERO_ROW_BYTES);
   w.topk_cand = take(ess_topk_cand_bytes());
   w.topk_cnt = take(ESS_TOPK_SHARED_ROWS * sizeof(uint32_t));
+  w.sel_sample = take(B * T * (size_t)ess_sample_count(c.max_ctx) * 64 * 4);
+  w.sel_tau = take(B * T * 8);
+  w.sel_cand = take(B * T * (size_t)ess_sel_cand_cap() * 8);
+  w.sel_cnt = take(B * T * 4);
   w.tickets = take(ESS_N_TICKETS * ESS_TICKET_WORDS * sizeof(uint32_t));
   w.total = off;
   return w;
@@ -149,7 +153,7 @@ int run_cache_step(ess_ctx* ctx, const ess_cache& cache, const int32_t* idx, int
   // confine: the fetch runs on the XCDs of ESS_FETCH_XCD_MASK and the kernels beside it stay off them, taking their work
   // through counters that this bookkeeping clears (counter 0: the fetch itself)
   int rc = ess_launch_bookkeeping(ctx, cache, idx, B, T, kk, step, slot_idx, miss_count, st, b0, half == 0,
-                                  ess_xcd{nullptr, 0, nullptr, 0}, confine ? ctx->tickets : nullptr, 5);
+                                  ess_xcd{nullptr, 0, nullptr, 0}, confine ? ctx->tickets : nullptr, ESS_TKT_FETCH2);
   if (rc != ESS_OK) return rc;
   if (!cache.host_pool_dev) return ESS_OK;      // nothing offloaded: no entry can be missing
   if (ctx->cfg.flags & ESS_FLAG_SERIAL) {
@@ -228,6 +232,10 @@ int ess_create(const ess_config* cfg, ess_ctx** out) {
   ctx->zero_row = base + w.zero_row;
   ctx->topk_cand = reinterpret_cast<unsigned long long*>(base + w.topk_cand);
   ctx->topk_cnt = reinterpret_cast<uint32_t*>(base + w.topk_cnt);
+  ctx->sel_sample = reinterpret_cast<float*>(base + w.sel_sample);
+  ctx->sel_tau = reinterpret_cast<uint32_t*>(base + w.sel_tau);
+  ctx->sel_cand = reinterpret_cast<unsigned long long*>(base + w.sel_cand);
+  ctx->sel_cnt = reinterpret_cast<uint32_t*>(base + w.sel_cnt);
   ctx->tickets = reinterpret_cast<uint32_t*>(base + w.tickets);
   auto bail = [&](const char* what, hipError_t err) {
     for (int h = 0; h < 2; ++h) {
@@ -358,6 +366,26 @@ int ess_index_score_paged(ess_ctx* ctx, const uint8_t* q, const float* w, const 
   if ((rc = check_paged(ctx, key_pages, block_table, n_pages)) != ESS_OK) return rc;
   return ess_launch_index_score(ctx->cfg, q, w, key_pages, ctx_len, B, T, score, static_cast<hipStream_t>(stream),
                                 block_table, n_pages);
+}
+
+int ess_index_topk(ess_ctx* ctx, const uint8_t* q, const float* w, const uint8_t* key, const int32_t* block_table,
+                   int32_t n_pages, const int32_t* ctx_len, int32_t B, int32_t T, int32_t* idx, void* stream) {
+  int rc = check_bt(ctx, B, T);
+  if (rc != ESS_OK) return rc;
+  if (!q || !w || !key || !ctx_len || !idx) return ess_fail(ESS_ERR_INVALID_ARG, "NULL argument");
+  if (!aligned16(q) || !aligned16(key)) return ess_fail(ESS_ERR_INVALID_ARG, "q and key must be 16-byte aligned");
+  if (block_table && (rc = check_paged(ctx, key, block_table, n_pages)) != ESS_OK) return rc;
+  // index score and top-k as one stage without a score array (see ess_internal.h)
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const ess_config& c = ctx->cfg;
+  const ess_xcd none{nullptr, 0, nullptr, 0};
+  const int np = block_table ? n_pages : 0, cap = ess_sel_cand_cap();
+  if ((rc = ess_launch_index_sample(c, q, w, key, ctx_len, B, T, ctx->sel_sample, st, block_table, np, none)) != ESS_OK) return rc;
+  if ((rc = ess_launch_index_tau(ctx, ctx_len, B, T, 0, st, none)) != ESS_OK) return rc;
+  rc = ess_launch_index_emit(c, q, w, key, ctx_len, B, T, ctx->sel_tau, ctx->sel_cand, ctx->sel_cnt, cap, st, block_table, np,
+                             nullptr, nullptr, none);
+  if (rc != ESS_OK) return rc;
+  return ess_launch_topk_finish(ctx, q, w, key, block_table, np, ctx_len, B, T, 0, idx, st, none);
 }
 
 int ess_topk(ess_ctx* ctx, const float* score, const int32_t* ctx_len, int32_t B, int32_t T, int32_t* idx,
@@ -530,34 +558,56 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     // the index-score kernel is timed by its own start and end (events handed to the launch), not by
     // marks on the stream, which would add the dispatch gaps to the figure the roofline is taken from
     hipEvent_t ev_s = nullptr, ev_e = nullptr;
-    if (pev && (ctx->prof_mask & 1u) && nmark + 2 <= ESS_PROF_MAIN) {
-      ev_s = pev[nmark];
-      ev_e = pev[nmark + 1];
-      ptag[nmark] = -1;
-      ptag[nmark + 1] = 0;
-      nmark += 2;
-      ctx->prof_nmark[pslot] = nmark;
-      adjacent = true;
-    } else {
-      adjacent = false;
-    }
+    auto take_index_events = [&]() {
+      if (pev && (ctx->prof_mask & 1u) && nmark + 2 <= ESS_PROF_MAIN) {
+        ev_s = pev[nmark];
+        ev_e = pev[nmark + 1];
+        ptag[nmark] = -1;
+        ptag[nmark + 1] = 0;
+        nmark += 2;
+        ctx->prof_nmark[pslot] = nmark;
+        adjacent = true;
+      } else {
+        adjacent = false;
+      }
+    };
     // second half of the split-batch schedule: these kernels run beside the first fetch, which is confined
-    // to the XCDs of ESS_FETCH_XCD_MASK; they stay off those (counters 1..4, cleared by the first half's bookkeeping)
+    // to the XCDs of ESS_FETCH_XCD_MASK; they stay off those (counter blocks ESS_TKT_INDEX .. ESS_TKT_BOOK, cleared by the first half's bookkeeping)
     const bool beside = confine && h == 1;
     auto xcd_of = [&](int counter) { return beside ? tk_xcd(counter) : ess_xcd{nullptr, 0, nullptr, 0}; };
-    if (a->block_table)     // paged: one pool for the whole batch, the table rows of this sub-batch
-      rc = ess_launch_index_score(c, a->q_idx_fp8 + bt0 * c.idx_heads * c.idx_dim, a->w + bt0 * c.idx_heads, a->key_fp8,
-                                  a->ctx_len + b0, Bh, T, sc, st,
-                                  a->block_table + (size_t)b0 * (c.max_ctx / ESS_PAGE_TOKENS), a->n_pages, ev_s, ev_e, xcd_of(1));
-    else
-      rc = ess_launch_index_score(c, a->q_idx_fp8 + bt0 * c.idx_heads * c.idx_dim, a->w + bt0 * c.idx_heads,
-                                  a->key_fp8 + (size_t)b0 * c.max_ctx * c.idx_dim, a->ctx_len + b0, Bh, T, sc, st,
-                                  nullptr, 0, ev_s, ev_e, xcd_of(1));
-    if (rc != ESS_OK) return rc;
-    ESS_BEGIN(1);
-    rc = ess_launch_topk(ctx, sc, a->ctx_len + b0, Bh, T, idx_h, st, xcd_of(2));
-    if (rc != ESS_OK) return rc;
-    ESS_END(1);
+    const uint8_t* q_h = a->q_idx_fp8 + bt0 * c.idx_heads * c.idx_dim;
+    const float* w_h = a->w + bt0 * c.idx_heads;
+    // paged: one pool for the whole batch, the table rows of this sub-batch
+    const uint8_t* key_h = a->block_table ? a->key_fp8 : a->key_fp8 + (size_t)b0 * c.max_ctx * c.idx_dim;
+    const int32_t* table_h = a->block_table ? a->block_table + (size_t)b0 * (c.max_ctx / ESS_PAGE_TOKENS) : nullptr;
+    const int np_h = a->block_table ? a->n_pages : 0;
+    if (c.flags & ESS_FLAG_DENSE_SCORES) {
+      take_index_events();
+      rc = ess_launch_index_score(c, q_h, w_h, key_h, a->ctx_len + b0, Bh, T, sc, st, table_h, np_h, ev_s, ev_e, xcd_of(ESS_TKT_INDEX));
+      if (rc != ESS_OK) return rc;
+      ESS_BEGIN(1);
+      rc = ess_launch_topk(ctx, sc, a->ctx_len + b0, Bh, T, idx_h, st, xcd_of(ESS_TKT_SAMPLE));
+      if (rc != ESS_OK) return rc;
+      ESS_END(1);
+    } else {
+      // index score and top-k as one stage without a score array (see ess_internal.h); the two small launches in
+      // front of the emitting pass are booked with the top-k, whose threshold search they are
+      const size_t pitch = (size_t)ess_sample_count(c.max_ctx) * 64, cap = (size_t)ess_sel_cand_cap();
+      ESS_BEGIN(1);
+      rc = ess_launch_index_sample(c, q_h, w_h, key_h, a->ctx_len + b0, Bh, T, ctx->sel_sample + bt0 * pitch, st, table_h, np_h,
+                                   xcd_of(ESS_TKT_SAMPLE));
+      if (rc != ESS_OK) return rc;
+      if ((rc = ess_launch_index_tau(ctx, a->ctx_len + b0, Bh, T, b0, st, xcd_of(ESS_TKT_TAU))) != ESS_OK) return rc;
+      ESS_END(1);
+      take_index_events();
+      rc = ess_launch_index_emit(c, q_h, w_h, key_h, a->ctx_len + b0, Bh, T, ctx->sel_tau + 2 * bt0, ctx->sel_cand + bt0 * cap,
+                                 ctx->sel_cnt + bt0, (int)cap, st, table_h, np_h, ev_s, ev_e, xcd_of(ESS_TKT_INDEX));
+      if (rc != ESS_OK) return rc;
+      ESS_BEGIN(1);
+      rc = ess_launch_topk_finish(ctx, q_h, w_h, key_h, table_h, np_h, a->ctx_len + b0, Bh, T, b0, idx_h, st, xcd_of(ESS_TKT_FINISH));
+      if (rc != ESS_OK) return rc;
+      ESS_END(1);
+    }
     if (!offloaded) continue;
     const int32_t* used = a->topk_override ? a->topk_override + bt0 * k : idx_h;
     const ess_cache ch = shift_cache(c, *cache, b0);
@@ -565,9 +615,9 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     ESS_BEGIN(2);
     if (da_swap || (dba && h == 1)) {      // bookkeeping only; the fetch follows on this stream further down
       rc = ess_launch_bookkeeping(ctx, ch, used, Bh, T, c.topk, a->step, ctx->slot_idx_ws + bt0 * k,
-                                  a->miss_count ? a->miss_count + b0 : nullptr, st, b0, h == 0, xcd_of(4),
-                                  (confine2 || (da_swap && confine_da)) ? ctx->tickets + (da_swap ? 0 : 5) * ESS_TICKET_WORDS : nullptr,
-                                  da_swap ? 8 : 3);
+                                  a->miss_count ? a->miss_count + b0 : nullptr, st, b0, h == 0, xcd_of(ESS_TKT_BOOK),
+                                  (confine2 || (da_swap && confine_da)) ? ctx->tickets + (da_swap ? 0 : ESS_TKT_FETCH2) * ESS_TICKET_WORDS : nullptr,
+                                  da_swap ? ESS_N_TICKETS : ESS_N_TICKETS - ESS_TKT_FETCH2);
       if (rc != ESS_OK) return rc;
     } else {
       rc = run_cache_step(ctx, ch, used, Bh, T, c.topk, a->step, ctx->slot_idx_ws + bt0 * k,
@@ -604,7 +654,7 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     hipEvent_t* aev = (pev && ((ctx->prof_mask >> 3) & 1u)) ? pev + ESS_PROF_MAIN : nullptr;
     if (aev) ESS_HIP(hipEventRecord(aev[0], ctx->side));
     rc = ess_launch_attn_partial(ctx, q16, cache->slot_pool, ctx->hit_list, ctx->n_hit, B, T, 0, ns0, ctx->side, 0,
-                                 confine_da ? tk_xcd(6) : ess_xcd{nullptr, 0, nullptr, 0});
+                                 confine_da ? tk_xcd(ESS_TKT_ATTN0) : ess_xcd{nullptr, 0, nullptr, 0});
     if (rc != ESS_OK) return rc;
     if (aev) {
       ESS_HIP(hipEventRecord(aev[1], ctx->side));
@@ -620,7 +670,7 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     ESS_HIP(hipStreamWaitEvent(st, ctx->ev_fill[0], 0));
     rc = ess_launch_attn_partial(ctx, q16, cache->slot_pool, ctx->miss_list, ctx->n_miss, B, T, ns0, ns1, st, 0);
     if (rc != ESS_OK) return rc;
-    chk.need[6] += check_extra;
+    chk.need[ESS_TKT_ATTN0] += check_extra;
     rc = ess_launch_attn_merge(ctx, B, T, ns0 + ns1, a->out_bf16, a->lse, st, nullptr, 0, 0, confine_da ? &chk : nullptr);
     if (rc != ESS_OK) return rc;
     ESS_END(4);
@@ -638,7 +688,7 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     const size_t bt1 = (size_t)hb0[1] * T;
     ESS_HIP(hipEventRecord(ctx->ev_book[1], st));                    // second half's bookkeeping done
     ESS_BEGIN(5);
-    rc = confine2 ? ess_launch_fill(ctx, c1, hB[1], st, hb0[1], wgs2, mask2, ctx->tickets + 5 * ESS_TICKET_WORDS)
+    rc = confine2 ? ess_launch_fill(ctx, c1, hB[1], st, hb0[1], wgs2, mask2, ctx->tickets + ESS_TKT_FETCH2 * ESS_TICKET_WORDS)
                   : ess_launch_fill(ctx, c1, hB[1], st, hb0[1], 28);
     if (rc != ESS_OK) return rc;
     ESS_END(5);
@@ -649,14 +699,14 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     // Attn0 of the whole batch in one launch (behind the first fetch it could not start much earlier
     // anyway): one workgroup per CU, the same splits as in the other schedules
     rc = ess_launch_attn_partial(ctx, q16, cache->slot_pool, ctx->hit_list, ctx->n_hit, B, T, 0, ns0, ctx->side, 0,
-                                 confine2 ? tk_xcd(6) : ess_xcd{nullptr, 0, nullptr, 0});
+                                 confine2 ? tk_xcd(ESS_TKT_ATTN0) : ess_xcd{nullptr, 0, nullptr, 0});
     if (rc != ESS_OK) return rc;
     if (aev) {
       ESS_HIP(hipEventRecord(aev[1], ctx->side));
       ESS_HIP(hipEventRecord(aev[2], ctx->side));
     }
     rc = ess_launch_attn_partial(ctx, q16, c0.slot_pool, ctx->miss_list, ctx->n_miss, hB[0], T, ns0, ns1, ctx->side, hb0[0],
-                                 confine2 ? tk_xcd(7) : ess_xcd{nullptr, 0, nullptr, 0});
+                                 confine2 ? tk_xcd(ESS_TKT_ATTN1) : ess_xcd{nullptr, 0, nullptr, 0});
     if (rc != ESS_OK) return rc;
     // each half is merged on the stream its Attn1 ran on: only half a merge is left behind the last fetch
     rc = ess_launch_attn_merge(ctx, hB[0], T, ns0 + ns1, a->out_bf16, a->lse, ctx->side, nullptr, 0, hb0[0]);
@@ -673,7 +723,7 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
                                  ctx->n_miss + bt1, hB[1], T, ns0, ns1, st, hb0[1]);
     if (rc != ESS_OK) return rc;
     ESS_HIP(hipStreamWaitEvent(st, ctx->ev_fill[1], 0));          // Attn0 of the second half ran on the side stream
-    chk.need[1] += check_extra;
+    chk.need[ESS_TKT_INDEX] += check_extra;
     rc = ess_launch_attn_merge(ctx, hB[1], T, ns0 + ns1, a->out_bf16, a->lse, st, nullptr, 0, hb0[1], confine ? &chk : nullptr);
     if (rc != ESS_OK) return rc;
     ESS_END(4);

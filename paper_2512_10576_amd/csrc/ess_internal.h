@@ -12,7 +12,18 @@
 #define ESS_ROW_DIM 576
 #define ESS_ZERO_ROW_BYTES 2048  // >= the largest row_stride
 #define ESS_TOPK_SHARED_ROWS 128 // rows (b,t) up to which a top-k row is shared by several workgroups
-#define ESS_N_TICKETS 8         // ticket-fed launches of one step
+#define ESS_N_TICKETS 9         // ticket-fed launches of one step:
+enum {                          // which launch uses which counter block
+  ESS_TKT_FETCH1 = 0,           // the first (or only) fetch
+  ESS_TKT_INDEX = 1,            // index score (dense or emitting)
+  ESS_TKT_SAMPLE = 2,           // fused selection: sample pass; two-kernel top-k: candidate pass
+  ESS_TKT_TAU = 3,              // fused selection: lower bounds; two-kernel top-k: its finish (the block after its candidate pass)
+  ESS_TKT_FINISH = 4,           // top-k finish
+  ESS_TKT_BOOK = 5,             // bookkeeping
+  ESS_TKT_FETCH2 = 6,           // the second fetch of the split-batch schedule
+  ESS_TKT_ATTN0 = 7,
+  ESS_TKT_ATTN1 = 8
+};
 // Counters of one such launch.  They are device-scope atomics from all XCDs, which the memory side executes one
 // after the other per address range, so each counter has 256 bytes to itself: [ESS_TK_WORK] work items handed out,
 // [ESS_TK_ARRIVE] workgroups that arrived on XCDs that take no work, [ESS_TK_CLASS + 64 c] per-XCD counters of
@@ -29,7 +40,7 @@
 // four 0.631 (the index score is short of CUs), unconfined 0.631; 48 workgroups on three XCDs.
 #define ESS_FETCH_XCD_MASK 7u
 #define ESS_FETCH_CONFINED_WGS 48
-#define ESS_PROF_MAIN 16        // stage marks on the caller's stream per step
+#define ESS_PROF_MAIN 24        // stage marks on the caller's stream per step
 #define ESS_PROF_FILL 3         // event pairs per step for work off the caller's stream (fetches, side-stream attention)
 #define ESS_PROF_EVENTS (ESS_PROF_MAIN + 2 * ESS_PROF_FILL)
 
@@ -54,6 +65,11 @@ struct ess_ctx {
   uint8_t* zero_row;            // ESS_ZERO_ROW_BYTES of zeros, never written: source of masked attention rows
   unsigned long long* topk_cand; // [ESS_TOPK_SHARED_ROWS][8192] candidate keys of rows shared by several workgroups
   uint32_t* topk_cnt;           // [ESS_TOPK_SHARED_ROWS] candidates listed per row: zero between steps
+  // fused selection inside ess_decode_step / ess_index_topk (no score array): per row (b,t)
+  float* sel_sample;            // [B,T,64 * ess_sample_count(max_ctx)] scores of the sequence's sample blocks
+  uint32_t* sel_tau;            // [B,T][2] bounds of the row's selection (ess_orderable images): candidates reach [0]; the k-th largest score very probably lies below [1]
+  unsigned long long* sel_cand; // [B,T][ess_sel_cand_cap()] candidate keys
+  uint32_t* sel_cnt;            // [B,T] candidates appended
   uint32_t* tickets;            // [ESS_N_TICKETS][ESS_TICKET_WORDS] work counters of kernels that run beside a fetch (see ess_xcd)
   bool xcds_even;               // workgroups go round the eight XCDs evenly (probed at creation): confining a fetch pays
   bool book_fits;               // the bookkeeping kernel's LDS arrays fit this configuration (else the cache calls are refused)
@@ -175,7 +191,23 @@ int ess_launch_index_score(const ess_config& c, const uint8_t* q, const float* w
                            const int32_t* block_table = nullptr, int n_pages = 0,
                            // optional: events that take the kernel's own start and end times
                            hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr, ess_xcd xcd = ess_xcd{nullptr, 0, nullptr, 0});
-// xcd: ticket[0] and ticket[1] are used (two kernels)
+// The fused selection (index score + top-k without a score array) is four launches: scores of each sequence's
+// sample blocks -> sel_sample; lower bounds -> sel_tau (and sel_cnt cleared); the emitting index-score pass ->
+// sel_cand / sel_cnt; the top-k finish -> idx.  b0: first sequence of the (sub-)batch, for the context's arrays;
+// caller-owned pointers are passed already shifted.
+int ess_launch_index_sample(const ess_config& c, const uint8_t* q, const float* w, const uint8_t* key,
+                            const int32_t* ctx_len, int B, int T, float* sample, hipStream_t st,
+                            const int32_t* block_table, int n_pages, ess_xcd xcd);
+int ess_launch_index_tau(ess_ctx* ctx, const int32_t* ctx_len, int B, int T, int b0, hipStream_t st, ess_xcd xcd);
+int ess_launch_index_emit(const ess_config& c, const uint8_t* q, const float* w, const uint8_t* key,
+                          const int32_t* ctx_len, int B, int T, const uint32_t* tau, unsigned long long* cand,
+                          uint32_t* cnt, int cand_cap, hipStream_t st, const int32_t* block_table, int n_pages,
+                          hipEvent_t ev_start, hipEvent_t ev_stop, ess_xcd xcd);
+int ess_launch_topk_finish(ess_ctx* ctx, const uint8_t* q, const float* w, const uint8_t* key, const int32_t* block_table,
+                           int n_pages, const int32_t* ctx_len, int B, int T, int b0, int32_t* idx, hipStream_t st,
+                           ess_xcd xcd);
+int ess_sel_cand_cap();
+// xcd: its counter block and the next one are used (two kernels)
 int ess_launch_topk(ess_ctx* ctx, const float* score, const int32_t* ctx_len, int B, int T, int32_t* idx,
                     hipStream_t st, ess_xcd xcd = ess_xcd{nullptr, 0, nullptr, 0});
 size_t ess_topk_cand_bytes();

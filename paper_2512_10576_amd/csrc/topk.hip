@@ -23,7 +23,8 @@
 //      and deterministic.
 // Row passes keep four 16-byte loads per thread in flight; a workgroup that
 // issued one load per thread and round would crawl at memory latency.
-#include "ess_internal.h"
+#include "index_tile.h"
+#include "select_common.h"
 #include <mutex>
 
 namespace {
@@ -32,17 +33,16 @@ constexpr int NT = 1024;
 constexpr int HBITS = 11;
 constexpr int NBINS = 1 << HBITS;
 constexpr int COPIES = 8;
-constexpr int CAND_CAP = 8192;
-
-constexpr int SBITS = 14;                  // sample histogram: top 14 bits of the orderable key
-constexpr int SBINS = 1 << SBITS;
+using ess_sel::CAND_CAP;
+using ess_sel::SBITS;
+using ess_sel::SBINS;
 constexpr int SAMPLE_TARGET = 4096;         // about this many samples per row, at least every 16th score
 constexpr int FAST_MIN_VIS = 16384;
 
 struct __align__(16) TopkShared {
   union {
     uint32_t hist[NBINS * COPIES];        // 64 KiB
-    uint32_t shist[SBINS];                // 64 KiB
+    uint32_t shist[ess_sel::sample_words<NT>()];   // 68 KiB, bins placed by sample_slot
     unsigned long long cand[CAND_CAP];    // 64 KiB
   };
   int32_t out_list[ESS_MAX_TOPK];         // 16 KiB
@@ -51,40 +51,14 @@ struct __align__(16) TopkShared {
   unsigned long long red_and[NT / 64], red_or[NT / 64];
   uint32_t out_n, cand_n;
   uint32_t sel_digit, sel_above, sel_count;
+  uint32_t sbin[2];                       // sample_bins' result words
 };
 
-__device__ __forceinline__ uint32_t orderable(float v) {
-  if (v != v) v = -__builtin_inff();      // NaN ranks as -inf
-  v += 0.0f;                              // -0 -> +0
-  const uint32_t u = __float_as_uint(v);
-  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
+__device__ __forceinline__ uint32_t orderable(float v) { return ess_orderable(v); }
 
-__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v, int lane) {
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    const uint32_t o = __shfl_up(v, d, 64);
-    if (lane >= d) v += o;
-  }
-  return v;
-}
-
-// inclusive scan over the NT threads in thread order; *total gets the sum
+using ess_sel::wave_incl_scan;
 __device__ __forceinline__ uint32_t block_incl_scan(uint32_t v, uint32_t* wave_tot, uint32_t* total) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const uint32_t inc = wave_incl_scan(v, lane);
-  __syncthreads();                         // wave_tot may still be read from a previous call
-  if (lane == 63) wave_tot[wave] = inc;
-  __syncthreads();
-  uint32_t off = 0, tot = 0;
-#pragma unroll
-  for (int i = 0; i < NT / 64; ++i) {
-    const uint32_t x = wave_tot[i];
-    if (i < wave) off += x;
-    tot += x;
-  }
-  *total = tot;
-  return inc + off;
+  return ess_sel::block_incl_scan<NT>(v, wave_tot, total);
 }
 
 // append `val` for lanes with pred, one LDS atomic per wave; entries past `cap` are counted, not stored
@@ -190,6 +164,117 @@ __device__ __forceinline__ void scan_row_rounds(const float* __restrict__ srow, 
   }
 }
 
+// D, second half: the positions marked in the bitmap bmp[0..W), in ascending order, to orow[0..k)
+__device__ __forceinline__ void emit_bitmap(TopkShared& sm, const uint32_t* bmp, int W, int k, int32_t* __restrict__ orow) {
+  const int tid = threadIdx.x;
+  const int wpt = (W + NT - 1) / NT;
+  const int w0 = min(tid * wpt, W), w1 = min(w0 + wpt, W);
+  uint32_t mine = 0;
+  for (int wd = w0; wd < w1; ++wd) mine += __popc(bmp[wd]);
+  uint32_t total;
+  uint32_t outp = block_incl_scan(mine, sm.wave_tot, &total) - mine;
+  for (int wd = w0; wd < w1; ++wd) {
+    uint32_t bits = bmp[wd];
+    while (bits) {
+      const int bit = __ffs(bits) - 1;
+      bits &= bits - 1;
+      if (outp < (uint32_t)k) orow[outp] = wd * 32 + bit;
+      ++outp;
+    }
+  }
+}
+
+// Which of the 2048 digits the radix select's histogram sm.lhist holds contains the need-th largest key, counted
+// from the top: sm.sel_digit, with sm.sel_above keys above it and sm.sel_count in it.  Ends with a barrier.
+__device__ __forceinline__ void crossing_digit(TopkShared& sm, uint32_t need) {
+  const int tid = threadIdx.x;
+  const int d_hi = NBINS - 1 - 2 * tid, d_lo = d_hi - 1;      // thread tid owns two digits, descending
+  const uint32_t c_hi = sm.lhist[d_hi], c_lo = sm.lhist[d_lo];
+  uint32_t total;
+  const uint32_t inc = block_incl_scan(c_hi + c_lo, sm.wave_tot, &total);
+  const uint32_t above_hi = inc - c_hi - c_lo;
+  const uint32_t above_lo = above_hi + c_hi;
+  if (above_hi < need && above_hi + c_hi >= need) {
+    sm.sel_digit = d_hi; sm.sel_above = above_hi; sm.sel_count = c_hi;
+  } else if (above_lo < need && above_lo + c_lo >= need) {
+    sm.sel_digit = d_lo; sm.sel_above = above_lo; sm.sel_count = c_lo;
+  }
+  __syncthreads();
+}
+
+// A row finished from its candidate list (`listed` keys at grow, k <= listed <= CAND_CAP) when the k-th largest
+// score very probably lies in [lo, hi) (ess_orderable images; see k_index_tau).  The keys stay in registers.  One
+// histogram pass spreads [lo, hi) over 2047 digits (whatever lies at or above hi goes into the top one), the digit
+// that holds the k-th largest key is found, and inside it -- a handful of keys -- the key is found by counting.
+// Returns false, with the keys copied to sm.cand, when that digit holds more keys than the counting step takes
+// (massive ties, or a k-th largest score outside the range): the caller goes on with the general selection.
+__device__ __forceinline__ bool finish_fast(TopkShared& sm, const unsigned long long* __restrict__ grow, uint32_t listed,
+                                            uint32_t lo, uint32_t hi, int vis, int k, int IB, int32_t* __restrict__ orow) {
+  constexpr int PER = CAND_CAP / NT;
+  constexpr uint32_t SMALL = 1024;           // keys the counting step takes: one per thread
+  const int tid = threadIdx.x;
+  const unsigned long long imask = (1ull << IB) - 1ull;
+  unsigned long long c[PER];
+#pragma unroll
+  for (int u = 0; u < PER; ++u) c[u] = (uint32_t)(u * NT + tid) < listed ? grow[u * NT + tid] : 0ull;
+  // while the keys are on their way: clear the histogram and the row's bitmap
+  uint32_t* bmp = sm.hist;
+  const int W = (vis + 31) >> 5;
+  for (int j = tid; j < W; j += NT) bmp[j] = 0;
+  for (int j = tid; j < NBINS; j += NT) sm.lhist[j] = 0;
+  if (tid == 0) sm.cand_n = 0;
+  int sh = 0;
+  while (((hi - lo) >> sh) > (uint32_t)(NBINS - 2)) ++sh;
+  auto digit = [&](unsigned long long key) -> uint32_t {
+    const uint32_t sc = (uint32_t)(key >> IB);
+    return sc >= hi ? (uint32_t)(NBINS - 1) : (sc <= lo ? 0u : min((sc - lo) >> sh, (uint32_t)(NBINS - 2)));
+  };
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < PER; ++u)
+    if ((uint32_t)(u * NT + tid) < listed) atomicAdd(&sm.lhist[digit(c[u])], 1u);
+  __syncthreads();
+  crossing_digit(sm, (uint32_t)k);
+  const uint32_t dsel = sm.sel_digit, take = (uint32_t)k - sm.sel_above, cnt = sm.sel_count;
+  unsigned long long t_in = 0ull;            // inside the digit, keys at or above this one are taken
+  if (cnt != take) {
+    if (cnt > SMALL) {
+#pragma unroll
+      for (int u = 0; u < PER; ++u)
+        if ((uint32_t)(u * NT + tid) < listed) sm.cand[u * NT + tid] = c[u];
+      if (tid == 0) sm.cand_n = listed;
+      __syncthreads();
+      return false;
+    }
+    unsigned long long* few = reinterpret_cast<unsigned long long*>(sm.out_list);     // room for 2048 keys
+#pragma unroll
+    for (int u = 0; u < PER; ++u)
+      wave_append<unsigned long long>((uint32_t)(u * NT + tid) < listed && digit(c[u]) == dsel, c[u], few, &sm.cand_n);
+    __syncthreads();
+    if ((uint32_t)tid < cnt) {
+      const unsigned long long my = few[tid];
+      uint32_t above = 0;
+      for (uint32_t i = 0; i < cnt; ++i) above += few[i] > my ? 1u : 0u;
+      if (above == take - 1u) sm.red_and[0] = my;            // keys are distinct: exactly one thread
+    }
+    __syncthreads();
+    t_in = sm.red_and[0];
+  }
+#pragma unroll
+  for (int u = 0; u < PER; ++u) {
+    if ((uint32_t)(u * NT + tid) < listed) {
+      const uint32_t d = digit(c[u]);
+      if (d > dsel || (d == dsel && c[u] >= t_in)) {
+        const uint32_t pos = (uint32_t)(imask - (c[u] & imask));
+        atomicOr(&bmp[pos >> 5], 1u << (pos & 31));
+      }
+    }
+  }
+  __syncthreads();
+  emit_bitmap(sm, bmp, W, k, orow);
+  return true;
+}
+
 // MODE 0: one workgroup does the whole row (grid: rows).
 // MODE 1 + MODE 2, for small batches of long rows: the candidate pass of path A, the only part that
 // scales with the row, is spread over `parts` workgroups per row in a kernel of its own (MODE 1, grid
@@ -199,24 +284,33 @@ __device__ __forceinline__ void scan_row_rounds(const float* __restrict__ srow, 
 // the row by itself like MODE 0.  The hand-over is the kernel boundary: workgroups of one kernel
 // never exchange data (an agent-scope fence inside a kernel costs tens of microseconds on this
 // multi-die part, where it writes the L2 back).  g_cnt is zero between steps: MODE 2 clears it.
+// MODE 3: the finishing kernel of the fused selection (grid rows).  The row's list was written by the emitting
+// index-score pass (index_kernel.h), for rows of any length; `score` is scratch memory, not scores: a row whose list
+// cannot be used (fewer than k or more than the buffer holds: a misleading sample, massive ties) has its scores
+// computed here, by this workgroup, into its row of `score`, and is then done like MODE 0.
 // one work item = (part, row) of k_topk<MODE>; every field of `sm` is set before it is read, so items may follow each other
+struct TopkRecompute {                     // MODE 3: what it takes to compute a row's scores
+  const uint8_t* q; const float* w; const uint8_t* key; const int32_t* block_table;
+  int n_pages, Hi, Di;
+  const uint32_t* tau;                     // [rows][2] the rows' bounds (see k_index_tau), shifted like the other row arrays
+};
 template <int MODE>
-__device__ __forceinline__ void topk_item(TopkShared& sm, int item, int parts, const float* __restrict__ score,
+__device__ __forceinline__ void topk_item(TopkShared& sm, int item, int parts, float* __restrict__ score,
                                           const int32_t* __restrict__ ctx_len, int T, int Lmax, int k, int IB,
                                           int32_t* __restrict__ idx_out, unsigned long long* __restrict__ g_cand,
-                                          uint32_t* __restrict__ g_cnt) {
+                                          uint32_t* __restrict__ g_cnt, const TopkRecompute& rc) {
   const int row = item / parts;
   const int part = item % parts;
   const int b = row / T, t = row % T;
   const int tid = threadIdx.x, lane = tid & 63;
   int vis = ctx_len[b] - (T - 1 - t);
   vis = max(0, min(vis, Lmax));
-  const float* srow = score + (size_t)row * Lmax;
+  float* srow = score + (size_t)row * Lmax;
   int32_t* orow = idx_out + (size_t)row * k;
 
   if (MODE == 1 && (vis <= k || vis < FAST_MIN_VIS)) return;      // nothing to prepare
   uint32_t listed = 0;
-  if (MODE == 2) {                         // candidates prepared by the MODE 1 kernel (0 if none)
+  if (MODE >= 2) {                         // candidates prepared by the kernel in front (0 if none)
     listed = g_cnt[row];
     __syncthreads();
     if (tid == 0) g_cnt[row] = 0;
@@ -242,14 +336,34 @@ __device__ __forceinline__ void topk_item(TopkShared& sm, int item, int parts, c
   int nc = 0;
 
   // ---- A: sampled one-pass collection for long rows
-  const bool use_list = MODE == 2 && listed >= (uint32_t)k && listed <= (uint32_t)CAND_CAP;
+  const bool use_list = MODE >= 2 && listed >= (uint32_t)k && listed <= (uint32_t)CAND_CAP;
+  if (MODE == 3 && !use_list) {
+    const uint8_t* q_row = rc.q + (size_t)row * rc.Hi * rc.Di;
+    const float* w_row = rc.w + (size_t)row * rc.Hi;
+    const int32_t* table_row = rc.block_table ? rc.block_table + (size_t)b * (Lmax / ESS_PAGE_TOKENS) : nullptr;
+    const uint8_t* keys = rc.block_table ? rc.key : rc.key + (size_t)b * Lmax * rc.Di;
+    if (rc.Di == 128) ess_idx::row_scores_slow<128>(q_row, w_row, rc.Hi, keys, Lmax, table_row, rc.n_pages, vis, srow);
+    else if (rc.Di == 64) ess_idx::row_scores_slow<64>(q_row, w_row, rc.Hi, keys, Lmax, table_row, rc.n_pages, vis, srow);
+    else ess_idx::row_scores_slow<32>(q_row, w_row, rc.Hi, keys, Lmax, table_row, rc.n_pages, vis, srow);
+    __syncthreads();                       // the scores are read back by other threads of this workgroup
+  }
   if (use_list) {
     const unsigned long long* grow = g_cand + (size_t)row * CAND_CAP;
-    for (int j = tid; j < (int)listed; j += NT) sm.cand[j] = grow[j];
-    if (tid == 0) sm.cand_n = listed;
-    __syncthreads();
+    bool copied = false;
+    if (MODE == 3) {
+      const uint32_t lo = rc.tau[2 * row], hi = rc.tau[2 * row + 1];
+      if (lo != 0u && hi > lo) {
+        if (finish_fast(sm, grow, listed, lo, hi, vis, k, IB, orow)) return;
+        copied = true;
+      }
+    }
+    if (!copied) {
+      for (int j = tid; j < (int)listed; j += NT) sm.cand[j] = grow[j];
+      if (tid == 0) sm.cand_n = listed;
+      __syncthreads();
+    }
   }
-  if (vis >= FAST_MIN_VIS) {
+  if (vis >= FAST_MIN_VIS || use_list) {
    uint32_t lo_bin = 0;
    if (!use_list) {
     // samples: blocks of 16 consecutive scores (one 64-byte piece of a cache line), every bstride-th block,
@@ -259,8 +373,8 @@ __device__ __forceinline__ void topk_item(TopkShared& sm, int item, int parts, c
     int bstride = 1;
     while (nblk_all / bstride > SAMPLE_TARGET / 16) bstride <<= 1;
     const int ns = (nblk_all / bstride) << 4;
-    for (int j = tid; j < SBINS; j += NT) sm.shist[j] = 0;
-    if (tid == 0) { sm.cand_n = 0; sm.sel_digit = 0xffffffffu; }
+    for (int j = tid; j < ess_sel::sample_words<NT>(); j += NT) sm.shist[j] = 0;
+    if (tid == 0) { sm.cand_n = 0; sm.sbin[0] = sm.sbin[1] = 0xffffffffu; }
     __syncthreads();
     for (int j0 = 0; j0 < ns; j0 += 4 * NT) {
       float sv[4];
@@ -271,29 +385,11 @@ __device__ __forceinline__ void topk_item(TopkShared& sm, int item, int parts, c
       }
 #pragma unroll
       for (int u = 0; u < 4; ++u)
-        if (j0 + u * NT + tid < ns) atomicAdd(&sm.shist[orderable(sv[u]) >> (32 - SBITS)], 1u);
+        if (j0 + u * NT + tid < ns) atomicAdd(&sm.shist[ess_sel::sample_slot<NT>(orderable(sv[u]) >> (32 - SBITS))], 1u);
     }
     __syncthreads();
-    // expected number of samples above the k-th largest score, plus a margin of about 4 sigma
-    const float expct = (float)k * (float)ns / (float)vis;
-    const uint32_t target = (uint32_t)(expct + 4.0f * sqrtf(expct) + 8.0f);
-    constexpr int BPT = SBINS / NT;          // bins per thread, descending
-    const int top_bin = SBINS - 1 - tid * BPT;
-    uint32_t mine = 0;
-#pragma unroll
-    for (int r = 0; r < BPT; ++r) mine += sm.shist[top_bin - r];
-    uint32_t total;
-    const uint32_t inc = block_incl_scan(mine, sm.wave_tot, &total);
-    uint32_t above = inc - mine;
-    if (above < target && inc >= target) {    // the crossing bin is one of mine
-      for (int r = 0; r < BPT; ++r) {
-        above += sm.shist[top_bin - r];
-        if (above >= target) { sm.sel_digit = (uint32_t)(top_bin - r); break; }
-      }
-    }
-    __syncthreads();
-    lo_bin = sm.sel_digit;
-    __syncthreads();                          // shist is dead from here: cand may overwrite it
+    uint32_t hi_unused;
+    ess_sel::sample_bins<NT>(sm.shist, sm.wave_tot, sm.sbin, k, ns, vis, &lo_bin, &hi_unused);      // (ends with a barrier: shist is dead from here, cand may overwrite it)
    }
     if (MODE == 1 && lo_bin == 0xffffffffu) return;   // no usable threshold: the finishing kernel takes path B
     if (use_list || lo_bin != 0xffffffffu) {
@@ -427,18 +523,7 @@ __device__ __forceinline__ void topk_item(TopkShared& sm, int item, int parts, c
       if ((c >> rem) == prefix) atomicAdd(&sm.lhist[((uint32_t)(c >> shift)) & dmask], 1u);
     }
     __syncthreads();
-    const int d_hi = NBINS - 1 - 2 * tid, d_lo = d_hi - 1;
-    const uint32_t c_hi = sm.lhist[d_hi], c_lo = sm.lhist[d_lo];
-    uint32_t total;
-    const uint32_t inc = block_incl_scan(c_hi + c_lo, sm.wave_tot, &total);
-    const uint32_t above_hi = inc - c_hi - c_lo;
-    const uint32_t above_lo = above_hi + c_hi;
-    if (above_hi < need && above_hi + c_hi >= need) {
-      sm.sel_digit = d_hi; sm.sel_above = above_hi; sm.sel_count = c_hi;
-    } else if (above_lo < need && above_lo + c_lo >= need) {
-      sm.sel_digit = d_lo; sm.sel_above = above_lo; sm.sel_count = c_lo;
-    }
-    __syncthreads();
+    crossing_digit(sm, need);
     need -= sm.sel_above;
     prefix = (prefix << bits) | sm.sel_digit;
     const uint32_t cnt = sm.sel_count;
@@ -475,34 +560,79 @@ __device__ __forceinline__ void topk_item(TopkShared& sm, int item, int parts, c
     });
   }
   __syncthreads();
-  const int wpt = (W + NT - 1) / NT;
-  const int w0 = min(tid * wpt, W), w1 = min(w0 + wpt, W);
-  uint32_t mine = 0;
-  for (int wd = w0; wd < w1; ++wd) mine += __popc(bmp[wd]);
-  uint32_t total;
-  uint32_t outp = block_incl_scan(mine, sm.wave_tot, &total) - mine;
-  for (int wd = w0; wd < w1; ++wd) {
-    uint32_t bits = bmp[wd];
-    while (bits) {
-      const int bit = __ffs(bits) - 1;
-      bits &= bits - 1;
-      if (outp < (uint32_t)k) orow[outp] = wd * 32 + bit;
-      ++outp;
-    }
-  }
+  emit_bitmap(sm, bmp, W, k, orow);
 }
 
 template <int MODE, bool DYN>
-__global__ __launch_bounds__(NT) void k_topk(const float* __restrict__ score, const int32_t* __restrict__ ctx_len,
+__global__ __launch_bounds__(NT) void k_topk(float* __restrict__ score, const int32_t* __restrict__ ctx_len,
                                              int T, int Lmax, int k, int IB, int32_t* __restrict__ idx_out,
                                              unsigned long long* __restrict__ g_cand, uint32_t* __restrict__ g_cnt,
-                                             ess_xcd xcd, int rows, int parts_arg) {
+                                             ess_xcd xcd, int rows, int parts_arg, const TopkRecompute rc) {
   __shared__ TopkShared sm;
   __shared__ int s_item;
   const int parts = MODE == 1 ? parts_arg : 1;
   // work item = (part, row): by workgroup index, or drawn from the launch's counter off the XCDs to be avoided
   ESS_WORK_LOOP(DYN, xcd, MODE == 1 ? blockIdx.y * parts + blockIdx.x : blockIdx.x, rows * parts, &s_item, item) {
-    topk_item<MODE>(sm, item, parts, score, ctx_len, T, Lmax, k, IB, idx_out, g_cand, g_cnt);
+    topk_item<MODE>(sm, item, parts, score, ctx_len, T, Lmax, k, IB, idx_out, g_cand, g_cnt, rc);
+  }
+}
+
+// The bounds of every row's selection, from the scores of the sequence's sample blocks (one workgroup per row), as
+// ess_orderable images of scores:
+// tau[row][0] = a score that very probably has at least k and at most a few thousand of the row's scores at or above
+// it; 0 (everything is a candidate) for rows that fit the candidate buffer whole or whose sample gives no bound;
+// 0xffffffff (nothing) for rows with at most k visible positions, which need no list;
+// tau[row][1] = a score that very probably has fewer than k of the row's scores at or above it (0xffffffff if the
+// sample gives none; 0 with no lower bound): the k-th largest score very probably lies between the two, which lets
+// the finishing kernel resolve that range in one pass.
+// Also clears the row's candidate counter for the pass that follows.
+template <bool DYN>
+__global__ __launch_bounds__(NT) void k_index_tau(const float* __restrict__ sample, const int32_t* __restrict__ ctx_len,
+                                                  int T, int Lmax, int k, int period, int nsamp,
+                                                  uint32_t* __restrict__ tau, uint32_t* __restrict__ g_cnt, ess_xcd xcd,
+                                                  int rows) {
+  __shared__ uint32_t shist[ess_sel::sample_words<NT>()];
+  __shared__ uint32_t wave_tot[NT / 64], sel[2];
+  __shared__ int s_item;
+  ESS_WORK_LOOP(DYN, xcd, blockIdx.x, rows, &s_item, row) {
+    const int tid = threadIdx.x;
+    const int b = row / T, t = row % T;
+    const int len = min(ctx_len[b], Lmax);
+    const int vis = max(0, len - (T - 1 - t));
+    if (tid == 0) g_cnt[row] = 0;
+    if (vis <= k || vis <= CAND_CAP) {
+      if (tid == 0) {
+        tau[2 * row] = vis <= k ? 0xffffffffu : 0u;
+        tau[2 * row + 1] = 0u;
+      }
+      continue;
+    }
+    // the blocks that count are the first nv: starts grow with the block number
+    const int lim = len - (T - 1);
+    int nv = lim / period;
+    if (nv < nsamp && ess_sample_start(nv, period) + 64 <= lim) ++nv;
+    nv = min(nv, nsamp);
+    const int ns = nv * 64;
+    // the samples are requested before the histogram is cleared: one round trip to memory, not two
+    const float* srow = sample + (size_t)row * nsamp * 64;
+    constexpr int PER = ESS_SAMPLE_BLOCKS * 64 / NT;
+    float sv[PER];
+#pragma unroll
+    for (int u = 0; u < PER; ++u) sv[u] = u * NT + tid < ns ? srow[u * NT + tid] : 0.f;
+    for (int j = tid; j < ess_sel::sample_words<NT>(); j += NT) shist[j] = 0;
+    if (tid == 0) sel[0] = sel[1] = 0xffffffffu;
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < PER; ++u)
+      if (u * NT + tid < ns) atomicAdd(&shist[ess_sel::sample_slot<NT>(orderable(sv[u]) >> (32 - SBITS))], 1u);
+    __syncthreads();
+    uint32_t lo = 0xffffffffu, hi = 0xffffffffu;
+    if (ns > 0) ess_sel::sample_bins<NT>(shist, wave_tot, sel, k, ns, vis, &lo, &hi);
+    if (tid == 0) {
+      tau[2 * row] = lo == 0xffffffffu ? 0u : lo << (32 - SBITS);
+      // scores in the bins above `hi` are very probably fewer than k; no such bin: no upper bound
+      tau[2 * row + 1] = lo == 0xffffffffu ? 0u : ((hi == 0xffffffffu || hi == SBINS - 1) ? 0xffffffffu : (hi + 1) << (32 - SBITS));
+    }
   }
 }
 
@@ -511,8 +641,10 @@ __global__ __launch_bounds__(NT) void k_topk(const float* __restrict__ score, co
 namespace {
 // Launches of one top-k call.  cand / cnt: candidate lists [ESS_TOPK_SHARED_ROWS][CAND_CAP] and their counters
 // (zero at launch, zero again afterwards), only used when rows are shared by several workgroups.
-int launch_topk(int max_ctx, int k, const float* score, const int32_t* ctx_len, int B, int T, int32_t* idx,
+int launch_topk(int max_ctx, int k, const float* score_in, const int32_t* ctx_len, int B, int T, int32_t* idx,
                 unsigned long long* cand, uint32_t* cnt, hipStream_t st, ess_xcd xcd) {
+  float* score = const_cast<float*>(score_in);          // read only in these modes
+  const TopkRecompute rc{};
   int IB = 1;
   while ((1 << IB) < max_ctx) ++IB;
   // small batches of long rows: the candidate pass goes to a kernel of its own that puts several
@@ -529,9 +661,9 @@ int launch_topk(int max_ctx, int k, const float* score, const int32_t* ctx_len, 
 #define ESS_TOPK_LAUNCH(MODE, grid, x, np)                                                                           \
   do {                                                                                                               \
     if (dyn) hipLaunchKernelGGL((k_topk<MODE, true>), grid, dim3(NT), 0, st, score, ctx_len, T, max_ctx, k, IB, idx, \
-                                cand, cnt, x, rows, np);                                                             \
+                                cand, cnt, x, rows, np, rc);                                                         \
     else hipLaunchKernelGGL((k_topk<MODE, false>), grid, dim3(NT), 0, st, score, ctx_len, T, max_ctx, k, IB, idx,    \
-                            cand, cnt, x, rows, np);                                                                 \
+                            cand, cnt, x, rows, np, rc);                                                             \
   } while (0)
   if (parts > 1) {
     const dim3 g1 = dyn ? dim3(ess_xcd_grid(parts * rows, x0)) : dim3(parts, rows);
@@ -550,6 +682,44 @@ int ess_launch_topk(ess_ctx* ctx, const float* score, const int32_t* ctx_len, in
                     hipStream_t st, ess_xcd xcd) {
   return launch_topk(ctx->cfg.max_ctx, ctx->cfg.topk, score, ctx_len, B, T, idx, ctx->topk_cand, ctx->topk_cnt, st, xcd);
 }
+
+// The two small kernels of the fused selection that live here (see ess_internal.h).
+int ess_launch_index_tau(ess_ctx* ctx, const int32_t* ctx_len, int B, int T, int b0, hipStream_t st, ess_xcd xcd) {
+  const ess_config& c = ctx->cfg;
+  const int rows = B * T, nsamp = ess_sample_count(c.max_ctx);
+  const size_t r0 = (size_t)b0 * T;
+  const dim3 grid(ess_xcd_grid(rows, xcd));
+  if (xcd.ticket)
+    hipLaunchKernelGGL((k_index_tau<true>), grid, dim3(NT), 0, st, ctx->sel_sample + r0 * nsamp * 64, ctx_len, T, c.max_ctx,
+                       c.topk, ess_sample_period(c.max_ctx), nsamp, ctx->sel_tau + 2 * r0, ctx->sel_cnt + r0, xcd, rows);
+  else
+    hipLaunchKernelGGL((k_index_tau<false>), grid, dim3(NT), 0, st, ctx->sel_sample + r0 * nsamp * 64, ctx_len, T, c.max_ctx,
+                       c.topk, ess_sample_period(c.max_ctx), nsamp, ctx->sel_tau + 2 * r0, ctx->sel_cnt + r0, xcd, rows);
+  ESS_HIP(hipGetLastError());
+  return ESS_OK;
+}
+
+int ess_launch_topk_finish(ess_ctx* ctx, const uint8_t* q, const float* w, const uint8_t* key, const int32_t* block_table,
+                           int n_pages, const int32_t* ctx_len, int B, int T, int b0, int32_t* idx, hipStream_t st,
+                           ess_xcd xcd) {
+  const ess_config& c = ctx->cfg;
+  int IB = 1;
+  while ((1 << IB) < c.max_ctx) ++IB;
+  const int rows = B * T;
+  const size_t r0 = (size_t)b0 * T;
+  const TopkRecompute rc{q, w, key, block_table, n_pages, c.idx_heads, c.idx_dim, ctx->sel_tau + 2 * r0};
+  const dim3 grid(ess_xcd_grid(rows, xcd));
+  if (xcd.ticket)
+    hipLaunchKernelGGL((k_topk<3, true>), grid, dim3(NT), 0, st, ctx->score_ws + r0 * c.max_ctx, ctx_len, T, c.max_ctx, c.topk,
+                       IB, idx, ctx->sel_cand + r0 * CAND_CAP, ctx->sel_cnt + r0, xcd, rows, 1, rc);
+  else
+    hipLaunchKernelGGL((k_topk<3, false>), grid, dim3(NT), 0, st, ctx->score_ws + r0 * c.max_ctx, ctx_len, T, c.max_ctx, c.topk,
+                       IB, idx, ctx->sel_cand + r0 * CAND_CAP, ctx->sel_cnt + r0, xcd, rows, 1, rc);
+  ESS_HIP(hipGetLastError());
+  return ESS_OK;
+}
+
+int ess_sel_cand_cap() { return CAND_CAP; }
 
 size_t ess_topk_cand_bytes() { return (size_t)ESS_TOPK_SHARED_ROWS * CAND_CAP * sizeof(unsigned long long); }
 
