@@ -53,7 +53,7 @@ WORKLOADS = {
 # HBM bytes per launch of the index-score kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, keyed by the
 # exact workload and flags they were measured on: (workload, overlap, paged, append) -> (bytes per step, source)
 MEASURED_TRAFFIC = {}
-DENSE_SCORES = False         # --dense-scores: stages 1-2 through the full score array (ESS_FLAG_DENSE_SCORES)
+SELECT_FLAGS = 0             # --dense-scores / --fused-select: force one form of stages 1-2 (ESS_FLAG_DENSE_SCORES / _FUSED_SELECT)
 ADMIT_SETS = 32              # access-trace sets admitted (untimed) before any decode step: LRU-Warmup, Sec. 3.2
 
 
@@ -79,8 +79,7 @@ def build_workload(name, steps_needed, overlap="auto", layers=None, rho=None, ra
         ctx_len = synth.ctx_lengths(seed, B, wl["lens"][0], wl["lens"][1], device=dev)
     S = L if wl["ratio"] is None else int(math.ceil(wl["ratio"] * L - 1e-9))
     flags = {"da": 0, "serial": bnd.ESS_FLAG_SERIAL, "dba": bnd.ESS_FLAG_DBA, "auto": bnd.ESS_FLAG_AUTO}[overlap]
-    if DENSE_SCORES:
-        flags |= bnd.ESS_FLAG_DENSE_SCORES
+    flags |= SELECT_FLAGS
     cfg = bnd.make_config(B, T, L, wl["Hi"], wl["Di"], k, H, latent_fmt=bnd.ESS_FMT_FP8 if fp8 else bnd.ESS_FMT_BF16,
                           row_stride=stride, slots_per_seq=S, flags=flags)
     ctx = bnd.Context(cfg)
@@ -503,7 +502,9 @@ def main():
                          "library picks one of the two per step from the previous step's miss count")
     ap.add_argument("--layers", type=int, default=None, help="layers run back to back per step (default: the workload's)")
     ap.add_argument("--dense-scores", action="store_true",
-                    help="index score and top-k through the full score array instead of fused (for comparison)")
+                    help="index score and top-k always through the full score array (for comparison)")
+    ap.add_argument("--fused-select", action="store_true",
+                    help="index score and top-k always in the fused form, without a score array (for comparison)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-32k", action="store_true", help="skip the extra 32K-context measurement (cfg2)")
     ap.add_argument("--no-extra", action="store_true",
@@ -522,8 +523,8 @@ def main():
                          "ratio = misses and step time against the Sparse Memory Ratio, with and without LRU-Warmup; "
                          "granularity = per-entry memcpy against the fetch kernel (prints one JSON object)")
     a = ap.parse_args()
-    global DENSE_SCORES
-    DENSE_SCORES = a.dense_scores
+    global SELECT_FLAGS
+    SELECT_FLAGS = (8 if a.dense_scores else 0) | (16 if a.fused_select else 0)
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the path shards by sequence with no collective); "
               "use --gpus 1", file=sys.stderr)

@@ -68,8 +68,11 @@ typedef enum {
                               counts of the previous step (the paper's switch on the number of misses, Sec. 3.3);
                               threshold: ess_set_overlap_threshold.  Ignored with ESS_FLAG_SERIAL. */
 
-#define ESS_FLAG_DENSE_SCORES 8u /* ess_decode_step computes stages 1 and 2 as ess_index_score + ess_topk do, through a full
-                              score array, instead of as ess_index_topk does.  Same result, slower. */
+/* ess_decode_step computes stages 1 and 2 as ess_index_score + ess_topk do, through a full score array, unless
+ * ESS_FLAG_FUSED_SELECT asks for the form of ess_index_topk (no score array).  The results are the same bits; on
+ * MI355X the first form gives the shorter step (the second is faster only as a stand-alone call on large batches). */
+#define ESS_FLAG_DENSE_SCORES 8u  /* through the score array (the default; overrides ESS_FLAG_FUSED_SELECT) */
+#define ESS_FLAG_FUSED_SELECT 16u /* as ess_index_topk */
 
 typedef struct ess_ctx ess_ctx;
 
@@ -177,8 +180,8 @@ int ess_topk(ess_ctx* ctx, const float* score, const int32_t* ctx_len, int32_t B
 
 /* Stages 1 and 2 as one: idx as ess_topk gives it for the scores ess_index_score (block_table NULL, key_fp8
  * [B,Lmax,Di]) or ess_index_score_paged (block_table given, key_fp8 = the page pool) would give -- the same bits --
- * without the score array (Sec. 3: only the top-k positions leave the indexer).  This is what ess_decode_step
- * runs.  Four launches: the scores of a sample of each sequence's keys (one block of 64 in every 2048) give, per
+ * without the score array (Sec. 3: only the top-k positions leave the indexer).  ess_decode_step runs this form
+ * under ESS_FLAG_FUSED_SELECT.  Four launches: the scores of a sample of each sequence's keys (one block of 64 in every 2048) give, per
  * row (b,t), a lower bound that very probably leaves at least k and at most a few thousand scores at or above it;
  * the main pass over all keys computes every score and keeps only (position, score) of those that reach the bound;
  * the selection is finished among them, exactly.  A row whose candidates number fewer than k or more than 8192
@@ -315,6 +318,12 @@ int ess_reset_stats(ess_ctx* ctx, void* stream);
 #define ESS_PROFILE_STAGES 6
 int ess_profile_enable(ess_ctx* ctx, int32_t max_steps);
 int ess_profile_read(ess_ctx* ctx, float* host_ms, int32_t* n_steps);
+/* Before ess_profile_read: the intervals between the events that recorded step `step` (0-based among the
+ * recorded ones) left on the caller's stream, in stream order: host_ms[i] milliseconds, stage[i] the stage the
+ * interval was booked under (as above) or -1 (not booked: the gap in front of a kernel that carries its own
+ * events).  A stage that appears twice was launched twice (the two halves of a split-batch step).  At most cap
+ * intervals; *n = how many.  WAITS for the events. */
+int ess_profile_intervals(ess_ctx* ctx, int32_t step, float* host_ms, int32_t* stage, int32_t cap, int32_t* n);
 /* Restrict the timing to some stages (bit i = stage i above; default all) and to every `every`-th
  * ess_decode_step (default 1): recorded events cost a few percent of a step, so a run whose
  * throughput matters samples one kernel on a few steps.  ess_profile_read then returns the sampled

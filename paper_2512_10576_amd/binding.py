@@ -24,6 +24,7 @@ ESS_FLAG_SERIAL = 1
 ESS_FLAG_DBA = 2
 ESS_FLAG_AUTO = 4
 ESS_FLAG_DENSE_SCORES = 8
+ESS_FLAG_FUSED_SELECT = 16
 
 
 class EssConfig(C.Structure):
@@ -90,6 +91,7 @@ def load() -> C.CDLL:
         "ess_append": [vp, C.POINTER(EssCache), vp, vp, vp, vp, i32, i32, u32, vp, vp, vp, i32, vp],
         "ess_index_score_paged": [vp, vp, vp, vp, vp, i32, vp, i32, i32, vp, vp],
         "ess_index_topk": [vp, vp, vp, vp, vp, i32, vp, i32, i32, vp, vp],
+        "ess_profile_intervals": [vp, i32, vp, vp, i32, vp],
         "ess_set_overlap_threshold": [vp, i32],
         "ess_last_overlap": [vp, C.POINTER(i32)],
         "ess_last_confined": [vp, C.POINTER(i32)],
@@ -318,6 +320,15 @@ class Context:
         self._prof_cap = max_steps
         _check(self.lib.ess_profile_select(self.h, stage_mask, every))
         _check(self.lib.ess_profile_enable(self.h, max_steps))
+
+    def profile_intervals(self, step):
+        """[(milliseconds, stage or -1), ...]: the intervals of recorded step `step` on the caller's stream, in order;
+        call before profile_read"""
+        ms = (C.c_float * 64)()
+        st = (C.c_int32 * 64)()
+        n = C.c_int32(0)
+        _check(self.lib.ess_profile_intervals(self.h, step, ms, st, 64, C.byref(n)))
+        return [(ms[i], st[i]) for i in range(n.value)]
 
     def profile_read(self):
         """list of per-step [index_score, topk, bookkeeping, attn0, attn1+merge, fetch] milliseconds"""

@@ -549,6 +549,21 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     ns1 = pick_splits(c, B, T, ESS_MAX_SPLITS - 16, 256, false);
   }
 
+  // Stages 1 and 2 come in two forms: through the score array (index score, then top-k), or fused (the score array
+  // never exists: a sample pass gives each row a lower bound, the index pass emits only candidates, the top-k is
+  // finished among them: ess_index_topk).  Alone, on batch 64 at 128K, the fused form is the faster one (sample pass
+  // 11 + 7 us, main pass 176 us against 189, finish 11 us against 17 + 15 for the two-kernel top-k: 211 against
+  // 223 us), but inside a step it is not: its main pass, launched for half a batch, takes the time of the dense one
+  // (99 against 98 us: the workgroup's wait for its place in the row's list weighs more the shorter the launch),
+  // its sample pass is two more launches in a chain of dependent ones, and beside a running fetch its main pass
+  // starts 10-15 us later than the dense one does.  Step time, batch 64 x 128K, split-batch with confined fetches:
+  // 0.620 ms fused against 0.606 through the score array, and 0.614 with the second half fused and its sample
+  // pass hidden on the side stream beside the first half's index score (which it slows by 8 us); batch 32 x 32K
+  // resident 0.101 against 0.096; batch 64 x 32K 0.398 against 0.394.  So the step goes through the score array
+  // unless ESS_FLAG_FUSED_SELECT asks for the fused form.
+  const bool fused = (c.flags & ESS_FLAG_FUSED_SELECT) && !(c.flags & ESS_FLAG_DENSE_SCORES);
+  const size_t sel_pitch = (size_t)ess_sample_count(c.max_ctx) * 64, sel_cap = (size_t)ess_sel_cand_cap();
+
   // stages 1-2 (+ 3, 5 when offloaded) per half; the fetch goes to the side stream
   for (int h = 0; h < nh; ++h) {
     const int b0 = hb0[h], Bh = hB[h];
@@ -581,7 +596,7 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     const uint8_t* key_h = a->block_table ? a->key_fp8 : a->key_fp8 + (size_t)b0 * c.max_ctx * c.idx_dim;
     const int32_t* table_h = a->block_table ? a->block_table + (size_t)b0 * (c.max_ctx / ESS_PAGE_TOKENS) : nullptr;
     const int np_h = a->block_table ? a->n_pages : 0;
-    if (c.flags & ESS_FLAG_DENSE_SCORES) {
+    if (!fused) {
       take_index_events();
       rc = ess_launch_index_score(c, q_h, w_h, key_h, a->ctx_len + b0, Bh, T, sc, st, table_h, np_h, ev_s, ev_e, xcd_of(ESS_TKT_INDEX));
       if (rc != ESS_OK) return rc;
@@ -590,11 +605,10 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
       if (rc != ESS_OK) return rc;
       ESS_END(1);
     } else {
-      // index score and top-k as one stage without a score array (see ess_internal.h); the two small launches in
-      // front of the emitting pass are booked with the top-k, whose threshold search they are
-      const size_t pitch = (size_t)ess_sample_count(c.max_ctx) * 64, cap = (size_t)ess_sel_cand_cap();
+      // the two small launches in front of the emitting pass are booked with the top-k, whose threshold search they are
+      const size_t cap = sel_cap;
       ESS_BEGIN(1);
-      rc = ess_launch_index_sample(c, q_h, w_h, key_h, a->ctx_len + b0, Bh, T, ctx->sel_sample + bt0 * pitch, st, table_h, np_h,
+      rc = ess_launch_index_sample(c, q_h, w_h, key_h, a->ctx_len + b0, Bh, T, ctx->sel_sample + bt0 * sel_pitch, st, table_h, np_h,
                                    xcd_of(ESS_TKT_SAMPLE));
       if (rc != ESS_OK) return rc;
       if ((rc = ess_launch_index_tau(ctx, a->ctx_len + b0, Bh, T, b0, st, xcd_of(ESS_TKT_TAU))) != ESS_OK) return rc;
@@ -884,6 +898,22 @@ int ess_profile_enable(ess_ctx* ctx, int32_t max_steps) {
     }
   }
   ctx->prof_cap = max_steps;
+  return ESS_OK;
+}
+
+int ess_profile_intervals(ess_ctx* ctx, int32_t step, float* host_ms, int32_t* stage, int32_t cap, int32_t* n) {
+  if (!ctx || !host_ms || !stage || !n) return ess_fail(ESS_ERR_INVALID_ARG, "NULL argument");
+  if (step < 0 || step >= ctx->prof_n) return ess_fail(ESS_ERR_INVALID_ARG, "step %d of %d recorded", step, ctx->prof_n);
+  hipEvent_t* ev = ctx->prof_ev + (size_t)step * ESS_PROF_EVENTS;
+  const int8_t* tag = ctx->prof_tag + (size_t)step * ESS_PROF_MAIN;
+  const int nm = ctx->prof_nmark[step];
+  if (nm > 0) ESS_HIP(hipEventSynchronize(ev[nm - 1]));
+  int k = 0;
+  for (int m = 1; m < nm && k < cap; ++m, ++k) {
+    ESS_HIP(hipEventElapsedTime(&host_ms[k], ev[m - 1], ev[m]));
+    stage[k] = tag[m];
+  }
+  *n = k;
   return ESS_OK;
 }
 

@@ -165,7 +165,7 @@ def test_switch_with_confined_fetches_at_odd_batch_sizes(ess_lib, B, ctx_lens):
             q = synth.attn_query(90 + step, B, T, H)
             ctx.decode_step(cache, qws[step - 1][0], qws[step - 1][1], dev[2], dev[3], q.cuda(), step, idx_out, out, lse, mc)
             torch.cuda.synchronize()
-            if flags == 4:
+            if flags != 0:
                 confined.append(ctx.last_confined())
                 parts.append(ctx.last_overlap())
             steps.append((idx_out.clone(), out.clone(), lse.clone(), mc.clone(), cache.slot_of.clone(),
@@ -201,10 +201,10 @@ def test_ticket_fed_launches_complete_at_any_launch_size(ess_lib, grid):
     qws = [(qi.cuda(), w.cuda())] + [tuple(x.cuda() for x in synth.indexer_inputs(87 + s, B, T, Hi, Di, L, 8, 8, 16)[:2])
                                      for s in (1, 2)]
     results, confined = {}, []
-    for flags in (0, 4):
+    for flags in (0, 4, 20):                                     # 20: stages 1-2 in the fused form, four ticket-fed launches
         ctx = _ctx(max_batch=B, max_q_tokens=T, max_ctx=L, idx_heads=Hi, idx_dim=Di, topk=k, attn_heads=H,
                    slots_per_seq=S, flags=flags)
-        if flags == 4:
+        if flags != 0:
             ctx.set_overlap_threshold(0)
             ctx.debug_ticket_grid(grid)
         cache = bnd.Cache.allocate(ctx.cfg, B, host_pool=hp,
@@ -219,17 +219,18 @@ def test_ticket_fed_launches_complete_at_any_launch_size(ess_lib, grid):
             q = synth.attn_query(95 + step, B, T, H)
             ctx.decode_step(cache, qws[step - 1][0], qws[step - 1][1], dev[2], dev[3], q.cuda(), step, idx_out, out, lse, mc)
             torch.cuda.synchronize()
-            if flags == 4:
+            if flags != 0:
                 confined.append(ctx.last_confined())
             steps.append((idx_out.clone(), out.clone(), lse.clone(), mc.clone(), cache.slot_of.clone(),
                           cache.token_of.clone(), cache.stamp.clone(), cache.slot_pool.clone()))
         assert ctx.get_stats()["steps"] == 3                     # also: no assertion of a confined step pending
         ctx.close()
         results[flags] = steps
-    for s0, s4 in zip(results[0], results[4]):
-        for x, y in zip(s0, s4):
-            assert torch.equal(x, y)
-    assert confined[0] == 0 and min(confined[1:]) >= 1, confined
+    for other in (4, 20):
+        for s0, s4 in zip(results[0], results[other]):
+            for x, y in zip(s0, s4):
+                assert torch.equal(x, y)
+    assert confined[0] == 0 and confined[3] == 0 and min(confined[1:3] + confined[4:]) >= 1, confined
 
 
 @pytest.mark.parametrize("stride,fmt", [(1152, 0), (656, 1)])

@@ -69,9 +69,12 @@ def _run_index_topk(ess_lib, q, w, key, lens, k, block_table=None, n_tok=None):
     return first
 
 
-def _run_decode_step(ess_lib, q, w, key, lens, k, block_table=None, flags=0):
-    """stages 1-2 through ess_decode_step, nothing offloaded (slot = position); returns idx_out"""
+def _run_decode_step(ess_lib, q, w, key, lens, k, block_table=None, flags=None):
+    """stages 1-2 through ess_decode_step (fused form unless flags say otherwise), nothing offloaded (slot =
+    position); returns idx_out"""
     from paper_2512_10576_amd import binding as bnd
+    if flags is None:
+        flags = bnd.ESS_FLAG_FUSED_SELECT
     q, w, key = (torch.as_tensor(x) for x in (q, w, key))
     B, T, Hi, Di = q.shape
     H = 8

@@ -323,13 +323,15 @@ def test_sparse_mla_large_values_keep_their_magnitude(ess_lib):
 
 
 # ---------------------------------------------------------------- whole step
-@pytest.mark.parametrize("flags,fmt", [(0, 0), (1, 0), (2, 0), (4, 0), (0, 1), (2, 1), (4, 1)])
+@pytest.mark.parametrize("flags,fmt", [(0, 0), (1, 0), (2, 0), (4, 0), (0, 1), (2, 1), (4, 1), (16, 0), (18, 0), (20, 0), (20, 1)])
 def test_decode_step_offloaded_vs_oracle(ess_lib, flags, fmt):
     """T = 2 (causal offset), offloaded entries in both storage formats, all overlap modes (4 = switch
     between DA and DBA on the miss count of the previous step; only this mode knows the miss count and
-    may confine a fetch to some XCDs, with the kernels beside it taking their work by ticket)"""
+    may confine a fetch to some XCDs, with the kernels beside it taking their work by ticket); + 16: stages 1-2 in
+    the fused form (no score array), whose kernels then take their work by ticket as well"""
     from paper_2512_10576_amd import binding as bnd
     print("decode_step offload flags", flags, "fmt", fmt, flush=True)
+    all_flags, flags = flags, flags & 7
     B, T, Hi, Di, L, k, H, S = 3, 2, 64, 128, 6000, 512, 128, 1500
     stride = 1152 if fmt == 0 else 656
     qi, w, key = synth.indexer_inputs(41, B, T, Hi, Di, L, 8, 8, 16)
@@ -338,7 +340,7 @@ def test_decode_step_offloaded_vs_oracle(ess_lib, flags, fmt):
     hp = torch.empty((B, L, stride), dtype=torch.uint8, pin_memory=True)
     hp.copy_(host)
     ctx = _ctx(ess_lib, max_batch=B, max_q_tokens=T, max_ctx=L, idx_heads=Hi, idx_dim=Di, topk=k, attn_heads=H,
-               slots_per_seq=S, flags=flags, latent_fmt=fmt)
+               slots_per_seq=S, flags=all_flags, latent_fmt=fmt)
     # poison: a NaN pattern for bf16 entries; for quantised entries 0x7E (448, finite) -- a never-filled slot
     # must not be read at all, but a NaN byte there would make the dequantised zero-weight product NaN
     poison = 0x7F if fmt == 0 else 0x7E
@@ -381,9 +383,9 @@ def test_decode_step_offloaded_vs_oracle(ess_lib, flags, fmt):
     else:
         assert all(m == {0: 0, 1: 2, 2: 1}[flags] for m, _ in modes), modes
     test_decode_step_offloaded_vs_oracle.results = getattr(test_decode_step_offloaded_vs_oracle, "results", {})
-    test_decode_step_offloaded_vs_oracle.results[(flags, fmt)] = outs
+    test_decode_step_offloaded_vs_oracle.results[(all_flags, fmt)] = outs
     res = test_decode_step_offloaded_vs_oracle.results
-    for other in (1, 2, 4):                                          # DA, serial, DBA and switching runs agree bit for bit
+    for other in (1, 2, 4, 16, 18, 20):                                          # DA, serial, DBA and switching runs agree bit for bit
         if (0, fmt) in res and (other, fmt) in res:
             for (o0, l0), (o1, l1) in zip(res[(0, fmt)], res[(other, fmt)]):
                 assert torch.equal(o0, o1) and torch.equal(l0, l1)
