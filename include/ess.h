@@ -195,7 +195,7 @@ int ess_index_topk(ess_ctx* ctx, const uint8_t* q_idx_fp8, const float* w, const
  * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same result as ess_topk for
  * score [B,T,max_ctx] and k (idx [B,T,k]).  The call allocates nothing: its scratch memory (candidate
  * lists of rows that several workgroups share, and their counters) is an array inside the library's
- * image, 8 MiB + 512 bytes, which every GPU the library runs on holds until the process ends.  Limits:
+ * image, 8 MiB + 1536 bytes, which every GPU the library runs on holds until the process ends.  Limits:
  * B*T <= ESS_TOPK_STATIC_MAX_ROWS, T <= 4, max_ctx <= 524288, k <= 4096; beyond them ESS_ERR_CAPACITY.
  * All calls on one GPU share that array: calls that overlap in time on one GPU (different streams or
  * threads) race; serialise them. */

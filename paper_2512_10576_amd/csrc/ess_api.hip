@@ -61,7 +61,7 @@ int validate_config(const ess_config* c) {
 }
 
 struct WsLayout {
-  size_t score, slot_idx, hit, miss, n_hit, n_miss, fill_tok, fill_slot, miss_cnt, o_part, lse_part, stats, zero_row, topk_cand, topk_cnt, sel_sample, sel_tau, sel_cand, sel_cnt, tickets, total;
+  size_t score, slot_idx, hit, miss, n_hit, n_miss, fill_tok, fill_slot, miss_cnt, o_part, lse_part, stats, zero_row, topk_cand, topk_cnt, topk_tau, sel_sample, sel_tau, sel_cand, sel_cnt, tickets, total;
 };
 
 size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -86,6 +86,7 @@ WsLayout ws_layout(const ess_config& c) {
   w.zero_row = take(ESS_ZERO_ROW_BYTES);
   w.topk_cand = take(ess_topk_cand_bytes());
   w.topk_cnt = take(ESS_TOPK_SHARED_ROWS * sizeof(uint32_t));
+  w.topk_tau = take(ESS_TOPK_SHARED_ROWS * 2 * sizeof(uint32_t));
   w.sel_sample = take(B * T * (size_t)ess_sample_count(c.max_ctx) * 64 * 4);
   w.sel_tau = take(B * T * 8);
   w.sel_cand = take(B * T * (size_t)ess_sel_cand_cap() * 8);
@@ -232,6 +233,7 @@ int ess_create(const ess_config* cfg, ess_ctx** out) {
   ctx->zero_row = base + w.zero_row;
   ctx->topk_cand = reinterpret_cast<unsigned long long*>(base + w.topk_cand);
   ctx->topk_cnt = reinterpret_cast<uint32_t*>(base + w.topk_cnt);
+  ctx->topk_tau = reinterpret_cast<uint32_t*>(base + w.topk_tau);
   ctx->sel_sample = reinterpret_cast<float*>(base + w.sel_sample);
   ctx->sel_tau = reinterpret_cast<uint32_t*>(base + w.sel_tau);
   ctx->sel_cand = reinterpret_cast<unsigned long long*>(base + w.sel_cand);

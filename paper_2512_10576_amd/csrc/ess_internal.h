@@ -65,6 +65,7 @@ struct ess_ctx {
   uint8_t* zero_row;            // ESS_ZERO_ROW_BYTES of zeros, never written: source of masked attention rows
   unsigned long long* topk_cand; // [ESS_TOPK_SHARED_ROWS][8192] candidate keys of rows shared by several workgroups
   uint32_t* topk_cnt;           // [ESS_TOPK_SHARED_ROWS] candidates listed per row: zero between steps
+  uint32_t* topk_tau;           // [ESS_TOPK_SHARED_ROWS][2] the bounds the candidate pass worked with (see sample_bins)
   // fused selection inside ess_decode_step / ess_index_topk (no score array): per row (b,t)
   float* sel_sample;            // [B,T,64 * ess_sample_count(max_ctx)] scores of the sequence's sample blocks
   uint32_t* sel_tau;            // [B,T][2] bounds of the row's selection (ess_orderable images): candidates reach [0]; the k-th largest score very probably lies below [1]

@@ -69,19 +69,22 @@ __device__ __forceinline__ void sample_bins(const uint32_t* shist, uint32_t* wav
   constexpr int BPT = SBINS / NTH;         // bins per thread, descending
   const int top_bin = SBINS - 1 - tid * BPT;
   const int top_slot = sample_slot<NTH>(top_bin);               // the thread's bins are consecutive words
-  uint32_t mine = 0;
+  uint32_t mine = 0, bin[BPT];              // (kept in registers: the search below is a chain of dependent steps)
 #pragma unroll
-  for (int r = 0; r < BPT; ++r) mine += shist[top_slot - r];
+  for (int r = 0; r < BPT; ++r) { bin[r] = shist[top_slot - r]; mine += bin[r]; }
   uint32_t total;
   const uint32_t inc = block_incl_scan<NTH>(mine, wave_tot, &total);
 #pragma unroll
   for (int w = 0; w < 2; ++w) {
     uint32_t above = inc - mine;
     if (target[w] > 0 && above < target[w] && inc >= target[w]) {    // the crossing bin is one of mine
-      for (int r = 0; r < BPT; ++r) {
-        above += shist[top_slot - r];
-        if (above >= target[w]) { sel[w] = (uint32_t)(top_bin - r); break; }
+      int at = -1;
+#pragma unroll
+      for (int r = 0; r < BPT; ++r) {                                // the first r at which the count reaches the target
+        above += bin[r];
+        if (at < 0 && above >= target[w]) at = r;
       }
+      sel[w] = (uint32_t)(top_bin - at);
     }
   }
   __syncthreads();

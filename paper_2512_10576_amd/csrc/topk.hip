@@ -36,7 +36,8 @@ constexpr int COPIES = 8;
 using ess_sel::CAND_CAP;
 using ess_sel::SBITS;
 using ess_sel::SBINS;
-constexpr int SAMPLE_TARGET = 4096;         // about this many samples per row, at least every 16th score
+constexpr int SAMPLE_TARGET = 4096;         // at most this many samples per row (four per thread), about every 16th score or fewer
+static_assert(SAMPLE_TARGET <= 4 * NT, "the sample is loaded in one round of four per thread");
 constexpr int FAST_MIN_VIS = 16384;
 
 struct __align__(16) TopkShared {
@@ -202,13 +203,15 @@ __device__ __forceinline__ void crossing_digit(TopkShared& sm, uint32_t need) {
   __syncthreads();
 }
 
-// A row finished from its candidate list (`listed` keys at grow, k <= listed <= CAND_CAP) when the k-th largest
-// score very probably lies in [lo, hi) (ess_orderable images; see k_index_tau).  The keys stay in registers.  One
+// A row finished from its candidate list (`listed` keys at grow, k <= listed <= CAND_CAP; SRC_LDS: the list is
+// sm.cand itself) when the k-th largest score very probably lies in [lo, hi) (ess_orderable images; see
+// sample_bins).  The keys stay in registers.  One
 // histogram pass spreads [lo, hi) over 2047 digits (whatever lies at or above hi goes into the top one), the digit
 // that holds the k-th largest key is found, and inside it -- a handful of keys -- the key is found by counting.
 // Returns false, with the keys copied to sm.cand, when that digit holds more keys than the counting step takes
 // (massive ties, or a k-th largest score outside the range): the caller goes on with the general selection.
-__device__ __forceinline__ bool finish_fast(TopkShared& sm, const unsigned long long* __restrict__ grow, uint32_t listed,
+template <bool SRC_LDS>
+__device__ __forceinline__ bool finish_fast(TopkShared& sm, const unsigned long long* grow, uint32_t listed,
                                             uint32_t lo, uint32_t hi, int vis, int k, int IB, int32_t* __restrict__ orow) {
   constexpr int PER = CAND_CAP / NT;
   constexpr uint32_t SMALL = 1024;           // keys the counting step takes: one per thread
@@ -216,7 +219,9 @@ __device__ __forceinline__ bool finish_fast(TopkShared& sm, const unsigned long 
   const unsigned long long imask = (1ull << IB) - 1ull;
   unsigned long long c[PER];
 #pragma unroll
-  for (int u = 0; u < PER; ++u) c[u] = (uint32_t)(u * NT + tid) < listed ? grow[u * NT + tid] : 0ull;
+  for (int u = 0; u < PER; ++u)
+    c[u] = (uint32_t)(u * NT + tid) < listed ? (SRC_LDS ? sm.cand[u * NT + tid] : grow[u * NT + tid]) : 0ull;
+  if (SRC_LDS) __syncthreads();              // the bitmap shares its memory with the list: every thread holds its keys first
   // while the keys are on their way: clear the histogram and the row's bitmap
   uint32_t* bmp = sm.hist;
   const int W = (vis + 31) >> 5;
@@ -292,13 +297,12 @@ __device__ __forceinline__ bool finish_fast(TopkShared& sm, const unsigned long 
 struct TopkRecompute {                     // MODE 3: what it takes to compute a row's scores
   const uint8_t* q; const float* w; const uint8_t* key; const int32_t* block_table;
   int n_pages, Hi, Di;
-  const uint32_t* tau;                     // [rows][2] the rows' bounds (see k_index_tau), shifted like the other row arrays
 };
 template <int MODE>
 __device__ __forceinline__ void topk_item(TopkShared& sm, int item, int parts, float* __restrict__ score,
                                           const int32_t* __restrict__ ctx_len, int T, int Lmax, int k, int IB,
                                           int32_t* __restrict__ idx_out, unsigned long long* __restrict__ g_cand,
-                                          uint32_t* __restrict__ g_cnt, const TopkRecompute& rc) {
+                                          uint32_t* __restrict__ g_cnt, uint32_t* __restrict__ g_tau, const TopkRecompute& rc) {
   const int row = item / parts;
   const int part = item % parts;
   const int b = row / T, t = row % T;
@@ -350,10 +354,10 @@ __device__ __forceinline__ void topk_item(TopkShared& sm, int item, int parts, f
   if (use_list) {
     const unsigned long long* grow = g_cand + (size_t)row * CAND_CAP;
     bool copied = false;
-    if (MODE == 3) {
-      const uint32_t lo = rc.tau[2 * row], hi = rc.tau[2 * row + 1];
+    {
+      const uint32_t lo = g_tau[2 * row], hi = g_tau[2 * row + 1];       // left by the kernel that made the list
       if (lo != 0u && hi > lo) {
-        if (finish_fast(sm, grow, listed, lo, hi, vis, k, IB, orow)) return;
+        if (finish_fast<false>(sm, grow, listed, lo, hi, vis, k, IB, orow)) return;
         copied = true;
       }
     }
@@ -364,7 +368,7 @@ __device__ __forceinline__ void topk_item(TopkShared& sm, int item, int parts, f
     }
   }
   if (vis >= FAST_MIN_VIS || use_list) {
-   uint32_t lo_bin = 0;
+   uint32_t lo_bin = 0, hi_bin = 0xffffffffu;
    if (!use_list) {
     // samples: blocks of 16 consecutive scores (one 64-byte piece of a cache line), every bstride-th block,
     // about SAMPLE_TARGET scores in all.  (One score out of every 16th..32nd touches every cache line of the
@@ -373,28 +377,28 @@ __device__ __forceinline__ void topk_item(TopkShared& sm, int item, int parts, f
     int bstride = 1;
     while (nblk_all / bstride > SAMPLE_TARGET / 16) bstride <<= 1;
     const int ns = (nblk_all / bstride) << 4;
+    // (at most SAMPLE_TARGET samples: four per thread, requested before the histogram is cleared)
+    float sv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = u * NT + tid;
+      sv[u] = j < ns ? srow[(size_t)(j >> 4) * bstride * 16 + (j & 15)] : 0.f;
+    }
     for (int j = tid; j < ess_sel::sample_words<NT>(); j += NT) sm.shist[j] = 0;
     if (tid == 0) { sm.cand_n = 0; sm.sbin[0] = sm.sbin[1] = 0xffffffffu; }
     __syncthreads();
-    for (int j0 = 0; j0 < ns; j0 += 4 * NT) {
-      float sv[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int j = j0 + u * NT + tid;
-        sv[u] = j < ns ? srow[(size_t)(j >> 4) * bstride * 16 + (j & 15)] : 0.f;
-      }
-#pragma unroll
-      for (int u = 0; u < 4; ++u)
-        if (j0 + u * NT + tid < ns) atomicAdd(&sm.shist[ess_sel::sample_slot<NT>(orderable(sv[u]) >> (32 - SBITS))], 1u);
-    }
+    for (int u = 0; u < 4; ++u)
+      if (u * NT + tid < ns) atomicAdd(&sm.shist[ess_sel::sample_slot<NT>(orderable(sv[u]) >> (32 - SBITS))], 1u);
     __syncthreads();
-    uint32_t hi_unused;
-    ess_sel::sample_bins<NT>(sm.shist, sm.wave_tot, sm.sbin, k, ns, vis, &lo_bin, &hi_unused);      // (ends with a barrier: shist is dead from here, cand may overwrite it)
+    ess_sel::sample_bins<NT>(sm.shist, sm.wave_tot, sm.sbin, k, ns, vis, &lo_bin, &hi_bin);      // (ends with a barrier: shist is dead from here, cand may overwrite it)
    }
     if (MODE == 1 && lo_bin == 0xffffffffu) return;   // no usable threshold: the finishing kernel takes path B
     if (use_list || lo_bin != 0xffffffffu) {
+     // the k-th largest score very probably lies in [tau, tau_hi) (see sample_bins)
+     const uint32_t tau = lo_bin << (32 - SBITS);
+     const uint32_t tau_hi = (hi_bin == 0xffffffffu || hi_bin == SBINS - 1) ? 0xffffffffu : (hi_bin + 1) << (32 - SBITS);
      if (!use_list) {
-      const uint32_t tau = lo_bin << (32 - SBITS);
       // The pass only compares floats and stores (position, score) of the few positions at or above
       // the key: v >= tau_f is the same predicate as orderable(v) >= tau (NaN fails both, -0 == +0),
       // and the composite keys are computed afterwards, densely, for the candidates alone.
@@ -433,7 +437,10 @@ __device__ __forceinline__ void topk_item(TopkShared& sm, int item, int parts, f
         // append this slice's candidates to the row's list; the true count is added even when it overflows,
         // so that the finishing kernel sees the overflow
         unsigned long long* grow = g_cand + (size_t)row * CAND_CAP;
-        if (tid == 0) sm.sel_above = atomicAdd(&g_cnt[row], (uint32_t)nc);
+        if (tid == 0) {
+          sm.sel_above = atomicAdd(&g_cnt[row], (uint32_t)nc);
+          if (part == 0) { g_tau[2 * row] = tau; g_tau[2 * row + 1] = tau_hi; }    // (every part finds the same two)
+        }
         __syncthreads();
         const uint32_t gbase = sm.sel_above;
         if (nc <= CAND_CAP)
@@ -441,6 +448,9 @@ __device__ __forceinline__ void topk_item(TopkShared& sm, int item, int parts, f
             if (gbase + (uint32_t)j < (uint32_t)CAND_CAP) grow[gbase + j] = sm.cand[j];
         return;
       }
+      if (!use_list && nc >= k && nc <= CAND_CAP && tau != 0u && tau_hi > tau &&
+          finish_fast<true>(sm, sm.cand, (uint32_t)nc, tau, tau_hi, vis, k, IB, orow))
+        return;
       if (nc >= k && nc <= CAND_CAP) {
         // bits on which the candidates differ: everything above is common and decided
         unsigned long long a = ~0ull, o = 0ull;
@@ -567,13 +577,14 @@ template <int MODE, bool DYN>
 __global__ __launch_bounds__(NT) void k_topk(float* __restrict__ score, const int32_t* __restrict__ ctx_len,
                                              int T, int Lmax, int k, int IB, int32_t* __restrict__ idx_out,
                                              unsigned long long* __restrict__ g_cand, uint32_t* __restrict__ g_cnt,
-                                             ess_xcd xcd, int rows, int parts_arg, const TopkRecompute rc) {
+                                             uint32_t* __restrict__ g_tau, ess_xcd xcd, int rows, int parts_arg,
+                                             const TopkRecompute rc) {
   __shared__ TopkShared sm;
   __shared__ int s_item;
   const int parts = MODE == 1 ? parts_arg : 1;
   // work item = (part, row): by workgroup index, or drawn from the launch's counter off the XCDs to be avoided
   ESS_WORK_LOOP(DYN, xcd, MODE == 1 ? blockIdx.y * parts + blockIdx.x : blockIdx.x, rows * parts, &s_item, item) {
-    topk_item<MODE>(sm, item, parts, score, ctx_len, T, Lmax, k, IB, idx_out, g_cand, g_cnt, rc);
+    topk_item<MODE>(sm, item, parts, score, ctx_len, T, Lmax, k, IB, idx_out, g_cand, g_cnt, g_tau, rc);
   }
 }
 
@@ -642,7 +653,7 @@ namespace {
 // Launches of one top-k call.  cand / cnt: candidate lists [ESS_TOPK_SHARED_ROWS][CAND_CAP] and their counters
 // (zero at launch, zero again afterwards), only used when rows are shared by several workgroups.
 int launch_topk(int max_ctx, int k, const float* score_in, const int32_t* ctx_len, int B, int T, int32_t* idx,
-                unsigned long long* cand, uint32_t* cnt, hipStream_t st, ess_xcd xcd) {
+                unsigned long long* cand, uint32_t* cnt, uint32_t* tau, hipStream_t st, ess_xcd xcd) {
   float* score = const_cast<float*>(score_in);          // read only in these modes
   const TopkRecompute rc{};
   int IB = 1;
@@ -661,9 +672,9 @@ int launch_topk(int max_ctx, int k, const float* score_in, const int32_t* ctx_le
 #define ESS_TOPK_LAUNCH(MODE, grid, x, np)                                                                           \
   do {                                                                                                               \
     if (dyn) hipLaunchKernelGGL((k_topk<MODE, true>), grid, dim3(NT), 0, st, score, ctx_len, T, max_ctx, k, IB, idx, \
-                                cand, cnt, x, rows, np, rc);                                                         \
+                                cand, cnt, tau, x, rows, np, rc);                                                    \
     else hipLaunchKernelGGL((k_topk<MODE, false>), grid, dim3(NT), 0, st, score, ctx_len, T, max_ctx, k, IB, idx,    \
-                            cand, cnt, x, rows, np, rc);                                                             \
+                            cand, cnt, tau, x, rows, np, rc);                                                        \
   } while (0)
   if (parts > 1) {
     const dim3 g1 = dyn ? dim3(ess_xcd_grid(parts * rows, x0)) : dim3(parts, rows);
@@ -680,7 +691,7 @@ int launch_topk(int max_ctx, int k, const float* score_in, const int32_t* ctx_le
 
 int ess_launch_topk(ess_ctx* ctx, const float* score, const int32_t* ctx_len, int B, int T, int32_t* idx,
                     hipStream_t st, ess_xcd xcd) {
-  return launch_topk(ctx->cfg.max_ctx, ctx->cfg.topk, score, ctx_len, B, T, idx, ctx->topk_cand, ctx->topk_cnt, st, xcd);
+  return launch_topk(ctx->cfg.max_ctx, ctx->cfg.topk, score, ctx_len, B, T, idx, ctx->topk_cand, ctx->topk_cnt, ctx->topk_tau, st, xcd);
 }
 
 // The two small kernels of the fused selection that live here (see ess_internal.h).
@@ -707,14 +718,14 @@ int ess_launch_topk_finish(ess_ctx* ctx, const uint8_t* q, const float* w, const
   while ((1 << IB) < c.max_ctx) ++IB;
   const int rows = B * T;
   const size_t r0 = (size_t)b0 * T;
-  const TopkRecompute rc{q, w, key, block_table, n_pages, c.idx_heads, c.idx_dim, ctx->sel_tau + 2 * r0};
+  const TopkRecompute rc{q, w, key, block_table, n_pages, c.idx_heads, c.idx_dim};
   const dim3 grid(ess_xcd_grid(rows, xcd));
   if (xcd.ticket)
     hipLaunchKernelGGL((k_topk<3, true>), grid, dim3(NT), 0, st, ctx->score_ws + r0 * c.max_ctx, ctx_len, T, c.max_ctx, c.topk,
-                       IB, idx, ctx->sel_cand + r0 * CAND_CAP, ctx->sel_cnt + r0, xcd, rows, 1, rc);
+                       IB, idx, ctx->sel_cand + r0 * CAND_CAP, ctx->sel_cnt + r0, ctx->sel_tau + 2 * r0, xcd, rows, 1, rc);
   else
     hipLaunchKernelGGL((k_topk<3, false>), grid, dim3(NT), 0, st, ctx->score_ws + r0 * c.max_ctx, ctx_len, T, c.max_ctx, c.topk,
-                       IB, idx, ctx->sel_cand + r0 * CAND_CAP, ctx->sel_cnt + r0, xcd, rows, 1, rc);
+                       IB, idx, ctx->sel_cand + r0 * CAND_CAP, ctx->sel_cnt + r0, ctx->sel_tau + 2 * r0, xcd, rows, 1, rc);
   ESS_HIP(hipGetLastError());
   return ESS_OK;
 }
@@ -726,11 +737,11 @@ size_t ess_topk_cand_bytes() { return (size_t)ESS_TOPK_SHARED_ROWS * CAND_CAP * 
 // ---------------------------------------------------------------------------------------------
 // ess_topk_static: the top-k for callers that cannot allocate.  Its scratch memory -- the candidate lists of rows
 // shared by several workgroups, and their counters -- is this array, part of the library's image on every
-// GPU it is loaded on (8 MiB + 512 bytes).  In host code the array's name is not a device address: the address
+// GPU it is loaded on (8 MiB + 1536 bytes).  In host code the array's name is not a device address: the address
 // on the current device is asked for once per device and kept.
 namespace {
 constexpr size_t kStaticCand = (size_t)ESS_TOPK_SHARED_ROWS * CAND_CAP;          // candidate keys
-constexpr size_t kStaticWords = kStaticCand + ESS_TOPK_SHARED_ROWS / 2;          // + the rows' counters (uint32 each)
+constexpr size_t kStaticWords = kStaticCand + ESS_TOPK_SHARED_ROWS / 2 + ESS_TOPK_SHARED_ROWS;   // + the rows' counters (uint32 each) + their bounds (2 x uint32)
 constexpr int kMaxDevices = 64;
 static_assert(ESS_TOPK_STATIC_MAX_ROWS == ESS_TOPK_SHARED_ROWS, "the static scratch holds one candidate list per shared row");
 }  // namespace
@@ -770,5 +781,5 @@ extern "C" int ess_topk_static(const float* score, const int32_t* ctx_len, int32
   // so that the call may be captured in a graph)
   int rc = ess_launch_fill_u32(cnt, ESS_TOPK_SHARED_ROWS, 0u, st);
   if (rc != ESS_OK) return rc;
-  return launch_topk(max_ctx, k, score, ctx_len, B, T, idx, base, cnt, st, ess_xcd{nullptr, 0, nullptr, 0});
+  return launch_topk(max_ctx, k, score, ctx_len, B, T, idx, base, cnt, cnt + ESS_TOPK_SHARED_ROWS, st, ess_xcd{nullptr, 0, nullptr, 0});
 }
