@@ -23,6 +23,7 @@
 // GPU threads read the pinned host pool by address (the paper's UVA idea),
 // one wave per 1152- or 656-byte entry, many entries in flight.
 #include "ess_internal.h"
+#include "select_common.h"
 
 namespace {
 
@@ -30,7 +31,7 @@ constexpr int BT = 1024;
 
 struct BookShared {
   uint32_t wave_tot[BT / 64];
-  uint32_t sel_digit, sel_below, vict_n;
+  uint32_t sel_digit, sel_below;
 };
 // The large arrays of the bookkeeping kernel live in dynamic LDS, sized by the configuration:
 //   bm [W]  bitmap of the missed positions (W = max_ctx / 32 words, rounded up to an even number)
@@ -48,30 +49,9 @@ inline size_t book_lds_bytes(int max_ctx, int sel_cap) {
   return book_words(max_ctx) * 4 + book_union_bytes(sel_cap) + (size_t)sel_cap * 4;
 }
 
-__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v, int lane) {
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    const uint32_t o = __shfl_up(v, d, 64);
-    if (lane >= d) v += o;
-  }
-  return v;
-}
-
+using ess_sel::wave_incl_scan;
 __device__ __forceinline__ uint32_t block_incl_scan(uint32_t v, uint32_t* wave_tot, uint32_t* total) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const uint32_t inc = wave_incl_scan(v, lane);
-  __syncthreads();
-  if (lane == 63) wave_tot[wave] = inc;
-  __syncthreads();
-  uint32_t off = 0, tot = 0;
-#pragma unroll
-  for (int i = 0; i < BT / 64; ++i) {
-    const uint32_t x = wave_tot[i];
-    if (i < wave) off += x;
-    tot += x;
-  }
-  *total = tot;
-  return inc + off;
+  return ess_sel::block_incl_scan<BT>(v, wave_tot, total);
 }
 
 __device__ void bitonic_sort_u64(unsigned long long* a, int n) {
@@ -129,9 +109,12 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
   __syncthreads();
   // look-up straight from the selection list (all gathers of a thread in flight together): hits get
   // their stamp, misses set their bit; duplicates across the T query tokens do the same thing twice
+  // (kept: when one round covers the selection and a query token's list is whole rounds of the workgroup, the
+  // lists at the end are built from these registers instead of a second look-up)
+  const bool keep = nsel <= 4 * BT && kk % BT == 0;
   uint32_t my_valid = 0;
+  int sv[4] = {-1, -1, -1, -1}, slv[4] = {-1, -1, -1, -1};
   for (int e0 = 0; e0 < nsel; e0 += 4 * BT) {
-    int sv[4], slv[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int e = e0 + u * BT + tid;
@@ -155,9 +138,10 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
   const int w0 = min(tid * wpt, W), w1 = min(w0 + wpt, W);
   uint32_t my_miss = 0;
   for (int wd = w0; wd < w1; ++wd) my_miss += __popc(bm[wd]);
-  uint32_t m, nvalid;
-  (void)block_incl_scan(my_valid, sm.wave_tot, &nvalid);
-  const uint32_t miss_inc = block_incl_scan(my_miss, sm.wave_tot, &m);
+  // one scan for both counts (each at most T * k <= 8192: 16 bits apiece)
+  uint32_t both;
+  const uint32_t miss_inc = block_incl_scan(my_miss | (my_valid << 16), sm.wave_tot, &both) & 0xffffu;
+  const uint32_t m = both & 0xffffu, nvalid = both >> 16;
   {
     uint32_t pos = miss_inc - my_miss;
     for (int wd = w0; wd < w1; ++wd) {
@@ -201,8 +185,14 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
       __syncthreads();
       uint32_t c = 0;
       if (tid < 256) {
+        // a thread's 32 copies are consecutive words, so consecutive threads start 32 words apart: the 16-byte
+        // pieces are taken in an order rotated by the thread index, which spreads a read over the banks
+        const uint4* h4 = reinterpret_cast<const uint4*>(s_hist + tid * 32);
 #pragma unroll
-        for (int r = 0; r < 32; ++r) c += s_hist[tid * 32 + r];
+        for (int g = 0; g < 8; ++g) {
+          const uint4 x = h4[(g + tid) & 7];
+          c += x.x + x.y + x.z + x.w;
+        }
       }
       uint32_t total;
       const uint32_t inc = block_incl_scan(c, sm.wave_tot, &total);
@@ -215,14 +205,19 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
     }
     const uint32_t tau = prefix;               // threshold stamp; `need` slots with stamp == tau are taken, lowest slots first
     // ---- collect victims: stamp < tau, plus the first `need` slots (in slot order) with stamp == tau
-    if (tid == 0) sm.vict_n = 0;
-    uint32_t my_eq = 0;
+    uint32_t my_eq = 0, my_lt = 0;
 #pragma unroll
     for (int j = 0; j < nj; ++j)
-      if (v0 + j < v1) my_eq += (stamp_at(j) == tau) ? 1u : 0u;
-    uint32_t eq_total;
-    const uint32_t eq_inc = block_incl_scan(my_eq, sm.wave_tot, &eq_total);   // also orders the vict_n reset
-    uint32_t rank = eq_inc - my_eq;
+      if (v0 + j < v1) {
+        const uint32_t st = stamp_at(j);
+        my_eq += (st == tau) ? 1u : 0u;
+        my_lt += (st < tau) ? 1u : 0u;
+      }
+    // slots at the threshold stamp (their order decides which of them are taken) and slots below it (all taken)
+    uint32_t tot_eq, tot_lt;
+    uint32_t rank = block_incl_scan(my_eq, sm.wave_tot, &tot_eq) - my_eq;      // slots at the threshold stamp in front of this thread's
+    // where this thread's victims go: those of the threads before it come first (the list is in slot order)
+    uint32_t at = (block_incl_scan(my_lt, sm.wave_tot, &tot_lt) - my_lt) + min(rank, need);
 #pragma unroll
     for (int j = 0; j < nj; ++j) {
       if (v0 + j >= v1) continue;
@@ -230,23 +225,34 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
       bool take = st < tau;
       if (st == tau) { take = rank < need; ++rank; }
       if (take) {
-        const uint32_t p = atomicAdd(&sm.vict_n, 1u);
-        if (p < (uint32_t)vict_cap) s_vict[p] = ((unsigned long long)st << 32) | (uint32_t)(v0 + j);
+        if (at < (uint32_t)vict_cap) s_vict[at] = ((unsigned long long)st << 32) | (uint32_t)(v0 + j);
+        ++at;
       }
     }
     __syncthreads();
     // order the victims by (stamp, slot).  Up to 1024 of them: every thread ranks one victim by counting
     // the smaller keys (keys are distinct; no barriers, LDS broadcast reads); more: bitonic sort.
     const bool by_rank = m <= (uint32_t)BT;
-    int my_rank = -1;
-    unsigned long long my_key = 0;
     if (by_rank) {
-      if (tid < (int)m) {
-        my_key = s_vict[tid];
+      // every victim's rank = the number of smaller keys, counted by BT / m threads per victim, each over its share
+      // of the list (LDS broadcast reads), and added up in LDS
+      uint32_t* s_rank = reinterpret_cast<uint32_t*>(s_vict + vict_cap / 2);        // the list takes the lower half at most
+      const int mr = ((int)m + 63) & ~63;            // threads of one share: whole waves
+      const int shares = BT / mr;
+      for (int j = tid; j < (int)m; j += BT) s_rank[j] = 0;
+      __syncthreads();
+      const int i = tid % mr, p = tid / mr;
+      unsigned long long my_key = 0;
+      if (i < (int)m && p < shares) {
+        my_key = s_vict[i];
+        const int j0 = (int)((long)m * p / shares), j1 = (int)((long)m * (p + 1) / shares);
         int rk = 0;
-        for (uint32_t j = 0; j < m; ++j) rk += s_vict[j] < my_key ? 1 : 0;
-        my_rank = rk;
+        for (int j = j0; j < j1; ++j) rk += s_vict[j] < my_key ? 1 : 0;
+        atomicAdd(&s_rank[i], (uint32_t)rk);
       }
+      __syncthreads();
+      const int my_rank = (tid < (int)m) ? (int)s_rank[tid] : -1;
+      if (tid < (int)m) my_key = s_vict[tid];
       __syncthreads();
       if (my_rank >= 0) s_vict[my_rank] = my_key;
       __syncthreads();
@@ -289,7 +295,18 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
       const int j = j0 + tid;
       int slot = -1;
       bool fresh = false;
-      if (j < kk) {
+      if (keep) {
+        // entry t * kk + j0 + tid was looked up by this thread in round u: a hit keeps the slot it had, a miss
+        // got its slot in the pairing above
+        const int u = (t * kk + j0) / BT;
+        const int s = u == 0 ? sv[0] : (u == 1 ? sv[1] : (u == 2 ? sv[2] : sv[3]));
+        const int s0 = u == 0 ? slv[0] : (u == 1 ? slv[1] : (u == 2 ? slv[2] : slv[3]));
+        if (s >= 0) {
+          fresh = s0 < 0;
+          slot = fresh ? so[s] : s0;
+        }
+        if (slot_idx_out) slot_idx_out[rowoff + j] = slot;
+      } else if (j < kk) {
         const int s = idx[rowoff + j];
         if (s >= 0 && s < Lmax) {
           slot = so[s];
