@@ -307,6 +307,10 @@ typedef struct {
   uint64_t bytes_filled; /* misses * row_stride */
 } ess_stats;
 int ess_get_stats(ess_ctx* ctx, ess_stats* host_out, void* stream);
+/* The same counters per sequence (Sec. 3.2 evaluates miss counts; Sec. 3.3 switches on them): host_out[b] for the
+ * first B sequences of the context, `steps` = bookkeeping steps of that sequence (admissions included).  Waits like
+ * ess_get_stats; ess_reset_stats clears both. */
+int ess_get_seq_stats(ess_ctx* ctx, int32_t B, ess_stats* host_out, void* stream);
 int ess_reset_stats(ess_ctx* ctx, void* stream);
 
 /* Measurement support.  After ess_profile_enable(ctx, n) every ess_decode_step records HIP

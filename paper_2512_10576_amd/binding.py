@@ -83,6 +83,7 @@ def load() -> C.CDLL:
         "ess_sparse_mla_decode": [vp, vp, vp, vp, i32, i32, vp, vp, vp],
         "ess_decode_step": [vp, C.POINTER(EssCache), C.POINTER(EssStepArgs), vp],
         "ess_get_stats": [vp, C.POINTER(EssStats), vp],
+        "ess_get_seq_stats": [vp, i32, vp, vp],
         "ess_reset_stats": [vp, vp],
         "ess_profile_enable": [vp, i32],
         "ess_profile_select": [vp, u32, i32],
@@ -315,6 +316,12 @@ class Context:
         s = EssStats()
         _check(self.lib.ess_get_stats(self.h, C.byref(s), _stream()))
         return dict(steps=s.steps, selected=s.selected, misses=s.misses, bytes_filled=s.bytes_filled)
+
+    def get_seq_stats(self, B: int) -> list:
+        """per sequence: dict(steps, selected, misses, bytes_filled)"""
+        arr = (EssStats * B)()
+        _check(self.lib.ess_get_seq_stats(self.h, B, arr, _stream()))
+        return [dict(steps=s.steps, selected=s.selected, misses=s.misses, bytes_filled=s.bytes_filled) for s in arr]
 
     def profile_enable(self, max_steps, stage_mask=0x3F, every=1):
         self._prof_cap = max_steps

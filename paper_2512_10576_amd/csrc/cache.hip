@@ -80,6 +80,7 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
     int32_t* __restrict__ hit_list, int32_t* __restrict__ miss_list, int32_t* __restrict__ n_hit,
     int32_t* __restrict__ n_miss, int32_t* __restrict__ fill_tok, int32_t* __restrict__ fill_slot, int fill_cap,
     int32_t* __restrict__ miss_cnt, int32_t* __restrict__ miss_count_out, unsigned long long* __restrict__ stats,
+    unsigned long long* __restrict__ seq_stats,
     int row_stride, int count_step, int32_t* __restrict__ host_miss, ess_xcd xcd, int n_seq,
     uint32_t* __restrict__ zero_tickets, int n_zero_tickets, int bm_words, int union_bytes) {
   extern __shared__ __align__(16) uint32_t bm[];              // see the layout above
@@ -283,6 +284,11 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
     atomicAdd(&stats[1], (unsigned long long)nvalid);
     atomicAdd(&stats[2], (unsigned long long)m);
     atomicAdd(&stats[3], (unsigned long long)m * (unsigned long long)row_stride);
+    // the same per sequence (this workgroup is the only writer of its sequence's four counters)
+    seq_stats[4 * b + 0] += 1ull;
+    seq_stats[4 * b + 1] += (unsigned long long)nvalid;
+    seq_stats[4 * b + 2] += (unsigned long long)m;
+    seq_stats[4 * b + 3] += (unsigned long long)m * (unsigned long long)row_stride;
   }
   __syncthreads();                               // table updates visible to the whole workgroup
 
@@ -644,7 +650,7 @@ int ess_launch_bookkeeping(ess_ctx* ctx, const ess_cache& cache, const int32_t* 
                      cache.slot_of, cache.token_of, cache.stamp, step, slot_idx,
                      lists ? ctx->hit_list + lo : nullptr, lists ? ctx->miss_list + lo : nullptr,
                      ctx->n_hit + (size_t)b0 * T, ctx->n_miss + (size_t)b0 * T, ctx->fill_tok + (size_t)b0 * cap,
-                     ctx->fill_slot + (size_t)b0 * cap, cap, ctx->miss_cnt + b0, miss_count_out, ctx->stats,
+                     ctx->fill_slot + (size_t)b0 * cap, cap, ctx->miss_cnt + b0, miss_count_out, ctx->stats, ctx->seq_stats + 4 * (size_t)b0,
                      c.row_stride, count_step ? 1 : 0, (c.flags & ESS_FLAG_AUTO) ? ctx->host_miss_dev + b0 : nullptr, xcd, B,
                      zero_tickets, n_zero_tickets, (int)book_words(c.max_ctx), (int)book_union_bytes(cap));
   ESS_HIP(hipGetLastError());

@@ -61,7 +61,7 @@ int validate_config(const ess_config* c) {
 }
 
 struct WsLayout {
-  size_t score, slot_idx, hit, miss, n_hit, n_miss, fill_tok, fill_slot, miss_cnt, o_part, lse_part, stats, zero_row, topk_cand, topk_cnt, topk_tau, sel_sample, sel_tau, sel_cand, sel_cnt, tickets, total;
+  size_t score, slot_idx, hit, miss, n_hit, n_miss, fill_tok, fill_slot, miss_cnt, o_part, lse_part, stats, seq_stats, zero_row, topk_cand, topk_cnt, topk_tau, sel_sample, sel_tau, sel_cand, sel_cnt, tickets, total;
 };
 
 size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -83,6 +83,7 @@ WsLayout ws_layout(const ess_config& c) {
   w.o_part = take(B * T * ESS_MAX_SPLITS * H * ESS_LATENT_DIM * 2);
   w.lse_part = take(B * T * ESS_MAX_SPLITS * H * 8);
   w.stats = take(4 * 8);
+  w.seq_stats = take(B * 4 * 8);
   w.zero_row = take(ESS_ZERO_ROW_BYTES);
   w.topk_cand = take(ess_topk_cand_bytes());
   w.topk_cnt = take(ESS_TOPK_SHARED_ROWS * sizeof(uint32_t));
@@ -230,6 +231,7 @@ int ess_create(const ess_config* cfg, ess_ctx** out) {
   ctx->o_part = reinterpret_cast<uint16_t*>(base + w.o_part);
   ctx->lse_part = reinterpret_cast<float*>(base + w.lse_part);
   ctx->stats = reinterpret_cast<unsigned long long*>(base + w.stats);
+  ctx->seq_stats = reinterpret_cast<unsigned long long*>(base + w.seq_stats);
   ctx->zero_row = base + w.zero_row;
   ctx->topk_cand = reinterpret_cast<unsigned long long*>(base + w.topk_cand);
   ctx->topk_cnt = reinterpret_cast<uint32_t*>(base + w.topk_cnt);
@@ -256,6 +258,7 @@ int ess_create(const ess_config* cfg, ess_ctx** out) {
     if ((e = hipEventCreateWithFlags(&ctx->ev_fill[h], hipEventDisableTiming)) != hipSuccess) return bail("hipEventCreate", e);
   }
   if ((e = hipMemset(ctx->stats, 0, 32)) != hipSuccess) return bail("hipMemset", e);
+  if ((e = hipMemset(ctx->seq_stats, 0, (size_t)cfg->max_batch * 32)) != hipSuccess) return bail("hipMemset", e);
   if ((e = hipMemset(ctx->zero_row, 0, ESS_ZERO_ROW_BYTES)) != hipSuccess) return bail("hipMemset", e);
   if ((e = hipMemset(ctx->topk_cnt, 0, ESS_TOPK_SHARED_ROWS * sizeof(uint32_t))) != hipSuccess) return bail("hipMemset", e);
   if ((e = hipMemset(ctx->tickets, 0, ESS_N_TICKETS * ESS_TICKET_WORDS * sizeof(uint32_t))) != hipSuccess) return bail("hipMemset", e);
@@ -960,9 +963,21 @@ int ess_get_stats(ess_ctx* ctx, ess_stats* host_out, void* stream) {
   return ESS_OK;
 }
 
+int ess_get_seq_stats(ess_ctx* ctx, int32_t B, ess_stats* host_out, void* stream) {
+  if (!ctx || !host_out) return ess_fail(ESS_ERR_INVALID_ARG, "NULL argument");
+  if (B < 1 || B > ctx->cfg.max_batch) return ess_fail(ESS_ERR_INVALID_ARG, "B %d outside [1, %d]", B, ctx->cfg.max_batch);
+  ESS_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+  ESS_HIP(hipStreamSynchronize(ctx->side));
+  static_assert(sizeof(ess_stats) == 32, "ess_stats is four 64-bit counters, the layout of the device arrays");
+  ESS_HIP(hipMemcpy(host_out, ctx->seq_stats, (size_t)B * sizeof(ess_stats), hipMemcpyDeviceToHost));
+  return ESS_OK;
+}
+
 int ess_reset_stats(ess_ctx* ctx, void* stream) {
   if (!ctx) return ess_fail(ESS_ERR_INVALID_ARG, "context is NULL");
-  return ess_launch_fill_u32(reinterpret_cast<uint32_t*>(ctx->stats), 8, 0u, static_cast<hipStream_t>(stream));
+  int rc = ess_launch_fill_u32(reinterpret_cast<uint32_t*>(ctx->stats), 8, 0u, static_cast<hipStream_t>(stream));
+  if (rc != ESS_OK) return rc;
+  return ess_launch_fill_u32(reinterpret_cast<uint32_t*>(ctx->seq_stats), 8 * ctx->cfg.max_batch, 0u, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

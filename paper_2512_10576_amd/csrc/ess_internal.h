@@ -62,6 +62,7 @@ struct ess_ctx {
   uint16_t* o_part;             // [B*T, ESS_MAX_SPLITS, H, 512] partial attention results, fp16 bits (times lse_part[..][1])
   float* lse_part;              // [B*T, ESS_MAX_SPLITS, H, 2]: log-sum-exp of a partial result and the power of two its fp16 values were divided by
   unsigned long long* stats;    // [4]
+  unsigned long long* seq_stats; // [max_batch][4] the same four counters per sequence
   uint8_t* zero_row;            // ESS_ZERO_ROW_BYTES of zeros, never written: source of masked attention rows
   unsigned long long* topk_cand; // [ESS_TOPK_SHARED_ROWS][8192] candidate keys of rows shared by several workgroups
   uint32_t* topk_cnt;           // [ESS_TOPK_SHARED_ROWS] candidates listed per row: zero between steps

@@ -359,6 +359,7 @@ def test_decode_step_offloaded_vs_oracle(ess_lib, flags, fmt):
     mc = torch.empty((B,), dtype=torch.int32, device="cuda")
     dev = [x.cuda() for x in (qi, w, key, ctx_len)]
     outs = []
+    tot_miss = np.zeros(B, np.int64)
     for step in range(1, 5):
         q = synth.attn_query(50 + step, B, T, H)
         ov = trace.next() if step != 3 else None                     # step 3 uses the real top-k
@@ -370,10 +371,16 @@ def test_decode_step_offloaded_vs_oracle(ess_lib, flags, fmt):
         modes.append((ctx.last_overlap(), float(r["miss_count"].mean())))
         _topk_sets_equal(idx_out.cpu().numpy(), r["idx"])
         assert np.array_equal(mc.cpu().numpy(), r["miss_count"])
+        tot_miss += r["miss_count"]
         assert np.array_equal(cache.slot_of.cpu().numpy(), oc.slot_of)
         assert np.array_equal(cache.slot_pool.cpu().numpy(), opool)
         _check_attn(out, lse, r["out"], r["lse"])
         outs.append((out.clone(), lse.clone()))
+    # the counters, per sequence and in all
+    per_seq, allseq = ctx.get_seq_stats(B), ctx.get_stats()
+    assert [s["misses"] for s in per_seq] == tot_miss.tolist() and all(s["steps"] == 4 for s in per_seq)
+    assert all(s["bytes_filled"] == s["misses"] * stride for s in per_seq)
+    assert sum(s["misses"] for s in per_seq) == allseq["misses"] and sum(s["selected"] for s in per_seq) == allseq["selected"]
     ctx.close()
     if flags == 4:                           # the schedule follows the previous step's misses
         assert modes[0][0] == 0
