@@ -525,11 +525,12 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     const double hits = c.topk - (mean_miss / T < c.topk ? mean_miss / T : c.topk);
     const double tiles_item = (hits / ESS_ATTN_TILE) / ns0e + 1.0;
     const double rounds = (double)((long)B * T * hg * ns0e + 159) / 160;
-    const double attn5 = (double)(long)rounds * (tiles_item * (c.latent_fmt == ESS_FMT_BF16 ? 1.8 : 2.6) + 11.0);
+    // (a tile of 32 entries x 128 heads: 2.6 us, 4.2 us when the entries are dequantised on the way; 16 us of start and end)
+    const double attn5 = (double)(long)rounds * (tiles_item * (c.latent_fmt == ESS_FMT_BF16 ? 2.6 : 4.2) + 16.0);
     // (one work counter serves one index-score launch: two query tokens at most)
     confine = dba && T <= 2 && fetch_half >= 1.5 * idx_half;
-    confine2 = confine && attn5 + 40.0 <= 0.9 * fetch_half;         // + Attn1 and merge of the first half
-    confine_da = da_swap && attn5 <= 1.1 * fetch_all;
+    confine2 = confine && attn5 + 40.0 <= 1.15 * fetch_half;        // + Attn1 and merge of the first half
+    confine_da = da_swap && attn5 <= 1.6 * fetch_all;
   }
   ctx->last_confined = confine_da ? 1 : (confine2 ? 2 : (confine ? 1 : 0));
   const uint32_t check_extra = ctx->last_confined ? ctx->check_extra : 0u;   // test hook, one confined step
