@@ -501,9 +501,9 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
   ctx->last_overlap = (c.flags & ESS_FLAG_SERIAL) ? 2 : (dba ? 1 : 0);
   const bool da_swap = offloaded && !dba && !(c.flags & ESS_FLAG_SERIAL);
   const int nh = dba ? 2 : 1;
-  // A fetch confined to three XCDs, with the kernels beside it kept off them (see ess_xcd), pays when the
-  // fetch is long: the kernels beside it then run as if alone, but on five XCDs.  With few misses the lost
-  // CUs cost more (Attn0, in more rounds of workgroups, becomes the longer side).  Measured at batch 64,
+  // A fetch confined to a few XCDs (ESS_FETCH_XCD_MASK), with the kernels beside it kept off them (see ess_xcd),
+  // pays when the fetch is long: the kernels beside it then run as if alone, but on the other XCDs only.  With few misses the lost
+  // CUs cost more (Attn0, in more rounds of workgroups, becomes the longer side).  Measured (with three XCDs) at batch 64,
   // 128K context, 1152-byte entries (step time, confined vs not): single-fetch schedule 0.436 vs 0.398 ms
   // at 31 misses per sequence, 0.447 vs 0.482 at 114, 0.557 vs 0.570 at 195; split-batch, first fetch:
   // 0.497 vs 0.476 at 114, 0.529 vs 0.529 at 195, 0.607 vs 0.631 at 289; second fetch as well: 0.546 vs
@@ -519,12 +519,13 @@ int ess_decode_step(ess_ctx* ctx, const ess_cache* cache, const ess_step_args* a
     const double link = 50e3;                                       // bytes per microsecond
     const double fetch_all = (double)B * mean_miss * c.row_stride / link, fetch_half = 0.5 * fetch_all;
     const double idx_half = 0.5 * B * (double)c.max_ctx * (c.idx_dim + 4.0 * T) / 5.3e6;
-    // Attn0 on five XCDs (160 CUs, one workgroup each): rounds x (tiles x time per tile + start and end)
+    // Attn0 on the XCDs the fetch leaves free (one workgroup per CU): rounds x (tiles x time per tile + start and end)
+    const int work_cus = 32 * (8 - __builtin_popcount(ESS_FETCH_XCD_MASK & 0xffu));
     const int hg = (c.attn_heads + 127) / 128;
     const int ns0e = pick_splits(c, B, T, 16, ESS_ATTN0_WGS);
     const double hits = c.topk - (mean_miss / T < c.topk ? mean_miss / T : c.topk);
     const double tiles_item = (hits / ESS_ATTN_TILE) / ns0e + 1.0;
-    const double rounds = (double)((long)B * T * hg * ns0e + 159) / 160;
+    const double rounds = (double)((long)B * T * hg * ns0e + work_cus - 1) / work_cus;
     // (a tile of 32 entries x 128 heads: 2.6 us, 4.2 us when the entries are dequantised on the way; 16 us of start and end)
     const double attn5 = (double)(long)rounds * (tiles_item * (c.latent_fmt == ESS_FMT_BF16 ? 2.6 : 4.2) + 16.0);
     // (one work counter serves one index-score launch: two query tokens at most)

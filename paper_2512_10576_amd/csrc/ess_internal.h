@@ -34,12 +34,19 @@ enum {                          // which launch uses which counter block
 #define ESS_TK_ARRIVE 64
 #define ESS_TK_CLASS 128
 #define ESS_TICKET_USED 10
-// The first fetch of the split-batch schedule is confined to these XCDs, and the kernels beside it stay
-// off them.  Measured at batch 64, 128K context (step time): one XCD 0.668 ms (the fetch drops to
-// 40 GB/s behind a single XCD's port when the other seven stream from HBM), two 0.614, three 0.605,
-// four 0.631 (the index score is short of CUs), unconfined 0.631; 48 workgroups on three XCDs.
-#define ESS_FETCH_XCD_MASK 7u
+// A confined fetch runs on these XCDs, and the kernels beside it stay off them.  Measured at batch 64, 128K
+// context (step time), with the kernels of the time: one XCD 0.668 ms (the fetch drops to 40 GB/s behind a single
+// XCD's port when the other seven stream from HBM), two 0.614, three 0.605, four 0.631 (the index score is short
+// of CUs), unconfined 0.631.  With the current kernels two and three XCDs give the same step there (0.590 ms), and
+// two give the kernels beside the fetch more of the chip: the index score beside it runs at 4.3 instead of 3.9
+// TB/s, and at batch 128 with two query tokens and quantised entries the step is 3 % shorter (1.078 against 1.113
+// ms).  48 workgroups on the two XCDs (40: the same; 64: 10 % longer steps).
+#ifndef ESS_FETCH_XCD_MASK
+#define ESS_FETCH_XCD_MASK 3u
+#endif
+#ifndef ESS_FETCH_CONFINED_WGS
 #define ESS_FETCH_CONFINED_WGS 48
+#endif
 #define ESS_PROF_MAIN 24        // stage marks on the caller's stream per step
 #define ESS_PROF_FILL 3         // event pairs per step for work off the caller's stream (fetches, side-stream attention)
 #define ESS_PROF_EVENTS (ESS_PROF_MAIN + 2 * ESS_PROF_FILL)
