@@ -133,7 +133,13 @@ typedef struct {
  * on one stream, or order the streams.  Different contexts are independent. */
 /* Create a context: validates the configuration, allocates the workspace
  * (see ess_workspace_bytes), a side stream and events on the current device.
- * ESS_ERR_INVALID_ARG / ESS_ERR_UNSUPPORTED / ESS_ERR_CAPACITY (S < T*k) / ESS_ERR_NOMEM. */
+ * ESS_ERR_INVALID_ARG / ESS_ERR_UNSUPPORTED / ESS_ERR_CAPACITY (S < T*k) / ESS_ERR_NOMEM.
+ * The calls that update the Sparse Memory Pool (ess_cache_admit, ess_gather_latent, ess_decode_step and ess_append
+ * with an offloaded cache) keep a bitmap of max_ctx bits, the larger of a 32 KiB histogram and 8 bytes per
+ * selected entry (max_q_tokens * topk, rounded up to a power of two), and 4 bytes per selected entry in the 160 KiB
+ * of a CU's LDS: max_ctx / 8 + max(32768, 8 * pow2(T*k)) + 4 * T*k + 1 KiB <= 160 KiB.  Every max_ctx fits with
+ * T*k <= 4096; with T*k = 8192 (64 + 32 KiB for the selection) max_ctx up to about 516000 does.  A configuration that
+ * does not fit is accepted by ess_create, and those calls return ESS_ERR_UNSUPPORTED. */
 int ess_create(const ess_config* cfg, ess_ctx** out);
 /* Waits for the context's side stream, frees what ess_create allocated. */
 int ess_destroy(ess_ctx* ctx);
