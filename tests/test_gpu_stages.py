@@ -536,4 +536,15 @@ def test_runtime_argument_errors(ess_lib):
         ctx.index_score(torch.zeros((2, 1, 4, 32), dtype=torch.uint8, device="cuda"),
                         torch.zeros((2, 1, 4), device="cuda"), key, torch.zeros(2, dtype=torch.int32, device="cuda"),
                         score[:2].contiguous())
+    with pytest.raises(bnd.EssError) as ei:                            # fused selection: the same checks
+        key = torch.zeros(2 * 256 * 32 + 1, dtype=torch.uint8, device="cuda")[1:].view(2, 256, 32)
+        ctx.index_topk(torch.zeros((2, 1, 4, 32), dtype=torch.uint8, device="cuda"), torch.zeros((2, 1, 4), device="cuda"),
+                       key, torch.zeros(2, dtype=torch.int32, device="cuda"), torch.zeros((2, 1, 16), dtype=torch.int32, device="cuda"))
+    assert ei.value.code == bnd.ESS_ERR_INVALID_ARG
+    with pytest.raises(bnd.EssError) as ei:                            # no step was recorded
+        ctx.profile_intervals(0)
+    assert ei.value.code == bnd.ESS_ERR_INVALID_ARG
+    with pytest.raises(bnd.EssError) as ei:
+        ctx.get_seq_stats(3)                                            # B above max_batch
+    assert ei.value.code == bnd.ESS_ERR_INVALID_ARG
     ctx.close()
