@@ -239,6 +239,15 @@ def measure(name, steps, warmup, overlap="auto", layers=None, rho=None, ratio=No
     t_enq = time.perf_counter() - t0                 # host time to enqueue the timed steps (no waiting)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    # the index-score launches of a sampled step one by one (a split-batch step has two: the first with the chip to
+    # itself, the second beside the first half's fetch)
+    per_launch = {}
+    for srec in range(min(steps * nl // every, steps * nl)):
+        try:
+            iv = [ms for ms, stage in ctx.profile_intervals(srec) if stage == 0]
+        except Exception:
+            break
+        per_launch.setdefault(len(iv), []).append(iv)
     prof_idx = ctx.profile_read()
     stats = ctx.get_stats()
     step_ms = [marks[i].elapsed_time(marks[i + 1]) / nl for i in range(steps)]       # per layer-step
@@ -287,6 +296,7 @@ def measure(name, steps, warmup, overlap="auto", layers=None, rho=None, ratio=No
         index_alone_ms=index_alone_ms,
         index_alone_GBs=(ab["index_score"] / (index_alone_ms * 1e-3) / 1e9) if index_alone_ms else None,
         index_launches_per_step=launches,
+        index_launch_ms=[sum(x[i] for x in v) / len(v) for n, v in sorted(per_launch.items()) if len(v) * 2 >= sum(len(w) for w in per_launch.values()) for i in range(n)],
         hbm_stream_GBs=hbm_stream_bytes / (hbm_stream_ms * 1e-3) / 1e9,
         hbm_stream_frac_of_peak=hbm_stream_bytes / (hbm_stream_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         whole_step_hbm_frac=(hbm_stream_bytes / (ms_step * 1e-3) / 1e9) / HBM_PEAK_GBS,
@@ -564,6 +574,9 @@ def main():
                 traffic=(traffic[0] / nlaunch) if traffic else None, traffic_source=traffic[1] if traffic else None,
                 algorithmic_bytes_per_launch=ab["index_score"] / nlaunch, avg_launch_ms=res["index_ms_timed"] / nlaunch,
                 launches_per_step=nlaunch, sampled_steps=res["index_samples"],
+                per_launch_ms=res["index_launch_ms"],
+                per_launch_frac=[ab["index_score"] / max(len(res["index_launch_ms"]), 1) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
+                                 for ms in res["index_launch_ms"]],
                 alone=dict(achieved=res["index_alone_GBs"], frac=res["index_alone_GBs"] / HBM_PEAK_GBS,
                            algorithmic_bytes_per_launch=ab["index_score"], avg_launch_ms=res["index_alone_ms"]))
     peaks = measured_peaks(W)
