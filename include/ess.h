@@ -159,7 +159,8 @@ int ess_cache_admit(ess_ctx* ctx, const ess_cache* cache, const int32_t* tok, in
 /* Stage 1, indexer (Sec. 3: the Indexer-Cache scores every Latent-Cache entry):
  *   score[b,t,s] = sum_j w[b,t,j] * max(0, sum_d q[b,t,j,d] * key[b,s,d]),  s < vis(b,t);
  * fp8 x fp8 products accumulated in fp32.  score [B,T,Lmax] fp32; positions
- * s >= vis(b,t) hold unspecified values. */
+ * s >= vis(b,t) hold unspecified values, and so does the score of a key when its
+ * bytes, or those of the query, hold an e4m3 NaN (0x7f, 0xff). */
 int ess_index_score(ess_ctx* ctx, const uint8_t* q_idx_fp8, const float* w, const uint8_t* key_fp8,
                     const int32_t* ctx_len, int32_t B, int32_t T, float* score, void* stream);
 

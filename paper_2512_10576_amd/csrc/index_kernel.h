@@ -47,8 +47,12 @@ struct IdxArgs {
 // row s % 64 of page block_table[b, s / 64] and its score is multiplied by its scale (positive, so the
 // scale commutes with the ReLU and the head sum: one multiplication of the exact sum).  A wave's batch
 // of 64 tokens is exactly one page.
+// Two waves per SIMD are asked for (all forms fit 256 registers), which also makes the compiler give the MFMAs
+// vector-register results: with one wave allowed it puts them in accumulation registers and copies every one back
+// before the ReLU (64 v_accvgpr_read per batch of 64 keys).  The looping single-token form is left as it was: beside
+// a fetch, on six XCDs, it measured 2 % slower in the other form.
 template <int HB, int DI, int T, bool PAGED, bool DYN, bool EMIT>
-__global__ __launch_bounds__(kWaves * 64, T == 2 ? 2 : 1) void k_index_score(const IdxArgs a) {
+__global__ __launch_bounds__(kWaves * 64, (T == 2 || !DYN) ? 2 : 1) void k_index_score(const IdxArgs a) {
   constexpr int KS = DI / 32;
   constexpr size_t kPageBytes = (size_t)kBatchTokens * (DI + 4);
   __shared__ int s_item;

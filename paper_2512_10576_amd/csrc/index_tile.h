@@ -76,6 +76,12 @@ __device__ __forceinline__ void load_query(QueryRegs<HB, DI, T>& r, const uint8_
   }
 }
 
+// max(x, 0) in one instruction: as signed integers, the bit patterns of the floats below zero (and of -0) are
+// negative and those of the others are themselves, so an integer max with 0 is the ReLU.  Written as fmaxf it costs
+// two (the compiler first quiets a possible signalling NaN with a v_max of the value with itself).  A NaN, which
+// only q or key bytes that encode one can produce, passes with its sign bit clear and becomes 0 with it set.
+__device__ __forceinline__ float relu(float x) { return __int_as_float(max(__float_as_int(x), 0)); }
+
 // Scores of one tile of 16 keys for token t: every lane (g,n) returns the score of key n.
 template <int HB, int DI, int T>
 __device__ __forceinline__ float tile_score(const QueryRegs<HB, DI, T>& r, int t, const KeyRegs<DI / 32>& key) {
@@ -109,7 +115,7 @@ __device__ __forceinline__ float tile_score(const QueryRegs<HB, DI, T>& r, int t
 #pragma unroll
   for (int mb = 0; mb < HB; ++mb)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) s = fmaf(r.wr[t][mb][i], fmaxf(acc[mb][i], 0.f), s);
+    for (int i = 0; i < 4; ++i) s = fmaf(r.wr[t][mb][i], relu(acc[mb][i]), s);
   s += __shfl_xor(s, 16, 64);
   s += __shfl_xor(s, 32, 64);
   return s;
