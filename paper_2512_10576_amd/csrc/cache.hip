@@ -414,10 +414,10 @@ __global__ __launch_bounds__(FILL_WPB * 64) void k_fill(const uint8_t* __restric
     if (c1 < chunks) a1 = srcA[c1];
     if (two && c0 < chunks) b0 = srcB[c0];
     if (two && c1 < chunks) b1 = srcB[c1];
-    if (c0 < chunks) dstA[c0] = a0;
-    if (c1 < chunks) dstA[c1] = a1;
-    if (two && c0 < chunks) dstB[c0] = b0;
-    if (two && c1 < chunks) dstB[c1] = b1;
+    if (c0 < chunks) ess_store_nt(dstA + c0, a0);
+    if (c1 < chunks) ess_store_nt(dstA + c1, a1);
+    if (two && c0 < chunks) ess_store_nt(dstB + c0, b0);
+    if (two && c1 < chunks) ess_store_nt(dstB + c1, b1);
   }
 }
 

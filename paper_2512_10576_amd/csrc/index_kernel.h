@@ -163,7 +163,9 @@ __global__ __launch_bounds__(kWaves * 64, (T == 2 || !DYN) ? 2 : 1) void k_index
     } else {
       if (tok < blk_end) {
 #pragma unroll
-        for (int t = 0; t < T; ++t) score[(size_t)(b * Ttot + t0 + t) * Lmax + tok] = PAGED ? res[t] * kr.sc : res[t];
+        for (int t = 0; t < T; ++t) {
+          __builtin_nontemporal_store(PAGED ? res[t] * kr.sc : res[t], &score[(size_t)(b * Ttot + t0 + t) * Lmax + tok]);
+        }
       }
     }
   };

@@ -685,7 +685,7 @@ __global__ __launch_bounds__(NTH, 1) void k_attn_partial_tr(
     for (int r = 0; r < rows_here; ++r) {
       const uint2* src = reinterpret_cast<const uint2*>(lds + (wave * HPW + r) * O_PITCH + lane2 * 16);
       const uint2 lo = src[0], hi = src[1];
-      *reinterpret_cast<uint4*>(reinterpret_cast<uint8_t*>(obase + (size_t)r * ESS_LATENT_DIM) + lane2 * 16) = make_uint4(lo.x, lo.y, hi.x, hi.y);
+      ess_store_nt(reinterpret_cast<uint4*>(reinterpret_cast<uint8_t*>(obase + (size_t)r * ESS_LATENT_DIM) + lane2 * 16), make_uint4(lo.x, lo.y, hi.x, hi.y));
     }
     if (head < H && hh2 == 0)
       *reinterpret_cast<float2*>(lse_part + 2 * prow) = make_float2(l_tot > 0.f ? (m_ref + log2f(l_tot)) * kLn2 : -__builtin_inff(), down);
@@ -756,7 +756,7 @@ __global__ __launch_bounds__(256) void k_attn_merge(const _Float16* __restrict__
   const float inv = den > 0.f ? 1.0f / den : 0.f;
   uint4 o = make_uint4(pack_bf16(a[0] * inv, a[1] * inv), pack_bf16(a[2] * inv, a[3] * inv),
                        pack_bf16(a[4] * inv, a[5] * inv), pack_bf16(a[6] * inv, a[7] * inv));
-  *reinterpret_cast<uint4*>(out + (size_t)rowi * ESS_LATENT_DIM + lane * 8) = o;
+  ess_store_nt(reinterpret_cast<uint4*>(out + (size_t)rowi * ESS_LATENT_DIM + lane * 8), o);
   if (lse_out && lane == 0) lse_out[rowi] = den > 0.f ? mx + __logf(den) : -__builtin_inff();
 }
 
