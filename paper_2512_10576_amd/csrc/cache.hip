@@ -98,7 +98,11 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
       zero_tickets[(i / ESS_TICKET_USED) * ESS_TICKET_WORDS + (i % ESS_TICKET_USED) * ESS_TK_STRIDE] = 0;
   // work item = sequence: by workgroup index, or drawn from the launch's counter off the XCDs to be avoided
   ESS_WORK_LOOP(DYN, xcd, blockIdx.x, n_seq, &s_item, b) {
-  const int tid = threadIdx.x, lane = tid & 63;
+  // (looping form: the thread index passes through an empty asm statement, so that what is derived from it is
+  // computed per work item instead of being carried in registers across the loop, where it led to spills)
+  int tid_ = threadIdx.x;
+  if constexpr (DYN) asm volatile("" : "+v"(tid_));
+  const int tid = tid_, lane = tid & 63;
   const int W = (Lmax + 31) >> 5;
   const int nsel = T * kk;
   const int32_t* sel = idx + (size_t)b * nsel;
@@ -248,7 +252,15 @@ __global__ __launch_bounds__(BT) void k_bookkeeping(
         my_key = s_vict[i];
         const int j0 = (int)((long)m * p / shares), j1 = (int)((long)m * (p + 1) / shares);
         int rk = 0;
-        for (int j = j0; j < j1; ++j) rk += s_vict[j] < my_key ? 1 : 0;
+        int j = j0;
+        for (; j + 8 <= j1; j += 8) {            // eight independent LDS reads in flight (the plain loop waits for each)
+          unsigned long long x[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) x[u] = s_vict[j + u];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) rk += x[u] < my_key ? 1 : 0;
+        }
+        for (; j < j1; ++j) rk += s_vict[j] < my_key ? 1 : 0;
         atomicAdd(&s_rank[i], (uint32_t)rk);
       }
       __syncthreads();
