@@ -141,10 +141,13 @@ def algorithmic_bytes(W, misses_per_step):
     B, T, k, H = wl["B"], wl["T"], wl["k"], wl["H"]
     key_bytes = wl["Di"] + (4 if W.get("paged") else 0)           # paged Indexer-Cache: one float32 scale per key
     a1 = int(lens.sum()) * (key_bytes + 4 * T) + B * T * wl["Hi"] * (wl["Di"] + 4)
+    # the emitting form of the kernel (--fused-select) writes no score array: keys and queries only
+    a1_emit = int(lens.sum()) * key_bytes + B * T * wl["Hi"] * (wl["Di"] + 4)
     a2 = int(lens.sum()) * 4 * T + B * T * k * 4
     a4 = B * T * k * W["stride"] + B * T * H * (576 * 2 + 512 * 2 + 4)
     fill = int(misses_per_step * W["stride"])
-    return dict(index_score=a1, topk=a2, attention_rows=a4, fill=fill)
+    fused = bool(SELECT_FLAGS & 16) and not (SELECT_FLAGS & 8)
+    return dict(index_score=a1, index_in_step=a1_emit if fused else a1, topk=a2, attention_rows=a4, fill=fill)
 
 
 def warm_slot_pool(W):
@@ -284,7 +287,7 @@ def measure(name, steps, warmup, overlap="auto", layers=None, rho=None, ratio=No
     ab = algorithmic_bytes(W, misses_timed)
     ab_stage = algorithmic_bytes(W, misses_stage)
     ms_step = dt / (steps * nl) * 1e3                            # per layer-step
-    hbm_stream_bytes = ab["index_score"] + ab["topk"] + ab["attention_rows"]
+    hbm_stream_bytes = ab["index_in_step"] + ab["topk"] + ab["attention_rows"]
     hbm_stream_ms = stage[0] + stage[1] + stage[3] + stage[4]
     res = dict(
         layer_steps_per_s=steps * nl / dt, ms_per_step=dt / steps * 1e3, ms_per_layer_step=ms_step, layers=nl,
@@ -292,7 +295,7 @@ def measure(name, steps, warmup, overlap="auto", layers=None, rho=None, ratio=No
         stage_ms=dict(index_score=stage[0], topk=stage[1], bookkeeping=stage[2], attn0=stage[3], attn1_merge=stage[4],
                       fetch=stage[5]),
         stage_steps=stage_steps, misses_per_step_stage_pass=misses_stage,
-        index_score_GBs=ab["index_score"] / (index_ms * 1e-3) / 1e9, index_ms_timed=index_ms, index_samples=len(prof_idx),
+        index_score_GBs=ab["index_in_step"] / (index_ms * 1e-3) / 1e9, index_ms_timed=index_ms, index_samples=len(prof_idx),
         index_alone_ms=index_alone_ms,
         index_alone_GBs=(ab["index_score"] / (index_alone_ms * 1e-3) / 1e9) if index_alone_ms else None,
         index_launches_per_step=launches,
@@ -572,10 +575,10 @@ def main():
     roof = dict(bound="hbm", kernel="k_index_score", achieved=res["index_score_GBs"], peak=HBM_PEAK_GBS, unit="GB/s",
                 frac=res["index_score_GBs"] / HBM_PEAK_GBS,
                 traffic=(traffic[0] / nlaunch) if traffic else None, traffic_source=traffic[1] if traffic else None,
-                algorithmic_bytes_per_launch=ab["index_score"] / nlaunch, avg_launch_ms=res["index_ms_timed"] / nlaunch,
+                algorithmic_bytes_per_launch=ab["index_in_step"] / nlaunch, avg_launch_ms=res["index_ms_timed"] / nlaunch,
                 launches_per_step=nlaunch, sampled_steps=res["index_samples"],
                 per_launch_ms=res["index_launch_ms"],
-                per_launch_frac=[ab["index_score"] / max(len(res["index_launch_ms"]), 1) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
+                per_launch_frac=[ab["index_in_step"] / max(len(res["index_launch_ms"]), 1) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
                                  for ms in res["index_launch_ms"]],
                 alone=dict(achieved=res["index_alone_GBs"], frac=res["index_alone_GBs"] / HBM_PEAK_GBS,
                            algorithmic_bytes_per_launch=ab["index_score"], avg_launch_ms=res["index_alone_ms"]))
