@@ -53,8 +53,8 @@ WORKLOADS = {
 # HBM bytes per launch of the index-score kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, keyed by the
 # exact workload and flags they were measured on: (workload, overlap, paged, append) -> (bytes per step, source)
 MEASURED_TRAFFIC = {
-    # (475,432 + 482,816) KiB: FETCH_SIZE x 2.00 + WRITE_SIZE of the two half-batch launches of a split-batch step
-    ("cfg4", "auto", False, False): ((475432 + 482816) * 1024, "profiles/pmc_traffic_cfg4.md"),
+    # (475,444 + 482,774) KiB: FETCH_SIZE x 2.00 + WRITE_SIZE of the two half-batch launches of a split-batch step
+    ("cfg4", "auto", False, False): ((475444 + 482774) * 1024, "profiles/pmc_traffic_cfg4.md"),
 }
 SELECT_FLAGS = 0             # --dense-scores / --fused-select: force one form of stages 1-2 (ESS_FLAG_DENSE_SCORES / _FUSED_SELECT)
 ADMIT_SETS = 32              # access-trace sets admitted (untimed) before any decode step: LRU-Warmup, Sec. 3.2
