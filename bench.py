@@ -571,7 +571,7 @@ def main():
     # beside the first half's fetch; achieved = bytes of a step / time of its launches, which is also
     # bytes per launch / average launch time.  `alone` is the same kernel on the whole batch with the GPU to itself.
     nlaunch = res["index_launches_per_step"]
-    traffic = MEASURED_TRAFFIC.get((a.workload, a.overlap, a.paged, a.append)) if a.layers is None else None
+    traffic = MEASURED_TRAFFIC.get((a.workload, a.overlap, a.paged, a.append)) if (a.layers is None and SELECT_FLAGS == 0) else None
     roof = dict(bound="hbm", kernel="k_index_score", achieved=res["index_score_GBs"], peak=HBM_PEAK_GBS, unit="GB/s",
                 frac=res["index_score_GBs"] / HBM_PEAK_GBS,
                 traffic=(traffic[0] / nlaunch) if traffic else None, traffic_source=traffic[1] if traffic else None,
